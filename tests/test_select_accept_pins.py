@@ -1,0 +1,208 @@
+"""Pins for EVICT prefix selection (Sec. 3.1-3.2) and greedy acceptance (Sec. 2.1)."""
+import os
+
+import numpy as np
+import pytest
+
+import synth
+from oracle import brute_force as bf
+from oracle import evict_oracle as orc
+
+
+def _tree(n, seed):
+    g = synth.philox(seed, 7)
+    par = synth.tree_random_parents(n, 4, g)
+    q = synth.draft_probs(n, g)
+    return par, q
+
+
+def _load_table4(golden_dir):
+    rows = {}
+    with open(os.path.join(golden_dir, "table4_cost_profile.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            name, *vals = line.split()
+            rows[name] = np.array([float(v) for v in vals])
+    ks = rows.pop("k")
+    # the table prints every fourth length; lengths in between are linearly interpolated
+    return {n: np.concatenate([[v[0]], np.interp(np.arange(1, 33), ks, v)]).astype(np.float32)
+            for n, v in rows.items()}
+
+
+# ---------------------------------------------------------------- exhaustive enumeration
+@pytest.mark.parametrize("seed", range(12))
+def test_select_prefix_matches_exhaustive_enumeration(seed):
+    n = 6 + seed % 5
+    par, q = _tree(n, seed)
+    g = synth.philox(seed, 8)
+    cost = np.sort(g.uniform(1.0, 3.0, n + 1)).astype(np.float32)   # increasing cost
+    if seed % 3 == 0:
+        cost = synth.cost_linear_in_union(n, 16, 2)
+    res = orc.select_prefix(par, q, cost, n)
+    best_sum, kbest, util = bf.best_prefix_exhaustive(par, res["score"], cost, n)
+    # (i) the top-k set attains the best score sum among ancestor-closed k-subsets (Sec. 3.2.1)
+    np.testing.assert_allclose(res["S"], best_sum, rtol=2e-6)
+    # (ii) k* maximises best_sum(k)/C(k) (Eq. 10); skip razor-thin margins
+    su = sorted(util, reverse=True)
+    if len(su) < 2 or su[0] - su[1] > 1e-5:
+        assert res["k_star"] == kbest
+    # every prefix of the ranking is ancestor-closed
+    for k in range(1, n + 1):
+        s = set(res["order"][:k].tolist())
+        assert 0 in s and all(par[v] in s for v in s if v != 0)
+
+
+def test_scores_are_root_path_products():
+    par, q = _tree(10, 3)
+    s = orc.node_scores(par, q)
+    for v in range(10):
+        ref = np.prod([np.float64(q[u]) for u in bf.root_path(par, v)[1:]])
+        assert abs(float(s[v]) - ref) < 1e-6
+        if v:
+            assert s[v] <= s[par[v]]             # a child cannot outscore its parent
+
+
+def test_root_probability_is_ignored():
+    par, q = _tree(9, 4)
+    q2 = q.copy(); q2[0] = 0.123
+    cost = synth.cost_linear_in_union(9, 16, 2)
+    a, b = orc.select_prefix(par, q, cost, 9), orc.select_prefix(par, q2, cost, 9)
+    assert a["k_star"] == b["k_star"] and np.array_equal(a["S"], b["S"])
+
+
+# ---------------------------------------------------------------- closed forms and invariants
+def test_constant_cost_keeps_whole_tree_and_linear_cost_keeps_root():
+    par, q = _tree(20, 5)
+    assert orc.select_prefix(par, q, np.ones(21, np.float32), 20)["k_star"] == 20
+    assert orc.select_prefix(par, q, np.arange(21, dtype=np.float32) + (np.arange(21) == 0), 20)["k_star"] == 1
+    # kmax caps the candidate lengths
+    assert orc.select_prefix(par, q, np.ones(21, np.float32), 7)["k_star"] == 7
+
+
+def test_cost_scaling_leaves_k_star_unchanged():
+    # App. C.1: uniformly scaling C(k) does not change the maximising k
+    for seed in range(8):
+        par, q = _tree(24, 100 + seed)
+        cost = synth.cost_linear_in_union(24, 128, 8)
+        base = orc.select_prefix(par, q, cost, 24)
+        for c in (0.25, 2.0, 1024.0):             # powers of two: exact in float32
+            assert orc.select_prefix(par, q, cost * np.float32(c), 24)["k_star"] == base["k_star"]
+        if base["margin"] > 1e-4 * float(base["u"].max()):
+            assert orc.select_prefix(par, q, cost * np.float32(3.3), 24)["k_star"] == base["k_star"]
+
+
+def test_chain_with_constant_q_is_a_geometric_series():
+    n, qq = 12, 0.7
+    par = synth.tree_chain(n)
+    q = np.full(n, qq, np.float32)
+    res = orc.select_prefix(par, q, np.ones(n + 1, np.float32), n)
+    k = np.arange(1, n + 1)
+    np.testing.assert_allclose(res["S"], (1 - np.float64(np.float32(qq)) ** k) / (1 - np.float64(np.float32(qq))), rtol=1e-6)
+    assert np.all(np.diff(res["S"]) >= 0)
+    assert res["order"].tolist() == list(range(n))
+    # Eq. 6 with target acceptance p = q on a chain: same series
+    assert orc.expected_accept_len_exact(par, np.r_[1.0, np.full(n - 1, qq)]) == pytest.approx(res["S"][-1], rel=1e-6)
+
+
+def test_exact_expected_accept_length_matches_simulation():
+    # Eq. 6 / App. B: node v is on the accepted path iff every node on its root path is accepted
+    par = np.array([-1, 0, 0, 1, 1, 2, 5], dtype=np.int32)
+    p = np.array([1.0, 0.6, 0.3, 0.5, 0.2, 0.9, 0.4])
+    g = synth.philox(9, 9)
+    trials = 40000
+    tot = 0
+    for _ in range(trials):
+        acc = g.random(7) < p
+        for v in range(7):
+            tot += all(acc[u] for u in bf.root_path(par, v))
+    assert abs(tot / trials - orc.expected_accept_len_exact(par, p)) < 0.02
+    # estimated length (Eq. 8) equals the exact one when draft probs equal target probs
+    s = orc.node_scores(par, p.astype(np.float32))
+    assert float(s.sum()) == pytest.approx(orc.expected_accept_len_exact(par, p), rel=1e-6)
+
+
+def test_score_ties_keep_prefixes_ancestor_closed():
+    par = np.array([-1, 0, 1, 2, 0, 4], dtype=np.int32)
+    q = np.ones(6, np.float32)                    # all scores equal
+    res = orc.select_prefix(par, q, np.ones(7, np.float32), 6)
+    assert res["order"].tolist() == [0, 1, 2, 3, 4, 5]
+
+
+def test_table4_cost_rows_as_non_monotone_profile(golden_dir):
+    tabs = _load_table4(golden_dir)
+    for name, cost in tabs.items():
+        assert cost[32] / cost[1] == pytest.approx(1.62, abs=0.005)   # growth stated beside Table 4
+    assert tabs["QA"][28] < tabs["QA"][24] < tabs["QA"][20]            # non-monotone stretch
+    for seed in range(6):
+        g = synth.philox(seed, 77)
+        par, q = synth.tree_eagle_style(32, g)
+        for cost in tabs.values():
+            res = orc.select_prefix(par, q, cost, 32)
+            # independent float64 evaluation: sort, cumulative sum, divide, argmax (Sec. 3.2.3)
+            sc = np.array([np.prod([np.float64(q[u]) for u in bf.root_path(par, v)[1:]]) for v in range(32)])
+            util = np.cumsum(np.sort(sc)[::-1]) / cost[1:33].astype(np.float64)
+            srt = np.sort(util)[::-1]
+            if srt[0] - srt[1] > 1e-5:
+                assert res["k_star"] == int(np.argmax(util)) + 1
+            keep = res["keep"]
+            assert len(keep) == res["k_star"] and keep[0] == 0 and np.all(np.diff(keep) > 0)
+            # compacted parents describe the same tree on the kept nodes
+            for r, v in enumerate(keep):
+                if v:
+                    assert keep[res["new_parent"][r]] == par[v]
+                    assert res["new_parent"][r] < r
+
+
+# ---------------------------------------------------------------- greedy acceptance
+@pytest.mark.parametrize("seed", range(10))
+def test_accept_path_matches_path_enumeration(seed):
+    g = synth.philox(seed, 5)
+    n = 5 + 3 * seed
+    par = synth.tree_random_parents(n, 5, g)
+    nxt = g.integers(0, 50, n).astype(np.int32)
+    tok = synth.plant_draft_tokens(par, nxt, 50, g, p_match=0.7)
+    path, bonus = orc.accept_path(par, tok, nxt)
+    assert path.tolist() == bf.accept_longest_matching_path(par, tok, nxt)
+    assert bonus == nxt[path[-1]]
+
+
+def test_accept_path_special_cases():
+    # chain: number of leading matches + 1
+    par = synth.tree_chain(6)
+    nxt = np.array([10, 11, 12, 13, 14, 15], np.int32)
+    tok = np.array([99, 10, 11, 77, 13, 14], np.int32)
+    path, bonus = orc.accept_path(par, tok, nxt)
+    assert path.tolist() == [0, 1, 2] and bonus == 12
+    # no child matches: the root alone, bonus is the target's token after the root
+    path, bonus = orc.accept_path(synth.tree_star(4), np.array([5, 1, 2, 3], np.int32),
+                                  np.array([9, 0, 0, 0], np.int32))
+    assert path.tolist() == [0] and bonus == 9
+    # duplicate sibling tokens: the lower index is taken
+    par = np.array([-1, 0, 0, 1, 2], np.int32)
+    path, _ = orc.accept_path(par, np.array([0, 7, 7, 8, 8], np.int32), np.array([7, 8, 8, 0, 0], np.int32))
+    assert path.tolist() == [0, 1, 3]
+    # single node
+    path, bonus = orc.accept_path(np.array([-1], np.int32), np.array([3], np.int32), np.array([4], np.int32))
+    assert path.tolist() == [0] and bonus == 4
+
+
+def test_planted_mistakes_in_selection_are_caught(monkeypatch):
+    par, q = _tree(9, 2)
+    cost = synth.cost_linear_in_union(9, 16, 2)
+
+    def agrees():
+        res = orc.select_prefix(par, q, cost, 9)
+        best_sum, kbest, _ = bf.best_prefix_exhaustive(par, res["score"], cost, 9)
+        return np.allclose(res["S"], best_sum, rtol=2e-6) and res["k_star"] == kbest
+
+    assert agrees()
+    real = orc.node_scores
+    # scores taken as the node's own probability rather than the path product
+    monkeypatch.setattr(orc, "node_scores", lambda p, qq: np.r_[np.float32(1), np.asarray(qq[1:], np.float32)])
+    res = orc.select_prefix(par, q, cost, 9)
+    ok = all(all(par[v] in set(res["order"][:k].tolist()) for v in res["order"][:k] if v) for k in range(1, 10))
+    ref = [np.prod([np.float64(q[u]) for u in bf.root_path(par, v)[1:]]) for v in range(9)]
+    assert (not ok) or not np.allclose(res["score"], ref)
+    monkeypatch.setattr(orc, "node_scores", real)
+    assert agrees()
