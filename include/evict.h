@@ -1,0 +1,186 @@
+/*
+ * evict.h — C ABI of the MI355X (gfx950) library for target-side verification of a draft
+ * token tree on a sparse Mixture-of-Experts transformer layer, and for EVICT's cost-aware
+ * choice of the tree prefix that is worth verifying.
+ *
+ * Conventions (all entry points)
+ *   - Plain C, no exceptions cross the boundary. Every call returns an int status:
+ *     EVICT_OK, EVICT_E_INVALID (bad argument, detected on the host before anything is
+ *     launched), EVICT_E_UNSUPPORTED (shape outside what the kernels cover) or EVICT_E_HIP
+ *     (a HIP runtime error). evict_last_error() returns a thread-local message.
+ *   - Pointers marked [dev] are device pointers owned by the caller, 16-byte aligned;
+ *     pointers marked [host] are host pointers. The library owns only evict_ctx and the
+ *     scratch memory inside it, allocated once in evict_create.
+ *   - Work is enqueued on the caller's hipStream_t (passed as void*; NULL = default
+ *     stream); no call synchronises the stream or allocates after evict_create.
+ *   - Inputs are never written. The KV cache is read-only: keys/values of the draft nodes
+ *     go to caller buffers.
+ *   - Trees are batched CSR-style: tree_off int32[B+1], node arrays concatenated, parent
+ *     ids are tree-local with parent[0] = -1 and parent[i] < i (node 0 is the root
+ *     x_{t+1}, which is sampled from the target and therefore always accepted and always
+ *     part of every prefix; Sec. 2.1).
+ *   - dtype: storage type of weights and activations; accumulation is always fp32.
+ */
+#ifndef EVICT_H_
+#define EVICT_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define EVICT_OK 0
+#define EVICT_E_INVALID 1
+#define EVICT_E_UNSUPPORTED 2
+#define EVICT_E_HIP 3
+
+#define EVICT_F32 0
+#define EVICT_BF16 1
+
+#define EVICT_MAX_TREE_NODES 128   /* nodes per tree in evict_verify_layer (ancestor bitmask) */
+#define EVICT_MAX_SELECT_NODES 1024 /* nodes per tree in evict_select_prefix / evict_accept_path */
+
+typedef struct evict_ctx evict_ctx;
+
+/* Shape of one MoE decoder layer. */
+typedef struct evict_model_desc {
+  int32_t dtype;      /* EVICT_F32 or EVICT_BF16 */
+  int32_t d;          /* model width */
+  int32_t Hq;         /* query heads */
+  int32_t Hkv;        /* key/value heads (Hq % Hkv == 0) */
+  int32_t D;          /* head dimension (64 or 128) */
+  int32_t E;          /* routed experts (the N of Sec. 2.2) */
+  int32_t k;          /* experts selected per token (Eq. 4) */
+  int32_t F;          /* expert hidden width */
+  int32_t n_shared;   /* always-on shared experts, not part of the union */
+  float rms_eps;      /* RMSNorm epsilon */
+  float rope_theta;   /* rotary base; 0 disables the rotation */
+} evict_model_desc;
+
+/* Device pointers to one layer's weights. Matrices are in the packed streaming layout
+ * written by the evict_pack_* calls; gains are plain vectors in the storage dtype. */
+typedef struct evict_layer_weights {
+  const void* g_attn;        /* [dev] [d] gain of the pre-attention RMSNorm */
+  const void* g_moe;         /* [dev] [d] gain of the pre-MoE RMSNorm */
+  const void* wqkv_packed;   /* [dev] from evict_pack_qkv */
+  const void* wo_packed;     /* [dev] from evict_pack_dense(W_o [d, Hq*D]) */
+  const void* wg;            /* [dev] router matrix W_g [E, d], row-major, NOT packed */
+  const void* w_gateup_packed; /* [dev] from evict_pack_experts */
+  const void* w_down_packed;   /* [dev] from evict_pack_experts */
+  const void* ws_gateup_packed; /* [dev] shared experts, or NULL when n_shared == 0 */
+  const void* ws_down_packed;   /* [dev] shared experts, or NULL */
+} evict_layer_weights;
+
+/* Optional per-stage outputs of evict_verify_layer, each [dev] and nullable. */
+typedef struct evict_layer_aux {
+  void* h;              /* [T, d] storage dtype: hidden state after attention + residual */
+  void* h_norm;         /* [T, d] storage dtype: RMSNorm(h), the router/expert input */
+  float* router_logits; /* [T, E] W_g h_norm (Eq. 4) */
+  int32_t* topk_idx;    /* [T, k] selected experts, by score descending, index ascending on ties */
+  float* topk_w;        /* [T, k] softmax over the selected scores */
+  int32_t* union_ids;   /* [E] activated experts ascending, tail -1 (Eq. 5) */
+  int32_t* union_count; /* [1] */
+  int32_t* hist;        /* [E] (token, slot) pairs per expert */
+  void* q;              /* [T, Hq, D] storage dtype, after rotation */
+  void* attn_out;       /* [T, Hq, D] storage dtype, attention output before W_o */
+} evict_layer_aux;
+
+int evict_version(void);
+const char* evict_last_error(void);
+
+/* Create a context for one model shape. max_tokens bounds T (sum of tree sizes in a call),
+ * max_batch bounds B, max_ctx bounds any sequence's KV context length. Allocates all
+ * scratch memory on the current device. */
+int evict_create(evict_ctx** out, const evict_model_desc* m, int max_tokens, int max_batch, int max_ctx);
+int evict_destroy(evict_ctx* ctx);
+
+/* Size in bytes of the packed form of a [rows, cols] matrix. */
+size_t evict_packed_bytes(int dtype, int rows, int cols);
+
+/* One-off weight packing, off the hot path. Sources are [dev], row-major with the
+ * contraction dimension contiguous: W_q [Hq*D, d], W_k, W_v [Hkv*D, d], W_o [d, Hq*D],
+ * expert W_gate, W_up [n_experts, F, d], W_down [n_experts, d, F]. Packing only reorders
+ * bytes (16-row strips, 64-byte column blocks, one 1 KiB block per wavefront load). */
+int evict_pack_dense(int dtype, const void* w, int rows, int cols, void* dst, void* stream);
+int evict_pack_qkv(const evict_model_desc* m, const void* wq, const void* wk, const void* wv, void* dst, void* stream);
+int evict_pack_experts(const evict_model_desc* m, int n_experts, const void* w_gate, const void* w_up,
+                       const void* w_down, void* dst_gateup, void* dst_down, void* stream);
+
+/* Verify all T nodes of B draft trees in one pass through one MoE decoder layer
+ * (Sec. 2.1: one forward pass with the tree attention mask of Fig. 4(c); Sec. 2.2: router
+ * TopK, expert union, weighted sum of the selected experts).
+ *   tree_off [dev] int32[B+1], parent [dev] int32[T] (tree-local), 1 <= tree size <= 128.
+ *   k_cache, v_cache [dev]: sequence b, head g, position p, channel c at
+ *     base + b*kv_seq_stride + g*kv_head_stride + p*D + c (strides in elements); keys are
+ *     already position-encoded. ctx_len [dev] int32[B], each <= max_ctx_host <= max_ctx.
+ *   x_in [dev] [T, d] -> x_out [dev] [T, d]; k_new, v_new [dev] [T, Hkv, D] receive the
+ *     draft nodes' keys (rotated at position ctx_len + depth) and values.
+ *   aux: nullable, and each field nullable. */
+int evict_verify_layer(evict_ctx* ctx, const evict_layer_weights* w,
+                       const int32_t* tree_off, const int32_t* parent, int B, int T,
+                       const void* k_cache, const void* v_cache, int64_t kv_seq_stride, int64_t kv_head_stride,
+                       const int32_t* ctx_len, int max_ctx_host,
+                       const void* x_in, void* x_out, void* k_new, void* v_new,
+                       const evict_layer_aux* aux, void* stream);
+
+/* Union of activated experts over all verified nodes (Eq. 5) and the grouping it induces.
+ *   topk_idx [dev] int32[T, k] with values in [0, E).
+ *   union_ids [dev] int32[E]: activated experts ascending, tail -1; union_count [dev] int32[1];
+ *   hist [dev] int32[E]; offsets [dev] int32[E+1] = exclusive prefix sum of hist;
+ *   perm [dev] int32[T*k]: pair ids (token*k + slot) grouped by expert, ascending inside a
+ *   group; inv [dev] int32[T*k]: position of each pair in perm. T*k <= 8192, E <= 1024. */
+int evict_expert_union(evict_ctx* ctx, const int32_t* topk_idx, int T, int k, int E,
+                       int32_t* union_ids, int32_t* union_count, int32_t* hist, int32_t* offsets,
+                       int32_t* perm, int32_t* inv, void* stream);
+
+/* Greedy (temperature 0) acceptance: the deterministic case of the sequential sibling rule
+ * of Sec. 2.1. From the root, the first child (ascending index) whose draft token equals
+ * the target's next token at the current node is accepted; the walk stops when none does.
+ *   draft_tok, target_next [dev] int32[T]; path [dev] int32[B, path_stride] tree-local ids,
+ *   tail -1; path_len [dev] int32[B] (>= 1); bonus_tok [dev] int32[B] = target_next at the
+ *   last accepted node. Trees up to 1024 nodes; path_stride >= 1 (longer paths are
+ *   truncated in `path` but counted in path_len). ctx may be NULL. */
+int evict_accept_path(evict_ctx* ctx, const int32_t* tree_off, const int32_t* parent,
+                      const int32_t* draft_tok, const int32_t* target_next, int B,
+                      int32_t* path, int path_stride, int32_t* path_len, int32_t* bonus_tok, void* stream);
+
+/* EVICT prefix selection, entirely on the device (Sec. 3.1-3.2): node score = product of
+ * draft probabilities along the root path (Eq. 7, root counted as 1), nodes ranked by score
+ * (Sec. 3.2.1; equal scores: lower index first, which keeps every prefix ancestor-closed),
+ * S_k = running fp32 sum of the k best scores (Eq. 8), k* = smallest k in 1..min(N, Kmax)
+ * maximising S_k / cost[k] (Eq. 10, evaluated as cumulative sums, division, argmax:
+ * Sec. 3.2.3). All arithmetic is single IEEE fp32 operations in a fixed order.
+ *   node_prob [dev] float[T] in (0, 1]; cost [dev] float[Kmax+1], cost[0] unused, all > 0.
+ *   k_star [dev] int32[B]; keep [dev] int32[T]: kept nodes of tree b, ascending tree-local
+ *   ids, written at new_tree_off[b]; new_parent [dev] int32[T] parents re-indexed into the
+ *   kept set; new_tree_off [dev] int32[B+1]; est_len [dev] float[B] = S_{k*};
+ *   order [dev] int32[T] nullable: full ranking per tree at tree_off[b];
+ *   prefix_sum [dev] float[T] nullable: S_1..S_N per tree at tree_off[b].
+ * Trees up to 1024 nodes. ctx may be NULL. */
+int evict_select_prefix(evict_ctx* ctx, const int32_t* tree_off, const int32_t* parent,
+                        const float* node_prob, int B, int T, const float* cost, int Kmax,
+                        int32_t* k_star, int32_t* keep, int32_t* new_parent, int32_t* new_tree_off,
+                        float* est_len, int32_t* order, float* prefix_sum, void* stream);
+
+/* Gather rows of a [T, row_bytes] array by the kept node lists of evict_select_prefix:
+ * dst row new_tree_off[b] + r = src row tree_off[b] + keep[new_tree_off[b] + r].
+ * row_bytes % 4 == 0. Grid is sized for T rows; rows beyond new_tree_off[B] are untouched. */
+int evict_gather_rows(const void* src, void* dst, int row_bytes, const int32_t* tree_off,
+                      const int32_t* new_tree_off, const int32_t* keep, int B, int T, void* stream);
+
+/* Host-side structural check of a batch of trees ([host] pointers): EVICT_OK, or
+ * EVICT_E_INVALID when some parent[i] is outside [-1, i), a root is not -1, offsets are not
+ * increasing, or a tree exceeds max_nodes. */
+int evict_validate_trees_host(const int32_t* tree_off, const int32_t* parent, int B, int max_nodes);
+
+/* Device-side status word of a context: 0, or a bit set when a kernel met an invalid
+ * parent id, expert index or context length (such values are clamped, never dereferenced).
+ * Synchronises the stream. */
+int evict_device_status(evict_ctx* ctx, int32_t* status_host, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EVICT_H_ */

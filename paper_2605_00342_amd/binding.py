@@ -1,0 +1,180 @@
+"""ctypes binding of libevict.so: argument marshalling only.
+
+Functions carry the names of the C entry points (include/evict.h). Tensors are torch tensors
+on the GPU (PyTorch supplies device memory and streams, nothing else); each call enqueues
+work on torch's current stream and raises EvictError on a non-zero status.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+__all__ = [
+    "EvictError", "lib_path", "load", "is_built", "EVICT_F32", "EVICT_BF16", "ModelDesc", "LayerWeights", "LayerAux",
+    "evict_version", "evict_last_error", "evict_create", "evict_destroy", "evict_packed_bytes", "evict_pack_dense",
+    "evict_pack_qkv", "evict_pack_experts", "evict_verify_layer", "evict_expert_union", "evict_accept_path",
+    "evict_select_prefix", "evict_gather_rows", "evict_validate_trees_host", "evict_device_status", "EXPORTS",
+]
+
+EVICT_F32, EVICT_BF16 = 0, 1
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+EXPORTS = [
+    "evict_version", "evict_last_error", "evict_create", "evict_destroy", "evict_packed_bytes", "evict_pack_dense",
+    "evict_pack_qkv", "evict_pack_experts", "evict_verify_layer", "evict_expert_union", "evict_accept_path",
+    "evict_select_prefix", "evict_gather_rows", "evict_validate_trees_host", "evict_device_status",
+]
+
+
+class EvictError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"evict status {code}: {msg}")
+        self.code = code
+
+
+class ModelDesc(C.Structure):
+    _fields_ = [("dtype", C.c_int32), ("d", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32), ("D", C.c_int32),
+                ("E", C.c_int32), ("k", C.c_int32), ("F", C.c_int32), ("n_shared", C.c_int32),
+                ("rms_eps", C.c_float), ("rope_theta", C.c_float)]
+
+
+class LayerWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("g_attn", "g_moe", "wqkv_packed", "wo_packed", "wg", "w_gateup_packed",
+                                          "w_down_packed", "ws_gateup_packed", "ws_down_packed")]
+
+
+class LayerAux(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("h", "h_norm", "router_logits", "topk_idx", "topk_w", "union_ids",
+                                          "union_count", "hist", "q", "attn_out")]
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "libevict.so")
+
+
+def is_built() -> bool:
+    return os.path.exists(lib_path())
+
+
+def load():
+    """Load libevict.so (built in-tree by paper_2605_00342_amd/build.py). Fails loudly if absent."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    if not is_built():
+        raise FileNotFoundError(f"{lib_path()} is missing: run `python -m paper_2605_00342_amd.build` "
+                                "(or __graft_entry__.build()); there is no fallback path")
+    lib = C.CDLL(lib_path())
+    vp, i32, i64, sz = C.c_void_p, C.c_int, C.c_int64, C.c_size_t
+    lib.evict_version.restype = i32
+    lib.evict_last_error.restype = C.c_char_p
+    lib.evict_create.argtypes = [C.POINTER(vp), C.POINTER(ModelDesc), i32, i32, i32]
+    lib.evict_destroy.argtypes = [vp]
+    lib.evict_packed_bytes.argtypes = [i32, i32, i32]
+    lib.evict_packed_bytes.restype = sz
+    lib.evict_pack_dense.argtypes = [i32, vp, i32, i32, vp, vp]
+    lib.evict_pack_qkv.argtypes = [C.POINTER(ModelDesc), vp, vp, vp, vp, vp]
+    lib.evict_pack_experts.argtypes = [C.POINTER(ModelDesc), i32, vp, vp, vp, vp, vp, vp]
+    lib.evict_verify_layer.argtypes = [vp, C.POINTER(LayerWeights), vp, vp, i32, i32, vp, vp, i64, i64, vp, i32,
+                                       vp, vp, vp, vp, C.POINTER(LayerAux), vp]
+    lib.evict_expert_union.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
+    lib.evict_accept_path.argtypes = [vp, vp, vp, vp, vp, i32, vp, i32, vp, vp, vp]
+    lib.evict_select_prefix.argtypes = [vp, vp, vp, vp, i32, i32, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.evict_gather_rows.argtypes = [vp, vp, i32, vp, vp, vp, i32, i32, vp]
+    lib.evict_validate_trees_host.argtypes = [vp, vp, i32, i32]
+    lib.evict_device_status.argtypes = [vp, C.POINTER(C.c_int32), vp]
+    _LIB = lib
+    return lib
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise EvictError(rc, load().evict_last_error().decode("utf-8", "replace"))
+
+
+def _p(t) -> Optional[int]:
+    """Device (or host) address of a tensor, None for a missing optional argument."""
+    if t is None:
+        return None
+    return t.data_ptr()
+
+
+def _stream() -> Optional[int]:
+    import torch
+    return torch.cuda.current_stream().cuda_stream or None
+
+
+def evict_version() -> int:
+    return load().evict_version()
+
+
+def evict_last_error() -> str:
+    return load().evict_last_error().decode("utf-8", "replace")
+
+
+def evict_create(desc: ModelDesc, max_tokens: int, max_batch: int, max_ctx: int) -> int:
+    h = C.c_void_p()
+    _check(load().evict_create(C.byref(h), C.byref(desc), max_tokens, max_batch, max_ctx))
+    return h.value
+
+
+def evict_destroy(ctx) -> None:
+    _check(load().evict_destroy(ctx))
+
+
+def evict_packed_bytes(dtype: int, rows: int, cols: int) -> int:
+    return load().evict_packed_bytes(dtype, rows, cols)
+
+
+def evict_pack_dense(dtype, w, rows, cols, dst) -> None:
+    _check(load().evict_pack_dense(dtype, _p(w), rows, cols, _p(dst), _stream()))
+
+
+def evict_pack_qkv(desc, wq, wk, wv, dst) -> None:
+    _check(load().evict_pack_qkv(C.byref(desc), _p(wq), _p(wk), _p(wv), _p(dst), _stream()))
+
+
+def evict_pack_experts(desc, n_experts, w_gate, w_up, w_down, dst_gateup, dst_down) -> None:
+    _check(load().evict_pack_experts(C.byref(desc), n_experts, _p(w_gate), _p(w_up), _p(w_down), _p(dst_gateup),
+                                     _p(dst_down), _stream()))
+
+
+def evict_verify_layer(ctx, weights: LayerWeights, tree_off, parent, B, T, k_cache, v_cache, kv_seq_stride,
+                       kv_head_stride, ctx_len, max_ctx_host, x_in, x_out, k_new, v_new, aux: Optional[LayerAux] = None) -> None:
+    _check(load().evict_verify_layer(ctx, C.byref(weights), _p(tree_off), _p(parent), B, T, _p(k_cache), _p(v_cache),
+                                     kv_seq_stride, kv_head_stride, _p(ctx_len), max_ctx_host, _p(x_in), _p(x_out),
+                                     _p(k_new), _p(v_new), C.byref(aux) if aux is not None else None, _stream()))
+
+
+def evict_expert_union(ctx, topk_idx, T, k, E, union_ids, union_count, hist, offsets, perm, inv) -> None:
+    _check(load().evict_expert_union(ctx, _p(topk_idx), T, k, E, _p(union_ids), _p(union_count), _p(hist), _p(offsets),
+                                     _p(perm), _p(inv), _stream()))
+
+
+def evict_accept_path(ctx, tree_off, parent, draft_tok, target_next, B, path, path_stride, path_len, bonus_tok) -> None:
+    _check(load().evict_accept_path(ctx, _p(tree_off), _p(parent), _p(draft_tok), _p(target_next), B, _p(path),
+                                    path_stride, _p(path_len), _p(bonus_tok), _stream()))
+
+
+def evict_select_prefix(ctx, tree_off, parent, node_prob, B, T, cost, Kmax, k_star, keep, new_parent, new_tree_off,
+                        est_len, order=None, prefix_sum=None) -> None:
+    _check(load().evict_select_prefix(ctx, _p(tree_off), _p(parent), _p(node_prob), B, T, _p(cost), Kmax, _p(k_star),
+                                      _p(keep), _p(new_parent), _p(new_tree_off), _p(est_len), _p(order),
+                                      _p(prefix_sum), _stream()))
+
+
+def evict_gather_rows(src, dst, row_bytes, tree_off, new_tree_off, keep, B, T) -> None:
+    _check(load().evict_gather_rows(_p(src), _p(dst), row_bytes, _p(tree_off), _p(new_tree_off), _p(keep), B, T, _stream()))
+
+
+def evict_validate_trees_host(tree_off, parent, B, max_nodes) -> int:
+    """tree_off, parent: contiguous int32 numpy arrays on the host. Returns the status code."""
+    return load().evict_validate_trees_host(tree_off.ctypes.data, parent.ctypes.data, B, max_nodes)
+
+
+def evict_device_status(ctx) -> int:
+    out = C.c_int32(0)
+    _check(load().evict_device_status(ctx, C.byref(out), _stream()))
+    return out.value

@@ -1,0 +1,321 @@
+// C-ABI entry points that own state or chain kernels: context, weight packing, the
+// per-layer verification pass (Sec. 2.1-2.2).
+#include <new>
+#include <vector>
+
+#include "ctx.h"
+#include "gemm_stream.h"
+#include "layer_launch.h"
+
+using namespace evict;
+
+namespace {
+
+int elem_bytes(int dtype) { return dtype == EVICT_BF16 ? 2 : 4; }
+
+int check_model(const evict_model_desc* m) {
+  EVICT_REQUIRE(m, EVICT_E_INVALID, "model description is null");
+  EVICT_REQUIRE(m->dtype == EVICT_F32 || m->dtype == EVICT_BF16, EVICT_E_INVALID, "unknown dtype %d", m->dtype);
+  EVICT_REQUIRE(m->d > 0 && m->Hq > 0 && m->Hkv > 0 && m->D > 0 && m->E > 0 && m->k > 0 && m->F > 0 && m->n_shared >= 0,
+                EVICT_E_INVALID, "model dimensions must be positive");
+  EVICT_REQUIRE(m->Hq % m->Hkv == 0, EVICT_E_INVALID, "Hq=%d is not a multiple of Hkv=%d", m->Hq, m->Hkv);
+  EVICT_REQUIRE(m->k <= m->E, EVICT_E_INVALID, "k=%d exceeds E=%d", m->k, m->E);
+  EVICT_REQUIRE(m->rms_eps >= 0.0f && m->rope_theta >= 0.0f, EVICT_E_INVALID, "rms_eps and rope_theta must be >= 0");
+  const int eb = elem_bytes(m->dtype);
+  EVICT_REQUIRE(m->D == 64 || m->D == 128, EVICT_E_UNSUPPORTED, "head dimension %d (supported: 64, 128)", m->D);
+  EVICT_REQUIRE(m->d % 16 == 0 && m->F % 16 == 0 && (m->d * eb) % 64 == 0 && (m->F * eb) % 64 == 0,
+                EVICT_E_UNSUPPORTED, "d=%d and F=%d must be multiples of 16 rows and of 64 bytes", m->d, m->F);
+  EVICT_REQUIRE(m->k <= 64 && m->E <= 1024, EVICT_E_UNSUPPORTED, "k=%d (limit 64), E=%d (limit 1024)", m->k, m->E);
+  return EVICT_OK;
+}
+
+template <typename P>
+int dev_alloc(P** p, size_t bytes, std::vector<void*>& owned) {
+  void* q = nullptr;
+  EVICT_HIP_CHECK(hipMalloc(&q, bytes ? bytes : 16));
+  owned.push_back(q);
+  *p = reinterpret_cast<P*>(q);
+  return EVICT_OK;
+}
+
+}  // namespace
+
+struct evict_ctx_owner {
+  evict_ctx c;
+  std::vector<void*> owned;
+};
+
+extern "C" {
+
+int evict_create(evict_ctx** out, const evict_model_desc* m, int max_tokens, int max_batch, int max_ctx) {
+  EVICT_REQUIRE(out, EVICT_E_INVALID, "evict_create: out is null");
+  *out = nullptr;
+  int rc = check_model(m);
+  if (rc) return rc;
+  EVICT_REQUIRE(max_tokens >= 1 && max_batch >= 1 && max_ctx >= 0, EVICT_E_INVALID,
+                "evict_create: max_tokens=%d, max_batch=%d, max_ctx=%d", max_tokens, max_batch, max_ctx);
+  EVICT_REQUIRE((long long)max_tokens * m->k <= 8192, EVICT_E_UNSUPPORTED, "max_tokens*k=%lld exceeds 8192",
+                (long long)max_tokens * m->k);
+  evict_ctx_owner* o = new (std::nothrow) evict_ctx_owner();
+  EVICT_REQUIRE(o, EVICT_E_INVALID, "out of host memory");
+  evict_ctx& c = o->c;
+  c.m = *m;
+  c.max_tokens = max_tokens;
+  c.max_batch = max_batch;
+  c.max_ctx = max_ctx;
+  c.max_splits = attn_splits_for(max_ctx);
+  const size_t T = max_tokens, eb = elem_bytes(m->dtype);
+  const size_t d = m->d, HqD = (size_t)m->Hq * m->D, E = m->E, k = m->k, F = m->F;
+  rc = EVICT_OK;
+  auto A = [&](auto** p, size_t bytes) { if (!rc) rc = dev_alloc(p, bytes, o->owned); };
+  hipError_t he = hipGetDevice(&c.device);
+  if (he != hipSuccess) { set_error("hipGetDevice failed: %s", hipGetErrorString(he)); delete o; return EVICT_E_HIP; }
+  A(&c.status, 16);
+  A(&c.anc, T * 16);
+  A(&c.depth, T * 4);
+  A(&c.seq_of, T * 4);
+  A(&c.rope_cs, T * m->D * 4);
+  A(&c.x_norm, T * d * eb);
+  A(&c.q, T * HqD * eb);
+  A(&c.part_o, (size_t)c.max_splits * T * HqD * 4);
+  A(&c.part_ml, (size_t)c.max_splits * T * m->Hq * 2 * 4);
+  A(&c.attn_o, T * HqD * eb);
+  A(&c.h, T * d * eb);
+  A(&c.h_norm, T * d * eb);
+  A(&c.logits, T * E * 4);
+  A(&c.topk_idx, T * k * 4);
+  A(&c.topk_w, T * k * 4);
+  A(&c.hist, E * 4);
+  A(&c.offsets, (E + 1) * 4);
+  A(&c.union_ids, E * 4);
+  A(&c.union_count, 16);
+  A(&c.perm, T * k * 4);
+  A(&c.inv, T * k * 4);
+  A(&c.act, T * k * F * eb);
+  A(&c.y, T * k * d * 4);
+  c.act_sh = nullptr;
+  c.y_sh = nullptr;
+  if (m->n_shared) {
+    A(&c.act_sh, (size_t)m->n_shared * T * F * eb);
+    A(&c.y_sh, (size_t)m->n_shared * T * d * 4);
+  }
+  if (!rc) {
+    he = hipMemset(c.status, 0, 16);
+    if (he != hipSuccess) { set_error("hipMemset failed: %s", hipGetErrorString(he)); rc = EVICT_E_HIP; }
+  }
+  if (!rc) rc = attn_setup();
+  if (rc) {
+    for (void* p : o->owned) (void)hipFree(p);
+    delete o;
+    return rc;
+  }
+  *out = &o->c;
+  return EVICT_OK;
+}
+
+int evict_destroy(evict_ctx* ctx) {
+  if (!ctx) return EVICT_OK;
+  evict_ctx_owner* o = reinterpret_cast<evict_ctx_owner*>(ctx);  // c is the first member
+  int rc = EVICT_OK;
+  for (void* p : o->owned) {
+    hipError_t e = hipFree(p);
+    if (e != hipSuccess) { set_error("hipFree failed: %s", hipGetErrorString(e)); rc = EVICT_E_HIP; }
+  }
+  delete o;
+  return rc;
+}
+
+size_t evict_packed_bytes(int dtype, int rows, int cols) {
+  if (rows <= 0 || cols <= 0 || (dtype != EVICT_F32 && dtype != EVICT_BF16)) return 0;
+  return (size_t)rows * cols * elem_bytes(dtype);
+}
+
+int evict_pack_dense(int dtype, const void* w, int rows, int cols, void* dst, void* stream) {
+  EVICT_REQUIRE(w && dst, EVICT_E_INVALID, "evict_pack_dense: null pointer");
+  EVICT_REQUIRE(dtype == EVICT_F32 || dtype == EVICT_BF16, EVICT_E_INVALID, "evict_pack_dense: unknown dtype %d", dtype);
+  EVICT_REQUIRE(rows > 0 && cols > 0, EVICT_E_INVALID, "evict_pack_dense: rows=%d cols=%d", rows, cols);
+  EVICT_REQUIRE(rows % 16 == 0 && (cols * elem_bytes(dtype)) % 64 == 0, EVICT_E_UNSUPPORTED,
+                "evict_pack_dense: rows=%d must be a multiple of 16 and a row (%d bytes) a multiple of 64 bytes", rows,
+                cols * elem_bytes(dtype));
+  EVICT_REQUIRE(aligned16(w) && aligned16(dst) && w != dst, EVICT_E_INVALID, "evict_pack_dense: pointers must be distinct and 16-byte aligned");
+  return launch_pack(w, 0, rows, cols, dtype, dst, 0, 1, 0, 1, 0, (hipStream_t)stream);
+}
+
+int evict_pack_qkv(const evict_model_desc* m, const void* wq, const void* wk, const void* wv, void* dst, void* stream) {
+  int rc = check_model(m);
+  if (rc) return rc;
+  EVICT_REQUIRE(wq && wk && wv && dst, EVICT_E_INVALID, "evict_pack_qkv: null pointer");
+  EVICT_REQUIRE(aligned16(wq) && aligned16(wk) && aligned16(wv) && aligned16(dst), EVICT_E_INVALID,
+                "evict_pack_qkv: pointers must be 16-byte aligned");
+  hipStream_t s = (hipStream_t)stream;
+  const int q_rows = m->Hq * m->D, kv_rows = m->Hkv * m->D;
+  rc = launch_pack(wq, 0, q_rows, m->d, m->dtype, dst, 0, 1, 0, 1, m->D, s);
+  if (!rc) rc = launch_pack(wk, 0, kv_rows, m->d, m->dtype, dst, q_rows / 16, 1, 0, 1, m->D, s);
+  if (!rc) rc = launch_pack(wv, 0, kv_rows, m->d, m->dtype, dst, (q_rows + kv_rows) / 16, 1, 0, 1, m->D, s);
+  return rc;
+}
+
+int evict_pack_experts(const evict_model_desc* m, int n_experts, const void* w_gate, const void* w_up, const void* w_down,
+                       void* dst_gateup, void* dst_down, void* stream) {
+  int rc = check_model(m);
+  if (rc) return rc;
+  EVICT_REQUIRE(w_gate && w_up && w_down && dst_gateup && dst_down, EVICT_E_INVALID, "evict_pack_experts: null pointer");
+  EVICT_REQUIRE(n_experts >= 1 && n_experts <= 65535, EVICT_E_INVALID, "evict_pack_experts: n_experts=%d", n_experts);
+  EVICT_REQUIRE(aligned16(w_gate) && aligned16(w_up) && aligned16(w_down) && aligned16(dst_gateup) && aligned16(dst_down),
+                EVICT_E_INVALID, "evict_pack_experts: pointers must be 16-byte aligned");
+  hipStream_t s = (hipStream_t)stream;
+  const int eb = elem_bytes(m->dtype);
+  const long long fd = (long long)m->F * m->d * eb;
+  const int fs = m->F / 16;
+  // gate strip s -> strip 2s, up strip s -> strip 2s+1 of the expert's gate/up matrix
+  rc = launch_pack(w_gate, fd, m->F, m->d, m->dtype, dst_gateup, 0, 2, 2 * fs, n_experts, 0, s);
+  if (!rc) rc = launch_pack(w_up, fd, m->F, m->d, m->dtype, dst_gateup, 1, 2, 2 * fs, n_experts, 0, s);
+  if (!rc) rc = launch_pack(w_down, fd, m->d, m->F, m->dtype, dst_down, 0, 1, m->d / 16, n_experts, 0, s);
+  return rc;
+}
+
+int evict_device_status(evict_ctx* ctx, int32_t* status_host, void* stream) {
+  EVICT_REQUIRE(ctx && status_host, EVICT_E_INVALID, "evict_device_status: null pointer");
+  EVICT_HIP_CHECK(hipMemcpyAsync(status_host, ctx->status, 4, hipMemcpyDeviceToHost, (hipStream_t)stream));
+  EVICT_HIP_CHECK(hipStreamSynchronize((hipStream_t)stream));
+  return EVICT_OK;
+}
+
+int evict_verify_layer(evict_ctx* ctx, const evict_layer_weights* w, const int32_t* tree_off, const int32_t* parent, int B,
+                       int T, const void* k_cache, const void* v_cache, int64_t kv_seq_stride, int64_t kv_head_stride,
+                       const int32_t* ctx_len, int max_ctx_host, const void* x_in, void* x_out, void* k_new, void* v_new,
+                       const evict_layer_aux* aux, void* stream) {
+  EVICT_REQUIRE(ctx && w && tree_off && parent && ctx_len && x_in && x_out && k_new && v_new, EVICT_E_INVALID,
+                "evict_verify_layer: null pointer argument");
+  const evict_model_desc& m = ctx->m;
+  EVICT_REQUIRE(w->g_attn && w->g_moe && w->wqkv_packed && w->wo_packed && w->wg && w->w_gateup_packed && w->w_down_packed,
+                EVICT_E_INVALID, "evict_verify_layer: null weight pointer");
+  EVICT_REQUIRE(m.n_shared == 0 || (w->ws_gateup_packed && w->ws_down_packed), EVICT_E_INVALID,
+                "evict_verify_layer: shared-expert weights missing");
+  EVICT_REQUIRE(B >= 1 && B <= ctx->max_batch, EVICT_E_INVALID, "evict_verify_layer: B=%d outside [1,%d]", B, ctx->max_batch);
+  EVICT_REQUIRE(T >= B && T <= ctx->max_tokens, EVICT_E_INVALID, "evict_verify_layer: T=%d outside [%d,%d]", T, B, ctx->max_tokens);
+  EVICT_REQUIRE(T <= (long long)B * EVICT_MAX_TREE_NODES, EVICT_E_UNSUPPORTED, "evict_verify_layer: more than %d nodes per tree",
+                EVICT_MAX_TREE_NODES);
+  EVICT_REQUIRE(max_ctx_host >= 0 && max_ctx_host <= ctx->max_ctx, EVICT_E_INVALID,
+                "evict_verify_layer: max_ctx_host=%d outside [0,%d]", max_ctx_host, ctx->max_ctx);
+  EVICT_REQUIRE(max_ctx_host == 0 || (k_cache && v_cache), EVICT_E_INVALID, "evict_verify_layer: null KV cache");
+  EVICT_REQUIRE(kv_head_stride >= (int64_t)max_ctx_host * m.D && kv_seq_stride >= 0, EVICT_E_INVALID,
+                "evict_verify_layer: kv_head_stride=%lld is smaller than max_ctx_host*D", (long long)kv_head_stride);
+  EVICT_REQUIRE(B == 1 || kv_seq_stride >= kv_head_stride * m.Hkv, EVICT_E_INVALID, "evict_verify_layer: kv_seq_stride too small");
+  EVICT_REQUIRE(aligned16(x_in) && aligned16(x_out) && aligned16(k_new) && aligned16(v_new) && aligned16(k_cache) && aligned16(v_cache),
+                EVICT_E_INVALID, "evict_verify_layer: pointers must be 16-byte aligned");
+  EVICT_REQUIRE(x_in != x_out, EVICT_E_INVALID, "evict_verify_layer: x_out must not alias x_in");
+
+  hipStream_t s = (hipStream_t)stream;
+  const int eb = elem_bytes(m.dtype);
+  const int HqD = m.Hq * m.D;
+  int rc = launch_prep(ctx, tree_off, parent, B, T, ctx_len, max_ctx_host, x_in, w->g_attn, s);
+  if (rc) return rc;
+
+  const int nt_dense = T <= 16 ? 1 : 2;
+  {  // q, k, v projections + rotation (positions ctx_len + depth)
+    GemmArgs a = {};
+    a.W = (const u32x4*)w->wqkv_packed;
+    a.n_strips = (m.Hq + 2 * m.Hkv) * m.D / 16;
+    a.nkb = m.d * eb / 64;
+    a.X = ctx->x_norm;
+    a.ldx_bytes = (long long)m.d * eb;
+    a.T = T;
+    a.out0 = ctx->q; a.out1 = k_new; a.out2 = v_new;
+    a.rope_cs = ctx->rope_cs;
+    a.Hq = m.Hq; a.Hkv = m.Hkv; a.D = m.D;
+    rc = launch_gemm(m.dtype, EPI_QKV, a, nt_dense, a.n_strips < 512 ? a.n_strips : 512, s);
+    if (rc) return rc;
+    if (aux && aux->q) EVICT_HIP_CHECK(hipMemcpyAsync(aux->q, ctx->q, (size_t)T * HqD * eb, hipMemcpyDeviceToDevice, s));
+  }
+  rc = launch_attention(ctx, k_cache, v_cache, kv_seq_stride, kv_head_stride, ctx_len, max_ctx_host, tree_off, B, T, k_new,
+                        v_new, aux ? aux->attn_out : nullptr, s);
+  if (rc) return rc;
+  {  // output projection + residual
+    GemmArgs a = {};
+    a.W = (const u32x4*)w->wo_packed;
+    a.n_strips = m.d / 16;
+    a.nkb = HqD * eb / 64;
+    a.X = ctx->attn_o;
+    a.ldx_bytes = (long long)HqD * eb;
+    a.T = T;
+    a.out0 = ctx->h;
+    a.ldo = m.d;
+    a.resid = x_in;
+    rc = launch_gemm(m.dtype, EPI_RESID, a, nt_dense, a.n_strips < 512 ? a.n_strips : 512, s);
+    if (rc) return rc;
+    if (aux && aux->h) EVICT_HIP_CHECK(hipMemcpyAsync(aux->h, ctx->h, (size_t)T * m.d * eb, hipMemcpyDeviceToDevice, s));
+  }
+  rc = launch_router(ctx, w->g_moe, w->wg, T, aux, s);
+  if (rc) return rc;
+  rc = evict_expert_union(ctx, ctx->topk_idx, T, m.k, m.E, ctx->union_ids, ctx->union_count, ctx->hist, ctx->offsets,
+                          ctx->perm, ctx->inv, stream);
+  if (rc) return rc;
+  if (aux) {
+    if (aux->union_ids) EVICT_HIP_CHECK(hipMemcpyAsync(aux->union_ids, ctx->union_ids, (size_t)m.E * 4, hipMemcpyDeviceToDevice, s));
+    if (aux->union_count) EVICT_HIP_CHECK(hipMemcpyAsync(aux->union_count, ctx->union_count, 4, hipMemcpyDeviceToDevice, s));
+    if (aux->hist) EVICT_HIP_CHECK(hipMemcpyAsync(aux->hist, ctx->hist, (size_t)m.E * 4, hipMemcpyDeviceToDevice, s));
+  }
+  const int nt_exp = T <= 48 ? 1 : 2;
+  {  // gate/up projections of the union experts + SiLU gating
+    GemmArgs a = {};
+    a.W = (const u32x4*)w->w_gateup_packed;
+    a.n_strips = 2 * m.F / 16;
+    a.nkb = m.d * eb / 64;
+    a.group_stride = (long long)a.n_strips * a.nkb * 64;
+    a.X = ctx->h_norm;
+    a.ldx_bytes = (long long)m.d * eb;
+    a.grouped = 1;
+    a.union_ids = ctx->union_ids; a.union_count = ctx->union_count; a.offsets = ctx->offsets; a.perm = ctx->perm;
+    a.topk = m.k;
+    a.x_by_token = 1;
+    a.out0 = ctx->act;
+    a.ldo = m.F;
+    rc = launch_gemm(m.dtype, EPI_SWIGLU, a, nt_exp, 512, s);
+    if (rc) return rc;
+  }
+  {  // down projections
+    GemmArgs a = {};
+    a.W = (const u32x4*)w->w_down_packed;
+    a.n_strips = m.d / 16;
+    a.nkb = m.F * eb / 64;
+    a.group_stride = (long long)a.n_strips * a.nkb * 64;
+    a.X = ctx->act;
+    a.ldx_bytes = (long long)m.F * eb;
+    a.grouped = 1;
+    a.union_ids = ctx->union_ids; a.union_count = ctx->union_count; a.offsets = ctx->offsets; a.perm = ctx->perm;
+    a.topk = m.k;
+    a.x_by_token = 0;
+    a.out0 = ctx->y;
+    a.ldo = m.d;
+    rc = launch_gemm(m.dtype, EPI_F32, a, nt_exp, 512, s);
+    if (rc) return rc;
+  }
+  for (int sh = 0; sh < m.n_shared; ++sh) {  // always-on shared experts on all tokens
+    GemmArgs a = {};
+    a.n_strips = 2 * m.F / 16;
+    a.nkb = m.d * eb / 64;
+    a.W = (const u32x4*)w->ws_gateup_packed + (long long)sh * a.n_strips * a.nkb * 64;
+    a.X = ctx->h_norm;
+    a.ldx_bytes = (long long)m.d * eb;
+    a.T = T;
+    a.out0 = (char*)ctx->act_sh + (size_t)sh * T * m.F * eb;
+    a.ldo = m.F;
+    rc = launch_gemm(m.dtype, EPI_SWIGLU, a, nt_dense, (a.n_strips / 2) < 512 ? (a.n_strips / 2) : 512, s);
+    if (rc) return rc;
+    GemmArgs b = {};
+    b.n_strips = m.d / 16;
+    b.nkb = m.F * eb / 64;
+    b.W = (const u32x4*)w->ws_down_packed + (long long)sh * b.n_strips * b.nkb * 64;
+    b.X = a.out0;
+    b.ldx_bytes = (long long)m.F * eb;
+    b.T = T;
+    b.out0 = ctx->y_sh + (size_t)sh * T * m.d;
+    b.ldo = m.d;
+    rc = launch_gemm(m.dtype, EPI_F32, b, nt_dense, b.n_strips < 512 ? b.n_strips : 512, s);
+    if (rc) return rc;
+  }
+  return launch_combine(ctx, T, x_out, s);
+}
+
+}  // extern "C"

@@ -1,0 +1,36 @@
+// Private definition of the opaque context: model shape plus scratch buffers allocated once.
+#pragma once
+#include "common.h"
+
+struct evict_ctx {
+  evict_model_desc m;
+  int max_tokens, max_batch, max_ctx;
+  int device;
+  int max_splits;        // KV splits the attention scratch is sized for (context part)
+  // ---- device scratch (all sized for max_tokens) ----
+  int32_t* status;       // [1] sticky status bits
+  uint64_t* anc;         // [T][2] ancestor-or-self bitmask of each node (tree-local bit index)
+  int32_t* depth;        // [T]
+  int32_t* seq_of;       // [T] sequence index of each token
+  float* rope_cs;        // [T][D] cos (first half) and sin (second half) per token
+  void* x_norm;          // [T][d] storage dtype
+  void* q;               // [T][Hq*D]
+  float* part_o;         // [splits+1][T][Hq][D]
+  float* part_ml;        // [splits+1][T][Hq][2]
+  void* attn_o;          // [T][Hq*D]
+  void* h;               // [T][d]
+  void* h_norm;          // [T][d]
+  float* logits;         // [T][E]
+  int32_t* topk_idx;     // [T][k]
+  float* topk_w;         // [T][k]
+  int32_t* hist;         // [E]
+  int32_t* offsets;      // [E+1]
+  int32_t* union_ids;    // [E]
+  int32_t* union_count;  // [1]
+  int32_t* perm;         // [T*k]
+  int32_t* inv;          // [T*k]
+  void* act;             // [T*k][F] storage dtype
+  float* y;              // [T*k][d]
+  void* act_sh;          // [n_shared][T][F]
+  float* y_sh;           // [n_shared][T][d]
+};

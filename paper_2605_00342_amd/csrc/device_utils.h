@@ -1,0 +1,92 @@
+// Device-side helpers: storage-type traits (fp32 / bf16), MFMA wrappers for gfx950,
+// wavefront reductions, an LDS-only barrier.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace evict {
+
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+
+struct F32 { typedef float elem; static constexpr int kBytes = 4; static constexpr int kBlockElems = 16; };
+struct BF16 { typedef uint16_t elem; static constexpr int kBytes = 2; static constexpr int kBlockElems = 32; };
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+// round-to-nearest-even; inputs are finite on this path
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+template <typename ST> __device__ __forceinline__ float load_elem(const void* p, size_t i);
+template <> __device__ __forceinline__ float load_elem<F32>(const void* p, size_t i) { return ((const float*)p)[i]; }
+template <> __device__ __forceinline__ float load_elem<BF16>(const void* p, size_t i) { return bf16_to_f32(((const uint16_t*)p)[i]); }
+
+template <typename ST> __device__ __forceinline__ void store_elem(void* p, size_t i, float v);
+template <> __device__ __forceinline__ void store_elem<F32>(void* p, size_t i, float v) { ((float*)p)[i] = v; }
+template <> __device__ __forceinline__ void store_elem<BF16>(void* p, size_t i, float v) { ((uint16_t*)p)[i] = f32_to_bf16(v); }
+
+// value after rounding to the storage type
+template <typename ST> __device__ __forceinline__ float round_store(float v);
+template <> __device__ __forceinline__ float round_store<F32>(float v) { return v; }
+template <> __device__ __forceinline__ float round_store<BF16>(float v) { return bf16_to_f32(f32_to_bf16(v)); }
+
+// Store 4 consecutive elements (16-byte aligned destination for fp32, 8-byte for bf16).
+template <typename ST> __device__ __forceinline__ void store4(void* p, size_t i, f32x4 v);
+template <> __device__ __forceinline__ void store4<F32>(void* p, size_t i, f32x4 v) {
+  *reinterpret_cast<f32x4*>((float*)p + i) = v;
+}
+template <> __device__ __forceinline__ void store4<BF16>(void* p, size_t i, f32x4 v) {
+  uint2 o;
+  o.x = (uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16);
+  o.y = (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16);
+  *reinterpret_cast<uint2*>((uint16_t*)p + i) = o;
+}
+template <typename ST> __device__ __forceinline__ f32x4 load4(const void* p, size_t i);
+template <> __device__ __forceinline__ f32x4 load4<F32>(const void* p, size_t i) {
+  return *reinterpret_cast<const f32x4*>((const float*)p + i);
+}
+template <> __device__ __forceinline__ f32x4 load4<BF16>(const void* p, size_t i) {
+  uint2 o = *reinterpret_cast<const uint2*>((const uint16_t*)p + i);
+  f32x4 v;
+  v[0] = __uint_as_float(o.x << 16); v[1] = __uint_as_float(o.x & 0xFFFF0000u);
+  v[2] = __uint_as_float(o.y << 16); v[3] = __uint_as_float(o.y & 0xFFFF0000u);
+  return v;
+}
+
+// One 1 KiB operand block: each lane holds 16 bytes. With A[m][k] (16 rows) and B[k][n]
+// (16 columns), lane l carries row/column l%16 and the (l/16)-th quarter of the block's
+// contraction range; both operands use the same mapping so any k order cancels out.
+template <typename ST> __device__ __forceinline__ f32x4 mfma_block(u32x4 a, u32x4 b, f32x4 c);
+template <> __device__ __forceinline__ f32x4 mfma_block<BF16>(u32x4 a, u32x4 b, f32x4 c) {
+  union { u32x4 u; bf16x8 v; } ua, ub;
+  ua.u = a; ub.u = b;
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(ua.v, ub.v, c, 0, 0, 0);
+}
+template <> __device__ __forceinline__ f32x4 mfma_block<F32>(u32x4 a, u32x4 b, f32x4 c) {
+  c = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a[0]), __uint_as_float(b[0]), c, 0, 0, 0);
+  c = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a[1]), __uint_as_float(b[1]), c, 0, 0, 0);
+  c = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a[2]), __uint_as_float(b[2]), c, 0, 0, 0);
+  c = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a[3]), __uint_as_float(b[3]), c, 0, 0, 0);
+  return c;
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+  return v;
+}
+
+// Workgroup barrier that waits for LDS traffic only, so that global loads already in
+// flight (weight prefetch) stay in flight across it.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+}  // namespace evict

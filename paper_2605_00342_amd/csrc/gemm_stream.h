@@ -1,0 +1,226 @@
+// Weight-streaming skinny GEMM for gfx950: out[token][row] = sum_k W[row][k] * X[token][k]
+// with at most a few dozen tokens per weight matrix, so the kernel is bound by reading W
+// from HBM exactly once. Used for the QKV / output projections and for the grouped expert
+// GEMMs over the union of activated experts (Sec. 2.2, Eq. 5).
+//
+// Layout: W is pre-packed into 16-row strips; a strip is nkb consecutive 1 KiB blocks, one
+// block = one wavefront-wide 16-byte load = one MFMA operand (64 bytes of each of 16 rows).
+// A workgroup of 8 wavefronts owns a contiguous range of strips (contiguous in memory, so
+// the stream is sequential); the contraction range of a strip is split across the 8
+// wavefronts, each keeping its slice of the token operand in registers for as long as the
+// expert does not change. Partial tiles meet in LDS, one wavefront (rotating) sums them and
+// runs the epilogue. The whole work list (union experts x strips) is cut into equal
+// contiguous ranges on the device, so no host knowledge of the union size is needed.
+#pragma once
+#include "device_utils.h"
+
+namespace evict {
+
+enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_F32 = 3 };
+
+struct GemmArgs {
+  const u32x4* W;        // packed weights
+  long long group_stride;  // u32x4 elements between experts
+  int n_strips;          // 16-row strips per matrix (gate/up interleaved: 2 per 16 rows of F)
+  int nkb;               // 1 KiB blocks per strip
+  const void* X;         // token operand rows, storage dtype
+  long long ldx_bytes;   // bytes between rows of X
+  int grouped;           // 0: one matrix, tokens 0..T-1; 1: one matrix per union expert
+  const int* union_ids;
+  const int* union_count;
+  const int* offsets;    // by expert id
+  const int* perm;       // pair ids grouped by expert
+  int topk;
+  int x_by_token;        // grouped: 1 -> X row = perm[p] / topk, 0 -> X row = p
+  int T;                 // dense: token rows
+  void* out0;            // QKV: q; RESID: h; SWIGLU: act; F32: y
+  void* out1;            // QKV: k_new
+  void* out2;            // QKV: v_new
+  long long ldo;         // elements between output rows (RESID / SWIGLU / F32)
+  const void* resid;     // RESID: residual rows, same layout as out0
+  const float* rope_cs;  // QKV: [T][D] cos | sin
+  int Hq, Hkv, D;
+};
+
+constexpr int kGemmWaves = 8;
+constexpr int kGemmThreads = kGemmWaves * 64;
+
+template <typename ST, int NT, int KBW, int PF, int EPI>
+__global__ __launch_bounds__(kGemmThreads) void gemm_stream_kernel(const GemmArgs a) {
+  constexpr int SPU = (EPI == EPI_SWIGLU) ? 2 : 1;  // strips per unit of work
+  __shared__ f32x4 s_part[2][kGemmWaves][NT][64];
+
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int upg = a.n_strips / SPU;
+  const int ngroups = a.grouped ? *a.union_count : 1;
+  const long long tot = (long long)ngroups * upg;
+  const long long u0 = tot * blockIdx.x / gridDim.x;
+  const long long u1 = tot * (blockIdx.x + 1) / gridDim.x;
+  const int nkb = a.nkb;
+  const int nchunks = (nkb + 63) >> 6;
+  int parity = 0;
+
+  for (long long unit = u0; unit < u1;) {
+    const int grp = (int)(unit / upg);
+    long long seg_end = (long long)(grp + 1) * upg;
+    if (seg_end > u1) seg_end = u1;
+    const int unit_in_grp = (int)(unit - (long long)grp * upg);
+    const int strip0 = unit_in_grp * SPU;
+    const int nitems = (int)(seg_end - unit) * SPU;
+    int p0 = 0, ntok = a.T;
+    const u32x4* wbase = a.W;
+    if (a.grouped) {
+      const int e = a.union_ids[grp];
+      p0 = a.offsets[e];
+      ntok = a.offsets[e + 1] - p0;
+      wbase += (long long)e * a.group_stride;
+    }
+    const int nsteps = nitems * nchunks;
+
+    for (int tok0 = 0; tok0 < ntok; tok0 += 16 * NT) {
+      // token operand rows of this lane's column in each tile
+      const char* xrow[NT];
+#pragma unroll
+      for (int t = 0; t < NT; ++t) {
+        int col = tok0 + t * 16 + (lane & 15);
+        if (col > ntok - 1) col = ntok - 1;  // padded columns repeat the last token; never stored
+        long long row = col;
+        if (a.grouped) row = a.x_by_token ? (a.perm[p0 + col] / a.topk) : (p0 + col);
+        xrow[t] = (const char*)a.X + row * a.ldx_bytes + (lane >> 4) * 16;
+      }
+      u32x4 A[PF][KBW];
+      u32x4 Bf[NT][KBW];
+      f32x4 acc[NT];
+      f32x4 gate[NT];
+#pragma unroll
+      for (int t = 0; t < NT; ++t) { acc[t] = f32x4{0, 0, 0, 0}; gate[t] = f32x4{0, 0, 0, 0}; }
+
+      // block range of this wavefront inside chunk c: [b0, b0 + nb)
+      auto range = [&](int c, int& b0, int& nb) {
+        int cb = nkb - c * 64;
+        cb = cb > 64 ? 64 : cb;
+        b0 = c * 64 + (w * cb) / kGemmWaves;
+        nb = c * 64 + ((w + 1) * cb) / kGemmWaves - b0;
+      };
+      auto issue = [&](u32x4(&dst)[KBW], int step) {
+        const int it = step / nchunks, c = step - it * nchunks;
+        int b0, nb;
+        range(c, b0, nb);
+        const u32x4* p = wbase + ((long long)(strip0 + it) * nkb + b0) * 64 + lane;
+#pragma unroll
+        for (int j = 0; j < KBW; ++j)
+          if (j < nb) dst[j] = __builtin_nontemporal_load(p + j * 64);
+      };
+      auto load_b = [&](int c) {
+        int b0, nb;
+        range(c, b0, nb);
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+          for (int j = 0; j < KBW; ++j)
+            if (j < nb) Bf[t][j] = *reinterpret_cast<const u32x4*>(xrow[t] + (long long)(b0 + j) * 64);
+      };
+
+#pragma unroll
+      for (int r = 0; r < PF; ++r)
+        if (r < nsteps) issue(A[r], r);
+      if (nchunks == 1) load_b(0);
+
+      for (int s0 = 0; s0 < nsteps; s0 += PF) {
+#pragma unroll
+        for (int r = 0; r < PF; ++r) {
+          const int step = s0 + r;
+          if (step < nsteps) {
+            const int it = step / nchunks, c = step - it * nchunks;
+            if (nchunks > 1) load_b(c);
+            int b0, nb;
+            range(c, b0, nb);
+#pragma unroll
+            for (int j = 0; j < KBW; ++j)
+              if (j < nb) {
+#pragma unroll
+                for (int t = 0; t < NT; ++t) acc[t] = mfma_block<ST>(A[r][j], Bf[t][j], acc[t]);
+              }
+            if (step + PF < nsteps) issue(A[r], step + PF);
+            if (c == nchunks - 1) {
+              // strip finished: exchange partial tiles, one wavefront reduces and stores
+#pragma unroll
+              for (int t = 0; t < NT; ++t) {
+                s_part[parity][w][t][lane] = acc[t];
+                acc[t] = f32x4{0, 0, 0, 0};
+              }
+              lds_barrier();
+              const int strip = strip0 + it;
+              const int reducer = ((unit_in_grp + it / SPU) & (kGemmWaves - 1));
+              if (w == reducer) {
+#pragma unroll
+                for (int t = 0; t < NT; ++t) {
+                  f32x4 sum = s_part[parity][0][t][lane];
+#pragma unroll
+                  for (int ww = 1; ww < kGemmWaves; ++ww) sum += s_part[parity][ww][t][lane];
+                  const int col = tok0 + t * 16 + (lane & 15);
+                  const bool valid = col < ntok;
+                  const int m0 = (lane >> 4) * 4;  // first of this lane's 4 rows in the strip
+                  if (EPI == EPI_F32) {
+                    if (valid) {
+                      const long long orow = a.grouped ? (p0 + col) : col;
+                      *reinterpret_cast<f32x4*>((float*)a.out0 + orow * a.ldo + strip * 16 + m0) = sum;
+                    }
+                  } else if (EPI == EPI_RESID) {
+                    if (valid) {
+                      const long long o = (long long)col * a.ldo + strip * 16 + m0;
+                      f32x4 rsd = load4<ST>(a.resid, o);
+                      store4<ST>(a.out0, o, rsd + sum);
+                    }
+                  } else if (EPI == EPI_SWIGLU) {
+                    if ((it & 1) == 0) {
+                      gate[t] = sum;  // gate strip; its up strip is the next item
+                    } else if (valid) {
+                      f32x4 g = gate[t], r4;
+#pragma unroll
+                      for (int i = 0; i < 4; ++i) r4[i] = (g[i] / (1.0f + __expf(-g[i]))) * sum[i];
+                      const long long orow = a.grouped ? (p0 + col) : col;
+                      store4<ST>(a.out0, orow * a.ldo + (strip >> 1) * 16 + m0, r4);
+                    }
+                  } else {  // EPI_QKV: rotate pairs (i, i + D/2), which sit 32 lanes apart
+                    const int spd = a.D >> 4;  // strips per head
+                    const int head = strip / spd, js = strip - head * spd;
+                    const int half = a.D >> 1;
+                    const int g4 = lane >> 4;
+                    const int idx = js * 8 + (g4 & 1) * 4;  // index inside the half
+                    f32x4 other, r4;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) other[i] = __shfl_xor(sum[i], 32);
+                    const int tokc = valid ? col : 0;
+                    const float* cs = a.rope_cs + (long long)tokc * a.D;
+                    const bool rot = head < a.Hq + a.Hkv;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                      const float cv = rot ? cs[idx + i] : 1.0f;
+                      const float sv = rot ? cs[half + idx + i] : 0.0f;
+                      r4[i] = (g4 < 2) ? (sum[i] * cv - other[i] * sv) : (sum[i] * cv + other[i] * sv);
+                    }
+                    if (valid) {
+                      const int hrow = (g4 < 2 ? 0 : half) + idx;
+                      if (head < a.Hq) {
+                        store4<ST>(a.out0, ((long long)col * a.Hq + head) * a.D + hrow, r4);
+                      } else if (head < a.Hq + a.Hkv) {
+                        store4<ST>(a.out1, ((long long)col * a.Hkv + (head - a.Hq)) * a.D + hrow, r4);
+                      } else {
+                        store4<ST>(a.out2, ((long long)col * a.Hkv + (head - a.Hq - a.Hkv)) * a.D + hrow, r4);
+                      }
+                    }
+                  }
+                }
+              }
+              parity ^= 1;
+            }
+          }
+        }
+      }
+    }
+    unit = seg_end;
+  }
+}
+
+}  // namespace evict

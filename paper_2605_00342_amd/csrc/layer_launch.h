@@ -1,0 +1,22 @@
+// Host-side launchers of the layer kernels (defined in layer_kernels.hip).
+#pragma once
+#include "ctx.h"
+
+namespace evict {
+
+struct GemmArgs;
+
+int launch_gemm(int dtype, int epi, const GemmArgs& a, int nt, int grid, hipStream_t s);
+int launch_pack(const void* src, long long src_group_bytes, int rows, int cols, int dtype, void* dst, int dst_strip0,
+                int dst_strip_step, long long dst_group_strips, int groups, int head_dim, hipStream_t s);
+int launch_prep(const evict_ctx* c, const int32_t* tree_off, const int32_t* parent, int B, int T, const int32_t* ctx_len,
+                int max_ctx, const void* x, const void* gain, hipStream_t s);
+int attn_setup();
+int attn_splits_for(int max_ctx);
+int launch_attention(const evict_ctx* c, const void* kc, const void* vc, long long seq_stride, long long head_stride,
+                     const int32_t* ctx_len, int max_ctx_host, const int32_t* tree_off, int B, int T, const void* k_new,
+                     const void* v_new, void* aux_out, hipStream_t s);
+int launch_router(const evict_ctx* c, const void* gain, const void* wg, int T, const evict_layer_aux* aux, hipStream_t s);
+int launch_combine(const evict_ctx* c, int T, void* out, hipStream_t s);
+
+}  // namespace evict

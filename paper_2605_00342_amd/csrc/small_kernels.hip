@@ -1,0 +1,429 @@
+// Integer / latency-bound parts of the verification step: EVICT prefix selection
+// (Sec. 3.1-3.2), greedy acceptance (Sec. 2.1, temperature 0), the expert union and the
+// token grouping it induces (Eq. 5), row gather for tree compaction.
+#include <stdarg.h>
+#include <string.h>
+
+#include "ctx.h"
+
+namespace evict {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
+
+namespace {
+
+constexpr int kSelThreads = 256;
+constexpr int kMaxSel = EVICT_MAX_SELECT_NODES;
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
+
+__device__ __forceinline__ int wave_incl_scan(int v) {
+  const int lane = lane_id();
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    int t = __shfl_up(v, o);
+    if (lane >= o) v += t;
+  }
+  return v;
+}
+
+// Exclusive prefix sum over the block (blockDim.x multiple of 64, <= 1024 threads).
+__device__ int block_excl_scan(int v, int* s_wave, int* total) {
+  const int lane = lane_id(), w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  int incl = wave_incl_scan(v);
+  __syncthreads();
+  if (lane == 63) s_wave[w] = incl;
+  __syncthreads();
+  int base = 0, tot = 0;
+  for (int i = 0; i < nw; ++i) {
+    int x = s_wave[i];
+    if (i < w) base += x;
+    tot += x;
+  }
+  *total = tot;
+  return base + incl - v;
+}
+
+// Kept-set compaction of one tree: nodes with rank < kstar, ascending node id; parents
+// re-indexed into the kept set. s_flag/s_new are LDS arrays of n ints.
+__device__ void compact_tree(int n, int kstar, const int* s_par, const int* s_rank, int* s_new, int* s_wave,
+                             int32_t* keep_out, int32_t* newpar_out) {
+  const int tid = threadIdx.x;
+  // 4 consecutive nodes per thread so that the scan keeps node order
+  int f[4], cnt = 0;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    int i = tid * 4 + j;
+    f[j] = (i < n && s_rank[i] < kstar) ? 1 : 0;
+    cnt += f[j];
+  }
+  int total;
+  int base = block_excl_scan(cnt, s_wave, &total);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    int i = tid * 4 + j;
+    if (i < n) s_new[i] = f[j] ? base : -1;
+    base += f[j];
+  }
+  __syncthreads();
+  for (int i = tid; i < n; i += blockDim.x) {
+    int ni = s_new[i];
+    if (ni >= 0) {
+      keep_out[ni] = i;
+      int p = s_par[i];
+      newpar_out[ni] = p < 0 ? -1 : s_new[p];
+    }
+  }
+}
+
+// One workgroup per tree. Writes k*, S_{k*}, the ranking and the running sums; when
+// `single` it also writes the compacted tree (B == 1), otherwise ranks go to rank_ws for
+// the second kernel.
+__global__ __launch_bounds__(kSelThreads) void select_prefix_kernel(
+    const int32_t* __restrict__ tree_off, const int32_t* __restrict__ parent, const float* __restrict__ prob,
+    const float* __restrict__ cost, int kmax, int32_t* __restrict__ k_star, float* __restrict__ est_len,
+    int32_t* __restrict__ order_out, float* __restrict__ psum_out, int32_t* __restrict__ rank_ws, int single,
+    int32_t* __restrict__ keep, int32_t* __restrict__ new_parent, int32_t* __restrict__ new_tree_off) {
+  __shared__ int s_par[kMaxSel];
+  __shared__ float s_score[kMaxSel];
+  __shared__ float s_sorted[kMaxSel];
+  __shared__ int s_rank[kMaxSel];
+  __shared__ int s_aux[kMaxSel];  // depth, later new index
+  __shared__ int s_wave[16];
+  __shared__ float s_bestv[4];
+  __shared__ int s_besti[4];
+  __shared__ int s_maxdep;
+
+  const int b = blockIdx.x, tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
+  const int lo = tree_off[b];
+  int n = tree_off[b + 1] - lo;
+  n = n < 1 ? 1 : (n > kMaxSel ? kMaxSel : n);
+
+  if (tid == 0) s_maxdep = 0;
+  for (int i = tid; i < n; i += kSelThreads) {
+    int p = parent[lo + i];
+    if (i == 0) p = -1;
+    else if (p < 0 || p >= i) p = 0;  // invalid ids are clamped (the host check rejects them)
+    s_par[i] = p;
+  }
+  __syncthreads();
+  // depth of every node (walk to the root; parent ids strictly decrease)
+  int mydep_max = 0;
+  for (int i = tid; i < n; i += kSelThreads) {
+    int dep = 0;
+    for (int p = s_par[i]; p >= 0; p = s_par[p]) ++dep;
+    s_aux[i] = dep;
+    mydep_max = dep > mydep_max ? dep : mydep_max;
+  }
+  atomicMax(&s_maxdep, mydep_max);
+  if (tid == 0) s_score[0] = 1.0f;  // the root counts as probability 1 (Eq. 7)
+  __syncthreads();
+  const int maxdep = s_maxdep;
+  // Score(v) = Score(parent(v)) * q(v): one rounded fp32 multiply per node, level by level
+  for (int lvl = 1; lvl <= maxdep; ++lvl) {
+    for (int i = tid; i < n; i += kSelThreads)
+      if (s_aux[i] == lvl) s_score[i] = __fmul_rn(s_score[s_par[i]], prob[lo + i]);
+    __syncthreads();
+  }
+  // rank by (score descending, index ascending)
+  for (int i = tid; i < n; i += kSelThreads) {
+    const float si = s_score[i];
+    int r = 0;
+    for (int j = 0; j < n; ++j) {
+      const float sj = s_score[j];
+      r += (sj > si || (sj == si && j < i)) ? 1 : 0;
+    }
+    s_rank[i] = r;
+    s_sorted[r] = si;
+    if (order_out) order_out[lo + r] = i;
+  }
+  __syncthreads();
+  // S_k: sequential fp32 running sum over the ranking (one wavefront, lane broadcast)
+  if (w == 0) {
+    float acc = 0.0f;
+    for (int c = 0; c < n; c += 64) {
+      const int idx = c + lane;
+      const int vbits = __float_as_int(idx < n ? s_sorted[idx] : 0.0f);
+      float mine = 0.0f;
+      const int lim = (n - c) < 64 ? (n - c) : 64;
+      for (int j = 0; j < lim; ++j) {
+        acc = __fadd_rn(acc, __int_as_float(__builtin_amdgcn_readlane(vbits, j)));
+        if (lane == j) mine = acc;
+      }
+      if (idx < n) s_sorted[idx] = mine;  // now holds S_{idx+1}
+    }
+  }
+  __syncthreads();
+  // u_k = S_k / cost[k]; k* = smallest k attaining the maximum over 1..min(n, kmax)
+  const int kk = n < kmax ? n : kmax;
+  float bv = -1.0f;
+  int bi = 0x7fffffff;
+  for (int i = tid; i < n; i += kSelThreads) {
+    const float S = s_sorted[i];
+    if (psum_out) psum_out[lo + i] = S;
+    if (i < kk) {
+      const float u = __fdiv_rn(S, cost[i + 1]);
+      if (u > bv || (u == bv && i < bi)) { bv = u; bi = i; }
+    }
+  }
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) {
+    const float ov = __shfl_xor(bv, o);
+    const int oi = __shfl_xor(bi, o);
+    if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+  }
+  if (lane == 0) { s_bestv[w] = bv; s_besti[w] = bi; }
+  __syncthreads();
+  bv = s_bestv[0]; bi = s_besti[0];
+  for (int i = 1; i < kSelThreads / 64; ++i) {
+    const float ov = s_bestv[i];
+    const int oi = s_besti[i];
+    if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+  }
+  const int kstar = bi + 1;
+  if (tid == 0) {
+    k_star[b] = kstar;
+    est_len[b] = s_sorted[bi];
+  }
+  if (single) {
+    if (tid == 0) { new_tree_off[0] = 0; new_tree_off[1] = kstar; }
+    compact_tree(n, kstar, s_par, s_rank, s_aux, s_wave, keep, new_parent);
+  } else {
+    for (int i = tid; i < n; i += kSelThreads) rank_ws[lo + i] = s_rank[i];
+  }
+}
+
+// Second step for batches: one workgroup walks the trees in order, so that tree b's
+// compacted output (which starts at or before tree b's own input offset) never overwrites
+// ranks of a tree not yet read. rank_ws aliases new_parent.
+__global__ __launch_bounds__(kSelThreads) void compact_batch_kernel(
+    const int32_t* __restrict__ tree_off, const int32_t* __restrict__ parent, const int32_t* __restrict__ k_star,
+    int B, int32_t* rank_ws, int32_t* keep, int32_t* new_parent, int32_t* __restrict__ new_tree_off) {
+  __shared__ int s_par[kMaxSel];
+  __shared__ int s_rank[kMaxSel];
+  __shared__ int s_new[kMaxSel];
+  __shared__ int s_wave[16];
+  const int tid = threadIdx.x;
+  int out = 0;
+  for (int b = 0; b < B; ++b) {
+    const int lo = tree_off[b];
+    int n = tree_off[b + 1] - lo;
+    n = n < 1 ? 1 : (n > kMaxSel ? kMaxSel : n);
+    const int ks = k_star[b];
+    __syncthreads();
+    for (int i = tid; i < n; i += kSelThreads) {
+      int p = parent[lo + i];
+      if (i == 0) p = -1;
+      else if (p < 0 || p >= i) p = 0;
+      s_par[i] = p;
+      s_rank[i] = rank_ws[lo + i];
+    }
+    __syncthreads();
+    if (tid == 0) new_tree_off[b] = out;
+    compact_tree(n, ks, s_par, s_rank, s_new, s_wave, keep + out, new_parent + out);
+    out += ks;
+  }
+  if (tid == 0) new_tree_off[B] = out;
+}
+
+// One wavefront per tree.
+__global__ __launch_bounds__(64) void accept_path_kernel(
+    const int32_t* __restrict__ tree_off, const int32_t* __restrict__ parent, const int32_t* __restrict__ tok,
+    const int32_t* __restrict__ next, int32_t* __restrict__ path, int path_stride, int32_t* __restrict__ path_len,
+    int32_t* __restrict__ bonus) {
+  const int b = blockIdx.x, lane = threadIdx.x;
+  const int lo = tree_off[b];
+  const int n = tree_off[b + 1] - lo;
+  int32_t* my = path + (size_t)b * path_stride;
+  for (int i = lane; i < path_stride; i += 64) my[i] = i == 0 ? 0 : -1;
+  int cur = 0, len = 1;
+  while (true) {
+    const int want = next[lo + cur];
+    int found = -1;
+    for (int base = cur + 1; base < n; base += 64) {
+      const int c = base + lane;
+      const bool m = c < n && parent[lo + c] == cur && tok[lo + c] == want;
+      const unsigned long long mask = __ballot(m);
+      if (mask) { found = base + __ffsll((long long)mask) - 1; break; }
+    }
+    if (found < 0) break;
+    cur = found;  // strictly increasing: the walk ends
+    if (lane == 0 && len < path_stride) my[len] = cur;
+    ++len;
+  }
+  if (lane == 0) { path_len[b] = len; bonus[b] = next[lo + cur]; }
+}
+
+constexpr int kUnionThreads = 256;
+
+__global__ __launch_bounds__(kUnionThreads) void expert_union_kernel(
+    const int32_t* __restrict__ topk_idx, int P, int E, int32_t* __restrict__ union_ids,
+    int32_t* __restrict__ union_count, int32_t* __restrict__ hist, int32_t* __restrict__ offsets,
+    int32_t* __restrict__ perm, int32_t* __restrict__ inv, int32_t* __restrict__ status) {
+  extern __shared__ int s_mem[];
+  int* s_idx = s_mem;            // [P]
+  int* s_hist = s_mem + P;       // [E]
+  int* s_off = s_hist + E;       // [E + 1]
+  __shared__ int s_wave[16];
+  const int tid = threadIdx.x;
+  for (int e = tid; e < E; e += kUnionThreads) s_hist[e] = 0;
+  __syncthreads();
+  bool bad = false;
+  for (int p = tid; p < P; p += kUnionThreads) {
+    int e = topk_idx[p];
+    if (e < 0 || e >= E) { bad = true; e = 0; }
+    s_idx[p] = e;
+    atomicAdd(&s_hist[e], 1);
+  }
+  if (bad && status) atomicOr(status, ST_BAD_EXPERT);
+  __syncthreads();
+  // exclusive scan of hist and of the activated flags, 4 consecutive experts per thread
+  int h[4], hs = 0, fs = 0;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int e = tid * 4 + j;
+    h[j] = e < E ? s_hist[e] : 0;
+    hs += h[j];
+    fs += h[j] > 0 ? 1 : 0;
+  }
+  int tot_h, tot_f;
+  int base_h = block_excl_scan(hs, s_wave, &tot_h);
+  int base_f = block_excl_scan(fs, s_wave, &tot_f);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int e = tid * 4 + j;
+    if (e < E) {
+      s_off[e] = base_h;
+      offsets[e] = base_h;
+      hist[e] = h[j];
+      if (h[j] > 0) union_ids[base_f] = e;
+    }
+    base_h += h[j];
+    base_f += h[j] > 0 ? 1 : 0;
+  }
+  for (int e = tot_f + tid; e < E; e += kUnionThreads) union_ids[e] = -1;
+  if (tid == 0) { offsets[E] = tot_h; union_count[0] = tot_f; }
+  __syncthreads();
+  // stable grouping: one thread per expert walks the pairs in ascending pair id
+  for (int e = tid; e < E; e += kUnionThreads) {
+    if (s_hist[e] == 0) continue;
+    int pos = s_off[e];
+    for (int p = 0; p < P; ++p) {
+      if (s_idx[p] == e) {
+        perm[pos] = p;
+        inv[p] = pos;
+        ++pos;
+      }
+    }
+  }
+}
+
+__global__ void gather_rows_kernel(const uint32_t* __restrict__ src, uint32_t* __restrict__ dst, int row_words,
+                                   const int32_t* __restrict__ tree_off, const int32_t* __restrict__ new_tree_off,
+                                   const int32_t* __restrict__ keep, int B) {
+  const int r = blockIdx.x;  // destination row
+  if (r >= new_tree_off[B]) return;
+  int b = 0;
+  while (b + 1 < B && new_tree_off[b + 1] <= r) ++b;
+  const int s = tree_off[b] + keep[r];
+  for (int i = threadIdx.x; i < row_words; i += blockDim.x) dst[(size_t)r * row_words + i] = src[(size_t)s * row_words + i];
+}
+
+}  // namespace
+}  // namespace evict
+
+using namespace evict;
+
+extern "C" {
+
+int evict_version(void) { return 1; }
+
+const char* evict_last_error(void) { return g_err; }
+
+int evict_validate_trees_host(const int32_t* tree_off, const int32_t* parent, int B, int max_nodes) {
+  EVICT_REQUIRE(tree_off && parent, EVICT_E_INVALID, "null tree arrays");
+  EVICT_REQUIRE(B >= 1, EVICT_E_INVALID, "B must be >= 1 (got %d)", B);
+  EVICT_REQUIRE(tree_off[0] == 0, EVICT_E_INVALID, "tree_off[0] must be 0");
+  for (int b = 0; b < B; ++b) {
+    const int lo = tree_off[b], n = tree_off[b + 1] - lo;
+    EVICT_REQUIRE(n >= 1, EVICT_E_INVALID, "tree %d has %d nodes", b, n);
+    EVICT_REQUIRE(n <= max_nodes, EVICT_E_INVALID, "tree %d has %d nodes, limit %d", b, n, max_nodes);
+    EVICT_REQUIRE(parent[lo] == -1, EVICT_E_INVALID, "tree %d: root parent must be -1", b);
+    for (int i = 1; i < n; ++i)
+      EVICT_REQUIRE(parent[lo + i] >= 0 && parent[lo + i] < i, EVICT_E_INVALID,
+                    "tree %d: parent[%d]=%d is not in [0,%d)", b, i, parent[lo + i], i);
+  }
+  return EVICT_OK;
+}
+
+int evict_select_prefix(evict_ctx*, const int32_t* tree_off, const int32_t* parent, const float* node_prob, int B,
+                        int T, const float* cost, int Kmax, int32_t* k_star, int32_t* keep, int32_t* new_parent,
+                        int32_t* new_tree_off, float* est_len, int32_t* order, float* prefix_sum, void* stream) {
+  EVICT_REQUIRE(tree_off && parent && node_prob && cost && k_star && keep && new_parent && new_tree_off && est_len,
+                EVICT_E_INVALID, "evict_select_prefix: null pointer argument");
+  EVICT_REQUIRE(B >= 1 && T >= B, EVICT_E_INVALID, "evict_select_prefix: need B >= 1 and T >= B (B=%d, T=%d)", B, T);
+  EVICT_REQUIRE(Kmax >= 1, EVICT_E_INVALID, "evict_select_prefix: Kmax must be >= 1 (got %d)", Kmax);
+  EVICT_REQUIRE(T <= B * (int64_t)EVICT_MAX_SELECT_NODES, EVICT_E_UNSUPPORTED,
+                "evict_select_prefix: more than %d nodes per tree", EVICT_MAX_SELECT_NODES);
+  hipStream_t s = (hipStream_t)stream;
+  const int single = B == 1;
+  hipLaunchKernelGGL(select_prefix_kernel, dim3(B), dim3(kSelThreads), 0, s, tree_off, parent, node_prob, cost, Kmax,
+                     k_star, est_len, order, prefix_sum, new_parent /* rank workspace */, single, keep, new_parent,
+                     new_tree_off);
+  int rc = launch_status("select_prefix_kernel");
+  if (rc) return rc;
+  if (!single) {
+    hipLaunchKernelGGL(compact_batch_kernel, dim3(1), dim3(kSelThreads), 0, s, tree_off, parent, k_star, B,
+                       new_parent, keep, new_parent, new_tree_off);
+    rc = launch_status("compact_batch_kernel");
+  }
+  return rc;
+}
+
+int evict_accept_path(evict_ctx*, const int32_t* tree_off, const int32_t* parent, const int32_t* draft_tok,
+                      const int32_t* target_next, int B, int32_t* path, int path_stride, int32_t* path_len,
+                      int32_t* bonus_tok, void* stream) {
+  EVICT_REQUIRE(tree_off && parent && draft_tok && target_next && path && path_len && bonus_tok, EVICT_E_INVALID,
+                "evict_accept_path: null pointer argument");
+  EVICT_REQUIRE(B >= 1, EVICT_E_INVALID, "evict_accept_path: B must be >= 1 (got %d)", B);
+  EVICT_REQUIRE(path_stride >= 1, EVICT_E_INVALID, "evict_accept_path: path_stride must be >= 1");
+  hipLaunchKernelGGL(accept_path_kernel, dim3(B), dim3(64), 0, (hipStream_t)stream, tree_off, parent, draft_tok,
+                     target_next, path, path_stride, path_len, bonus_tok);
+  return launch_status("accept_path_kernel");
+}
+
+int evict_expert_union(evict_ctx* ctx, const int32_t* topk_idx, int T, int k, int E, int32_t* union_ids,
+                       int32_t* union_count, int32_t* hist, int32_t* offsets, int32_t* perm, int32_t* inv,
+                       void* stream) {
+  EVICT_REQUIRE(topk_idx && union_ids && union_count && hist && offsets && perm && inv, EVICT_E_INVALID,
+                "evict_expert_union: null pointer argument");
+  EVICT_REQUIRE(T >= 1 && k >= 1 && E >= 1, EVICT_E_INVALID, "evict_expert_union: T, k, E must be >= 1");
+  EVICT_REQUIRE(k <= E, EVICT_E_INVALID, "evict_expert_union: k=%d exceeds E=%d", k, E);
+  EVICT_REQUIRE((int64_t)T * k <= 8192 && E <= 1024, EVICT_E_UNSUPPORTED,
+                "evict_expert_union: T*k=%lld (limit 8192), E=%d (limit 1024)", (long long)T * k, E);
+  const int P = T * k;
+  const size_t lds = sizeof(int) * (size_t)(P + 2 * E + 1);
+  hipLaunchKernelGGL(expert_union_kernel, dim3(1), dim3(kUnionThreads), lds, (hipStream_t)stream, topk_idx, P, E,
+                     union_ids, union_count, hist, offsets, perm, inv, ctx ? ctx->status : nullptr);
+  return launch_status("expert_union_kernel");
+}
+
+int evict_gather_rows(const void* src, void* dst, int row_bytes, const int32_t* tree_off, const int32_t* new_tree_off,
+                      const int32_t* keep, int B, int T, void* stream) {
+  EVICT_REQUIRE(src && dst && tree_off && new_tree_off && keep, EVICT_E_INVALID, "evict_gather_rows: null pointer");
+  EVICT_REQUIRE(row_bytes > 0 && row_bytes % 4 == 0, EVICT_E_INVALID, "evict_gather_rows: row_bytes must be a positive multiple of 4");
+  EVICT_REQUIRE(B >= 1 && T >= 1, EVICT_E_INVALID, "evict_gather_rows: B, T must be >= 1");
+  EVICT_REQUIRE(src != dst, EVICT_E_INVALID, "evict_gather_rows: in-place gather is not supported");
+  hipLaunchKernelGGL(gather_rows_kernel, dim3(T), dim3(128), 0, (hipStream_t)stream, (const uint32_t*)src,
+                     (uint32_t*)dst, row_bytes / 4, tree_off, new_tree_off, keep, B);
+  return launch_status("gather_rows_kernel");
+}
+
+}  // extern "C"
