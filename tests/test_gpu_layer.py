@@ -75,9 +75,11 @@ def check_against_oracle(case, got):
         shared = sum(orc.expert_mlp(np.asarray(got["h_norm"], np.float64), case["W"]["ws_gate"][s], case["W"]["ws_up"][s],
                                     case["W"]["ws_down"][s], cfg.dtype) for s in range(cfg.n_shared))
     out_stage = orc.moe_combine(got["h"], y, got["topk_w"], shared)
-    assert rel_l2(got["out"], out_stage) < (5e-3 if cfg.dtype == "bf16" else 1e-5), "MoE stage"
-    moe_part = rel_l2(got["out"] - got["h"], out_stage - np.asarray(got["h"], np.float64))
-    assert moe_part < (2e-2 if cfg.dtype == "bf16" else 1e-4), "MoE contribution"
+    out_stored = orc.handoff(out_stage, cfg.dtype)     # the layer output is stored in the storage type
+    assert rel_l2(got["out"], out_stored) < (1e-3 if cfg.dtype == "bf16" else 1e-5), "MoE stage"
+    # error measured against the size of the MoE contribution itself (a wrong expert sum gives ~1)
+    moe_part = np.linalg.norm(got["out"] - out_stored) / np.linalg.norm(out_stage - np.asarray(got["h"], np.float64))
+    assert moe_part < (5e-2 if cfg.dtype == "bf16" else 1e-4), f"MoE contribution {moe_part}"
     # --- hidden output end to end
     flips = int((np.sort(got["topk_idx"], -1) != np.sort(ref["topk_idx"], -1)).any(-1).sum())
     err = rel_l2(got["out"], ref["out"])
