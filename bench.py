@@ -1,0 +1,195 @@
+#!/usr/bin/env python3
+"""Verify-step benchmark on one MI355X.
+
+A step is one pass of the whole hot path over one batch of seeded synthetic input at the
+Qwen3-30B-A3B-shaped configuration (one MoE decoder layer, bf16, KV context 2048, N = 32
+draft-tree nodes): EVICT prefix selection on the draft probabilities, target-side tree
+verification of the layer (tree-masked GQA attention, router top-k, expert union, grouped
+SwiGLU expert GEMMs, combine) and greedy acceptance. Inputs are resident in HBM before the
+timed region. Successive steps rotate over several copies of the layer's weights so the
+last-level cache cannot hold the working set.
+
+Prints one JSON line (metric = verify-step latency in microseconds) with the HBM roofline of
+the dominant kernel (the gate/up grouped GEMM) measured by HIP events inside the library, and
+the CPU oracle timed on the same inputs on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--nodes", type=int, default=32, help="draft-tree size N")
+    ap.add_argument("--ctx", type=int, default=2048, help="KV context length")
+    ap.add_argument("--sigma", type=float, default=0.5, help="child = parent + sigma*N(0,1)")
+    ap.add_argument("--copies", type=int, default=4, help="weight copies rotated between steps")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
+    ap.add_argument("--seed", type=int, default=1000)
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    import synth
+    import paper_2605_00342_amd as ev
+    from paper_2605_00342_amd import harness
+
+    if not torch.cuda.is_available():
+        print("no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    cfg = synth.CONFIGS["qwen3"]
+    N, L = args.nodes, args.ctx
+    case = synth.make_case("qwen3", n=N, L=L, seed=args.seed, sigma=args.sigma)
+    layer = harness.DeviceLayer(cfg, case["W"], max_tokens=N, max_batch=1, max_ctx=L)
+    dc = harness.DeviceCase(case, with_aux=True)
+
+    # weight copies (same values, distinct addresses) so that no step finds its weights in cache
+    names = ("wqkv", "wo", "wg", "w_gateup", "w_down")
+    weight_sets = [layer.weights]
+    keep_alive = []
+    for _ in range(max(1, args.copies) - 1):
+        cp = {n: getattr(layer, n).clone() for n in names}
+        keep_alive.append(cp)
+        weight_sets.append(ev.LayerWeights(layer.g_attn.data_ptr(), layer.g_moe.data_ptr(), cp["wqkv"].data_ptr(),
+                                           cp["wo"].data_ptr(), cp["wg"].data_ptr(), cp["w_gateup"].data_ptr(),
+                                           cp["w_down"].data_ptr(), None, None))
+
+    # selection / acceptance inputs
+    i32, f32 = torch.int32, torch.float32
+    q_dev = torch.from_numpy(case["q"]).to(dev)
+    cost = synth.cost_linear_in_union(N, cfg.E, cfg.k)
+    cost_dev = torch.from_numpy(cost).to(dev)
+    sel = dict(k_star=torch.zeros(1, dtype=i32, device=dev), keep=torch.zeros(N, dtype=i32, device=dev),
+               new_parent=torch.zeros(N, dtype=i32, device=dev), new_off=torch.zeros(2, dtype=i32, device=dev),
+               est=torch.zeros(1, dtype=f32, device=dev))
+    g = synth.philox(args.seed, 900)
+    target_next = g.integers(0, 151936, N).astype(np.int32)
+    draft_tok = synth.plant_draft_tokens(case["parent"], target_next, 151936, g)
+    tn_dev, dt_dev = harness.dev_i32(target_next), harness.dev_i32(draft_tok)
+    path = torch.zeros(1, N, dtype=i32, device=dev)
+    path_len = torch.zeros(1, dtype=i32, device=dev)
+    bonus = torch.zeros(1, dtype=i32, device=dev)
+
+    def step(i):
+        ev.evict_select_prefix(None, dc.tree_off, dc.parent, q_dev, 1, N, cost_dev, N, sel["k_star"], sel["keep"],
+                               sel["new_parent"], sel["new_off"], sel["est"])
+        ev.evict_verify_layer(layer.ctx, weight_sets[i % len(weight_sets)], dc.tree_off, dc.parent, 1, N, dc.k_cache,
+                              dc.v_cache, dc.seq_stride, dc.head_stride, dc.ctx_len, L, dc.x, dc.out, dc.k_new,
+                              dc.v_new, None)
+        ev.evict_accept_path(None, dc.tree_off, dc.parent, dt_dev, tn_dev, 1, path, N, path_len, bonus)
+
+    # one checked run: union size for the byte count
+    dc.run(layer)
+    res = dc.results()
+    U = int(res["union_count"])
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    # per-stage durations from HIP events recorded by the library on the launch stream
+    ev.evict_stage_timing(layer.ctx, True)
+    stage_ms = {n: 0.0 for n in ev.STAGES}
+    n_timed = min(args.steps, 50)
+    for i in range(n_timed):
+        step(i)
+        t = ev.evict_stage_times(layer.ctx)
+        for n in ev.STAGES:
+            stage_ms[n] += t[n] / n_timed
+    ev.evict_stage_timing(layer.ctx, False)
+
+    eb = 2
+    expert_bytes = 3 * cfg.d * cfg.F * eb
+    kv_bytes = 2 * L * cfg.Hkv * cfg.D * eb
+    proj_bytes = (2 * cfg.Hq * cfg.D * cfg.d + 2 * cfg.Hkv * cfg.D * cfg.d) * eb + cfg.E * cfg.d * eb
+    north_star_bytes = U * expert_bytes + kv_bytes
+    all_bytes = north_star_bytes + proj_bytes
+    gateup_bytes = U * 2 * cfg.d * cfg.F * eb            # algorithmic bytes of the dominant kernel per launch
+    gateup_s = stage_ms["gateup"] * 1e-3
+    achieved = gateup_bytes / gateup_s / 1e9 if gateup_s > 0 else 0.0
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "pmc_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(f"gateup_N{N}_L{L}")
+        except Exception:
+            traffic = None
+
+    out = {
+        "metric": "verify_step_latency_us",
+        "value": round(ms_per_step * 1e3, 2),
+        "unit": "us",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"qwen3-30b-a3b-shaped MoE layer, N={N} tree nodes, ctx={L}, 1 sequence, sigma={args.sigma}",
+                   "d_model": cfg.d, "heads": f"{cfg.Hq}q/{cfg.Hkv}kv x {cfg.D}", "experts": f"{cfg.E} top-{cfg.k}",
+                   "d_ff": cfg.F, "union_experts": U, "weight_copies": len(weight_sets)},
+        "tokens_per_s": round(N / (ms_per_step * 1e-3), 1),
+        "step_roofline": {"north_star_bytes": north_star_bytes, "all_required_bytes": all_bytes,
+                          "hbm_frac_north_star": round(north_star_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                          "hbm_frac_all_required": round(all_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
+        "stage_us": {n: round(v * 1e3, 2) for n, v in stage_ms.items()},
+        "roofline": {"bound": "hbm", "kernel": "gemm_stream_kernel (gate/up grouped GEMM + SiLU gating)",
+                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                     "bytes_per_launch": gateup_bytes, "avg_launch_us": round(stage_ms["gateup"] * 1e3, 2)},
+    }
+
+    if not args.no_cpu:
+        from oracle import evict_oracle as orc
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        c0 = time.perf_counter()
+        orc.select_prefix(case["parent"], case["q"], cost, N)
+        ref = orc.verify_layer(cfg, case["W"], case["tree_off"], case["parent"], case["x"], case["K"], case["V"],
+                               case["ctx_len"])
+        orc.accept_path(case["parent"], draft_tok, target_next)
+        c1 = time.perf_counter()
+        rel = float(np.linalg.norm(res["out"] - ref["out"]) / np.linalg.norm(ref["out"]))
+        out["cpu_baseline"] = {"value": round((c1 - c0) * 1e6, 1), "unit": "us", "cores": int(cores), "kind": "oracle",
+                               "sample": "1 full step of the same workload (numpy float64 oracle: select + layer + accept)",
+                               "gpu_vs_oracle_rel_l2": round(rel, 6)}
+    print(json.dumps(out), flush=True)
+    layer.close()
+
+
+if __name__ == "__main__":
+    main()

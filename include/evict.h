@@ -180,6 +180,17 @@ int evict_validate_trees_host(const int32_t* tree_off, const int32_t* parent, in
  * Synchronises the stream. */
 int evict_device_status(evict_ctx* ctx, int32_t* status_host, void* stream);
 
+/* Per-stage timing of evict_verify_layer with HIP events recorded on the call's stream
+ * between the stages (for measurement; adds event records to the stream). Stages, in order:
+ * 0 tree prep + RMSNorm, 1 QKV projection + rotation, 2 tree attention (partials + merge),
+ * 3 output projection + residual, 4 router top-k, 5 expert union / grouping,
+ * 6 gate/up grouped GEMM + SiLU gating, 7 down grouped GEMM, 8 shared experts, 9 combine.
+ * evict_stage_times waits for the last timed call to finish and writes the milliseconds of
+ * each stage of that call to ms_host [host] float[EVICT_N_STAGES]. */
+#define EVICT_N_STAGES 10
+int evict_stage_timing(evict_ctx* ctx, int enable);
+int evict_stage_times(evict_ctx* ctx, float* ms_host);
+
 #ifdef __cplusplus
 }
 #endif

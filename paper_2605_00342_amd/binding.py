@@ -14,7 +14,8 @@ __all__ = [
     "EvictError", "lib_path", "load", "is_built", "EVICT_F32", "EVICT_BF16", "ModelDesc", "LayerWeights", "LayerAux",
     "evict_version", "evict_last_error", "evict_create", "evict_destroy", "evict_packed_bytes", "evict_pack_dense",
     "evict_pack_qkv", "evict_pack_experts", "evict_verify_layer", "evict_expert_union", "evict_accept_path",
-    "evict_select_prefix", "evict_gather_rows", "evict_validate_trees_host", "evict_device_status", "EXPORTS",
+    "evict_select_prefix", "evict_gather_rows", "evict_validate_trees_host", "evict_device_status",
+    "evict_stage_timing", "evict_stage_times", "STAGES", "EXPORTS",
 ]
 
 EVICT_F32, EVICT_BF16 = 0, 1
@@ -25,7 +26,9 @@ EXPORTS = [
     "evict_version", "evict_last_error", "evict_create", "evict_destroy", "evict_packed_bytes", "evict_pack_dense",
     "evict_pack_qkv", "evict_pack_experts", "evict_verify_layer", "evict_expert_union", "evict_accept_path",
     "evict_select_prefix", "evict_gather_rows", "evict_validate_trees_host", "evict_device_status",
+    "evict_stage_timing", "evict_stage_times",
 ]
+STAGES = ["prep", "qkv", "attention", "oproj", "router", "union", "gateup", "down", "shared", "combine"]
 
 
 class EvictError(RuntimeError):
@@ -85,6 +88,8 @@ def load():
     lib.evict_gather_rows.argtypes = [vp, vp, i32, vp, vp, vp, i32, i32, vp]
     lib.evict_validate_trees_host.argtypes = [vp, vp, i32, i32]
     lib.evict_device_status.argtypes = [vp, C.POINTER(C.c_int32), vp]
+    lib.evict_stage_timing.argtypes = [vp, i32]
+    lib.evict_stage_times.argtypes = [vp, C.POINTER(C.c_float)]
     _LIB = lib
     return lib
 
@@ -178,3 +183,14 @@ def evict_device_status(ctx) -> int:
     out = C.c_int32(0)
     _check(load().evict_device_status(ctx, C.byref(out), _stream()))
     return out.value
+
+
+def evict_stage_timing(ctx, enable: bool) -> None:
+    _check(load().evict_stage_timing(ctx, 1 if enable else 0))
+
+
+def evict_stage_times(ctx) -> dict:
+    """Milliseconds per stage of the last timed evict_verify_layer call."""
+    buf = (C.c_float * len(STAGES))()
+    _check(load().evict_stage_times(ctx, buf))
+    return {n: float(buf[i]) for i, n in enumerate(STAGES)}

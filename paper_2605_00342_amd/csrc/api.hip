@@ -104,7 +104,15 @@ int evict_create(evict_ctx** out, const evict_model_desc* m, int max_tokens, int
     if (he != hipSuccess) { set_error("hipMemset failed: %s", hipGetErrorString(he)); rc = EVICT_E_HIP; }
   }
   if (!rc) rc = attn_setup();
+  c.timing = 0;
+  c.timed_once = 0;
+  int n_ev = 0;
+  for (; !rc && n_ev <= EVICT_N_STAGES; ++n_ev) {
+    he = hipEventCreate(&c.ev[n_ev]);
+    if (he != hipSuccess) { set_error("hipEventCreate failed: %s", hipGetErrorString(he)); rc = EVICT_E_HIP; break; }
+  }
   if (rc) {
+    for (int i = 0; i < n_ev; ++i) (void)hipEventDestroy(c.ev[i]);
     for (void* p : o->owned) (void)hipFree(p);
     delete o;
     return rc;
@@ -117,6 +125,7 @@ int evict_destroy(evict_ctx* ctx) {
   if (!ctx) return EVICT_OK;
   evict_ctx_owner* o = reinterpret_cast<evict_ctx_owner*>(ctx);  // c is the first member
   int rc = EVICT_OK;
+  for (int i = 0; i <= EVICT_N_STAGES; ++i) (void)hipEventDestroy(ctx->ev[i]);
   for (void* p : o->owned) {
     hipError_t e = hipFree(p);
     if (e != hipSuccess) { set_error("hipFree failed: %s", hipGetErrorString(e)); rc = EVICT_E_HIP; }
@@ -209,8 +218,12 @@ int evict_verify_layer(evict_ctx* ctx, const evict_layer_weights* w, const int32
   hipStream_t s = (hipStream_t)stream;
   const int eb = elem_bytes(m.dtype);
   const int HqD = m.Hq * m.D;
+  const bool timing = ctx->timing != 0;
+#define EVICT_MARK(i_) do { if (timing) EVICT_HIP_CHECK(hipEventRecord(ctx->ev[i_], s)); } while (0)
+  EVICT_MARK(0);
   int rc = launch_prep(ctx, tree_off, parent, B, T, ctx_len, max_ctx_host, x_in, w->g_attn, s);
   if (rc) return rc;
+  EVICT_MARK(1);
 
   const int nt_dense = T <= 16 ? 1 : 2;
   {  // q, k, v projections + rotation (positions ctx_len + depth)
@@ -228,9 +241,11 @@ int evict_verify_layer(evict_ctx* ctx, const evict_layer_weights* w, const int32
     if (rc) return rc;
     if (aux && aux->q) EVICT_HIP_CHECK(hipMemcpyAsync(aux->q, ctx->q, (size_t)T * HqD * eb, hipMemcpyDeviceToDevice, s));
   }
+  EVICT_MARK(2);
   rc = launch_attention(ctx, k_cache, v_cache, kv_seq_stride, kv_head_stride, ctx_len, max_ctx_host, tree_off, B, T, k_new,
                         v_new, aux ? aux->attn_out : nullptr, s);
   if (rc) return rc;
+  EVICT_MARK(3);
   {  // output projection + residual
     GemmArgs a = {};
     a.W = (const u32x4*)w->wo_packed;
@@ -246,8 +261,10 @@ int evict_verify_layer(evict_ctx* ctx, const evict_layer_weights* w, const int32
     if (rc) return rc;
     if (aux && aux->h) EVICT_HIP_CHECK(hipMemcpyAsync(aux->h, ctx->h, (size_t)T * m.d * eb, hipMemcpyDeviceToDevice, s));
   }
+  EVICT_MARK(4);
   rc = launch_router(ctx, w->g_moe, w->wg, T, aux, s);
   if (rc) return rc;
+  EVICT_MARK(5);
   rc = evict_expert_union(ctx, ctx->topk_idx, T, m.k, m.E, ctx->union_ids, ctx->union_count, ctx->hist, ctx->offsets,
                           ctx->perm, ctx->inv, stream);
   if (rc) return rc;
@@ -256,6 +273,7 @@ int evict_verify_layer(evict_ctx* ctx, const evict_layer_weights* w, const int32
     if (aux->union_count) EVICT_HIP_CHECK(hipMemcpyAsync(aux->union_count, ctx->union_count, 4, hipMemcpyDeviceToDevice, s));
     if (aux->hist) EVICT_HIP_CHECK(hipMemcpyAsync(aux->hist, ctx->hist, (size_t)m.E * 4, hipMemcpyDeviceToDevice, s));
   }
+  EVICT_MARK(6);
   const int nt_exp = T <= 48 ? 1 : 2;
   {  // gate/up projections of the union experts + SiLU gating
     GemmArgs a = {};
@@ -274,6 +292,7 @@ int evict_verify_layer(evict_ctx* ctx, const evict_layer_weights* w, const int32
     rc = launch_gemm(m.dtype, EPI_SWIGLU, a, nt_exp, 512, s);
     if (rc) return rc;
   }
+  EVICT_MARK(7);
   {  // down projections
     GemmArgs a = {};
     a.W = (const u32x4*)w->w_down_packed;
@@ -291,6 +310,7 @@ int evict_verify_layer(evict_ctx* ctx, const evict_layer_weights* w, const int32
     rc = launch_gemm(m.dtype, EPI_F32, a, nt_exp, 512, s);
     if (rc) return rc;
   }
+  EVICT_MARK(8);
   for (int sh = 0; sh < m.n_shared; ++sh) {  // always-on shared experts on all tokens
     GemmArgs a = {};
     a.n_strips = 2 * m.F / 16;
@@ -315,7 +335,28 @@ int evict_verify_layer(evict_ctx* ctx, const evict_layer_weights* w, const int32
     rc = launch_gemm(m.dtype, EPI_F32, b, nt_dense, b.n_strips < 512 ? b.n_strips : 512, s);
     if (rc) return rc;
   }
-  return launch_combine(ctx, T, x_out, s);
+  EVICT_MARK(9);
+  rc = launch_combine(ctx, T, x_out, s);
+  if (rc) return rc;
+  EVICT_MARK(10);
+  if (timing) ctx->timed_once = 1;
+#undef EVICT_MARK
+  return EVICT_OK;
+}
+
+int evict_stage_timing(evict_ctx* ctx, int enable) {
+  EVICT_REQUIRE(ctx, EVICT_E_INVALID, "evict_stage_timing: null context");
+  ctx->timing = enable ? 1 : 0;
+  if (!enable) ctx->timed_once = 0;
+  return EVICT_OK;
+}
+
+int evict_stage_times(evict_ctx* ctx, float* ms_host) {
+  EVICT_REQUIRE(ctx && ms_host, EVICT_E_INVALID, "evict_stage_times: null pointer");
+  EVICT_REQUIRE(ctx->timed_once, EVICT_E_INVALID, "evict_stage_times: no call has been timed (enable evict_stage_timing first)");
+  EVICT_HIP_CHECK(hipEventSynchronize(ctx->ev[EVICT_N_STAGES]));
+  for (int i = 0; i < EVICT_N_STAGES; ++i) EVICT_HIP_CHECK(hipEventElapsedTime(&ms_host[i], ctx->ev[i], ctx->ev[i + 1]));
+  return EVICT_OK;
 }
 
 }  // extern "C"

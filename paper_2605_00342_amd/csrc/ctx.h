@@ -7,6 +7,9 @@ struct evict_ctx {
   int max_tokens, max_batch, max_ctx;
   int device;
   int max_splits;        // KV splits the attention scratch is sized for (context part)
+  int timing;            // record stage events in evict_verify_layer
+  int timed_once;        // a timed call has been recorded
+  hipEvent_t ev[EVICT_N_STAGES + 1];
   // ---- device scratch (all sized for max_tokens) ----
   int32_t* status;       // [1] sticky status bits
   uint64_t* anc;         // [T][2] ancestor-or-self bitmask of each node (tree-local bit index)
