@@ -66,7 +66,7 @@ typedef struct evict_layer_weights {
   const void* g_moe;         /* [dev] [d] gain of the pre-MoE RMSNorm */
   const void* wqkv_packed;   /* [dev] from evict_pack_qkv */
   const void* wo_packed;     /* [dev] from evict_pack_dense(W_o [d, Hq*D]) */
-  const void* wg;            /* [dev] router matrix W_g [E, d], row-major, NOT packed */
+  const void* wg_packed;     /* [dev] router matrix W_g from evict_pack_dense(W_g [E, d]) */
   const void* w_gateup_packed; /* [dev] from evict_pack_experts */
   const void* w_down_packed;   /* [dev] from evict_pack_experts */
   const void* ws_gateup_packed; /* [dev] shared experts, or NULL when n_shared == 0 */

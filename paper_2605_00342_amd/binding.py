@@ -44,7 +44,7 @@ class ModelDesc(C.Structure):
 
 
 class LayerWeights(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in ("g_attn", "g_moe", "wqkv_packed", "wo_packed", "wg", "w_gateup_packed",
+    _fields_ = [(n, C.c_void_p) for n in ("g_attn", "g_moe", "wqkv_packed", "wo_packed", "wg_packed", "w_gateup_packed",
                                           "w_down_packed", "ws_gateup_packed", "ws_down_packed")]
 
 

@@ -25,7 +25,8 @@ int check_model(const evict_model_desc* m) {
   EVICT_REQUIRE(m->D == 64 || m->D == 128, EVICT_E_UNSUPPORTED, "head dimension %d (supported: 64, 128)", m->D);
   EVICT_REQUIRE(m->d % 16 == 0 && m->F % 16 == 0 && (m->d * eb) % 64 == 0 && (m->F * eb) % 64 == 0,
                 EVICT_E_UNSUPPORTED, "d=%d and F=%d must be multiples of 16 rows and of 64 bytes", m->d, m->F);
-  EVICT_REQUIRE(m->k <= 64 && m->E <= 1024, EVICT_E_UNSUPPORTED, "k=%d (limit 64), E=%d (limit 1024)", m->k, m->E);
+  EVICT_REQUIRE(m->k <= 64 && m->E <= 1024 && m->E % 16 == 0, EVICT_E_UNSUPPORTED,
+                "k=%d (limit 64), E=%d (limit 1024, multiple of 16)", m->k, m->E);
   return EVICT_OK;
 }
 
@@ -103,7 +104,7 @@ int evict_create(evict_ctx** out, const evict_model_desc* m, int max_tokens, int
     he = hipMemset(c.status, 0, 16);
     if (he != hipSuccess) { set_error("hipMemset failed: %s", hipGetErrorString(he)); rc = EVICT_E_HIP; }
   }
-  if (!rc) rc = attn_setup();
+  if (!rc) rc = kernels_setup(*m);
   c.timing = 0;
   c.timed_once = 0;
   int n_ev = 0;
@@ -197,7 +198,7 @@ int evict_verify_layer(evict_ctx* ctx, const evict_layer_weights* w, const int32
   EVICT_REQUIRE(ctx && w && tree_off && parent && ctx_len && x_in && x_out && k_new && v_new, EVICT_E_INVALID,
                 "evict_verify_layer: null pointer argument");
   const evict_model_desc& m = ctx->m;
-  EVICT_REQUIRE(w->g_attn && w->g_moe && w->wqkv_packed && w->wo_packed && w->wg && w->w_gateup_packed && w->w_down_packed,
+  EVICT_REQUIRE(w->g_attn && w->g_moe && w->wqkv_packed && w->wo_packed && w->wg_packed && w->w_gateup_packed && w->w_down_packed,
                 EVICT_E_INVALID, "evict_verify_layer: null weight pointer");
   EVICT_REQUIRE(m.n_shared == 0 || (w->ws_gateup_packed && w->ws_down_packed), EVICT_E_INVALID,
                 "evict_verify_layer: shared-expert weights missing");
@@ -262,7 +263,7 @@ int evict_verify_layer(evict_ctx* ctx, const evict_layer_weights* w, const int32
     if (aux && aux->h) EVICT_HIP_CHECK(hipMemcpyAsync(aux->h, ctx->h, (size_t)T * m.d * eb, hipMemcpyDeviceToDevice, s));
   }
   EVICT_MARK(4);
-  rc = launch_router(ctx, w->g_moe, w->wg, T, aux, s);
+  rc = launch_router(ctx, w->g_moe, w->wg_packed, T, aux, s);
   if (rc) return rc;
   EVICT_MARK(5);
   rc = evict_expert_union(ctx, ctx->topk_idx, T, m.k, m.E, ctx->union_ids, ctx->union_count, ctx->hist, ctx->offsets,

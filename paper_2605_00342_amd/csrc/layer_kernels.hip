@@ -205,32 +205,210 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(
   }
 }
 
+// ------------------------------------------------------------------------------------
+// bf16 tree-masked attention on the matrix cores. Grid (splits * row_blocks, Hkv, B); one
+// split = 128 keys of the KV cache, the last split = the draft nodes of the sequence under
+// the ancestor mask. K and V of the split are staged once in LDS (K row-major, V
+// transposed so that the contraction over keys reads contiguous bytes); each wavefront
+// takes 16 query rows (node x query head of this KV group) at a time:
+//   S^T = K Q^T  (MFMA, 16 keys x 16 rows per tile),  masked softmax numerators in
+//   registers, O = P V (MFMA) with P taken straight from the S^T accumulators.
+// Writes un-normalised partial outputs with their (max, sum) for the merge kernel.
+// ------------------------------------------------------------------------------------
+constexpr int kMfmaKeys = 128;
+
+template <int D>
+__global__ __launch_bounds__(256) void attn_partial_mfma_kernel(
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ kc, const uint16_t* __restrict__ vc,
+    long long seq_stride, long long head_stride, const int32_t* __restrict__ ctx_len, int max_ctx,
+    const int32_t* __restrict__ tree_off, const uint16_t* __restrict__ k_new, const uint16_t* __restrict__ v_new,
+    const uint64_t* __restrict__ anc, int Hq, int Hkv, int ctx_splits, int row_blocks, int T,
+    float* __restrict__ part_o, float* __restrict__ part_ml) {
+  constexpr int LDK = D + 8;            // bf16 per K row in LDS (16-byte pad)
+  constexpr int LDV = kMfmaKeys + 4;    // bf16 per V^T row in LDS
+  constexpr int CH = D / 8;             // 16-byte chunks per row
+  constexpr int KT = kMfmaKeys / 16;    // key tiles
+  constexpr int KB = D / 32;            // contraction blocks of Q K^T
+  extern __shared__ __attribute__((aligned(16))) uint16_t s_kv[];
+  uint16_t* s_k = s_kv;                          // [128][LDK]
+  uint32_t* s_vt = reinterpret_cast<uint32_t*>(s_kv + kMfmaKeys * LDK);  // [D][LDV/2] key pairs
+  const int split = blockIdx.x / row_blocks, rb = blockIdx.x - split * row_blocks;
+  const int g = blockIdx.y, b = blockIdx.z;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int lo = tree_off[b];
+  int n = tree_off[b + 1] - lo;
+  n = n > EVICT_MAX_TREE_NODES ? EVICT_MAX_TREE_NODES : n;
+  int L = ctx_len[b];
+  L = L < 0 ? 0 : (L > max_ctx ? max_ctx : L);
+  const bool tree_part = split >= ctx_splits;
+  const int key0 = tree_part ? 0 : split * kMfmaKeys;
+  int nkeys = (tree_part ? n : L) - key0;
+  nkeys = nkeys > kMfmaKeys ? kMfmaKeys : nkeys;
+  if (nkeys <= 0) return;  // split lies beyond this sequence's context; the merge skips it
+  const int G = Hq / Hkv;
+  const int R = n * G;
+  const int ntiles = (R + 15) >> 4;
+  const int per_rb = (ntiles + row_blocks - 1) / row_blocks;
+  const int t_begin = rb * per_rb;
+  int t_end = t_begin + per_rb;
+  t_end = t_end > ntiles ? ntiles : t_end;
+  if (t_begin >= t_end) return;
+
+  // ---- stage K (row-major) and V (transposed, two keys per dword)
+  const uint16_t* kbase = tree_part ? k_new + ((size_t)lo * Hkv + g) * D : kc + (size_t)b * seq_stride + (size_t)g * head_stride + (size_t)key0 * D;
+  const uint16_t* vbase = tree_part ? v_new + ((size_t)lo * Hkv + g) * D : vc + (size_t)b * seq_stride + (size_t)g * head_stride + (size_t)key0 * D;
+  const size_t kstep = tree_part ? (size_t)Hkv * D : (size_t)D;  // elements between consecutive keys
+  for (int idx = tid; idx < kMfmaKeys * CH; idx += 256) {
+    const int j = idx / CH, c = idx - j * CH;
+    u32x4 v = {0, 0, 0, 0};
+    if (j < nkeys) v = *reinterpret_cast<const u32x4*>(kbase + j * kstep + c * 8);
+    *reinterpret_cast<u32x4*>(s_k + j * LDK + c * 8) = v;
+  }
+  for (int idx = tid; idx < (kMfmaKeys / 2) * CH; idx += 256) {
+    const int jp = idx / CH, c = idx - jp * CH;
+    u32x4 v0 = {0, 0, 0, 0}, v1 = {0, 0, 0, 0};
+    if (2 * jp < nkeys) v0 = *reinterpret_cast<const u32x4*>(vbase + (2 * jp) * kstep + c * 8);
+    if (2 * jp + 1 < nkeys) v1 = *reinterpret_cast<const u32x4*>(vbase + (2 * jp + 1) * kstep + c * 8);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t a = v0[i], bb = v1[i];
+      s_vt[(c * 8 + 2 * i) * (LDV / 2) + jp] = (a & 0xFFFFu) | (bb << 16);
+      s_vt[(c * 8 + 2 * i + 1) * (LDV / 2) + jp] = (a >> 16) | (bb & 0xFFFF0000u);
+    }
+  }
+  __syncthreads();
+
+  const float scale = 1.0f / sqrtf((float)D);
+  const int kq = lane >> 4, ln = lane & 15;
+  for (int rt = t_begin + w; rt < t_end; rt += 4) {
+    int r = rt * 16 + ln;
+    r = r < R ? r : R - 1;
+    const int i = r / G, hh = r - i * G;
+    const int t = lo + i;
+    const uint16_t* qrow = q + ((size_t)t * Hq + g * G + hh) * D + kq * 8;
+    u32x4 Qf[KB];
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb) Qf[kb] = *reinterpret_cast<const u32x4*>(qrow + kb * 32);
+    uint64_t a0 = ~0ull, a1 = ~0ull;
+    if (tree_part) { a0 = anc[2 * (size_t)t]; a1 = anc[2 * (size_t)t + 1]; }
+    // S^T tiles: lane holds keys kt*16 + kq*4 + j of query row ln
+    f32x4 S[KT];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int kt = 0; kt < KT; ++kt) {
+      f32x4 acc = {0, 0, 0, 0};
+#pragma unroll
+      for (int kb = 0; kb < KB; ++kb) {
+        const u32x4 kf = *reinterpret_cast<const u32x4*>(s_k + (kt * 16 + ln) * LDK + kb * 32 + kq * 8);
+        acc = mfma_block<BF16>(kf, Qf[kb], acc);
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int key = kt * 16 + kq * 4 + j;
+        const uint64_t word = key < 64 ? a0 : a1;
+        const bool vis = key < nkeys && ((word >> (key & 63)) & 1ull);
+        acc[j] = vis ? acc[j] * scale : -INFINITY;
+        mx = fmaxf(mx, acc[j]);
+      }
+      S[kt] = acc;
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    float lsum = 0.0f;
+    u32x4 Pf[KT / 2];
+#pragma unroll
+    for (int kt = 0; kt < KT; ++kt) {
+      uint32_t pk[2];
+#pragma unroll
+      for (int jj = 0; jj < 2; ++jj) {
+        const float p0 = S[kt][2 * jj] == -INFINITY ? 0.0f : __expf(S[kt][2 * jj] - mx);
+        const float p1 = S[kt][2 * jj + 1] == -INFINITY ? 0.0f : __expf(S[kt][2 * jj + 1] - mx);
+        const uint16_t b0 = f32_to_bf16(p0), b1 = f32_to_bf16(p1);
+        lsum += bf16_to_f32(b0) + bf16_to_f32(b1);  // the sum uses the rounded weights the MFMA sees
+        pk[jj] = (uint32_t)b0 | ((uint32_t)b1 << 16);
+      }
+      // contraction block kt/2 takes keys 32b + 4kq + {0..3} (even tile) and 32b + 16 + 4kq + {0..3} (odd tile)
+      if (kt & 1) { Pf[kt >> 1][2] = pk[0]; Pf[kt >> 1][3] = pk[1]; }
+      else        { Pf[kt >> 1][0] = pk[0]; Pf[kt >> 1][1] = pk[1]; }
+    }
+    lsum += __shfl_xor(lsum, 16);
+    lsum += __shfl_xor(lsum, 32);
+    if (kq == 0 && rt * 16 + ln < R) {
+      const size_t prow = ((size_t)split * T + t) * Hq + g * G + hh;
+      part_ml[prow * 2] = mx;
+      part_ml[prow * 2 + 1] = lsum;
+    }
+    // O = P V: lane holds rows kq*4 + j, column dt*16 + ln
+    size_t orow[4];
+    bool ovalid[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int r2 = rt * 16 + kq * 4 + j;
+      ovalid[j] = r2 < R;
+      const int rc = ovalid[j] ? r2 : R - 1;
+      const int i2 = rc / G, h2 = rc - i2 * G;
+      orow[j] = (((size_t)split * T + lo + i2) * Hq + g * G + h2) * D;
+    }
+#pragma unroll
+    for (int dt = 0; dt < D / 16; ++dt) {
+      f32x4 acc = {0, 0, 0, 0};
+#pragma unroll
+      for (int bk = 0; bk < KT / 2; ++bk) {
+        const uint32_t* vrow = s_vt + (dt * 16 + ln) * (LDV / 2) + bk * 16 + kq * 2;
+        const uint2 lo2 = *reinterpret_cast<const uint2*>(vrow);
+        const uint2 hi2 = *reinterpret_cast<const uint2*>(vrow + 8);
+        const u32x4 vf = {lo2.x, lo2.y, hi2.x, hi2.y};
+        acc = mfma_block<BF16>(Pf[bk], vf, acc);
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        if (ovalid[j]) part_o[orow[j] + dt * 16 + ln] = acc[j];
+    }
+  }
+}
+
 // merge of the per-split partial softmaxes: grid (T*Hq), block D threads
 template <typename ST>
 __global__ void attn_merge_kernel(const float* __restrict__ part_o, const float* __restrict__ part_ml, int nsplits,
                                   int T, int Hq, int D, const int32_t* __restrict__ seq_of,
                                   const int32_t* __restrict__ ctx_len, int max_ctx, int keys_per_split, int ctx_splits,
                                   void* __restrict__ out, void* __restrict__ aux_out) {
-  const int row = blockIdx.x;  // t * Hq + h
-  const int c = threadIdx.x;
+  __shared__ float s_sc[2][192];  // per-split weights, one copy per wavefront
+  const int row = blockIdx.x;     // t * Hq + h
+  const int c = threadIdx.x, lane = c & 63, w = c >> 6;
   const int t = row / Hq;
   int L = ctx_len[seq_of[t]];
   L = L < 0 ? 0 : (L > max_ctx ? max_ctx : L);
-  const int used_ctx = (L + keys_per_split - 1) / keys_per_split;  // splits past the context are skipped
+  const int used_ctx = (L + keys_per_split - 1) / keys_per_split;  // context splits past this are skipped
+  // each lane fetches the (max, sum) of different splits
   float M = -INFINITY;
-  for (int s = 0; s < nsplits; ++s) {
-    if (s >= used_ctx && s < ctx_splits) continue;
-    M = fmaxf(M, part_ml[((size_t)s * T * Hq + row) * 2]);
+  for (int s0 = 0; s0 < nsplits; s0 += 64) {
+    const int s = s0 + lane;
+    float ms = -INFINITY;
+    if (s < nsplits && !(s >= used_ctx && s < ctx_splits)) ms = part_ml[((size_t)s * T * Hq + row) * 2];
+    s_sc[w][s < 192 ? s : 191] = ms;
+    M = fmaxf(M, ms);
   }
-  float l = 0.0f, o = 0.0f;
+  M = wave_max(M);
+  float l = 0.0f;
+  for (int s0 = 0; s0 < nsplits; s0 += 64) {
+    const int s = s0 + lane;
+    float sc = 0.0f;
+    if (s < nsplits) {
+      const float ms = s_sc[w][s];
+      if (ms != -INFINITY) {
+        sc = __expf(ms - M);
+        l += part_ml[((size_t)s * T * Hq + row) * 2 + 1] * sc;
+      }
+      s_sc[w][s] = sc;
+    }
+  }
+  l = wave_sum(l);
+  float o = 0.0f;
+#pragma unroll 8
   for (int s = 0; s < nsplits; ++s) {
-    if (s >= used_ctx && s < ctx_splits) continue;
-    const size_t pr = (size_t)s * T * Hq + row;
-    const float ms = part_ml[pr * 2];
-    if (ms == -INFINITY) continue;
-    const float sc = __expf(ms - M);
-    l += part_ml[pr * 2 + 1] * sc;
-    o += part_o[pr * D + c] * sc;
+    const float sc = s_sc[w][s];
+    if (sc != 0.0f) o += part_o[((size_t)s * T * Hq + row) * D + c] * sc;
   }
   const float r = o / l;
   store_elem<ST>(out, (size_t)row * D + c, r);
@@ -238,62 +416,101 @@ __global__ void attn_merge_kernel(const float* __restrict__ part_o, const float*
 }
 
 // ------------------------------------------------------------------------------------
-// router: RMSNorm(h), scores W_g h (Eq. 4), top-k by wavefront shuffles, softmax over the
-// selected scores. One workgroup per token.
+// router: RMSNorm(h), scores W_g h (Eq. 4) on the matrix cores, top-k by wavefront shuffles,
+// softmax over the selected scores. One workgroup (8 wavefronts) per tile of 16 tokens.
+// W_g is in the packed streaming layout (16-expert strips).
 // ------------------------------------------------------------------------------------
+constexpr int kRouterThreads = 512;
+
 template <typename ST>
-__global__ __launch_bounds__(256) void router_kernel(const void* __restrict__ h, const void* __restrict__ gain,
-                                                     const void* __restrict__ wg, int d, int E, int k, float eps,
-                                                     void* __restrict__ h_norm, float* __restrict__ logits,
-                                                     int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
-                                                     void* __restrict__ aux_hn, float* __restrict__ aux_logits,
-                                                     int32_t* __restrict__ aux_idx, float* __restrict__ aux_w) {
-  extern __shared__ float s_dyn[];
-  float* s_h = s_dyn;       // [d]
-  float* s_l = s_dyn + d;   // [E]
-  __shared__ float s_red[4];
-  const int t = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  float ss = 0.0f;
-  for (int c = tid; c < d; c += 256) {
-    const float v = load_elem<ST>(h, (size_t)t * d + c);
-    s_h[c] = v;
-    ss += v * v;
-  }
-  ss = wave_sum(ss);
-  if (lane == 0) s_red[w] = ss;
-  __syncthreads();
-  const float ms = (s_red[0] + s_red[1] + s_red[2] + s_red[3]) / (float)d;
-  const float rinv = 1.0f / sqrtf(ms + eps);
-  for (int c = tid; c < d; c += 256) {
-    const float v = round_store<ST>(s_h[c] * rinv * load_elem<ST>(gain, c));
-    s_h[c] = v;
-    store_elem<ST>(h_norm, (size_t)t * d + c, v);
-    if (aux_hn) store_elem<ST>(aux_hn, (size_t)t * d + c, v);
-  }
-  __syncthreads();
-  // scores: one wavefront per expert, lanes stride over d in 4-element groups
-  for (int e = w; e < E; e += 4) {
-    float acc = 0.0f;
-    for (int c = lane * 4; c < d; c += 256) {
-      const f32x4 wv = load4<ST>(wg, (size_t)e * d + c);
-      acc += wv[0] * s_h[c] + wv[1] * s_h[c + 1] + wv[2] * s_h[c + 2] + wv[3] * s_h[c + 3];
+__global__ __launch_bounds__(kRouterThreads) void router_kernel(
+    const void* __restrict__ h, const void* __restrict__ gain, const u32x4* __restrict__ wg_packed, int T, int d, int E,
+    int k, float eps, void* __restrict__ h_norm, float* __restrict__ logits, int32_t* __restrict__ topk_idx,
+    float* __restrict__ topk_w, void* __restrict__ aux_hn, float* __restrict__ aux_logits,
+    int32_t* __restrict__ aux_idx, float* __restrict__ aux_w) {
+  constexpr int EB = ST::kBytes;
+  constexpr int CE = 16 / EB;  // elements per 16-byte chunk
+  extern __shared__ __attribute__((aligned(16))) unsigned char s_raw[];
+  const int nkb = d * EB / 64;
+  u32x4* s_b = reinterpret_cast<u32x4*>(s_raw);                       // [nkb][64] token operand blocks
+  float* s_l = reinterpret_cast<float*>(s_raw + (size_t)nkb * 1024);  // [16][E]
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int tok0 = blockIdx.x * 16;
+  // ---- normalise two tokens per wavefront and lay them out as MFMA operand blocks
+  for (int n = w * 2; n < w * 2 + 2; ++n) {
+    const int t = tok0 + n;
+    const bool live = t < T;
+    float ss = 0.0f;
+    if (live)
+      for (int c = lane * 4; c < d; c += 256) {
+        const f32x4 v = load4<ST>(h, (size_t)t * d + c);
+        ss += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
+      }
+    ss = wave_sum(ss);
+    const float rinv = 1.0f / sqrtf(ss / (float)d + eps);
+    for (int c = lane * CE; c < d; c += 64 * CE) {  // one 16-byte chunk = one operand slot
+      u32x4 packed = {0, 0, 0, 0};
+      if (live) {
+        float v[CE];
+#pragma unroll
+        for (int i = 0; i < CE; i += 4) {
+          const f32x4 hv = load4<ST>(h, (size_t)t * d + c + i), gv = load4<ST>(gain, c + i);
+#pragma unroll
+          for (int u = 0; u < 4; ++u) v[i + u] = hv[u] * rinv * gv[u];
+        }
+        if (EB == 2) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) packed[i] = (uint32_t)f32_to_bf16(v[2 * i]) | ((uint32_t)f32_to_bf16(v[2 * i + 1]) << 16);
+        } else {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) packed[i] = __float_as_uint(v[i]);
+        }
+        *reinterpret_cast<u32x4*>((char*)h_norm + ((size_t)t * d + c) * EB) = packed;
+        if (aux_hn) *reinterpret_cast<u32x4*>((char*)aux_hn + ((size_t)t * d + c) * EB) = packed;
+      }
+      const int byte = c * EB;  // position in the row
+      s_b[(byte >> 6) * 64 + ((byte >> 4) & 3) * 16 + n] = packed;
     }
-    acc = wave_sum(acc);
-    if (lane == 0) {
-      s_l[e] = acc;
-      logits[(size_t)t * E + e] = acc;
-      if (aux_logits) aux_logits[(size_t)t * E + e] = acc;
+  }
+  __syncthreads();
+  // ---- scores: expert strips round-robin over the wavefronts
+  const int nstrips = E >> 4;
+  for (int strip = w; strip < nstrips; strip += kRouterThreads / 64) {
+    const u32x4* wp = wg_packed + (size_t)strip * nkb * 64 + lane;
+    f32x4 acc = {0, 0, 0, 0};
+    for (int kb0 = 0; kb0 < nkb; kb0 += 8) {
+      u32x4 a[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        if (kb0 + j < nkb) a[j] = wp[(size_t)(kb0 + j) * 64];
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        if (kb0 + j < nkb) acc = mfma_block<ST>(a[j], s_b[(kb0 + j) * 64 + lane], acc);
+    }
+    const int n = lane & 15, t = tok0 + n;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int e = strip * 16 + (lane >> 4) * 4 + j;
+      s_l[n * E + e] = acc[j];
+    }
+    if (t < T) {
+      *reinterpret_cast<f32x4*>(logits + (size_t)t * E + strip * 16 + (lane >> 4) * 4) = acc;
+      if (aux_logits) *reinterpret_cast<f32x4*>(aux_logits + (size_t)t * E + strip * 16 + (lane >> 4) * 4) = acc;
     }
   }
   __syncthreads();
-  if (w == 0) {
+  // ---- top-k and weights, two tokens per wavefront
+  for (int n = w * 2; n < w * 2 + 2; ++n) {
+    const int t = tok0 + n;
+    if (t >= T) continue;
+    float* sl = s_l + n * E;
     float sel_v = 0.0f, first = 0.0f, denom = 0.0f;
     int sel_i = 0;
     for (int j = 0; j < k; ++j) {
       float bv = -INFINITY;
       int bi = 0x7fffffff;
       for (int e = lane; e < E; e += 64) {
-        const float v = s_l[e];
+        const float v = sl[e];
         if (v > bv) { bv = v; bi = e; }  // ascending e inside a lane keeps the lowest index on ties
       }
 #pragma unroll
@@ -306,7 +523,7 @@ __global__ __launch_bounds__(256) void router_kernel(const void* __restrict__ h,
       const float ex = __expf(bv - first);
       denom += ex;
       if (lane == j) { sel_v = ex; sel_i = bi; }
-      if (lane == 0) s_l[bi] = -INFINITY;  // remove from the candidates
+      if (lane == 0) sl[bi] = -INFINITY;  // remove from the candidates
     }
     if (lane < k) {
       const float wv = sel_v / denom;
@@ -398,12 +615,24 @@ int launch_prep(const evict_ctx* c, const int32_t* tree_off, const int32_t* pare
 }
 
 size_t attn_partial_lds_bytes(int D) { return sizeof(float) * (size_t)(2 * kAttnKeys * (D + 1) + 4 * D + 4 * 64); }
+size_t attn_mfma_lds_bytes(int D) { return 2 * (size_t)(kMfmaKeys * (D + 8) + D * (kMfmaKeys + 4)); }
+size_t router_lds_bytes(const evict_model_desc& m) {
+  const size_t eb = m.dtype == EVICT_BF16 ? 2 : 4;
+  return (size_t)m.d * eb * 16 + (size_t)16 * m.E * sizeof(float);
+}
 
-int attn_setup() {
-  // the partial kernel needs more than the default 64 KiB of dynamic LDS at D = 128
-  const size_t need = attn_partial_lds_bytes(128);
-  EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)attn_partial_kernel<BF16>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)need));
-  EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)attn_partial_kernel<F32>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)need));
+int kernels_setup(const evict_model_desc& m) {
+  // kernels whose dynamic LDS exceeds the default 64 KiB limit
+  EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)attn_partial_kernel<BF16>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_partial_lds_bytes(128)));
+  EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)attn_partial_kernel<F32>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_partial_lds_bytes(128)));
+  EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)attn_partial_mfma_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_mfma_lds_bytes(128)));
+  EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)attn_partial_mfma_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_mfma_lds_bytes(64)));
+  const size_t rl = router_lds_bytes(m);
+  EVICT_REQUIRE(rl <= 160 * 1024, EVICT_E_UNSUPPORTED, "router needs %zu bytes of LDS (limit 160 KiB): d or E too large", rl);
+  if (m.dtype == EVICT_BF16)
+    EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)router_kernel<BF16>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)rl));
+  else
+    EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)router_kernel<F32>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)rl));
   return EVICT_OK;
 }
 
@@ -411,26 +640,43 @@ int launch_attention(const evict_ctx* c, const void* kc, const void* vc, long lo
                      const int32_t* ctx_len, int max_ctx_host, const int32_t* tree_off, int B, int T, const void* k_new,
                      const void* v_new, void* aux_out, hipStream_t s) {
   const evict_model_desc& m = c->m;
-  const int ctx_splits = (max_ctx_host + kAttnKeys - 1) / kAttnKeys;
-  const int nsplits = ctx_splits + EVICT_MAX_TREE_NODES / kAttnKeys;
-  const size_t lds = attn_partial_lds_bytes(m.D);
+  int ctx_splits, nsplits, keys;
   if (m.dtype == EVICT_BF16) {
-    hipLaunchKernelGGL(attn_partial_kernel<BF16>, dim3(nsplits, m.Hkv, B), dim3(256), lds, s, c->q, kc, vc, seq_stride,
-                       head_stride, ctx_len, max_ctx_host, tree_off, k_new, v_new, c->anc, m.Hq, m.Hkv, m.D, ctx_splits, T,
-                       c->part_o, c->part_ml);
+    keys = kMfmaKeys;
+    ctx_splits = (max_ctx_host + keys - 1) / keys;
+    nsplits = ctx_splits + 1;
+    // spread the query-row tiles over enough workgroups to cover the chip
+    const int G = m.Hq / m.Hkv;
+    const int max_nodes = T < EVICT_MAX_TREE_NODES ? T : EVICT_MAX_TREE_NODES;
+    const int ntiles = (max_nodes * G + 15) / 16;
+    int rb = (256 + nsplits * m.Hkv * B - 1) / (nsplits * m.Hkv * B);
+    const int rb_max = (ntiles + 3) / 4;
+    rb = rb > rb_max ? rb_max : rb;
+    rb = rb < 1 ? 1 : rb;
+    const dim3 grid(nsplits * rb, m.Hkv, B);
+    const size_t lds = attn_mfma_lds_bytes(m.D);
+#define EVICT_ATTN_ARGS (const uint16_t*)c->q, (const uint16_t*)kc, (const uint16_t*)vc, seq_stride, head_stride, ctx_len, \
+                        max_ctx_host, tree_off, (const uint16_t*)k_new, (const uint16_t*)v_new, c->anc, m.Hq, m.Hkv,       \
+                        ctx_splits, rb, T, c->part_o, c->part_ml
+    if (m.D == 128) hipLaunchKernelGGL(attn_partial_mfma_kernel<128>, grid, dim3(256), lds, s, EVICT_ATTN_ARGS);
+    else hipLaunchKernelGGL(attn_partial_mfma_kernel<64>, grid, dim3(256), lds, s, EVICT_ATTN_ARGS);
+#undef EVICT_ATTN_ARGS
   } else {
-    hipLaunchKernelGGL(attn_partial_kernel<F32>, dim3(nsplits, m.Hkv, B), dim3(256), lds, s, c->q, kc, vc, seq_stride,
-                       head_stride, ctx_len, max_ctx_host, tree_off, k_new, v_new, c->anc, m.Hq, m.Hkv, m.D, ctx_splits, T,
-                       c->part_o, c->part_ml);
+    keys = kAttnKeys;
+    ctx_splits = (max_ctx_host + keys - 1) / keys;
+    nsplits = ctx_splits + EVICT_MAX_TREE_NODES / keys;
+    hipLaunchKernelGGL(attn_partial_kernel<F32>, dim3(nsplits, m.Hkv, B), dim3(256), attn_partial_lds_bytes(m.D), s, c->q,
+                       kc, vc, seq_stride, head_stride, ctx_len, max_ctx_host, tree_off, k_new, v_new, c->anc, m.Hq,
+                       m.Hkv, m.D, ctx_splits, T, c->part_o, c->part_ml);
   }
-  int rc = launch_status("attn_partial_kernel");
+  int rc = launch_status("attention partial kernel");
   if (rc) return rc;
   if (m.dtype == EVICT_BF16)
     hipLaunchKernelGGL(attn_merge_kernel<BF16>, dim3(T * m.Hq), dim3(m.D), 0, s, c->part_o, c->part_ml, nsplits, T, m.Hq,
-                       m.D, c->seq_of, ctx_len, max_ctx_host, kAttnKeys, ctx_splits, c->attn_o, aux_out);
+                       m.D, c->seq_of, ctx_len, max_ctx_host, keys, ctx_splits, c->attn_o, aux_out);
   else
     hipLaunchKernelGGL(attn_merge_kernel<F32>, dim3(T * m.Hq), dim3(m.D), 0, s, c->part_o, c->part_ml, nsplits, T, m.Hq,
-                       m.D, c->seq_of, ctx_len, max_ctx_host, kAttnKeys, ctx_splits, c->attn_o, aux_out);
+                       m.D, c->seq_of, ctx_len, max_ctx_host, keys, ctx_splits, c->attn_o, aux_out);
   return launch_status("attn_merge_kernel");
 }
 
@@ -438,17 +684,18 @@ int attn_splits_for(int max_ctx) { return (max_ctx + kAttnKeys - 1) / kAttnKeys 
 
 int launch_router(const evict_ctx* c, const void* gain, const void* wg, int T, const evict_layer_aux* aux, hipStream_t s) {
   const evict_model_desc& m = c->m;
-  const size_t lds = sizeof(float) * (size_t)(m.d + m.E);
+  const size_t lds = router_lds_bytes(m);
   void* a_hn = aux ? aux->h_norm : nullptr;
   float* a_lg = aux ? aux->router_logits : nullptr;
   int32_t* a_ix = aux ? aux->topk_idx : nullptr;
   float* a_w = aux ? aux->topk_w : nullptr;
+  const int grid = (T + 15) / 16;
   if (m.dtype == EVICT_BF16)
-    hipLaunchKernelGGL(router_kernel<BF16>, dim3(T), dim3(256), lds, s, c->h, gain, wg, m.d, m.E, m.k, m.rms_eps, c->h_norm,
-                       c->logits, c->topk_idx, c->topk_w, a_hn, a_lg, a_ix, a_w);
+    hipLaunchKernelGGL(router_kernel<BF16>, dim3(grid), dim3(kRouterThreads), lds, s, c->h, gain, (const u32x4*)wg, T, m.d,
+                       m.E, m.k, m.rms_eps, c->h_norm, c->logits, c->topk_idx, c->topk_w, a_hn, a_lg, a_ix, a_w);
   else
-    hipLaunchKernelGGL(router_kernel<F32>, dim3(T), dim3(256), lds, s, c->h, gain, wg, m.d, m.E, m.k, m.rms_eps, c->h_norm,
-                       c->logits, c->topk_idx, c->topk_w, a_hn, a_lg, a_ix, a_w);
+    hipLaunchKernelGGL(router_kernel<F32>, dim3(grid), dim3(kRouterThreads), lds, s, c->h, gain, (const u32x4*)wg, T, m.d,
+                       m.E, m.k, m.rms_eps, c->h_norm, c->logits, c->topk_idx, c->topk_w, a_hn, a_lg, a_ix, a_w);
   return launch_status("router_kernel");
 }
 

@@ -11,7 +11,7 @@ int launch_pack(const void* src, long long src_group_bytes, int rows, int cols, 
                 int dst_strip_step, long long dst_group_strips, int groups, int head_dim, hipStream_t s);
 int launch_prep(const evict_ctx* c, const int32_t* tree_off, const int32_t* parent, int B, int T, const int32_t* ctx_len,
                 int max_ctx, const void* x, const void* gain, hipStream_t s);
-int attn_setup();
+int kernels_setup(const evict_model_desc& m);
 int attn_splits_for(int max_ctx);
 int launch_attention(const evict_ctx* c, const void* kc, const void* vc, long long seq_stride, long long head_stride,
                      const int32_t* ctx_len, int max_ctx_host, const int32_t* tree_off, int B, int T, const void* k_new,

@@ -89,8 +89,8 @@ __device__ void compact_tree(int n, int kstar, const int* s_par, const int* s_ra
 __global__ __launch_bounds__(kSelThreads) void select_prefix_kernel(
     const int32_t* __restrict__ tree_off, const int32_t* __restrict__ parent, const float* __restrict__ prob,
     const float* __restrict__ cost, int kmax, int32_t* __restrict__ k_star, float* __restrict__ est_len,
-    int32_t* __restrict__ order_out, float* __restrict__ psum_out, int32_t* __restrict__ rank_ws, int single,
-    int32_t* __restrict__ keep, int32_t* __restrict__ new_parent, int32_t* __restrict__ new_tree_off) {
+    int32_t* __restrict__ order_out, float* __restrict__ psum_out, int32_t* rank_ws, int single, int32_t* keep,
+    int32_t* new_parent, int32_t* __restrict__ new_tree_off) {
   __shared__ int s_par[kMaxSel];
   __shared__ float s_score[kMaxSel];
   __shared__ float s_sorted[kMaxSel];
@@ -263,17 +263,29 @@ __global__ __launch_bounds__(64) void accept_path_kernel(
 
 constexpr int kUnionThreads = 256;
 
+// Eq. 5 and the grouping it induces, one workgroup. Fast path (no expert repeated inside a
+// token, which is what TopK produces): per expert a bitmask over tokens, built with LDS
+// atomics; counts, ranks inside an expert and the stable order all follow from popcounts.
+// General path (repeats present, or masks too large for LDS): one thread per expert walks
+// the pairs in ascending pair id.
 __global__ __launch_bounds__(kUnionThreads) void expert_union_kernel(
-    const int32_t* __restrict__ topk_idx, int P, int E, int32_t* __restrict__ union_ids,
+    const int32_t* __restrict__ topk_idx, int T, int k, int E, int use_masks, int32_t* __restrict__ union_ids,
     int32_t* __restrict__ union_count, int32_t* __restrict__ hist, int32_t* __restrict__ offsets,
     int32_t* __restrict__ perm, int32_t* __restrict__ inv, int32_t* __restrict__ status) {
-  extern __shared__ int s_mem[];
+  extern __shared__ __attribute__((aligned(8))) int s_mem[];
+  const int P = T * k;
+  const int words = (T + 63) >> 6;
   int* s_idx = s_mem;            // [P]
   int* s_hist = s_mem + P;       // [E]
   int* s_off = s_hist + E;       // [E + 1]
+  unsigned long long* s_mask = reinterpret_cast<unsigned long long*>(s_mem + ((P + 2 * E + 2) & ~1));  // [E][words]
   __shared__ int s_wave[16];
+  __shared__ int s_dup;
   const int tid = threadIdx.x;
   for (int e = tid; e < E; e += kUnionThreads) s_hist[e] = 0;
+  if (use_masks)
+    for (int i = tid; i < E * words; i += kUnionThreads) s_mask[i] = 0ull;
+  if (tid == 0) s_dup = 0;
   __syncthreads();
   bool bad = false;
   for (int p = tid; p < P; p += kUnionThreads) {
@@ -281,6 +293,12 @@ __global__ __launch_bounds__(kUnionThreads) void expert_union_kernel(
     if (e < 0 || e >= E) { bad = true; e = 0; }
     s_idx[p] = e;
     atomicAdd(&s_hist[e], 1);
+    if (use_masks) {
+      const int t = p / k;
+      const unsigned long long bit = 1ull << (t & 63);
+      const unsigned long long old = atomicOr(&s_mask[e * words + (t >> 6)], bit);
+      if (old & bit) s_dup = 1;  // the same expert twice in one token
+    }
   }
   if (bad && status) atomicOr(status, ST_BAD_EXPERT);
   __syncthreads();
@@ -311,15 +329,27 @@ __global__ __launch_bounds__(kUnionThreads) void expert_union_kernel(
   for (int e = tot_f + tid; e < E; e += kUnionThreads) union_ids[e] = -1;
   if (tid == 0) { offsets[E] = tot_h; union_count[0] = tot_f; }
   __syncthreads();
-  // stable grouping: one thread per expert walks the pairs in ascending pair id
-  for (int e = tid; e < E; e += kUnionThreads) {
-    if (s_hist[e] == 0) continue;
-    int pos = s_off[e];
-    for (int p = 0; p < P; ++p) {
-      if (s_idx[p] == e) {
-        perm[pos] = p;
-        inv[p] = pos;
-        ++pos;
+  if (use_masks && !s_dup) {
+    // position of pair (t, slot) inside its expert = number of earlier tokens routed there
+    for (int p = tid; p < P; p += kUnionThreads) {
+      const int e = s_idx[p], t = p / k;
+      const unsigned long long* m = s_mask + e * words;
+      int pos = s_off[e];
+      for (int wd = 0; wd < (t >> 6); ++wd) pos += __popcll(m[wd]);
+      pos += __popcll(m[t >> 6] & ((1ull << (t & 63)) - 1ull));
+      perm[pos] = p;
+      inv[p] = pos;
+    }
+  } else {
+    for (int e = tid; e < E; e += kUnionThreads) {
+      if (s_hist[e] == 0) continue;
+      int pos = s_off[e];
+      for (int p = 0; p < P; ++p) {
+        if (s_idx[p] == e) {
+          perm[pos] = p;
+          inv[p] = pos;
+          ++pos;
+        }
       }
     }
   }
@@ -409,9 +439,13 @@ int evict_expert_union(evict_ctx* ctx, const int32_t* topk_idx, int T, int k, in
   EVICT_REQUIRE((int64_t)T * k <= 8192 && E <= 1024, EVICT_E_UNSUPPORTED,
                 "evict_expert_union: T*k=%lld (limit 8192), E=%d (limit 1024)", (long long)T * k, E);
   const int P = T * k;
-  const size_t lds = sizeof(int) * (size_t)(P + 2 * E + 1);
-  hipLaunchKernelGGL(expert_union_kernel, dim3(1), dim3(kUnionThreads), lds, (hipStream_t)stream, topk_idx, P, E,
-                     union_ids, union_count, hist, offsets, perm, inv, ctx ? ctx->status : nullptr);
+  const size_t words = (size_t)(T + 63) / 64;
+  size_t lds = sizeof(int) * (size_t)((P + 2 * E + 2) & ~1);
+  const size_t mask_bytes = 8 * (size_t)E * words;
+  const int use_masks = lds + mask_bytes <= 60 * 1024 ? 1 : 0;
+  if (use_masks) lds += mask_bytes;
+  hipLaunchKernelGGL(expert_union_kernel, dim3(1), dim3(kUnionThreads), lds, (hipStream_t)stream, topk_idx, T, k, E,
+                     use_masks, union_ids, union_count, hist, offsets, perm, inv, ctx ? ctx->status : nullptr);
   return launch_status("expert_union_kernel");
 }
 

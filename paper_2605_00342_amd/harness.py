@@ -50,7 +50,10 @@ class DeviceLayer:
         def empty(nbytes):
             return torch.empty(nbytes // eb, dtype=tdt, device=device)
 
-        self.g_attn, self.g_moe, self.wg = up("g_attn"), up("g_moe"), up("wg")
+        self.g_attn, self.g_moe = up("g_attn"), up("g_moe")
+        wg_raw = up("wg")
+        self.wg = empty(cfg.E * cfg.d * eb)
+        ev.evict_pack_dense(code, wg_raw, cfg.E, cfg.d, self.wg)
         wq, wk, wv, wo = up("wq"), up("wk"), up("wv"), up("wo")
         self.wqkv = empty((cfg.Hq + 2 * cfg.Hkv) * cfg.D * cfg.d * eb)
         ev.evict_pack_qkv(self.desc, wq, wk, wv, self.wqkv)

@@ -134,6 +134,9 @@ def test_expert_union_bit_exact(T, k, E, seed):
     idx = np.stack([g.permutation(E)[:k] for _ in range(T)]).astype(np.int32)
     if seed == 3:
         idx[:] = idx[0]          # identical routing: union of exactly k experts
+    if seed == 5:
+        idx[7, 1] = idx[7, 0]    # an expert repeated inside a token: the general path must take over
+        idx[20, 5] = idx[20, 2]
     ref = orc.expert_union(idx, E)
     P = T * k
     z = lambda n: torch.full((n,), -5, dtype=torch.int32, device=DEV)
