@@ -57,6 +57,8 @@ int evict_create(evict_ctx** out, const evict_model_desc* m, int max_tokens, int
                 "evict_create: max_tokens=%d, max_batch=%d, max_ctx=%d", max_tokens, max_batch, max_ctx);
   EVICT_REQUIRE((long long)max_tokens * m->k <= 8192, EVICT_E_UNSUPPORTED, "max_tokens*k=%lld exceeds 8192",
                 (long long)max_tokens * m->k);
+  EVICT_REQUIRE(attn_splits_for(max_ctx) <= 192, EVICT_E_UNSUPPORTED, "max_ctx=%d needs more than 192 attention splits", max_ctx);
+  EVICT_REQUIRE(m->d * (m->dtype == EVICT_BF16 ? 2 : 4) <= 16384, EVICT_E_UNSUPPORTED, "d=%d: rows above 16 KiB are not supported", m->d);
   evict_ctx_owner* o = new (std::nothrow) evict_ctx_owner();
   EVICT_REQUIRE(o, EVICT_E_INVALID, "out of host memory");
   evict_ctx& c = o->c;
@@ -92,6 +94,8 @@ int evict_create(evict_ctx** out, const evict_model_desc* m, int max_tokens, int
   A(&c.union_count, 16);
   A(&c.perm, T * k * 4);
   A(&c.inv, T * k * 4);
+  A(&c.work, E * 16);
+  A(&c.tok_of_pos, T * k * 4);
   A(&c.act, T * k * F * eb);
   A(&c.y, T * k * d * 4);
   c.act_sh = nullptr;
@@ -226,7 +230,9 @@ int evict_verify_layer(evict_ctx* ctx, const evict_layer_weights* w, const int32
   if (rc) return rc;
   EVICT_MARK(1);
 
-  const int nt_dense = T <= 16 ? 1 : 2;
+  const int nt_dense = 1;
+  const int dense_tiles = (T + 15) / 16;
+  auto dense_grid = [&](int units) { return ((units + 7) / 8) * 8 * dense_tiles; };
   {  // q, k, v projections + rotation (positions ctx_len + depth)
     GemmArgs a = {};
     a.W = (const u32x4*)w->wqkv_packed;
@@ -238,7 +244,8 @@ int evict_verify_layer(evict_ctx* ctx, const evict_layer_weights* w, const int32
     a.out0 = ctx->q; a.out1 = k_new; a.out2 = v_new;
     a.rope_cs = ctx->rope_cs;
     a.Hq = m.Hq; a.Hkv = m.Hkv; a.D = m.D;
-    rc = launch_gemm(m.dtype, EPI_QKV, a, nt_dense, a.n_strips < 512 ? a.n_strips : 512, s);
+    a.dense_tiles = dense_tiles;
+    rc = launch_gemm(m.dtype, EPI_QKV, a, nt_dense, dense_grid(a.n_strips), s);
     if (rc) return rc;
     if (aux && aux->q) EVICT_HIP_CHECK(hipMemcpyAsync(aux->q, ctx->q, (size_t)T * HqD * eb, hipMemcpyDeviceToDevice, s));
   }
@@ -258,7 +265,8 @@ int evict_verify_layer(evict_ctx* ctx, const evict_layer_weights* w, const int32
     a.out0 = ctx->h;
     a.ldo = m.d;
     a.resid = x_in;
-    rc = launch_gemm(m.dtype, EPI_RESID, a, nt_dense, a.n_strips < 512 ? a.n_strips : 512, s);
+    a.dense_tiles = dense_tiles;
+    rc = launch_gemm(m.dtype, EPI_RESID, a, nt_dense, dense_grid(a.n_strips), s);
     if (rc) return rc;
     if (aux && aux->h) EVICT_HIP_CHECK(hipMemcpyAsync(aux->h, ctx->h, (size_t)T * m.d * eb, hipMemcpyDeviceToDevice, s));
   }
@@ -266,8 +274,8 @@ int evict_verify_layer(evict_ctx* ctx, const evict_layer_weights* w, const int32
   rc = launch_router(ctx, w->g_moe, w->wg_packed, T, aux, s);
   if (rc) return rc;
   EVICT_MARK(5);
-  rc = evict_expert_union(ctx, ctx->topk_idx, T, m.k, m.E, ctx->union_ids, ctx->union_count, ctx->hist, ctx->offsets,
-                          ctx->perm, ctx->inv, stream);
+  rc = launch_union(ctx->status, ctx->topk_idx, T, m.k, m.E, ctx->union_ids, ctx->union_count, ctx->hist, ctx->offsets,
+                    ctx->perm, ctx->inv, ctx->work, ctx->tok_of_pos, s);
   if (rc) return rc;
   if (aux) {
     if (aux->union_ids) EVICT_HIP_CHECK(hipMemcpyAsync(aux->union_ids, ctx->union_ids, (size_t)m.E * 4, hipMemcpyDeviceToDevice, s));
@@ -285,8 +293,7 @@ int evict_verify_layer(evict_ctx* ctx, const evict_layer_weights* w, const int32
     a.X = ctx->h_norm;
     a.ldx_bytes = (long long)m.d * eb;
     a.grouped = 1;
-    a.union_ids = ctx->union_ids; a.union_count = ctx->union_count; a.offsets = ctx->offsets; a.perm = ctx->perm;
-    a.topk = m.k;
+    a.union_count = ctx->union_count; a.work = ctx->work; a.tok_of_pos = ctx->tok_of_pos;
     a.x_by_token = 1;
     a.out0 = ctx->act;
     a.ldo = m.F;
@@ -303,8 +310,7 @@ int evict_verify_layer(evict_ctx* ctx, const evict_layer_weights* w, const int32
     a.X = ctx->act;
     a.ldx_bytes = (long long)m.F * eb;
     a.grouped = 1;
-    a.union_ids = ctx->union_ids; a.union_count = ctx->union_count; a.offsets = ctx->offsets; a.perm = ctx->perm;
-    a.topk = m.k;
+    a.union_count = ctx->union_count; a.work = ctx->work; a.tok_of_pos = ctx->tok_of_pos;
     a.x_by_token = 0;
     a.out0 = ctx->y;
     a.ldo = m.d;
@@ -322,7 +328,8 @@ int evict_verify_layer(evict_ctx* ctx, const evict_layer_weights* w, const int32
     a.T = T;
     a.out0 = (char*)ctx->act_sh + (size_t)sh * T * m.F * eb;
     a.ldo = m.F;
-    rc = launch_gemm(m.dtype, EPI_SWIGLU, a, nt_dense, (a.n_strips / 2) < 512 ? (a.n_strips / 2) : 512, s);
+    a.dense_tiles = dense_tiles;
+    rc = launch_gemm(m.dtype, EPI_SWIGLU, a, nt_dense, dense_grid(a.n_strips / 2), s);
     if (rc) return rc;
     GemmArgs b = {};
     b.n_strips = m.d / 16;
@@ -333,7 +340,8 @@ int evict_verify_layer(evict_ctx* ctx, const evict_layer_weights* w, const int32
     b.T = T;
     b.out0 = ctx->y_sh + (size_t)sh * T * m.d;
     b.ldo = m.d;
-    rc = launch_gemm(m.dtype, EPI_F32, b, nt_dense, b.n_strips < 512 ? b.n_strips : 512, s);
+    b.dense_tiles = dense_tiles;
+    rc = launch_gemm(m.dtype, EPI_F32, b, nt_dense, dense_grid(b.n_strips), s);
     if (rc) return rc;
   }
   EVICT_MARK(9);

@@ -32,6 +32,8 @@ struct evict_ctx {
   int32_t* union_count;  // [1]
   int32_t* perm;         // [T*k]
   int32_t* inv;          // [T*k]
+  int4* work;            // [E] per union slot: expert id, first position, token count
+  int32_t* tok_of_pos;   // [T*k] token of each grouped position
   void* act;             // [T*k][F] storage dtype
   float* y;              // [T*k][d]
   void* act_sh;          // [n_shared][T][F]

@@ -26,13 +26,12 @@ struct GemmArgs {
   const void* X;         // token operand rows, storage dtype
   long long ldx_bytes;   // bytes between rows of X
   int grouped;           // 0: one matrix, tokens 0..T-1; 1: one matrix per union expert
-  const int* union_ids;
   const int* union_count;
-  const int* offsets;    // by expert id
-  const int* perm;       // pair ids grouped by expert
-  int topk;
-  int x_by_token;        // grouped: 1 -> X row = perm[p] / topk, 0 -> X row = p
+  const int4* work;      // per union slot: {expert id, first position, token count, 0}
+  const int* tok_of_pos; // token of each grouped position (perm[p] / k)
+  int x_by_token;        // grouped: 1 -> X row = tok_of_pos[p], 0 -> X row = p
   int T;                 // dense: token rows
+  int dense_tiles;       // dense: workgroups per strip, each taking 16*NT tokens
   void* out0;            // QKV: q; RESID: h; SWIGLU: act; F32: y
   void* out1;            // QKV: k_new
   void* out2;            // QKV: v_new
@@ -45,49 +44,61 @@ struct GemmArgs {
 constexpr int kGemmWaves = 8;
 constexpr int kGemmThreads = kGemmWaves * 64;
 
-template <typename ST, int NT, int KBW, int PF, int EPI>
-__global__ __launch_bounds__(kGemmThreads) void gemm_stream_kernel(const GemmArgs a) {
+// KBW: 1 KiB blocks a wavefront takes per step (EXACT: every step has exactly KBW, no masking);
+// PF: steps of weight loads kept in flight; NT: 16-token tiles held in registers.
+template <typename ST, int NT, int KBW, int PF, int EPI, bool EXACT>
+__global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 4 : 2))) void gemm_stream_kernel(const GemmArgs a) {
   constexpr int SPU = (EPI == EPI_SWIGLU) ? 2 : 1;  // strips per unit of work
+  // expert weights are read exactly once per call: keep them out of the caches' way
+  constexpr bool kStreamOnce = (EPI == EPI_SWIGLU || EPI == EPI_F32);
   __shared__ f32x4 s_part[2][kGemmWaves][NT][64];
 
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wavefront index, known uniform
   const int upg = a.n_strips / SPU;
   const int ngroups = a.grouped ? *a.union_count : 1;
-  const long long tot = (long long)ngroups * upg;
-  const long long u0 = tot * blockIdx.x / gridDim.x;
-  const long long u1 = tot * (blockIdx.x + 1) / gridDim.x;
+  unsigned u0, u1;
+  int tok_begin = 0, tok_limit = 0x7fffffff;
+  if (a.grouped) {
+    // equal contiguous ranges of the unit list (32-bit: units * workgroups stays far below 2^32)
+    const unsigned tot = (unsigned)ngroups * (unsigned)upg;
+    u0 = tot * blockIdx.x / gridDim.x;
+    u1 = tot * (blockIdx.x + 1) / gridDim.x;
+  } else {
+    // one workgroup per (strip, token tile). Workgroup ids go round-robin over the 8 XCDs, so
+    // the tiles of one strip are given ids 8 apart: they share an L2 and read the strip from
+    // HBM once.
+    const unsigned xcd = blockIdx.x & 7u, i = blockIdx.x >> 3;
+    const unsigned tile = i % (unsigned)a.dense_tiles;
+    u0 = (i / (unsigned)a.dense_tiles) * 8u + xcd;
+    if (u0 >= (unsigned)upg) return;
+    u1 = u0 + 1;
+    tok_begin = (int)tile * 16 * NT;
+    tok_limit = tok_begin + 16 * NT;
+  }
   const int nkb = a.nkb;
   const int nchunks = (nkb + 63) >> 6;
   int parity = 0;
 
-  for (long long unit = u0; unit < u1;) {
-    const int grp = (int)(unit / upg);
-    long long seg_end = (long long)(grp + 1) * upg;
+  for (unsigned unit = u0; unit < u1;) {
+    const int grp = (int)(unit / (unsigned)upg);
+    unsigned seg_end = (unsigned)(grp + 1) * (unsigned)upg;
     if (seg_end > u1) seg_end = u1;
-    const int unit_in_grp = (int)(unit - (long long)grp * upg);
+    const int unit_in_grp = (int)(unit - (unsigned)grp * (unsigned)upg);
     const int strip0 = unit_in_grp * SPU;
     const int nitems = (int)(seg_end - unit) * SPU;
     int p0 = 0, ntok = a.T;
     const u32x4* wbase = a.W;
     if (a.grouped) {
-      const int e = a.union_ids[grp];
-      p0 = a.offsets[e];
-      ntok = a.offsets[e + 1] - p0;
-      wbase += (long long)e * a.group_stride;
+      const int4 rec = a.work[grp];
+      p0 = rec.y;
+      ntok = rec.z;
+      wbase += (long long)rec.x * a.group_stride;
     }
     const int nsteps = nitems * nchunks;
 
-    for (int tok0 = 0; tok0 < ntok; tok0 += 16 * NT) {
-      // token operand rows of this lane's column in each tile
-      const char* xrow[NT];
-#pragma unroll
-      for (int t = 0; t < NT; ++t) {
-        int col = tok0 + t * 16 + (lane & 15);
-        if (col > ntok - 1) col = ntok - 1;  // padded columns repeat the last token; never stored
-        long long row = col;
-        if (a.grouped) row = a.x_by_token ? (a.perm[p0 + col] / a.topk) : (p0 + col);
-        xrow[t] = (const char*)a.X + row * a.ldx_bytes + (lane >> 4) * 16;
-      }
+    const int tok_end = ntok < tok_limit ? ntok : tok_limit;
+    for (int tok0 = tok_begin; tok0 < tok_end; tok0 += 16 * NT) {
       u32x4 A[PF][KBW];
       u32x4 Bf[NT][KBW];
       f32x4 acc[NT];
@@ -97,10 +108,15 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_stream_kernel(const GemmArg
 
       // block range of this wavefront inside chunk c: [b0, b0 + nb)
       auto range = [&](int c, int& b0, int& nb) {
-        int cb = nkb - c * 64;
-        cb = cb > 64 ? 64 : cb;
-        b0 = c * 64 + (w * cb) / kGemmWaves;
-        nb = c * 64 + ((w + 1) * cb) / kGemmWaves - b0;
+        if (EXACT) {
+          b0 = c * 64 + w * KBW;
+          nb = KBW;
+        } else {
+          int cb = nkb - c * 64;
+          cb = cb > 64 ? 64 : cb;
+          b0 = c * 64 + (w * cb) / kGemmWaves;
+          nb = c * 64 + ((w + 1) * cb) / kGemmWaves - b0;
+        }
       };
       auto issue = [&](u32x4(&dst)[KBW], int step) {
         const int it = step / nchunks, c = step - it * nchunks;
@@ -109,21 +125,34 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_stream_kernel(const GemmArg
         const u32x4* p = wbase + ((long long)(strip0 + it) * nkb + b0) * 64 + lane;
 #pragma unroll
         for (int j = 0; j < KBW; ++j)
-          if (j < nb) dst[j] = __builtin_nontemporal_load(p + j * 64);
+          if (EXACT || j < nb) dst[j] = kStreamOnce ? __builtin_nontemporal_load(p + j * 64) : p[j * 64];
       };
+      // weights first: their addresses need nothing but the expert id
+#pragma unroll
+      for (int r = 0; r < PF; ++r)
+        if (r < nsteps) issue(A[r], r);
+
+      // token operand rows of this lane's column in each tile
+      const char* xrow[NT];
+#pragma unroll
+      for (int t = 0; t < NT; ++t) {
+        int col = tok0 + t * 16 + (lane & 15);
+        if (col > ntok - 1) col = ntok - 1;  // padded columns repeat the last token; never stored
+        long long row = col;
+        if (a.grouped) row = a.x_by_token ? a.tok_of_pos[p0 + col] : (p0 + col);
+        xrow[t] = (const char*)a.X + row * a.ldx_bytes + (lane >> 4) * 16;
+      }
       auto load_b = [&](int c) {
         int b0, nb;
         range(c, b0, nb);
 #pragma unroll
-        for (int t = 0; t < NT; ++t)
+        for (int t = 0; t < NT; ++t) {
+          const char* bp = xrow[t] + (long long)b0 * 64;  // one base per tile, constant offsets below
 #pragma unroll
           for (int j = 0; j < KBW; ++j)
-            if (j < nb) Bf[t][j] = *reinterpret_cast<const u32x4*>(xrow[t] + (long long)(b0 + j) * 64);
+            if (EXACT || j < nb) Bf[t][j] = *reinterpret_cast<const u32x4*>(bp + j * 64);
+        }
       };
-
-#pragma unroll
-      for (int r = 0; r < PF; ++r)
-        if (r < nsteps) issue(A[r], r);
       if (nchunks == 1) load_b(0);
 
       for (int s0 = 0; s0 < nsteps; s0 += PF) {
@@ -137,7 +166,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_stream_kernel(const GemmArg
             range(c, b0, nb);
 #pragma unroll
             for (int j = 0; j < KBW; ++j)
-              if (j < nb) {
+              if (EXACT || j < nb) {
 #pragma unroll
                 for (int t = 0; t < NT; ++t) acc[t] = mfma_block<ST>(A[r][j], Bf[t][j], acc[t]);
               }

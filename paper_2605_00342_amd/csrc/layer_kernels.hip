@@ -49,10 +49,25 @@ __global__ __launch_bounds__(256) void prep_kernel(const int32_t* __restrict__ t
                                                    int32_t* __restrict__ depth, int32_t* __restrict__ seq_of,
                                                    float* __restrict__ rope_cs, void* __restrict__ x_norm,
                                                    int32_t* __restrict__ status) {
+  constexpr int EB = ST::kBytes;
+  constexpr int CE = 16 / EB;
+  constexpr int MAXC = 4;  // 16-byte chunks of the row per thread (d <= 256*CE*MAXC)
   __shared__ int s_par[EVICT_MAX_TREE_NODES];
   __shared__ int s_b, s_depth;
   __shared__ float s_red[4];
   const int t = blockIdx.x, tid = threadIdx.x;
+  // the row and the gain do not depend on the tree: fetch them first
+  u32x4 raw[MAXC], graw[MAXC];
+#pragma unroll
+  for (int i = 0; i < MAXC; ++i) {
+    const int c = (tid + 256 * i) * CE;
+    raw[i] = u32x4{0, 0, 0, 0};
+    graw[i] = u32x4{0, 0, 0, 0};
+    if (c < d) {
+      raw[i] = *reinterpret_cast<const u32x4*>((const char*)x + ((size_t)t * d + c) * EB);
+      graw[i] = *reinterpret_cast<const u32x4*>((const char*)gain + (size_t)c * EB);
+    }
+  }
   if (tid == 0) s_b = 0;
   __syncthreads();
   for (int b = tid; b < B; b += 256)
@@ -61,6 +76,7 @@ __global__ __launch_bounds__(256) void prep_kernel(const int32_t* __restrict__ t
   const int b = s_b;
   const int lo = tree_off[b];
   int n = tree_off[b + 1] - lo;
+  int L = ctx_len[b];
   if (n > EVICT_MAX_TREE_NODES) { n = EVICT_MAX_TREE_NODES; if (tid == 0) atomicOr(status, ST_BAD_TREE_SIZE); }
   const int i = t - lo < n ? t - lo : n - 1;
   for (int j = tid; j < n; j += 256) {
@@ -69,6 +85,22 @@ __global__ __launch_bounds__(256) void prep_kernel(const int32_t* __restrict__ t
     else if (p < 0 || p >= j) { p = 0; atomicOr(status, ST_BAD_PARENT); }
     s_par[j] = p;
   }
+  // sum of squares while the tree loads are in flight
+  float ss = 0.0f;
+#pragma unroll
+  for (int k = 0; k < MAXC; ++k)
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (EB == 2) {
+        const float a = __uint_as_float(raw[k][u] << 16), bb = __uint_as_float(raw[k][u] & 0xFFFF0000u);
+        ss += a * a + bb * bb;
+      } else {
+        const float a = __uint_as_float(raw[k][u]);
+        ss += a * a;
+      }
+    }
+  ss = wave_sum(ss);
+  if ((tid & 63) == 0) s_red[tid >> 6] = ss;
   __syncthreads();
   if (tid == 0) {
     uint64_t m0 = 0, m1 = 0;
@@ -83,8 +115,28 @@ __global__ __launch_bounds__(256) void prep_kernel(const int32_t* __restrict__ t
     seq_of[t] = b;
     s_depth = dep;
   }
+  // RMSNorm(x[t]) * gain, rounded to the storage type
+  const float ms = (s_red[0] + s_red[1] + s_red[2] + s_red[3]) / (float)d;
+  const float rinv = 1.0f / sqrtf(ms + eps);
+#pragma unroll
+  for (int k = 0; k < MAXC; ++k) {
+    const int c = (tid + 256 * k) * CE;
+    if (c < d) {
+      u32x4 packed;
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (EB == 2) {
+          const float a = __uint_as_float(raw[k][u] << 16) * rinv * __uint_as_float(graw[k][u] << 16);
+          const float bb = __uint_as_float(raw[k][u] & 0xFFFF0000u) * rinv * __uint_as_float(graw[k][u] & 0xFFFF0000u);
+          packed[u] = (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(bb) << 16);
+        } else {
+          packed[u] = __float_as_uint(__uint_as_float(raw[k][u]) * rinv * __uint_as_float(graw[k][u]));
+        }
+      }
+      *reinterpret_cast<u32x4*>((char*)x_norm + ((size_t)t * d + c) * EB) = packed;
+    }
+  }
   __syncthreads();
-  int L = ctx_len[b];
   if (L < 0 || L > max_ctx) { L = L < 0 ? 0 : max_ctx; if (tid == 0) atomicOr(status, ST_BAD_CTXLEN); }
   const int half = D >> 1;
   if (tid < half) {
@@ -98,21 +150,6 @@ __global__ __launch_bounds__(256) void prep_kernel(const int32_t* __restrict__ t
     }
     rope_cs[(size_t)t * D + tid] = cv;
     rope_cs[(size_t)t * D + half + tid] = sv;
-  }
-  // RMSNorm(x[t]) * gain, rounded to the storage type
-  float ss = 0.0f;
-  for (int c = tid; c < d; c += 256) {
-    const float v = load_elem<ST>(x, (size_t)t * d + c);
-    ss += v * v;
-  }
-  ss = wave_sum(ss);
-  if ((tid & 63) == 0) s_red[tid >> 6] = ss;
-  __syncthreads();
-  const float ms = (s_red[0] + s_red[1] + s_red[2] + s_red[3]) / (float)d;
-  const float rinv = 1.0f / sqrtf(ms + eps);
-  for (int c = tid; c < d; c += 256) {
-    const float v = load_elem<ST>(x, (size_t)t * d + c);
-    store_elem<ST>(x_norm, (size_t)t * d + c, v * rinv * load_elem<ST>(gain, c));
   }
 }
 
@@ -218,7 +255,7 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(
 constexpr int kMfmaKeys = 128;
 
 template <int D>
-__global__ __launch_bounds__(256) void attn_partial_mfma_kernel(
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void attn_partial_mfma_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ kc, const uint16_t* __restrict__ vc,
     long long seq_stride, long long head_stride, const int32_t* __restrict__ ctx_len, int max_ctx,
     const int32_t* __restrict__ tree_off, const uint16_t* __restrict__ k_new, const uint16_t* __restrict__ v_new,
@@ -244,7 +281,6 @@ __global__ __launch_bounds__(256) void attn_partial_mfma_kernel(
   const int key0 = tree_part ? 0 : split * kMfmaKeys;
   int nkeys = (tree_part ? n : L) - key0;
   nkeys = nkeys > kMfmaKeys ? kMfmaKeys : nkeys;
-  if (nkeys <= 0) return;  // split lies beyond this sequence's context; the merge skips it
   const int G = Hq / Hkv;
   const int R = n * G;
   const int ntiles = (R + 15) >> 4;
@@ -253,6 +289,16 @@ __global__ __launch_bounds__(256) void attn_partial_mfma_kernel(
   int t_end = t_begin + per_rb;
   t_end = t_end > ntiles ? ntiles : t_end;
   if (t_begin >= t_end) return;
+  if (nkeys <= 0) {
+    // split lies beyond this sequence's context: mark its rows empty for the merge
+    for (int r = t_begin * 16 + tid; r < t_end * 16 && r < R; r += 256) {
+      const int i = r / G, hh = r - i * G;
+      const size_t prow = ((size_t)split * T + lo + i) * Hq + g * G + hh;
+      part_ml[prow * 2] = -INFINITY;
+      part_ml[prow * 2 + 1] = 0.0f;
+    }
+    return;
+  }
 
   // ---- stage K (row-major) and V (transposed, two keys per dword)
   const uint16_t* kbase = tree_part ? k_new + ((size_t)lo * Hkv + g) * D : kc + (size_t)b * seq_stride + (size_t)g * head_stride + (size_t)key0 * D;
@@ -349,7 +395,7 @@ __global__ __launch_bounds__(256) void attn_partial_mfma_kernel(
       const int i2 = rc / G, h2 = rc - i2 * G;
       orow[j] = (((size_t)split * T + lo + i2) * Hq + g * G + h2) * D;
     }
-#pragma unroll
+#pragma unroll 2
     for (int dt = 0; dt < D / 16; ++dt) {
       f32x4 acc = {0, 0, 0, 0};
 #pragma unroll
@@ -367,39 +413,38 @@ __global__ __launch_bounds__(256) void attn_partial_mfma_kernel(
   }
 }
 
-// merge of the per-split partial softmaxes: grid (T*Hq), block D threads
+// merge of the per-split partial softmaxes: grid (T*Hq), block D threads. Empty splits carry
+// max = -inf.
 template <typename ST>
 __global__ void attn_merge_kernel(const float* __restrict__ part_o, const float* __restrict__ part_ml, int nsplits,
-                                  int T, int Hq, int D, const int32_t* __restrict__ seq_of,
-                                  const int32_t* __restrict__ ctx_len, int max_ctx, int keys_per_split, int ctx_splits,
-                                  void* __restrict__ out, void* __restrict__ aux_out) {
+                                  int T, int Hq, int D, void* __restrict__ out, void* __restrict__ aux_out) {
   __shared__ float s_sc[2][192];  // per-split weights, one copy per wavefront
   const int row = blockIdx.x;     // t * Hq + h
   const int c = threadIdx.x, lane = c & 63, w = c >> 6;
-  const int t = row / Hq;
-  int L = ctx_len[seq_of[t]];
-  L = L < 0 ? 0 : (L > max_ctx ? max_ctx : L);
-  const int used_ctx = (L + keys_per_split - 1) / keys_per_split;  // context splits past this are skipped
   // each lane fetches the (max, sum) of different splits
   float M = -INFINITY;
-  for (int s0 = 0; s0 < nsplits; s0 += 64) {
-    const int s = s0 + lane;
+  float lpart[3] = {0.0f, 0.0f, 0.0f};
+#pragma unroll
+  for (int i = 0; i < 3; ++i) {
+    const int s = i * 64 + lane;
     float ms = -INFINITY;
-    if (s < nsplits && !(s >= used_ctx && s < ctx_splits)) ms = part_ml[((size_t)s * T * Hq + row) * 2];
-    s_sc[w][s < 192 ? s : 191] = ms;
+    if (s < nsplits) {
+      const float2 ml = *reinterpret_cast<const float2*>(part_ml + ((size_t)s * T * Hq + row) * 2);
+      ms = ml.x;
+      lpart[i] = ml.y;
+    }
+    if (s < 192) s_sc[w][s] = ms;
     M = fmaxf(M, ms);
   }
   M = wave_max(M);
   float l = 0.0f;
-  for (int s0 = 0; s0 < nsplits; s0 += 64) {
-    const int s = s0 + lane;
-    float sc = 0.0f;
+#pragma unroll
+  for (int i = 0; i < 3; ++i) {
+    const int s = i * 64 + lane;
     if (s < nsplits) {
       const float ms = s_sc[w][s];
-      if (ms != -INFINITY) {
-        sc = __expf(ms - M);
-        l += part_ml[((size_t)s * T * Hq + row) * 2 + 1] * sc;
-      }
+      const float sc = ms == -INFINITY ? 0.0f : __expf(ms - M);
+      l += lpart[i] * sc;
       s_sc[w][s] = sc;
     }
   }
@@ -420,89 +465,119 @@ __global__ void attn_merge_kernel(const float* __restrict__ part_o, const float*
 // softmax over the selected scores. One workgroup (8 wavefronts) per tile of 16 tokens.
 // W_g is in the packed streaming layout (16-expert strips).
 // ------------------------------------------------------------------------------------
-constexpr int kRouterThreads = 512;
+constexpr int kRouterWaves = 16;
+constexpr int kRouterThreads = kRouterWaves * 64;
 
+// LDS: token operand blocks [nkb][64] x 16 B, then partial scores [KS][16][E] floats, where
+// KS = ways the contraction is split so that all 16 wavefronts have an (expert strip, slice).
 template <typename ST>
 __global__ __launch_bounds__(kRouterThreads) void router_kernel(
     const void* __restrict__ h, const void* __restrict__ gain, const u32x4* __restrict__ wg_packed, int T, int d, int E,
-    int k, float eps, void* __restrict__ h_norm, float* __restrict__ logits, int32_t* __restrict__ topk_idx,
+    int k, int ksplit, float eps, void* __restrict__ h_norm, float* __restrict__ logits, int32_t* __restrict__ topk_idx,
     float* __restrict__ topk_w, void* __restrict__ aux_hn, float* __restrict__ aux_logits,
     int32_t* __restrict__ aux_idx, float* __restrict__ aux_w) {
   constexpr int EB = ST::kBytes;
-  constexpr int CE = 16 / EB;  // elements per 16-byte chunk
+  constexpr int CE = 16 / EB;   // elements per 16-byte chunk
+  constexpr int MAXC = 8;       // 16-byte chunks a lane keeps of its token row (d <= 64*CE*MAXC)
   extern __shared__ __attribute__((aligned(16))) unsigned char s_raw[];
   const int nkb = d * EB / 64;
   u32x4* s_b = reinterpret_cast<u32x4*>(s_raw);                       // [nkb][64] token operand blocks
-  float* s_l = reinterpret_cast<float*>(s_raw + (size_t)nkb * 1024);  // [16][E]
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  float* s_l = reinterpret_cast<float*>(s_raw + (size_t)nkb * 1024);  // [ksplit][16][E]
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int tok0 = blockIdx.x * 16;
-  // ---- normalise two tokens per wavefront and lay them out as MFMA operand blocks
-  for (int n = w * 2; n < w * 2 + 2; ++n) {
-    const int t = tok0 + n;
+  // ---- one token per wavefront: the row stays in registers between the two passes
+  {
+    const int n = w, t = tok0 + n;
     const bool live = t < T;
+    u32x4 raw[MAXC];
     float ss = 0.0f;
-    if (live)
-      for (int c = lane * 4; c < d; c += 256) {
-        const f32x4 v = load4<ST>(h, (size_t)t * d + c);
-        ss += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
+#pragma unroll
+    for (int i = 0; i < MAXC; ++i) {
+      const int c = (lane + 64 * i) * CE;
+      raw[i] = u32x4{0, 0, 0, 0};
+      if (live && c < d) raw[i] = *reinterpret_cast<const u32x4*>((const char*)h + ((size_t)t * d + c) * EB);
+    }
+#pragma unroll
+    for (int i = 0; i < MAXC; ++i) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (EB == 2) {
+          const float a = __uint_as_float(raw[i][u] << 16), b = __uint_as_float(raw[i][u] & 0xFFFF0000u);
+          ss += a * a + b * b;
+        } else {
+          const float a = __uint_as_float(raw[i][u]);
+          ss += a * a;
+        }
       }
+    }
     ss = wave_sum(ss);
     const float rinv = 1.0f / sqrtf(ss / (float)d + eps);
-    for (int c = lane * CE; c < d; c += 64 * CE) {  // one 16-byte chunk = one operand slot
-      u32x4 packed = {0, 0, 0, 0};
-      if (live) {
-        float v[CE];
 #pragma unroll
-        for (int i = 0; i < CE; i += 4) {
-          const f32x4 hv = load4<ST>(h, (size_t)t * d + c + i), gv = load4<ST>(gain, c + i);
+    for (int i = 0; i < MAXC; ++i) {
+      const int c = (lane + 64 * i) * CE;
+      if (c < d) {
+        u32x4 packed = {0, 0, 0, 0};
+        if (live) {
+          const u32x4 graw = *reinterpret_cast<const u32x4*>((const char*)gain + (size_t)c * EB);
 #pragma unroll
-          for (int u = 0; u < 4; ++u) v[i + u] = hv[u] * rinv * gv[u];
+          for (int u = 0; u < 4; ++u) {
+            if (EB == 2) {
+              const float a = __uint_as_float(raw[i][u] << 16) * rinv * __uint_as_float(graw[u] << 16);
+              const float b = __uint_as_float(raw[i][u] & 0xFFFF0000u) * rinv * __uint_as_float(graw[u] & 0xFFFF0000u);
+              packed[u] = (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
+            } else {
+              packed[u] = __float_as_uint(__uint_as_float(raw[i][u]) * rinv * __uint_as_float(graw[u]));
+            }
+          }
+          *reinterpret_cast<u32x4*>((char*)h_norm + ((size_t)t * d + c) * EB) = packed;
+          if (aux_hn) *reinterpret_cast<u32x4*>((char*)aux_hn + ((size_t)t * d + c) * EB) = packed;
         }
-        if (EB == 2) {
-#pragma unroll
-          for (int i = 0; i < 4; ++i) packed[i] = (uint32_t)f32_to_bf16(v[2 * i]) | ((uint32_t)f32_to_bf16(v[2 * i + 1]) << 16);
-        } else {
-#pragma unroll
-          for (int i = 0; i < 4; ++i) packed[i] = __float_as_uint(v[i]);
-        }
-        *reinterpret_cast<u32x4*>((char*)h_norm + ((size_t)t * d + c) * EB) = packed;
-        if (aux_hn) *reinterpret_cast<u32x4*>((char*)aux_hn + ((size_t)t * d + c) * EB) = packed;
+        const int byte = c * EB;  // position in the row -> operand block, quarter, column n
+        s_b[(byte >> 6) * 64 + ((byte >> 4) & 3) * 16 + n] = packed;
       }
-      const int byte = c * EB;  // position in the row
-      s_b[(byte >> 6) * 64 + ((byte >> 4) & 3) * 16 + n] = packed;
     }
   }
   __syncthreads();
-  // ---- scores: expert strips round-robin over the wavefronts
+  // ---- scores: (expert strip, contraction slice) items round-robin over the wavefronts
   const int nstrips = E >> 4;
-  for (int strip = w; strip < nstrips; strip += kRouterThreads / 64) {
+  const int per = (nkb + ksplit - 1) / ksplit;  // blocks per slice
+  for (int item = w; item < nstrips * ksplit; item += kRouterWaves) {
+    const int strip = item / ksplit, ks = item - strip * ksplit;
+    const int kb_lo = ks * per;
+    int kb_hi = kb_lo + per;
+    kb_hi = kb_hi > nkb ? nkb : kb_hi;
     const u32x4* wp = wg_packed + (size_t)strip * nkb * 64 + lane;
     f32x4 acc = {0, 0, 0, 0};
-    for (int kb0 = 0; kb0 < nkb; kb0 += 8) {
-      u32x4 a[8];
+    for (int kb0 = kb_lo; kb0 < kb_hi; kb0 += 16) {
+      u32x4 a[16];
 #pragma unroll
-      for (int j = 0; j < 8; ++j)
-        if (kb0 + j < nkb) a[j] = wp[(size_t)(kb0 + j) * 64];
+      for (int j = 0; j < 16; ++j)
+        if (kb0 + j < kb_hi) a[j] = wp[(size_t)(kb0 + j) * 64];
 #pragma unroll
-      for (int j = 0; j < 8; ++j)
-        if (kb0 + j < nkb) acc = mfma_block<ST>(a[j], s_b[(kb0 + j) * 64 + lane], acc);
+      for (int j = 0; j < 16; ++j)
+        if (kb0 + j < kb_hi) acc = mfma_block<ST>(a[j], s_b[(kb0 + j) * 64 + lane], acc);
     }
-    const int n = lane & 15, t = tok0 + n;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int e = strip * 16 + (lane >> 4) * 4 + j;
-      s_l[n * E + e] = acc[j];
-    }
+    const int n = lane & 15;
+    *reinterpret_cast<f32x4*>(s_l + ((size_t)ks * 16 + n) * E + strip * 16 + (lane >> 4) * 4) = acc;
+  }
+  __syncthreads();
+  // ---- sum the slices in a fixed order, publish the scores
+  for (int idx = tid; idx < 16 * E; idx += kRouterThreads) {
+    float v = s_l[idx];
+    for (int ks = 1; ks < ksplit; ++ks) v += s_l[(size_t)ks * 16 * E + idx];
+    s_l[idx] = v;
+    const int n = idx / E, t = tok0 + n;
     if (t < T) {
-      *reinterpret_cast<f32x4*>(logits + (size_t)t * E + strip * 16 + (lane >> 4) * 4) = acc;
-      if (aux_logits) *reinterpret_cast<f32x4*>(aux_logits + (size_t)t * E + strip * 16 + (lane >> 4) * 4) = acc;
+      logits[(size_t)t * E + (idx - n * E)] = v;
+      if (aux_logits) aux_logits[(size_t)t * E + (idx - n * E)] = v;
     }
   }
   __syncthreads();
-  // ---- top-k and weights, two tokens per wavefront
-  for (int n = w * 2; n < w * 2 + 2; ++n) {
-    const int t = tok0 + n;
-    if (t >= T) continue;
+  // ---- top-k and weights, one token per wavefront
+  {
+    const int n = w, t = tok0 + n;
+    if (t >= T) return;
     float* sl = s_l + n * E;
     float sel_v = 0.0f, first = 0.0f, denom = 0.0f;
     int sel_i = 0;
@@ -539,17 +614,28 @@ __global__ __launch_bounds__(kRouterThreads) void router_kernel(
 // un-permute + weighted combine + residual (+ shared experts), fixed slot order
 // ------------------------------------------------------------------------------------
 template <typename ST>
-__global__ __launch_bounds__(256) void combine_kernel(const void* __restrict__ h, const float* __restrict__ y,
+__global__ __launch_bounds__(512) void combine_kernel(const void* __restrict__ h, const float* __restrict__ y,
                                                       const float* __restrict__ w, const int32_t* __restrict__ inv,
                                                       int k, int d, const float* __restrict__ y_sh, int n_shared, int T,
                                                       void* __restrict__ out) {
+  __shared__ float s_w[64];
+  __shared__ int s_inv[64];
   const int t = blockIdx.x;
-  for (int c = threadIdx.x * 4; c < d; c += 256 * 4) {
+  if (threadIdx.x < k) {
+    s_w[threadIdx.x] = w[(size_t)t * k + threadIdx.x];
+    s_inv[threadIdx.x] = inv[(size_t)t * k + threadIdx.x];
+  }
+  __syncthreads();
+  for (int c = threadIdx.x * 4; c < d; c += 512 * 4) {
     f32x4 acc = load4<ST>(h, (size_t)t * d + c);
-    for (int j = 0; j < k; ++j) {
-      const float wj = w[(size_t)t * k + j];
-      const f32x4 yv = *reinterpret_cast<const f32x4*>(y + (size_t)inv[(size_t)t * k + j] * d + c);
-      acc += wj * yv;
+    for (int j0 = 0; j0 < k; j0 += 8) {
+      f32x4 yv[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        if (j0 + j < k) yv[j] = *reinterpret_cast<const f32x4*>(y + (size_t)s_inv[j0 + j] * d + c);
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        if (j0 + j < k) acc += s_w[j0 + j] * yv[j];  // slot order j = 0..k-1
     }
     for (int s = 0; s < n_shared; ++s) acc += *reinterpret_cast<const f32x4*>(y_sh + ((size_t)s * T + t) * d + c);
     store4<ST>(out, (size_t)t * d + c, acc);
@@ -558,11 +644,23 @@ __global__ __launch_bounds__(256) void combine_kernel(const void* __restrict__ h
 
 template <typename ST, int NT, int EPI>
 int launch_gemm_nt(const GemmArgs& a, int grid, hipStream_t s) {
-  const int need = ((a.nkb > 64 ? 64 : a.nkb) + kGemmWaves - 1) / kGemmWaves;
-  if (need <= 4)
-    hipLaunchKernelGGL((gemm_stream_kernel<ST, NT, 4, 4, EPI>), dim3(grid), dim3(kGemmThreads), 0, s, a);
-  else
-    hipLaunchKernelGGL((gemm_stream_kernel<ST, NT, 8, 2, EPI>), dim3(grid), dim3(kGemmThreads), 0, s, a);
+#define EVICT_GEMM_LAUNCH(KBW_, PF_, EXACT_) \
+  hipLaunchKernelGGL((gemm_stream_kernel<ST, NT, KBW_, PF_, EPI, EXACT_>), dim3(grid), dim3(kGemmThreads), 0, s, a)
+  const int nkb = a.nkb;
+  const int need = ((nkb > 64 ? 64 : nkb) + kGemmWaves - 1) / kGemmWaves;
+  const bool bf16 = ST::kBytes == 2;
+  if (bf16 && nkb % 64 == 0) {
+    // the next step's 8 loads are issued right after the MFMAs, so they fly during the
+    // partial-tile exchange; one buffer keeps the kernel under 128 VGPRs (2 workgroups per CU)
+    EVICT_GEMM_LAUNCH(8, 1, true);
+  } else if (bf16 && nkb == 24) {
+    EVICT_GEMM_LAUNCH(3, 4, true);
+  } else if (need <= 4) {
+    EVICT_GEMM_LAUNCH(4, 4, false);
+  } else {
+    EVICT_GEMM_LAUNCH(8, 2, false);
+  }
+#undef EVICT_GEMM_LAUNCH
   return launch_status("gemm_stream_kernel");
 }
 
@@ -616,9 +714,13 @@ int launch_prep(const evict_ctx* c, const int32_t* tree_off, const int32_t* pare
 
 size_t attn_partial_lds_bytes(int D) { return sizeof(float) * (size_t)(2 * kAttnKeys * (D + 1) + 4 * D + 4 * 64); }
 size_t attn_mfma_lds_bytes(int D) { return 2 * (size_t)(kMfmaKeys * (D + 8) + D * (kMfmaKeys + 4)); }
+int router_ksplit(const evict_model_desc& m) {
+  int ks = kRouterWaves / (m.E / 16);
+  return ks < 1 ? 1 : ks;
+}
 size_t router_lds_bytes(const evict_model_desc& m) {
   const size_t eb = m.dtype == EVICT_BF16 ? 2 : 4;
-  return (size_t)m.d * eb * 16 + (size_t)16 * m.E * sizeof(float);
+  return (size_t)m.d * eb * 16 + (size_t)router_ksplit(m) * 16 * m.E * sizeof(float);
 }
 
 int kernels_setup(const evict_model_desc& m) {
@@ -629,6 +731,7 @@ int kernels_setup(const evict_model_desc& m) {
   EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)attn_partial_mfma_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_mfma_lds_bytes(64)));
   const size_t rl = router_lds_bytes(m);
   EVICT_REQUIRE(rl <= 160 * 1024, EVICT_E_UNSUPPORTED, "router needs %zu bytes of LDS (limit 160 KiB): d or E too large", rl);
+  EVICT_REQUIRE(m.d <= 64 * 8 * (m.dtype == EVICT_BF16 ? 8 : 4), EVICT_E_UNSUPPORTED, "router keeps a token row in registers: d=%d too large", m.d);
   if (m.dtype == EVICT_BF16)
     EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)router_kernel<BF16>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)rl));
   else
@@ -673,10 +776,10 @@ int launch_attention(const evict_ctx* c, const void* kc, const void* vc, long lo
   if (rc) return rc;
   if (m.dtype == EVICT_BF16)
     hipLaunchKernelGGL(attn_merge_kernel<BF16>, dim3(T * m.Hq), dim3(m.D), 0, s, c->part_o, c->part_ml, nsplits, T, m.Hq,
-                       m.D, c->seq_of, ctx_len, max_ctx_host, keys, ctx_splits, c->attn_o, aux_out);
+                       m.D, c->attn_o, aux_out);
   else
     hipLaunchKernelGGL(attn_merge_kernel<F32>, dim3(T * m.Hq), dim3(m.D), 0, s, c->part_o, c->part_ml, nsplits, T, m.Hq,
-                       m.D, c->seq_of, ctx_len, max_ctx_host, keys, ctx_splits, c->attn_o, aux_out);
+                       m.D, c->attn_o, aux_out);
   return launch_status("attn_merge_kernel");
 }
 
@@ -692,20 +795,20 @@ int launch_router(const evict_ctx* c, const void* gain, const void* wg, int T, c
   const int grid = (T + 15) / 16;
   if (m.dtype == EVICT_BF16)
     hipLaunchKernelGGL(router_kernel<BF16>, dim3(grid), dim3(kRouterThreads), lds, s, c->h, gain, (const u32x4*)wg, T, m.d,
-                       m.E, m.k, m.rms_eps, c->h_norm, c->logits, c->topk_idx, c->topk_w, a_hn, a_lg, a_ix, a_w);
+                       m.E, m.k, router_ksplit(m), m.rms_eps, c->h_norm, c->logits, c->topk_idx, c->topk_w, a_hn, a_lg, a_ix, a_w);
   else
     hipLaunchKernelGGL(router_kernel<F32>, dim3(grid), dim3(kRouterThreads), lds, s, c->h, gain, (const u32x4*)wg, T, m.d,
-                       m.E, m.k, m.rms_eps, c->h_norm, c->logits, c->topk_idx, c->topk_w, a_hn, a_lg, a_ix, a_w);
+                       m.E, m.k, router_ksplit(m), m.rms_eps, c->h_norm, c->logits, c->topk_idx, c->topk_w, a_hn, a_lg, a_ix, a_w);
   return launch_status("router_kernel");
 }
 
 int launch_combine(const evict_ctx* c, int T, void* out, hipStream_t s) {
   const evict_model_desc& m = c->m;
   if (m.dtype == EVICT_BF16)
-    hipLaunchKernelGGL(combine_kernel<BF16>, dim3(T), dim3(256), 0, s, c->h, c->y, c->topk_w, c->inv, m.k, m.d, c->y_sh,
+    hipLaunchKernelGGL(combine_kernel<BF16>, dim3(T), dim3(512), 0, s, c->h, c->y, c->topk_w, c->inv, m.k, m.d, c->y_sh,
                        m.n_shared, T, out);
   else
-    hipLaunchKernelGGL(combine_kernel<F32>, dim3(T), dim3(256), 0, s, c->h, c->y, c->topk_w, c->inv, m.k, m.d, c->y_sh,
+    hipLaunchKernelGGL(combine_kernel<F32>, dim3(T), dim3(512), 0, s, c->h, c->y, c->topk_w, c->inv, m.k, m.d, c->y_sh,
                        m.n_shared, T, out);
   return launch_status("combine_kernel");
 }

@@ -94,6 +94,8 @@ __global__ __launch_bounds__(kSelThreads) void select_prefix_kernel(
   __shared__ int s_par[kMaxSel];
   __shared__ float s_score[kMaxSel];
   __shared__ float s_sorted[kMaxSel];
+  __shared__ float s_prob[kMaxSel];
+  __shared__ float s_cost[kMaxSel];
   __shared__ int s_rank[kMaxSel];
   __shared__ int s_aux[kMaxSel];  // depth, later new index
   __shared__ int s_wave[16];
@@ -112,6 +114,8 @@ __global__ __launch_bounds__(kSelThreads) void select_prefix_kernel(
     if (i == 0) p = -1;
     else if (p < 0 || p >= i) p = 0;  // invalid ids are clamped (the host check rejects them)
     s_par[i] = p;
+    s_prob[i] = prob[lo + i];                      // all global reads issued together, up front
+    s_cost[i] = i < kmax ? cost[i + 1] : 1.0f;     // s_cost[i] = C(i + 1)
   }
   __syncthreads();
   // depth of every node (walk to the root; parent ids strictly decrease)
@@ -129,7 +133,7 @@ __global__ __launch_bounds__(kSelThreads) void select_prefix_kernel(
   // Score(v) = Score(parent(v)) * q(v): one rounded fp32 multiply per node, level by level
   for (int lvl = 1; lvl <= maxdep; ++lvl) {
     for (int i = tid; i < n; i += kSelThreads)
-      if (s_aux[i] == lvl) s_score[i] = __fmul_rn(s_score[s_par[i]], prob[lo + i]);
+      if (s_aux[i] == lvl) s_score[i] = __fmul_rn(s_score[s_par[i]], s_prob[i]);
     __syncthreads();
   }
   // rank by (score descending, index ascending)
@@ -169,7 +173,7 @@ __global__ __launch_bounds__(kSelThreads) void select_prefix_kernel(
     const float S = s_sorted[i];
     if (psum_out) psum_out[lo + i] = S;
     if (i < kk) {
-      const float u = __fdiv_rn(S, cost[i + 1]);
+      const float u = __fdiv_rn(S, s_cost[i]);
       if (u > bv || (u == bv && i < bi)) { bv = u; bi = i; }
     }
   }
@@ -233,23 +237,33 @@ __global__ __launch_bounds__(kSelThreads) void compact_batch_kernel(
   if (tid == 0) new_tree_off[B] = out;
 }
 
-// One wavefront per tree.
+// One wavefront per tree; the tree is staged in LDS so the walk has no global-memory latency.
 __global__ __launch_bounds__(64) void accept_path_kernel(
     const int32_t* __restrict__ tree_off, const int32_t* __restrict__ parent, const int32_t* __restrict__ tok,
     const int32_t* __restrict__ next, int32_t* __restrict__ path, int path_stride, int32_t* __restrict__ path_len,
     int32_t* __restrict__ bonus) {
+  __shared__ int s_par[kMaxSel];
+  __shared__ int s_tok[kMaxSel];
+  __shared__ int s_next[kMaxSel];
   const int b = blockIdx.x, lane = threadIdx.x;
   const int lo = tree_off[b];
-  const int n = tree_off[b + 1] - lo;
+  int n = tree_off[b + 1] - lo;
+  n = n < 1 ? 1 : (n > kMaxSel ? kMaxSel : n);
+  for (int i = lane; i < n; i += 64) {
+    s_par[i] = parent[lo + i];
+    s_tok[i] = tok[lo + i];
+    s_next[i] = next[lo + i];
+  }
   int32_t* my = path + (size_t)b * path_stride;
   for (int i = lane; i < path_stride; i += 64) my[i] = i == 0 ? 0 : -1;
+  __syncthreads();
   int cur = 0, len = 1;
   while (true) {
-    const int want = next[lo + cur];
+    const int want = s_next[cur];
     int found = -1;
     for (int base = cur + 1; base < n; base += 64) {
       const int c = base + lane;
-      const bool m = c < n && parent[lo + c] == cur && tok[lo + c] == want;
+      const bool m = c < n && s_par[c] == cur && s_tok[c] == want;
       const unsigned long long mask = __ballot(m);
       if (mask) { found = base + __ffsll((long long)mask) - 1; break; }
     }
@@ -258,7 +272,7 @@ __global__ __launch_bounds__(64) void accept_path_kernel(
     if (lane == 0 && len < path_stride) my[len] = cur;
     ++len;
   }
-  if (lane == 0) { path_len[b] = len; bonus[b] = next[lo + cur]; }
+  if (lane == 0) { path_len[b] = len; bonus[b] = s_next[cur]; }
 }
 
 constexpr int kUnionThreads = 256;
@@ -271,7 +285,8 @@ constexpr int kUnionThreads = 256;
 __global__ __launch_bounds__(kUnionThreads) void expert_union_kernel(
     const int32_t* __restrict__ topk_idx, int T, int k, int E, int use_masks, int32_t* __restrict__ union_ids,
     int32_t* __restrict__ union_count, int32_t* __restrict__ hist, int32_t* __restrict__ offsets,
-    int32_t* __restrict__ perm, int32_t* __restrict__ inv, int32_t* __restrict__ status) {
+    int32_t* __restrict__ perm, int32_t* __restrict__ inv, int32_t* __restrict__ status, int4* __restrict__ work,
+    int32_t* __restrict__ tok_of_pos) {
   extern __shared__ __attribute__((aligned(8))) int s_mem[];
   const int P = T * k;
   const int words = (T + 63) >> 6;
@@ -321,7 +336,10 @@ __global__ __launch_bounds__(kUnionThreads) void expert_union_kernel(
       s_off[e] = base_h;
       offsets[e] = base_h;
       hist[e] = h[j];
-      if (h[j] > 0) union_ids[base_f] = e;
+      if (h[j] > 0) {
+        union_ids[base_f] = e;
+        if (work) work[base_f] = make_int4(e, base_h, h[j], 0);
+      }
     }
     base_h += h[j];
     base_f += h[j] > 0 ? 1 : 0;
@@ -339,6 +357,7 @@ __global__ __launch_bounds__(kUnionThreads) void expert_union_kernel(
       pos += __popcll(m[t >> 6] & ((1ull << (t & 63)) - 1ull));
       perm[pos] = p;
       inv[p] = pos;
+      if (tok_of_pos) tok_of_pos[pos] = t;
     }
   } else {
     for (int e = tid; e < E; e += kUnionThreads) {
@@ -348,6 +367,7 @@ __global__ __launch_bounds__(kUnionThreads) void expert_union_kernel(
         if (s_idx[p] == e) {
           perm[pos] = p;
           inv[p] = pos;
+          if (tok_of_pos) tok_of_pos[pos] = p / k;
           ++pos;
         }
       }
@@ -367,6 +387,27 @@ __global__ void gather_rows_kernel(const uint32_t* __restrict__ src, uint32_t* _
 }
 
 }  // namespace
+
+int launch_union(int32_t* status, const int32_t* topk_idx, int T, int k, int E, int32_t* union_ids, int32_t* union_count,
+                 int32_t* hist, int32_t* offsets, int32_t* perm, int32_t* inv, int4* work, int32_t* tok_of_pos,
+                 hipStream_t stream) {
+  EVICT_REQUIRE(topk_idx && union_ids && union_count && hist && offsets && perm && inv, EVICT_E_INVALID,
+                "evict_expert_union: null pointer argument");
+  EVICT_REQUIRE(T >= 1 && k >= 1 && E >= 1, EVICT_E_INVALID, "evict_expert_union: T, k, E must be >= 1");
+  EVICT_REQUIRE(k <= E, EVICT_E_INVALID, "evict_expert_union: k=%d exceeds E=%d", k, E);
+  EVICT_REQUIRE((int64_t)T * k <= 8192 && E <= 1024, EVICT_E_UNSUPPORTED,
+                "evict_expert_union: T*k=%lld (limit 8192), E=%d (limit 1024)", (long long)T * k, E);
+  const int P = T * k;
+  const size_t words = (size_t)(T + 63) / 64;
+  size_t lds = sizeof(int) * (size_t)((P + 2 * E + 2) & ~1);
+  const size_t mask_bytes = 8 * (size_t)E * words;
+  const int use_masks = lds + mask_bytes <= 60 * 1024 ? 1 : 0;
+  if (use_masks) lds += mask_bytes;
+  hipLaunchKernelGGL(expert_union_kernel, dim3(1), dim3(kUnionThreads), lds, stream, topk_idx, T, k, E, use_masks,
+                     union_ids, union_count, hist, offsets, perm, inv, status, work, tok_of_pos);
+  return launch_status("expert_union_kernel");
+}
+
 }  // namespace evict
 
 using namespace evict;
@@ -432,21 +473,8 @@ int evict_accept_path(evict_ctx*, const int32_t* tree_off, const int32_t* parent
 int evict_expert_union(evict_ctx* ctx, const int32_t* topk_idx, int T, int k, int E, int32_t* union_ids,
                        int32_t* union_count, int32_t* hist, int32_t* offsets, int32_t* perm, int32_t* inv,
                        void* stream) {
-  EVICT_REQUIRE(topk_idx && union_ids && union_count && hist && offsets && perm && inv, EVICT_E_INVALID,
-                "evict_expert_union: null pointer argument");
-  EVICT_REQUIRE(T >= 1 && k >= 1 && E >= 1, EVICT_E_INVALID, "evict_expert_union: T, k, E must be >= 1");
-  EVICT_REQUIRE(k <= E, EVICT_E_INVALID, "evict_expert_union: k=%d exceeds E=%d", k, E);
-  EVICT_REQUIRE((int64_t)T * k <= 8192 && E <= 1024, EVICT_E_UNSUPPORTED,
-                "evict_expert_union: T*k=%lld (limit 8192), E=%d (limit 1024)", (long long)T * k, E);
-  const int P = T * k;
-  const size_t words = (size_t)(T + 63) / 64;
-  size_t lds = sizeof(int) * (size_t)((P + 2 * E + 2) & ~1);
-  const size_t mask_bytes = 8 * (size_t)E * words;
-  const int use_masks = lds + mask_bytes <= 60 * 1024 ? 1 : 0;
-  if (use_masks) lds += mask_bytes;
-  hipLaunchKernelGGL(expert_union_kernel, dim3(1), dim3(kUnionThreads), lds, (hipStream_t)stream, topk_idx, T, k, E,
-                     use_masks, union_ids, union_count, hist, offsets, perm, inv, ctx ? ctx->status : nullptr);
-  return launch_status("expert_union_kernel");
+  return evict::launch_union(ctx ? ctx->status : nullptr, topk_idx, T, k, E, union_ids, union_count, hist, offsets, perm,
+                             inv, nullptr, nullptr, (hipStream_t)stream);
 }
 
 int evict_gather_rows(const void* src, void* dst, int row_bytes, const int32_t* tree_off, const int32_t* new_tree_off,
