@@ -40,6 +40,7 @@ def parse():
     ap.add_argument("--copies", type=int, default=4, help="weight copies rotated between steps")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     ap.add_argument("--seed", type=int, default=1000)
+    ap.add_argument("--tune", action="append", default=[], help="key=value launch-shape knob (evict_tune)")
     return ap.parse_args()
 
 
@@ -64,6 +65,9 @@ def main():
     case = synth.make_case("qwen3", n=N, L=L, seed=args.seed, sigma=args.sigma)
     layer = harness.DeviceLayer(cfg, case["W"], max_tokens=N, max_batch=1, max_ctx=L)
     dc = harness.DeviceCase(case, with_aux=True)
+    for kv in args.tune:
+        key, val = kv.split("=")
+        ev.evict_tune(layer.ctx, key, int(val))
 
     # weight copies (same values, distinct addresses) so that no step finds its weights in cache
     names = ("wqkv", "wo", "wg", "w_gateup", "w_down")

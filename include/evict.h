@@ -180,6 +180,22 @@ int evict_validate_trees_host(const int32_t* tree_off, const int32_t* parent, in
  * Synchronises the stream. */
 int evict_device_status(evict_ctx* ctx, int32_t* status_host, void* stream);
 
+/* Launch-shape tuning knobs of a context (defaults are chosen in evict_create):
+ *   "moe_grid"        workgroups of the grouped expert GEMMs (chunks are dealt round-robin)
+ *   "moe_prefetch"    1 or 2 weight-load stages in flight per wavefront in the gate/up GEMM
+ *   "moe_chunk_gateup", "moe_chunk_down"  units (16-row strips; strip pairs for gate/up) a
+ *                     workgroup takes from the device-side work list at a time
+ *   "attn_row_blocks" workgroups per (KV split, KV head) in the bf16 attention kernel, 0 = auto
+ * Returns EVICT_E_INVALID for an unknown key or a value out of range. */
+int evict_tune(evict_ctx* ctx, const char* key, int value);
+
+/* Measurement helpers: a plain streaming read (every byte of src read once with 16-byte
+ * loads, a checksum written to sink [dev] uint32[4]) and a plain copy, used to measure the
+ * achievable HBM read bandwidth of the device and to calibrate hardware byte counters against
+ * a kernel of known traffic. bytes must be a multiple of 16; pointers [dev], 16-byte aligned. */
+int evict_probe_read(const void* src, size_t bytes, void* sink, void* stream);
+int evict_probe_copy(const void* src, void* dst, size_t bytes, void* stream);
+
 /* Per-stage timing of evict_verify_layer with HIP events recorded on the call's stream
  * between the stages (for measurement; adds event records to the stream). Stages, in order:
  * 0 tree prep + RMSNorm, 1 QKV projection + rotation, 2 tree attention (partials + merge),

@@ -15,7 +15,7 @@ __all__ = [
     "evict_version", "evict_last_error", "evict_create", "evict_destroy", "evict_packed_bytes", "evict_pack_dense",
     "evict_pack_qkv", "evict_pack_experts", "evict_verify_layer", "evict_expert_union", "evict_accept_path",
     "evict_select_prefix", "evict_gather_rows", "evict_validate_trees_host", "evict_device_status",
-    "evict_stage_timing", "evict_stage_times", "STAGES", "EXPORTS",
+    "evict_stage_timing", "evict_stage_times", "evict_probe_read", "evict_probe_copy", "evict_tune", "STAGES", "EXPORTS",
 ]
 
 EVICT_F32, EVICT_BF16 = 0, 1
@@ -26,7 +26,7 @@ EXPORTS = [
     "evict_version", "evict_last_error", "evict_create", "evict_destroy", "evict_packed_bytes", "evict_pack_dense",
     "evict_pack_qkv", "evict_pack_experts", "evict_verify_layer", "evict_expert_union", "evict_accept_path",
     "evict_select_prefix", "evict_gather_rows", "evict_validate_trees_host", "evict_device_status",
-    "evict_stage_timing", "evict_stage_times",
+    "evict_stage_timing", "evict_stage_times", "evict_probe_read", "evict_probe_copy", "evict_tune",
 ]
 STAGES = ["prep", "qkv", "attention", "oproj", "router", "union", "gateup", "down", "shared", "combine"]
 
@@ -89,6 +89,9 @@ def load():
     lib.evict_validate_trees_host.argtypes = [vp, vp, i32, i32]
     lib.evict_device_status.argtypes = [vp, C.POINTER(C.c_int32), vp]
     lib.evict_stage_timing.argtypes = [vp, i32]
+    lib.evict_tune.argtypes = [vp, C.c_char_p, i32]
+    lib.evict_probe_read.argtypes = [vp, sz, vp, vp]
+    lib.evict_probe_copy.argtypes = [vp, vp, sz, vp]
     lib.evict_stage_times.argtypes = [vp, C.POINTER(C.c_float)]
     _LIB = lib
     return lib
@@ -194,3 +197,15 @@ def evict_stage_times(ctx) -> dict:
     buf = (C.c_float * len(STAGES))()
     _check(load().evict_stage_times(ctx, buf))
     return {n: float(buf[i]) for i, n in enumerate(STAGES)}
+
+
+def evict_probe_read(src, nbytes: int, sink) -> None:
+    _check(load().evict_probe_read(_p(src), nbytes, _p(sink), _stream()))
+
+
+def evict_probe_copy(src, dst, nbytes: int) -> None:
+    _check(load().evict_probe_copy(_p(src), _p(dst), nbytes, _stream()))
+
+
+def evict_tune(ctx, key: str, value: int) -> None:
+    _check(load().evict_tune(ctx, key.encode(), value))

@@ -1,5 +1,7 @@
 // C-ABI entry points that own state or chain kernels: context, weight packing, the
 // per-layer verification pass (Sec. 2.1-2.2).
+#include <string.h>
+
 #include <new>
 #include <vector>
 
@@ -94,7 +96,8 @@ int evict_create(evict_ctx** out, const evict_model_desc* m, int max_tokens, int
   A(&c.union_count, 16);
   A(&c.perm, T * k * 4);
   A(&c.inv, T * k * 4);
-  A(&c.work, E * 16);
+  A(&c.work, E * sizeof(WorkRec));
+  A(&c.sched, 16);
   A(&c.tok_of_pos, T * k * 4);
   A(&c.act, T * k * F * eb);
   A(&c.y, T * k * d * 4);
@@ -110,6 +113,12 @@ int evict_create(evict_ctx** out, const evict_model_desc* m, int max_tokens, int
   }
   if (!rc) rc = kernels_setup(*m);
   c.timing = 0;
+  c.moe_grid = 2048;
+  c.moe_prefetch = 1;
+  c.moe_chunk_gateup = 1;
+  c.moe_chunk_down = 1;
+  for (int cu : {4, 2}) if ((m->d / 16) % cu == 0) { c.moe_chunk_down = cu; break; }
+  c.attn_row_blocks = 0;
   c.timed_once = 0;
   int n_ev = 0;
   for (; !rc && n_ev <= EVICT_N_STAGES; ++n_ev) {
@@ -275,7 +284,7 @@ int evict_verify_layer(evict_ctx* ctx, const evict_layer_weights* w, const int32
   if (rc) return rc;
   EVICT_MARK(5);
   rc = launch_union(ctx->status, ctx->topk_idx, T, m.k, m.E, ctx->union_ids, ctx->union_count, ctx->hist, ctx->offsets,
-                    ctx->perm, ctx->inv, ctx->work, ctx->tok_of_pos, s);
+                    ctx->perm, ctx->inv, ctx->work, ctx->tok_of_pos, ctx->sched, s);
   if (rc) return rc;
   if (aux) {
     if (aux->union_ids) EVICT_HIP_CHECK(hipMemcpyAsync(aux->union_ids, ctx->union_ids, (size_t)m.E * 4, hipMemcpyDeviceToDevice, s));
@@ -297,7 +306,9 @@ int evict_verify_layer(evict_ctx* ctx, const evict_layer_weights* w, const int32
     a.x_by_token = 1;
     a.out0 = ctx->act;
     a.ldo = m.F;
-    rc = launch_gemm(m.dtype, EPI_SWIGLU, a, nt_exp, 512, s);
+    a.prefetch = ctx->moe_prefetch;
+    a.chunk_units = ctx->moe_chunk_gateup;
+    rc = launch_gemm(m.dtype, EPI_SWIGLU, a, nt_exp, ctx->moe_grid, s);
     if (rc) return rc;
   }
   EVICT_MARK(7);
@@ -314,7 +325,8 @@ int evict_verify_layer(evict_ctx* ctx, const evict_layer_weights* w, const int32
     a.x_by_token = 0;
     a.out0 = ctx->y;
     a.ldo = m.d;
-    rc = launch_gemm(m.dtype, EPI_F32, a, nt_exp, 512, s);
+    a.chunk_units = ctx->moe_chunk_down;
+    rc = launch_gemm(m.dtype, EPI_F32, a, nt_exp, ctx->moe_grid, s);
     if (rc) return rc;
   }
   EVICT_MARK(8);
@@ -350,6 +362,30 @@ int evict_verify_layer(evict_ctx* ctx, const evict_layer_weights* w, const int32
   EVICT_MARK(10);
   if (timing) ctx->timed_once = 1;
 #undef EVICT_MARK
+  return EVICT_OK;
+}
+
+int evict_tune(evict_ctx* ctx, const char* key, int value) {
+  EVICT_REQUIRE(ctx && key, EVICT_E_INVALID, "evict_tune: null argument");
+  if (!strcmp(key, "moe_grid")) {
+    EVICT_REQUIRE(value >= 1 && value <= 65535, EVICT_E_INVALID, "evict_tune: moe_grid=%d out of range", value);
+    ctx->moe_grid = value;
+  } else if (!strcmp(key, "moe_prefetch")) {
+    EVICT_REQUIRE(value == 1 || value == 2, EVICT_E_INVALID, "evict_tune: moe_prefetch must be 1 or 2");
+    ctx->moe_prefetch = value;
+  } else if (!strcmp(key, "moe_chunk_gateup")) {
+    EVICT_REQUIRE(value >= 1 && (ctx->m.F / 16) % value == 0, EVICT_E_INVALID, "evict_tune: moe_chunk_gateup=%d must divide F/16", value);
+    ctx->moe_chunk_gateup = value;
+  } else if (!strcmp(key, "moe_chunk_down")) {
+    EVICT_REQUIRE(value >= 1 && (ctx->m.d / 16) % value == 0, EVICT_E_INVALID, "evict_tune: moe_chunk_down=%d must divide d/16", value);
+    ctx->moe_chunk_down = value;
+  } else if (!strcmp(key, "attn_row_blocks")) {
+    EVICT_REQUIRE(value >= 0 && value <= 64, EVICT_E_INVALID, "evict_tune: attn_row_blocks=%d out of range", value);
+    ctx->attn_row_blocks = value;
+  } else {
+    set_error("evict_tune: unknown key '%s'", key);
+    return EVICT_E_INVALID;
+  }
   return EVICT_OK;
 }
 

@@ -2,11 +2,14 @@
 #pragma once
 #include "common.h"
 
+namespace evict { struct WorkRec; }
+
 struct evict_ctx {
   evict_model_desc m;
   int max_tokens, max_batch, max_ctx;
   int device;
   int max_splits;        // KV splits the attention scratch is sized for (context part)
+  int moe_grid, moe_prefetch, moe_chunk_gateup, moe_chunk_down, attn_row_blocks;  // launch-shape knobs (evict_tune)
   int timing;            // record stage events in evict_verify_layer
   int timed_once;        // a timed call has been recorded
   hipEvent_t ev[EVICT_N_STAGES + 1];
@@ -32,7 +35,8 @@ struct evict_ctx {
   int32_t* union_count;  // [1]
   int32_t* perm;         // [T*k]
   int32_t* inv;          // [T*k]
-  int4* work;            // [E] per union slot: expert id, first position, token count
+  evict::WorkRec* work;  // [E] device-side work list, one record per union slot
+  int32_t* sched;        // [4] chunk counters of the grouped GEMMs
   int32_t* tok_of_pos;   // [T*k] token of each grouped position
   void* act;             // [T*k][F] storage dtype
   float* y;              // [T*k][d]

@@ -18,6 +18,15 @@ namespace evict {
 
 enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_F32 = 3 };
 
+// One union slot of the device-side work list: the expert, where its tokens sit in the
+// grouped order, how many there are, and the token ids of the first few positions (so that
+// a workgroup learns everything it needs to start loading from one 64-byte record).
+constexpr int kWorkToks = 12;
+struct WorkRec {
+  int expert, p0, ntok, pad;
+  int tok[kWorkToks];
+};
+
 struct GemmArgs {
   const u32x4* W;        // packed weights
   long long group_stride;  // u32x4 elements between experts
@@ -27,11 +36,13 @@ struct GemmArgs {
   long long ldx_bytes;   // bytes between rows of X
   int grouped;           // 0: one matrix, tokens 0..T-1; 1: one matrix per union expert
   const int* union_count;
-  const int4* work;      // per union slot: {expert id, first position, token count, 0}
+  const WorkRec* work;   // per union slot (see WorkRec)
+  int chunk_units;       // grouped: units per chunk (divides the units per expert)
   const int* tok_of_pos; // token of each grouped position (perm[p] / k)
   int x_by_token;        // grouped: 1 -> X row = tok_of_pos[p], 0 -> X row = p
   int T;                 // dense: token rows
   int dense_tiles;       // dense: workgroups per strip, each taking 16*NT tokens
+  int prefetch;          // host-side choice of the kernel variant (weight-load stages), 0 = default
   void* out0;            // QKV: q; RESID: h; SWIGLU: act; F32: y
   void* out1;            // QKV: k_new
   void* out2;            // QKV: v_new
@@ -56,44 +67,26 @@ __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(NT
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wavefront index, known uniform
   const int upg = a.n_strips / SPU;
-  const int ngroups = a.grouped ? *a.union_count : 1;
-  unsigned u0, u1;
-  int tok_begin = 0, tok_limit = 0x7fffffff;
-  if (a.grouped) {
-    // equal contiguous ranges of the unit list (32-bit: units * workgroups stays far below 2^32)
-    const unsigned tot = (unsigned)ngroups * (unsigned)upg;
-    u0 = tot * blockIdx.x / gridDim.x;
-    u1 = tot * (blockIdx.x + 1) / gridDim.x;
-  } else {
-    // one workgroup per (strip, token tile). Workgroup ids go round-robin over the 8 XCDs, so
-    // the tiles of one strip are given ids 8 apart: they share an L2 and read the strip from
-    // HBM once.
-    const unsigned xcd = blockIdx.x & 7u, i = blockIdx.x >> 3;
-    const unsigned tile = i % (unsigned)a.dense_tiles;
-    u0 = (i / (unsigned)a.dense_tiles) * 8u + xcd;
-    if (u0 >= (unsigned)upg) return;
-    u1 = u0 + 1;
-    tok_begin = (int)tile * 16 * NT;
-    tok_limit = tok_begin + 16 * NT;
-  }
   const int nkb = a.nkb;
   const int nchunks = (nkb + 63) >> 6;
   int parity = 0;
 
-  for (unsigned unit = u0; unit < u1;) {
-    const int grp = (int)(unit / (unsigned)upg);
-    unsigned seg_end = (unsigned)(grp + 1) * (unsigned)upg;
-    if (seg_end > u1) seg_end = u1;
-    const int unit_in_grp = (int)(unit - (unsigned)grp * (unsigned)upg);
+  // One segment = `nunits` consecutive units (strips, or gate/up strip pairs) of one weight
+  // matrix, applied to the tokens [tok_begin, min(ntok, tok_limit)) of its group.
+  auto run_segment = [&](int grp, int unit_in_grp, int nunits, int tok_begin, int tok_limit) {
     const int strip0 = unit_in_grp * SPU;
-    const int nitems = (int)(seg_end - unit) * SPU;
+    const int nitems = nunits * SPU;
     int p0 = 0, ntok = a.T;
+    int tok_early = 0;  // token id from the work record (grouped, first kWorkToks positions)
     const u32x4* wbase = a.W;
     if (a.grouped) {
-      const int4 rec = a.work[grp];
-      p0 = rec.y;
-      ntok = rec.z;
-      wbase += (long long)rec.x * a.group_stride;
+      // one hop: the record (scalar) and this lane's token id (vector) are fetched together
+      const WorkRec* rec = a.work + grp;
+      const int lc = lane & 15;
+      tok_early = rec->tok[lc < kWorkToks ? lc : kWorkToks - 1];  // entries past ntok repeat the last token
+      p0 = rec->p0;
+      ntok = rec->ntok;
+      wbase += (long long)rec->expert * a.group_stride;
     }
     const int nsteps = nitems * nchunks;
 
@@ -139,7 +132,10 @@ __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(NT
         int col = tok0 + t * 16 + (lane & 15);
         if (col > ntok - 1) col = ntok - 1;  // padded columns repeat the last token; never stored
         long long row = col;
-        if (a.grouped) row = a.x_by_token ? a.tok_of_pos[p0 + col] : (p0 + col);
+        if (a.grouped) {
+          if (!a.x_by_token) row = p0 + col;
+          else row = (t == 0 && tok0 == 0 && (lane & 15) < kWorkToks) ? tok_early : a.tok_of_pos[p0 + col];
+        }
         xrow[t] = (const char*)a.X + row * a.ldx_bytes + (lane >> 4) * 16;
       }
       auto load_b = [&](int c) {
@@ -248,7 +244,27 @@ __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(NT
         }
       }
     }
-    unit = seg_end;
+  };
+
+  if (a.grouped) {
+    // Device-side work list: union experts x units, cut into chunks of `chunk_units` units that
+    // never straddle an expert. Chunks are dealt round-robin to the workgroups; all chunks cost
+    // the same, so this stays balanced for any union size without the host knowing it.
+    const int cpg = upg / a.chunk_units;
+    const int total = *a.union_count * cpg;
+    for (int chunk = blockIdx.x; chunk < total; chunk += gridDim.x) {
+      const int grp = chunk / cpg;
+      run_segment(grp, (chunk - grp * cpg) * a.chunk_units, a.chunk_units, 0, 0x7fffffff);
+    }
+  } else {
+    // one workgroup per (strip, token tile). Workgroup ids go round-robin over the 8 XCDs, so
+    // the tiles of one strip are given ids 8 apart: they share an L2 and read the strip from
+    // HBM once.
+    const unsigned xcd = blockIdx.x & 7u, i = blockIdx.x >> 3;
+    const unsigned tile = i % (unsigned)a.dense_tiles;
+    const unsigned unit = (i / (unsigned)a.dense_tiles) * 8u + xcd;
+    if (unit >= (unsigned)upg) return;
+    run_segment(0, (int)unit, 1, (int)tile * 16 * NT, (int)(tile + 1) * 16 * NT);
   }
 }
 

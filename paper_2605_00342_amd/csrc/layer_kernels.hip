@@ -652,7 +652,8 @@ int launch_gemm_nt(const GemmArgs& a, int grid, hipStream_t s) {
   if (bf16 && nkb % 64 == 0) {
     // the next step's 8 loads are issued right after the MFMAs, so they fly during the
     // partial-tile exchange; one buffer keeps the kernel under 128 VGPRs (2 workgroups per CU)
-    EVICT_GEMM_LAUNCH(8, 1, true);
+    if (a.prefetch == 2) EVICT_GEMM_LAUNCH(8, 2, true);
+    else EVICT_GEMM_LAUNCH(8, 1, true);
   } else if (bf16 && nkb == 24) {
     EVICT_GEMM_LAUNCH(3, 4, true);
   } else if (need <= 4) {
@@ -752,7 +753,7 @@ int launch_attention(const evict_ctx* c, const void* kc, const void* vc, long lo
     const int G = m.Hq / m.Hkv;
     const int max_nodes = T < EVICT_MAX_TREE_NODES ? T : EVICT_MAX_TREE_NODES;
     const int ntiles = (max_nodes * G + 15) / 16;
-    int rb = (256 + nsplits * m.Hkv * B - 1) / (nsplits * m.Hkv * B);
+    int rb = c->attn_row_blocks > 0 ? c->attn_row_blocks : (256 + nsplits * m.Hkv * B - 1) / (nsplits * m.Hkv * B);
     const int rb_max = (ntiles + 3) / 4;
     rb = rb > rb_max ? rb_max : rb;
     rb = rb < 1 ? 1 : rb;

@@ -5,6 +5,7 @@
 namespace evict {
 
 struct GemmArgs;
+struct WorkRec;
 
 int launch_gemm(int dtype, int epi, const GemmArgs& a, int nt, int grid, hipStream_t s);
 int launch_pack(const void* src, long long src_group_bytes, int rows, int cols, int dtype, void* dst, int dst_strip0,
@@ -18,8 +19,8 @@ int launch_attention(const evict_ctx* c, const void* kc, const void* vc, long lo
                      const void* v_new, void* aux_out, hipStream_t s);
 int launch_router(const evict_ctx* c, const void* gain, const void* wg, int T, const evict_layer_aux* aux, hipStream_t s);
 int launch_union(int32_t* status, const int32_t* topk_idx, int T, int k, int E, int32_t* union_ids, int32_t* union_count,
-                 int32_t* hist, int32_t* offsets, int32_t* perm, int32_t* inv, int4* work, int32_t* tok_of_pos,
-                 hipStream_t stream);
+                 int32_t* hist, int32_t* offsets, int32_t* perm, int32_t* inv, WorkRec* work, int32_t* tok_of_pos,
+                 int32_t* sched, hipStream_t stream);
 int launch_combine(const evict_ctx* c, int T, void* out, hipStream_t s);
 
 }  // namespace evict

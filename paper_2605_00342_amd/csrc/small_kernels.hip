@@ -5,6 +5,7 @@
 #include <string.h>
 
 #include "ctx.h"
+#include "gemm_stream.h"
 
 namespace evict {
 
@@ -285,22 +286,26 @@ constexpr int kUnionThreads = 256;
 __global__ __launch_bounds__(kUnionThreads) void expert_union_kernel(
     const int32_t* __restrict__ topk_idx, int T, int k, int E, int use_masks, int32_t* __restrict__ union_ids,
     int32_t* __restrict__ union_count, int32_t* __restrict__ hist, int32_t* __restrict__ offsets,
-    int32_t* __restrict__ perm, int32_t* __restrict__ inv, int32_t* __restrict__ status, int4* __restrict__ work,
-    int32_t* __restrict__ tok_of_pos) {
+    int32_t* __restrict__ perm, int32_t* __restrict__ inv, int32_t* __restrict__ status, WorkRec* __restrict__ work,
+    int32_t* __restrict__ tok_of_pos, int32_t* __restrict__ sched) {
   extern __shared__ __attribute__((aligned(8))) int s_mem[];
   const int P = T * k;
   const int words = (T + 63) >> 6;
   int* s_idx = s_mem;            // [P]
   int* s_hist = s_mem + P;       // [E]
   int* s_off = s_hist + E;       // [E + 1]
-  unsigned long long* s_mask = reinterpret_cast<unsigned long long*>(s_mem + ((P + 2 * E + 2) & ~1));  // [E][words]
+  int* s_slot = s_off + E + 1;   // [E] union slot of each activated expert
+  unsigned long long* s_mask = reinterpret_cast<unsigned long long*>(s_mem + ((P + 3 * E + 2) & ~1));  // [E][words]
   __shared__ int s_wave[16];
   __shared__ int s_dup;
   const int tid = threadIdx.x;
   for (int e = tid; e < E; e += kUnionThreads) s_hist[e] = 0;
   if (use_masks)
     for (int i = tid; i < E * words; i += kUnionThreads) s_mask[i] = 0ull;
-  if (tid == 0) s_dup = 0;
+  if (tid == 0) {
+    s_dup = 0;
+    if (sched) { sched[0] = 0; sched[1] = 0; }  // chunk counters of the two grouped GEMMs
+  }
   __syncthreads();
   bool bad = false;
   for (int p = tid; p < P; p += kUnionThreads) {
@@ -338,7 +343,8 @@ __global__ __launch_bounds__(kUnionThreads) void expert_union_kernel(
       hist[e] = h[j];
       if (h[j] > 0) {
         union_ids[base_f] = e;
-        if (work) work[base_f] = make_int4(e, base_h, h[j], 0);
+        s_slot[e] = base_f;
+        if (work) { work[base_f].expert = e; work[base_f].p0 = base_h; work[base_f].ntok = h[j]; work[base_f].pad = 0; }
       }
     }
     base_h += h[j];
@@ -358,6 +364,13 @@ __global__ __launch_bounds__(kUnionThreads) void expert_union_kernel(
       perm[pos] = p;
       inv[p] = pos;
       if (tok_of_pos) tok_of_pos[pos] = t;
+      if (work) {
+        const int r = pos - s_off[e], last = s_hist[e] - 1;
+        WorkRec* rec = work + s_slot[e];
+        if (r < kWorkToks) rec->tok[r] = t;
+        if (r == last)
+          for (int i = r + 1; i < kWorkToks; ++i) rec->tok[i] = t;  // padded columns repeat the last token
+      }
     }
   } else {
     for (int e = tid; e < E; e += kUnionThreads) {
@@ -368,9 +381,58 @@ __global__ __launch_bounds__(kUnionThreads) void expert_union_kernel(
           perm[pos] = p;
           inv[p] = pos;
           if (tok_of_pos) tok_of_pos[pos] = p / k;
+          if (work) {
+            const int r = pos - s_off[e];
+            WorkRec* rec = work + s_slot[e];
+            if (r < kWorkToks) rec->tok[r] = p / k;
+            if (r == s_hist[e] - 1)
+              for (int i = r + 1; i < kWorkToks; ++i) rec->tok[i] = p / k;
+          }
           ++pos;
         }
       }
+    }
+  }
+}
+
+typedef __attribute__((ext_vector_type(4))) unsigned int probe_u32x4;
+
+// Streaming read: 512 workgroups x 256 threads, each thread keeps 8 independent 16-byte loads in flight.
+__global__ __launch_bounds__(256) void probe_read_kernel(const probe_u32x4* __restrict__ src, size_t n16, unsigned* __restrict__ sink) {
+  const size_t per_wg = (n16 + gridDim.x - 1) / gridDim.x;
+  const size_t lo = per_wg * blockIdx.x;
+  size_t hi = lo + per_wg;
+  hi = hi > n16 ? n16 : hi;
+  probe_u32x4 acc = {0, 0, 0, 0};
+  for (size_t i = lo + threadIdx.x; i < hi; i += 256 * 8) {
+    probe_u32x4 v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const size_t idx = i + (size_t)j * 256;
+      v[j] = idx < hi ? __builtin_nontemporal_load(src + idx) : probe_u32x4{0, 0, 0, 0};
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc ^= v[j];
+  }
+  if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x9E3779B9u) sink[threadIdx.x & 3] = acc[0];  // keeps the loads alive
+}
+
+__global__ __launch_bounds__(256) void probe_copy_kernel(const probe_u32x4* __restrict__ src, probe_u32x4* __restrict__ dst, size_t n16) {
+  const size_t per_wg = (n16 + gridDim.x - 1) / gridDim.x;
+  const size_t lo = per_wg * blockIdx.x;
+  size_t hi = lo + per_wg;
+  hi = hi > n16 ? n16 : hi;
+  for (size_t i = lo + threadIdx.x; i < hi; i += 256 * 4) {
+    probe_u32x4 v[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const size_t idx = i + (size_t)j * 256;
+      if (idx < hi) v[j] = src[idx];
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const size_t idx = i + (size_t)j * 256;
+      if (idx < hi) dst[idx] = v[j];
     }
   }
 }
@@ -389,8 +451,8 @@ __global__ void gather_rows_kernel(const uint32_t* __restrict__ src, uint32_t* _
 }  // namespace
 
 int launch_union(int32_t* status, const int32_t* topk_idx, int T, int k, int E, int32_t* union_ids, int32_t* union_count,
-                 int32_t* hist, int32_t* offsets, int32_t* perm, int32_t* inv, int4* work, int32_t* tok_of_pos,
-                 hipStream_t stream) {
+                 int32_t* hist, int32_t* offsets, int32_t* perm, int32_t* inv, WorkRec* work, int32_t* tok_of_pos,
+                 int32_t* sched, hipStream_t stream) {
   EVICT_REQUIRE(topk_idx && union_ids && union_count && hist && offsets && perm && inv, EVICT_E_INVALID,
                 "evict_expert_union: null pointer argument");
   EVICT_REQUIRE(T >= 1 && k >= 1 && E >= 1, EVICT_E_INVALID, "evict_expert_union: T, k, E must be >= 1");
@@ -399,12 +461,12 @@ int launch_union(int32_t* status, const int32_t* topk_idx, int T, int k, int E, 
                 "evict_expert_union: T*k=%lld (limit 8192), E=%d (limit 1024)", (long long)T * k, E);
   const int P = T * k;
   const size_t words = (size_t)(T + 63) / 64;
-  size_t lds = sizeof(int) * (size_t)((P + 2 * E + 2) & ~1);
+  size_t lds = sizeof(int) * (size_t)((P + 3 * E + 2) & ~1);
   const size_t mask_bytes = 8 * (size_t)E * words;
   const int use_masks = lds + mask_bytes <= 60 * 1024 ? 1 : 0;
   if (use_masks) lds += mask_bytes;
   hipLaunchKernelGGL(expert_union_kernel, dim3(1), dim3(kUnionThreads), lds, stream, topk_idx, T, k, E, use_masks,
-                     union_ids, union_count, hist, offsets, perm, inv, status, work, tok_of_pos);
+                     union_ids, union_count, hist, offsets, perm, inv, status, work, tok_of_pos, sched);
   return launch_status("expert_union_kernel");
 }
 
@@ -474,7 +536,23 @@ int evict_expert_union(evict_ctx* ctx, const int32_t* topk_idx, int T, int k, in
                        int32_t* union_count, int32_t* hist, int32_t* offsets, int32_t* perm, int32_t* inv,
                        void* stream) {
   return evict::launch_union(ctx ? ctx->status : nullptr, topk_idx, T, k, E, union_ids, union_count, hist, offsets, perm,
-                             inv, nullptr, nullptr, (hipStream_t)stream);
+                             inv, nullptr, nullptr, nullptr, (hipStream_t)stream);
+}
+
+int evict_probe_read(const void* src, size_t bytes, void* sink, void* stream) {
+  EVICT_REQUIRE(src && sink && bytes > 0 && bytes % 16 == 0 && aligned16(src), EVICT_E_INVALID,
+                "evict_probe_read: need non-null 16-byte aligned src, sink, and bytes a positive multiple of 16");
+  hipLaunchKernelGGL(probe_read_kernel, dim3(2048), dim3(256), 0, (hipStream_t)stream, (const probe_u32x4*)src, bytes / 16,
+                     (unsigned*)sink);
+  return launch_status("probe_read_kernel");
+}
+
+int evict_probe_copy(const void* src, void* dst, size_t bytes, void* stream) {
+  EVICT_REQUIRE(src && dst && bytes > 0 && bytes % 16 == 0 && aligned16(src) && aligned16(dst), EVICT_E_INVALID,
+                "evict_probe_copy: need non-null 16-byte aligned pointers and bytes a positive multiple of 16");
+  hipLaunchKernelGGL(probe_copy_kernel, dim3(2048), dim3(256), 0, (hipStream_t)stream, (const probe_u32x4*)src,
+                     (probe_u32x4*)dst, bytes / 16);
+  return launch_status("probe_copy_kernel");
 }
 
 int evict_gather_rows(const void* src, void* dst, int row_bytes, const int32_t* tree_off, const int32_t* new_tree_off,
