@@ -15,7 +15,8 @@
  *     stream); no call synchronises the stream or allocates after evict_create.
  *   - Inputs are never written. The KV cache is read-only: keys/values of the draft nodes
  *     go to caller buffers.
- *   - Trees are batched CSR-style: tree_off int32[B+1], node arrays concatenated, parent
+ *   - Trees are batched CSR-style: tree_off int32[B+1] with tree_off[0] = 0 and
+ *     tree_off[B] = T (the calls that take T rely on it), node arrays concatenated, parent
  *     ids are tree-local with parent[0] = -1 and parent[i] < i (node 0 is the root
  *     x_{t+1}, which is sampled from the target and therefore always accepted and always
  *     part of every prefix; Sec. 2.1).

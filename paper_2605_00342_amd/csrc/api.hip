@@ -283,8 +283,7 @@ int evict_verify_layer(evict_ctx* ctx, const evict_layer_weights* w, const int32
   rc = launch_router(ctx, w->g_moe, w->wg_packed, T, aux, s);
   if (rc) return rc;
   EVICT_MARK(5);
-  rc = launch_union(ctx->status, ctx->topk_idx, T, m.k, m.E, ctx->union_ids, ctx->union_count, ctx->hist, ctx->offsets,
-                    ctx->perm, ctx->inv, ctx->work, ctx->tok_of_pos, ctx->sched, s);
+  rc = launch_topk_union(ctx, T, aux, s);
   if (rc) return rc;
   if (aux) {
     if (aux->union_ids) EVICT_HIP_CHECK(hipMemcpyAsync(aux->union_ids, ctx->union_ids, (size_t)m.E * 4, hipMemcpyDeviceToDevice, s));

@@ -85,6 +85,20 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
+// Wavefront-wide maximum of an unsigned value through DPP row operations (no LDS traffic):
+// butterflies inside each row of 16 lanes, then row broadcasts; the result is read from the
+// last lane as a scalar.
+__device__ __forceinline__ unsigned wave_max_u32(unsigned v) {
+  auto mx = [](unsigned a, unsigned b) { return a > b ? a : b; };
+  v = mx(v, (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0xB1, 0xF, 0xF, false));   // quad_perm [1,0,3,2]
+  v = mx(v, (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x4E, 0xF, 0xF, false));   // quad_perm [2,3,0,1]
+  v = mx(v, (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x141, 0xF, 0xF, false));  // row_half_mirror
+  v = mx(v, (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x140, 0xF, 0xF, false));  // row_mirror
+  v = mx(v, (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x142, 0xA, 0xF, false));  // row_bcast:15 into rows 1, 3
+  v = mx(v, (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x143, 0xC, 0xF, false));  // row_bcast:31 into rows 2, 3
+  return (unsigned)__builtin_amdgcn_readlane((int)v, 63);
+}
+
 // Workgroup barrier that waits for LDS traffic only, so that global loads already in
 // flight (weight prefetch) stay in flight across it.
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }

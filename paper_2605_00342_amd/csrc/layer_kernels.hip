@@ -4,6 +4,7 @@
 #include "ctx.h"
 #include "gemm_stream.h"
 #include "layer_launch.h"
+#include "union_device.h"
 
 namespace evict {
 namespace {
@@ -48,7 +49,7 @@ __global__ __launch_bounds__(256) void prep_kernel(const int32_t* __restrict__ t
                                                    float eps, float theta, int D, uint64_t* __restrict__ anc,
                                                    int32_t* __restrict__ depth, int32_t* __restrict__ seq_of,
                                                    float* __restrict__ rope_cs, void* __restrict__ x_norm,
-                                                   int32_t* __restrict__ status) {
+                                                   int32_t* __restrict__ status, int n_single) {
   constexpr int EB = ST::kBytes;
   constexpr int CE = 16 / EB;
   constexpr int MAXC = 4;  // 16-byte chunks of the row per thread (d <= 256*CE*MAXC)
@@ -70,12 +71,14 @@ __global__ __launch_bounds__(256) void prep_kernel(const int32_t* __restrict__ t
   }
   if (tid == 0) s_b = 0;
   __syncthreads();
-  for (int b = tid; b < B; b += 256)
-    if (tree_off[b] <= t && t < tree_off[b + 1]) s_b = b;
+  if (n_single == 0)
+    for (int b = tid; b < B; b += 256)
+      if (tree_off[b] <= t && t < tree_off[b + 1]) s_b = b;
   __syncthreads();
   const int b = s_b;
-  const int lo = tree_off[b];
-  int n = tree_off[b + 1] - lo;
+  // a single tree spans [0, T): its offsets need not be fetched
+  const int lo = n_single > 0 ? 0 : tree_off[b];
+  int n = n_single > 0 ? n_single : tree_off[b + 1] - lo;
   int L = ctx_len[b];
   if (n > EVICT_MAX_TREE_NODES) { n = EVICT_MAX_TREE_NODES; if (tid == 0) atomicOr(status, ST_BAD_TREE_SIZE); }
   const int i = t - lo < n ? t - lo : n - 1;
@@ -260,7 +263,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
     long long seq_stride, long long head_stride, const int32_t* __restrict__ ctx_len, int max_ctx,
     const int32_t* __restrict__ tree_off, const uint16_t* __restrict__ k_new, const uint16_t* __restrict__ v_new,
     const uint64_t* __restrict__ anc, int Hq, int Hkv, int ctx_splits, int row_blocks, int T,
-    float* __restrict__ part_o, float* __restrict__ part_ml) {
+    float* __restrict__ part_o, float* __restrict__ part_ml, int n_single) {
   constexpr int LDK = D + 8;            // bf16 per K row in LDS (16-byte pad)
   constexpr int LDV = kMfmaKeys + 4;    // bf16 per V^T row in LDS
   constexpr int CH = D / 8;             // 16-byte chunks per row
@@ -272,8 +275,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
   const int split = blockIdx.x / row_blocks, rb = blockIdx.x - split * row_blocks;
   const int g = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const int lo = tree_off[b];
-  int n = tree_off[b + 1] - lo;
+  const int lo = n_single > 0 ? 0 : tree_off[b];
+  int n = n_single > 0 ? n_single : tree_off[b + 1] - lo;
   n = n > EVICT_MAX_TREE_NODES ? EVICT_MAX_TREE_NODES : n;
   int L = ctx_len[b];
   L = L < 0 ? 0 : (L > max_ctx ? max_ctx : L);
@@ -300,6 +303,24 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
     return;
   }
 
+  // ---- this wavefront's first query tile is fetched before the K/V staging so that the two
+  // round trips overlap
+  const float scale = 1.0f / sqrtf((float)D);
+  const int kq = lane >> 4, ln = lane & 15;
+  u32x4 Qn[KB];
+  uint64_t a0n = ~0ull, a1n = ~0ull;
+  auto fetch_rows = [&](int rt) {
+    int r = rt * 16 + ln;
+    r = r < R ? r : R - 1;
+    const int i = r / G, hh = r - i * G;
+    const int t = lo + i;
+    const uint16_t* qrow = q + ((size_t)t * Hq + g * G + hh) * D + kq * 8;
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb) Qn[kb] = *reinterpret_cast<const u32x4*>(qrow + kb * 32);
+    if (tree_part) { a0n = anc[2 * (size_t)t]; a1n = anc[2 * (size_t)t + 1]; }
+  };
+  if (t_begin + w < t_end) fetch_rows(t_begin + w);
+
   // ---- stage K (row-major) and V (transposed, two keys per dword)
   const uint16_t* kbase = tree_part ? k_new + ((size_t)lo * Hkv + g) * D : kc + (size_t)b * seq_stride + (size_t)g * head_stride + (size_t)key0 * D;
   const uint16_t* vbase = tree_part ? v_new + ((size_t)lo * Hkv + g) * D : vc + (size_t)b * seq_stride + (size_t)g * head_stride + (size_t)key0 * D;
@@ -324,19 +345,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
   }
   __syncthreads();
 
-  const float scale = 1.0f / sqrtf((float)D);
-  const int kq = lane >> 4, ln = lane & 15;
   for (int rt = t_begin + w; rt < t_end; rt += 4) {
     int r = rt * 16 + ln;
     r = r < R ? r : R - 1;
     const int i = r / G, hh = r - i * G;
     const int t = lo + i;
-    const uint16_t* qrow = q + ((size_t)t * Hq + g * G + hh) * D + kq * 8;
     u32x4 Qf[KB];
 #pragma unroll
-    for (int kb = 0; kb < KB; ++kb) Qf[kb] = *reinterpret_cast<const u32x4*>(qrow + kb * 32);
-    uint64_t a0 = ~0ull, a1 = ~0ull;
-    if (tree_part) { a0 = anc[2 * (size_t)t]; a1 = anc[2 * (size_t)t + 1]; }
+    for (int kb = 0; kb < KB; ++kb) Qf[kb] = Qn[kb];
+    const uint64_t a0 = a0n, a1 = a1n;
+    if (rt + 4 < t_end) fetch_rows(rt + 4);  // next tile's rows travel while this one is computed
     // S^T tiles: lane holds keys kt*16 + kq*4 + j of query row ln
     f32x4 S[KT];
     float mx = -INFINITY;
@@ -357,6 +375,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
         mx = fmaxf(mx, acc[j]);
       }
       S[kt] = acc;
+      __builtin_amdgcn_sched_barrier(0);  // keep the LDS reads of later tiles from piling up in registers
     }
     mx = fmaxf(mx, __shfl_xor(mx, 16));
     mx = fmaxf(mx, __shfl_xor(mx, 32));
@@ -461,42 +480,47 @@ __global__ void attn_merge_kernel(const float* __restrict__ part_o, const float*
 }
 
 // ------------------------------------------------------------------------------------
-// router: RMSNorm(h), scores W_g h (Eq. 4) on the matrix cores, top-k by wavefront shuffles,
-// softmax over the selected scores. One workgroup (8 wavefronts) per tile of 16 tokens.
-// W_g is in the packed streaming layout (16-expert strips).
+// router, part 1: RMSNorm(h) and scores W_g h (Eq. 4) on the matrix cores. Grid (token tiles of
+// 16, expert-strip groups); 16 wavefronts split the strips of the group and the contraction
+// range between them. W_g is in the packed streaming layout (16-expert strips). Every
+// workgroup normalises its 16 tokens (cheap); the first strip group also stores them.
+// LDS: token operand blocks [nkb][64] x 16 B, then partial scores [ksplit][strips][16][16].
 // ------------------------------------------------------------------------------------
 constexpr int kRouterWaves = 16;
 constexpr int kRouterThreads = kRouterWaves * 64;
 
-// LDS: token operand blocks [nkb][64] x 16 B, then partial scores [KS][16][E] floats, where
-// KS = ways the contraction is split so that all 16 wavefronts have an (expert strip, slice).
 template <typename ST>
-__global__ __launch_bounds__(kRouterThreads) void router_kernel(
+__global__ __launch_bounds__(kRouterThreads) void router_logits_kernel(
     const void* __restrict__ h, const void* __restrict__ gain, const u32x4* __restrict__ wg_packed, int T, int d, int E,
-    int k, int ksplit, float eps, void* __restrict__ h_norm, float* __restrict__ logits, int32_t* __restrict__ topk_idx,
-    float* __restrict__ topk_w, void* __restrict__ aux_hn, float* __restrict__ aux_logits,
-    int32_t* __restrict__ aux_idx, float* __restrict__ aux_w) {
+    int strips_per_wg, int ksplit, float eps, void* __restrict__ h_norm, float* __restrict__ logits,
+    void* __restrict__ aux_hn, float* __restrict__ aux_logits) {
   constexpr int EB = ST::kBytes;
   constexpr int CE = 16 / EB;   // elements per 16-byte chunk
   constexpr int MAXC = 8;       // 16-byte chunks a lane keeps of its token row (d <= 64*CE*MAXC)
   extern __shared__ __attribute__((aligned(16))) unsigned char s_raw[];
   const int nkb = d * EB / 64;
   u32x4* s_b = reinterpret_cast<u32x4*>(s_raw);                       // [nkb][64] token operand blocks
-  float* s_l = reinterpret_cast<float*>(s_raw + (size_t)nkb * 1024);  // [ksplit][16][E]
+  f32x4* s_p = reinterpret_cast<f32x4*>(s_raw + (size_t)nkb * 1024);  // [ksplit][strips_per_wg][64]
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int tok0 = blockIdx.x * 16;
+  const int strip_base = blockIdx.y * strips_per_wg;
+  const bool writer = blockIdx.y == 0;
   // ---- one token per wavefront: the row stays in registers between the two passes
   {
     const int n = w, t = tok0 + n;
     const bool live = t < T;
-    u32x4 raw[MAXC];
+    u32x4 raw[MAXC], graw[MAXC];
     float ss = 0.0f;
 #pragma unroll
     for (int i = 0; i < MAXC; ++i) {
       const int c = (lane + 64 * i) * CE;
       raw[i] = u32x4{0, 0, 0, 0};
-      if (live && c < d) raw[i] = *reinterpret_cast<const u32x4*>((const char*)h + ((size_t)t * d + c) * EB);
+      graw[i] = u32x4{0, 0, 0, 0};
+      if (c < d) {
+        if (live) raw[i] = *reinterpret_cast<const u32x4*>((const char*)h + ((size_t)t * d + c) * EB);
+        graw[i] = *reinterpret_cast<const u32x4*>((const char*)gain + (size_t)c * EB);
+      }
     }
 #pragma unroll
     for (int i = 0; i < MAXC; ++i) {
@@ -519,19 +543,20 @@ __global__ __launch_bounds__(kRouterThreads) void router_kernel(
       if (c < d) {
         u32x4 packed = {0, 0, 0, 0};
         if (live) {
-          const u32x4 graw = *reinterpret_cast<const u32x4*>((const char*)gain + (size_t)c * EB);
 #pragma unroll
           for (int u = 0; u < 4; ++u) {
             if (EB == 2) {
-              const float a = __uint_as_float(raw[i][u] << 16) * rinv * __uint_as_float(graw[u] << 16);
-              const float b = __uint_as_float(raw[i][u] & 0xFFFF0000u) * rinv * __uint_as_float(graw[u] & 0xFFFF0000u);
+              const float a = __uint_as_float(raw[i][u] << 16) * rinv * __uint_as_float(graw[i][u] << 16);
+              const float b = __uint_as_float(raw[i][u] & 0xFFFF0000u) * rinv * __uint_as_float(graw[i][u] & 0xFFFF0000u);
               packed[u] = (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
             } else {
-              packed[u] = __float_as_uint(__uint_as_float(raw[i][u]) * rinv * __uint_as_float(graw[u]));
+              packed[u] = __float_as_uint(__uint_as_float(raw[i][u]) * rinv * __uint_as_float(graw[i][u]));
             }
           }
-          *reinterpret_cast<u32x4*>((char*)h_norm + ((size_t)t * d + c) * EB) = packed;
-          if (aux_hn) *reinterpret_cast<u32x4*>((char*)aux_hn + ((size_t)t * d + c) * EB) = packed;
+          if (writer) {
+            *reinterpret_cast<u32x4*>((char*)h_norm + ((size_t)t * d + c) * EB) = packed;
+            if (aux_hn) *reinterpret_cast<u32x4*>((char*)aux_hn + ((size_t)t * d + c) * EB) = packed;
+          }
         }
         const int byte = c * EB;  // position in the row -> operand block, quarter, column n
         s_b[(byte >> 6) * 64 + ((byte >> 4) & 3) * 16 + n] = packed;
@@ -541,73 +566,112 @@ __global__ __launch_bounds__(kRouterThreads) void router_kernel(
   __syncthreads();
   // ---- scores: (expert strip, contraction slice) items round-robin over the wavefronts
   const int nstrips = E >> 4;
+  int my_strips = nstrips - strip_base;
+  my_strips = my_strips > strips_per_wg ? strips_per_wg : my_strips;
   const int per = (nkb + ksplit - 1) / ksplit;  // blocks per slice
-  for (int item = w; item < nstrips * ksplit; item += kRouterWaves) {
-    const int strip = item / ksplit, ks = item - strip * ksplit;
+  for (int item = w; item < my_strips * ksplit; item += kRouterWaves) {
+    const int sl = item / ksplit, ks = item - sl * ksplit;
     const int kb_lo = ks * per;
     int kb_hi = kb_lo + per;
     kb_hi = kb_hi > nkb ? nkb : kb_hi;
-    const u32x4* wp = wg_packed + (size_t)strip * nkb * 64 + lane;
+    const u32x4* wp = wg_packed + (size_t)(strip_base + sl) * nkb * 64 + lane;
     f32x4 acc = {0, 0, 0, 0};
-    for (int kb0 = kb_lo; kb0 < kb_hi; kb0 += 16) {
-      u32x4 a[16];
+    for (int kb0 = kb_lo; kb0 < kb_hi; kb0 += 8) {
+      u32x4 a[8];
 #pragma unroll
-      for (int j = 0; j < 16; ++j)
+      for (int j = 0; j < 8; ++j)
         if (kb0 + j < kb_hi) a[j] = wp[(size_t)(kb0 + j) * 64];
 #pragma unroll
-      for (int j = 0; j < 16; ++j)
+      for (int j = 0; j < 8; ++j)
         if (kb0 + j < kb_hi) acc = mfma_block<ST>(a[j], s_b[(kb0 + j) * 64 + lane], acc);
     }
-    const int n = lane & 15;
-    *reinterpret_cast<f32x4*>(s_l + ((size_t)ks * 16 + n) * E + strip * 16 + (lane >> 4) * 4) = acc;
+    s_p[((size_t)ks * strips_per_wg + sl) * 64 + lane] = acc;
   }
   __syncthreads();
-  // ---- sum the slices in a fixed order, publish the scores
-  for (int idx = tid; idx < 16 * E; idx += kRouterThreads) {
-    float v = s_l[idx];
-    for (int ks = 1; ks < ksplit; ++ks) v += s_l[(size_t)ks * 16 * E + idx];
-    s_l[idx] = v;
-    const int n = idx / E, t = tok0 + n;
+  // ---- sum the slices in a fixed order, publish the scores: lane holds 4 experts of one token
+  for (int idx = tid; idx < my_strips * 64; idx += kRouterThreads) {
+    const int sl = idx >> 6, ln = idx & 63;
+    f32x4 v = s_p[(size_t)sl * 64 + ln];
+    for (int ks = 1; ks < ksplit; ++ks) v += s_p[((size_t)ks * strips_per_wg + sl) * 64 + ln];
+    const int t = tok0 + (ln & 15);
     if (t < T) {
-      logits[(size_t)t * E + (idx - n * E)] = v;
-      if (aux_logits) aux_logits[(size_t)t * E + (idx - n * E)] = v;
+      const size_t o = (size_t)t * E + (strip_base + sl) * 16 + (ln >> 4) * 4;
+      *reinterpret_cast<f32x4*>(logits + o) = v;
+      if (aux_logits) *reinterpret_cast<f32x4*>(aux_logits + o) = v;
     }
   }
-  __syncthreads();
-  // ---- top-k and weights, one token per wavefront
-  {
-    const int n = w, t = tok0 + n;
-    if (t >= T) return;
-    float* sl = s_l + n * E;
-    float sel_v = 0.0f, first = 0.0f, denom = 0.0f;
-    int sel_i = 0;
-    for (int j = 0; j < k; ++j) {
-      float bv = -INFINITY;
-      int bi = 0x7fffffff;
-      for (int e = lane; e < E; e += 64) {
-        const float v = sl[e];
-        if (v > bv) { bv = v; bi = e; }  // ascending e inside a lane keeps the lowest index on ties
-      }
-#pragma unroll
-      for (int o = 32; o >= 1; o >>= 1) {
-        const float ov = __shfl_xor(bv, o);
-        const int oi = __shfl_xor(bi, o);
-        if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
-      }
-      if (j == 0) first = bv;
-      const float ex = __expf(bv - first);
-      denom += ex;
-      if (lane == j) { sel_v = ex; sel_i = bi; }
-      if (lane == 0) sl[bi] = -INFINITY;  // remove from the candidates
+}
+
+// ------------------------------------------------------------------------------------
+// router, part 2 + grouping, one workgroup: TopK of every token's scores with the selected
+// scores normalised by softmax (Eq. 4), then the expert union and the token grouping (Eq. 5)
+// without a round trip of the indices through global memory.
+// Selection: one wavefront per token; scores become unsigned keys monotone in the float value,
+// each of the k picks is a wavefront maximum (DPP row operations) followed by ballots that find
+// the lowest expert index holding it, so equal scores go to the lower index.
+// ------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kRouterThreads) void topk_union_kernel(
+    const float* __restrict__ logits, int T, int E, int k, int use_masks, int32_t* __restrict__ topk_idx,
+    float* __restrict__ topk_w, int32_t* __restrict__ aux_idx, float* __restrict__ aux_w,
+    int32_t* __restrict__ union_ids, int32_t* __restrict__ union_count, int32_t* __restrict__ hist,
+    int32_t* __restrict__ offsets, int32_t* __restrict__ perm, int32_t* __restrict__ inv, int32_t* __restrict__ status,
+    WorkRec* __restrict__ work, int32_t* __restrict__ tok_of_pos, int union_ints) {
+  extern __shared__ __attribute__((aligned(16))) int s_all[];
+  int* s_mem = s_all;  // union scratch (first T*k ints: the indices), masks behind it
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  float* s_sel = reinterpret_cast<float*>(s_all + union_ints) + w * 64;                                   // [k] per wavefront
+  unsigned* s_ord = reinterpret_cast<unsigned*>(s_all + union_ints + kRouterWaves * 64) + (size_t)w * E;  // [E] per wavefront
+  // The loops below are deliberately not unrolled: this kernel runs on one compute unit with a
+  // cold instruction cache, so its cost follows the size of the code it walks through.
+  for (int t = w; t < T; t += kRouterWaves) {
+    const float* row = logits + (size_t)t * E;
+    // scores as unsigned keys, monotone in the float value; 0 marks "taken" (below every key)
+#pragma unroll 1
+    for (int e = lane; e < E; e += 64) {
+      unsigned bits = __float_as_uint(row[e]);
+      bits = bits == 0x80000000u ? 0u : bits;  // -0 and +0 compare equal
+      const unsigned o = bits ^ ((bits >> 31) ? 0xFFFFFFFFu : 0x80000000u);
+      s_ord[e] = o == 0u ? 1u : o;             // (only the most negative NaN pattern maps to 0)
     }
+    // k extractions: wavefront maximum by DPP, then the lowest index holding it by ballots
+    // (LDS operations of one wavefront complete in order: s_ord / s_sel are visible to its lanes)
+#pragma unroll 1
+    for (int j = 0; j < k; ++j) {
+      unsigned local = 0u;
+#pragma unroll 1
+      for (int e = lane; e < E; e += 64) {
+        const unsigned o = s_ord[e];
+        local = o > local ? o : local;
+      }
+      const unsigned best = wave_max_u32(local);
+      int sel = -1;
+#pragma unroll 1
+      for (int base = 0; base < E && sel < 0; base += 64) {
+        const int e = base + lane;
+        const unsigned long long m = __ballot(e < E && s_ord[e] == best);
+        if (m) sel = base + (int)__ffsll((long long)m) - 1;
+      }
+      if (lane == 0) {
+        s_ord[sel] = 0u;
+        s_sel[j] = __uint_as_float(best ^ ((best >> 31) ? 0x80000000u : 0xFFFFFFFFu));
+        s_mem[t * k + j] = sel;
+        topk_idx[(size_t)t * k + j] = sel;
+        if (aux_idx) aux_idx[(size_t)t * k + j] = sel;
+      }
+    }
+    const float first = s_sel[0];
+    const float ex = lane < k ? __expf(s_sel[lane < k ? lane : 0] - first) : 0.0f;
+    const float denom = wave_sum(ex);
     if (lane < k) {
-      const float wv = sel_v / denom;
-      topk_idx[(size_t)t * k + lane] = sel_i;
+      const float wv = ex / denom;
       topk_w[(size_t)t * k + lane] = wv;
-      if (aux_idx) aux_idx[(size_t)t * k + lane] = sel_i;
       if (aux_w) aux_w[(size_t)t * k + lane] = wv;
     }
   }
+  __syncthreads();
+  expert_union_body(s_mem, nullptr, T, k, E, use_masks, union_ids, union_count, hist, offsets, perm, inv, status, work,
+                    tok_of_pos);
 }
 
 // ------------------------------------------------------------------------------------
@@ -706,22 +770,38 @@ int launch_prep(const evict_ctx* c, const int32_t* tree_off, const int32_t* pare
   const evict_model_desc& m = c->m;
   if (m.dtype == EVICT_BF16)
     hipLaunchKernelGGL(prep_kernel<BF16>, dim3(T), dim3(256), 0, s, tree_off, parent, B, ctx_len, max_ctx, x, gain, m.d,
-                       m.rms_eps, m.rope_theta, m.D, c->anc, c->depth, c->seq_of, c->rope_cs, c->x_norm, c->status);
+                       m.rms_eps, m.rope_theta, m.D, c->anc, c->depth, c->seq_of, c->rope_cs, c->x_norm, c->status, B == 1 ? T : 0);
   else
     hipLaunchKernelGGL(prep_kernel<F32>, dim3(T), dim3(256), 0, s, tree_off, parent, B, ctx_len, max_ctx, x, gain, m.d,
-                       m.rms_eps, m.rope_theta, m.D, c->anc, c->depth, c->seq_of, c->rope_cs, c->x_norm, c->status);
+                       m.rms_eps, m.rope_theta, m.D, c->anc, c->depth, c->seq_of, c->rope_cs, c->x_norm, c->status, B == 1 ? T : 0);
   return launch_status("prep_kernel");
 }
 
 size_t attn_partial_lds_bytes(int D) { return sizeof(float) * (size_t)(2 * kAttnKeys * (D + 1) + 4 * D + 4 * 64); }
 size_t attn_mfma_lds_bytes(int D) { return 2 * (size_t)(kMfmaKeys * (D + 8) + D * (kMfmaKeys + 4)); }
+// strips of 16 experts per workgroup and contraction split of the score kernel: enough
+// workgroups to spread W_g over the chip, 16 (strip, slice) items per workgroup
+int router_strips_per_wg(const evict_model_desc& m) {
+  const int nstrips = m.E / 16;
+  return nstrips <= 16 ? 1 : (nstrips + 15) / 16;
+}
 int router_ksplit(const evict_model_desc& m) {
-  int ks = kRouterWaves / (m.E / 16);
+  int ks = kRouterWaves / router_strips_per_wg(m);
+  const int nkb = m.d * (m.dtype == EVICT_BF16 ? 2 : 4) / 64;
+  ks = ks > nkb ? nkb : ks;
   return ks < 1 ? 1 : ks;
 }
 size_t router_lds_bytes(const evict_model_desc& m) {
   const size_t eb = m.dtype == EVICT_BF16 ? 2 : 4;
-  return (size_t)m.d * eb * 16 + (size_t)router_ksplit(m) * 16 * m.E * sizeof(float);
+  return (size_t)m.d * eb * 16 + (size_t)router_ksplit(m) * router_strips_per_wg(m) * 64 * sizeof(f32x4);
+}
+int union_mask_plan(int T, int k, int E, size_t* lds_bytes);  // small_kernels.hip
+size_t topk_union_lds_bytes(int T, int k, int E, int* use_masks, int* union_ints) {
+  size_t ub;
+  *use_masks = union_mask_plan(T, k, E, &ub);
+  const size_t ints = (ub / sizeof(int) + 3) & ~(size_t)3;  // keep the keys 16-byte aligned
+  *union_ints = (int)ints;
+  return ints * sizeof(int) + kRouterWaves * 64 * sizeof(float) + (size_t)kRouterWaves * E * sizeof(unsigned);
 }
 
 int kernels_setup(const evict_model_desc& m) {
@@ -731,12 +811,13 @@ int kernels_setup(const evict_model_desc& m) {
   EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)attn_partial_mfma_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_mfma_lds_bytes(128)));
   EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)attn_partial_mfma_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_mfma_lds_bytes(64)));
   const size_t rl = router_lds_bytes(m);
-  EVICT_REQUIRE(rl <= 160 * 1024, EVICT_E_UNSUPPORTED, "router needs %zu bytes of LDS (limit 160 KiB): d or E too large", rl);
+  EVICT_REQUIRE(rl <= 152 * 1024, EVICT_E_UNSUPPORTED, "router needs %zu bytes of LDS (limit 152 KiB): d too large", rl);
   EVICT_REQUIRE(m.d <= 64 * 8 * (m.dtype == EVICT_BF16 ? 8 : 4), EVICT_E_UNSUPPORTED, "router keeps a token row in registers: d=%d too large", m.d);
   if (m.dtype == EVICT_BF16)
-    EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)router_kernel<BF16>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)rl));
+    EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)router_logits_kernel<BF16>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)rl));
   else
-    EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)router_kernel<F32>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)rl));
+    EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)router_logits_kernel<F32>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)rl));
+  EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)topk_union_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024));
   return EVICT_OK;
 }
 
@@ -761,7 +842,7 @@ int launch_attention(const evict_ctx* c, const void* kc, const void* vc, long lo
     const size_t lds = attn_mfma_lds_bytes(m.D);
 #define EVICT_ATTN_ARGS (const uint16_t*)c->q, (const uint16_t*)kc, (const uint16_t*)vc, seq_stride, head_stride, ctx_len, \
                         max_ctx_host, tree_off, (const uint16_t*)k_new, (const uint16_t*)v_new, c->anc, m.Hq, m.Hkv,       \
-                        ctx_splits, rb, T, c->part_o, c->part_ml
+                        ctx_splits, rb, T, c->part_o, c->part_ml, B == 1 ? T : 0
     if (m.D == 128) hipLaunchKernelGGL(attn_partial_mfma_kernel<128>, grid, dim3(256), lds, s, EVICT_ATTN_ARGS);
     else hipLaunchKernelGGL(attn_partial_mfma_kernel<64>, grid, dim3(256), lds, s, EVICT_ATTN_ARGS);
 #undef EVICT_ATTN_ARGS
@@ -791,16 +872,26 @@ int launch_router(const evict_ctx* c, const void* gain, const void* wg, int T, c
   const size_t lds = router_lds_bytes(m);
   void* a_hn = aux ? aux->h_norm : nullptr;
   float* a_lg = aux ? aux->router_logits : nullptr;
-  int32_t* a_ix = aux ? aux->topk_idx : nullptr;
-  float* a_w = aux ? aux->topk_w : nullptr;
-  const int grid = (T + 15) / 16;
+  const int spw = router_strips_per_wg(m);
+  const dim3 grid((T + 15) / 16, (m.E / 16 + spw - 1) / spw);
   if (m.dtype == EVICT_BF16)
-    hipLaunchKernelGGL(router_kernel<BF16>, dim3(grid), dim3(kRouterThreads), lds, s, c->h, gain, (const u32x4*)wg, T, m.d,
-                       m.E, m.k, router_ksplit(m), m.rms_eps, c->h_norm, c->logits, c->topk_idx, c->topk_w, a_hn, a_lg, a_ix, a_w);
+    hipLaunchKernelGGL(router_logits_kernel<BF16>, grid, dim3(kRouterThreads), lds, s, c->h, gain, (const u32x4*)wg, T, m.d,
+                       m.E, spw, router_ksplit(m), m.rms_eps, c->h_norm, c->logits, a_hn, a_lg);
   else
-    hipLaunchKernelGGL(router_kernel<F32>, dim3(grid), dim3(kRouterThreads), lds, s, c->h, gain, (const u32x4*)wg, T, m.d,
-                       m.E, m.k, router_ksplit(m), m.rms_eps, c->h_norm, c->logits, c->topk_idx, c->topk_w, a_hn, a_lg, a_ix, a_w);
-  return launch_status("router_kernel");
+    hipLaunchKernelGGL(router_logits_kernel<F32>, grid, dim3(kRouterThreads), lds, s, c->h, gain, (const u32x4*)wg, T, m.d,
+                       m.E, spw, router_ksplit(m), m.rms_eps, c->h_norm, c->logits, a_hn, a_lg);
+  return launch_status("router_logits_kernel");
+}
+
+int launch_topk_union(const evict_ctx* c, int T, const evict_layer_aux* aux, hipStream_t s) {
+  const evict_model_desc& m = c->m;
+  int use_masks, union_ints;
+  const size_t lds = topk_union_lds_bytes(T, m.k, m.E, &use_masks, &union_ints);
+  EVICT_REQUIRE(lds <= 152 * 1024, EVICT_E_UNSUPPORTED, "top-k/union needs %zu bytes of LDS (limit 152 KiB)", lds);
+  hipLaunchKernelGGL(topk_union_kernel, dim3(1), dim3(kRouterThreads), lds, s, c->logits, T, m.E, m.k, use_masks,
+                     c->topk_idx, c->topk_w, aux ? aux->topk_idx : nullptr, aux ? aux->topk_w : nullptr, c->union_ids,
+                     c->union_count, c->hist, c->offsets, c->perm, c->inv, c->status, c->work, c->tok_of_pos, union_ints);
+  return launch_status("topk_union_kernel");
 }
 
 int launch_combine(const evict_ctx* c, int T, void* out, hipStream_t s) {

@@ -18,9 +18,7 @@ int launch_attention(const evict_ctx* c, const void* kc, const void* vc, long lo
                      const int32_t* ctx_len, int max_ctx_host, const int32_t* tree_off, int B, int T, const void* k_new,
                      const void* v_new, void* aux_out, hipStream_t s);
 int launch_router(const evict_ctx* c, const void* gain, const void* wg, int T, const evict_layer_aux* aux, hipStream_t s);
-int launch_union(int32_t* status, const int32_t* topk_idx, int T, int k, int E, int32_t* union_ids, int32_t* union_count,
-                 int32_t* hist, int32_t* offsets, int32_t* perm, int32_t* inv, WorkRec* work, int32_t* tok_of_pos,
-                 int32_t* sched, hipStream_t stream);
+int launch_topk_union(const evict_ctx* c, int T, const evict_layer_aux* aux, hipStream_t s);
 int launch_combine(const evict_ctx* c, int T, void* out, hipStream_t s);
 
 }  // namespace evict

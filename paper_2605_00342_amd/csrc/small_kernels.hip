@@ -5,7 +5,7 @@
 #include <string.h>
 
 #include "ctx.h"
-#include "gemm_stream.h"
+#include "union_device.h"
 
 namespace evict {
 
@@ -22,35 +22,6 @@ namespace {
 
 constexpr int kSelThreads = 256;
 constexpr int kMaxSel = EVICT_MAX_SELECT_NODES;
-
-__device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
-
-__device__ __forceinline__ int wave_incl_scan(int v) {
-  const int lane = lane_id();
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    int t = __shfl_up(v, o);
-    if (lane >= o) v += t;
-  }
-  return v;
-}
-
-// Exclusive prefix sum over the block (blockDim.x multiple of 64, <= 1024 threads).
-__device__ int block_excl_scan(int v, int* s_wave, int* total) {
-  const int lane = lane_id(), w = threadIdx.x >> 6, nw = blockDim.x >> 6;
-  int incl = wave_incl_scan(v);
-  __syncthreads();
-  if (lane == 63) s_wave[w] = incl;
-  __syncthreads();
-  int base = 0, tot = 0;
-  for (int i = 0; i < nw; ++i) {
-    int x = s_wave[i];
-    if (i < w) base += x;
-    tot += x;
-  }
-  *total = tot;
-  return base + incl - v;
-}
 
 // Kept-set compaction of one tree: nodes with rank < kstar, ascending node id; parents
 // re-indexed into the kept set. s_flag/s_new are LDS arrays of n ints.
@@ -91,9 +62,9 @@ __global__ __launch_bounds__(kSelThreads) void select_prefix_kernel(
     const int32_t* __restrict__ tree_off, const int32_t* __restrict__ parent, const float* __restrict__ prob,
     const float* __restrict__ cost, int kmax, int32_t* __restrict__ k_star, float* __restrict__ est_len,
     int32_t* __restrict__ order_out, float* __restrict__ psum_out, int32_t* rank_ws, int single, int32_t* keep,
-    int32_t* new_parent, int32_t* __restrict__ new_tree_off) {
+    int32_t* new_parent, int32_t* __restrict__ new_tree_off, int n_single) {
   __shared__ int s_par[kMaxSel];
-  __shared__ float s_score[kMaxSel];
+  __shared__ __attribute__((aligned(16))) float s_score[kMaxSel];
   __shared__ float s_sorted[kMaxSel];
   __shared__ float s_prob[kMaxSel];
   __shared__ float s_cost[kMaxSel];
@@ -105,8 +76,9 @@ __global__ __launch_bounds__(kSelThreads) void select_prefix_kernel(
   __shared__ int s_maxdep;
 
   const int b = blockIdx.x, tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
-  const int lo = tree_off[b];
-  int n = tree_off[b + 1] - lo;
+  // a single tree spans [0, T): its offsets need not be fetched
+  const int lo = n_single > 0 ? 0 : tree_off[b];
+  int n = n_single > 0 ? n_single : tree_off[b + 1] - lo;
   n = n < 1 ? 1 : (n > kMaxSel ? kMaxSel : n);
 
   if (tid == 0) s_maxdep = 0;
@@ -141,7 +113,16 @@ __global__ __launch_bounds__(kSelThreads) void select_prefix_kernel(
   for (int i = tid; i < n; i += kSelThreads) {
     const float si = s_score[i];
     int r = 0;
-    for (int j = 0; j < n; ++j) {
+    int j = 0;
+#pragma unroll 2
+    for (; j + 4 <= n; j += 4) {  // LDS broadcast reads, four scores at a time
+      const float4 s4 = *reinterpret_cast<const float4*>(&s_score[j]);
+      r += (s4.x > si || (s4.x == si && j < i)) ? 1 : 0;
+      r += (s4.y > si || (s4.y == si && j + 1 < i)) ? 1 : 0;
+      r += (s4.z > si || (s4.z == si && j + 2 < i)) ? 1 : 0;
+      r += (s4.w > si || (s4.w == si && j + 3 < i)) ? 1 : 0;
+    }
+    for (; j < n; ++j) {
       const float sj = s_score[j];
       r += (sj > si || (sj == si && j < i)) ? 1 : 0;
     }
@@ -278,121 +259,13 @@ __global__ __launch_bounds__(64) void accept_path_kernel(
 
 constexpr int kUnionThreads = 256;
 
-// Eq. 5 and the grouping it induces, one workgroup. Fast path (no expert repeated inside a
-// token, which is what TopK produces): per expert a bitmask over tokens, built with LDS
-// atomics; counts, ranks inside an expert and the stable order all follow from popcounts.
-// General path (repeats present, or masks too large for LDS): one thread per expert walks
-// the pairs in ascending pair id.
 __global__ __launch_bounds__(kUnionThreads) void expert_union_kernel(
     const int32_t* __restrict__ topk_idx, int T, int k, int E, int use_masks, int32_t* __restrict__ union_ids,
     int32_t* __restrict__ union_count, int32_t* __restrict__ hist, int32_t* __restrict__ offsets,
-    int32_t* __restrict__ perm, int32_t* __restrict__ inv, int32_t* __restrict__ status, WorkRec* __restrict__ work,
-    int32_t* __restrict__ tok_of_pos, int32_t* __restrict__ sched) {
+    int32_t* __restrict__ perm, int32_t* __restrict__ inv, int32_t* __restrict__ status) {
   extern __shared__ __attribute__((aligned(8))) int s_mem[];
-  const int P = T * k;
-  const int words = (T + 63) >> 6;
-  int* s_idx = s_mem;            // [P]
-  int* s_hist = s_mem + P;       // [E]
-  int* s_off = s_hist + E;       // [E + 1]
-  int* s_slot = s_off + E + 1;   // [E] union slot of each activated expert
-  unsigned long long* s_mask = reinterpret_cast<unsigned long long*>(s_mem + ((P + 3 * E + 2) & ~1));  // [E][words]
-  __shared__ int s_wave[16];
-  __shared__ int s_dup;
-  const int tid = threadIdx.x;
-  for (int e = tid; e < E; e += kUnionThreads) s_hist[e] = 0;
-  if (use_masks)
-    for (int i = tid; i < E * words; i += kUnionThreads) s_mask[i] = 0ull;
-  if (tid == 0) {
-    s_dup = 0;
-    if (sched) { sched[0] = 0; sched[1] = 0; }  // chunk counters of the two grouped GEMMs
-  }
-  __syncthreads();
-  bool bad = false;
-  for (int p = tid; p < P; p += kUnionThreads) {
-    int e = topk_idx[p];
-    if (e < 0 || e >= E) { bad = true; e = 0; }
-    s_idx[p] = e;
-    atomicAdd(&s_hist[e], 1);
-    if (use_masks) {
-      const int t = p / k;
-      const unsigned long long bit = 1ull << (t & 63);
-      const unsigned long long old = atomicOr(&s_mask[e * words + (t >> 6)], bit);
-      if (old & bit) s_dup = 1;  // the same expert twice in one token
-    }
-  }
-  if (bad && status) atomicOr(status, ST_BAD_EXPERT);
-  __syncthreads();
-  // exclusive scan of hist and of the activated flags, 4 consecutive experts per thread
-  int h[4], hs = 0, fs = 0;
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int e = tid * 4 + j;
-    h[j] = e < E ? s_hist[e] : 0;
-    hs += h[j];
-    fs += h[j] > 0 ? 1 : 0;
-  }
-  int tot_h, tot_f;
-  int base_h = block_excl_scan(hs, s_wave, &tot_h);
-  int base_f = block_excl_scan(fs, s_wave, &tot_f);
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int e = tid * 4 + j;
-    if (e < E) {
-      s_off[e] = base_h;
-      offsets[e] = base_h;
-      hist[e] = h[j];
-      if (h[j] > 0) {
-        union_ids[base_f] = e;
-        s_slot[e] = base_f;
-        if (work) { work[base_f].expert = e; work[base_f].p0 = base_h; work[base_f].ntok = h[j]; work[base_f].pad = 0; }
-      }
-    }
-    base_h += h[j];
-    base_f += h[j] > 0 ? 1 : 0;
-  }
-  for (int e = tot_f + tid; e < E; e += kUnionThreads) union_ids[e] = -1;
-  if (tid == 0) { offsets[E] = tot_h; union_count[0] = tot_f; }
-  __syncthreads();
-  if (use_masks && !s_dup) {
-    // position of pair (t, slot) inside its expert = number of earlier tokens routed there
-    for (int p = tid; p < P; p += kUnionThreads) {
-      const int e = s_idx[p], t = p / k;
-      const unsigned long long* m = s_mask + e * words;
-      int pos = s_off[e];
-      for (int wd = 0; wd < (t >> 6); ++wd) pos += __popcll(m[wd]);
-      pos += __popcll(m[t >> 6] & ((1ull << (t & 63)) - 1ull));
-      perm[pos] = p;
-      inv[p] = pos;
-      if (tok_of_pos) tok_of_pos[pos] = t;
-      if (work) {
-        const int r = pos - s_off[e], last = s_hist[e] - 1;
-        WorkRec* rec = work + s_slot[e];
-        if (r < kWorkToks) rec->tok[r] = t;
-        if (r == last)
-          for (int i = r + 1; i < kWorkToks; ++i) rec->tok[i] = t;  // padded columns repeat the last token
-      }
-    }
-  } else {
-    for (int e = tid; e < E; e += kUnionThreads) {
-      if (s_hist[e] == 0) continue;
-      int pos = s_off[e];
-      for (int p = 0; p < P; ++p) {
-        if (s_idx[p] == e) {
-          perm[pos] = p;
-          inv[p] = pos;
-          if (tok_of_pos) tok_of_pos[pos] = p / k;
-          if (work) {
-            const int r = pos - s_off[e];
-            WorkRec* rec = work + s_slot[e];
-            if (r < kWorkToks) rec->tok[r] = p / k;
-            if (r == s_hist[e] - 1)
-              for (int i = r + 1; i < kWorkToks; ++i) rec->tok[i] = p / k;
-          }
-          ++pos;
-        }
-      }
-    }
-  }
+  expert_union_body(s_mem, topk_idx, T, k, E, use_masks, union_ids, union_count, hist, offsets, perm, inv, status, nullptr,
+                    nullptr);
 }
 
 typedef __attribute__((ext_vector_type(4))) unsigned int probe_u32x4;
@@ -450,24 +323,15 @@ __global__ void gather_rows_kernel(const uint32_t* __restrict__ src, uint32_t* _
 
 }  // namespace
 
-int launch_union(int32_t* status, const int32_t* topk_idx, int T, int k, int E, int32_t* union_ids, int32_t* union_count,
-                 int32_t* hist, int32_t* offsets, int32_t* perm, int32_t* inv, WorkRec* work, int32_t* tok_of_pos,
-                 int32_t* sched, hipStream_t stream) {
-  EVICT_REQUIRE(topk_idx && union_ids && union_count && hist && offsets && perm && inv, EVICT_E_INVALID,
-                "evict_expert_union: null pointer argument");
-  EVICT_REQUIRE(T >= 1 && k >= 1 && E >= 1, EVICT_E_INVALID, "evict_expert_union: T, k, E must be >= 1");
-  EVICT_REQUIRE(k <= E, EVICT_E_INVALID, "evict_expert_union: k=%d exceeds E=%d", k, E);
-  EVICT_REQUIRE((int64_t)T * k <= 8192 && E <= 1024, EVICT_E_UNSUPPORTED,
-                "evict_expert_union: T*k=%lld (limit 8192), E=%d (limit 1024)", (long long)T * k, E);
+int union_mask_plan(int T, int k, int E, size_t* lds_bytes) {
   const int P = T * k;
   const size_t words = (size_t)(T + 63) / 64;
-  size_t lds = sizeof(int) * (size_t)((P + 3 * E + 2) & ~1);
+  size_t lds = sizeof(int) * union_lds_ints(P, E);
   const size_t mask_bytes = 8 * (size_t)E * words;
   const int use_masks = lds + mask_bytes <= 60 * 1024 ? 1 : 0;
   if (use_masks) lds += mask_bytes;
-  hipLaunchKernelGGL(expert_union_kernel, dim3(1), dim3(kUnionThreads), lds, stream, topk_idx, T, k, E, use_masks,
-                     union_ids, union_count, hist, offsets, perm, inv, status, work, tok_of_pos, sched);
-  return launch_status("expert_union_kernel");
+  *lds_bytes = lds;
+  return use_masks;
 }
 
 }  // namespace evict
@@ -509,7 +373,7 @@ int evict_select_prefix(evict_ctx*, const int32_t* tree_off, const int32_t* pare
   const int single = B == 1;
   hipLaunchKernelGGL(select_prefix_kernel, dim3(B), dim3(kSelThreads), 0, s, tree_off, parent, node_prob, cost, Kmax,
                      k_star, est_len, order, prefix_sum, new_parent /* rank workspace */, single, keep, new_parent,
-                     new_tree_off);
+                     new_tree_off, single ? T : 0);
   int rc = launch_status("select_prefix_kernel");
   if (rc) return rc;
   if (!single) {
@@ -535,8 +399,17 @@ int evict_accept_path(evict_ctx*, const int32_t* tree_off, const int32_t* parent
 int evict_expert_union(evict_ctx* ctx, const int32_t* topk_idx, int T, int k, int E, int32_t* union_ids,
                        int32_t* union_count, int32_t* hist, int32_t* offsets, int32_t* perm, int32_t* inv,
                        void* stream) {
-  return evict::launch_union(ctx ? ctx->status : nullptr, topk_idx, T, k, E, union_ids, union_count, hist, offsets, perm,
-                             inv, nullptr, nullptr, nullptr, (hipStream_t)stream);
+  EVICT_REQUIRE(topk_idx && union_ids && union_count && hist && offsets && perm && inv, EVICT_E_INVALID,
+                "evict_expert_union: null pointer argument");
+  EVICT_REQUIRE(T >= 1 && k >= 1 && E >= 1, EVICT_E_INVALID, "evict_expert_union: T, k, E must be >= 1");
+  EVICT_REQUIRE(k <= E, EVICT_E_INVALID, "evict_expert_union: k=%d exceeds E=%d", k, E);
+  EVICT_REQUIRE((int64_t)T * k <= 8192 && E <= 1024, EVICT_E_UNSUPPORTED,
+                "evict_expert_union: T*k=%lld (limit 8192), E=%d (limit 1024)", (long long)T * k, E);
+  size_t lds;
+  const int use_masks = union_mask_plan(T, k, E, &lds);
+  hipLaunchKernelGGL(expert_union_kernel, dim3(1), dim3(kUnionThreads), lds, (hipStream_t)stream, topk_idx, T, k, E,
+                     use_masks, union_ids, union_count, hist, offsets, perm, inv, ctx ? ctx->status : nullptr);
+  return launch_status("expert_union_kernel");
 }
 
 int evict_probe_read(const void* src, size_t bytes, void* sink, void* stream) {

@@ -1,0 +1,154 @@
+// Expert union (Eq. 5) and the token grouping it induces, as a device routine run by one
+// workgroup; shared by the stand-alone union kernel and the fused top-k + union kernel.
+#pragma once
+#include "ctx.h"
+#include "gemm_stream.h"
+
+namespace evict {
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
+
+__device__ __forceinline__ int wave_incl_scan(int v) {
+  const int lane = lane_id();
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    int t = __shfl_up(v, o);
+    if (lane >= o) v += t;
+  }
+  return v;
+}
+
+// Exclusive prefix sum over the block (blockDim.x multiple of 64, <= 1024 threads).
+__device__ int block_excl_scan(int v, int* s_wave, int* total) {
+  const int lane = lane_id(), w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  int incl = wave_incl_scan(v);
+  __syncthreads();
+  if (lane == 63) s_wave[w] = incl;
+  __syncthreads();
+  int base = 0, tot = 0;
+  for (int i = 0; i < nw; ++i) {
+    int x = s_wave[i];
+    if (i < w) base += x;
+    tot += x;
+  }
+  *total = tot;
+  return base + incl - v;
+}
+
+// LDS needed by expert_union_body, in ints (before the optional bitmasks).
+__host__ __device__ inline size_t union_lds_ints(int P, int E) { return (size_t)((P + 3 * E + 2) & ~1); }
+
+// Fast path (no expert repeated inside a token, which is what TopK produces): per expert a
+// bitmask over tokens, built with LDS atomics; counts, ranks inside an expert and the stable
+// order all follow from popcounts. General path (repeats present, or masks too large for
+// LDS): one thread per expert walks the pairs in ascending pair id.
+// topk_idx: global [T*k], or nullptr when s_mem[0..P) already holds the indices.
+__device__ inline void expert_union_body(
+    int* s_mem, const int32_t* __restrict__ topk_idx, int T, int k, int E, int use_masks, int32_t* __restrict__ union_ids,
+    int32_t* __restrict__ union_count, int32_t* __restrict__ hist, int32_t* __restrict__ offsets,
+    int32_t* __restrict__ perm, int32_t* __restrict__ inv, int32_t* __restrict__ status, WorkRec* __restrict__ work,
+    int32_t* __restrict__ tok_of_pos) {
+  const int P = T * k;
+  const int words = (T + 63) >> 6;
+  int* s_idx = s_mem;            // [P]
+  int* s_hist = s_mem + P;       // [E]
+  int* s_off = s_hist + E;       // [E + 1]
+  int* s_slot = s_off + E + 1;   // [E] union slot of each activated expert
+  unsigned long long* s_mask = reinterpret_cast<unsigned long long*>(s_mem + ((P + 3 * E + 2) & ~1));  // [E][words]
+  __shared__ int s_wave[16];
+  __shared__ int s_dup;
+  const int tid = threadIdx.x, nthreads = blockDim.x;
+  for (int e = tid; e < E; e += nthreads) s_hist[e] = 0;
+  if (use_masks)
+    for (int i = tid; i < E * words; i += nthreads) s_mask[i] = 0ull;
+  if (tid == 0) s_dup = 0;
+  __syncthreads();
+  bool bad = false;
+  for (int p = tid; p < P; p += nthreads) {
+    int e = topk_idx ? topk_idx[p] : s_idx[p];  // null: the caller has already filled s_idx
+    if (e < 0 || e >= E) { bad = true; e = 0; }
+    s_idx[p] = e;
+    atomicAdd(&s_hist[e], 1);
+    if (use_masks) {
+      const int t = p / k;
+      const unsigned long long bit = 1ull << (t & 63);
+      const unsigned long long old = atomicOr(&s_mask[e * words + (t >> 6)], bit);
+      if (old & bit) s_dup = 1;  // the same expert twice in one token
+    }
+  }
+  if (bad && status) atomicOr(status, ST_BAD_EXPERT);
+  __syncthreads();
+  // exclusive scan of hist and of the activated flags, 4 consecutive experts per thread
+  int h[4], hs = 0, fs = 0;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int e = tid * 4 + j;
+    h[j] = e < E ? s_hist[e] : 0;
+    hs += h[j];
+    fs += h[j] > 0 ? 1 : 0;
+  }
+  int tot_h, tot_f;
+  int base_h = block_excl_scan(hs, s_wave, &tot_h);
+  int base_f = block_excl_scan(fs, s_wave, &tot_f);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int e = tid * 4 + j;
+    if (e < E) {
+      s_off[e] = base_h;
+      offsets[e] = base_h;
+      hist[e] = h[j];
+      if (h[j] > 0) {
+        union_ids[base_f] = e;
+        s_slot[e] = base_f;
+        if (work) { work[base_f].expert = e; work[base_f].p0 = base_h; work[base_f].ntok = h[j]; work[base_f].pad = 0; }
+      }
+    }
+    base_h += h[j];
+    base_f += h[j] > 0 ? 1 : 0;
+  }
+  for (int e = tot_f + tid; e < E; e += nthreads) union_ids[e] = -1;
+  if (tid == 0) { offsets[E] = tot_h; union_count[0] = tot_f; }
+  __syncthreads();
+  if (use_masks && !s_dup) {
+    // position of pair (t, slot) inside its expert = number of earlier tokens routed there
+    for (int p = tid; p < P; p += nthreads) {
+      const int e = s_idx[p], t = p / k;
+      const unsigned long long* m = s_mask + e * words;
+      int pos = s_off[e];
+      for (int wd = 0; wd < (t >> 6); ++wd) pos += __popcll(m[wd]);
+      pos += __popcll(m[t >> 6] & ((1ull << (t & 63)) - 1ull));
+      perm[pos] = p;
+      inv[p] = pos;
+      if (tok_of_pos) tok_of_pos[pos] = t;
+      if (work) {
+        const int r = pos - s_off[e], last = s_hist[e] - 1;
+        WorkRec* rec = work + s_slot[e];
+        if (r < kWorkToks) rec->tok[r] = t;
+        if (r == last)
+          for (int i = r + 1; i < kWorkToks; ++i) rec->tok[i] = t;  // padded columns repeat the last token
+      }
+    }
+  } else {
+    for (int e = tid; e < E; e += nthreads) {
+      if (s_hist[e] == 0) continue;
+      int pos = s_off[e];
+      for (int p = 0; p < P; ++p) {
+        if (s_idx[p] == e) {
+          perm[pos] = p;
+          inv[p] = pos;
+          if (tok_of_pos) tok_of_pos[pos] = p / k;
+          if (work) {
+            const int r = pos - s_off[e];
+            WorkRec* rec = work + s_slot[e];
+            if (r < kWorkToks) rec->tok[r] = p / k;
+            if (r == s_hist[e] - 1)
+              for (int i = r + 1; i < kWorkToks; ++i) rec->tok[i] = p / k;
+          }
+          ++pos;
+        }
+      }
+    }
+  }
+}
+
+}  // namespace evict
