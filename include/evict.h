@@ -58,6 +58,7 @@ typedef struct evict_model_desc {
   int32_t n_shared;   /* always-on shared experts, not part of the union */
   float rms_eps;      /* RMSNorm epsilon */
   float rope_theta;   /* rotary base; 0 disables the rotation */
+  int32_t vocab;      /* vocabulary size for evict_lm_head_argmax (multiple of 16), 0 = no LM head */
 } evict_model_desc;
 
 /* Device pointers to one layer's weights. Matrices are in the packed streaming layout
@@ -125,6 +126,37 @@ int evict_verify_layer(evict_ctx* ctx, const evict_layer_weights* w,
                        const int32_t* ctx_len, int max_ctx_host,
                        const void* x_in, void* x_out, void* k_new, void* v_new,
                        const evict_layer_aux* aux, void* stream);
+
+/* The same pass through a stack of n_layers decoder layers (the target's forward over the tree,
+ * Sec. 2.1): layers [host] array of n_layers weight structs; k_caches, v_caches [host] arrays
+ * of n_layers [dev] cache pointers with the layout and strides of evict_verify_layer;
+ * k_new, v_new [host] arrays of n_layers [dev] output pointers [T, Hkv, D]. The tree is
+ * prepared once; x_out must not alias x_in. */
+int evict_verify_stack(evict_ctx* ctx, const evict_layer_weights* layers, int n_layers,
+                       const int32_t* tree_off, const int32_t* parent, int B, int T,
+                       const void* const* k_caches, const void* const* v_caches, int64_t kv_seq_stride,
+                       int64_t kv_head_stride, const int32_t* ctx_len, int max_ctx_host,
+                       const void* x_in, void* x_out, void* const* k_new, void* const* v_new, void* stream);
+
+/* Target token after every node: final RMSNorm, logits = W_lm x, next = argmax over the
+ * vocabulary, lowest index on equal values (the p(. | prefix of node) of Sec. 2.1 at
+ * temperature 0; feeds evict_accept_path).
+ *   x [dev] [T, d]; g_final [dev] [d]; wlm_packed [dev] from evict_pack_dense(W_lm [vocab, d]);
+ *   next [dev] int32[T]; best_logit [dev] float[T], nullable; x_norm_out [dev] [T, d] storage
+ *   dtype, nullable: the normalised input the logits were formed from. Needs vocab > 0 in the
+ *   model description given to evict_create. */
+int evict_lm_head_argmax(evict_ctx* ctx, const void* x, const void* g_final, const void* wlm_packed, int T,
+                         int32_t* next, float* best_logit, void* x_norm_out, void* stream);
+
+/* Offline cost profiling (Sec. 3.2.3): for every verification length k = 1..Kmax, the mean
+ * latency in milliseconds of evict_verify_stack on the first k nodes of one tree (B = 1; any
+ * prefix of a topologically numbered tree is a tree), `reps` timed runs after one warm-up,
+ * written to cost_host [host] float[Kmax+1] (cost_host[0] = 0). Synchronises the stream. The
+ * table is what evict_select_prefix consumes as C(k) (upload it). */
+int evict_profile_cost(evict_ctx* ctx, const evict_layer_weights* layers, int n_layers, const int32_t* tree_off,
+                       const int32_t* parent, int Kmax, const void* const* k_caches, const void* const* v_caches,
+                       int64_t kv_head_stride, const int32_t* ctx_len, int max_ctx_host, const void* x_in, void* x_out,
+                       void* const* k_new, void* const* v_new, int reps, float* cost_host, void* stream);
 
 /* Union of activated experts over all verified nodes (Eq. 5) and the grouping it induces.
  *   topk_idx [dev] int32[T, k] with values in [0, E).

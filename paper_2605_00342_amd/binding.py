@@ -15,7 +15,8 @@ __all__ = [
     "evict_version", "evict_last_error", "evict_create", "evict_destroy", "evict_packed_bytes", "evict_pack_dense",
     "evict_pack_qkv", "evict_pack_experts", "evict_verify_layer", "evict_expert_union", "evict_accept_path",
     "evict_select_prefix", "evict_gather_rows", "evict_validate_trees_host", "evict_device_status",
-    "evict_stage_timing", "evict_stage_times", "evict_probe_read", "evict_probe_copy", "evict_tune", "STAGES", "EXPORTS",
+    "evict_stage_timing", "evict_stage_times", "evict_probe_read", "evict_probe_copy", "evict_tune", "evict_verify_stack", "evict_lm_head_argmax",
+    "evict_profile_cost", "STAGES", "EXPORTS",
 ]
 
 EVICT_F32, EVICT_BF16 = 0, 1
@@ -26,7 +27,8 @@ EXPORTS = [
     "evict_version", "evict_last_error", "evict_create", "evict_destroy", "evict_packed_bytes", "evict_pack_dense",
     "evict_pack_qkv", "evict_pack_experts", "evict_verify_layer", "evict_expert_union", "evict_accept_path",
     "evict_select_prefix", "evict_gather_rows", "evict_validate_trees_host", "evict_device_status",
-    "evict_stage_timing", "evict_stage_times", "evict_probe_read", "evict_probe_copy", "evict_tune",
+    "evict_stage_timing", "evict_stage_times", "evict_probe_read", "evict_probe_copy", "evict_tune", "evict_verify_stack", "evict_lm_head_argmax",
+    "evict_profile_cost",
 ]
 STAGES = ["prep", "qkv", "attention", "oproj", "router", "union", "gateup", "down", "shared", "combine"]
 
@@ -40,7 +42,7 @@ class EvictError(RuntimeError):
 class ModelDesc(C.Structure):
     _fields_ = [("dtype", C.c_int32), ("d", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32), ("D", C.c_int32),
                 ("E", C.c_int32), ("k", C.c_int32), ("F", C.c_int32), ("n_shared", C.c_int32),
-                ("rms_eps", C.c_float), ("rope_theta", C.c_float)]
+                ("rms_eps", C.c_float), ("rope_theta", C.c_float), ("vocab", C.c_int32)]
 
 
 class LayerWeights(C.Structure):
@@ -90,6 +92,11 @@ def load():
     lib.evict_device_status.argtypes = [vp, C.POINTER(C.c_int32), vp]
     lib.evict_stage_timing.argtypes = [vp, i32]
     lib.evict_tune.argtypes = [vp, C.c_char_p, i32]
+    lib.evict_verify_stack.argtypes = [vp, C.POINTER(LayerWeights), i32, vp, vp, i32, i32, C.POINTER(vp), C.POINTER(vp), i64, i64,
+                                       vp, i32, vp, vp, C.POINTER(vp), C.POINTER(vp), vp]
+    lib.evict_lm_head_argmax.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp]
+    lib.evict_profile_cost.argtypes = [vp, C.POINTER(LayerWeights), i32, vp, vp, i32, C.POINTER(vp), C.POINTER(vp), i64, vp, i32,
+                                       vp, vp, C.POINTER(vp), C.POINTER(vp), i32, C.POINTER(C.c_float), vp]
     lib.evict_probe_read.argtypes = [vp, sz, vp, vp]
     lib.evict_probe_copy.argtypes = [vp, vp, sz, vp]
     lib.evict_stage_times.argtypes = [vp, C.POINTER(C.c_float)]
@@ -209,3 +216,39 @@ def evict_probe_copy(src, dst, nbytes: int) -> None:
 
 def evict_tune(ctx, key: str, value: int) -> None:
     _check(load().evict_tune(ctx, key.encode(), value))
+
+
+def _ptr_array(tensors):
+    arr = (C.c_void_p * len(tensors))(*[t.data_ptr() if t is not None else None for t in tensors])
+    return arr
+
+
+def _layer_array(layers):
+    arr = (LayerWeights * len(layers))()
+    for i, lw in enumerate(layers):
+        arr[i] = lw
+    return arr
+
+
+def evict_verify_stack(ctx, layers, tree_off, parent, B, T, k_caches, v_caches, kv_seq_stride, kv_head_stride, ctx_len,
+                       max_ctx_host, x_in, x_out, k_new, v_new) -> None:
+    """layers: list of LayerWeights; k_caches, v_caches, k_new, v_new: lists of device tensors, one per layer."""
+    _check(load().evict_verify_stack(ctx, _layer_array(layers), len(layers), _p(tree_off), _p(parent), B, T,
+                                     _ptr_array(k_caches), _ptr_array(v_caches), kv_seq_stride, kv_head_stride,
+                                     _p(ctx_len), max_ctx_host, _p(x_in), _p(x_out), _ptr_array(k_new), _ptr_array(v_new),
+                                     _stream()))
+
+
+def evict_lm_head_argmax(ctx, x, g_final, wlm_packed, T, next_out, best_logit=None, x_norm_out=None) -> None:
+    _check(load().evict_lm_head_argmax(ctx, _p(x), _p(g_final), _p(wlm_packed), T, _p(next_out), _p(best_logit),
+                                       _p(x_norm_out), _stream()))
+
+
+def evict_profile_cost(ctx, layers, tree_off, parent, Kmax, k_caches, v_caches, kv_head_stride, ctx_len, max_ctx_host,
+                       x_in, x_out, k_new, v_new, reps: int):
+    """Returns the profiled cost table as a list of Kmax+1 floats (milliseconds, entry 0 unused)."""
+    buf = (C.c_float * (Kmax + 1))()
+    _check(load().evict_profile_cost(ctx, _layer_array(layers), len(layers), _p(tree_off), _p(parent), Kmax,
+                                     _ptr_array(k_caches), _ptr_array(v_caches), kv_head_stride, _p(ctx_len), max_ctx_host,
+                                     _p(x_in), _p(x_out), _ptr_array(k_new), _ptr_array(v_new), reps, buf, _stream()))
+    return [float(v) for v in buf]

@@ -27,6 +27,7 @@ int check_model(const evict_model_desc* m) {
   EVICT_REQUIRE(m->D == 64 || m->D == 128, EVICT_E_UNSUPPORTED, "head dimension %d (supported: 64, 128)", m->D);
   EVICT_REQUIRE(m->d % 16 == 0 && m->F % 16 == 0 && (m->d * eb) % 64 == 0 && (m->F * eb) % 64 == 0,
                 EVICT_E_UNSUPPORTED, "d=%d and F=%d must be multiples of 16 rows and of 64 bytes", m->d, m->F);
+  EVICT_REQUIRE(m->vocab >= 0 && m->vocab % 16 == 0, EVICT_E_UNSUPPORTED, "vocab=%d must be a non-negative multiple of 16", m->vocab);
   EVICT_REQUIRE(m->k <= 64 && m->E <= 1024 && m->E % 16 == 0, EVICT_E_UNSUPPORTED,
                 "k=%d (limit 64), E=%d (limit 1024, multiple of 16)", m->k, m->E);
   return EVICT_OK;
@@ -101,6 +102,14 @@ int evict_create(evict_ctx** out, const evict_model_desc* m, int max_tokens, int
   A(&c.tok_of_pos, T * k * 4);
   A(&c.act, T * k * F * eb);
   A(&c.y, T * k * d * 4);
+  c.lm_val = nullptr;
+  c.lm_idx = nullptr;
+  if (m->vocab) {
+    A(&c.lm_val, (size_t)(m->vocab / 16) * T * 4);
+    A(&c.lm_idx, (size_t)(m->vocab / 16) * T * 4);
+  }
+  A(&c.stack_buf[0], T * d * eb);
+  A(&c.stack_buf[1], T * d * eb);
   c.act_sh = nullptr;
   c.y_sh = nullptr;
   if (m->n_shared) {
@@ -120,6 +129,11 @@ int evict_create(evict_ctx** out, const evict_model_desc* m, int max_tokens, int
   for (int cu : {4, 2}) if ((m->d / 16) % cu == 0) { c.moe_chunk_down = cu; break; }
   c.attn_row_blocks = 0;
   c.timed_once = 0;
+  c.prof_ev[0] = c.prof_ev[1] = nullptr;
+  for (int i = 0; !rc && i < 2; ++i) {
+    he = hipEventCreate(&c.prof_ev[i]);
+    if (he != hipSuccess) { set_error("hipEventCreate failed: %s", hipGetErrorString(he)); rc = EVICT_E_HIP; }
+  }
   int n_ev = 0;
   for (; !rc && n_ev <= EVICT_N_STAGES; ++n_ev) {
     he = hipEventCreate(&c.ev[n_ev]);
@@ -127,6 +141,7 @@ int evict_create(evict_ctx** out, const evict_model_desc* m, int max_tokens, int
   }
   if (rc) {
     for (int i = 0; i < n_ev; ++i) (void)hipEventDestroy(c.ev[i]);
+    for (int i = 0; i < 2; ++i) if (c.prof_ev[i]) (void)hipEventDestroy(c.prof_ev[i]);
     for (void* p : o->owned) (void)hipFree(p);
     delete o;
     return rc;
@@ -140,6 +155,7 @@ int evict_destroy(evict_ctx* ctx) {
   evict_ctx_owner* o = reinterpret_cast<evict_ctx_owner*>(ctx);  // c is the first member
   int rc = EVICT_OK;
   for (int i = 0; i <= EVICT_N_STAGES; ++i) (void)hipEventDestroy(ctx->ev[i]);
+  for (int i = 0; i < 2; ++i) (void)hipEventDestroy(ctx->prof_ev[i]);
   for (void* p : o->owned) {
     hipError_t e = hipFree(p);
     if (e != hipSuccess) { set_error("hipFree failed: %s", hipGetErrorString(e)); rc = EVICT_E_HIP; }
@@ -204,10 +220,9 @@ int evict_device_status(evict_ctx* ctx, int32_t* status_host, void* stream) {
   return EVICT_OK;
 }
 
-int evict_verify_layer(evict_ctx* ctx, const evict_layer_weights* w, const int32_t* tree_off, const int32_t* parent, int B,
-                       int T, const void* k_cache, const void* v_cache, int64_t kv_seq_stride, int64_t kv_head_stride,
-                       const int32_t* ctx_len, int max_ctx_host, const void* x_in, void* x_out, void* k_new, void* v_new,
-                       const evict_layer_aux* aux, void* stream) {
+static int check_layer_args(evict_ctx* ctx, const evict_layer_weights* w, const int32_t* tree_off, const int32_t* parent, int B,
+                            int T, const void* k_cache, const void* v_cache, int64_t kv_seq_stride, int64_t kv_head_stride,
+                            const int32_t* ctx_len, int max_ctx_host, const void* x_in, void* x_out, void* k_new, void* v_new) {
   EVICT_REQUIRE(ctx && w && tree_off && parent && ctx_len && x_in && x_out && k_new && v_new, EVICT_E_INVALID,
                 "evict_verify_layer: null pointer argument");
   const evict_model_desc& m = ctx->m;
@@ -229,13 +244,21 @@ int evict_verify_layer(evict_ctx* ctx, const evict_layer_weights* w, const int32
                 EVICT_E_INVALID, "evict_verify_layer: pointers must be 16-byte aligned");
   EVICT_REQUIRE(x_in != x_out, EVICT_E_INVALID, "evict_verify_layer: x_out must not alias x_in");
 
+  return EVICT_OK;
+}
+
+static int verify_layer_impl(evict_ctx* ctx, const evict_layer_weights* w, const int32_t* tree_off, const int32_t* parent, int B,
+                             int T, const void* k_cache, const void* v_cache, int64_t kv_seq_stride, int64_t kv_head_stride,
+                             const int32_t* ctx_len, int max_ctx_host, const void* x_in, void* x_out, void* k_new, void* v_new,
+                             const evict_layer_aux* aux, int tree_ready, void* stream) {
+  const evict_model_desc& m = ctx->m;
   hipStream_t s = (hipStream_t)stream;
   const int eb = elem_bytes(m.dtype);
   const int HqD = m.Hq * m.D;
   const bool timing = ctx->timing != 0;
 #define EVICT_MARK(i_) do { if (timing) EVICT_HIP_CHECK(hipEventRecord(ctx->ev[i_], s)); } while (0)
   EVICT_MARK(0);
-  int rc = launch_prep(ctx, tree_off, parent, B, T, ctx_len, max_ctx_host, x_in, w->g_attn, s);
+  int rc = launch_prep(ctx, tree_off, parent, B, T, ctx_len, max_ctx_host, x_in, w->g_attn, tree_ready, s);
   if (rc) return rc;
   EVICT_MARK(1);
 
@@ -325,6 +348,7 @@ int evict_verify_layer(evict_ctx* ctx, const evict_layer_weights* w, const int32
     a.out0 = ctx->y;
     a.ldo = m.d;
     a.chunk_units = ctx->moe_chunk_down;
+    a.prefetch = ctx->moe_prefetch;
     rc = launch_gemm(m.dtype, EPI_F32, a, nt_exp, ctx->moe_grid, s);
     if (rc) return rc;
   }
@@ -361,6 +385,94 @@ int evict_verify_layer(evict_ctx* ctx, const evict_layer_weights* w, const int32
   EVICT_MARK(10);
   if (timing) ctx->timed_once = 1;
 #undef EVICT_MARK
+  return EVICT_OK;
+}
+
+int evict_verify_layer(evict_ctx* ctx, const evict_layer_weights* w, const int32_t* tree_off, const int32_t* parent, int B,
+                       int T, const void* k_cache, const void* v_cache, int64_t kv_seq_stride, int64_t kv_head_stride,
+                       const int32_t* ctx_len, int max_ctx_host, const void* x_in, void* x_out, void* k_new, void* v_new,
+                       const evict_layer_aux* aux, void* stream) {
+  int rc = check_layer_args(ctx, w, tree_off, parent, B, T, k_cache, v_cache, kv_seq_stride, kv_head_stride, ctx_len,
+                            max_ctx_host, x_in, x_out, k_new, v_new);
+  if (rc) return rc;
+  return verify_layer_impl(ctx, w, tree_off, parent, B, T, k_cache, v_cache, kv_seq_stride, kv_head_stride, ctx_len,
+                           max_ctx_host, x_in, x_out, k_new, v_new, aux, 0, stream);
+}
+
+int evict_verify_stack(evict_ctx* ctx, const evict_layer_weights* layers, int n_layers, const int32_t* tree_off,
+                       const int32_t* parent, int B, int T, const void* const* k_caches, const void* const* v_caches,
+                       int64_t kv_seq_stride, int64_t kv_head_stride, const int32_t* ctx_len, int max_ctx_host,
+                       const void* x_in, void* x_out, void* const* k_new, void* const* v_new, void* stream) {
+  EVICT_REQUIRE(ctx && layers && k_new && v_new, EVICT_E_INVALID, "evict_verify_stack: null pointer argument");
+  EVICT_REQUIRE(n_layers >= 1, EVICT_E_INVALID, "evict_verify_stack: n_layers=%d", n_layers);
+  EVICT_REQUIRE(max_ctx_host == 0 || (k_caches && v_caches), EVICT_E_INVALID, "evict_verify_stack: null KV cache arrays");
+  for (int l = 0; l < n_layers; ++l) {
+    const void* in = l == 0 ? x_in : ctx->stack_buf[(l - 1) & 1];
+    void* out = l == n_layers - 1 ? x_out : ctx->stack_buf[l & 1];
+    const void* kc = k_caches ? k_caches[l] : nullptr;
+    const void* vc = v_caches ? v_caches[l] : nullptr;
+    int rc = check_layer_args(ctx, layers + l, tree_off, parent, B, T, kc, vc, kv_seq_stride, kv_head_stride, ctx_len,
+                              max_ctx_host, in, out, k_new[l], v_new[l]);
+    if (rc) return rc;
+    rc = verify_layer_impl(ctx, layers + l, tree_off, parent, B, T, kc, vc, kv_seq_stride, kv_head_stride, ctx_len,
+                           max_ctx_host, in, out, k_new[l], v_new[l], nullptr, l > 0, stream);
+    if (rc) return rc;
+  }
+  return EVICT_OK;
+}
+
+int evict_lm_head_argmax(evict_ctx* ctx, const void* x, const void* g_final, const void* wlm_packed, int T, int32_t* next,
+                         float* best_logit, void* x_norm_out, void* stream) {
+  EVICT_REQUIRE(ctx && x && g_final && wlm_packed && next, EVICT_E_INVALID, "evict_lm_head_argmax: null pointer argument");
+  const evict_model_desc& m = ctx->m;
+  EVICT_REQUIRE(m.vocab > 0, EVICT_E_INVALID, "evict_lm_head_argmax: the context was created without a vocabulary size");
+  EVICT_REQUIRE(T >= 1 && T <= ctx->max_tokens, EVICT_E_INVALID, "evict_lm_head_argmax: T=%d outside [1,%d]", T, ctx->max_tokens);
+  EVICT_REQUIRE(aligned16(x) && aligned16(wlm_packed), EVICT_E_INVALID, "evict_lm_head_argmax: pointers must be 16-byte aligned");
+  hipStream_t s = (hipStream_t)stream;
+  const int eb = elem_bytes(m.dtype);
+  int rc = launch_prep(ctx, nullptr, nullptr, 1, T, nullptr, 0, x, g_final, 1, s);  // final RMSNorm only
+  if (rc) return rc;
+  if (x_norm_out) EVICT_HIP_CHECK(hipMemcpyAsync(x_norm_out, ctx->x_norm, (size_t)T * m.d * eb, hipMemcpyDeviceToDevice, s));
+  GemmArgs a = {};
+  a.W = (const u32x4*)wlm_packed;
+  a.n_strips = m.vocab / 16;
+  a.nkb = m.d * eb / 64;
+  a.X = ctx->x_norm;
+  a.ldx_bytes = (long long)m.d * eb;
+  a.T = T;
+  a.out0 = ctx->lm_val;
+  a.out1 = ctx->lm_idx;
+  a.ldo = T;
+  a.dense_tiles = (T + 15) / 16;
+  rc = launch_gemm(m.dtype, EPI_ARGMAX, a, 1, ((a.n_strips + 7) / 8) * 8 * a.dense_tiles, s);
+  if (rc) return rc;
+  return launch_argmax_reduce(ctx->lm_val, ctx->lm_idx, a.n_strips, T, T, next, best_logit, s);
+}
+
+int evict_profile_cost(evict_ctx* ctx, const evict_layer_weights* layers, int n_layers, const int32_t* tree_off,
+                       const int32_t* parent, int Kmax, const void* const* k_caches, const void* const* v_caches,
+                       int64_t kv_head_stride, const int32_t* ctx_len, int max_ctx_host, const void* x_in, void* x_out,
+                       void* const* k_new, void* const* v_new, int reps, float* cost_host, void* stream) {
+  EVICT_REQUIRE(ctx && cost_host, EVICT_E_INVALID, "evict_profile_cost: null pointer argument");
+  EVICT_REQUIRE(Kmax >= 1 && Kmax <= ctx->max_tokens && Kmax <= EVICT_MAX_TREE_NODES, EVICT_E_INVALID,
+                "evict_profile_cost: Kmax=%d outside [1, min(max_tokens, %d)]", Kmax, EVICT_MAX_TREE_NODES);
+  EVICT_REQUIRE(reps >= 1, EVICT_E_INVALID, "evict_profile_cost: reps must be >= 1");
+  hipStream_t s = (hipStream_t)stream;
+  cost_host[0] = 0.0f;
+  for (int k = 1; k <= Kmax; ++k) {
+    // B = 1: the kernels take the tree size from T, so the first k nodes are verified as a tree of their own
+    for (int r = -1; r < reps; ++r) {
+      if (r == 0) EVICT_HIP_CHECK(hipEventRecord(ctx->prof_ev[0], s));
+      int rc = evict_verify_stack(ctx, layers, n_layers, tree_off, parent, 1, k, k_caches, v_caches, 0, kv_head_stride,
+                                  ctx_len, max_ctx_host, x_in, x_out, k_new, v_new, stream);
+      if (rc) return rc;
+    }
+    EVICT_HIP_CHECK(hipEventRecord(ctx->prof_ev[1], s));
+    EVICT_HIP_CHECK(hipEventSynchronize(ctx->prof_ev[1]));
+    float ms = 0.0f;
+    EVICT_HIP_CHECK(hipEventElapsedTime(&ms, ctx->prof_ev[0], ctx->prof_ev[1]));
+    cost_host[k] = ms / (float)reps;
+  }
   return EVICT_OK;
 }
 

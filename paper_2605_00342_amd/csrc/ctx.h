@@ -40,6 +40,10 @@ struct evict_ctx {
   int32_t* tok_of_pos;   // [T*k] token of each grouped position
   void* act;             // [T*k][F] storage dtype
   float* y;              // [T*k][d]
+  float* lm_val;         // [vocab/16][T] best logit per strip and token
+  int32_t* lm_idx;       // [vocab/16][T]
+  void* stack_buf[2];    // [T][d] ping-pong hidden states of evict_verify_stack
+  hipEvent_t prof_ev[2]; // evict_profile_cost
   void* act_sh;          // [n_shared][T][F]
   float* y_sh;           // [n_shared][T][d]
 };

@@ -16,7 +16,7 @@
 
 namespace evict {
 
-enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_F32 = 3 };
+enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_F32 = 3, EPI_ARGMAX = 4 };
 
 // One union slot of the device-side work list: the expert, where its tokens sit in the
 // grouped order, how many there are, and the token ids of the first few positions (so that
@@ -43,8 +43,8 @@ struct GemmArgs {
   int T;                 // dense: token rows
   int dense_tiles;       // dense: workgroups per strip, each taking 16*NT tokens
   int prefetch;          // host-side choice of the kernel variant (weight-load stages), 0 = default
-  void* out0;            // QKV: q; RESID: h; SWIGLU: act; F32: y
-  void* out1;            // QKV: k_new
+  void* out0;            // QKV: q; RESID: h; SWIGLU: act; F32: y; ARGMAX: best value per (strip, token)
+  void* out1;            // QKV: k_new; ARGMAX: row index of the best value per (strip, token)
   void* out2;            // QKV: v_new
   long long ldo;         // elements between output rows (RESID / SWIGLU / F32)
   const void* resid;     // RESID: residual rows, same layout as out0
@@ -56,13 +56,15 @@ constexpr int kGemmWaves = 8;
 constexpr int kGemmThreads = kGemmWaves * 64;
 
 // KBW: 1 KiB blocks a wavefront takes per step (EXACT: every step has exactly KBW, no masking);
-// PF: steps of weight loads kept in flight; NT: 16-token tiles held in registers.
-template <typename ST, int NT, int KBW, int PF, int EPI, bool EXACT>
+// PF: steps of weight loads kept in flight; NT: 16-token tiles held in registers; IS: strips
+// taken per step (one partial-tile exchange per IS strips).
+template <typename ST, int NT, int KBW, int PF, int EPI, bool EXACT, int IS = 1>
 __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 4 : 2))) void gemm_stream_kernel(const GemmArgs a) {
   constexpr int SPU = (EPI == EPI_SWIGLU) ? 2 : 1;  // strips per unit of work
   // expert weights are read exactly once per call: keep them out of the caches' way
-  constexpr bool kStreamOnce = (EPI == EPI_SWIGLU || EPI == EPI_F32);
-  __shared__ f32x4 s_part[2][kGemmWaves][NT][64];
+  constexpr bool kStreamOnce = (EPI == EPI_SWIGLU || EPI == EPI_F32 || EPI == EPI_ARGMAX);
+  static_assert(EPI != EPI_SWIGLU || IS == 1, "gate/up strips are exchanged one at a time");
+  __shared__ f32x4 s_part[2][kGemmWaves][IS * NT][64];
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wavefront index, known uniform
@@ -88,16 +90,20 @@ __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(NT
       ntok = rec->ntok;
       wbase += (long long)rec->expert * a.group_stride;
     }
-    const int nsteps = nitems * nchunks;
+    const int nsteps = (nitems / IS) * nchunks;  // nitems is a multiple of IS (host-checked)
 
     const int tok_end = ntok < tok_limit ? ntok : tok_limit;
     for (int tok0 = tok_begin; tok0 < tok_end; tok0 += 16 * NT) {
-      u32x4 A[PF][KBW];
+      u32x4 A[PF][IS * KBW];
       u32x4 Bf[NT][KBW];
-      f32x4 acc[NT];
+      f32x4 acc[IS][NT];
       f32x4 gate[NT];
 #pragma unroll
-      for (int t = 0; t < NT; ++t) { acc[t] = f32x4{0, 0, 0, 0}; gate[t] = f32x4{0, 0, 0, 0}; }
+      for (int t = 0; t < NT; ++t) {
+        gate[t] = f32x4{0, 0, 0, 0};
+#pragma unroll
+        for (int i = 0; i < IS; ++i) acc[i][t] = f32x4{0, 0, 0, 0};
+      }
 
       // block range of this wavefront inside chunk c: [b0, b0 + nb)
       auto range = [&](int c, int& b0, int& nb) {
@@ -111,14 +117,17 @@ __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(NT
           nb = c * 64 + ((w + 1) * cb) / kGemmWaves - b0;
         }
       };
-      auto issue = [&](u32x4(&dst)[KBW], int step) {
+      auto issue = [&](u32x4(&dst)[IS * KBW], int step) {
         const int it = step / nchunks, c = step - it * nchunks;
         int b0, nb;
         range(c, b0, nb);
-        const u32x4* p = wbase + ((long long)(strip0 + it) * nkb + b0) * 64 + lane;
 #pragma unroll
-        for (int j = 0; j < KBW; ++j)
-          if (EXACT || j < nb) dst[j] = kStreamOnce ? __builtin_nontemporal_load(p + j * 64) : p[j * 64];
+        for (int i = 0; i < IS; ++i) {
+          const u32x4* p = wbase + ((long long)(strip0 + it * IS + i) * nkb + b0) * 64 + lane;
+#pragma unroll
+          for (int j = 0; j < KBW; ++j)
+            if (EXACT || j < nb) dst[i * KBW + j] = kStreamOnce ? __builtin_nontemporal_load(p + j * 64) : p[j * 64];
+        }
       };
       // weights first: their addresses need nothing but the expert id
 #pragma unroll
@@ -161,32 +170,56 @@ __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(NT
             int b0, nb;
             range(c, b0, nb);
 #pragma unroll
-            for (int j = 0; j < KBW; ++j)
-              if (EXACT || j < nb) {
+            for (int i = 0; i < IS; ++i)
 #pragma unroll
-                for (int t = 0; t < NT; ++t) acc[t] = mfma_block<ST>(A[r][j], Bf[t][j], acc[t]);
-              }
+              for (int j = 0; j < KBW; ++j)
+                if (EXACT || j < nb) {
+#pragma unroll
+                  for (int t = 0; t < NT; ++t) acc[i][t] = mfma_block<ST>(A[r][i * KBW + j], Bf[t][j], acc[i][t]);
+                }
             if (step + PF < nsteps) issue(A[r], step + PF);
             if (c == nchunks - 1) {
               // strip finished: exchange partial tiles, one wavefront reduces and stores
 #pragma unroll
-              for (int t = 0; t < NT; ++t) {
-                s_part[parity][w][t][lane] = acc[t];
-                acc[t] = f32x4{0, 0, 0, 0};
-              }
-              lds_barrier();
-              const int strip = strip0 + it;
-              const int reducer = ((unit_in_grp + it / SPU) & (kGemmWaves - 1));
-              if (w == reducer) {
+              for (int i = 0; i < IS; ++i)
 #pragma unroll
                 for (int t = 0; t < NT; ++t) {
-                  f32x4 sum = s_part[parity][0][t][lane];
+                  s_part[parity][w][i * NT + t][lane] = acc[i][t];
+                  acc[i][t] = f32x4{0, 0, 0, 0};
+                }
+              lds_barrier();
+              // tile q = (strip i of the step, token tile t) is summed by wavefront (rbase + q) % 8
+              const int rbase = unit_in_grp + it / SPU;
 #pragma unroll
-                  for (int ww = 1; ww < kGemmWaves; ++ww) sum += s_part[parity][ww][t][lane];
+              for (int q = 0; q < IS * NT; ++q) {
+                if (w == ((rbase + q) & (kGemmWaves - 1))) {
+                  const int t = q % NT;
+                  const int strip = strip0 + it * IS + q / NT;
+                  f32x4 sum = s_part[parity][0][q][lane];
+#pragma unroll
+                  for (int ww = 1; ww < kGemmWaves; ++ww) sum += s_part[parity][ww][q][lane];
                   const int col = tok0 + t * 16 + (lane & 15);
                   const bool valid = col < ntok;
                   const int m0 = (lane >> 4) * 4;  // first of this lane's 4 rows in the strip
-                  if (EPI == EPI_F32) {
+                  if (EPI == EPI_ARGMAX) {
+                    // best of this lane's 4 rows (lowest row on equal values), then across the 4
+                    // lanes that hold the other rows of the same token
+                    float bv = sum[0];
+                    int bi = strip * 16 + m0;
+#pragma unroll
+                    for (int i = 1; i < 4; ++i)
+                      if (sum[i] > bv) { bv = sum[i]; bi = strip * 16 + m0 + i; }
+#pragma unroll
+                    for (int o = 16; o <= 32; o <<= 1) {
+                      const float ov = __shfl_xor(bv, o);
+                      const int oi = __shfl_xor(bi, o);
+                      if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+                    }
+                    if (valid && lane < 16) {
+                      ((float*)a.out0)[(long long)strip * a.ldo + col] = bv;
+                      ((int*)a.out1)[(long long)strip * a.ldo + col] = bi;
+                    }
+                  } else if (EPI == EPI_F32) {
                     if (valid) {
                       const long long orow = a.grouped ? (p0 + col) : col;
                       *reinterpret_cast<f32x4*>((float*)a.out0 + orow * a.ldo + strip * 16 + m0) = sum;

@@ -49,7 +49,7 @@ __global__ __launch_bounds__(256) void prep_kernel(const int32_t* __restrict__ t
                                                    float eps, float theta, int D, uint64_t* __restrict__ anc,
                                                    int32_t* __restrict__ depth, int32_t* __restrict__ seq_of,
                                                    float* __restrict__ rope_cs, void* __restrict__ x_norm,
-                                                   int32_t* __restrict__ status, int n_single) {
+                                                   int32_t* __restrict__ status, int n_single, int norm_only) {
   constexpr int EB = ST::kBytes;
   constexpr int CE = 16 / EB;
   constexpr int MAXC = 4;  // 16-byte chunks of the row per thread (d <= 256*CE*MAXC)
@@ -68,6 +68,45 @@ __global__ __launch_bounds__(256) void prep_kernel(const int32_t* __restrict__ t
       raw[i] = *reinterpret_cast<const u32x4*>((const char*)x + ((size_t)t * d + c) * EB);
       graw[i] = *reinterpret_cast<const u32x4*>((const char*)gain + (size_t)c * EB);
     }
+  }
+  if (norm_only) {
+    // the tree is already prepared (later layers of a stack, final norm): RMSNorm only
+    float ss = 0.0f;
+#pragma unroll
+    for (int k = 0; k < MAXC; ++k)
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (EB == 2) {
+          const float a = __uint_as_float(raw[k][u] << 16), bb = __uint_as_float(raw[k][u] & 0xFFFF0000u);
+          ss += a * a + bb * bb;
+        } else {
+          const float a = __uint_as_float(raw[k][u]);
+          ss += a * a;
+        }
+      }
+    ss = wave_sum(ss);
+    if ((tid & 63) == 0) s_red[tid >> 6] = ss;
+    __syncthreads();
+    const float rinv = 1.0f / sqrtf((s_red[0] + s_red[1] + s_red[2] + s_red[3]) / (float)d + eps);
+#pragma unroll
+    for (int k = 0; k < MAXC; ++k) {
+      const int c = (tid + 256 * k) * CE;
+      if (c < d) {
+        u32x4 packed;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          if (EB == 2) {
+            const float a = __uint_as_float(raw[k][u] << 16) * rinv * __uint_as_float(graw[k][u] << 16);
+            const float bb = __uint_as_float(raw[k][u] & 0xFFFF0000u) * rinv * __uint_as_float(graw[k][u] & 0xFFFF0000u);
+            packed[u] = (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(bb) << 16);
+          } else {
+            packed[u] = __float_as_uint(__uint_as_float(raw[k][u]) * rinv * __uint_as_float(graw[k][u]));
+          }
+        }
+        *reinterpret_cast<u32x4*>((char*)x_norm + ((size_t)t * d + c) * EB) = packed;
+      }
+    }
+    return;
   }
   if (tid == 0) s_b = 0;
   __syncthreads();
@@ -675,6 +714,39 @@ __global__ __launch_bounds__(kRouterThreads) void topk_union_kernel(
 }
 
 // ------------------------------------------------------------------------------------
+// LM head, second step: per token, the best (value, row) over the per-strip candidates;
+// equal values go to the lower row (vocabulary) index. One workgroup per token.
+// ------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void argmax_reduce_kernel(const float* __restrict__ val, const int32_t* __restrict__ idx,
+                                                            int nstrips, int ld, int32_t* __restrict__ next,
+                                                            float* __restrict__ best_out) {
+  __shared__ float s_v[4];
+  __shared__ int s_i[4];
+  const int t = blockIdx.x, tid = threadIdx.x;
+  float bv = -INFINITY;
+  int bi = 0x7fffffff;
+  for (int s = tid; s < nstrips; s += 256) {
+    const float v = val[(size_t)s * ld + t];
+    const int i = idx[(size_t)s * ld + t];
+    if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
+  }
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) {
+    const float ov = __shfl_xor(bv, o);
+    const int oi = __shfl_xor(bi, o);
+    if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+  }
+  if ((tid & 63) == 0) { s_v[tid >> 6] = bv; s_i[tid >> 6] = bi; }
+  __syncthreads();
+  if (tid == 0) {
+    for (int w = 1; w < 4; ++w)
+      if (s_v[w] > bv || (s_v[w] == bv && s_i[w] < bi)) { bv = s_v[w]; bi = s_i[w]; }
+    next[t] = bi;
+    if (best_out) best_out[t] = bv;
+  }
+}
+
+// ------------------------------------------------------------------------------------
 // un-permute + weighted combine + residual (+ shared experts), fixed slot order
 // ------------------------------------------------------------------------------------
 template <typename ST>
@@ -719,7 +791,12 @@ int launch_gemm_nt(const GemmArgs& a, int grid, hipStream_t s) {
     if (a.prefetch == 2) EVICT_GEMM_LAUNCH(8, 2, true);
     else EVICT_GEMM_LAUNCH(8, 1, true);
   } else if (bf16 && nkb == 24) {
-    EVICT_GEMM_LAUNCH(3, 4, true);
+    // 3 blocks per wavefront per strip: take 4 strips per exchange step when the chunking allows
+    if (EPI == EPI_F32 && NT == 1 && a.grouped && a.chunk_units % 4 == 0 && a.prefetch != 2)
+      hipLaunchKernelGGL((gemm_stream_kernel<ST, NT, 3, 1, EPI, true, (EPI == EPI_F32 && NT == 1) ? 4 : 1>), dim3(grid),
+                         dim3(kGemmThreads), 0, s, a);
+    else
+      EVICT_GEMM_LAUNCH(3, 4, true);
   } else if (need <= 4) {
     EVICT_GEMM_LAUNCH(4, 4, false);
   } else {
@@ -746,6 +823,7 @@ int launch_gemm(int dtype, int epi, const GemmArgs& a, int nt, int grid, hipStre
     EVICT_GEMM_CASE(EPI_RESID)
     EVICT_GEMM_CASE(EPI_SWIGLU)
     EVICT_GEMM_CASE(EPI_F32)
+    EVICT_GEMM_CASE(EPI_ARGMAX)
   }
 #undef EVICT_GEMM_CASE
   set_error("unknown epilogue %d", epi);
@@ -766,14 +844,14 @@ int launch_pack(const void* src, long long src_group_bytes, int rows, int cols, 
 }
 
 int launch_prep(const evict_ctx* c, const int32_t* tree_off, const int32_t* parent, int B, int T, const int32_t* ctx_len,
-                int max_ctx, const void* x, const void* gain, hipStream_t s) {
+                int max_ctx, const void* x, const void* gain, int norm_only, hipStream_t s) {
   const evict_model_desc& m = c->m;
   if (m.dtype == EVICT_BF16)
     hipLaunchKernelGGL(prep_kernel<BF16>, dim3(T), dim3(256), 0, s, tree_off, parent, B, ctx_len, max_ctx, x, gain, m.d,
-                       m.rms_eps, m.rope_theta, m.D, c->anc, c->depth, c->seq_of, c->rope_cs, c->x_norm, c->status, B == 1 ? T : 0);
+                       m.rms_eps, m.rope_theta, m.D, c->anc, c->depth, c->seq_of, c->rope_cs, c->x_norm, c->status, B == 1 ? T : 0, norm_only);
   else
     hipLaunchKernelGGL(prep_kernel<F32>, dim3(T), dim3(256), 0, s, tree_off, parent, B, ctx_len, max_ctx, x, gain, m.d,
-                       m.rms_eps, m.rope_theta, m.D, c->anc, c->depth, c->seq_of, c->rope_cs, c->x_norm, c->status, B == 1 ? T : 0);
+                       m.rms_eps, m.rope_theta, m.D, c->anc, c->depth, c->seq_of, c->rope_cs, c->x_norm, c->status, B == 1 ? T : 0, norm_only);
   return launch_status("prep_kernel");
 }
 
@@ -892,6 +970,12 @@ int launch_topk_union(const evict_ctx* c, int T, const evict_layer_aux* aux, hip
                      c->topk_idx, c->topk_w, aux ? aux->topk_idx : nullptr, aux ? aux->topk_w : nullptr, c->union_ids,
                      c->union_count, c->hist, c->offsets, c->perm, c->inv, c->status, c->work, c->tok_of_pos, union_ints);
   return launch_status("topk_union_kernel");
+}
+
+int launch_argmax_reduce(const float* val, const int32_t* idx, int nstrips, int ld, int T, int32_t* next, float* best_out,
+                         hipStream_t s) {
+  hipLaunchKernelGGL(argmax_reduce_kernel, dim3(T), dim3(256), 0, s, val, idx, nstrips, ld, next, best_out);
+  return launch_status("argmax_reduce_kernel");
 }
 
 int launch_combine(const evict_ctx* c, int T, void* out, hipStream_t s) {

@@ -11,7 +11,7 @@ int launch_gemm(int dtype, int epi, const GemmArgs& a, int nt, int grid, hipStre
 int launch_pack(const void* src, long long src_group_bytes, int rows, int cols, int dtype, void* dst, int dst_strip0,
                 int dst_strip_step, long long dst_group_strips, int groups, int head_dim, hipStream_t s);
 int launch_prep(const evict_ctx* c, const int32_t* tree_off, const int32_t* parent, int B, int T, const int32_t* ctx_len,
-                int max_ctx, const void* x, const void* gain, hipStream_t s);
+                int max_ctx, const void* x, const void* gain, int norm_only, hipStream_t s);
 int kernels_setup(const evict_model_desc& m);
 int attn_splits_for(int max_ctx);
 int launch_attention(const evict_ctx* c, const void* kc, const void* vc, long long seq_stride, long long head_stride,
@@ -19,6 +19,8 @@ int launch_attention(const evict_ctx* c, const void* kc, const void* vc, long lo
                      const void* v_new, void* aux_out, hipStream_t s);
 int launch_router(const evict_ctx* c, const void* gain, const void* wg, int T, const evict_layer_aux* aux, hipStream_t s);
 int launch_topk_union(const evict_ctx* c, int T, const evict_layer_aux* aux, hipStream_t s);
+int launch_argmax_reduce(const float* val, const int32_t* idx, int nstrips, int ld, int T, int32_t* next, float* best_out,
+                         hipStream_t s);
 int launch_combine(const evict_ctx* c, int T, void* out, hipStream_t s);
 
 }  // namespace evict

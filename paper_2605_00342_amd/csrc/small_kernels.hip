@@ -257,7 +257,7 @@ __global__ __launch_bounds__(64) void accept_path_kernel(
   if (lane == 0) { path_len[b] = len; bonus[b] = s_next[cur]; }
 }
 
-constexpr int kUnionThreads = 256;
+constexpr int kUnionThreads = 1024;  // >= the largest supported E: one expert per thread in the scan
 
 __global__ __launch_bounds__(kUnionThreads) void expert_union_kernel(
     const int32_t* __restrict__ topk_idx, int T, int k, int E, int use_masks, int32_t* __restrict__ union_ids,

@@ -38,6 +38,7 @@ __device__ int block_excl_scan(int v, int* s_wave, int* total) {
 // LDS needed by expert_union_body, in ints (before the optional bitmasks).
 __host__ __device__ inline size_t union_lds_ints(int P, int E) { return (size_t)((P + 3 * E + 2) & ~1); }
 
+// Requires blockDim.x >= E (one expert per thread in the scan).
 // Fast path (no expert repeated inside a token, which is what TopK produces): per expert a
 // bitmask over tokens, built with LDS atomics; counts, ranks inside an expert and the stable
 // order all follow from popcounts. General path (repeats present, or masks too large for
@@ -78,33 +79,22 @@ __device__ inline void expert_union_body(
   }
   if (bad && status) atomicOr(status, ST_BAD_EXPERT);
   __syncthreads();
-  // exclusive scan of hist and of the activated flags, 4 consecutive experts per thread
-  int h[4], hs = 0, fs = 0;
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int e = tid * 4 + j;
-    h[j] = e < E ? s_hist[e] : 0;
-    hs += h[j];
-    fs += h[j] > 0 ? 1 : 0;
-  }
-  int tot_h, tot_f;
-  int base_h = block_excl_scan(hs, s_wave, &tot_h);
-  int base_f = block_excl_scan(fs, s_wave, &tot_f);
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int e = tid * 4 + j;
-    if (e < E) {
-      s_off[e] = base_h;
-      offsets[e] = base_h;
-      hist[e] = h[j];
-      if (h[j] > 0) {
-        union_ids[base_f] = e;
-        s_slot[e] = base_f;
-        if (work) { work[base_f].expert = e; work[base_f].p0 = base_h; work[base_f].ntok = h[j]; work[base_f].pad = 0; }
-      }
+  // one exclusive scan for both the pair counts and the activated flags (packed: count in the
+  // low 16 bits, flag above; T*k <= 8192 and E <= 1024 fit), one expert per thread
+  const int hcount = tid < E ? s_hist[tid] : 0;
+  int tot;
+  const int base = block_excl_scan(hcount | ((hcount > 0 ? 1 : 0) << 16), s_wave, &tot);
+  const int base_h = base & 0xFFFF, base_f = base >> 16;
+  const int tot_h = tot & 0xFFFF, tot_f = tot >> 16;
+  if (tid < E) {
+    s_off[tid] = base_h;
+    offsets[tid] = base_h;
+    hist[tid] = hcount;
+    if (hcount > 0) {
+      union_ids[base_f] = tid;
+      s_slot[tid] = base_f;
+      if (work) { work[base_f].expert = tid; work[base_f].p0 = base_h; work[base_f].ntok = hcount; work[base_f].pad = 0; }
     }
-    base_h += h[j];
-    base_f += h[j] > 0 ? 1 : 0;
   }
   for (int e = tot_f + tid; e < E; e += nthreads) union_ids[e] = -1;
   if (tid == 0) { offsets[E] = tot_h; union_count[0] = tot_f; }

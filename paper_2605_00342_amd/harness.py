@@ -13,9 +13,9 @@ def storage_code(dtype: str) -> int:
     return ev.EVICT_BF16 if dtype == "bf16" else ev.EVICT_F32
 
 
-def model_desc(cfg) -> ev.ModelDesc:
+def model_desc(cfg, vocab: int = 0) -> ev.ModelDesc:
     return ev.ModelDesc(storage_code(cfg.dtype), cfg.d, cfg.Hq, cfg.Hkv, cfg.D, cfg.E, cfg.k, cfg.F, cfg.n_shared,
-                        cfg.eps, cfg.theta)
+                        cfg.eps, cfg.theta, vocab)
 
 
 def to_dev(a: np.ndarray, dtype: str, device="cuda:0") -> torch.Tensor:
@@ -36,10 +36,11 @@ def dev_i32(a, device="cuda:0") -> torch.Tensor:
 class DeviceLayer:
     """Context + packed weights of one layer on the GPU."""
 
-    def __init__(self, cfg, W, max_tokens, max_batch, max_ctx, device="cuda:0"):
+    def __init__(self, cfg, W, max_tokens, max_batch, max_ctx, device="cuda:0", vocab=0, ctx=None):
         self.cfg, self.device = cfg, device
-        self.desc = model_desc(cfg)
-        self.ctx = ev.evict_create(self.desc, max_tokens, max_batch, max_ctx)
+        self.desc = model_desc(cfg, vocab)
+        self.owns_ctx = ctx is None
+        self.ctx = ev.evict_create(self.desc, max_tokens, max_batch, max_ctx) if ctx is None else ctx
         tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
         eb = 2 if cfg.dtype == "bf16" else 4
         code = storage_code(cfg.dtype)
@@ -78,9 +79,9 @@ class DeviceLayer:
                                        self.ws_down.data_ptr() if cfg.n_shared else None)
 
     def close(self):
-        if self.ctx:
+        if self.ctx and self.owns_ctx:
             ev.evict_destroy(self.ctx)
-            self.ctx = None
+        self.ctx = None
 
     def __del__(self):
         try:
@@ -145,3 +146,12 @@ class DeviceCase:
             r.update({k: to_host(v) for k, v in self.a.items()})
             r["union_count"] = int(r["union_count"][0])
         return r
+
+
+def pack_lm_head(cfg, w_lm: np.ndarray, device="cuda:0") -> torch.Tensor:
+    """Upload and pack W_lm [vocab, d] into the streaming layout."""
+    raw = to_dev(w_lm, cfg.dtype, device)
+    out = torch.empty_like(raw).reshape(-1)
+    ev.evict_pack_dense(storage_code(cfg.dtype), raw, w_lm.shape[0], w_lm.shape[1], out)
+    torch.cuda.synchronize()
+    return out

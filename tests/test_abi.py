@@ -47,10 +47,10 @@ def test_host_side_argument_checks_need_no_gpu():
     assert lib.evict_expert_union(None, one, 4, 9, 8, one, one, one, one, one, one, None) == 1      # k > E
     assert lib.evict_expert_union(None, one, 4096, 8, 128, one, one, one, one, one, one, None) == 2  # too large
     assert lib.evict_gather_rows(one, one, 6, one, one, one, 1, 1, None) == 1                       # row_bytes % 4
-    d = ev.ModelDesc(ev.EVICT_BF16, 2048, 32, 5, 128, 128, 8, 768, 0, 1e-6, 1e6)
+    d = ev.ModelDesc(ev.EVICT_BF16, 2048, 32, 5, 128, 128, 8, 768, 0, 1e-6, 1e6, 0)
     h = ctypes.c_void_p()
     assert lib.evict_create(ctypes.byref(h), ctypes.byref(d), 32, 1, 2048) == 1                      # Hq % Hkv
-    d = ev.ModelDesc(ev.EVICT_BF16, 2048, 32, 4, 96, 128, 8, 768, 0, 1e-6, 1e6)
+    d = ev.ModelDesc(ev.EVICT_BF16, 2048, 32, 4, 96, 128, 8, 768, 0, 1e-6, 1e6, 0)
     assert lib.evict_create(ctypes.byref(h), ctypes.byref(d), 32, 1, 2048) == 2                      # head dim
     assert lib.evict_pack_dense(ev.EVICT_BF16, one, 24, 64, ctypes.c_void_p(32), None) == 2          # rows % 16
     assert ev.evict_packed_bytes(ev.EVICT_BF16, 2048, 768) == 2048 * 768 * 2

@@ -1,0 +1,214 @@
+"""GPU parity of the multi-layer pass, the LM head + argmax, the whole selection -> verification ->
+acceptance pipeline on truncated trees, and the on-device cost profile, against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+import synth
+from oracle import evict_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+ev = pytest.importorskip("paper_2605_00342_amd")
+from paper_2605_00342_amd import harness  # noqa: E402
+
+DEV = "cuda:0"
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def rel_l2(a, b):
+    return float(np.linalg.norm(np.asarray(a, np.float64) - b) / max(np.linalg.norm(b), 1e-30))
+
+
+def make_stack(cfg_name, n_layers, n, L, seed, batch=1, L_list=None, tree="auto"):
+    case = synth.make_case(cfg_name, n=n, L=L, seed=seed, batch=batch, L_list=L_list, tree=tree)
+    cfg = case["cfg"]
+    Ws = [case["W"]] + [synth.layer_weights(cfg, synth.philox(seed, 1000 + l)) for l in range(1, n_layers)]
+    Ks, Vs = [case["K"]], [case["V"]]
+    for l in range(1, n_layers):
+        kv = [synth.kv_cache(cfg, int(Lb), synth.philox(seed, 2000 + 10 * l + b)) for b, Lb in enumerate(case["ctx_len"])]
+        Ks.append([k for k, _ in kv]); Vs.append([v for _, v in kv])
+    return case, Ws, Ks, Vs
+
+
+class DeviceStack:
+    def __init__(self, case, Ws, Ks, Vs, vocab=0, max_tokens=None):
+        cfg = case["cfg"]
+        T = int(case["tree_off"][-1])
+        self.cfg, self.T, self.B = cfg, T, len(case["ctx_len"])
+        self.layers = [harness.DeviceLayer(cfg, Ws[0], max_tokens or T, self.B, int(max(case["ctx_len"])), vocab=vocab)]
+        self.ctx = self.layers[0].ctx
+        for W in Ws[1:]:
+            self.layers.append(harness.DeviceLayer(cfg, W, 0, 0, 0, ctx=self.ctx))
+        self.cases = []
+        for l in range(len(Ws)):
+            c = dict(case); c["K"], c["V"] = Ks[l], Vs[l]
+            self.cases.append(harness.DeviceCase(c, with_aux=False))
+        self.dc = self.cases[0]
+
+    def run(self, tree_off=None, parent=None, T=None, x=None, out=None):
+        dc = self.dc
+        ev.evict_verify_stack(self.ctx, [l.weights for l in self.layers], tree_off if tree_off is not None else dc.tree_off,
+                              parent if parent is not None else dc.parent, self.B, T or self.T,
+                              [c.k_cache for c in self.cases], [c.v_cache for c in self.cases], dc.seq_stride, dc.head_stride,
+                              dc.ctx_len, dc.max_ctx, x if x is not None else dc.x, out if out is not None else dc.out,
+                              [c.k_new for c in self.cases], [c.v_new for c in self.cases])
+
+    def close(self):
+        self.layers[0].close()
+
+
+def oracle_stack(case, Ws, Ks, Vs, tree_off=None, parent=None, x=None):
+    cfg = case["cfg"]
+    x = case["x"] if x is None else x
+    outs = []
+    for l in range(len(Ws)):
+        r = orc.verify_layer(cfg, Ws[l], case["tree_off"] if tree_off is None else tree_off,
+                             case["parent"] if parent is None else parent, x, Ks[l], Vs[l], case["ctx_len"])
+        outs.append(r)
+        x = r["out"]
+    return outs
+
+
+@pytest.mark.parametrize("cfg_name,n,L,seed", [("tiny", 9, 40, 40), ("mini_bf16", 20, 70, 41)])
+def test_stack_of_layers_matches_oracle(cfg_name, n, L, seed):
+    case, Ws, Ks, Vs = make_stack(cfg_name, 3, n, L, seed)
+    st = DeviceStack(case, Ws, Ks, Vs)
+    st.run()
+    torch.cuda.synchronize()
+    ref = oracle_stack(case, Ws, Ks, Vs)
+    tol = TOL[case["cfg"].dtype]
+    assert rel_l2(harness.to_host(st.dc.out), ref[-1]["out"]) < tol * 1.5
+    for l in range(3):
+        assert rel_l2(harness.to_host(st.cases[l].k_new), ref[l]["k_new"]) < tol * 1.5
+    assert ev.evict_device_status(st.ctx) == 0
+    # the stack equals the same layers called one by one
+    x = st.dc.x
+    for l in range(3):
+        o = torch.zeros_like(st.dc.out)
+        c = st.cases[l]
+        ev.evict_verify_layer(st.ctx, st.layers[l].weights, c.tree_off, c.parent, 1, n, c.k_cache, c.v_cache, c.seq_stride,
+                              c.head_stride, c.ctx_len, c.max_ctx, x, o, c.k_new, c.v_new, None)
+        x = o
+    torch.cuda.synchronize()
+    assert torch.equal(x, st.dc.out)
+    st.close()
+
+
+@pytest.mark.parametrize("cfg_name,vocab,T,seed", [("tiny", 1008, 8, 50), ("mini_bf16", 4000, 37, 51), ("mini_bf16", 160, 1, 52)])
+def test_lm_head_argmax_matches_oracle(cfg_name, vocab, T, seed):
+    cfg = synth.CONFIGS[cfg_name]
+    g = synth.philox(seed, 1)
+    x = synth.store(g.standard_normal((T, cfg.d)), cfg.dtype)
+    gain = synth.store(1.0 + 0.1 * g.standard_normal(cfg.d), cfg.dtype)
+    w_lm = synth.store(g.standard_normal((vocab, cfg.d)) * 0.05, cfg.dtype)
+    if T > 4:
+        w_lm[7] = w_lm[3]            # two identical rows: equal logits must go to the lower index
+    ctx = ev.evict_create(harness.model_desc(cfg, vocab), T, 1, 16)
+    wp = harness.pack_lm_head(cfg, w_lm)
+    nxt = torch.zeros(T, dtype=torch.int32, device=DEV)
+    best = torch.zeros(T, device=DEV)
+    xd, gd = harness.to_dev(x, cfg.dtype), harness.to_dev(gain, cfg.dtype)
+    xn = torch.zeros_like(xd)
+    ev.evict_lm_head_argmax(ctx, xd, gd, wp, T, nxt, best, xn)
+    torch.cuda.synchronize()
+    # stage-wise: logits from the normalised input the GPU used; near-ties excluded and counted
+    logits = (np.asarray(harness.to_host(xn), np.float64) @ np.asarray(w_lm, np.float64).T).astype(np.float32)
+    srt = -np.sort(-logits.astype(np.float64), axis=-1)
+    uniq_gap = np.array([np.min(np.diff(np.unique(-row))[:1]) if len(np.unique(row)) > 1 else np.inf for row in logits])
+    ok = uniq_gap >= 1e-4
+    assert (~ok).sum() <= max(1, T // 8)
+    ref = np.argmax(logits, axis=-1)     # first (lowest) index on equal values
+    assert np.array_equal(nxt.cpu().numpy()[ok], ref[ok])
+    np.testing.assert_allclose(best.cpu().numpy(), logits.max(-1), rtol=0, atol=2e-5)
+    # end to end against the oracle's own normalisation
+    ref2, _ = orc.lm_head_argmax(x, gain, w_lm, cfg.eps, act=cfg.dtype)
+    assert rel_l2(harness.to_host(xn), orc.handoff(orc.rmsnorm(x, gain, cfg.eps), cfg.dtype)) < TOL[cfg.dtype]
+    assert (ref2 != nxt.cpu().numpy()).sum() <= max(1, T // 8)
+    ev.evict_destroy(ctx)
+
+
+def test_select_verify_lmhead_accept_pipeline_on_truncated_trees():
+    """EVICT selection first, the truncated trees verified in one batched pass, greedy acceptance
+    on the target's tokens: every step against the oracle fed with the previous GPU step."""
+    cfg_name, vocab, seed = "mini_bf16", 512, 60
+    case, Ws, Ks, Vs = make_stack(cfg_name, 2, 24, 0, seed, batch=3, L_list=[33, 70, 5], tree="bfs")
+    cfg = case["cfg"]
+    T, B = int(case["tree_off"][-1]), 3
+    st = DeviceStack(case, Ws, Ks, Vs, vocab=vocab)
+    i32 = torch.int32
+    cost = synth.cost_linear_in_union(24, cfg.E, cfg.k, a=1.0, b=0.4)
+    ks = torch.zeros(B, dtype=i32, device=DEV); keep = torch.zeros(T, dtype=i32, device=DEV)
+    npar = torch.zeros(T, dtype=i32, device=DEV); noff = torch.zeros(B + 1, dtype=i32, device=DEV); est = torch.zeros(B, device=DEV)
+    ev.evict_select_prefix(None, st.dc.tree_off, st.dc.parent, torch.from_numpy(case["q"]).to(DEV), B, T,
+                           torch.from_numpy(cost).to(DEV), 24, ks, keep, npar, noff, est)
+    x2 = torch.zeros_like(st.dc.x)
+    eb = 2
+    ev.evict_gather_rows(st.dc.x, x2, cfg.d * eb, st.dc.tree_off, noff, keep, B, T)
+    torch.cuda.synchronize()
+    noff_h, keep_h, npar_h = noff.cpu().numpy(), keep.cpu().numpy(), npar.cpu().numpy()
+    T2 = int(noff_h[B])
+    # oracle selection
+    xs, pars = [], []
+    for b in range(B):
+        lo, hi = case["tree_off"][b], case["tree_off"][b + 1]
+        ref = orc.select_prefix(case["parents"][b], case["q"][lo:hi], cost, 24)
+        assert ks[b].item() == ref["k_star"]
+        assert np.array_equal(keep_h[noff_h[b]:noff_h[b + 1]], ref["keep"])
+        assert np.array_equal(npar_h[noff_h[b]:noff_h[b + 1]], ref["new_parent"])
+        xs.append(case["x"][lo:hi][ref["keep"]]); pars.append(ref["new_parent"])
+    assert 3 <= T2 < T
+    x_trunc = np.concatenate(xs)
+    assert np.array_equal(harness.to_host(x2)[:T2], x_trunc)
+    # verify the truncated trees
+    out = torch.zeros_like(st.dc.out)
+    st.run(tree_off=noff, parent=npar, T=T2, x=x2, out=out)
+    off2, par2 = synth.concat_trees(pars)
+    ref_layers = oracle_stack(case, Ws, Ks, Vs, tree_off=off2, parent=par2, x=x_trunc)
+    torch.cuda.synchronize()
+    assert rel_l2(harness.to_host(out)[:T2], ref_layers[-1]["out"]) < 3e-2
+    # target tokens and acceptance
+    g = synth.philox(seed, 5)
+    gain = synth.store(np.ones(cfg.d), cfg.dtype)
+    w_lm = synth.store(g.standard_normal((vocab, cfg.d)) * 0.05, cfg.dtype)
+    wp = harness.pack_lm_head(cfg, w_lm)
+    nxt = torch.zeros(T, dtype=i32, device=DEV)
+    ev.evict_lm_head_argmax(st.ctx, out, harness.to_dev(gain, cfg.dtype), wp, T2, nxt, None, None)
+    torch.cuda.synchronize()
+    nxt_h = nxt.cpu().numpy()[:T2]
+    tok = np.concatenate([synth.plant_draft_tokens(pars[b], nxt_h[off2[b]:off2[b + 1]], vocab, g, 0.8) for b in range(B)]).astype(np.int32)
+    path = torch.zeros(B, 16, dtype=i32, device=DEV); plen = torch.zeros(B, dtype=i32, device=DEV); bonus = torch.zeros(B, dtype=i32, device=DEV)
+    ev.evict_accept_path(None, noff, npar, harness.dev_i32(tok), nxt, B, path, 16, plen, bonus)
+    torch.cuda.synchronize()
+    for b in range(B):
+        rp, rb = orc.accept_path(pars[b], tok[off2[b]:off2[b + 1]], nxt_h[off2[b]:off2[b + 1]])
+        assert plen[b].item() == len(rp) and bonus[b].item() == rb
+        assert np.array_equal(path.cpu().numpy()[b, :len(rp)], rp)
+    assert ev.evict_device_status(st.ctx) == 0
+    st.close()
+
+
+def test_profile_cost_table_and_selection_from_it():
+    case, Ws, Ks, Vs = make_stack("mini_bf16", 2, 16, 64, 70)
+    st = DeviceStack(case, Ws, Ks, Vs)
+    dc = st.dc
+    cost = ev.evict_profile_cost(st.ctx, [l.weights for l in st.layers], dc.tree_off, dc.parent, 16,
+                                 [c.k_cache for c in st.cases], [c.v_cache for c in st.cases], dc.head_stride, dc.ctx_len,
+                                 dc.max_ctx, dc.x, dc.out, [c.k_new for c in st.cases], [c.v_new for c in st.cases], 3)
+    assert len(cost) == 17 and cost[0] == 0.0
+    assert all(np.isfinite(c) and 0.0 < c < 50.0 for c in cost[1:])
+    # the profiled table drives the on-device selection exactly as the oracle's
+    cost_np = np.asarray(cost, np.float32); cost_np[0] = 1.0
+    i32 = torch.int32
+    ks = torch.zeros(1, dtype=i32, device=DEV); keep = torch.zeros(16, dtype=i32, device=DEV)
+    npar = torch.zeros(16, dtype=i32, device=DEV); noff = torch.zeros(2, dtype=i32, device=DEV); est = torch.zeros(1, device=DEV)
+    ev.evict_select_prefix(None, dc.tree_off, dc.parent, torch.from_numpy(case["q"]).to(DEV), 1, 16,
+                           torch.from_numpy(cost_np).to(DEV), 16, ks, keep, npar, noff, est)
+    torch.cuda.synchronize()
+    assert ks.item() == orc.select_prefix(case["parent"], case["q"], cost_np, 16)["k_star"]
+    # a prefix of the tree verified alone equals the profile's k-node case
+    st.run(T=5)
+    torch.cuda.synchronize()
+    ref = oracle_stack(case, Ws, Ks, Vs, tree_off=np.array([0, 5], np.int32), parent=case["parent"][:5], x=case["x"][:5])
+    assert rel_l2(harness.to_host(dc.out)[:5], ref[-1]["out"]) < 3e-2
+    st.close()
