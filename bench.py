@@ -41,7 +41,60 @@ def parse():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     ap.add_argument("--seed", type=int, default=1000)
     ap.add_argument("--tune", action="append", default=[], help="key=value launch-shape knob (evict_tune)")
+    ap.add_argument("--sweep", action="store_true",
+                    help="not the default line: one JSON line per (N, sigma) point, N in 1..128, sigma in {0.2, 0.5, 1.0}")
     return ap.parse_args()
+
+
+def sweep(args):
+    """Latency, tokens/s and roofline fraction against tree size and union size (one layer)."""
+    import torch
+
+    import synth
+    import paper_2605_00342_amd as ev
+    from paper_2605_00342_amd import harness
+
+    cfg = synth.CONFIGS["qwen3"]
+    L = args.ctx
+    base = synth.make_case("qwen3", n=128, L=L, seed=args.seed)
+    layer = harness.DeviceLayer(cfg, base["W"], max_tokens=128, max_batch=1, max_ctx=L)
+    names = ("wqkv", "wo", "wg", "w_gateup", "w_down")
+    sets = [layer.weights]
+    keep = []
+    for _ in range(max(1, args.copies) - 1):
+        cp = {n: getattr(layer, n).clone() for n in names}
+        keep.append(cp)
+        sets.append(ev.LayerWeights(layer.g_attn.data_ptr(), layer.g_moe.data_ptr(), cp["wqkv"].data_ptr(), cp["wo"].data_ptr(),
+                                    cp["wg"].data_ptr(), cp["w_gateup"].data_ptr(), cp["w_down"].data_ptr(), None, None))
+    eb = 2
+    for sigma in (0.2, 0.5, 1.0):
+        for N in (1, 8, 16, 32, 64, 128):
+            g = synth.philox(args.seed, 100)
+            par, q = synth.tree_eagle_style(N, g)
+            case = dict(base)
+            case.update(tree_off=np.array([0, N], np.int32), parent=par, parents=[par], q=q,
+                        x=synth.hidden_states(par, cfg.d, sigma, synth.philox(args.seed, 300), cfg.dtype))
+            dc = harness.DeviceCase(case, with_aux=True)
+            dc.run(layer)
+            U = int(dc.results()["union_count"])
+
+            def step(i):
+                ev.evict_verify_layer(layer.ctx, sets[i % len(sets)], dc.tree_off, dc.parent, 1, N, dc.k_cache, dc.v_cache,
+                                      dc.seq_stride, dc.head_stride, dc.ctx_len, L, dc.x, dc.out, dc.k_new, dc.v_new, None)
+            for i in range(args.warmup):
+                step(i)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for i in range(args.steps):
+                step(i)
+            torch.cuda.synchronize()
+            us = (time.perf_counter() - t0) * 1e6 / args.steps
+            ns_bytes = U * 3 * cfg.d * cfg.F * eb + 2 * L * cfg.Hkv * cfg.D * eb
+            print(json.dumps({"metric": "verify_layer_latency_us", "value": round(us, 2), "unit": "us", "nodes": N,
+                              "sigma": sigma, "ctx": L, "union_experts": U, "tokens_per_s": round(N / us * 1e6, 1),
+                              "north_star_bytes": ns_bytes,
+                              "hbm_frac_north_star": round(ns_bytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}), flush=True)
+    layer.close()
 
 
 def main():
@@ -60,6 +113,9 @@ def main():
         sys.exit(1)
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.sweep:
+        sweep(args)
+        return
     cfg = synth.CONFIGS["qwen3"]
     N, L = args.nodes, args.ctx
     case = synth.make_case("qwen3", n=N, L=L, seed=args.seed, sigma=args.sigma)

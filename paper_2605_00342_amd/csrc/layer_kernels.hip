@@ -642,74 +642,76 @@ __global__ __launch_bounds__(kRouterThreads) void router_logits_kernel(
 }
 
 // ------------------------------------------------------------------------------------
-// router, part 2 + grouping, one workgroup: TopK of every token's scores with the selected
-// scores normalised by softmax (Eq. 4), then the expert union and the token grouping (Eq. 5)
-// without a round trip of the indices through global memory.
+// router, part 2: TopK of every token's scores with the selected scores normalised by softmax
+// (Eq. 4); 16 tokens per workgroup, one per wavefront.
 // Selection: one wavefront per token; scores become unsigned keys monotone in the float value,
 // each of the k picks is a wavefront maximum (DPP row operations) followed by ballots that find
 // the lowest expert index holding it, so equal scores go to the lower index.
 // ------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kRouterThreads) void topk_union_kernel(
-    const float* __restrict__ logits, int T, int E, int k, int use_masks, int32_t* __restrict__ topk_idx,
-    float* __restrict__ topk_w, int32_t* __restrict__ aux_idx, float* __restrict__ aux_w,
-    int32_t* __restrict__ union_ids, int32_t* __restrict__ union_count, int32_t* __restrict__ hist,
-    int32_t* __restrict__ offsets, int32_t* __restrict__ perm, int32_t* __restrict__ inv, int32_t* __restrict__ status,
-    WorkRec* __restrict__ work, int32_t* __restrict__ tok_of_pos, int union_ints) {
+__global__ __launch_bounds__(kRouterThreads) void topk_kernel(
+    const float* __restrict__ logits, int T, int E, int k, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
+    int32_t* __restrict__ aux_idx, float* __restrict__ aux_w) {
   extern __shared__ __attribute__((aligned(16))) int s_all[];
-  int* s_mem = s_all;  // union scratch (first T*k ints: the indices), masks behind it
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-  float* s_sel = reinterpret_cast<float*>(s_all + union_ints) + w * 64;                                   // [k] per wavefront
-  unsigned* s_ord = reinterpret_cast<unsigned*>(s_all + union_ints + kRouterWaves * 64) + (size_t)w * E;  // [E] per wavefront
-  // The loops below are deliberately not unrolled: this kernel runs on one compute unit with a
-  // cold instruction cache, so its cost follows the size of the code it walks through.
-  for (int t = w; t < T; t += kRouterWaves) {
-    const float* row = logits + (size_t)t * E;
-    // scores as unsigned keys, monotone in the float value; 0 marks "taken" (below every key)
+  float* s_sel = reinterpret_cast<float*>(s_all) + w * 64;                                   // [k] per wavefront
+  unsigned* s_ord = reinterpret_cast<unsigned*>(s_all) + kRouterWaves * 64 + (size_t)w * E;  // [E] per wavefront
+  // The loops below are deliberately not unrolled: with a cold instruction cache the cost of
+  // this small kernel follows the size of the code it walks through.
+  const int t = blockIdx.x * kRouterWaves + w;  // one token per wavefront
+  if (t >= T) return;
+  const float* row = logits + (size_t)t * E;
+  // scores as unsigned keys, monotone in the float value; 0 marks "taken" (below every key)
+#pragma unroll 1
+  for (int e = lane; e < E; e += 64) {
+    unsigned bits = __float_as_uint(row[e]);
+    bits = bits == 0x80000000u ? 0u : bits;  // -0 and +0 compare equal
+    const unsigned o = bits ^ ((bits >> 31) ? 0xFFFFFFFFu : 0x80000000u);
+    s_ord[e] = o == 0u ? 1u : o;             // (only the most negative NaN pattern maps to 0)
+  }
+  // k extractions: wavefront maximum by DPP, then the lowest index holding it by ballots
+  // (LDS operations of one wavefront complete in order: s_ord / s_sel are visible to its lanes)
+#pragma unroll 1
+  for (int j = 0; j < k; ++j) {
+    unsigned local = 0u;
 #pragma unroll 1
     for (int e = lane; e < E; e += 64) {
-      unsigned bits = __float_as_uint(row[e]);
-      bits = bits == 0x80000000u ? 0u : bits;  // -0 and +0 compare equal
-      const unsigned o = bits ^ ((bits >> 31) ? 0xFFFFFFFFu : 0x80000000u);
-      s_ord[e] = o == 0u ? 1u : o;             // (only the most negative NaN pattern maps to 0)
+      const unsigned o = s_ord[e];
+      local = o > local ? o : local;
     }
-    // k extractions: wavefront maximum by DPP, then the lowest index holding it by ballots
-    // (LDS operations of one wavefront complete in order: s_ord / s_sel are visible to its lanes)
+    const unsigned best = wave_max_u32(local);
+    int sel = -1;
 #pragma unroll 1
-    for (int j = 0; j < k; ++j) {
-      unsigned local = 0u;
-#pragma unroll 1
-      for (int e = lane; e < E; e += 64) {
-        const unsigned o = s_ord[e];
-        local = o > local ? o : local;
-      }
-      const unsigned best = wave_max_u32(local);
-      int sel = -1;
-#pragma unroll 1
-      for (int base = 0; base < E && sel < 0; base += 64) {
-        const int e = base + lane;
-        const unsigned long long m = __ballot(e < E && s_ord[e] == best);
-        if (m) sel = base + (int)__ffsll((long long)m) - 1;
-      }
-      if (lane == 0) {
-        s_ord[sel] = 0u;
-        s_sel[j] = __uint_as_float(best ^ ((best >> 31) ? 0x80000000u : 0xFFFFFFFFu));
-        s_mem[t * k + j] = sel;
-        topk_idx[(size_t)t * k + j] = sel;
-        if (aux_idx) aux_idx[(size_t)t * k + j] = sel;
-      }
+    for (int base = 0; base < E && sel < 0; base += 64) {
+      const int e = base + lane;
+      const unsigned long long m = __ballot(e < E && s_ord[e] == best);
+      if (m) sel = base + (int)__ffsll((long long)m) - 1;
     }
-    const float first = s_sel[0];
-    const float ex = lane < k ? __expf(s_sel[lane < k ? lane : 0] - first) : 0.0f;
-    const float denom = wave_sum(ex);
-    if (lane < k) {
-      const float wv = ex / denom;
-      topk_w[(size_t)t * k + lane] = wv;
-      if (aux_w) aux_w[(size_t)t * k + lane] = wv;
+    if (lane == 0) {
+      s_ord[sel] = 0u;
+      s_sel[j] = __uint_as_float(best ^ ((best >> 31) ? 0x80000000u : 0xFFFFFFFFu));
+      topk_idx[(size_t)t * k + j] = sel;
+      if (aux_idx) aux_idx[(size_t)t * k + j] = sel;
     }
   }
-  __syncthreads();
-  expert_union_body(s_mem, nullptr, T, k, E, use_masks, union_ids, union_count, hist, offsets, perm, inv, status, work,
+  const float first = s_sel[0];
+  const float ex = lane < k ? __expf(s_sel[lane < k ? lane : 0] - first) : 0.0f;
+  const float denom = wave_sum(ex);
+  if (lane < k) {
+    const float wv = ex / denom;
+    topk_w[(size_t)t * k + lane] = wv;
+    if (aux_w) aux_w[(size_t)t * k + lane] = wv;
+  }
+}
+
+// expert union and grouping (Eq. 5) with the device-side work list, one workgroup
+__global__ __launch_bounds__(kRouterThreads) void union_worklist_kernel(
+    const int32_t* __restrict__ topk_idx, int T, int k, int E, int use_masks, int32_t* __restrict__ union_ids,
+    int32_t* __restrict__ union_count, int32_t* __restrict__ hist, int32_t* __restrict__ offsets,
+    int32_t* __restrict__ perm, int32_t* __restrict__ inv, int32_t* __restrict__ status, WorkRec* __restrict__ work,
+    int32_t* __restrict__ tok_of_pos) {
+  extern __shared__ __attribute__((aligned(16))) int s_all[];
+  expert_union_body(s_all, topk_idx, T, k, E, use_masks, union_ids, union_count, hist, offsets, perm, inv, status, work,
                     tok_of_pos);
 }
 
@@ -874,13 +876,6 @@ size_t router_lds_bytes(const evict_model_desc& m) {
   return (size_t)m.d * eb * 16 + (size_t)router_ksplit(m) * router_strips_per_wg(m) * 64 * sizeof(f32x4);
 }
 int union_mask_plan(int T, int k, int E, size_t* lds_bytes);  // small_kernels.hip
-size_t topk_union_lds_bytes(int T, int k, int E, int* use_masks, int* union_ints) {
-  size_t ub;
-  *use_masks = union_mask_plan(T, k, E, &ub);
-  const size_t ints = (ub / sizeof(int) + 3) & ~(size_t)3;  // keep the keys 16-byte aligned
-  *union_ints = (int)ints;
-  return ints * sizeof(int) + kRouterWaves * 64 * sizeof(float) + (size_t)kRouterWaves * E * sizeof(unsigned);
-}
 
 int kernels_setup(const evict_model_desc& m) {
   // kernels whose dynamic LDS exceeds the default 64 KiB limit
@@ -895,7 +890,6 @@ int kernels_setup(const evict_model_desc& m) {
     EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)router_logits_kernel<BF16>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)rl));
   else
     EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)router_logits_kernel<F32>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)rl));
-  EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)topk_union_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024));
   return EVICT_OK;
 }
 
@@ -963,13 +957,16 @@ int launch_router(const evict_ctx* c, const void* gain, const void* wg, int T, c
 
 int launch_topk_union(const evict_ctx* c, int T, const evict_layer_aux* aux, hipStream_t s) {
   const evict_model_desc& m = c->m;
-  int use_masks, union_ints;
-  const size_t lds = topk_union_lds_bytes(T, m.k, m.E, &use_masks, &union_ints);
-  EVICT_REQUIRE(lds <= 152 * 1024, EVICT_E_UNSUPPORTED, "top-k/union needs %zu bytes of LDS (limit 152 KiB)", lds);
-  hipLaunchKernelGGL(topk_union_kernel, dim3(1), dim3(kRouterThreads), lds, s, c->logits, T, m.E, m.k, use_masks,
-                     c->topk_idx, c->topk_w, aux ? aux->topk_idx : nullptr, aux ? aux->topk_w : nullptr, c->union_ids,
-                     c->union_count, c->hist, c->offsets, c->perm, c->inv, c->status, c->work, c->tok_of_pos, union_ints);
-  return launch_status("topk_union_kernel");
+  const size_t lds_topk = (size_t)kRouterWaves * (64 + m.E) * sizeof(float);
+  hipLaunchKernelGGL(topk_kernel, dim3((T + kRouterWaves - 1) / kRouterWaves), dim3(kRouterThreads), lds_topk, s, c->logits,
+                     T, m.E, m.k, c->topk_idx, c->topk_w, aux ? aux->topk_idx : nullptr, aux ? aux->topk_w : nullptr);
+  int rc = launch_status("topk_kernel");
+  if (rc) return rc;
+  size_t lds;
+  const int use_masks = union_mask_plan(T, m.k, m.E, &lds);
+  hipLaunchKernelGGL(union_worklist_kernel, dim3(1), dim3(kRouterThreads), lds, s, c->topk_idx, T, m.k, m.E, use_masks,
+                     c->union_ids, c->union_count, c->hist, c->offsets, c->perm, c->inv, c->status, c->work, c->tok_of_pos);
+  return launch_status("union_worklist_kernel");
 }
 
 int launch_argmax_reduce(const float* val, const int32_t* idx, int nstrips, int ld, int T, int32_t* next, float* best_out,

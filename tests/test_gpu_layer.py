@@ -155,3 +155,19 @@ def test_qwen3_shaped_layer_n32_full_size():
     got = run_case(case)
     info = check_against_oracle(case, got)
     print("qwen3 N=32:", info)
+
+
+def test_batched_qwen3_shaped_full_size_four_trees():
+    # configs[4] shape for one layer: 4 sequences, N = 64 each, contexts between 2048 and 8192
+    case = synth.make_case("qwen3", n=64, L=0, seed=1004, batch=4, L_list=[2048, 8192, 5000, 3333], tree="bfs")
+    got = run_case(case)
+    info = check_against_oracle(case, got)
+    print("qwen3 4 x N=64:", info)
+
+
+def test_dsv2lite_shaped_layer_full_size():
+    # configs[3] layer shape: MHA 16 x 128, 64 experts top-6 + 2 shared, d_ff 1408, ctx 8192, N = 64
+    case = synth.make_case("dsv2lite", n=64, L=8192, seed=1003)
+    got = run_case(case)
+    info = check_against_oracle(case, got)
+    print("dsv2lite N=64:", info)

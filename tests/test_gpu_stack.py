@@ -212,3 +212,27 @@ def test_profile_cost_table_and_selection_from_it():
     ref = oracle_stack(case, Ws, Ks, Vs, tree_off=np.array([0, 5], np.int32), parent=case["parent"][:5], x=case["x"][:5])
     assert rel_l2(harness.to_host(dc.out)[:5], ref[-1]["out"]) < 3e-2
     st.close()
+
+
+def test_lm_head_full_vocabulary():
+    # Qwen3-sized LM head: vocab 151936, d = 2048, 32 tokens
+    cfg, vocab, T = synth.CONFIGS["qwen3"], 151936, 32
+    g = synth.philox(80, 1)
+    x = synth.store(g.standard_normal((T, cfg.d)), cfg.dtype)
+    gain = synth.store(np.ones(cfg.d), cfg.dtype)
+    w_lm = synth.store(g.standard_normal((vocab, cfg.d), dtype=np.float32) * np.float32(0.02), cfg.dtype)
+    ctx = ev.evict_create(harness.model_desc(cfg, vocab), T, 1, 16)
+    wp = harness.pack_lm_head(cfg, w_lm)
+    nxt = torch.zeros(T, dtype=torch.int32, device=DEV)
+    best = torch.zeros(T, device=DEV)
+    xd = harness.to_dev(x, cfg.dtype)
+    xn = torch.zeros_like(xd)
+    ev.evict_lm_head_argmax(ctx, xd, harness.to_dev(gain, cfg.dtype), wp, T, nxt, best, xn)
+    torch.cuda.synchronize()
+    logits = (torch.from_numpy(harness.to_host(xn)).double() @ torch.from_numpy(w_lm).double().T).float().numpy()
+    top2 = -np.sort(-logits, axis=-1)[:, :2]
+    ok = (top2[:, 0] - top2[:, 1]) >= 1e-4
+    assert (~ok).sum() <= 2
+    assert np.array_equal(nxt.cpu().numpy()[ok], np.argmax(logits, -1)[ok])
+    np.testing.assert_allclose(best.cpu().numpy(), logits.max(-1), rtol=0, atol=5e-5)
+    ev.evict_destroy(ctx)
