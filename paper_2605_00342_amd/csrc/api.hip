@@ -97,7 +97,7 @@ int evict_create(evict_ctx** out, const evict_model_desc* m, int max_tokens, int
   A(&c.union_count, 16);
   A(&c.perm, T * k * 4);
   A(&c.inv, T * k * 4);
-  A(&c.work, E * sizeof(WorkRec));
+  A(&c.work, (E + T * k / 16 + 1) * sizeof(WorkRec));  // one slot per (expert, 16-token tile)
   A(&c.sched, 16);
   A(&c.tok_of_pos, T * k * 4);
   A(&c.act, T * k * F * eb);
@@ -314,7 +314,7 @@ static int verify_layer_impl(evict_ctx* ctx, const evict_layer_weights* w, const
     if (aux->hist) EVICT_HIP_CHECK(hipMemcpyAsync(aux->hist, ctx->hist, (size_t)m.E * 4, hipMemcpyDeviceToDevice, s));
   }
   EVICT_MARK(6);
-  const int nt_exp = T <= 48 ? 1 : 2;
+  const int nt_exp = 1;  // token tiles of an expert are separate work slots
   {  // gate/up projections of the union experts + SiLU gating
     GemmArgs a = {};
     a.W = (const u32x4*)w->w_gateup_packed;
@@ -324,7 +324,7 @@ static int verify_layer_impl(evict_ctx* ctx, const evict_layer_weights* w, const
     a.X = ctx->h_norm;
     a.ldx_bytes = (long long)m.d * eb;
     a.grouped = 1;
-    a.union_count = ctx->union_count; a.work = ctx->work; a.tok_of_pos = ctx->tok_of_pos;
+    a.union_count = ctx->sched; a.work = ctx->work; a.tok_of_pos = ctx->tok_of_pos;
     a.x_by_token = 1;
     a.out0 = ctx->act;
     a.ldo = m.F;
@@ -343,7 +343,7 @@ static int verify_layer_impl(evict_ctx* ctx, const evict_layer_weights* w, const
     a.X = ctx->act;
     a.ldx_bytes = (long long)m.F * eb;
     a.grouped = 1;
-    a.union_count = ctx->union_count; a.work = ctx->work; a.tok_of_pos = ctx->tok_of_pos;
+    a.union_count = ctx->sched; a.work = ctx->work; a.tok_of_pos = ctx->tok_of_pos;
     a.x_by_token = 0;
     a.out0 = ctx->y;
     a.ldo = m.d;

@@ -18,9 +18,10 @@ namespace evict {
 
 enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_F32 = 3, EPI_ARGMAX = 4 };
 
-// One union slot of the device-side work list: the expert, where its tokens sit in the
-// grouped order, how many there are, and the token ids of the first few positions (so that
-// a workgroup learns everything it needs to start loading from one 64-byte record).
+// One slot of the device-side work list = one activated expert and one tile of up to 16 of its
+// tokens: the expert, where the tile sits in the grouped order, how many tokens it has, how many
+// tiles the expert has, and the token ids of the tile's first positions (so that a workgroup
+// learns everything it needs to start loading from one 64-byte record).
 constexpr int kWorkToks = 12;
 struct WorkRec {
   int expert, p0, ntok, pad;
@@ -35,7 +36,7 @@ struct GemmArgs {
   const void* X;         // token operand rows, storage dtype
   long long ldx_bytes;   // bytes between rows of X
   int grouped;           // 0: one matrix, tokens 0..T-1; 1: one matrix per union expert
-  const int* union_count;
+  const int* union_count;  // grouped: number of work slots (expert x token tile)
   const WorkRec* work;   // per union slot (see WorkRec)
   int chunk_units;       // grouped: units per chunk (divides the units per expert)
   const int* tok_of_pos; // token of each grouped position (perm[p] / k)
@@ -80,6 +81,7 @@ __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(NT
     const int nitems = nunits * SPU;
     int p0 = 0, ntok = a.T;
     int tok_early = 0;  // token id from the work record (grouped, first kWorkToks positions)
+    bool once = kStreamOnce;  // weights read by this workgroup only: keep them out of the caches' way
     const u32x4* wbase = a.W;
     if (a.grouped) {
       // one hop: the record (scalar) and this lane's token id (vector) are fetched together
@@ -88,6 +90,7 @@ __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(NT
       tok_early = rec->tok[lc < kWorkToks ? lc : kWorkToks - 1];  // entries past ntok repeat the last token
       p0 = rec->p0;
       ntok = rec->ntok;
+      once = kStreamOnce && (rec->pad & 0xFFFF) == 1;
       wbase += (long long)rec->expert * a.group_stride;
     }
     const int nsteps = (nitems / IS) * nchunks;  // nitems is a multiple of IS (host-checked)
@@ -126,7 +129,7 @@ __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(NT
           const u32x4* p = wbase + ((long long)(strip0 + it * IS + i) * nkb + b0) * 64 + lane;
 #pragma unroll
           for (int j = 0; j < KBW; ++j)
-            if (EXACT || j < nb) dst[i * KBW + j] = kStreamOnce ? __builtin_nontemporal_load(p + j * 64) : p[j * 64];
+            if (EXACT || j < nb) dst[i * KBW + j] = once ? __builtin_nontemporal_load(p + j * 64) : p[j * 64];
         }
       };
       // weights first: their addresses need nothing but the expert id
@@ -286,8 +289,10 @@ __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(NT
     const int cpg = upg / a.chunk_units;
     const int total = *a.union_count * cpg;
     for (int chunk = blockIdx.x; chunk < total; chunk += gridDim.x) {
-      const int grp = chunk / cpg;
-      run_segment(grp, (chunk - grp * cpg) * a.chunk_units, a.chunk_units, 0, 0x7fffffff);
+      // (the token tiles of one expert are consecutive slots: with cpg a multiple of 8 their
+      // chunks land on the same XCD, whose L2 serves the second reader of the weights)
+      const int slot = chunk / cpg, uc = chunk - slot * cpg;
+      run_segment(slot, uc * a.chunk_units, a.chunk_units, 0, 0x7fffffff);
     }
   } else {
     // one workgroup per (strip, token tile). Workgroup ids go round-robin over the 8 XCDs, so

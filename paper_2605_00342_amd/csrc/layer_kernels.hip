@@ -709,10 +709,10 @@ __global__ __launch_bounds__(kRouterThreads) void union_worklist_kernel(
     const int32_t* __restrict__ topk_idx, int T, int k, int E, int use_masks, int32_t* __restrict__ union_ids,
     int32_t* __restrict__ union_count, int32_t* __restrict__ hist, int32_t* __restrict__ offsets,
     int32_t* __restrict__ perm, int32_t* __restrict__ inv, int32_t* __restrict__ status, WorkRec* __restrict__ work,
-    int32_t* __restrict__ tok_of_pos) {
+    int32_t* __restrict__ tok_of_pos, int32_t* __restrict__ slot_count) {
   extern __shared__ __attribute__((aligned(16))) int s_all[];
   expert_union_body(s_all, topk_idx, T, k, E, use_masks, union_ids, union_count, hist, offsets, perm, inv, status, work,
-                    tok_of_pos);
+                    tok_of_pos, slot_count);
 }
 
 // ------------------------------------------------------------------------------------
@@ -965,7 +965,8 @@ int launch_topk_union(const evict_ctx* c, int T, const evict_layer_aux* aux, hip
   size_t lds;
   const int use_masks = union_mask_plan(T, m.k, m.E, &lds);
   hipLaunchKernelGGL(union_worklist_kernel, dim3(1), dim3(kRouterThreads), lds, s, c->topk_idx, T, m.k, m.E, use_masks,
-                     c->union_ids, c->union_count, c->hist, c->offsets, c->perm, c->inv, c->status, c->work, c->tok_of_pos);
+                     c->union_ids, c->union_count, c->hist, c->offsets, c->perm, c->inv, c->status, c->work, c->tok_of_pos,
+                     c->sched);
   return launch_status("union_worklist_kernel");
 }
 

@@ -35,6 +35,16 @@ __device__ int block_excl_scan(int v, int* s_wave, int* total) {
   return base + incl - v;
 }
 
+// Token t sits at rank r (of n) inside its expert: enter it into the record of its 16-token tile;
+// the last token of a tile also fills the record's unused entries (padded columns repeat it).
+__device__ inline void work_put_token(WorkRec* first, int r, int n, int t) {
+  WorkRec* rec = first + (r >> 4);
+  const int i = r & 15;
+  if (i < kWorkToks) rec->tok[i] = t;
+  if (i == 15 || r == n - 1)
+    for (int j = i + 1; j < kWorkToks; ++j) rec->tok[j] = t;
+}
+
 // LDS needed by expert_union_body, in ints (before the optional bitmasks).
 __host__ __device__ inline size_t union_lds_ints(int P, int E) { return (size_t)((P + 3 * E + 2) & ~1); }
 
@@ -48,7 +58,7 @@ __device__ inline void expert_union_body(
     int* s_mem, const int32_t* __restrict__ topk_idx, int T, int k, int E, int use_masks, int32_t* __restrict__ union_ids,
     int32_t* __restrict__ union_count, int32_t* __restrict__ hist, int32_t* __restrict__ offsets,
     int32_t* __restrict__ perm, int32_t* __restrict__ inv, int32_t* __restrict__ status, WorkRec* __restrict__ work,
-    int32_t* __restrict__ tok_of_pos) {
+    int32_t* __restrict__ tok_of_pos, int32_t* __restrict__ slot_count = nullptr) {
   const int P = T * k;
   const int words = (T + 63) >> 6;
   int* s_idx = s_mem;            // [P]
@@ -86,14 +96,30 @@ __device__ inline void expert_union_body(
   const int base = block_excl_scan(hcount | ((hcount > 0 ? 1 : 0) << 16), s_wave, &tot);
   const int base_h = base & 0xFFFF, base_f = base >> 16;
   const int tot_h = tot & 0xFFFF, tot_f = tot >> 16;
+  // work list: one slot per (activated expert, tile of 16 of its tokens); second scan for the slots
+  int wslot = 0;
+  if (work) {
+    int tot_s;
+    wslot = block_excl_scan((hcount + 15) >> 4, s_wave, &tot_s);
+    if (tid == 0 && slot_count) slot_count[0] = tot_s;
+  }
   if (tid < E) {
     s_off[tid] = base_h;
     offsets[tid] = base_h;
     hist[tid] = hcount;
     if (hcount > 0) {
       union_ids[base_f] = tid;
-      s_slot[tid] = base_f;
-      if (work) { work[base_f].expert = tid; work[base_f].p0 = base_h; work[base_f].ntok = hcount; work[base_f].pad = 0; }
+      s_slot[tid] = wslot;
+      if (work) {
+        const int ntile = (hcount + 15) >> 4;
+        for (int i = 0; i < ntile; ++i) {
+          WorkRec* rec = work + wslot + i;
+          rec->expert = tid;
+          rec->p0 = base_h + 16 * i;
+          rec->ntok = hcount - 16 * i < 16 ? hcount - 16 * i : 16;
+          rec->pad = ntile | (i << 16);  // tiles of this expert (low half), index of this tile (high half)
+        }
+      }
     }
   }
   for (int e = tot_f + tid; e < E; e += nthreads) union_ids[e] = -1;
@@ -110,13 +136,7 @@ __device__ inline void expert_union_body(
       perm[pos] = p;
       inv[p] = pos;
       if (tok_of_pos) tok_of_pos[pos] = t;
-      if (work) {
-        const int r = pos - s_off[e], last = s_hist[e] - 1;
-        WorkRec* rec = work + s_slot[e];
-        if (r < kWorkToks) rec->tok[r] = t;
-        if (r == last)
-          for (int i = r + 1; i < kWorkToks; ++i) rec->tok[i] = t;  // padded columns repeat the last token
-      }
+      if (work) work_put_token(work + s_slot[e], pos - s_off[e], s_hist[e], t);
     }
   } else {
     for (int e = tid; e < E; e += nthreads) {
@@ -127,13 +147,7 @@ __device__ inline void expert_union_body(
           perm[pos] = p;
           inv[p] = pos;
           if (tok_of_pos) tok_of_pos[pos] = p / k;
-          if (work) {
-            const int r = pos - s_off[e];
-            WorkRec* rec = work + s_slot[e];
-            if (r < kWorkToks) rec->tok[r] = p / k;
-            if (r == s_hist[e] - 1)
-              for (int i = r + 1; i < kWorkToks; ++i) rec->tok[i] = p / k;
-          }
+          if (work) work_put_token(work + s_slot[e], pos - s_off[e], s_hist[e], p / k);
           ++pos;
         }
       }
