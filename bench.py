@@ -40,6 +40,8 @@ def parse():
     ap.add_argument("--copies", type=int, default=4, help="weight copies rotated between steps")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     ap.add_argument("--seed", type=int, default=1000)
+    ap.add_argument("--model", default="qwen3", choices=["qwen3", "dsv2lite"],
+                    help="layer shape; the default line is the Qwen3-30B-A3B-shaped one")
     ap.add_argument("--tune", action="append", default=[], help="key=value launch-shape knob (evict_tune)")
     ap.add_argument("--sweep", action="store_true",
                     help="not the default line: one JSON line per (N, sigma) point, N in 1..128, sigma in {0.2, 0.5, 1.0}")
@@ -116,9 +118,9 @@ def main():
     if args.sweep:
         sweep(args)
         return
-    cfg = synth.CONFIGS["qwen3"]
+    cfg = synth.CONFIGS[args.model]
     N, L = args.nodes, args.ctx
-    case = synth.make_case("qwen3", n=N, L=L, seed=args.seed, sigma=args.sigma)
+    case = synth.make_case(args.model, n=N, L=L, seed=args.seed, sigma=args.sigma)
     layer = harness.DeviceLayer(cfg, case["W"], max_tokens=N, max_batch=1, max_ctx=L)
     dc = harness.DeviceCase(case, with_aux=True)
     for kv in args.tune:
@@ -131,10 +133,14 @@ def main():
     keep_alive = []
     for _ in range(max(1, args.copies) - 1):
         cp = {n: getattr(layer, n).clone() for n in names}
+        if cfg.n_shared:
+            cp["ws_gateup"], cp["ws_down"] = layer.ws_gateup.clone(), layer.ws_down.clone()
         keep_alive.append(cp)
         weight_sets.append(ev.LayerWeights(layer.g_attn.data_ptr(), layer.g_moe.data_ptr(), cp["wqkv"].data_ptr(),
                                            cp["wo"].data_ptr(), cp["wg"].data_ptr(), cp["w_gateup"].data_ptr(),
-                                           cp["w_down"].data_ptr(), None, None))
+                                           cp["w_down"].data_ptr(),
+                                           cp["ws_gateup"].data_ptr() if cfg.n_shared else None,
+                                           cp["ws_down"].data_ptr() if cfg.n_shared else None))
 
     # selection / acceptance inputs
     i32, f32 = torch.int32, torch.float32
@@ -190,7 +196,7 @@ def main():
     expert_bytes = 3 * cfg.d * cfg.F * eb
     kv_bytes = 2 * L * cfg.Hkv * cfg.D * eb
     proj_bytes = (2 * cfg.Hq * cfg.D * cfg.d + 2 * cfg.Hkv * cfg.D * cfg.d) * eb + cfg.E * cfg.d * eb
-    north_star_bytes = U * expert_bytes + kv_bytes
+    north_star_bytes = (U + cfg.n_shared) * expert_bytes + kv_bytes
     all_bytes = north_star_bytes + proj_bytes
     gateup_bytes = U * 2 * cfg.d * cfg.F * eb            # algorithmic bytes of the dominant kernel per launch
     # an event pair around an empty stage (no shared experts at this shape) measures the
@@ -220,7 +226,7 @@ def main():
         "vs_baseline": None,
         "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": f"qwen3-30b-a3b-shaped MoE layer, N={N} tree nodes, ctx={L}, 1 sequence, sigma={args.sigma}",
+        "config": {"workload": f"{'qwen3-30b-a3b' if args.model == 'qwen3' else 'deepseek-v2-lite'}-shaped MoE layer, N={N} tree nodes, ctx={L}, 1 sequence, sigma={args.sigma}",
                    "d_model": cfg.d, "heads": f"{cfg.Hq}q/{cfg.Hkv}kv x {cfg.D}", "experts": f"{cfg.E} top-{cfg.k}",
                    "d_ff": cfg.F, "union_experts": U, "weight_copies": len(weight_sets)},
         "tokens_per_s": round(N / (ms_per_step * 1e-3), 1),

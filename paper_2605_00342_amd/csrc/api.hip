@@ -97,11 +97,11 @@ int evict_create(evict_ctx** out, const evict_model_desc* m, int max_tokens, int
   A(&c.union_count, 16);
   A(&c.perm, T * k * 4);
   A(&c.inv, T * k * 4);
-  A(&c.work, (E + T * k / 16 + 1) * sizeof(WorkRec));  // one slot per (expert, 16-token tile)
+  A(&c.work, (E + T * k / 16 + 1 + (size_t)m->n_shared * (T / 16 + 1)) * sizeof(WorkRec));  // one slot per (expert, 16-token tile)
   A(&c.sched, 16);
-  A(&c.tok_of_pos, T * k * 4);
-  A(&c.act, T * k * F * eb);
-  A(&c.y, T * k * d * 4);
+  A(&c.tok_of_pos, (T * k + (size_t)m->n_shared * T) * 4);
+  A(&c.act, (T * k + (size_t)m->n_shared * T) * F * eb);
+  A(&c.y, (T * k + (size_t)m->n_shared * T) * d * 4);
   c.lm_val = nullptr;
   c.lm_idx = nullptr;
   if (m->vocab) {
@@ -110,12 +110,6 @@ int evict_create(evict_ctx** out, const evict_model_desc* m, int max_tokens, int
   }
   A(&c.stack_buf[0], T * d * eb);
   A(&c.stack_buf[1], T * d * eb);
-  c.act_sh = nullptr;
-  c.y_sh = nullptr;
-  if (m->n_shared) {
-    A(&c.act_sh, (size_t)m->n_shared * T * F * eb);
-    A(&c.y_sh, (size_t)m->n_shared * T * d * 4);
-  }
   if (!rc) {
     he = hipMemset(c.status, 0, 16);
     if (he != hipSuccess) { set_error("hipMemset failed: %s", hipGetErrorString(he)); rc = EVICT_E_HIP; }
@@ -318,6 +312,8 @@ static int verify_layer_impl(evict_ctx* ctx, const evict_layer_weights* w, const
   {  // gate/up projections of the union experts + SiLU gating
     GemmArgs a = {};
     a.W = (const u32x4*)w->w_gateup_packed;
+    a.W_shared = (const u32x4*)w->ws_gateup_packed;
+    a.n_routed = m.E;
     a.n_strips = 2 * m.F / 16;
     a.nkb = m.d * eb / 64;
     a.group_stride = (long long)a.n_strips * a.nkb * 64;
@@ -337,6 +333,8 @@ static int verify_layer_impl(evict_ctx* ctx, const evict_layer_weights* w, const
   {  // down projections
     GemmArgs a = {};
     a.W = (const u32x4*)w->w_down_packed;
+    a.W_shared = (const u32x4*)w->ws_down_packed;
+    a.n_routed = m.E;
     a.n_strips = m.d / 16;
     a.nkb = m.F * eb / 64;
     a.group_stride = (long long)a.n_strips * a.nkb * 64;
@@ -353,32 +351,7 @@ static int verify_layer_impl(evict_ctx* ctx, const evict_layer_weights* w, const
     if (rc) return rc;
   }
   EVICT_MARK(8);
-  for (int sh = 0; sh < m.n_shared; ++sh) {  // always-on shared experts on all tokens
-    GemmArgs a = {};
-    a.n_strips = 2 * m.F / 16;
-    a.nkb = m.d * eb / 64;
-    a.W = (const u32x4*)w->ws_gateup_packed + (long long)sh * a.n_strips * a.nkb * 64;
-    a.X = ctx->h_norm;
-    a.ldx_bytes = (long long)m.d * eb;
-    a.T = T;
-    a.out0 = (char*)ctx->act_sh + (size_t)sh * T * m.F * eb;
-    a.ldo = m.F;
-    a.dense_tiles = dense_tiles;
-    rc = launch_gemm(m.dtype, EPI_SWIGLU, a, nt_dense, dense_grid(a.n_strips / 2), s);
-    if (rc) return rc;
-    GemmArgs b = {};
-    b.n_strips = m.d / 16;
-    b.nkb = m.F * eb / 64;
-    b.W = (const u32x4*)w->ws_down_packed + (long long)sh * b.n_strips * b.nkb * 64;
-    b.X = a.out0;
-    b.ldx_bytes = (long long)m.F * eb;
-    b.T = T;
-    b.out0 = ctx->y_sh + (size_t)sh * T * m.d;
-    b.ldo = m.d;
-    b.dense_tiles = dense_tiles;
-    rc = launch_gemm(m.dtype, EPI_F32, b, nt_dense, dense_grid(b.n_strips), s);
-    if (rc) return rc;
-  }
+  // (the always-on shared experts are extra slots of the work list: same two launches)
   EVICT_MARK(9);
   rc = launch_combine(ctx, T, x_out, s);
   if (rc) return rc;

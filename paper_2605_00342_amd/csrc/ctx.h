@@ -38,12 +38,10 @@ struct evict_ctx {
   evict::WorkRec* work;  // [E] device-side work list, one record per union slot
   int32_t* sched;        // [4] chunk counters of the grouped GEMMs
   int32_t* tok_of_pos;   // [T*k] token of each grouped position
-  void* act;             // [T*k][F] storage dtype
-  float* y;              // [T*k][d]
+  void* act;             // [T*k + n_shared*T][F] storage dtype (routed pairs, then shared experts x tokens)
+  float* y;              // [T*k + n_shared*T][d]
   float* lm_val;         // [vocab/16][T] best logit per strip and token
   int32_t* lm_idx;       // [vocab/16][T]
   void* stack_buf[2];    // [T][d] ping-pong hidden states of evict_verify_stack
   hipEvent_t prof_ev[2]; // evict_profile_cost
-  void* act_sh;          // [n_shared][T][F]
-  float* y_sh;           // [n_shared][T][d]
 };

@@ -30,6 +30,8 @@ struct WorkRec {
 
 struct GemmArgs {
   const u32x4* W;        // packed weights
+  const u32x4* W_shared; // grouped: packed weights of the always-on shared experts (expert ids >= n_routed)
+  int n_routed;          // grouped: number of routed experts E
   long long group_stride;  // u32x4 elements between experts
   int n_strips;          // 16-row strips per matrix (gate/up interleaved: 2 per 16 rows of F)
   int nkb;               // 1 KiB blocks per strip
@@ -91,7 +93,8 @@ __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(NT
       p0 = rec->p0;
       ntok = rec->ntok;
       once = kStreamOnce && (rec->pad & 0xFFFF) == 1;
-      wbase += (long long)rec->expert * a.group_stride;
+      const int ex = rec->expert;
+      wbase = ex < a.n_routed ? a.W + (long long)ex * a.group_stride : a.W_shared + (long long)(ex - a.n_routed) * a.group_stride;
     }
     const int nsteps = (nitems / IS) * nchunks;  // nitems is a multiple of IS (host-checked)
 

@@ -709,10 +709,10 @@ __global__ __launch_bounds__(kRouterThreads) void union_worklist_kernel(
     const int32_t* __restrict__ topk_idx, int T, int k, int E, int use_masks, int32_t* __restrict__ union_ids,
     int32_t* __restrict__ union_count, int32_t* __restrict__ hist, int32_t* __restrict__ offsets,
     int32_t* __restrict__ perm, int32_t* __restrict__ inv, int32_t* __restrict__ status, WorkRec* __restrict__ work,
-    int32_t* __restrict__ tok_of_pos, int32_t* __restrict__ slot_count) {
+    int32_t* __restrict__ tok_of_pos, int32_t* __restrict__ slot_count, int n_shared) {
   extern __shared__ __attribute__((aligned(16))) int s_all[];
   expert_union_body(s_all, topk_idx, T, k, E, use_masks, union_ids, union_count, hist, offsets, perm, inv, status, work,
-                    tok_of_pos, slot_count);
+                    tok_of_pos, slot_count, n_shared);
 }
 
 // ------------------------------------------------------------------------------------
@@ -966,7 +966,7 @@ int launch_topk_union(const evict_ctx* c, int T, const evict_layer_aux* aux, hip
   const int use_masks = union_mask_plan(T, m.k, m.E, &lds);
   hipLaunchKernelGGL(union_worklist_kernel, dim3(1), dim3(kRouterThreads), lds, s, c->topk_idx, T, m.k, m.E, use_masks,
                      c->union_ids, c->union_count, c->hist, c->offsets, c->perm, c->inv, c->status, c->work, c->tok_of_pos,
-                     c->sched);
+                     c->sched, m.n_shared);
   return launch_status("union_worklist_kernel");
 }
 
@@ -979,11 +979,11 @@ int launch_argmax_reduce(const float* val, const int32_t* idx, int nstrips, int 
 int launch_combine(const evict_ctx* c, int T, void* out, hipStream_t s) {
   const evict_model_desc& m = c->m;
   if (m.dtype == EVICT_BF16)
-    hipLaunchKernelGGL(combine_kernel<BF16>, dim3(T), dim3(512), 0, s, c->h, c->y, c->topk_w, c->inv, m.k, m.d, c->y_sh,
-                       m.n_shared, T, out);
+    hipLaunchKernelGGL(combine_kernel<BF16>, dim3(T), dim3(512), 0, s, c->h, c->y, c->topk_w, c->inv, m.k, m.d,
+                       c->y + (size_t)T * m.k * m.d, m.n_shared, T, out);
   else
-    hipLaunchKernelGGL(combine_kernel<F32>, dim3(T), dim3(512), 0, s, c->h, c->y, c->topk_w, c->inv, m.k, m.d, c->y_sh,
-                       m.n_shared, T, out);
+    hipLaunchKernelGGL(combine_kernel<F32>, dim3(T), dim3(512), 0, s, c->h, c->y, c->topk_w, c->inv, m.k, m.d,
+                       c->y + (size_t)T * m.k * m.d, m.n_shared, T, out);
   return launch_status("combine_kernel");
 }
 

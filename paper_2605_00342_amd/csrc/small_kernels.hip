@@ -76,13 +76,14 @@ __global__ __launch_bounds__(kSelThreads) void select_prefix_kernel(
   __shared__ int s_maxdep;
 
   const int b = blockIdx.x, tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
+  const int nthreads = blockDim.x, nwaves = nthreads >> 6;  // 64 threads for small trees: barriers cost nothing
   // a single tree spans [0, T): its offsets need not be fetched
   const int lo = n_single > 0 ? 0 : tree_off[b];
   int n = n_single > 0 ? n_single : tree_off[b + 1] - lo;
   n = n < 1 ? 1 : (n > kMaxSel ? kMaxSel : n);
 
   if (tid == 0) s_maxdep = 0;
-  for (int i = tid; i < n; i += kSelThreads) {
+  for (int i = tid; i < n; i += nthreads) {
     int p = parent[lo + i];
     if (i == 0) p = -1;
     else if (p < 0 || p >= i) p = 0;  // invalid ids are clamped (the host check rejects them)
@@ -93,7 +94,7 @@ __global__ __launch_bounds__(kSelThreads) void select_prefix_kernel(
   __syncthreads();
   // depth of every node (walk to the root; parent ids strictly decrease)
   int mydep_max = 0;
-  for (int i = tid; i < n; i += kSelThreads) {
+  for (int i = tid; i < n; i += nthreads) {
     int dep = 0;
     for (int p = s_par[i]; p >= 0; p = s_par[p]) ++dep;
     s_aux[i] = dep;
@@ -105,12 +106,12 @@ __global__ __launch_bounds__(kSelThreads) void select_prefix_kernel(
   const int maxdep = s_maxdep;
   // Score(v) = Score(parent(v)) * q(v): one rounded fp32 multiply per node, level by level
   for (int lvl = 1; lvl <= maxdep; ++lvl) {
-    for (int i = tid; i < n; i += kSelThreads)
+    for (int i = tid; i < n; i += nthreads)
       if (s_aux[i] == lvl) s_score[i] = __fmul_rn(s_score[s_par[i]], s_prob[i]);
     __syncthreads();
   }
   // rank by (score descending, index ascending)
-  for (int i = tid; i < n; i += kSelThreads) {
+  for (int i = tid; i < n; i += nthreads) {
     const float si = s_score[i];
     int r = 0;
     int j = 0;
@@ -151,7 +152,7 @@ __global__ __launch_bounds__(kSelThreads) void select_prefix_kernel(
   const int kk = n < kmax ? n : kmax;
   float bv = -1.0f;
   int bi = 0x7fffffff;
-  for (int i = tid; i < n; i += kSelThreads) {
+  for (int i = tid; i < n; i += nthreads) {
     const float S = s_sorted[i];
     if (psum_out) psum_out[lo + i] = S;
     if (i < kk) {
@@ -168,7 +169,7 @@ __global__ __launch_bounds__(kSelThreads) void select_prefix_kernel(
   if (lane == 0) { s_bestv[w] = bv; s_besti[w] = bi; }
   __syncthreads();
   bv = s_bestv[0]; bi = s_besti[0];
-  for (int i = 1; i < kSelThreads / 64; ++i) {
+  for (int i = 1; i < nwaves; ++i) {
     const float ov = s_bestv[i];
     const int oi = s_besti[i];
     if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
@@ -182,7 +183,7 @@ __global__ __launch_bounds__(kSelThreads) void select_prefix_kernel(
     if (tid == 0) { new_tree_off[0] = 0; new_tree_off[1] = kstar; }
     compact_tree(n, kstar, s_par, s_rank, s_aux, s_wave, keep, new_parent);
   } else {
-    for (int i = tid; i < n; i += kSelThreads) rank_ws[lo + i] = s_rank[i];
+    for (int i = tid; i < n; i += nthreads) rank_ws[lo + i] = s_rank[i];
   }
 }
 
@@ -371,7 +372,9 @@ int evict_select_prefix(evict_ctx*, const int32_t* tree_off, const int32_t* pare
                 "evict_select_prefix: more than %d nodes per tree", EVICT_MAX_SELECT_NODES);
   hipStream_t s = (hipStream_t)stream;
   const int single = B == 1;
-  hipLaunchKernelGGL(select_prefix_kernel, dim3(B), dim3(kSelThreads), 0, s, tree_off, parent, node_prob, cost, Kmax,
+  // trees of at most 64 nodes are handled by a single wavefront per tree
+  const int sel_threads = (B == 1 && T <= 64) ? 64 : kSelThreads;
+  hipLaunchKernelGGL(select_prefix_kernel, dim3(B), dim3(sel_threads), 0, s, tree_off, parent, node_prob, cost, Kmax,
                      k_star, est_len, order, prefix_sum, new_parent /* rank workspace */, single, keep, new_parent,
                      new_tree_off, single ? T : 0);
   int rc = launch_status("select_prefix_kernel");

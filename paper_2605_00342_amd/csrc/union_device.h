@@ -58,7 +58,7 @@ __device__ inline void expert_union_body(
     int* s_mem, const int32_t* __restrict__ topk_idx, int T, int k, int E, int use_masks, int32_t* __restrict__ union_ids,
     int32_t* __restrict__ union_count, int32_t* __restrict__ hist, int32_t* __restrict__ offsets,
     int32_t* __restrict__ perm, int32_t* __restrict__ inv, int32_t* __restrict__ status, WorkRec* __restrict__ work,
-    int32_t* __restrict__ tok_of_pos, int32_t* __restrict__ slot_count = nullptr) {
+    int32_t* __restrict__ tok_of_pos, int32_t* __restrict__ slot_count = nullptr, int n_shared = 0) {
   const int P = T * k;
   const int words = (T + 63) >> 6;
   int* s_idx = s_mem;            // [P]
@@ -101,7 +101,21 @@ __device__ inline void expert_union_body(
   if (work) {
     int tot_s;
     wslot = block_excl_scan((hcount + 15) >> 4, s_wave, &tot_s);
-    if (tid == 0 && slot_count) slot_count[0] = tot_s;
+    // always-on shared experts: every token, in token order, appended behind the routed pairs
+    // (expert id E + s; positions T*k + s*T + t), one slot per tile of 16 tokens
+    const int ttiles = (T + 15) >> 4;
+    if (tid == 0 && slot_count) slot_count[0] = tot_s + n_shared * ttiles;
+    for (int q = tid; q < n_shared * ttiles; q += nthreads) {
+      const int sh = q / ttiles, i = q - sh * ttiles;
+      WorkRec* rec = work + tot_s + q;
+      rec->expert = E + sh;
+      rec->p0 = P + sh * T + 16 * i;
+      rec->ntok = T - 16 * i < 16 ? T - 16 * i : 16;
+      rec->pad = ttiles | (i << 16);
+      for (int j = 0; j < kWorkToks; ++j) rec->tok[j] = 16 * i + (j < rec->ntok ? j : rec->ntok - 1);
+    }
+    if (tok_of_pos)
+      for (int q = tid; q < n_shared * T; q += nthreads) tok_of_pos[P + q] = q % T;
   }
   if (tid < E) {
     s_off[tid] = base_h;
