@@ -198,10 +198,11 @@ def main():
     proj_bytes = (2 * cfg.Hq * cfg.D * cfg.d + 2 * cfg.Hkv * cfg.D * cfg.d) * eb + cfg.E * cfg.d * eb
     north_star_bytes = (U + cfg.n_shared) * expert_bytes + kv_bytes
     all_bytes = north_star_bytes + proj_bytes
-    gateup_bytes = U * 2 * cfg.d * cfg.F * eb            # algorithmic bytes of the dominant kernel per launch
-    # an event pair around an empty stage (no shared experts at this shape) measures the
-    # event-to-event overhead, which is taken off the kernel's stage time
-    ev_overhead_ms = stage_ms["shared"] if cfg.n_shared == 0 else 0.0
+    # algorithmic bytes of the dominant kernel per launch (shared experts ride in the same launch)
+    gateup_bytes = (U + cfg.n_shared) * 2 * cfg.d * cfg.F * eb
+    # the "shared" stage launches nothing (shared experts are slots of the grouped GEMMs), so its
+    # event pair measures the event-to-event overhead, which is taken off the kernel's stage time
+    ev_overhead_ms = stage_ms["shared"]
     gateup_ms = max(stage_ms["gateup"] - ev_overhead_ms, 1e-6)
     gateup_s = gateup_ms * 1e-3
     achieved = gateup_bytes / gateup_s / 1e9

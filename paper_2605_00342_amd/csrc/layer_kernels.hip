@@ -301,99 +301,121 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ kc, const uint16_t* __restrict__ vc,
     long long seq_stride, long long head_stride, const int32_t* __restrict__ ctx_len, int max_ctx,
     const int32_t* __restrict__ tree_off, const uint16_t* __restrict__ k_new, const uint16_t* __restrict__ v_new,
-    const uint64_t* __restrict__ anc, int Hq, int Hkv, int ctx_splits, int row_blocks, int T,
+    const uint64_t* __restrict__ anc, int Hq, int Hkv, int ctx_splits, int keys_per_split, int row_blocks, int T,
     float* __restrict__ part_o, float* __restrict__ part_ml, int n_single) {
   constexpr int LDK = D + 8;            // bf16 per K row in LDS (16-byte pad)
   constexpr int LDV = kMfmaKeys + 4;    // bf16 per V^T row in LDS
   constexpr int CH = D / 8;             // 16-byte chunks per row
   constexpr int KT = kMfmaKeys / 16;    // key tiles
   constexpr int KB = D / 32;            // contraction blocks of Q K^T
+  constexpr int DT = D / 16;            // output column tiles
   extern __shared__ __attribute__((aligned(16))) uint16_t s_kv[];
   uint16_t* s_k = s_kv;                          // [128][LDK]
   uint32_t* s_vt = reinterpret_cast<uint32_t*>(s_kv + kMfmaKeys * LDK);  // [D][LDV/2] key pairs
   const int split = blockIdx.x / row_blocks, rb = blockIdx.x - split * row_blocks;
   const int g = blockIdx.y, b = blockIdx.z;
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lo = n_single > 0 ? 0 : tree_off[b];
   int n = n_single > 0 ? n_single : tree_off[b + 1] - lo;
   n = n > EVICT_MAX_TREE_NODES ? EVICT_MAX_TREE_NODES : n;
   int L = ctx_len[b];
   L = L < 0 ? 0 : (L > max_ctx ? max_ctx : L);
   const bool tree_part = split >= ctx_splits;
-  const int key0 = tree_part ? 0 : split * kMfmaKeys;
-  int nkeys = (tree_part ? n : L) - key0;
-  nkeys = nkeys > kMfmaKeys ? kMfmaKeys : nkeys;
+  // keys of this split: a range of the cache, or the sequence's draft nodes
+  const int key_begin = tree_part ? 0 : split * keys_per_split;
+  int key_end = tree_part ? n : key_begin + keys_per_split;
+  if (!tree_part && key_end > L) key_end = L;
   const int G = Hq / Hkv;
   const int R = n * G;
   const int ntiles = (R + 15) >> 4;
-  const int per_rb = (ntiles + row_blocks - 1) / row_blocks;
-  const int t_begin = rb * per_rb;
-  int t_end = t_begin + per_rb;
-  t_end = t_end > ntiles ? ntiles : t_end;
-  if (t_begin >= t_end) return;
-  if (nkeys <= 0) {
+  // one 16-row query tile per wavefront (the host sizes row_blocks for that)
+  const int rt = rb * 4 + w;
+  const bool active = rt < ntiles;
+  const int kq = lane >> 4, ln = lane & 15;
+  if (key_begin >= key_end) {
     // split lies beyond this sequence's context: mark its rows empty for the merge
-    for (int r = t_begin * 16 + tid; r < t_end * 16 && r < R; r += 256) {
-      const int i = r / G, hh = r - i * G;
+    if (active && kq == 0 && rt * 16 + ln < R) {
+      const int r = rt * 16 + ln, i = r / G, hh = r - i * G;
       const size_t prow = ((size_t)split * T + lo + i) * Hq + g * G + hh;
       part_ml[prow * 2] = -INFINITY;
       part_ml[prow * 2 + 1] = 0.0f;
     }
     return;
   }
+  if (rb * 4 >= ntiles) return;
 
-  // ---- this wavefront's first query tile is fetched before the K/V staging so that the two
-  // round trips overlap
+  // ---- this wavefront's query rows are fetched before the K/V staging: the round trips overlap
   const float scale = 1.0f / sqrtf((float)D);
-  const int kq = lane >> 4, ln = lane & 15;
-  u32x4 Qn[KB];
-  uint64_t a0n = ~0ull, a1n = ~0ull;
-  auto fetch_rows = [&](int rt) {
-    int r = rt * 16 + ln;
-    r = r < R ? r : R - 1;
-    const int i = r / G, hh = r - i * G;
-    const int t = lo + i;
-    const uint16_t* qrow = q + ((size_t)t * Hq + g * G + hh) * D + kq * 8;
+  int r = rt * 16 + ln;
+  r = r < R ? r : R - 1;
+  const int qi = r / G, qh = r - qi * G;
+  const int t = lo + qi;
+  u32x4 Qf[KB];
+  uint64_t a0 = ~0ull, a1 = ~0ull;
+  if (active) {
+    const uint16_t* qrow = q + ((size_t)t * Hq + g * G + qh) * D + kq * 8;
 #pragma unroll
-    for (int kb = 0; kb < KB; ++kb) Qn[kb] = *reinterpret_cast<const u32x4*>(qrow + kb * 32);
-    if (tree_part) { a0n = anc[2 * (size_t)t]; a1n = anc[2 * (size_t)t + 1]; }
-  };
-  if (t_begin + w < t_end) fetch_rows(t_begin + w);
-
-  // ---- stage K (row-major) and V (transposed, two keys per dword)
-  const uint16_t* kbase = tree_part ? k_new + ((size_t)lo * Hkv + g) * D : kc + (size_t)b * seq_stride + (size_t)g * head_stride + (size_t)key0 * D;
-  const uint16_t* vbase = tree_part ? v_new + ((size_t)lo * Hkv + g) * D : vc + (size_t)b * seq_stride + (size_t)g * head_stride + (size_t)key0 * D;
+    for (int kb = 0; kb < KB; ++kb) Qf[kb] = *reinterpret_cast<const u32x4*>(qrow + kb * 32);
+    if (tree_part) { a0 = anc[2 * (size_t)t]; a1 = anc[2 * (size_t)t + 1]; }
+  }
+  const uint16_t* kbase = tree_part ? k_new + ((size_t)lo * Hkv + g) * D : kc + (size_t)b * seq_stride + (size_t)g * head_stride;
+  const uint16_t* vbase = tree_part ? v_new + ((size_t)lo * Hkv + g) * D : vc + (size_t)b * seq_stride + (size_t)g * head_stride;
   const size_t kstep = tree_part ? (size_t)Hkv * D : (size_t)D;  // elements between consecutive keys
-  for (int idx = tid; idx < kMfmaKeys * CH; idx += 256) {
-    const int j = idx / CH, c = idx - j * CH;
-    u32x4 v = {0, 0, 0, 0};
-    if (j < nkeys) v = *reinterpret_cast<const u32x4*>(kbase + j * kstep + c * 8);
-    *reinterpret_cast<u32x4*>(s_k + j * LDK + c * 8) = v;
-  }
-  for (int idx = tid; idx < (kMfmaKeys / 2) * CH; idx += 256) {
-    const int jp = idx / CH, c = idx - jp * CH;
-    u32x4 v0 = {0, 0, 0, 0}, v1 = {0, 0, 0, 0};
-    if (2 * jp < nkeys) v0 = *reinterpret_cast<const u32x4*>(vbase + (2 * jp) * kstep + c * 8);
-    if (2 * jp + 1 < nkeys) v1 = *reinterpret_cast<const u32x4*>(vbase + (2 * jp + 1) * kstep + c * 8);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const uint32_t a = v0[i], bb = v1[i];
-      s_vt[(c * 8 + 2 * i) * (LDV / 2) + jp] = (a & 0xFFFFu) | (bb << 16);
-      s_vt[(c * 8 + 2 * i + 1) * (LDV / 2) + jp] = (a >> 16) | (bb & 0xFFFF0000u);
-    }
-  }
-  __syncthreads();
 
-  for (int rt = t_begin + w; rt < t_end; rt += 4) {
-    int r = rt * 16 + ln;
-    r = r < R ? r : R - 1;
-    const int i = r / G, hh = r - i * G;
-    const int t = lo + i;
-    u32x4 Qf[KB];
+  // running softmax state of this wavefront's 16 rows over the chunks of the split
+  f32x4 O[DT];
 #pragma unroll
-    for (int kb = 0; kb < KB; ++kb) Qf[kb] = Qn[kb];
-    const uint64_t a0 = a0n, a1 = a1n;
-    if (rt + 4 < t_end) fetch_rows(rt + 4);  // next tile's rows travel while this one is computed
+  for (int dt = 0; dt < DT; ++dt) O[dt] = f32x4{0, 0, 0, 0};
+  float m_run = -INFINITY, l_run = 0.0f;
+
+  // K/V of a chunk travel global -> registers -> LDS, all loads issued before the first LDS
+  // write so one memory round trip covers the chunk. (Issuing the next chunk's loads ahead of
+  // the MFMA work was measured and gained nothing: two workgroups per CU already overlap.)
+  constexpr int KI = kMfmaKeys * CH / 256, VI = (kMfmaKeys / 2) * CH / 256;
+  u32x4 kreg[KI], vreg0[VI], vreg1[VI];
+  auto fetch_chunk = [&](int kc0) {
+    int nk = key_end - kc0;
+    nk = nk > kMfmaKeys ? kMfmaKeys : nk;
+#pragma unroll
+    for (int it = 0; it < KI; ++it) {
+      const int idx = tid + 256 * it, j = idx / CH, c = idx - j * CH;
+      kreg[it] = u32x4{0, 0, 0, 0};  // keys past the end are zeros
+      if (j < nk) kreg[it] = *reinterpret_cast<const u32x4*>(kbase + (size_t)(kc0 + j) * kstep + c * 8);
+    }
+#pragma unroll
+    for (int it = 0; it < VI; ++it) {
+      const int idx = tid + 256 * it, jp = idx / CH, c = idx - jp * CH;
+      vreg0[it] = u32x4{0, 0, 0, 0};
+      vreg1[it] = u32x4{0, 0, 0, 0};
+      if (2 * jp < nk) vreg0[it] = *reinterpret_cast<const u32x4*>(vbase + (size_t)(kc0 + 2 * jp) * kstep + c * 8);
+      if (2 * jp + 1 < nk) vreg1[it] = *reinterpret_cast<const u32x4*>(vbase + (size_t)(kc0 + 2 * jp + 1) * kstep + c * 8);
+    }
+  };
+  for (int kc0 = key_begin; kc0 < key_end; kc0 += kMfmaKeys) {
+    int nkeys = key_end - kc0;
+    nkeys = nkeys > kMfmaKeys ? kMfmaKeys : nkeys;
+    fetch_chunk(kc0);
+    if (kc0 != key_begin) __syncthreads();  // the previous chunk has been consumed by every wavefront
+    // ---- K row-major, V transposed (two keys per dword)
+#pragma unroll
+    for (int it = 0; it < KI; ++it) {
+      const int idx = tid + 256 * it, j = idx / CH, c = idx - j * CH;
+      *reinterpret_cast<u32x4*>(s_k + j * LDK + c * 8) = kreg[it];
+    }
+#pragma unroll
+    for (int it = 0; it < VI; ++it) {
+      const int idx = tid + 256 * it, jp = idx / CH, c = idx - jp * CH;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const uint32_t a = vreg0[it][i], bb = vreg1[it][i];
+        s_vt[(c * 8 + 2 * i) * (LDV / 2) + jp] = (a & 0xFFFFu) | (bb << 16);
+        s_vt[(c * 8 + 2 * i + 1) * (LDV / 2) + jp] = (a >> 16) | (bb & 0xFFFF0000u);
+      }
+    }
+    __syncthreads();
+    if (!active) continue;
+
     // S^T tiles: lane holds keys kt*16 + kq*4 + j of query row ln
     f32x4 S[KT];
     float mx = -INFINITY;
@@ -407,7 +429,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
       }
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        const int key = kt * 16 + kq * 4 + j;
+        const int key = kt * 16 + kq * 4 + j;  // (the draft-node split has a single chunk: key = node index)
         const uint64_t word = key < 64 ? a0 : a1;
         const bool vis = key < nkeys && ((word >> (key & 63)) & 1ull);
         acc[j] = vis ? acc[j] * scale : -INFINITY;
@@ -418,6 +440,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
     }
     mx = fmaxf(mx, __shfl_xor(mx, 16));
     mx = fmaxf(mx, __shfl_xor(mx, 32));
+    // online softmax: new running maximum, rescale of what has been accumulated so far
+    const float m_new = fmaxf(m_run, mx);
+    const float alpha = m_run == -INFINITY ? 0.0f : __expf(m_run - m_new);
     float lsum = 0.0f;
     u32x4 Pf[KT / 2];
 #pragma unroll
@@ -425,8 +450,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
       uint32_t pk[2];
 #pragma unroll
       for (int jj = 0; jj < 2; ++jj) {
-        const float p0 = S[kt][2 * jj] == -INFINITY ? 0.0f : __expf(S[kt][2 * jj] - mx);
-        const float p1 = S[kt][2 * jj + 1] == -INFINITY ? 0.0f : __expf(S[kt][2 * jj + 1] - mx);
+        const float p0 = S[kt][2 * jj] == -INFINITY ? 0.0f : __expf(S[kt][2 * jj] - m_new);
+        const float p1 = S[kt][2 * jj + 1] == -INFINITY ? 0.0f : __expf(S[kt][2 * jj + 1] - m_new);
         const uint16_t b0 = f32_to_bf16(p0), b1 = f32_to_bf16(p1);
         lsum += bf16_to_f32(b0) + bf16_to_f32(b1);  // the sum uses the rounded weights the MFMA sees
         pk[jj] = (uint32_t)b0 | ((uint32_t)b1 << 16);
@@ -437,25 +462,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
     }
     lsum += __shfl_xor(lsum, 16);
     lsum += __shfl_xor(lsum, 32);
-    if (kq == 0 && rt * 16 + ln < R) {
-      const size_t prow = ((size_t)split * T + t) * Hq + g * G + hh;
-      part_ml[prow * 2] = mx;
-      part_ml[prow * 2 + 1] = lsum;
-    }
-    // O = P V: lane holds rows kq*4 + j, column dt*16 + ln
-    size_t orow[4];
-    bool ovalid[4];
+    l_run = l_run * alpha + lsum;
+    m_run = m_new;
+    // O = O * alpha + P V: lane holds rows kq*4 + j (their alpha lives in lane kq*4 + j), column dt*16 + ln
+    f32x4 ar;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int r2 = rt * 16 + kq * 4 + j;
-      ovalid[j] = r2 < R;
-      const int rc = ovalid[j] ? r2 : R - 1;
-      const int i2 = rc / G, h2 = rc - i2 * G;
-      orow[j] = (((size_t)split * T + lo + i2) * Hq + g * G + h2) * D;
-    }
-#pragma unroll 2
-    for (int dt = 0; dt < D / 16; ++dt) {
-      f32x4 acc = {0, 0, 0, 0};
+    for (int j = 0; j < 4; ++j) ar[j] = __shfl(alpha, kq * 4 + j);
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+      f32x4 acc = O[dt] * ar;
 #pragma unroll
       for (int bk = 0; bk < KT / 2; ++bk) {
         const uint32_t* vrow = s_vt + (dt * 16 + ln) * (LDV / 2) + bk * 16 + kq * 2;
@@ -464,9 +479,24 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
         const u32x4 vf = {lo2.x, lo2.y, hi2.x, hi2.y};
         acc = mfma_block<BF16>(Pf[bk], vf, acc);
       }
+      O[dt] = acc;
+      if (dt & 1) __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+  if (!active) return;
+  if (kq == 0 && rt * 16 + ln < R) {
+    const size_t prow = ((size_t)split * T + t) * Hq + g * G + qh;
+    part_ml[prow * 2] = m_run;
+    part_ml[prow * 2 + 1] = l_run;
+  }
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
-        if (ovalid[j]) part_o[orow[j] + dt * 16 + ln] = acc[j];
+  for (int j = 0; j < 4; ++j) {
+    const int r2 = rt * 16 + kq * 4 + j;
+    if (r2 < R) {
+      const int i2 = r2 / G, h2 = r2 - i2 * G;
+      float* dst = part_o + (((size_t)split * T + lo + i2) * Hq + g * G + h2) * D + ln;
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) dst[dt * 16] = O[dt][j];
     }
   }
 }
@@ -802,7 +832,7 @@ int launch_gemm_nt(const GemmArgs& a, int grid, hipStream_t s) {
   } else if (need <= 4) {
     EVICT_GEMM_LAUNCH(4, 4, false);
   } else {
-    EVICT_GEMM_LAUNCH(8, 2, false);
+    EVICT_GEMM_LAUNCH(8, 1, false);
   }
 #undef EVICT_GEMM_LAUNCH
   return launch_status("gemm_stream_kernel");
@@ -899,22 +929,26 @@ int launch_attention(const evict_ctx* c, const void* kc, const void* vc, long lo
   const evict_model_desc& m = c->m;
   int ctx_splits, nsplits, keys;
   if (m.dtype == EVICT_BF16) {
-    keys = kMfmaKeys;
-    ctx_splits = (max_ctx_host + keys - 1) / keys;
-    nsplits = ctx_splits + 1;
-    // spread the query-row tiles over enough workgroups to cover the chip
+    // one 16-row query tile per wavefront; enough context splits to cover the chip, each a whole
+    // number of 128-key chunks (more chunks per split = fewer partial results to merge)
     const int G = m.Hq / m.Hkv;
     const int max_nodes = T < EVICT_MAX_TREE_NODES ? T : EVICT_MAX_TREE_NODES;
     const int ntiles = (max_nodes * G + 15) / 16;
-    int rb = c->attn_row_blocks > 0 ? c->attn_row_blocks : (256 + nsplits * m.Hkv * B - 1) / (nsplits * m.Hkv * B);
-    const int rb_max = (ntiles + 3) / 4;
-    rb = rb > rb_max ? rb_max : rb;
-    rb = rb < 1 ? 1 : rb;
+    const int rb = c->attn_row_blocks > 0 ? c->attn_row_blocks : (ntiles + 3) / 4;
+    int want = 512 / (m.Hkv * B * rb);  // context splits that give every CU two workgroups to overlap
+    want = want < 1 ? 1 : want;
+    int chunks = (max_ctx_host + kMfmaKeys - 1) / kMfmaKeys;
+    int cps = (chunks + want - 1) / want;  // chunks per split
+    cps = cps < 1 ? 1 : cps;
+    keys = cps * kMfmaKeys;
+    ctx_splits = (max_ctx_host + keys - 1) / keys;
+    nsplits = ctx_splits + 1;
+    EVICT_REQUIRE(rb * 4 >= ntiles, EVICT_E_INVALID, "attn_row_blocks=%d is too small for %d query tiles", rb, ntiles);
     const dim3 grid(nsplits * rb, m.Hkv, B);
     const size_t lds = attn_mfma_lds_bytes(m.D);
 #define EVICT_ATTN_ARGS (const uint16_t*)c->q, (const uint16_t*)kc, (const uint16_t*)vc, seq_stride, head_stride, ctx_len, \
                         max_ctx_host, tree_off, (const uint16_t*)k_new, (const uint16_t*)v_new, c->anc, m.Hq, m.Hkv,       \
-                        ctx_splits, rb, T, c->part_o, c->part_ml, B == 1 ? T : 0
+                        ctx_splits, keys, rb, T, c->part_o, c->part_ml, B == 1 ? T : 0
     if (m.D == 128) hipLaunchKernelGGL(attn_partial_mfma_kernel<128>, grid, dim3(256), lds, s, EVICT_ATTN_ARGS);
     else hipLaunchKernelGGL(attn_partial_mfma_kernel<64>, grid, dim3(256), lds, s, EVICT_ATTN_ARGS);
 #undef EVICT_ATTN_ARGS
