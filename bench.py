@@ -45,7 +45,35 @@ def parse():
     ap.add_argument("--tune", action="append", default=[], help="key=value launch-shape knob (evict_tune)")
     ap.add_argument("--sweep", action="store_true",
                     help="not the default line: one JSON line per (N, sigma) point, N in 1..128, sigma in {0.2, 0.5, 1.0}")
+    ap.add_argument("--probe-copy", type=int, default=0, metavar="MiB",
+                    help="not the default line: run the plain copy and read kernels on MiB bytes (counter "
+                         "calibration under rocprofv3 --pmc, and the streaming-read ceiling) and exit")
     return ap.parse_args()
+
+
+def probe_copy(mib):
+    """Plain copy / read kernels of a known size: what the HBM byte counters are scaled by."""
+    import torch
+
+    import paper_2605_00342_amd as ev
+
+    n = mib * 1024 * 1024
+    a = torch.empty(n, dtype=torch.uint8, device="cuda:0").random_(0, 255)
+    b = torch.empty_like(a)
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda:0")
+    out = {"probe_bytes": n}
+    for name, fn in (("copy", lambda: ev.evict_probe_copy(a, b, n)), ("read", lambda: ev.evict_probe_read(a, n, sink))):
+        for _ in range(2):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 5
+        out[name + "_GBps"] = round((2 if name == "copy" else 1) * n / ms / 1e6, 1)
+    print(json.dumps(out))
 
 
 def sweep(args):
@@ -115,6 +143,9 @@ def main():
         sys.exit(1)
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.probe_copy:
+        probe_copy(args.probe_copy)
+        return
     if args.sweep:
         sweep(args)
         return

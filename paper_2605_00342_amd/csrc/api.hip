@@ -118,6 +118,7 @@ int evict_create(evict_ctx** out, const evict_model_desc* m, int max_tokens, int
   c.timing = 0;
   c.moe_grid = 2048;
   c.moe_prefetch = 1;
+  c.moe_down_kernel = 1;
   c.moe_chunk_gateup = 1;
   c.moe_chunk_down = 1;
   for (int cu : {4, 2}) if ((m->d / 16) % cu == 0) { c.moe_chunk_down = cu; break; }
@@ -347,6 +348,7 @@ static int verify_layer_impl(evict_ctx* ctx, const evict_layer_weights* w, const
     a.ldo = m.d;
     a.chunk_units = ctx->moe_chunk_down;
     a.prefetch = ctx->moe_prefetch;
+    a.wave_strip = ctx->moe_down_kernel;
     rc = launch_gemm(m.dtype, EPI_F32, a, nt_exp, ctx->moe_grid, s);
     if (rc) return rc;
   }
@@ -463,6 +465,9 @@ int evict_tune(evict_ctx* ctx, const char* key, int value) {
   } else if (!strcmp(key, "moe_chunk_down")) {
     EVICT_REQUIRE(value >= 1 && (ctx->m.d / 16) % value == 0, EVICT_E_INVALID, "evict_tune: moe_chunk_down=%d must divide d/16", value);
     ctx->moe_chunk_down = value;
+  } else if (!strcmp(key, "moe_down_kernel")) {
+    EVICT_REQUIRE(value == 0 || value == 1, EVICT_E_INVALID, "evict_tune: moe_down_kernel must be 0 or 1");
+    ctx->moe_down_kernel = value;
   } else if (!strcmp(key, "attn_row_blocks")) {
     EVICT_REQUIRE(value >= 0 && value <= 64, EVICT_E_INVALID, "evict_tune: attn_row_blocks=%d out of range", value);
     ctx->attn_row_blocks = value;

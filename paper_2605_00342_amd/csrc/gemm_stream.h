@@ -46,6 +46,7 @@ struct GemmArgs {
   int T;                 // dense: token rows
   int dense_tiles;       // dense: workgroups per strip, each taking 16*NT tokens
   int prefetch;          // host-side choice of the kernel variant (weight-load stages), 0 = default
+  int wave_strip;        // host-side: grouped fp32-output GEMM may use gemm_wave_strip_kernel
   void* out0;            // QKV: q; RESID: h; SWIGLU: act; F32: y; ARGMAX: best value per (strip, token)
   void* out1;            // QKV: k_new; ARGMAX: row index of the best value per (strip, token)
   void* out2;            // QKV: v_new
@@ -306,6 +307,82 @@ __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(NT
     const unsigned unit = (i / (unsigned)a.dense_tiles) * 8u + xcd;
     if (unit >= (unsigned)upg) return;
     run_segment(0, (int)unit, 1, (int)tile * 16 * NT, (int)(tile + 1) * 16 * NT);
+  }
+}
+
+// ------------------------------------------------------------------------------------
+// Second decomposition for grouped GEMMs with many strips and a short contraction (the down
+// projections: d/16 strips of F columns per expert): one strip per wavefront over the whole
+// contraction range, so no partial tiles are exchanged and nothing synchronises the wavefronts
+// after the token operand has been staged. The 16 x K token operand of the slot sits in LDS as
+// ready-made MFMA operand blocks; weight blocks travel through a rolling window of WIN
+// registers per lane (WIN KiB in flight per wavefront); NB operand blocks are staged per wavefront and
+// pass. A workgroup takes WS consecutive strips
+// of one slot (chunk); chunks are dealt round-robin like in gemm_stream_kernel.
+// Output: fp32 rows y[p0 + column][strip * 16 + ...] (the EPI_F32 contract).
+// LDS: nkb KiB (dynamic).
+// ------------------------------------------------------------------------------------
+template <typename ST, int WIN, int NB, bool EXACT, int WS = 8>
+__global__ __launch_bounds__(WS * 64) __attribute__((amdgpu_waves_per_eu(4))) void gemm_wave_strip_kernel(const GemmArgs a) {
+  extern __shared__ __attribute__((aligned(16))) u32x4 s_b[];  // [nkb][64]
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int nkb = a.nkb;
+  const int cpg = a.n_strips / WS;  // chunks per slot (host-checked: divides)
+  const int total = *a.union_count * cpg;
+  bool first = true;
+  for (int chunk = blockIdx.x; chunk < total; chunk += gridDim.x) {
+    const int slot = chunk / cpg, strip = (chunk - slot * cpg) * WS + w;
+    const WorkRec* rec = a.work + slot;
+    const int p0 = rec->p0, ntok = rec->ntok, ex = rec->expert;
+    const bool once = (rec->pad & 0xFFFF) == 1;  // single token tile: nobody else reads these weights
+    const u32x4* wbase = ex < a.n_routed ? a.W + (long long)ex * a.group_stride
+                                         : a.W_shared + (long long)(ex - a.n_routed) * a.group_stride;
+    // token operand first, weights behind it: the in-order load counter then lets the operand
+    // be consumed while the weight window is still in flight
+    int col = lane & 15;
+    const bool valid = col < ntok;
+    col = valid ? col : ntok - 1;  // padded columns repeat the last token; never stored
+    const long long xr = a.x_by_token ? a.tok_of_pos[p0 + col] : p0 + col;
+    const char* xrow = (const char*)a.X + xr * a.ldx_bytes + (lane >> 4) * 16;
+    constexpr int BMAX = NB;  // operand blocks a wavefront stages per pass
+    const u32x4* wp = wbase + (long long)strip * nkb * 64 + lane;
+    u32x4 A[WIN];
+    for (int kb0 = 0; kb0 < nkb; kb0 += BMAX * WS) {
+      u32x4 bst[BMAX];
+#pragma unroll
+      for (int i = 0; i < BMAX; ++i) {
+        const int kb = kb0 + i * WS + w;
+        if (kb < nkb) bst[i] = *reinterpret_cast<const u32x4*>(xrow + (long long)kb * 64);
+      }
+      if (kb0 == 0) {
+#pragma unroll
+        for (int j = 0; j < WIN; ++j)
+          if (EXACT || j < nkb) A[j] = once ? __builtin_nontemporal_load(wp + j * 64) : wp[j * 64];
+        if (!first) lds_barrier();  // every wavefront is done with the previous chunk's operand
+      }
+#pragma unroll
+      for (int i = 0; i < BMAX; ++i) {
+        const int kb = kb0 + i * WS + w;
+        if (kb < nkb) s_b[kb * 64 + lane] = bst[i];
+      }
+    }
+    lds_barrier();
+    first = false;
+    f32x4 acc = {0, 0, 0, 0};
+    for (int j0 = 0; j0 < nkb; j0 += WIN) {
+#pragma unroll
+      for (int jj = 0; jj < WIN; ++jj) {
+        const int j = j0 + jj;
+        if (EXACT || j < nkb) {
+          const u32x4 bf = s_b[j * 64 + lane];
+          acc = mfma_block<ST>(A[jj], bf, acc);
+          if (j + WIN < nkb) A[jj] = once ? __builtin_nontemporal_load(wp + (j + WIN) * 64) : wp[(j + WIN) * 64];
+        }
+      }
+    }
+    if (valid)
+      *reinterpret_cast<f32x4*>((float*)a.out0 + (p0 + (lane & 15)) * a.ldo + strip * 16 + (lane >> 4) * 4) = acc;
   }
 }
 

@@ -501,51 +501,61 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
   }
 }
 
-// merge of the per-split partial softmaxes: grid (T*Hq), block D threads. Empty splits carry
-// max = -inf.
+// merge of the per-split partial softmaxes. D/4 lanes per (token, head) row, each with four
+// consecutive output columns; 256 / (D/4) rows per workgroup (D is 64 or 128, so the lanes of a
+// row sit in one wavefront). Empty splits carry max = -inf and their partial rows are never read
+// into the sum. The partial rows of the first splits are requested before the (max, sum) pairs
+// are reduced, so the two round trips overlap.
+constexpr int kMergeBatch = 16;
+
 template <typename ST>
-__global__ void attn_merge_kernel(const float* __restrict__ part_o, const float* __restrict__ part_ml, int nsplits,
-                                  int T, int Hq, int D, void* __restrict__ out, void* __restrict__ aux_out) {
-  __shared__ float s_sc[2][192];  // per-split weights, one copy per wavefront
-  const int row = blockIdx.x;     // t * Hq + h
-  const int c = threadIdx.x, lane = c & 63, w = c >> 6;
-  // each lane fetches the (max, sum) of different splits
+__global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict__ part_o, const float* __restrict__ part_ml,
+                                                         int nsplits, int rows, int D, void* __restrict__ out,
+                                                         void* __restrict__ aux_out) {
+  const int lpr = D >> 2;  // lanes per row: 16 or 32
+  const int tid = threadIdx.x;
+  const int row = blockIdx.x * (256 / lpr) + tid / lpr;
+  const int c4 = tid & (lpr - 1);
+  if (row >= rows) return;  // (whole row groups leave together; no barrier follows)
+  const size_t sstride = (size_t)rows * D;
+  const float* po = part_o + (size_t)row * D + c4 * 4;
+  const float* pml = part_ml + (size_t)row * 2;
+  f32x4 v[kMergeBatch];
+#pragma unroll
+  for (int i = 0; i < kMergeBatch; ++i)
+    v[i] = i < nsplits ? *reinterpret_cast<const f32x4*>(po + (size_t)i * sstride) : f32x4{0, 0, 0, 0};
+  // global maximum and normaliser: the lanes of a row share the splits between them
   float M = -INFINITY;
-  float lpart[3] = {0.0f, 0.0f, 0.0f};
-#pragma unroll
-  for (int i = 0; i < 3; ++i) {
-    const int s = i * 64 + lane;
-    float ms = -INFINITY;
-    if (s < nsplits) {
-      const float2 ml = *reinterpret_cast<const float2*>(part_ml + ((size_t)s * T * Hq + row) * 2);
-      ms = ml.x;
-      lpart[i] = ml.y;
-    }
-    if (s < 192) s_sc[w][s] = ms;
-    M = fmaxf(M, ms);
-  }
-  M = wave_max(M);
+  for (int sp = c4; sp < nsplits; sp += lpr) M = fmaxf(M, pml[(size_t)sp * rows * 2]);
+  for (int o = 1; o < lpr; o <<= 1) M = fmaxf(M, __shfl_xor(M, o));
   float l = 0.0f;
+  for (int sp = c4; sp < nsplits; sp += lpr) {
+    const float2 ml = *reinterpret_cast<const float2*>(pml + (size_t)sp * rows * 2);
+    l += ml.x == -INFINITY ? 0.0f : ml.y * __expf(ml.x - M);
+  }
+  for (int o = 1; o < lpr; o <<= 1) l += __shfl_xor(l, o);
+  f32x4 acc = {0, 0, 0, 0};
+  for (int s0 = 0; s0 < nsplits; s0 += kMergeBatch) {
+    if (s0 > 0) {
 #pragma unroll
-  for (int i = 0; i < 3; ++i) {
-    const int s = i * 64 + lane;
-    if (s < nsplits) {
-      const float ms = s_sc[w][s];
-      const float sc = ms == -INFINITY ? 0.0f : __expf(ms - M);
-      l += lpart[i] * sc;
-      s_sc[w][s] = sc;
+      for (int i = 0; i < kMergeBatch; ++i)
+        v[i] = s0 + i < nsplits ? *reinterpret_cast<const f32x4*>(po + (size_t)(s0 + i) * sstride) : f32x4{0, 0, 0, 0};
+    }
+#pragma unroll
+    for (int i = 0; i < kMergeBatch; ++i) {
+      if (s0 + i < nsplits) {
+        const float ms = pml[(size_t)(s0 + i) * rows * 2];
+        const float sc = ms == -INFINITY ? 0.0f : __expf(ms - M);
+        if (sc != 0.0f) acc += v[i] * sc;  // rows of empty splits hold no data
+      }
     }
   }
-  l = wave_sum(l);
-  float o = 0.0f;
-#pragma unroll 8
-  for (int s = 0; s < nsplits; ++s) {
-    const float sc = s_sc[w][s];
-    if (sc != 0.0f) o += part_o[((size_t)s * T * Hq + row) * D + c] * sc;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const float r = acc[j] / l;
+    store_elem<ST>(out, (size_t)row * D + c4 * 4 + j, r);
+    if (aux_out) store_elem<ST>(aux_out, (size_t)row * D + c4 * 4 + j, r);
   }
-  const float r = o / l;
-  store_elem<ST>(out, (size_t)row * D + c, r);
-  if (aux_out) store_elem<ST>(aux_out, (size_t)row * D + c, r);
 }
 
 // ------------------------------------------------------------------------------------
@@ -557,6 +567,7 @@ __global__ void attn_merge_kernel(const float* __restrict__ part_o, const float*
 // ------------------------------------------------------------------------------------
 constexpr int kRouterWaves = 16;
 constexpr int kRouterThreads = kRouterWaves * 64;
+constexpr int kFusedTopkTokens = 64;  // up to here TopK and the union share one workgroup
 
 template <typename ST>
 __global__ __launch_bounds__(kRouterThreads) void router_logits_kernel(
@@ -734,6 +745,99 @@ __global__ __launch_bounds__(kRouterThreads) void topk_kernel(
   }
 }
 
+// TopK of one token by one wavefront with the scores held in registers (E <= 64 * NR): the same
+// selection rule as topk_kernel, without the LDS round trips. Lane j ends up with the j-th pick.
+// Returns the expert index picked at position `lane` (for lane < k) and its softmax weight.
+template <int NR>
+__device__ __forceinline__ void topk_wave_regs(const float* __restrict__ row, int E, int k, int lane, int* my_idx,
+                                               float* my_w) {
+  unsigned key[NR];
+#pragma unroll
+  for (int i = 0; i < NR; ++i) {
+    const int e = i * 64 + lane;
+    unsigned o = 0u;
+    if (e < E) {
+      unsigned bits = __float_as_uint(row[e]);
+      bits = bits == 0x80000000u ? 0u : bits;
+      o = bits ^ ((bits >> 31) ? 0xFFFFFFFFu : 0x80000000u);
+      o = o == 0u ? 1u : o;
+    }
+    key[i] = o;
+  }
+  unsigned mine = 0u;
+  int mine_idx = 0;
+#pragma unroll 1
+  for (int j = 0; j < k; ++j) {
+    unsigned local = key[0];
+#pragma unroll
+    for (int i = 1; i < NR; ++i) local = key[i] > local ? key[i] : local;
+    const unsigned best = wave_max_u32(local);
+    int sel = -1;
+#pragma unroll
+    for (int i = 0; i < NR; ++i) {
+      const unsigned long long m = __ballot(key[i] == best);
+      if (sel < 0 && m) sel = i * 64 + (int)__ffsll((long long)m) - 1;
+    }
+#pragma unroll
+    for (int i = 0; i < NR; ++i)
+      if (i * 64 + lane == sel) key[i] = 0u;
+    if (lane == j) { mine = best; mine_idx = sel; }
+  }
+  const float val = __uint_as_float(mine ^ ((mine >> 31) ? 0x80000000u : 0xFFFFFFFFu));
+  const float first = __shfl(val, 0);
+  const float ex = lane < k ? __expf(val - first) : 0.0f;
+  const float denom = wave_sum(ex);
+  *my_idx = mine_idx;
+  *my_w = ex / denom;
+}
+
+// Register variant of topk_kernel for E <= 256: grid over groups of 16 tokens, one per wavefront.
+__global__ __launch_bounds__(kRouterThreads) void topk_regs_kernel(
+    const float* __restrict__ logits, int T, int E, int k, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
+    int32_t* __restrict__ aux_idx, float* __restrict__ aux_w) {
+  const int lane = threadIdx.x & 63;
+  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int t = blockIdx.x * kRouterWaves + w;
+  if (t >= T) return;
+  int idx;
+  float wv;
+  topk_wave_regs<4>(logits + (size_t)t * E, E, k, lane, &idx, &wv);
+  if (lane < k) {
+    topk_idx[(size_t)t * k + lane] = idx;
+    topk_w[(size_t)t * k + lane] = wv;
+    if (aux_idx) aux_idx[(size_t)t * k + lane] = idx;
+    if (aux_w) aux_w[(size_t)t * k + lane] = wv;
+  }
+}
+
+// Small token counts: TopK (register variant) and the expert union in one workgroup, the
+// wavefronts taking the tokens in turn; saves a launch when there are few tokens to share out.
+__global__ __launch_bounds__(kRouterThreads) void topk_union_kernel(
+    const float* __restrict__ logits, int T, int E, int k, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
+    int32_t* __restrict__ aux_idx, float* __restrict__ aux_w, int use_masks, int32_t* __restrict__ union_ids,
+    int32_t* __restrict__ union_count, int32_t* __restrict__ hist, int32_t* __restrict__ offsets,
+    int32_t* __restrict__ perm, int32_t* __restrict__ inv, int32_t* __restrict__ status, WorkRec* __restrict__ work,
+    int32_t* __restrict__ tok_of_pos, int32_t* __restrict__ slot_count, int n_shared) {
+  extern __shared__ __attribute__((aligned(16))) int s_all[];
+  const int lane = threadIdx.x & 63;
+  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  for (int t = w; t < T; t += kRouterWaves) {
+    int idx;
+    float wv;
+    topk_wave_regs<4>(logits + (size_t)t * E, E, k, lane, &idx, &wv);
+    if (lane < k) {
+      s_all[t * k + lane] = idx;  // where expert_union_body expects the pairs
+      topk_idx[(size_t)t * k + lane] = idx;
+      topk_w[(size_t)t * k + lane] = wv;
+      if (aux_idx) aux_idx[(size_t)t * k + lane] = idx;
+      if (aux_w) aux_w[(size_t)t * k + lane] = wv;
+    }
+  }
+  __syncthreads();
+  expert_union_body(s_all, nullptr, T, k, E, use_masks, union_ids, union_count, hist, offsets, perm, inv, status, work,
+                    tok_of_pos, slot_count, n_shared);
+}
+
 // expert union and grouping (Eq. 5) with the device-side work list, one workgroup
 __global__ __launch_bounds__(kRouterThreads) void union_worklist_kernel(
     const int32_t* __restrict__ topk_idx, int T, int k, int E, int use_masks, int32_t* __restrict__ union_ids,
@@ -838,8 +942,28 @@ int launch_gemm_nt(const GemmArgs& a, int grid, hipStream_t s) {
   return launch_status("gemm_stream_kernel");
 }
 
+// one strip per wavefront (see gemm_wave_strip_kernel): grouped, fp32 output rows
+template <typename ST>
+int launch_gemm_wave_strip(const GemmArgs& a, int grid, hipStream_t s) {
+  const int nkb = a.nkb;
+  const size_t lds = (size_t)nkb * 1024;
+#define EVICT_WS_LAUNCH(WIN_, NB_, EXACT_) \
+  hipLaunchKernelGGL((gemm_wave_strip_kernel<ST, WIN_, NB_, EXACT_>), dim3(grid), dim3(8 * 64), lds, s, a)
+  // (windows sized to stay under 128 VGPRs together with the staged operand blocks)
+  if (nkb == 24) EVICT_WS_LAUNCH(12, 3, true);
+  else if (nkb == 44) EVICT_WS_LAUNCH(11, 6, true);
+  else if (nkb % 16 == 0) EVICT_WS_LAUNCH(16, 4, true);
+  else if (nkb % 8 == 0) EVICT_WS_LAUNCH(8, 2, true);
+  else EVICT_WS_LAUNCH(16, 4, false);
+#undef EVICT_WS_LAUNCH
+  return launch_status("gemm_wave_strip_kernel");
+}
+
+bool wave_strip_applies(const GemmArgs& a) { return a.grouped && a.n_strips % 8 == 0 && a.nkb <= 64; }
+
 template <typename ST, int EPI>
 int launch_gemm_st(const GemmArgs& a, int nt, int grid, hipStream_t s) {
+  if (EPI == EPI_F32 && a.wave_strip && wave_strip_applies(a)) return launch_gemm_wave_strip<ST>(a, grid, s);
   return nt == 1 ? launch_gemm_nt<ST, 1, EPI>(a, grid, s) : launch_gemm_nt<ST, 2, EPI>(a, grid, s);
 }
 
@@ -962,12 +1086,14 @@ int launch_attention(const evict_ctx* c, const void* kc, const void* vc, long lo
   }
   int rc = launch_status("attention partial kernel");
   if (rc) return rc;
+  const int mrows = T * m.Hq, rows_per_wg = 256 / (m.D / 4);
+  const dim3 mgrid((mrows + rows_per_wg - 1) / rows_per_wg);
   if (m.dtype == EVICT_BF16)
-    hipLaunchKernelGGL(attn_merge_kernel<BF16>, dim3(T * m.Hq), dim3(m.D), 0, s, c->part_o, c->part_ml, nsplits, T, m.Hq,
-                       m.D, c->attn_o, aux_out);
+    hipLaunchKernelGGL(attn_merge_kernel<BF16>, mgrid, dim3(256), 0, s, c->part_o, c->part_ml, nsplits, mrows, m.D,
+                       c->attn_o, aux_out);
   else
-    hipLaunchKernelGGL(attn_merge_kernel<F32>, dim3(T * m.Hq), dim3(m.D), 0, s, c->part_o, c->part_ml, nsplits, T, m.Hq,
-                       m.D, c->attn_o, aux_out);
+    hipLaunchKernelGGL(attn_merge_kernel<F32>, mgrid, dim3(256), 0, s, c->part_o, c->part_ml, nsplits, mrows, m.D,
+                       c->attn_o, aux_out);
   return launch_status("attn_merge_kernel");
 }
 
@@ -991,13 +1117,28 @@ int launch_router(const evict_ctx* c, const void* gain, const void* wg, int T, c
 
 int launch_topk_union(const evict_ctx* c, int T, const evict_layer_aux* aux, hipStream_t s) {
   const evict_model_desc& m = c->m;
-  const size_t lds_topk = (size_t)kRouterWaves * (64 + m.E) * sizeof(float);
-  hipLaunchKernelGGL(topk_kernel, dim3((T + kRouterWaves - 1) / kRouterWaves), dim3(kRouterThreads), lds_topk, s, c->logits,
-                     T, m.E, m.k, c->topk_idx, c->topk_w, aux ? aux->topk_idx : nullptr, aux ? aux->topk_w : nullptr);
-  int rc = launch_status("topk_kernel");
-  if (rc) return rc;
+  int32_t* a_idx = aux ? aux->topk_idx : nullptr;
+  float* a_w = aux ? aux->topk_w : nullptr;
   size_t lds;
   const int use_masks = union_mask_plan(T, m.k, m.E, &lds);
+  const bool regs = m.E <= 256;
+  if (regs && T <= kFusedTopkTokens) {
+    hipLaunchKernelGGL(topk_union_kernel, dim3(1), dim3(kRouterThreads), lds, s, c->logits, T, m.E, m.k, c->topk_idx,
+                       c->topk_w, a_idx, a_w, use_masks, c->union_ids, c->union_count, c->hist, c->offsets, c->perm, c->inv,
+                       c->status, c->work, c->tok_of_pos, c->sched, m.n_shared);
+    return launch_status("topk_union_kernel");
+  }
+  const dim3 tgrid((T + kRouterWaves - 1) / kRouterWaves);
+  if (regs) {
+    hipLaunchKernelGGL(topk_regs_kernel, tgrid, dim3(kRouterThreads), 0, s, c->logits, T, m.E, m.k, c->topk_idx, c->topk_w,
+                       a_idx, a_w);
+  } else {
+    const size_t lds_topk = (size_t)kRouterWaves * (64 + m.E) * sizeof(float);
+    hipLaunchKernelGGL(topk_kernel, tgrid, dim3(kRouterThreads), lds_topk, s, c->logits, T, m.E, m.k, c->topk_idx, c->topk_w,
+                       a_idx, a_w);
+  }
+  int rc = launch_status("topk_kernel");
+  if (rc) return rc;
   hipLaunchKernelGGL(union_worklist_kernel, dim3(1), dim3(kRouterThreads), lds, s, c->topk_idx, T, m.k, m.E, use_masks,
                      c->union_ids, c->union_count, c->hist, c->offsets, c->perm, c->inv, c->status, c->work, c->tok_of_pos,
                      c->sched, m.n_shared);
