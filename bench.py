@@ -45,6 +45,8 @@ def parse():
     ap.add_argument("--tune", action="append", default=[], help="key=value launch-shape knob (evict_tune)")
     ap.add_argument("--sweep", action="store_true",
                     help="not the default line: one JSON line per (N, sigma) point, N in 1..128, sigma in {0.2, 0.5, 1.0}")
+    ap.add_argument("--launch", default="eager", choices=["graph", "eager"],
+                    help="timed steps call the entry points (default), or replay one captured HIP graph per weight copy")
     ap.add_argument("--probe-copy", type=int, default=0, metavar="MiB",
                     help="not the default line: run the plain copy and read kernels on MiB bytes (counter "
                          "calibration under rocprofv3 --pmc, and the streaming-read ceiling) and exit")
@@ -202,15 +204,37 @@ def main():
     res = dc.results()
     U = int(res["union_count"])
 
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    def timed(fn):
+        for i in range(args.warmup):
+            fn(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            fn(i)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / args.steps
+
+    other_ms = None
+    if args.launch == "graph":
+        # one graph per weight copy: the same three calls, recorded once on a side stream
+        side = torch.cuda.Stream()
+        graphs = []
+        with torch.cuda.stream(side):
+            for i in range(len(weight_sets)):
+                ev.evict_graph_begin(layer.ctx)
+                step(i)
+                graphs.append(ev.evict_graph_end(layer.ctx))
+
+            def replay(i):
+                ev.evict_graph_launch(graphs[i % len(graphs)])
+
+            ms_per_step = timed(replay)
+        torch.cuda.synchronize()
+        other_ms = timed(step)  # the same steps as direct calls, for comparison
+        for gr in graphs:
+            ev.evict_graph_destroy(gr)
+    else:
+        ms_per_step = timed(step)
 
     # per-stage durations from HIP events recorded by the library on the launch stream
     ev.evict_stage_timing(layer.ctx, True)
@@ -261,6 +285,8 @@ def main():
         "config": {"workload": f"{'qwen3-30b-a3b' if args.model == 'qwen3' else 'deepseek-v2-lite'}-shaped MoE layer, N={N} tree nodes, ctx={L}, 1 sequence, sigma={args.sigma}",
                    "d_model": cfg.d, "heads": f"{cfg.Hq}q/{cfg.Hkv}kv x {cfg.D}", "experts": f"{cfg.E} top-{cfg.k}",
                    "d_ff": cfg.F, "union_experts": U, "weight_copies": len(weight_sets)},
+        "launch": args.launch,
+        "eager_us": None if other_ms is None else round(other_ms * 1e3, 2),
         "tokens_per_s": round(N / (ms_per_step * 1e-3), 1),
         "step_roofline": {"north_star_bytes": north_star_bytes, "all_required_bytes": all_bytes,
                           "hbm_frac_north_star": round(north_star_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),

@@ -225,6 +225,25 @@ int evict_device_status(evict_ctx* ctx, int32_t* status_host, void* stream);
  * Returns EVICT_E_INVALID for an unknown key or a value out of range. */
 int evict_tune(evict_ctx* ctx, const char* key, int value);
 
+/* HIP-graph capture of a sequence of calls, for the launch-bound regime (small trees) and for
+ * one pre-built graph per verification length as in Sec. 3.3: evict_graph_begin puts `stream`
+ * (not the null stream) into capture mode; every entry point called on that stream until
+ * evict_graph_end is recorded instead of run (all of them only enqueue kernels and
+ * device-to-device copies; evict_device_status, evict_profile_cost and evict_stage_times
+ * synchronise and must stay outside, and stage timing must be off). evict_graph_end
+ * instantiates the recorded work as *out, which evict_graph_launch replays on any stream of
+ * the same device. The graph holds the pointer and size arguments of the recorded calls:
+ * the caller keeps those buffers alive and refreshes their contents in place between
+ * launches. Launches of graphs recorded from one context share its scratch, so they must not
+ * overlap each other or eager calls on that context. The context must outlive its graphs.
+ * Errors: EVICT_E_INVALID (null stream, capture already open / not open, timing on),
+ * EVICT_E_HIP (the capture was invalidated or could not be instantiated; *out is NULL). */
+typedef struct evict_graph evict_graph;
+int evict_graph_begin(evict_ctx* ctx, void* stream);
+int evict_graph_end(evict_ctx* ctx, void* stream, evict_graph** out);
+int evict_graph_launch(evict_graph* graph, void* stream);
+int evict_graph_destroy(evict_graph* graph);
+
 /* Measurement helpers: a plain streaming read (every byte of src read once with 16-byte
  * loads, a checksum written to sink [dev] uint32[4]) and a plain copy, used to measure the
  * achievable HBM read bandwidth of the device and to calibrate hardware byte counters against

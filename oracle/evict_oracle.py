@@ -17,7 +17,9 @@ numpy in float64 on the (already storage-rounded) inputs:
     (Sec. 3.2.1), and k* = argmax_k Ehat[A(T_k)] / C(k) (Eq. 10) evaluated as
     cumulative sums, element-wise division and argmax (Sec. 3.2.3);
   * greedy (temperature 0) acceptance, the deterministic case of the sequential sibling
-    rule of Sec. 2.1;
+    rule of Sec. 2.1, and the rule itself under sampling (Eq. 3: accept a child with its
+    current probability, on rejection remove its mass and renormalise, after the last
+    sibling draw from the residual);
   * the exact expected accepted length (Eq. 6) and the expected number of distinct experts
     (App. A, Eq. 11) used as closed forms by the tests.
 
@@ -309,6 +311,58 @@ def accept_path(parent, draft_tok, target_next):
         cur = nxt
         path.append(cur)
     return np.asarray(path, dtype=np.int32), int(target_next[cur])
+
+
+# --------------------------------------------------------------------------------------
+# acceptance under sampling: the sequential sibling rule (Sec. 2.1, Eq. 3)
+# --------------------------------------------------------------------------------------
+def softmax_temperature(logits, temperature):
+    """Target distribution of every node: softmax(logits / temperature), float64."""
+    z = np.asarray(logits, F64) / F64(temperature)
+    z = z - z.max(axis=-1, keepdims=True)
+    e = np.exp(z)
+    return e / e.sum(axis=-1, keepdims=True)
+
+
+def accept_path_sampled(parent, draft_tok, P, u_node, u_bonus, with_trace=False):
+    """Tree verification under sampling (Sec. 2.1, Eq. 3).
+
+    P[u] is the target distribution over the vocabulary after node u; u_node[c] in [0, 1) is
+    the random number spent when child c is tried, u_bonus the one spent on the final draw.
+    At the surviving node u the children are tried in ascending index: c is accepted with
+    the current probability of its token; on rejection that token's mass is set to zero and
+    the rest is divided by (1 - that mass) (Eq. 3), then the next sibling is tried. When a
+    child is accepted the walk moves to it with that child's own (fresh) distribution. When no
+    child is left, one token is drawn from the current distribution by inverting its
+    cumulative sum at u_bonus (smallest token whose cumulative mass exceeds u_bonus).
+    Returns (path node ids, bonus token[, trace of (child, probability used, accepted)])."""
+    n = len(parent)
+    cur = 0
+    path = [0]
+    trace = []
+    while True:
+        p = np.array(P[cur], dtype=F64)
+        nxt = None
+        for c in range(cur + 1, n):
+            if parent[c] != cur:
+                continue
+            pc = p[draft_tok[c]]
+            ok = bool(u_node[c] < pc)
+            trace.append((c, float(pc), ok))
+            if ok:
+                nxt = c
+                break
+            p[draft_tok[c]] = 0.0
+            p = p / (1.0 - pc)
+        if nxt is None:
+            cdf = np.cumsum(p)
+            # (the last entry of the cumulative sum may fall short of 1 by rounding)
+            tok = int(min(np.searchsorted(cdf, F64(u_bonus) * cdf[-1], side="right"), len(p) - 1))
+            if with_trace:
+                return np.asarray(path, dtype=np.int32), tok, trace, cdf / cdf[-1]
+            return np.asarray(path, dtype=np.int32), tok
+        cur = nxt
+        path.append(cur)
 
 
 # --------------------------------------------------------------------------------------

@@ -16,7 +16,8 @@ __all__ = [
     "evict_pack_qkv", "evict_pack_experts", "evict_verify_layer", "evict_expert_union", "evict_accept_path",
     "evict_select_prefix", "evict_gather_rows", "evict_validate_trees_host", "evict_device_status",
     "evict_stage_timing", "evict_stage_times", "evict_probe_read", "evict_probe_copy", "evict_tune", "evict_verify_stack", "evict_lm_head_argmax",
-    "evict_profile_cost", "STAGES", "EXPORTS",
+    "evict_profile_cost", "evict_graph_begin", "evict_graph_end", "evict_graph_launch", "evict_graph_destroy",
+    "STAGES", "EXPORTS",
 ]
 
 EVICT_F32, EVICT_BF16 = 0, 1
@@ -28,7 +29,7 @@ EXPORTS = [
     "evict_pack_qkv", "evict_pack_experts", "evict_verify_layer", "evict_expert_union", "evict_accept_path",
     "evict_select_prefix", "evict_gather_rows", "evict_validate_trees_host", "evict_device_status",
     "evict_stage_timing", "evict_stage_times", "evict_probe_read", "evict_probe_copy", "evict_tune", "evict_verify_stack", "evict_lm_head_argmax",
-    "evict_profile_cost",
+    "evict_profile_cost", "evict_graph_begin", "evict_graph_end", "evict_graph_launch", "evict_graph_destroy",
 ]
 STAGES = ["prep", "qkv", "attention", "oproj", "router", "union", "gateup", "down", "shared", "combine"]
 
@@ -100,6 +101,10 @@ def load():
     lib.evict_probe_read.argtypes = [vp, sz, vp, vp]
     lib.evict_probe_copy.argtypes = [vp, vp, sz, vp]
     lib.evict_stage_times.argtypes = [vp, C.POINTER(C.c_float)]
+    lib.evict_graph_begin.argtypes = [vp, vp]
+    lib.evict_graph_end.argtypes = [vp, vp, C.POINTER(vp)]
+    lib.evict_graph_launch.argtypes = [vp, vp]
+    lib.evict_graph_destroy.argtypes = [vp]
     _LIB = lib
     return lib
 
@@ -212,6 +217,26 @@ def evict_probe_read(src, nbytes: int, sink) -> None:
 
 def evict_probe_copy(src, dst, nbytes: int) -> None:
     _check(load().evict_probe_copy(_p(src), _p(dst), nbytes, _stream()))
+
+
+def evict_graph_begin(ctx) -> None:
+    """Start recording the calls made on torch's current (non-default) stream."""
+    _check(load().evict_graph_begin(ctx, _stream()))
+
+
+def evict_graph_end(ctx):
+    """Stop recording; returns the graph handle for evict_graph_launch."""
+    g = C.c_void_p()
+    _check(load().evict_graph_end(ctx, _stream(), C.byref(g)))
+    return g
+
+
+def evict_graph_launch(graph) -> None:
+    _check(load().evict_graph_launch(graph, _stream()))
+
+
+def evict_graph_destroy(graph) -> None:
+    _check(load().evict_graph_destroy(graph))
 
 
 def evict_tune(ctx, key: str, value: int) -> None:

@@ -124,6 +124,7 @@ int evict_create(evict_ctx** out, const evict_model_desc* m, int max_tokens, int
   for (int cu : {4, 2}) if ((m->d / 16) % cu == 0) { c.moe_chunk_down = cu; break; }
   c.attn_row_blocks = 0;
   c.timed_once = 0;
+  c.capturing = 0;
   c.prof_ev[0] = c.prof_ev[1] = nullptr;
   for (int i = 0; !rc && i < 2; ++i) {
     he = hipEventCreate(&c.prof_ev[i]);
@@ -490,6 +491,63 @@ int evict_stage_times(evict_ctx* ctx, float* ms_host) {
   EVICT_REQUIRE(ctx->timed_once, EVICT_E_INVALID, "evict_stage_times: no call has been timed (enable evict_stage_timing first)");
   EVICT_HIP_CHECK(hipEventSynchronize(ctx->ev[EVICT_N_STAGES]));
   for (int i = 0; i < EVICT_N_STAGES; ++i) EVICT_HIP_CHECK(hipEventElapsedTime(&ms_host[i], ctx->ev[i], ctx->ev[i + 1]));
+  return EVICT_OK;
+}
+
+// ---- HIP-graph capture of a sequence of calls (one graph per verification length) ----
+struct evict_graph {
+  hipGraph_t graph;
+  hipGraphExec_t exec;
+  int device;
+};
+
+int evict_graph_begin(evict_ctx* ctx, void* stream) {
+  EVICT_REQUIRE(ctx, EVICT_E_INVALID, "evict_graph_begin: null context");
+  EVICT_REQUIRE(stream != nullptr, EVICT_E_INVALID, "evict_graph_begin: the default (null) stream cannot be captured");
+  EVICT_REQUIRE(!ctx->timing, EVICT_E_INVALID, "evict_graph_begin: switch evict_stage_timing off before capturing");
+  EVICT_REQUIRE(!ctx->capturing, EVICT_E_INVALID, "evict_graph_begin: a capture is already open on this context");
+  EVICT_HIP_CHECK(hipStreamBeginCapture((hipStream_t)stream, hipStreamCaptureModeThreadLocal));
+  ctx->capturing = 1;
+  return EVICT_OK;
+}
+
+int evict_graph_end(evict_ctx* ctx, void* stream, evict_graph** out) {
+  EVICT_REQUIRE(ctx && out, EVICT_E_INVALID, "evict_graph_end: null argument");
+  EVICT_REQUIRE(ctx->capturing, EVICT_E_INVALID, "evict_graph_end: no capture is open on this context");
+  *out = nullptr;
+  ctx->capturing = 0;
+  hipGraph_t g = nullptr;
+  EVICT_HIP_CHECK(hipStreamEndCapture((hipStream_t)stream, &g));
+  EVICT_REQUIRE(g != nullptr, EVICT_E_HIP, "evict_graph_end: the capture was invalidated (a call inside it failed or synchronised)");
+  hipGraphExec_t ex = nullptr;
+  hipError_t e = hipGraphInstantiate(&ex, g, nullptr, nullptr, 0);
+  if (e != hipSuccess) {
+    (void)hipGraphDestroy(g);
+    set_error("hipGraphInstantiate: %s", hipGetErrorString(e));
+    return EVICT_E_HIP;
+  }
+  evict_graph* h = new (std::nothrow) evict_graph{g, ex, ctx->device};
+  if (!h) {
+    (void)hipGraphExecDestroy(ex);
+    (void)hipGraphDestroy(g);
+    set_error("evict_graph_end: out of host memory");
+    return EVICT_E_HIP;
+  }
+  *out = h;
+  return EVICT_OK;
+}
+
+int evict_graph_launch(evict_graph* g, void* stream) {
+  EVICT_REQUIRE(g, EVICT_E_INVALID, "evict_graph_launch: null graph");
+  EVICT_HIP_CHECK(hipGraphLaunch(g->exec, (hipStream_t)stream));
+  return EVICT_OK;
+}
+
+int evict_graph_destroy(evict_graph* g) {
+  if (!g) return EVICT_OK;
+  (void)hipGraphExecDestroy(g->exec);
+  (void)hipGraphDestroy(g->graph);
+  delete g;
   return EVICT_OK;
 }
 

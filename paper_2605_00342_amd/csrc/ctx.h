@@ -12,6 +12,7 @@ struct evict_ctx {
   int moe_grid, moe_prefetch, moe_chunk_gateup, moe_chunk_down, moe_down_kernel, attn_row_blocks;  // launch-shape knobs (evict_tune)
   int timing;            // record stage events in evict_verify_layer
   int timed_once;        // a timed call has been recorded
+  int capturing;         // a stream capture opened by evict_graph_begin is in progress
   hipEvent_t ev[EVICT_N_STAGES + 1];
   // ---- device scratch (all sized for max_tokens) ----
   int32_t* status;       // [1] sticky status bits

@@ -1,0 +1,149 @@
+"""HIP-graph capture of the verification step (one pre-built graph per verification length,
+Sec. 3.3): every replay must reproduce the directly launched calls bit for bit, also after the
+inputs were refreshed in place and with the program's own eager work between replays; the
+directly launched calls are themselves checked against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+import synth
+from oracle import evict_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+ev = pytest.importorskip("paper_2605_00342_amd")
+from paper_2605_00342_amd import harness  # noqa: E402
+
+DEV = "cuda:0"
+
+
+def rel_l2(a, b):
+    return float(np.linalg.norm(np.asarray(a, np.float64) - b) / max(np.linalg.norm(b), 1e-30))
+
+
+class StepBuffers:
+    """select_prefix + verify_layer + accept_path of one tree, with every output in its own buffer."""
+
+    def __init__(self, case, dc, layer, vocab=1000):
+        i32, f32 = torch.int32, torch.float32
+        N = dc.T
+        self.case, self.dc, self.layer, self.N = case, dc, layer, N
+        cfg = case["cfg"]
+        self.q = torch.from_numpy(case["q"]).to(DEV)
+        self.cost = torch.from_numpy(synth.cost_linear_in_union(N, cfg.E, cfg.k)).to(DEV)
+        self.k_star = torch.zeros(1, dtype=i32, device=DEV)
+        self.keep = torch.zeros(N, dtype=i32, device=DEV)
+        self.new_parent = torch.zeros(N, dtype=i32, device=DEV)
+        self.new_off = torch.zeros(2, dtype=i32, device=DEV)
+        self.est = torch.zeros(1, dtype=f32, device=DEV)
+        g = synth.philox(77, 900)
+        self.target_next_np = g.integers(0, vocab, N).astype(np.int32)
+        self.draft_tok_np = synth.plant_draft_tokens(case["parent"], self.target_next_np, vocab, g)
+        self.tn, self.dt = harness.dev_i32(self.target_next_np), harness.dev_i32(self.draft_tok_np)
+        self.path = torch.zeros(1, N, dtype=i32, device=DEV)
+        self.path_len = torch.zeros(1, dtype=i32, device=DEV)
+        self.bonus = torch.zeros(1, dtype=i32, device=DEV)
+
+    def step(self):
+        dc, N = self.dc, self.N
+        ev.evict_select_prefix(None, dc.tree_off, dc.parent, self.q, 1, N, self.cost, N, self.k_star, self.keep,
+                               self.new_parent, self.new_off, self.est)
+        dc.run(self.layer)
+        ev.evict_accept_path(None, dc.tree_off, dc.parent, self.dt, self.tn, 1, self.path, N, self.path_len, self.bonus)
+
+    def outputs(self):
+        dc = self.dc
+        return [t.clone() for t in (dc.out, dc.k_new, dc.v_new, self.k_star, self.keep, self.new_parent, self.est,
+                                    self.path, self.path_len, self.bonus, dc.a["topk_idx"], dc.a["union_ids"])]
+
+    def clear(self):
+        dc = self.dc
+        for t in (dc.out, dc.k_new, dc.v_new, self.k_star, self.keep, self.new_parent, self.est, self.path,
+                  self.path_len, self.bonus, dc.a["topk_idx"], dc.a["union_ids"]):
+            t.zero_()
+
+
+@pytest.mark.parametrize("cfg_name,n,L", [("tiny", 8, 64), ("mini_bf16", 40, 300)])
+def test_graph_replays_match_direct_calls(cfg_name, n, L):
+    case = synth.make_case(cfg_name, n=n, L=L, seed=31)
+    cfg = case["cfg"]
+    layer = harness.DeviceLayer(cfg, case["W"], max_tokens=n, max_batch=1, max_ctx=L)
+    dc = harness.DeviceCase(case, with_aux=True)
+    sb = StepBuffers(case, dc, layer)
+    side = torch.cuda.Stream()
+    graph = None
+    try:
+        with torch.cuda.stream(side):
+            # direct calls first: reference outputs, checked against the oracle
+            sb.step()
+            side.synchronize()
+            ref = sb.outputs()
+            want = orc.verify_layer(cfg, case["W"], case["tree_off"], case["parent"], case["x"], case["K"], case["V"],
+                                    case["ctx_len"])
+            tol = 1e-4 if cfg.dtype == "f32" else 2e-2
+            assert rel_l2(harness.to_host(dc.out), want["out"]) < tol
+            path, bonus = orc.accept_path(case["parent"], sb.draft_tok_np, sb.target_next_np)
+            assert harness.to_host(sb.path_len)[0] == len(path) and harness.to_host(sb.bonus)[0] == bonus
+
+            ev.evict_graph_begin(layer.ctx)
+            sb.step()
+            graph = ev.evict_graph_end(layer.ctx)
+
+            x0 = dc.x.clone()
+            q0 = sb.q.clone()
+            for rep in range(4):
+                if rep == 2:
+                    # inputs refreshed in place: other hidden states and draft probabilities
+                    g = torch.Generator(device="cpu").manual_seed(5)
+                    dc.x.copy_((x0.float().cpu() + 0.25 * torch.randn(x0.shape, generator=g)).to(x0.dtype))
+                    sb.q.copy_(torch.clamp(q0 * 0.5 + 0.2, 0.05, 1.0))
+                    sb.clear()
+                    sb.step()  # eager work of the program's own between replays
+                    side.synchronize()
+                    ref = sb.outputs()
+                sb.clear()
+                ev.evict_graph_launch(graph)
+                side.synchronize()
+                got = sb.outputs()
+                for a, b in zip(got, ref):
+                    assert torch.equal(a, b), f"replay {rep} differs from the direct calls"
+    finally:
+        if graph is not None:
+            ev.evict_graph_destroy(graph)
+        layer.close()
+
+
+def test_graph_error_paths():
+    case = synth.make_case("tiny", n=8, L=64, seed=3)
+    layer = harness.DeviceLayer(case["cfg"], case["W"], max_tokens=8, max_batch=1, max_ctx=64)
+    try:
+        with pytest.raises(ev.EvictError):  # the null stream cannot be captured
+            ev.evict_graph_begin(layer.ctx)
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            with pytest.raises(ev.EvictError):  # no capture open
+                ev.evict_graph_end(layer.ctx)
+            ev.evict_stage_timing(layer.ctx, True)
+            with pytest.raises(ev.EvictError):  # stage timing records events
+                ev.evict_graph_begin(layer.ctx)
+            ev.evict_stage_timing(layer.ctx, False)
+            # (buffers are allocated before the capture opens: an allocation would invalidate it)
+            keep = torch.arange(8, dtype=torch.int32, device=DEV)
+            off = torch.tensor([0, 8], dtype=torch.int32, device=DEV)
+            src = torch.ones(8, 4, device=DEV)
+            dst = torch.zeros(8, 4, device=DEV)
+            side.synchronize()
+            ev.evict_graph_begin(layer.ctx)
+            with pytest.raises(ev.EvictError):  # already open
+                ev.evict_graph_begin(layer.ctx)
+            ev.evict_gather_rows(src, dst, 16, off, off, keep, 1, 8)
+            g = ev.evict_graph_end(layer.ctx)
+            side.synchronize()
+            assert float(dst.sum()) == 0.0  # recorded, not run
+            ev.evict_graph_launch(g)
+            side.synchronize()
+            assert float(dst.sum()) == 32.0
+            side.synchronize()
+            ev.evict_graph_destroy(g)
+    finally:
+        layer.close()
