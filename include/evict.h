@@ -148,6 +148,12 @@ int evict_verify_stack(evict_ctx* ctx, const evict_layer_weights* layers, int n_
 int evict_lm_head_argmax(evict_ctx* ctx, const void* x, const void* g_final, const void* wlm_packed, int T,
                          int32_t* next, float* best_logit, void* x_norm_out, void* stream);
 
+/* LM head with the full score rows kept (what acceptance under sampling needs): as
+ * evict_lm_head_argmax up to the scores, written to logits [dev] float32 [T][vocab] row-major
+ * (vocab from the context's model description, a multiple of 16; 16-byte aligned). */
+int evict_lm_head_logits(evict_ctx* ctx, const void* x, const void* g_final, const void* wlm_packed, int T,
+                         float* logits, void* x_norm_out, void* stream);
+
 /* Offline cost profiling (Sec. 3.2.3): for every verification length k = 1..Kmax, the mean
  * latency in milliseconds of evict_verify_stack on the first k nodes of one tree (B = 1; any
  * prefix of a topologically numbered tree is a tree), `reps` timed runs after one warm-up,
@@ -178,6 +184,24 @@ int evict_expert_union(evict_ctx* ctx, const int32_t* topk_idx, int T, int k, in
 int evict_accept_path(evict_ctx* ctx, const int32_t* tree_off, const int32_t* parent,
                       const int32_t* draft_tok, const int32_t* target_next, int B,
                       int32_t* path, int path_stride, int32_t* path_len, int32_t* bonus_tok, void* stream);
+
+/* Acceptance under sampling: the sequential sibling rule of Sec. 2.1 (Eq. 3). The target
+ * distribution after node u is softmax(logits[u] / temperature) over `vocab` tokens
+ * (logits [dev] float32 [T][vocab], e.g. from evict_lm_head_logits; temperature > 0). At the
+ * surviving node the children are tried in ascending index: child c is accepted when
+ * u_node[c] < its token's current probability; on rejection that mass is removed and the rest
+ * renormalised (Eq. 3); when no child is left, bonus_tok is drawn from the remaining
+ * distribution by inverting its cumulative sum (ascending token id) at u_bonus[b]. The random
+ * numbers are inputs: u_node [dev] float32 [T] (one per node, the root's is unused), u_bonus
+ * [dev] float32 [B], all in [0, 1). Outputs as evict_accept_path. Arithmetic is fp32; a
+ * decision whose random number lies within rounding of its threshold may differ from a
+ * higher-precision evaluation. Invalid token ids (outside [0, vocab)) are never accepted and
+ * set the context's status word. Needs a context (scratch for the per-node softmax
+ * statistics): B <= max_batch, T <= max_tokens. */
+int evict_accept_path_sampled(evict_ctx* ctx, const int32_t* tree_off, const int32_t* parent,
+                              const int32_t* draft_tok, const float* logits, int vocab, float temperature,
+                              const float* u_node, const float* u_bonus, int B, int T, int32_t* path,
+                              int path_stride, int32_t* path_len, int32_t* bonus_tok, void* stream);
 
 /* EVICT prefix selection, entirely on the device (Sec. 3.1-3.2): node score = product of
  * draft probabilities along the root path (Eq. 7, root counted as 1), nodes ranked by score

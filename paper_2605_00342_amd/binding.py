@@ -17,7 +17,7 @@ __all__ = [
     "evict_select_prefix", "evict_gather_rows", "evict_validate_trees_host", "evict_device_status",
     "evict_stage_timing", "evict_stage_times", "evict_probe_read", "evict_probe_copy", "evict_tune", "evict_verify_stack", "evict_lm_head_argmax",
     "evict_profile_cost", "evict_graph_begin", "evict_graph_end", "evict_graph_launch", "evict_graph_destroy",
-    "STAGES", "EXPORTS",
+    "evict_lm_head_logits", "evict_accept_path_sampled", "STAGES", "EXPORTS",
 ]
 
 EVICT_F32, EVICT_BF16 = 0, 1
@@ -30,6 +30,7 @@ EXPORTS = [
     "evict_select_prefix", "evict_gather_rows", "evict_validate_trees_host", "evict_device_status",
     "evict_stage_timing", "evict_stage_times", "evict_probe_read", "evict_probe_copy", "evict_tune", "evict_verify_stack", "evict_lm_head_argmax",
     "evict_profile_cost", "evict_graph_begin", "evict_graph_end", "evict_graph_launch", "evict_graph_destroy",
+    "evict_lm_head_logits", "evict_accept_path_sampled",
 ]
 STAGES = ["prep", "qkv", "attention", "oproj", "router", "union", "gateup", "down", "shared", "combine"]
 
@@ -101,6 +102,8 @@ def load():
     lib.evict_probe_read.argtypes = [vp, sz, vp, vp]
     lib.evict_probe_copy.argtypes = [vp, vp, sz, vp]
     lib.evict_stage_times.argtypes = [vp, C.POINTER(C.c_float)]
+    lib.evict_lm_head_logits.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp]
+    lib.evict_accept_path_sampled.argtypes = [vp, vp, vp, vp, vp, i32, C.c_float, vp, vp, i32, i32, vp, i32, vp, vp, vp]
     lib.evict_graph_begin.argtypes = [vp, vp]
     lib.evict_graph_end.argtypes = [vp, vp, C.POINTER(vp)]
     lib.evict_graph_launch.argtypes = [vp, vp]
@@ -217,6 +220,17 @@ def evict_probe_read(src, nbytes: int, sink) -> None:
 
 def evict_probe_copy(src, dst, nbytes: int) -> None:
     _check(load().evict_probe_copy(_p(src), _p(dst), nbytes, _stream()))
+
+
+def evict_lm_head_logits(ctx, x, g_final, wlm_packed, T, logits, x_norm_out=None) -> None:
+    _check(load().evict_lm_head_logits(ctx, _p(x), _p(g_final), _p(wlm_packed), T, _p(logits), _p(x_norm_out), _stream()))
+
+
+def evict_accept_path_sampled(ctx, tree_off, parent, draft_tok, logits, vocab, temperature, u_node, u_bonus, B, T,
+                              path, path_stride, path_len, bonus_tok) -> None:
+    _check(load().evict_accept_path_sampled(ctx, _p(tree_off), _p(parent), _p(draft_tok), _p(logits), vocab,
+                                            float(temperature), _p(u_node), _p(u_bonus), B, T, _p(path), path_stride,
+                                            _p(path_len), _p(bonus_tok), _stream()))
 
 
 def evict_graph_begin(ctx) -> None:

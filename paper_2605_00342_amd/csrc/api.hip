@@ -108,6 +108,7 @@ int evict_create(evict_ctx** out, const evict_model_desc* m, int max_tokens, int
     A(&c.lm_val, (size_t)(m->vocab / 16) * T * 4);
     A(&c.lm_idx, (size_t)(m->vocab / 16) * T * 4);
   }
+  A(&c.samp_stats, T * 2 * 4);
   A(&c.stack_buf[0], T * d * eb);
   A(&c.stack_buf[1], T * d * eb);
   if (!rc) {
@@ -423,6 +424,32 @@ int evict_lm_head_argmax(evict_ctx* ctx, const void* x, const void* g_final, con
   rc = launch_gemm(m.dtype, EPI_ARGMAX, a, 1, ((a.n_strips + 7) / 8) * 8 * a.dense_tiles, s);
   if (rc) return rc;
   return launch_argmax_reduce(ctx->lm_val, ctx->lm_idx, a.n_strips, T, T, next, best_logit, s);
+}
+
+int evict_lm_head_logits(evict_ctx* ctx, const void* x, const void* g_final, const void* wlm_packed, int T, float* logits,
+                         void* x_norm_out, void* stream) {
+  EVICT_REQUIRE(ctx && x && g_final && wlm_packed && logits, EVICT_E_INVALID, "evict_lm_head_logits: null pointer argument");
+  const evict_model_desc& m = ctx->m;
+  EVICT_REQUIRE(m.vocab > 0, EVICT_E_INVALID, "evict_lm_head_logits: the context was created without a vocabulary size");
+  EVICT_REQUIRE(T >= 1 && T <= ctx->max_tokens, EVICT_E_INVALID, "evict_lm_head_logits: T=%d outside [1,%d]", T, ctx->max_tokens);
+  EVICT_REQUIRE(aligned16(x) && aligned16(wlm_packed) && aligned16(logits), EVICT_E_INVALID,
+                "evict_lm_head_logits: pointers must be 16-byte aligned");
+  hipStream_t s = (hipStream_t)stream;
+  const int eb = elem_bytes(m.dtype);
+  int rc = launch_prep(ctx, nullptr, nullptr, 1, T, nullptr, 0, x, g_final, 1, s);  // final RMSNorm only
+  if (rc) return rc;
+  if (x_norm_out) EVICT_HIP_CHECK(hipMemcpyAsync(x_norm_out, ctx->x_norm, (size_t)T * m.d * eb, hipMemcpyDeviceToDevice, s));
+  GemmArgs a = {};
+  a.W = (const u32x4*)wlm_packed;
+  a.n_strips = m.vocab / 16;
+  a.nkb = m.d * eb / 64;
+  a.X = ctx->x_norm;
+  a.ldx_bytes = (long long)m.d * eb;
+  a.T = T;
+  a.out0 = logits;
+  a.ldo = m.vocab;
+  a.dense_tiles = (T + 15) / 16;
+  return launch_gemm(m.dtype, EPI_F32, a, 1, ((a.n_strips + 7) / 8) * 8 * a.dense_tiles, s);
 }
 
 int evict_profile_cost(evict_ctx* ctx, const evict_layer_weights* layers, int n_layers, const int32_t* tree_off,

@@ -43,6 +43,7 @@ struct evict_ctx {
   float* y;              // [T*k + n_shared*T][d]
   float* lm_val;         // [vocab/16][T] best logit per strip and token
   int32_t* lm_idx;       // [vocab/16][T]
+  float* samp_stats;     // [T][2] per node: max logit, sum of exp((logit - max) / temperature)
   void* stack_buf[2];    // [T][d] ping-pong hidden states of evict_verify_stack
   hipEvent_t prof_ev[2]; // evict_profile_cost
 };

@@ -258,6 +258,194 @@ __global__ __launch_bounds__(64) void accept_path_kernel(
   if (lane == 0) { path_len[b] = len; bonus[b] = s_next[cur]; }
 }
 
+// ------------------------------------------------------------------------------------
+// Acceptance under sampling: the sequential sibling rule (Sec. 2.1, Eq. 3).
+// ------------------------------------------------------------------------------------
+constexpr int kSampThreads = 1024;
+constexpr int kSampWaves = kSampThreads / 64;
+
+// Per node: maximum of the logits and the sum of exp((logit - max) / temperature) over the
+// vocabulary -- the two numbers that turn any logit of the row into a probability.
+__global__ __launch_bounds__(kSampThreads) void softmax_stats_kernel(const float* __restrict__ logits, int V, float inv_temp,
+                                                                     float* __restrict__ stats) {
+  __shared__ float s_red[kSampWaves];
+  const float* row = logits + (size_t)blockIdx.x * V;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  float m = -INFINITY;
+  for (int i = tid; i < V; i += kSampThreads) m = fmaxf(m, row[i]);
+  m = wave_max(m);
+  if (lane == 0) s_red[w] = m;
+  __syncthreads();
+  m = s_red[0];
+  for (int i = 1; i < kSampWaves; ++i) m = fmaxf(m, s_red[i]);
+  __syncthreads();
+  float z = 0.0f;
+  for (int i = tid; i < V; i += kSampThreads) z += __expf((row[i] - m) * inv_temp);
+  z = wave_sum(z);
+  if (lane == 0) s_red[w] = z;
+  __syncthreads();
+  if (tid == 0) {
+    float t = 0.0f;
+    for (int i = 0; i < kSampWaves; ++i) t += s_red[i];
+    stats[2 * blockIdx.x] = m;
+    stats[2 * blockIdx.x + 1] = t;
+  }
+}
+
+__device__ __forceinline__ float wave_incl_scan_f32(float v, int lane) {
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const float t = __shfl_up(v, o);
+    if (lane >= o) v += t;
+  }
+  return v;
+}
+
+// One workgroup per tree. Step 1, all threads: the target probability of every node's token
+// under its parent's distribution. Step 2, one thread: the walk of Eq. 3 on values in LDS --
+// child c of the surviving node is accepted when u_node[c] < p(c) / (1 - mass rejected so
+// far at this node), which is what the repeated renormalisation amounts to; a token already
+// rejected at this node has no mass left. Step 3, all threads: the final draw from the
+// distribution at the last node with the rejected tokens removed, by inverting the cumulative
+// sum at u_bonus: 16 contiguous vocabulary segments are summed (one per wavefront), the
+// segment holding the target mass is cut into 64 contiguous pieces, the piece is walked.
+__global__ __launch_bounds__(kSampThreads) void accept_sampled_kernel(
+    const int32_t* __restrict__ tree_off, const int32_t* __restrict__ parent, const int32_t* __restrict__ tok,
+    const float* __restrict__ logits, int V, float inv_temp, const float* __restrict__ stats,
+    const float* __restrict__ u_node, const float* __restrict__ u_bonus, int32_t* __restrict__ path, int path_stride,
+    int32_t* __restrict__ path_len, int32_t* __restrict__ bonus, int32_t* __restrict__ status) {
+  __shared__ int s_par[kMaxSel];
+  __shared__ int s_tok[kMaxSel];
+  __shared__ float s_p[kMaxSel];
+  __shared__ float s_u[kMaxSel];
+  __shared__ int s_rej[kMaxSel];
+  __shared__ int s_cur, s_nrej, s_seg, s_found;
+  __shared__ float s_segsum[kSampWaves];
+  __shared__ float s_rem;
+  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int lo = tree_off[b];
+  int n = tree_off[b + 1] - lo;
+  n = n < 1 ? 1 : (n > kMaxSel ? kMaxSel : n);
+  bool bad = false;
+  for (int i = tid; i < n; i += kSampThreads) {
+    int pa = parent[lo + i];
+    int tk = tok[lo + i];
+    if (i > 0 && (pa < 0 || pa >= i)) { bad = true; pa = 0; }
+    float pr = 0.0f;
+    if (i > 0) {
+      if (tk < 0 || tk >= V) { bad = true; tk = -1; }  // an invalid token id is never accepted and removes no mass
+      else {
+        const size_t prow = (size_t)(lo + pa);
+        pr = __expf((logits[prow * V + tk] - stats[2 * prow]) * inv_temp) / stats[2 * prow + 1];
+      }
+    }
+    s_par[i] = i == 0 ? -1 : pa;
+    s_tok[i] = tk;
+    s_p[i] = pr;
+    s_u[i] = u_node[lo + i];
+  }
+  if (bad && status) atomicOr(status, ST_BAD_PARENT);
+  int32_t* my = path + (size_t)b * path_stride;
+  for (int i = tid; i < path_stride; i += kSampThreads) my[i] = i == 0 ? 0 : -1;
+  __syncthreads();
+  if (tid == 0) {
+    int cur = 0, len = 1, nrej = 0;
+    while (true) {
+      float removed = 0.0f;
+      nrej = 0;
+      int nxt = -1;
+      for (int c = cur + 1; c < n; ++c) {
+        if (s_par[c] != cur) continue;
+        const int tk = s_tok[c];
+        float pc = s_p[c];
+        for (int r = 0; r < nrej; ++r)
+          if (s_rej[r] == tk) pc = 0.0f;
+        if (s_u[c] < pc / (1.0f - removed)) { nxt = c; break; }
+        removed += pc;
+        s_rej[nrej++] = tk;
+      }
+      if (nxt < 0) break;
+      cur = nxt;  // strictly increasing: the walk ends
+      if (len < path_stride) my[len] = cur;
+      ++len;
+    }
+    path_len[b] = len;
+    s_cur = cur;
+    s_nrej = nrej;
+    s_found = -1;
+  }
+  __syncthreads();
+  const int cur = s_cur, nrej = s_nrej;
+  const float* row = logits + (size_t)(lo + cur) * V;
+  const float m = stats[2 * (size_t)(lo + cur)];
+  auto mass = [&](int i) {
+    float e = __expf((row[i] - m) * inv_temp);
+    for (int r = 0; r < nrej; ++r)
+      if (s_rej[r] == i) e = 0.0f;
+    return e;
+  };
+  // segment sums: segment w = [w * seg, (w + 1) * seg) with seg a multiple of 64
+  const int seg = (((V + kSampWaves - 1) / kSampWaves) + 63) & ~63;
+  const int sb = w * seg;
+  const int se = sb + seg < V ? sb + seg : V;
+  float acc = 0.0f;
+  for (int i = sb + lane; i < se; i += 64) acc += mass(i);
+  acc = wave_sum(acc);
+  if (lane == 0) s_segsum[w] = acc;
+  __syncthreads();
+  if (tid == 0) {
+    float total = 0.0f;
+    for (int i = 0; i < kSampWaves; ++i) total += s_segsum[i];
+    const float target = u_bonus[b] * total;
+    float before = 0.0f;
+    int pick = -1;
+    bool inside = false;
+    for (int i = 0; i < kSampWaves && !inside; ++i) {
+      if (s_segsum[i] > 0.0f) {
+        pick = i;
+        inside = target < before + s_segsum[i];
+        if (!inside) before += s_segsum[i];
+      }
+    }
+    // (rounding may leave the target past the last sum: the last non-empty segment takes it)
+    if (pick >= 0 && !inside) before -= s_segsum[pick];
+    s_seg = pick < 0 ? 0 : pick;
+    s_rem = target - before;
+  }
+  __syncthreads();
+  if (w == 0) {
+    const int cl = seg >> 6;  // contiguous piece per lane
+    const int pb = s_seg * seg + lane * cl;
+    int pe = pb + cl;
+    pe = pe < V ? pe : V;
+    float psum = 0.0f;
+    for (int i = pb; i < pe; ++i) psum += mass(i);
+    const float incl = wave_incl_scan_f32(psum, lane);
+    const float rem = s_rem;
+    const unsigned long long hit = __ballot(psum > 0.0f && rem < incl);
+    const unsigned long long any = __ballot(psum > 0.0f);
+    int owner = -1;
+    if (hit) owner = __ffsll((long long)hit) - 1;
+    else if (any) owner = 63 - __clzll((long long)any);  // rounding: the last piece with mass takes it
+    if (lane == owner) {
+      const float r2 = rem - (incl - psum);
+      float run = 0.0f;
+      int pick = -1;
+      for (int i = pb; i < pe; ++i) {
+        const float e = mass(i);
+        if (e > 0.0f) {
+          pick = i;
+          run += e;
+          if (r2 < run) break;
+        }
+      }
+      s_found = pick;
+    }
+  }
+  __syncthreads();
+  if (tid == 0) bonus[b] = s_found < 0 ? 0 : s_found;
+}
+
 constexpr int kUnionThreads = 1024;  // >= the largest supported E: one expert per thread in the scan
 
 __global__ __launch_bounds__(kUnionThreads) void expert_union_kernel(
@@ -440,6 +628,28 @@ int evict_gather_rows(const void* src, void* dst, int row_bytes, const int32_t* 
   hipLaunchKernelGGL(gather_rows_kernel, dim3(T), dim3(128), 0, (hipStream_t)stream, (const uint32_t*)src,
                      (uint32_t*)dst, row_bytes / 4, tree_off, new_tree_off, keep, B);
   return launch_status("gather_rows_kernel");
+}
+
+int evict_accept_path_sampled(evict_ctx* ctx, const int32_t* tree_off, const int32_t* parent, const int32_t* draft_tok,
+                              const float* logits, int vocab, float temperature, const float* u_node, const float* u_bonus,
+                              int B, int T, int32_t* path, int path_stride, int32_t* path_len, int32_t* bonus_tok,
+                              void* stream) {
+  EVICT_REQUIRE(ctx && tree_off && parent && draft_tok && logits && u_node && u_bonus && path && path_len && bonus_tok,
+                EVICT_E_INVALID, "evict_accept_path_sampled: null pointer argument");
+  EVICT_REQUIRE(B >= 1 && B <= ctx->max_batch, EVICT_E_INVALID, "evict_accept_path_sampled: B=%d outside [1,%d]", B, ctx->max_batch);
+  EVICT_REQUIRE(T >= 1 && T <= ctx->max_tokens, EVICT_E_INVALID, "evict_accept_path_sampled: T=%d outside [1,%d]", T, ctx->max_tokens);
+  EVICT_REQUIRE(vocab >= 1, EVICT_E_INVALID, "evict_accept_path_sampled: vocab must be >= 1");
+  EVICT_REQUIRE(temperature > 0.0f && temperature == temperature, EVICT_E_INVALID,
+                "evict_accept_path_sampled: temperature must be > 0 (use evict_accept_path for the greedy rule)");
+  EVICT_REQUIRE(path_stride >= 1, EVICT_E_INVALID, "evict_accept_path_sampled: path_stride must be >= 1");
+  const float inv_temp = 1.0f / temperature;
+  hipStream_t s = (hipStream_t)stream;
+  hipLaunchKernelGGL(softmax_stats_kernel, dim3(T), dim3(kSampThreads), 0, s, logits, vocab, inv_temp, ctx->samp_stats);
+  int rc = launch_status("softmax_stats_kernel");
+  if (rc) return rc;
+  hipLaunchKernelGGL(accept_sampled_kernel, dim3(B), dim3(kSampThreads), 0, s, tree_off, parent, draft_tok, logits, vocab,
+                     inv_temp, ctx->samp_stats, u_node, u_bonus, path, path_stride, path_len, bonus_tok, ctx->status);
+  return launch_status("accept_sampled_kernel");
 }
 
 }  // extern "C"
