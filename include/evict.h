@@ -221,6 +221,21 @@ int evict_select_prefix(evict_ctx* ctx, const int32_t* tree_off, const int32_t* 
                         int32_t* k_star, int32_t* keep, int32_t* new_parent, int32_t* new_tree_off,
                         float* est_len, int32_t* order, float* prefix_sum, void* stream);
 
+/* Commit of the accepted path to the KV cache of one layer (what follows acceptance in every
+ * speculative iteration, Sec. 2.1): for sequence b and j < path_len[b], the draft key/value row
+ * of node path[b][j] (k_new / v_new [dev] [T][Hkv][D], storage dtype, as written by
+ * evict_verify_layer: rotated at position ctx_len[b] + depth, and the j-th node of an accepted
+ * path has depth j) becomes row ctx_len[b] + j of every KV head of k_cache / v_cache [dev]
+ * (element strides kv_seq_stride between sequences, kv_head_stride between heads, `capacity`
+ * rows per head). ctx_len_out[b] = ctx_len[b] + path_len[b]; it must not alias ctx_len (all
+ * workgroups read the old length). Rows past the capacity are dropped and the length clamped;
+ * that, a length outside [0, capacity] or a path entry outside its tree set the status word of
+ * ctx (ctx may be NULL: no status). dtype / Hkv / D describe the rows (EVICT_F32 / EVICT_BF16). */
+int evict_kv_commit(evict_ctx* ctx, int dtype, int Hkv, int D, const void* k_new, const void* v_new,
+                    const int32_t* tree_off, const int32_t* path, int path_stride, const int32_t* path_len,
+                    void* k_cache, void* v_cache, int64_t kv_seq_stride, int64_t kv_head_stride,
+                    const int32_t* ctx_len, int capacity, int32_t* ctx_len_out, int B, void* stream);
+
 /* Gather rows of a [T, row_bytes] array by the kept node lists of evict_select_prefix:
  * dst row new_tree_off[b] + r = src row tree_off[b] + keep[new_tree_off[b] + r].
  * row_bytes % 4 == 0. Grid is sized for T rows; rows beyond new_tree_off[B] are untouched. */

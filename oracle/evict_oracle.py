@@ -365,6 +365,17 @@ def accept_path_sampled(parent, draft_tok, P, u_node, u_bonus, with_trace=False)
         path.append(cur)
 
 
+def kv_commit(K, V, k_new, v_new, path):
+    """What follows acceptance in one sequence: the keys / values of the accepted path's nodes
+    (rows of k_new / v_new [n, Hkv, D], already rotated at context_length + depth) are appended
+    to the cache [Hkv, L, D] in path order, so the j-th accepted node (depth j) lands at
+    position L + j. Returns the extended (K, V)."""
+    kn = np.asarray(k_new)[np.asarray(path)]          # [len, Hkv, D]
+    vn = np.asarray(v_new)[np.asarray(path)]
+    return (np.concatenate([np.asarray(K), np.transpose(kn, (1, 0, 2))], axis=1),
+            np.concatenate([np.asarray(V), np.transpose(vn, (1, 0, 2))], axis=1))
+
+
 # --------------------------------------------------------------------------------------
 # EVICT prefix selection (Sec. 3.1-3.2)
 # --------------------------------------------------------------------------------------

@@ -510,6 +510,44 @@ __global__ void gather_rows_kernel(const uint32_t* __restrict__ src, uint32_t* _
   for (int i = threadIdx.x; i < row_words; i += blockDim.x) dst[(size_t)r * row_words + i] = src[(size_t)s * row_words + i];
 }
 
+// Commit of the accepted path to the KV cache: the j-th accepted node of sequence b (depth j, so
+// its key was rotated at position ctx_len[b] + j) becomes cache row ctx_len[b] + j of every KV
+// head. Grid (path position, sequence); rows are copied as 4-byte words. Rows that would fall
+// past the cache capacity are dropped and the new length is clamped.
+__global__ __launch_bounds__(256) void kv_commit_kernel(
+    const uint32_t* __restrict__ k_new, const uint32_t* __restrict__ v_new, int Hkv, int head_words,
+    const int32_t* __restrict__ tree_off, const int32_t* __restrict__ path, int path_stride,
+    const int32_t* __restrict__ path_len, uint32_t* __restrict__ k_cache, uint32_t* __restrict__ v_cache,
+    long long seq_words, long long head_stride_words, const int32_t* __restrict__ ctx_len, int capacity,
+    int32_t* __restrict__ ctx_len_out, int32_t* __restrict__ status) {
+  const int j = blockIdx.x, b = blockIdx.y;
+  int len = path_len[b];
+  len = len < 0 ? 0 : (len > path_stride ? path_stride : len);
+  int L = ctx_len[b];
+  const bool badL = L < 0 || L > capacity;
+  L = L < 0 ? 0 : (L > capacity ? capacity : L);
+  const int room = capacity - L;
+  if (j == 0 && threadIdx.x == 0) {
+    ctx_len_out[b] = L + (len < room ? len : room);
+    if (status && (badL || len > room)) atomicOr(status, ST_BAD_CTXLEN);
+  }
+  if (j >= len || j >= room) return;
+  const int n = tree_off[b + 1] - tree_off[b];
+  const int node = path[(size_t)b * path_stride + j];
+  if (node < 0 || node >= n) {
+    if (status && threadIdx.x == 0) atomicOr(status, ST_BAD_PARENT);
+    return;
+  }
+  const size_t src = (size_t)(tree_off[b] + node) * Hkv * head_words;
+  const int row_words = Hkv * head_words;
+  for (int i = threadIdx.x; i < row_words; i += 256) {
+    const int h = i / head_words, c = i - h * head_words;
+    const size_t dst = (size_t)b * seq_words + (size_t)h * head_stride_words + (size_t)(L + j) * head_words + c;
+    k_cache[dst] = k_new[src + i];
+    v_cache[dst] = v_new[src + i];
+  }
+}
+
 }  // namespace
 
 int union_mask_plan(int T, int k, int E, size_t* lds_bytes) {
@@ -650,6 +688,29 @@ int evict_accept_path_sampled(evict_ctx* ctx, const int32_t* tree_off, const int
   hipLaunchKernelGGL(accept_sampled_kernel, dim3(B), dim3(kSampThreads), 0, s, tree_off, parent, draft_tok, logits, vocab,
                      inv_temp, ctx->samp_stats, u_node, u_bonus, path, path_stride, path_len, bonus_tok, ctx->status);
   return launch_status("accept_sampled_kernel");
+}
+
+int evict_kv_commit(evict_ctx* ctx, int dtype, int Hkv, int D, const void* k_new, const void* v_new, const int32_t* tree_off,
+                    const int32_t* path, int path_stride, const int32_t* path_len, void* k_cache, void* v_cache,
+                    int64_t kv_seq_stride, int64_t kv_head_stride, const int32_t* ctx_len, int capacity, int32_t* ctx_len_out,
+                    int B, void* stream) {
+  EVICT_REQUIRE(k_new && v_new && tree_off && path && path_len && k_cache && v_cache && ctx_len && ctx_len_out,
+                EVICT_E_INVALID, "evict_kv_commit: null pointer argument");
+  EVICT_REQUIRE(dtype == EVICT_F32 || dtype == EVICT_BF16, EVICT_E_INVALID, "evict_kv_commit: unknown dtype %d", dtype);
+  EVICT_REQUIRE(B >= 1 && B <= 65535 && Hkv >= 1 && D >= 1 && path_stride >= 1 && path_stride <= EVICT_MAX_SELECT_NODES,
+                EVICT_E_INVALID, "evict_kv_commit: B, Hkv, D, path_stride out of range");
+  const int eb = dtype == EVICT_BF16 ? 2 : 4;
+  EVICT_REQUIRE((D * eb) % 4 == 0, EVICT_E_INVALID, "evict_kv_commit: a head row must be a multiple of 4 bytes");
+  EVICT_REQUIRE(capacity >= 1 && kv_head_stride >= (int64_t)capacity * D && (kv_head_stride * eb) % 4 == 0 &&
+                    (kv_seq_stride * eb) % 4 == 0 && (B == 1 || kv_seq_stride >= kv_head_stride * Hkv),
+                EVICT_E_INVALID, "evict_kv_commit: cache strides do not hold capacity=%d rows per head", capacity);
+  EVICT_REQUIRE(ctx_len_out != ctx_len, EVICT_E_INVALID, "evict_kv_commit: ctx_len_out must not alias ctx_len");
+  const int head_words = D * eb / 4;
+  hipLaunchKernelGGL(kv_commit_kernel, dim3(path_stride, B), dim3(256), 0, (hipStream_t)stream, (const uint32_t*)k_new,
+                     (const uint32_t*)v_new, Hkv, head_words, tree_off, path, path_stride, path_len, (uint32_t*)k_cache,
+                     (uint32_t*)v_cache, (long long)(kv_seq_stride * eb / 4), (long long)(kv_head_stride * eb / 4), ctx_len,
+                     capacity, ctx_len_out, ctx ? ctx->status : nullptr);
+  return launch_status("kv_commit_kernel");
 }
 
 }  // extern "C"

@@ -344,3 +344,39 @@ def test_planted_mistakes_fail_the_pins(monkeypatch):
     assert disagreement() > 1e-4
     monkeypatch.setattr(orc, "tree_attention", real_att)
     assert disagreement() < 2e-7
+
+
+# ---------------------------------------------------------------- KV commit between iterations
+@pytest.mark.parametrize("m", [1, 3, 5])
+def test_commit_then_continue_equals_one_pass(m):
+    """A chain of 6 nodes verified in one pass equals: verify its first m nodes, commit them
+    (depth j -> cache position L + j), then verify the remaining nodes as a chain at context
+    L + m. A commit at the wrong position or with unrotated keys breaks this."""
+    case = _tiny_case(seed=21, n=6, L=20, tree="chain")
+    cfg, W = case["cfg"], case["W"]
+    one = _run(case)
+    first = orc.verify_layer(cfg, W, np.array([0, m]), case["parent"][:m], case["x"][:m], case["K"], case["V"],
+                             case["ctx_len"], act="f64")
+    K2, V2 = orc.kv_commit(case["K"][0], case["V"][0], first["k_new"], first["v_new"], np.arange(m))
+    assert K2.shape[1] == 20 + m
+    rest = orc.verify_layer(cfg, W, np.array([0, 6 - m]), np.arange(-1, 5 - m), case["x"][m:], [K2], [V2],
+                            np.array([20 + m]), act="f64")
+    np.testing.assert_allclose(rest["out"], one["out"][m:], rtol=0, atol=1e-9)
+    np.testing.assert_allclose(rest["k_new"], one["k_new"][m:], rtol=0, atol=1e-12)
+
+
+def test_commit_of_a_branch_equals_dense_root_path():
+    """Commit an accepted root path of a branching tree, then decode one more token: equals the
+    separately written dense evaluation of (cache + path + token) as a plain causal sequence."""
+    case = _tiny_case(seed=22, n=8, L=16, tree="random")
+    cfg, W = case["cfg"], case["W"]
+    res = _run(case)
+    leaf = 7
+    path = bf.root_path(case["parent"], leaf)
+    K2, V2 = orc.kv_commit(case["K"][0], case["V"][0], res["k_new"], res["v_new"], path)
+    g = synth.philox(22, 77)
+    xt = g.standard_normal((1, cfg.d))
+    nxt = orc.verify_layer(cfg, W, np.array([0, 1]), np.array([-1]), xt, [K2], [V2], np.array([16 + len(path)]), act="f64")
+    seq_x = np.concatenate([case["x"][path], xt])
+    out, h, _, _ = bf.node_output_dense(cfg, W, seq_x, case["K"][0], case["V"][0], 16)
+    np.testing.assert_allclose(nxt["out"][0], out, rtol=0, atol=2e-7)
