@@ -1,0 +1,108 @@
+"""Multi-iteration speculative-decoding loop around the C entry points (host-side driver only).
+
+One iteration = what the target side does between two calls of the draft model (Sec. 2.1 and
+Sec. 3): EVICT prefix selection on the draft tree (optional), compaction of the kept nodes,
+verification through the layer stack, LM head, acceptance, and the commit of the accepted
+path to every layer's KV cache. Every step runs in the library's kernels; this module only
+sequences the calls and reads back two integers per iteration (the selected length, because
+the host sizes the verification launch by it -- the analogue of picking the pre-built graph for
+that length in Sec. 3.3 -- and the accepted length, which the drafter needs to go on).
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import List, Optional
+
+import torch
+
+from . import binding as ev
+
+
+@dataclass
+class DraftOnDevice:
+    """One draft tree on the GPU (single sequence): CSR offsets, parents, draft probabilities,
+    hidden states, draft token ids; target_next replaces the LM head's argmax when given (the
+    synthetic drafter decides acceptance, see synth/drafter.py)."""
+    tree_off: torch.Tensor
+    parent: torch.Tensor
+    q: torch.Tensor
+    x: torch.Tensor
+    tok: torch.Tensor
+    target_next: Optional[torch.Tensor]
+    n: int
+
+
+@dataclass
+class IterationLog:
+    k_used: int
+    path_len: int
+    keep: Optional[List[int]] = None
+    path: List[int] = field(default_factory=list)
+    bonus: int = -1
+
+
+class SpecLoop:
+    def __init__(self, cfg, ctx, layers, k_caches, v_caches, seq_stride, head_stride, capacity, n_max,
+                 lm_head=None, device="cuda:0"):
+        """layers: list of LayerWeights; k_caches / v_caches: one [1][Hkv][capacity][D] tensor per layer;
+        lm_head: (g_final, wlm_packed) or None (then every draft must carry target_next)."""
+        self.cfg, self.ctx, self.layers = cfg, ctx, layers
+        self.kc, self.vc = k_caches, v_caches
+        self.seq_stride, self.head_stride, self.capacity = seq_stride, head_stride, capacity
+        self.n_max, self.lm_head = n_max, lm_head
+        self.dtype_code = ev.EVICT_BF16 if cfg.dtype == "bf16" else ev.EVICT_F32
+        tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+        self.eb = 2 if cfg.dtype == "bf16" else 4
+        i32, f32 = torch.int32, torch.float32
+        N, L = n_max, len(layers)
+        z = lambda *s, dt=i32: torch.zeros(*s, dtype=dt, device=device)  # noqa: E731
+        self.k_star, self.keep, self.new_parent, self.new_off, self.est = z(1), z(N), z(N), z(2), z(1, dt=f32)
+        self.xg, self.out = z(N, cfg.d, dt=tdt), z(N, cfg.d, dt=tdt)
+        self.tokg, self.tng, self.next = z(N), z(N), z(N)
+        self.k_new = [z(N, cfg.Hkv, cfg.D, dt=tdt) for _ in range(L)]
+        self.v_new = [z(N, cfg.Hkv, cfg.D, dt=tdt) for _ in range(L)]
+        self.path, self.path_len, self.bonus = z(1, N), z(1), z(1)
+        self.ctx_len = [z(1), z(1)]  # ping-pong: a commit reads one and writes the other
+        self.cur = 0
+        self.ctx_len_host = 0
+
+    def set_context_length(self, L: int):
+        self.ctx_len[self.cur].fill_(L)
+        self.ctx_len_host = L
+
+    def iteration(self, d: DraftOnDevice, cost: Optional[torch.Tensor], log_lists: bool = False) -> IterationLog:
+        """cost: device cost table float32[n + 1] -> EVICT truncation; None -> verify all n nodes."""
+        cfg, n = self.cfg, d.n
+        cl_in, cl_out = self.ctx_len[self.cur], self.ctx_len[self.cur ^ 1]
+        if cost is not None:
+            ev.evict_select_prefix(None, d.tree_off, d.parent, d.q, 1, n, cost, n, self.k_star, self.keep, self.new_parent,
+                                   self.new_off, self.est)
+            k = int(self.k_star.item())
+            ev.evict_gather_rows(d.x, self.xg, cfg.d * self.eb, d.tree_off, self.new_off, self.keep, 1, n)
+            ev.evict_gather_rows(d.tok, self.tokg, 4, d.tree_off, self.new_off, self.keep, 1, n)
+            if d.target_next is not None:
+                ev.evict_gather_rows(d.target_next, self.tng, 4, d.tree_off, self.new_off, self.keep, 1, n)
+            off, par, x, tok, tn = self.new_off, self.new_parent, self.xg, self.tokg, self.tng
+        else:
+            k = n
+            off, par, x, tok, tn = d.tree_off, d.parent, d.x, d.tok, d.target_next
+        ev.evict_verify_stack(self.ctx, self.layers, off, par, 1, k, self.kc, self.vc, self.seq_stride, self.head_stride,
+                              cl_in, max(self.ctx_len_host, 1), x, self.out, self.k_new, self.v_new)
+        if self.lm_head is not None:
+            ev.evict_lm_head_argmax(self.ctx, self.out, self.lm_head[0], self.lm_head[1], k, self.next)
+        if d.target_next is None:
+            tn = self.next
+        ev.evict_accept_path(None, off, par, tok, tn, 1, self.path, self.n_max, self.path_len, self.bonus)
+        for l in range(len(self.layers)):
+            ev.evict_kv_commit(self.ctx, self.dtype_code, cfg.Hkv, cfg.D, self.k_new[l], self.v_new[l], off, self.path,
+                               self.n_max, self.path_len, self.kc[l], self.vc[l], self.seq_stride, self.head_stride, cl_in,
+                               self.capacity, cl_out, 1)
+        plen = int(self.path_len.item())
+        self.cur ^= 1
+        self.ctx_len_host = min(self.ctx_len_host + plen, self.capacity)
+        log = IterationLog(k_used=k, path_len=plen)
+        if log_lists:
+            log.keep = self.keep[:k].tolist() if cost is not None else None
+            log.path = self.path[0, :plen].tolist()
+            log.bonus = int(self.bonus.item())
+        return log

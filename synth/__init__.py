@@ -5,3 +5,4 @@ probabilities, cost vectors, storage-dtype rounding). It contains none of the me
 arithmetic and imports neither the CPU oracle nor the HIP library.
 """
 from .inputs import *  # noqa: F401,F403
+from .drafter import draft_iteration  # noqa: F401

@@ -1,0 +1,91 @@
+"""Several speculative iterations in a row (selection -> compaction -> layer stack -> acceptance
+-> KV commit) on the GPU against the same loop composed from the CPU oracle's functions, with
+the synthetic drafter's draws as shared inputs. Integers (selected length, kept nodes, accepted
+path, context length) must be identical in every iteration; the hidden states of the last
+iteration, which depend on every earlier commit, must agree within the layer tolerance."""
+import numpy as np
+import pytest
+import torch
+
+import synth
+from oracle import evict_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+ev = pytest.importorskip("paper_2605_00342_amd")
+from paper_2605_00342_amd import harness  # noqa: E402
+from paper_2605_00342_amd.spec_loop import DraftOnDevice, SpecLoop  # noqa: E402
+
+DEV = "cuda:0"
+
+
+def rel_l2(a, b):
+    return float(np.linalg.norm(np.asarray(a, np.float64) - b) / max(np.linalg.norm(b), 1e-30))
+
+
+def to_device(cfg, d):
+    n = len(d["parent"])
+    return DraftOnDevice(harness.dev_i32(np.array([0, n])), harness.dev_i32(d["parent"]), torch.from_numpy(d["q"]).to(DEV),
+                         harness.to_dev(d["x"], cfg.dtype), harness.dev_i32(d["tok"]), harness.dev_i32(d["target_next"]), n)
+
+
+@pytest.mark.parametrize("cfg_name,truncate", [("tiny", True), ("tiny", False), ("mini_bf16", True)])
+def test_loop_matches_oracle_composition(cfg_name, truncate):
+    cfg = synth.CONFIGS[cfg_name]
+    n_layers, N, L0, cap, iters, seed = 2, 14, 37, 128, 4, 71
+    Ws = [synth.layer_weights(cfg, synth.philox(seed, 1 + l)) for l in range(n_layers)]
+    kv = [synth.kv_cache(cfg, L0, synth.philox(seed, 200 + l)) for l in range(n_layers)]
+    drafts = [synth.draft_iteration(cfg, N, seed, it, 0.4, vocab=500) for it in range(iters)]
+    # a cost table steep enough that truncation really cuts some trees
+    cost = (1.0 + 0.35 * np.arange(N + 1)).astype(np.float32)
+
+    layers = [harness.DeviceLayer(cfg, Ws[0], max_tokens=N, max_batch=1, max_ctx=cap)]
+    for W in Ws[1:]:
+        layers.append(harness.DeviceLayer(cfg, W, 0, 0, 0, ctx=layers[0].ctx))
+    try:
+        tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+        kc = [torch.zeros(1, cfg.Hkv, cap, cfg.D, dtype=tdt, device=DEV) for _ in range(n_layers)]
+        vc = [torch.zeros_like(k) for k in kc]
+        for l in range(n_layers):
+            kc[l][0, :, :L0] = harness.to_dev(kv[l][0], cfg.dtype)
+            vc[l][0, :, :L0] = harness.to_dev(kv[l][1], cfg.dtype)
+        loop = SpecLoop(cfg, layers[0].ctx, [l.weights for l in layers], kc, vc, cfg.Hkv * cap * cfg.D, cap * cfg.D, cap, N)
+        loop.set_context_length(L0)
+        cost_dev = torch.from_numpy(cost).to(DEV) if truncate else None
+
+        K = [kv[l][0] for l in range(n_layers)]
+        V = [kv[l][1] for l in range(n_layers)]
+        L = L0
+        lens = []
+        for it, d in enumerate(drafts):
+            log = loop.iteration(to_device(cfg, d), cost_dev, log_lists=True)
+            # ---- the same iteration from the oracle's functions
+            par, x, tok, tn = d["parent"], d["x"], d["tok"], d["target_next"]
+            if truncate:
+                sel = orc.select_prefix(d["parent"], d["q"], cost, N)
+                keep = sel["keep"]
+                assert log.k_used == sel["k_star"] and log.keep == list(keep)
+                par, x, tok, tn = sel["new_parent"], x[keep], tok[keep], tn[keep]
+            else:
+                assert log.k_used == N
+            outs = []
+            xin = x
+            for l in range(n_layers):
+                r = orc.verify_layer(cfg, Ws[l], np.array([0, len(par)]), par, xin, [K[l]], [V[l]], np.array([L]))
+                outs.append(r)
+                xin = r["out"]
+            path, bonus = orc.accept_path(par, tok, tn)
+            assert log.path == list(path) and log.bonus == bonus and log.path_len == len(path)
+            for l in range(n_layers):
+                K[l], V[l] = orc.kv_commit(K[l], V[l], orc.handoff(outs[l]["k_new"], cfg.dtype),
+                                           orc.handoff(outs[l]["v_new"], cfg.dtype), path)
+            L += len(path)
+            lens.append(len(path))
+            assert loop.ctx_len_host == L and int(loop.ctx_len[loop.cur].item()) == L
+            tol = (1e-4 if cfg.dtype == "f32" else 2e-2) * 1.5
+            assert rel_l2(harness.to_host(loop.out[: len(par)]), outs[-1]["out"]) < tol, f"iteration {it}"
+        assert max(lens) > 1, "the synthetic drafter never got a token accepted: the case tests nothing"
+        if truncate:
+            assert ev.evict_device_status(layers[0].ctx) == 0
+    finally:
+        layers[0].close()
