@@ -47,6 +47,11 @@ def parse():
                     help="not the default line: one JSON line per (N, sigma) point, N in 1..128, sigma in {0.2, 0.5, 1.0}")
     ap.add_argument("--launch", default="eager", choices=["graph", "eager"],
                     help="timed steps call the entry points (default), or replay one captured HIP graph per weight copy")
+    ap.add_argument("--loop", action="store_true",
+                    help="not the default line: multi-iteration speculative loop with a synthetic calibrated drafter, "
+                         "fixed-size verification against EVICT truncation (one JSON line each)")
+    ap.add_argument("--layers", type=int, default=8, help="--loop: layers in the stack (distinct weights each)")
+    ap.add_argument("--iters", type=int, default=128, help="--loop: timed iterations per mode")
     ap.add_argument("--probe-copy", type=int, default=0, metavar="MiB",
                     help="not the default line: run the plain copy and read kernels on MiB bytes (counter "
                          "calibration under rocprofv3 --pmc, and the streaming-read ceiling) and exit")
@@ -129,6 +134,90 @@ def sweep(args):
     layer.close()
 
 
+def spec_loop(args):
+    """End-to-end simulated decoding: tokens/s and mean accepted tokens per iteration, verifying all
+    N draft nodes every iteration against EVICT's cost-aware prefix (Sec. 3), on one stack of
+    Qwen3-shaped layers + LM head. The cost table is profiled on the device (Sec. 3.2.3)."""
+    import torch
+
+    import synth
+    import paper_2605_00342_amd as ev
+    from paper_2605_00342_amd import harness
+    from paper_2605_00342_amd.spec_loop import DraftOnDevice, SpecLoop
+
+    dev = "cuda:0"
+    cfg = synth.CONFIGS["qwen3"]
+    N, L0, nl, vocab = args.nodes, args.ctx, args.layers, 151936
+    cap = L0 + 4096
+    base = synth.make_case("qwen3", n=N, L=16, seed=args.seed)
+    first = harness.DeviceLayer(cfg, base["W"], max_tokens=N, max_batch=1, max_ctx=cap, vocab=vocab)
+    # further layers: independent values of the same distribution, drawn directly in the packed layout
+    # (packing is a permutation, so i.i.d. values packed or not are the same thing)
+    gen = torch.Generator(device=dev).manual_seed(args.seed)
+    keep, layers = [], [first.weights]
+    for _ in range(nl - 1):
+        cp = {n: (torch.randn(getattr(first, n).shape, generator=gen, device=dev) * 0.02).to(torch.bfloat16)
+              for n in ("wqkv", "wo", "wg", "w_gateup", "w_down")}
+        keep.append(cp)
+        layers.append(ev.LayerWeights(first.g_attn.data_ptr(), first.g_moe.data_ptr(), cp["wqkv"].data_ptr(), cp["wo"].data_ptr(),
+                                      cp["wg"].data_ptr(), cp["w_gateup"].data_ptr(), cp["w_down"].data_ptr(), None, None))
+    wlm = (torch.randn(vocab * cfg.d, generator=gen, device=dev) * 0.02).to(torch.bfloat16)
+    g_final = torch.ones(cfg.d, dtype=torch.bfloat16, device=dev)
+    kc = [torch.randn(1, cfg.Hkv, cap, cfg.D, generator=gen, device=dev).to(torch.bfloat16) for _ in range(nl)]
+    vc = [torch.randn(1, cfg.Hkv, cap, cfg.D, generator=gen, device=dev).to(torch.bfloat16) for _ in range(nl)]
+    loop = SpecLoop(cfg, first.ctx, layers, kc, vc, cfg.Hkv * cap * cfg.D, cap * cfg.D, cap, N, lm_head=(g_final, wlm))
+
+    pool = []
+    for it in range(64):
+        d = synth.draft_iteration(cfg, N, args.seed, it, args.sigma, vocab)
+        pool.append(DraftOnDevice(harness.dev_i32(np.array([0, N])), harness.dev_i32(d["parent"]), torch.from_numpy(d["q"]).to(dev),
+                                  harness.to_dev(d["x"], cfg.dtype), harness.dev_i32(d["tok"]), harness.dev_i32(d["target_next"]), N))
+
+    # cost table C(k) of the stack, timed on the device stream; the LM head's share is constant in k
+    # up to its token tiles and is left out, as the layers are what grows with k
+    d0 = pool[0]
+    loop.set_context_length(L0)
+    cost = ev.evict_profile_cost(first.ctx, layers, d0.tree_off, d0.parent, N, kc, vc, cap * cfg.D, loop.ctx_len[loop.cur], L0,
+                                 d0.x, loop.out, loop.k_new, loop.v_new, 6)
+    results = {}
+    cost_dev = None
+    for mode in ("verify_all", "evict"):
+        if mode == "evict":
+            # C(k) must be the cost of a whole iteration at length k: the part outside the layer stack
+            # (LM head, acceptance, commits, read-backs) is taken from the measured full-size iteration
+            offset = max(results["verify_all"]["ms_per_iteration"] - cost[N], 0.0)
+            cost = [c + offset for c in cost]
+            cost_dev = torch.tensor(cost, dtype=torch.float32, device=dev)
+        table = cost_dev
+        loop.set_context_length(L0)
+        for i in range(8):
+            loop.iteration(pool[i % len(pool)], table)
+        loop.set_context_length(L0)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        tokens = ksum = 0
+        for i in range(args.iters):
+            log = loop.iteration(pool[i % len(pool)], table)
+            tokens += log.path_len
+            ksum += log.k_used
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        results[mode] = {"tokens_per_s": tokens / dt, "ms_per_iteration": dt * 1e3 / args.iters,
+                         "mean_accepted_tokens": tokens / args.iters, "mean_verified_nodes": ksum / args.iters}
+    for mode, r in results.items():
+        print(json.dumps({"metric": "simulated_decode_tokens_per_s", "mode": mode, "value": round(r["tokens_per_s"], 1),
+                          "unit": "tokens/s", "ms_per_iteration": round(r["ms_per_iteration"], 4),
+                          "mean_accepted_tokens": round(r["mean_accepted_tokens"], 3),
+                          "mean_verified_nodes": round(r["mean_verified_nodes"], 2),
+                          "speedup_vs_verify_all": round(r["tokens_per_s"] / results["verify_all"]["tokens_per_s"], 4),
+                          "config": {"workload": f"qwen3-30b-a3b-shaped stack of {nl} layers + LM head, N={N} draft nodes, "
+                                                 f"ctx from {L0}, synthetic calibrated drafter, sigma={args.sigma}",
+                                     "iterations": args.iters},
+                          "cost_table_ms": [round(c, 4) for c in cost[1:]] if mode == "evict" else None,
+                          "data": "synthetic", "dtype": "bf16"}), flush=True)
+    first.close()
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -150,6 +239,9 @@ def main():
         return
     if args.sweep:
         sweep(args)
+        return
+    if args.loop:
+        spec_loop(args)
         return
     cfg = synth.CONFIGS[args.model]
     N, L = args.nodes, args.ctx
