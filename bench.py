@@ -181,23 +181,24 @@ def spec_loop(args):
                                  d0.x, loop.out, loop.k_new, loop.v_new, 6)
     results = {}
     cost_dev = None
-    for mode in ("verify_all", "evict"):
+    for mode in ("verify_all", "evict", "coverage_0.7", "coverage_0.4"):
+        rho = float(mode.split("_")[1]) if mode.startswith("coverage") else None
         if mode == "evict":
             # C(k) must be the cost of a whole iteration at length k: the part outside the layer stack
             # (LM head, acceptance, commits, read-backs) is taken from the measured full-size iteration
             offset = max(results["verify_all"]["ms_per_iteration"] - cost[N], 0.0)
             cost = [c + offset for c in cost]
             cost_dev = torch.tensor(cost, dtype=torch.float32, device=dev)
-        table = cost_dev
+        table = cost_dev if mode == "evict" else None
         loop.set_context_length(L0)
         for i in range(8):
-            loop.iteration(pool[i % len(pool)], table)
+            loop.iteration(pool[i % len(pool)], table, rho=rho)
         loop.set_context_length(L0)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         tokens = ksum = 0
         for i in range(args.iters):
-            log = loop.iteration(pool[i % len(pool)], table)
+            log = loop.iteration(pool[i % len(pool)], table, rho=rho)
             tokens += log.path_len
             ksum += log.k_used
         torch.cuda.synchronize()

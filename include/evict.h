@@ -221,6 +221,16 @@ int evict_select_prefix(evict_ctx* ctx, const int32_t* tree_off, const int32_t* 
                         int32_t* k_star, int32_t* keep, int32_t* new_parent, int32_t* new_tree_off,
                         float* est_len, int32_t* order, float* prefix_sum, void* stream);
 
+/* Cost-agnostic ablation of the selection (Sec. 4.3.2): same ranking and prefix sums, but
+ * k*[b] = the smallest k in 1..min(N_b, Kmax) with S_k / S_{N_b} >= rho (one IEEE fp32 division
+ * and comparison per k; the whole budget min(N_b, Kmax) when no such k exists). rho in [0, 1];
+ * rho = 1 keeps every node whose score still changes the fp32 running sum. All other
+ * arguments and outputs as evict_select_prefix. */
+int evict_select_prefix_coverage(evict_ctx* ctx, const int32_t* tree_off, const int32_t* parent,
+                                 const float* node_prob, int B, int T, float rho, int Kmax, int32_t* k_star,
+                                 int32_t* keep, int32_t* new_parent, int32_t* new_tree_off, float* est_len,
+                                 int32_t* order, float* prefix_sum, void* stream);
+
 /* Commit of the accepted path to the KV cache of one layer (what follows acceptance in every
  * speculative iteration, Sec. 2.1): for sequence b and j < path_len[b], the draft key/value row
  * of node path[b][j] (k_new / v_new [dev] [T][Hkv][D], storage dtype, as written by

@@ -422,6 +422,30 @@ def select_prefix(parent, q, cost, kmax):
             "new_parent": new_parent, "est_len": F32(S[kstar - 1]), "margin": margin}
 
 
+def select_prefix_coverage(parent, q, rho, kmax):
+    """Cost-agnostic ablation (Sec. 4.3.2): same ranking and float32 running sums as
+    select_prefix; k* = smallest k in 1..min(N, kmax) with S_k / S_N >= rho (float32 division),
+    or the whole budget when no such k exists."""
+    n = len(parent)
+    score = node_scores(parent, q)
+    order = np.asarray(sorted(range(n), key=lambda i: (-float(score[i]), i)), dtype=np.int32)
+    S = np.zeros(n, dtype=F32)
+    acc = F32(0.0)
+    for j in range(n):
+        acc = F32(acc + score[order[j]])
+        S[j] = acc
+    kk = min(n, int(kmax))
+    kstar = kk
+    for j in range(kk):
+        if F32(S[j] / S[n - 1]) >= F32(rho):
+            kstar = j + 1
+            break
+    keep = np.sort(order[:kstar]).astype(np.int32)
+    rank = {int(v): r for r, v in enumerate(keep)}
+    new_parent = np.asarray([-1 if parent[v] < 0 else rank[int(parent[v])] for v in keep], dtype=np.int32)
+    return {"k_star": kstar, "order": order, "S": S, "keep": keep, "new_parent": new_parent, "est_len": F32(S[kstar - 1])}
+
+
 def expected_accept_len_exact(parent, p):
     """Eq. 6: sum over nodes of the product of acceptance probabilities along the root path."""
     n = len(parent)

@@ -17,7 +17,8 @@ __all__ = [
     "evict_select_prefix", "evict_gather_rows", "evict_validate_trees_host", "evict_device_status",
     "evict_stage_timing", "evict_stage_times", "evict_probe_read", "evict_probe_copy", "evict_tune", "evict_verify_stack", "evict_lm_head_argmax",
     "evict_profile_cost", "evict_graph_begin", "evict_graph_end", "evict_graph_launch", "evict_graph_destroy",
-    "evict_lm_head_logits", "evict_accept_path_sampled", "evict_kv_commit", "STAGES", "EXPORTS",
+    "evict_lm_head_logits", "evict_accept_path_sampled", "evict_kv_commit", "evict_select_prefix_coverage",
+    "STAGES", "EXPORTS",
 ]
 
 EVICT_F32, EVICT_BF16 = 0, 1
@@ -30,7 +31,7 @@ EXPORTS = [
     "evict_select_prefix", "evict_gather_rows", "evict_validate_trees_host", "evict_device_status",
     "evict_stage_timing", "evict_stage_times", "evict_probe_read", "evict_probe_copy", "evict_tune", "evict_verify_stack", "evict_lm_head_argmax",
     "evict_profile_cost", "evict_graph_begin", "evict_graph_end", "evict_graph_launch", "evict_graph_destroy",
-    "evict_lm_head_logits", "evict_accept_path_sampled", "evict_kv_commit",
+    "evict_lm_head_logits", "evict_accept_path_sampled", "evict_kv_commit", "evict_select_prefix_coverage",
 ]
 STAGES = ["prep", "qkv", "attention", "oproj", "router", "union", "gateup", "down", "shared", "combine"]
 
@@ -89,6 +90,7 @@ def load():
     lib.evict_expert_union.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.evict_accept_path.argtypes = [vp, vp, vp, vp, vp, i32, vp, i32, vp, vp, vp]
     lib.evict_select_prefix.argtypes = [vp, vp, vp, vp, i32, i32, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.evict_select_prefix_coverage.argtypes = [vp, vp, vp, vp, i32, i32, C.c_float, i32, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.evict_gather_rows.argtypes = [vp, vp, i32, vp, vp, vp, i32, i32, vp]
     lib.evict_validate_trees_host.argtypes = [vp, vp, i32, i32]
     lib.evict_device_status.argtypes = [vp, C.POINTER(C.c_int32), vp]
@@ -187,6 +189,13 @@ def evict_select_prefix(ctx, tree_off, parent, node_prob, B, T, cost, Kmax, k_st
     _check(load().evict_select_prefix(ctx, _p(tree_off), _p(parent), _p(node_prob), B, T, _p(cost), Kmax, _p(k_star),
                                       _p(keep), _p(new_parent), _p(new_tree_off), _p(est_len), _p(order),
                                       _p(prefix_sum), _stream()))
+
+
+def evict_select_prefix_coverage(ctx, tree_off, parent, node_prob, B, T, rho, Kmax, k_star, keep, new_parent, new_tree_off,
+                                 est_len, order=None, prefix_sum=None) -> None:
+    _check(load().evict_select_prefix_coverage(ctx, _p(tree_off), _p(parent), _p(node_prob), B, T, float(rho), Kmax,
+                                               _p(k_star), _p(keep), _p(new_parent), _p(new_tree_off), _p(est_len),
+                                               _p(order), _p(prefix_sum), _stream()))
 
 
 def evict_gather_rows(src, dst, row_bytes, tree_off, new_tree_off, keep, B, T) -> None:

@@ -62,7 +62,7 @@ __global__ __launch_bounds__(kSelThreads) void select_prefix_kernel(
     const int32_t* __restrict__ tree_off, const int32_t* __restrict__ parent, const float* __restrict__ prob,
     const float* __restrict__ cost, int kmax, int32_t* __restrict__ k_star, float* __restrict__ est_len,
     int32_t* __restrict__ order_out, float* __restrict__ psum_out, int32_t* rank_ws, int single, int32_t* keep,
-    int32_t* new_parent, int32_t* __restrict__ new_tree_off, int n_single) {
+    int32_t* new_parent, int32_t* __restrict__ new_tree_off, int n_single, float rho) {
   __shared__ int s_par[kMaxSel];
   __shared__ __attribute__((aligned(16))) float s_score[kMaxSel];
   __shared__ float s_sorted[kMaxSel];
@@ -89,7 +89,7 @@ __global__ __launch_bounds__(kSelThreads) void select_prefix_kernel(
     else if (p < 0 || p >= i) p = 0;  // invalid ids are clamped (the host check rejects them)
     s_par[i] = p;
     s_prob[i] = prob[lo + i];                      // all global reads issued together, up front
-    s_cost[i] = i < kmax ? cost[i + 1] : 1.0f;     // s_cost[i] = C(i + 1)
+    s_cost[i] = (cost && i < kmax) ? cost[i + 1] : 1.0f;  // s_cost[i] = C(i + 1)
   }
   __syncthreads();
   // depth of every node (walk to the root; parent ids strictly decrease)
@@ -156,7 +156,12 @@ __global__ __launch_bounds__(kSelThreads) void select_prefix_kernel(
     const float S = s_sorted[i];
     if (psum_out) psum_out[lo + i] = S;
     if (i < kk) {
-      const float u = __fdiv_rn(S, s_cost[i]);
+      // cost-aware rule: u_k = S_k / C(k). Coverage rule (rho >= 0, the cost-agnostic ablation of
+      // Sec. 4.3.2): u_k = 1 where S_k / S_n >= rho, else 0, so that the first maximum is the
+      // smallest prefix reaching the coverage.
+      float u;
+      if (rho >= 0.0f) u = __fdiv_rn(S, s_sorted[n - 1]) >= rho ? 1.0f : 0.0f;
+      else u = __fdiv_rn(S, s_cost[i]);
       if (u > bv || (u == bv && i < bi)) { bv = u; bi = i; }
     }
   }
@@ -174,6 +179,7 @@ __global__ __launch_bounds__(kSelThreads) void select_prefix_kernel(
     const int oi = s_besti[i];
     if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
   }
+  if (rho >= 0.0f && bv == 0.0f) bi = kk - 1;  // coverage not reached within kmax: the whole budget
   const int kstar = bi + 1;
   if (tid == 0) {
     k_star[b] = kstar;
@@ -587,22 +593,23 @@ int evict_validate_trees_host(const int32_t* tree_off, const int32_t* parent, in
   return EVICT_OK;
 }
 
-int evict_select_prefix(evict_ctx*, const int32_t* tree_off, const int32_t* parent, const float* node_prob, int B,
-                        int T, const float* cost, int Kmax, int32_t* k_star, int32_t* keep, int32_t* new_parent,
-                        int32_t* new_tree_off, float* est_len, int32_t* order, float* prefix_sum, void* stream) {
-  EVICT_REQUIRE(tree_off && parent && node_prob && cost && k_star && keep && new_parent && new_tree_off && est_len,
-                EVICT_E_INVALID, "evict_select_prefix: null pointer argument");
-  EVICT_REQUIRE(B >= 1 && T >= B, EVICT_E_INVALID, "evict_select_prefix: need B >= 1 and T >= B (B=%d, T=%d)", B, T);
-  EVICT_REQUIRE(Kmax >= 1, EVICT_E_INVALID, "evict_select_prefix: Kmax must be >= 1 (got %d)", Kmax);
-  EVICT_REQUIRE(T <= B * (int64_t)EVICT_MAX_SELECT_NODES, EVICT_E_UNSUPPORTED,
-                "evict_select_prefix: more than %d nodes per tree", EVICT_MAX_SELECT_NODES);
+static int select_prefix_impl(const char* who, const int32_t* tree_off, const int32_t* parent, const float* node_prob, int B,
+                              int T, const float* cost, float rho, int Kmax, int32_t* k_star, int32_t* keep,
+                              int32_t* new_parent, int32_t* new_tree_off, float* est_len, int32_t* order,
+                              float* prefix_sum, void* stream) {
+  EVICT_REQUIRE(tree_off && parent && node_prob && k_star && keep && new_parent && new_tree_off && est_len,
+                EVICT_E_INVALID, "%s: null pointer argument", who);
+  EVICT_REQUIRE(B >= 1 && T >= B, EVICT_E_INVALID, "%s: need B >= 1 and T >= B (B=%d, T=%d)", who, B, T);
+  EVICT_REQUIRE(Kmax >= 1, EVICT_E_INVALID, "%s: Kmax must be >= 1 (got %d)", who, Kmax);
+  EVICT_REQUIRE(T <= B * (int64_t)EVICT_MAX_SELECT_NODES, EVICT_E_UNSUPPORTED, "%s: more than %d nodes per tree", who,
+                EVICT_MAX_SELECT_NODES);
   hipStream_t s = (hipStream_t)stream;
   const int single = B == 1;
   // trees of at most 64 nodes are handled by a single wavefront per tree
   const int sel_threads = (B == 1 && T <= 64) ? 64 : kSelThreads;
   hipLaunchKernelGGL(select_prefix_kernel, dim3(B), dim3(sel_threads), 0, s, tree_off, parent, node_prob, cost, Kmax,
                      k_star, est_len, order, prefix_sum, new_parent /* rank workspace */, single, keep, new_parent,
-                     new_tree_off, single ? T : 0);
+                     new_tree_off, single ? T : 0, rho);
   int rc = launch_status("select_prefix_kernel");
   if (rc) return rc;
   if (!single) {
@@ -611,6 +618,22 @@ int evict_select_prefix(evict_ctx*, const int32_t* tree_off, const int32_t* pare
     rc = launch_status("compact_batch_kernel");
   }
   return rc;
+}
+
+int evict_select_prefix(evict_ctx*, const int32_t* tree_off, const int32_t* parent, const float* node_prob, int B,
+                        int T, const float* cost, int Kmax, int32_t* k_star, int32_t* keep, int32_t* new_parent,
+                        int32_t* new_tree_off, float* est_len, int32_t* order, float* prefix_sum, void* stream) {
+  EVICT_REQUIRE(cost, EVICT_E_INVALID, "evict_select_prefix: null cost table");
+  return select_prefix_impl("evict_select_prefix", tree_off, parent, node_prob, B, T, cost, -1.0f, Kmax, k_star, keep,
+                            new_parent, new_tree_off, est_len, order, prefix_sum, stream);
+}
+
+int evict_select_prefix_coverage(evict_ctx*, const int32_t* tree_off, const int32_t* parent, const float* node_prob, int B,
+                                 int T, float rho, int Kmax, int32_t* k_star, int32_t* keep, int32_t* new_parent,
+                                 int32_t* new_tree_off, float* est_len, int32_t* order, float* prefix_sum, void* stream) {
+  EVICT_REQUIRE(rho >= 0.0f && rho <= 1.0f, EVICT_E_INVALID, "evict_select_prefix_coverage: rho=%g outside [0, 1]", (double)rho);
+  return select_prefix_impl("evict_select_prefix_coverage", tree_off, parent, node_prob, B, T, nullptr, rho, Kmax, k_star,
+                            keep, new_parent, new_tree_off, est_len, order, prefix_sum, stream);
 }
 
 int evict_accept_path(evict_ctx*, const int32_t* tree_off, const int32_t* parent, const int32_t* draft_tok,

@@ -70,13 +70,19 @@ class SpecLoop:
         self.ctx_len[self.cur].fill_(L)
         self.ctx_len_host = L
 
-    def iteration(self, d: DraftOnDevice, cost: Optional[torch.Tensor], log_lists: bool = False) -> IterationLog:
-        """cost: device cost table float32[n + 1] -> EVICT truncation; None -> verify all n nodes."""
+    def iteration(self, d: DraftOnDevice, cost: Optional[torch.Tensor], log_lists: bool = False,
+                  rho: Optional[float] = None) -> IterationLog:
+        """cost: device cost table float32[n + 1] -> EVICT truncation; rho -> the cost-agnostic
+        coverage rule instead; neither -> verify all n nodes."""
         cfg, n = self.cfg, d.n
         cl_in, cl_out = self.ctx_len[self.cur], self.ctx_len[self.cur ^ 1]
-        if cost is not None:
-            ev.evict_select_prefix(None, d.tree_off, d.parent, d.q, 1, n, cost, n, self.k_star, self.keep, self.new_parent,
-                                   self.new_off, self.est)
+        if cost is not None or rho is not None:
+            if cost is not None:
+                ev.evict_select_prefix(None, d.tree_off, d.parent, d.q, 1, n, cost, n, self.k_star, self.keep,
+                                       self.new_parent, self.new_off, self.est)
+            else:
+                ev.evict_select_prefix_coverage(None, d.tree_off, d.parent, d.q, 1, n, rho, n, self.k_star, self.keep,
+                                                self.new_parent, self.new_off, self.est)
             k = int(self.k_star.item())
             ev.evict_gather_rows(d.x, self.xg, cfg.d * self.eb, d.tree_off, self.new_off, self.keep, 1, n)
             ev.evict_gather_rows(d.tok, self.tokg, 4, d.tree_off, self.new_off, self.keep, 1, n)
@@ -102,7 +108,7 @@ class SpecLoop:
         self.ctx_len_host = min(self.ctx_len_host + plen, self.capacity)
         log = IterationLog(k_used=k, path_len=plen)
         if log_lists:
-            log.keep = self.keep[:k].tolist() if cost is not None else None
+            log.keep = self.keep[:k].tolist() if (cost is not None or rho is not None) else None
             log.path = self.path[0, :plen].tolist()
             log.bonus = int(self.bonus.item())
         return log

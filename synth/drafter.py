@@ -14,9 +14,48 @@ import numpy as np
 from .inputs import ModelCfg, hidden_states, philox, tree_bfs_random, tree_eagle_style, draft_probs
 
 
-def draft_iteration(cfg: ModelCfg, n: int, seed: int, it: int, sigma: float, vocab: int, tree: str = "eagle") -> dict:
+def tree_topk_drafter(n: int, g: np.random.Generator, first_branch: int = 4, branch: int = 2, max_depth: int = 6,
+                      support: int = 32, sharpness: float = 2.0):
+    """Draft tree whose sibling probabilities are parts of one distribution, as a real drafter's
+    are: at an expanded node a categorical over `support` candidates is drawn (softmax of
+    sharpness * N(0,1)) and its most likely entries become the children, so siblings sum to at
+    most 1. Expansion order as in tree_eagle_style: the root gets `first_branch` children, then
+    the childless node of depth < max_depth with the highest cumulative probability (ties:
+    lowest index) gets `branch`, until n nodes exist. Returns (parent, q)."""
+    parent, q, cum, dep, has_child = [-1], [1.0], [1.0], [0], [False]
+
+    def expand(v: int, m: int):
+        has_child[v] = True
+        z = sharpness * g.standard_normal(support)
+        p = np.exp(z - z.max())
+        p = np.sort(p / p.sum())[::-1]
+        for j in range(m):
+            if len(parent) >= n:
+                return
+            parent.append(v)
+            q.append(float(p[j]))
+            cum.append(cum[v] * float(p[j]))
+            dep.append(dep[v] + 1)
+            has_child.append(False)
+
+    if n > 1:
+        expand(0, first_branch)
+    while len(parent) < n:
+        cand = [i for i in range(len(parent)) if not has_child[i] and dep[i] < max_depth]
+        if not cand:
+            break
+        expand(max(cand, key=lambda i: (cum[i], -i)), branch)
+    while len(parent) < n:  # every leaf at max depth: hang the rest under the root with small mass
+        parent.append(0)
+        q.append(1e-3)
+    return np.asarray(parent, dtype=np.int32), np.asarray(q, dtype=np.float32)
+
+
+def draft_iteration(cfg: ModelCfg, n: int, seed: int, it: int, sigma: float, vocab: int, tree: str = "topk") -> dict:
     g = philox(seed, 5000 + it)
-    if tree == "eagle":
+    if tree == "topk":
+        parent, q = tree_topk_drafter(n, g)
+    elif tree == "eagle":
         parent, q = tree_eagle_style(n, g)
     else:
         parent = tree_bfs_random(n, g)

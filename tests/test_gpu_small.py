@@ -168,3 +168,36 @@ def test_gather_rows_matches_keep_lists():
         for r in range(got["new_off"][b], got["new_off"][b + 1]):
             assert np.array_equal(dst[r], srcn[off[b] + got["keep"][r]])
     assert np.all(dst[n_new:] == -1)
+
+
+@pytest.mark.parametrize("sizes,kind,seed,rho,kdiv", [
+    ([32], "eagle", 1, 0.7, 1), ([32], "eagle", 1, 0.4, 1), ([1], "random", 2, 0.5, 1),
+    ([64, 64, 64, 64], "random", 3, 0.85, 1), ([5, 128, 1, 77, 32], "random", 4, 1.0, 1),
+    ([300, 1024, 17], "eagle", 7, 0.6, 1), ([40, 90], "random", 9, 0.999, 2), ([24], "chain", 10, 0.0, 1),
+])
+def test_select_prefix_coverage_bit_exact(sizes, kind, seed, rho, kdiv):
+    """Cost-agnostic coverage rule (Sec. 4.3.2): smallest prefix with S_k / S_N >= rho, decided in fp32 on both sides."""
+    off, par, pars, q, qs = _trees(sizes, seed, kind)
+    kmax = max(1, max(sizes) // kdiv)
+    B, T = len(sizes), int(off[-1])
+    d = dict(k_star=torch.zeros(B, dtype=torch.int32, device=DEV), keep=torch.full((T,), -7, dtype=torch.int32, device=DEV),
+             new_parent=torch.full((T,), -7, dtype=torch.int32, device=DEV),
+             new_off=torch.zeros(B + 1, dtype=torch.int32, device=DEV), est=torch.zeros(B, device=DEV))
+    ev.evict_select_prefix_coverage(None, _i32(off), _i32(par), _f32(q), B, T, rho, kmax, d["k_star"], d["keep"],
+                                    d["new_parent"], d["new_off"], d["est"])
+    torch.cuda.synchronize()
+    got = {k: v.cpu().numpy() for k, v in d.items()}
+    out = 0
+    for b, n in enumerate(sizes):
+        ref = orc.select_prefix_coverage(pars[b], qs[b], rho, kmax)
+        ks = ref["k_star"]
+        assert got["k_star"][b] == ks, (b, n)
+        assert got["new_off"][b] == out
+        assert got["est"][b:b + 1].view(np.uint32)[0] == np.float32(ref["est_len"]).view(np.uint32)
+        assert np.array_equal(got["keep"][out:out + ks], ref["keep"])
+        assert np.array_equal(got["new_parent"][out:out + ks], ref["new_parent"])
+        out += ks
+    assert got["new_off"][B] == out
+    with pytest.raises(ev.EvictError):
+        ev.evict_select_prefix_coverage(None, _i32(off), _i32(par), _f32(q), B, T, 1.5, kmax, d["k_star"], d["keep"],
+                                        d["new_parent"], d["new_off"], d["est"])

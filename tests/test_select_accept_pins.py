@@ -206,3 +206,60 @@ def test_planted_mistakes_in_selection_are_caught(monkeypatch):
     assert (not ok) or not np.allclose(res["score"], ref)
     monkeypatch.setattr(orc, "node_scores", real)
     assert agrees()
+
+
+# ---------------------------------------------------------------- coverage rule (cost-agnostic ablation)
+def test_coverage_rule_on_a_chain_closed_form():
+    # chain with constant q = a: S_k = (1 - a^k) / (1 - a); smallest k with S_k / S_N >= rho
+    n, a = 24, 0.8
+    parent = np.arange(-1, n - 1)
+    q = np.full(n, a, np.float32)
+    q[0] = 1.0
+    for rho in (0.1, 0.35, 0.5, 0.77, 0.9, 0.97):
+        total = (1 - a ** n) / (1 - a)
+        want = next(k for k in range(1, n + 1) if (1 - a ** k) / (1 - a) / total >= rho + 1e-6)
+        lo = next(k for k in range(1, n + 1) if (1 - a ** k) / (1 - a) / total >= rho - 1e-6)
+        got = orc.select_prefix_coverage(parent, q, rho, n)["k_star"]
+        assert lo <= got <= want
+
+
+@pytest.mark.parametrize("seed", range(5))
+def test_coverage_rule_limits_and_monotonicity(seed):
+    g = synth.philox(seed, 55)
+    n = 40
+    parent = synth.tree_random_parents(n, 6, g)
+    q = synth.draft_probs(n, g)
+    assert orc.select_prefix_coverage(parent, q, 0.0, n)["k_star"] == 1
+    assert orc.select_prefix_coverage(parent, q, 1.0, n)["k_star"] == n   # every score here still moves the fp32 sum
+    assert orc.select_prefix_coverage(parent, q, 1.0, 7)["k_star"] == 7   # budget reached first
+    ks = [orc.select_prefix_coverage(parent, q, r, n)["k_star"] for r in np.linspace(0, 1, 21)]
+    assert all(a <= b for a, b in zip(ks, ks[1:]))
+    # same ranking and sums as the cost-aware rule; kept set is the top-k* by score, ancestor-closed
+    ref = orc.select_prefix(parent, q, np.ones(n + 1, np.float32), n)
+    r = orc.select_prefix_coverage(parent, q, 0.6, n)
+    assert np.array_equal(r["order"], ref["order"]) and np.array_equal(r["S"], ref["S"])
+    keep = set(int(v) for v in r["keep"])
+    assert all(parent[v] < 0 or int(parent[v]) in keep for v in keep)
+    # float64 definition with a margin
+    score = orc.node_scores(parent, q).astype(np.float64)
+    S64 = np.cumsum(np.sort(score)[::-1])
+    k64 = int(np.argmax(S64 / S64[-1] >= 0.6)) + 1
+    if abs(S64[k64 - 1] / S64[-1] - 0.6) > 1e-5 and (k64 < 2 or abs(S64[k64 - 2] / S64[-1] - 0.6) > 1e-5):
+        assert r["k_star"] == k64
+
+
+def test_synthetic_drafter_is_calibrated():
+    """The stand-in drafter's draws realise what Eq. 7-8 assume: over many draft trees the mean
+    accepted length (greedy walk on the drawn target ids) equals the mean of sum_v Score(v)."""
+    cfg = synth.CONFIGS["tiny"]
+    acc, est = [], []
+    for it in range(600):
+        d = synth.draft_iteration(cfg, 24, 3, it, 0.3, vocab=500)
+        par = d["parent"]
+        for u in range(len(par)):                      # siblings are parts of one distribution
+            assert d["q"][[c for c in range(len(par)) if par[c] == u]].sum() <= 1.0 + 1e-6
+        path, _ = orc.accept_path(par, d["tok"], d["target_next"])
+        acc.append(len(path))
+        est.append(float(orc.node_scores(par, d["q"]).astype(np.float64).sum()))
+    se = np.std(acc) / np.sqrt(len(acc))
+    assert abs(np.mean(acc) - np.mean(est)) < 4 * se
