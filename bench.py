@@ -340,6 +340,23 @@ def main():
             stage_ms[n] += t[n] / n_timed
     ev.evict_stage_timing(layer.ctx, False)
 
+    # The same layer calls without the stage events, between two events on the launch stream: what
+    # the stage events add per stage is (sum of stage times - this) / stages. (An event pair around
+    # nothing, like the empty "shared" stage, costs more than an event between two kernels does.)
+    def layer_only(i):
+        ev.evict_verify_layer(layer.ctx, weight_sets[i % len(weight_sets)], dc.tree_off, dc.parent, 1, N, dc.k_cache,
+                              dc.v_cache, dc.seq_stride, dc.head_stride, dc.ctx_len, L, dc.x, dc.out, dc.k_new,
+                              dc.v_new, None)
+    for i in range(5):
+        layer_only(i)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(n_timed):
+        layer_only(i)
+    e1.record()
+    torch.cuda.synchronize()
+    layer_ms = e0.elapsed_time(e1) / n_timed
+
     eb = 2
     expert_bytes = 3 * cfg.d * cfg.F * eb
     kv_bytes = 2 * L * cfg.Hkv * cfg.D * eb
@@ -348,9 +365,7 @@ def main():
     all_bytes = north_star_bytes + proj_bytes
     # algorithmic bytes of the dominant kernel per launch (shared experts ride in the same launch)
     gateup_bytes = (U + cfg.n_shared) * 2 * cfg.d * cfg.F * eb
-    # the "shared" stage launches nothing (shared experts are slots of the grouped GEMMs), so its
-    # event pair measures the event-to-event overhead, which is taken off the kernel's stage time
-    ev_overhead_ms = stage_ms["shared"]
+    ev_overhead_ms = max(sum(stage_ms.values()) - layer_ms, 0.0) / len(ev.STAGES)
     gateup_ms = max(stage_ms["gateup"] - ev_overhead_ms, 1e-6)
     gateup_s = gateup_ms * 1e-3
     achieved = gateup_bytes / gateup_s / 1e9
@@ -389,7 +404,7 @@ def main():
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                      "bytes_per_launch": gateup_bytes, "avg_launch_us": round(gateup_ms * 1e3, 2),
-                     "event_overhead_us": round(ev_overhead_ms * 1e3, 2)},
+                     "event_overhead_us": round(ev_overhead_ms * 1e3, 2), "layer_us": round(layer_ms * 1e3, 2)},
     }
 
     if not args.no_cpu:
