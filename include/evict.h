@@ -270,6 +270,7 @@ int evict_device_status(evict_ctx* ctx, int32_t* status_host, void* stream);
  *   "moe_down_kernel" 1: down projections with one 16-row strip per wavefront over the whole
  *                     contraction range (token operand staged in LDS); 0: contraction split
  *                     over the wavefronts of a workgroup like the other GEMMs
+ *   "moe_plain_loads" 1: expert weights with ordinary loads instead of non-temporal ones
  *   "attn_row_blocks" workgroups per (KV split, KV head) in the bf16 attention kernel, 0 = auto
  * Returns EVICT_E_INVALID for an unknown key or a value out of range. */
 int evict_tune(evict_ctx* ctx, const char* key, int value);

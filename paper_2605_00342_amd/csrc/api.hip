@@ -120,6 +120,7 @@ int evict_create(evict_ctx** out, const evict_model_desc* m, int max_tokens, int
   c.moe_grid = 2048;
   c.moe_prefetch = 1;
   c.moe_down_kernel = 1;
+  c.moe_plain_loads = 0;
   c.moe_chunk_gateup = 1;
   c.moe_chunk_down = 1;
   for (int cu : {4, 2}) if ((m->d / 16) % cu == 0) { c.moe_chunk_down = cu; break; }
@@ -247,7 +248,8 @@ static int check_layer_args(evict_ctx* ctx, const evict_layer_weights* w, const 
 static int verify_layer_impl(evict_ctx* ctx, const evict_layer_weights* w, const int32_t* tree_off, const int32_t* parent, int B,
                              int T, const void* k_cache, const void* v_cache, int64_t kv_seq_stride, int64_t kv_head_stride,
                              const int32_t* ctx_len, int max_ctx_host, const void* x_in, void* x_out, void* k_new, void* v_new,
-                             const evict_layer_aux* aux, int tree_ready, void* stream) {
+                             const evict_layer_aux* aux, int tree_ready, void* stream, int x_norm_ready = 0,
+                             const void* next_gain = nullptr) {
   const evict_model_desc& m = ctx->m;
   hipStream_t s = (hipStream_t)stream;
   const int eb = elem_bytes(m.dtype);
@@ -255,7 +257,9 @@ static int verify_layer_impl(evict_ctx* ctx, const evict_layer_weights* w, const
   const bool timing = ctx->timing != 0;
 #define EVICT_MARK(i_) do { if (timing) EVICT_HIP_CHECK(hipEventRecord(ctx->ev[i_], s)); } while (0)
   EVICT_MARK(0);
-  int rc = launch_prep(ctx, tree_off, parent, B, T, ctx_len, max_ctx_host, x_in, w->g_attn, tree_ready, s);
+  // (in a stack the previous layer's combine has already normalised this layer's input)
+  int rc = (tree_ready && x_norm_ready) ? EVICT_OK
+                                        : launch_prep(ctx, tree_off, parent, B, T, ctx_len, max_ctx_host, x_in, w->g_attn, tree_ready, s);
   if (rc) return rc;
   EVICT_MARK(1);
 
@@ -328,6 +332,7 @@ static int verify_layer_impl(evict_ctx* ctx, const evict_layer_weights* w, const
     a.out0 = ctx->act;
     a.ldo = m.F;
     a.prefetch = ctx->moe_prefetch;
+    a.plain_loads = ctx->moe_plain_loads;
     a.chunk_units = ctx->moe_chunk_gateup;
     rc = launch_gemm(m.dtype, EPI_SWIGLU, a, nt_exp, ctx->moe_grid, s);
     if (rc) return rc;
@@ -351,13 +356,14 @@ static int verify_layer_impl(evict_ctx* ctx, const evict_layer_weights* w, const
     a.chunk_units = ctx->moe_chunk_down;
     a.prefetch = ctx->moe_prefetch;
     a.wave_strip = ctx->moe_down_kernel;
+    a.plain_loads = ctx->moe_plain_loads;
     rc = launch_gemm(m.dtype, EPI_F32, a, nt_exp, ctx->moe_grid, s);
     if (rc) return rc;
   }
   EVICT_MARK(8);
   // (the always-on shared experts are extra slots of the work list: same two launches)
   EVICT_MARK(9);
-  rc = launch_combine(ctx, T, x_out, s);
+  rc = launch_combine(ctx, T, x_out, next_gain, s);
   if (rc) return rc;
   EVICT_MARK(10);
   if (timing) ctx->timed_once = 1;
@@ -392,7 +398,8 @@ int evict_verify_stack(evict_ctx* ctx, const evict_layer_weights* layers, int n_
                               max_ctx_host, in, out, k_new[l], v_new[l]);
     if (rc) return rc;
     rc = verify_layer_impl(ctx, layers + l, tree_off, parent, B, T, kc, vc, kv_seq_stride, kv_head_stride, ctx_len,
-                           max_ctx_host, in, out, k_new[l], v_new[l], nullptr, l > 0, stream);
+                           max_ctx_host, in, out, k_new[l], v_new[l], nullptr, l > 0, stream, l > 0,
+                           l + 1 < n_layers ? layers[l + 1].g_attn : nullptr);
     if (rc) return rc;
   }
   return EVICT_OK;
@@ -493,6 +500,9 @@ int evict_tune(evict_ctx* ctx, const char* key, int value) {
   } else if (!strcmp(key, "moe_chunk_down")) {
     EVICT_REQUIRE(value >= 1 && (ctx->m.d / 16) % value == 0, EVICT_E_INVALID, "evict_tune: moe_chunk_down=%d must divide d/16", value);
     ctx->moe_chunk_down = value;
+  } else if (!strcmp(key, "moe_plain_loads")) {
+    EVICT_REQUIRE(value == 0 || value == 1, EVICT_E_INVALID, "evict_tune: moe_plain_loads must be 0 or 1");
+    ctx->moe_plain_loads = value;
   } else if (!strcmp(key, "moe_down_kernel")) {
     EVICT_REQUIRE(value == 0 || value == 1, EVICT_E_INVALID, "evict_tune: moe_down_kernel must be 0 or 1");
     ctx->moe_down_kernel = value;

@@ -47,6 +47,7 @@ struct GemmArgs {
   int dense_tiles;       // dense: workgroups per strip, each taking 16*NT tokens
   int prefetch;          // host-side choice of the kernel variant (weight-load stages), 0 = default
   int wave_strip;        // host-side: grouped fp32-output GEMM may use gemm_wave_strip_kernel
+  int plain_loads;       // 1: never use non-temporal weight loads (measurement knob)
   void* out0;            // QKV: q; RESID: h; SWIGLU: act; F32: y; ARGMAX: best value per (strip, token)
   void* out1;            // QKV: k_new; ARGMAX: row index of the best value per (strip, token)
   void* out2;            // QKV: v_new
@@ -84,7 +85,7 @@ __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(NT
     const int nitems = nunits * SPU;
     int p0 = 0, ntok = a.T;
     int tok_early = 0;  // token id from the work record (grouped, first kWorkToks positions)
-    bool once = kStreamOnce;  // weights read by this workgroup only: keep them out of the caches' way
+    bool once = kStreamOnce && !a.plain_loads;  // weights read by this workgroup only: keep them out of the caches' way
     const u32x4* wbase = a.W;
     if (a.grouped) {
       // one hop: the record (scalar) and this lane's token id (vector) are fetched together
@@ -93,7 +94,7 @@ __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(NT
       tok_early = rec->tok[lc < kWorkToks ? lc : kWorkToks - 1];  // entries past ntok repeat the last token
       p0 = rec->p0;
       ntok = rec->ntok;
-      once = kStreamOnce && (rec->pad & 0xFFFF) == 1;
+      once = kStreamOnce && !a.plain_loads && (rec->pad & 0xFFFF) == 1;
       const int ex = rec->expert;
       wbase = ex < a.n_routed ? a.W + (long long)ex * a.group_stride : a.W_shared + (long long)(ex - a.n_routed) * a.group_stride;
     }
@@ -335,7 +336,7 @@ __global__ __launch_bounds__(WS * 64) __attribute__((amdgpu_waves_per_eu(4))) vo
     const int slot = chunk / cpg, strip = (chunk - slot * cpg) * WS + w;
     const WorkRec* rec = a.work + slot;
     const int p0 = rec->p0, ntok = rec->ntok, ex = rec->expert;
-    const bool once = (rec->pad & 0xFFFF) == 1;  // single token tile: nobody else reads these weights
+    const bool once = !a.plain_loads && (rec->pad & 0xFFFF) == 1;  // single token tile: nobody else reads these weights
     const u32x4* wbase = ex < a.n_routed ? a.W + (long long)ex * a.group_stride
                                          : a.W_shared + (long long)(ex - a.n_routed) * a.group_stride;
     // token operand first, weights behind it: the in-order load counter then lets the operand

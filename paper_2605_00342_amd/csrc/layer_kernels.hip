@@ -883,34 +883,107 @@ __global__ __launch_bounds__(256) void argmax_reduce_kernel(const float* __restr
 }
 
 // ------------------------------------------------------------------------------------
-// un-permute + weighted combine + residual (+ shared experts), fixed slot order
+// un-permute + weighted combine + residual (+ shared experts), fixed slot order; one workgroup
+// per token. Optionally also the next layer's pre-attention RMSNorm of the row just produced
+// (layer stacks: saves that layer's norm launch). The row is cut into 16-byte chunks exactly as
+// prep_kernel cuts it, and the norm is the same arithmetic in the same order, so a stack gives
+// bit-identical results to the layers called one by one.
 // ------------------------------------------------------------------------------------
 template <typename ST>
-__global__ __launch_bounds__(512) void combine_kernel(const void* __restrict__ h, const float* __restrict__ y,
+__global__ __launch_bounds__(256) void combine_kernel(const void* __restrict__ h, const float* __restrict__ y,
                                                       const float* __restrict__ w, const int32_t* __restrict__ inv,
                                                       int k, int d, const float* __restrict__ y_sh, int n_shared, int T,
-                                                      void* __restrict__ out) {
+                                                      void* __restrict__ out, const void* __restrict__ next_gain, float eps,
+                                                      void* __restrict__ x_norm) {
+  constexpr int EB = ST::kBytes;
+  constexpr int CE = 16 / EB;
+  constexpr int MAXC = 4;  // 16-byte chunks of the row per thread (d <= 256*CE*MAXC, as in prep_kernel)
   __shared__ float s_w[64];
   __shared__ int s_inv[64];
-  const int t = blockIdx.x;
-  if (threadIdx.x < k) {
-    s_w[threadIdx.x] = w[(size_t)t * k + threadIdx.x];
-    s_inv[threadIdx.x] = inv[(size_t)t * k + threadIdx.x];
+  __shared__ float s_red[4];
+  const int t = blockIdx.x, tid = threadIdx.x;
+  if (tid < k) {
+    s_w[tid] = w[(size_t)t * k + tid];
+    s_inv[tid] = inv[(size_t)t * k + tid];
   }
   __syncthreads();
-  for (int c = threadIdx.x * 4; c < d; c += 512 * 4) {
-    f32x4 acc = load4<ST>(h, (size_t)t * d + c);
-    for (int j0 = 0; j0 < k; j0 += 8) {
-      f32x4 yv[8];
+  u32x4 raw[MAXC];
 #pragma unroll
-      for (int j = 0; j < 8; ++j)
-        if (j0 + j < k) yv[j] = *reinterpret_cast<const f32x4*>(y + (size_t)s_inv[j0 + j] * d + c);
+  for (int i = 0; i < MAXC; ++i) {
+    const int c = (tid + 256 * i) * CE;
+    raw[i] = u32x4{0, 0, 0, 0};
+    if (c < d) {
+      f32x4 acc[CE / 4];
 #pragma unroll
-      for (int j = 0; j < 8; ++j)
-        if (j0 + j < k) acc += s_w[j0 + j] * yv[j];  // slot order j = 0..k-1
+      for (int q = 0; q < CE / 4; ++q) acc[q] = load4<ST>(h, (size_t)t * d + c + 4 * q);
+      for (int j0 = 0; j0 < k; j0 += 8) {  // eight experts' rows requested together, summed in slot order
+        f32x4 yv[8][CE / 4];
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+          if (j0 + j < k) {
+            const float* yr = y + (size_t)s_inv[j0 + j] * d + c;
+#pragma unroll
+            for (int q = 0; q < CE / 4; ++q) yv[j][q] = *reinterpret_cast<const f32x4*>(yr + 4 * q);
+          }
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+          if (j0 + j < k) {
+#pragma unroll
+            for (int q = 0; q < CE / 4; ++q) acc[q] += s_w[j0 + j] * yv[j][q];
+          }
+      }
+      for (int sh = 0; sh < n_shared; ++sh) {
+        const float* yr = y_sh + ((size_t)sh * T + t) * d + c;
+#pragma unroll
+        for (int q = 0; q < CE / 4; ++q) acc[q] += *reinterpret_cast<const f32x4*>(yr + 4 * q);
+      }
+      if (EB == 2) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+          raw[i][u] = (uint32_t)f32_to_bf16(acc[u >> 1][(2 * u) & 3]) | ((uint32_t)f32_to_bf16(acc[u >> 1][(2 * u + 1) & 3]) << 16);
+      } else {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) raw[i][u] = __float_as_uint(acc[0][u]);
+      }
+      *reinterpret_cast<u32x4*>((char*)out + ((size_t)t * d + c) * EB) = raw[i];
     }
-    for (int s = 0; s < n_shared; ++s) acc += *reinterpret_cast<const f32x4*>(y_sh + ((size_t)s * T + t) * d + c);
-    store4<ST>(out, (size_t)t * d + c, acc);
+  }
+  if (!next_gain) return;
+  float ss = 0.0f;
+#pragma unroll
+  for (int kk = 0; kk < MAXC; ++kk)
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (EB == 2) {
+        const float a = __uint_as_float(raw[kk][u] << 16), bb = __uint_as_float(raw[kk][u] & 0xFFFF0000u);
+        ss += a * a + bb * bb;
+      } else {
+        const float a = __uint_as_float(raw[kk][u]);
+        ss += a * a;
+      }
+    }
+  ss = wave_sum(ss);
+  if ((tid & 63) == 0) s_red[tid >> 6] = ss;
+  __syncthreads();
+  const float rinv = 1.0f / sqrtf((s_red[0] + s_red[1] + s_red[2] + s_red[3]) / (float)d + eps);
+#pragma unroll
+  for (int kk = 0; kk < MAXC; ++kk) {
+    const int c = (tid + 256 * kk) * CE;
+    if (c < d) {
+      const u32x4 graw = *reinterpret_cast<const u32x4*>((const char*)next_gain + (size_t)c * EB);
+      u32x4 packed;
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (EB == 2) {
+          const float a = __uint_as_float(raw[kk][u] << 16) * rinv * __uint_as_float(graw[u] << 16);
+          const float bb = __uint_as_float(raw[kk][u] & 0xFFFF0000u) * rinv * __uint_as_float(graw[u] & 0xFFFF0000u);
+          packed[u] = (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(bb) << 16);
+        } else {
+          packed[u] = __float_as_uint(__uint_as_float(raw[kk][u]) * rinv * __uint_as_float(graw[u]));
+        }
+      }
+      *reinterpret_cast<u32x4*>((char*)x_norm + ((size_t)t * d + c) * EB) = packed;
+    }
   }
 }
 
@@ -1151,14 +1224,14 @@ int launch_argmax_reduce(const float* val, const int32_t* idx, int nstrips, int 
   return launch_status("argmax_reduce_kernel");
 }
 
-int launch_combine(const evict_ctx* c, int T, void* out, hipStream_t s) {
+int launch_combine(const evict_ctx* c, int T, void* out, const void* next_gain, hipStream_t s) {
   const evict_model_desc& m = c->m;
   if (m.dtype == EVICT_BF16)
-    hipLaunchKernelGGL(combine_kernel<BF16>, dim3(T), dim3(512), 0, s, c->h, c->y, c->topk_w, c->inv, m.k, m.d,
-                       c->y + (size_t)T * m.k * m.d, m.n_shared, T, out);
+    hipLaunchKernelGGL(combine_kernel<BF16>, dim3(T), dim3(256), 0, s, c->h, c->y, c->topk_w, c->inv, m.k, m.d,
+                       c->y + (size_t)T * m.k * m.d, m.n_shared, T, out, next_gain, m.rms_eps, c->x_norm);
   else
-    hipLaunchKernelGGL(combine_kernel<F32>, dim3(T), dim3(512), 0, s, c->h, c->y, c->topk_w, c->inv, m.k, m.d,
-                       c->y + (size_t)T * m.k * m.d, m.n_shared, T, out);
+    hipLaunchKernelGGL(combine_kernel<F32>, dim3(T), dim3(256), 0, s, c->h, c->y, c->topk_w, c->inv, m.k, m.d,
+                       c->y + (size_t)T * m.k * m.d, m.n_shared, T, out, next_gain, m.rms_eps, c->x_norm);
   return launch_status("combine_kernel");
 }
 

@@ -21,6 +21,6 @@ int launch_router(const evict_ctx* c, const void* gain, const void* wg, int T, c
 int launch_topk_union(const evict_ctx* c, int T, const evict_layer_aux* aux, hipStream_t s);
 int launch_argmax_reduce(const float* val, const int32_t* idx, int nstrips, int ld, int T, int32_t* next, float* best_out,
                          hipStream_t s);
-int launch_combine(const evict_ctx* c, int T, void* out, hipStream_t s);
+int launch_combine(const evict_ctx* c, int T, void* out, const void* next_gain, hipStream_t s);
 
 }  // namespace evict
