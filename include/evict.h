@@ -246,6 +246,15 @@ int evict_kv_commit(evict_ctx* ctx, int dtype, int Hkv, int D, const void* k_new
                     void* k_cache, void* v_cache, int64_t kv_seq_stride, int64_t kv_head_stride,
                     const int32_t* ctx_len, int capacity, int32_t* ctx_len_out, int B, void* stream);
 
+/* The same commit for all layers of a stack in one call (one launch per 64 layers): k_new,
+ * v_new, k_caches, v_caches are [host] arrays of n_layers [dev] pointers as in
+ * evict_verify_stack; the caches share strides and capacity. */
+int evict_kv_commit_stack(evict_ctx* ctx, int dtype, int Hkv, int D, const void* const* k_new,
+                          const void* const* v_new, int n_layers, const int32_t* tree_off, const int32_t* path,
+                          int path_stride, const int32_t* path_len, void* const* k_caches, void* const* v_caches,
+                          int64_t kv_seq_stride, int64_t kv_head_stride, const int32_t* ctx_len, int capacity,
+                          int32_t* ctx_len_out, int B, void* stream);
+
 /* Gather rows of a [T, row_bytes] array by the kept node lists of evict_select_prefix:
  * dst row new_tree_off[b] + r = src row tree_off[b] + keep[new_tree_off[b] + r].
  * row_bytes % 4 == 0. Grid is sized for T rows; rows beyond new_tree_off[B] are untouched. */

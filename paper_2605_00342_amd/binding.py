@@ -17,7 +17,7 @@ __all__ = [
     "evict_select_prefix", "evict_gather_rows", "evict_validate_trees_host", "evict_device_status",
     "evict_stage_timing", "evict_stage_times", "evict_probe_read", "evict_probe_copy", "evict_tune", "evict_verify_stack", "evict_lm_head_argmax",
     "evict_profile_cost", "evict_graph_begin", "evict_graph_end", "evict_graph_launch", "evict_graph_destroy",
-    "evict_lm_head_logits", "evict_accept_path_sampled", "evict_kv_commit", "evict_select_prefix_coverage",
+    "evict_lm_head_logits", "evict_accept_path_sampled", "evict_kv_commit", "evict_select_prefix_coverage", "evict_kv_commit_stack",
     "STAGES", "EXPORTS",
 ]
 
@@ -31,7 +31,7 @@ EXPORTS = [
     "evict_select_prefix", "evict_gather_rows", "evict_validate_trees_host", "evict_device_status",
     "evict_stage_timing", "evict_stage_times", "evict_probe_read", "evict_probe_copy", "evict_tune", "evict_verify_stack", "evict_lm_head_argmax",
     "evict_profile_cost", "evict_graph_begin", "evict_graph_end", "evict_graph_launch", "evict_graph_destroy",
-    "evict_lm_head_logits", "evict_accept_path_sampled", "evict_kv_commit", "evict_select_prefix_coverage",
+    "evict_lm_head_logits", "evict_accept_path_sampled", "evict_kv_commit", "evict_select_prefix_coverage", "evict_kv_commit_stack",
 ]
 STAGES = ["prep", "qkv", "attention", "oproj", "router", "union", "gateup", "down", "shared", "combine"]
 
@@ -107,6 +107,8 @@ def load():
     lib.evict_lm_head_logits.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp]
     lib.evict_accept_path_sampled.argtypes = [vp, vp, vp, vp, vp, i32, C.c_float, vp, vp, i32, i32, vp, i32, vp, vp, vp]
     lib.evict_kv_commit.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, i32, vp, vp, vp, i64, i64, vp, i32, vp, i32, vp]
+    lib.evict_kv_commit_stack.argtypes = [vp, i32, i32, i32, C.POINTER(vp), C.POINTER(vp), i32, vp, vp, i32, vp, C.POINTER(vp),
+                                          C.POINTER(vp), i64, i64, vp, i32, vp, i32, vp]
     lib.evict_graph_begin.argtypes = [vp, vp]
     lib.evict_graph_end.argtypes = [vp, vp, C.POINTER(vp)]
     lib.evict_graph_launch.argtypes = [vp, vp]
@@ -248,6 +250,14 @@ def evict_kv_commit(ctx, dtype, Hkv, D, k_new, v_new, tree_off, path, path_strid
     _check(load().evict_kv_commit(ctx, dtype, Hkv, D, _p(k_new), _p(v_new), _p(tree_off), _p(path), path_stride,
                                   _p(path_len), _p(k_cache), _p(v_cache), kv_seq_stride, kv_head_stride, _p(ctx_len),
                                   capacity, _p(ctx_len_out), B, _stream()))
+
+
+def evict_kv_commit_stack(ctx, dtype, Hkv, D, k_new, v_new, tree_off, path, path_stride, path_len, k_caches, v_caches,
+                          kv_seq_stride, kv_head_stride, ctx_len, capacity, ctx_len_out, B) -> None:
+    """k_new, v_new, k_caches, v_caches: lists of device tensors, one per layer."""
+    _check(load().evict_kv_commit_stack(ctx, dtype, Hkv, D, _ptr_array(k_new), _ptr_array(v_new), len(k_new), _p(tree_off),
+                                        _p(path), path_stride, _p(path_len), _ptr_array(k_caches), _ptr_array(v_caches),
+                                        kv_seq_stride, kv_head_stride, _p(ctx_len), capacity, _p(ctx_len_out), B, _stream()))
 
 
 def evict_graph_begin(ctx) -> None:

@@ -520,20 +520,31 @@ __global__ void gather_rows_kernel(const uint32_t* __restrict__ src, uint32_t* _
 // its key was rotated at position ctx_len[b] + j) becomes cache row ctx_len[b] + j of every KV
 // head. Grid (path position, sequence); rows are copied as 4-byte words. Rows that would fall
 // past the cache capacity are dropped and the new length is clamped.
+constexpr int kCommitLayers = 64;  // layers per launch (their pointers travel as a kernel argument)
+struct KvLayerPtrs {
+  const uint32_t* k_new[kCommitLayers];
+  const uint32_t* v_new[kCommitLayers];
+  uint32_t* k_cache[kCommitLayers];
+  uint32_t* v_cache[kCommitLayers];
+};
+
 __global__ __launch_bounds__(256) void kv_commit_kernel(
-    const uint32_t* __restrict__ k_new, const uint32_t* __restrict__ v_new, int Hkv, int head_words,
+    const KvLayerPtrs lp, int Hkv, int head_words,
     const int32_t* __restrict__ tree_off, const int32_t* __restrict__ path, int path_stride,
-    const int32_t* __restrict__ path_len, uint32_t* __restrict__ k_cache, uint32_t* __restrict__ v_cache,
-    long long seq_words, long long head_stride_words, const int32_t* __restrict__ ctx_len, int capacity,
-    int32_t* __restrict__ ctx_len_out, int32_t* __restrict__ status) {
-  const int j = blockIdx.x, b = blockIdx.y;
+    const int32_t* __restrict__ path_len, long long seq_words, long long head_stride_words,
+    const int32_t* __restrict__ ctx_len, int capacity, int32_t* __restrict__ ctx_len_out, int32_t* __restrict__ status) {
+  const int j = blockIdx.x, b = blockIdx.y, layer = blockIdx.z;
+  const uint32_t* __restrict__ k_new = lp.k_new[layer];
+  const uint32_t* __restrict__ v_new = lp.v_new[layer];
+  uint32_t* __restrict__ k_cache = lp.k_cache[layer];
+  uint32_t* __restrict__ v_cache = lp.v_cache[layer];
   int len = path_len[b];
   len = len < 0 ? 0 : (len > path_stride ? path_stride : len);
   int L = ctx_len[b];
   const bool badL = L < 0 || L > capacity;
   L = L < 0 ? 0 : (L > capacity ? capacity : L);
   const int room = capacity - L;
-  if (j == 0 && threadIdx.x == 0) {
+  if (j == 0 && layer == 0 && threadIdx.x == 0) {
     ctx_len_out[b] = L + (len < room ? len : room);
     if (status && (badL || len > room)) atomicOr(status, ST_BAD_CTXLEN);
   }
@@ -713,27 +724,58 @@ int evict_accept_path_sampled(evict_ctx* ctx, const int32_t* tree_off, const int
   return launch_status("accept_sampled_kernel");
 }
 
+static int kv_commit_impl(const char* who, evict_ctx* ctx, int dtype, int Hkv, int D, const void* const* k_new,
+                          const void* const* v_new, int n_layers, const int32_t* tree_off, const int32_t* path, int path_stride,
+                          const int32_t* path_len, void* const* k_caches, void* const* v_caches, int64_t kv_seq_stride,
+                          int64_t kv_head_stride, const int32_t* ctx_len, int capacity, int32_t* ctx_len_out, int B,
+                          void* stream) {
+  EVICT_REQUIRE(k_new && v_new && tree_off && path && path_len && k_caches && v_caches && ctx_len && ctx_len_out,
+                EVICT_E_INVALID, "%s: null pointer argument", who);
+  EVICT_REQUIRE(dtype == EVICT_F32 || dtype == EVICT_BF16, EVICT_E_INVALID, "%s: unknown dtype %d", who, dtype);
+  EVICT_REQUIRE(n_layers >= 1, EVICT_E_INVALID, "%s: n_layers=%d", who, n_layers);
+  EVICT_REQUIRE(B >= 1 && B <= 65535 && Hkv >= 1 && D >= 1 && path_stride >= 1 && path_stride <= EVICT_MAX_SELECT_NODES,
+                EVICT_E_INVALID, "%s: B, Hkv, D, path_stride out of range", who);
+  const int eb = dtype == EVICT_BF16 ? 2 : 4;
+  EVICT_REQUIRE((D * eb) % 4 == 0, EVICT_E_INVALID, "%s: a head row must be a multiple of 4 bytes", who);
+  EVICT_REQUIRE(capacity >= 1 && kv_head_stride >= (int64_t)capacity * D && (kv_head_stride * eb) % 4 == 0 &&
+                    (kv_seq_stride * eb) % 4 == 0 && (B == 1 || kv_seq_stride >= kv_head_stride * Hkv),
+                EVICT_E_INVALID, "%s: cache strides do not hold capacity=%d rows per head", who, capacity);
+  EVICT_REQUIRE(ctx_len_out != ctx_len, EVICT_E_INVALID, "%s: ctx_len_out must not alias ctx_len", who);
+  for (int l = 0; l < n_layers; ++l)
+    EVICT_REQUIRE(k_new[l] && v_new[l] && k_caches[l] && v_caches[l], EVICT_E_INVALID, "%s: null pointer for layer %d", who, l);
+  const int head_words = D * eb / 4;
+  for (int l0 = 0; l0 < n_layers; l0 += kCommitLayers) {
+    const int nl = n_layers - l0 < kCommitLayers ? n_layers - l0 : kCommitLayers;
+    KvLayerPtrs lp = {};
+    for (int l = 0; l < nl; ++l) {
+      lp.k_new[l] = (const uint32_t*)k_new[l0 + l];
+      lp.v_new[l] = (const uint32_t*)v_new[l0 + l];
+      lp.k_cache[l] = (uint32_t*)k_caches[l0 + l];
+      lp.v_cache[l] = (uint32_t*)v_caches[l0 + l];
+    }
+    hipLaunchKernelGGL(kv_commit_kernel, dim3(path_stride, B, nl), dim3(256), 0, (hipStream_t)stream, lp, Hkv, head_words,
+                       tree_off, path, path_stride, path_len, (long long)(kv_seq_stride * eb / 4),
+                       (long long)(kv_head_stride * eb / 4), ctx_len, capacity, ctx_len_out, ctx ? ctx->status : nullptr);
+    int rc = launch_status("kv_commit_kernel");
+    if (rc) return rc;
+  }
+  return EVICT_OK;
+}
+
 int evict_kv_commit(evict_ctx* ctx, int dtype, int Hkv, int D, const void* k_new, const void* v_new, const int32_t* tree_off,
                     const int32_t* path, int path_stride, const int32_t* path_len, void* k_cache, void* v_cache,
                     int64_t kv_seq_stride, int64_t kv_head_stride, const int32_t* ctx_len, int capacity, int32_t* ctx_len_out,
                     int B, void* stream) {
-  EVICT_REQUIRE(k_new && v_new && tree_off && path && path_len && k_cache && v_cache && ctx_len && ctx_len_out,
-                EVICT_E_INVALID, "evict_kv_commit: null pointer argument");
-  EVICT_REQUIRE(dtype == EVICT_F32 || dtype == EVICT_BF16, EVICT_E_INVALID, "evict_kv_commit: unknown dtype %d", dtype);
-  EVICT_REQUIRE(B >= 1 && B <= 65535 && Hkv >= 1 && D >= 1 && path_stride >= 1 && path_stride <= EVICT_MAX_SELECT_NODES,
-                EVICT_E_INVALID, "evict_kv_commit: B, Hkv, D, path_stride out of range");
-  const int eb = dtype == EVICT_BF16 ? 2 : 4;
-  EVICT_REQUIRE((D * eb) % 4 == 0, EVICT_E_INVALID, "evict_kv_commit: a head row must be a multiple of 4 bytes");
-  EVICT_REQUIRE(capacity >= 1 && kv_head_stride >= (int64_t)capacity * D && (kv_head_stride * eb) % 4 == 0 &&
-                    (kv_seq_stride * eb) % 4 == 0 && (B == 1 || kv_seq_stride >= kv_head_stride * Hkv),
-                EVICT_E_INVALID, "evict_kv_commit: cache strides do not hold capacity=%d rows per head", capacity);
-  EVICT_REQUIRE(ctx_len_out != ctx_len, EVICT_E_INVALID, "evict_kv_commit: ctx_len_out must not alias ctx_len");
-  const int head_words = D * eb / 4;
-  hipLaunchKernelGGL(kv_commit_kernel, dim3(path_stride, B), dim3(256), 0, (hipStream_t)stream, (const uint32_t*)k_new,
-                     (const uint32_t*)v_new, Hkv, head_words, tree_off, path, path_stride, path_len, (uint32_t*)k_cache,
-                     (uint32_t*)v_cache, (long long)(kv_seq_stride * eb / 4), (long long)(kv_head_stride * eb / 4), ctx_len,
-                     capacity, ctx_len_out, ctx ? ctx->status : nullptr);
-  return launch_status("kv_commit_kernel");
+  return kv_commit_impl("evict_kv_commit", ctx, dtype, Hkv, D, &k_new, &v_new, 1, tree_off, path, path_stride, path_len,
+                        &k_cache, &v_cache, kv_seq_stride, kv_head_stride, ctx_len, capacity, ctx_len_out, B, stream);
+}
+
+int evict_kv_commit_stack(evict_ctx* ctx, int dtype, int Hkv, int D, const void* const* k_new, const void* const* v_new,
+                          int n_layers, const int32_t* tree_off, const int32_t* path, int path_stride, const int32_t* path_len,
+                          void* const* k_caches, void* const* v_caches, int64_t kv_seq_stride, int64_t kv_head_stride,
+                          const int32_t* ctx_len, int capacity, int32_t* ctx_len_out, int B, void* stream) {
+  return kv_commit_impl("evict_kv_commit_stack", ctx, dtype, Hkv, D, k_new, v_new, n_layers, tree_off, path, path_stride,
+                        path_len, k_caches, v_caches, kv_seq_stride, kv_head_stride, ctx_len, capacity, ctx_len_out, B, stream);
 }
 
 }  // extern "C"

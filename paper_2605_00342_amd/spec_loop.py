@@ -99,10 +99,9 @@ class SpecLoop:
         if d.target_next is None:
             tn = self.next
         ev.evict_accept_path(None, off, par, tok, tn, 1, self.path, self.n_max, self.path_len, self.bonus)
-        for l in range(len(self.layers)):
-            ev.evict_kv_commit(self.ctx, self.dtype_code, cfg.Hkv, cfg.D, self.k_new[l], self.v_new[l], off, self.path,
-                               self.n_max, self.path_len, self.kc[l], self.vc[l], self.seq_stride, self.head_stride, cl_in,
-                               self.capacity, cl_out, 1)
+        ev.evict_kv_commit_stack(self.ctx, self.dtype_code, cfg.Hkv, cfg.D, self.k_new, self.v_new, off, self.path, self.n_max,
+                                 self.path_len, self.kc, self.vc, self.seq_stride, self.head_stride, cl_in, self.capacity,
+                                 cl_out, 1)
         plen = int(self.path_len.item())
         self.cur ^= 1
         self.ctx_len_host = min(self.ctx_len_host + plen, self.capacity)
