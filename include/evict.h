@@ -59,6 +59,8 @@ typedef struct evict_model_desc {
   float rms_eps;      /* RMSNorm epsilon */
   float rope_theta;   /* rotary base; 0 disables the rotation */
   int32_t vocab;      /* vocabulary size for evict_lm_head_argmax (multiple of 16), 0 = no LM head */
+  int32_t router_norm; /* weights of the k selected scores (Sec. 2.2): 0 softmax over them; 1 sigmoid of
+                        * each, divided by the sum of the k sigmoids */
 } evict_model_desc;
 
 /* Device pointers to one layer's weights. Matrices are in the packed streaming layout

@@ -130,10 +130,12 @@ def tree_attention(q, k_new, v_new, K, V, anc):
     return out
 
 
-def router_topk(h_norm, wg, k):
+def router_topk(h_norm, wg, k, norm="softmax"):
     """Eq. 4: scores W_g h, indices of the k largest (ordered by value descending, index
-    ascending on equal values), selected scores normalised by softmax. Scores are formed in
-    float64 and stored as float32; the selection is taken on the float32 values."""
+    ascending on equal values), selected scores normalised into weights: by softmax over the
+    selected scores, or ("sigmoid", the other choice Sec. 2.2 names) by the sigmoid of each
+    divided by the sum of the k sigmoids. Scores are formed in float64 and stored as float32;
+    the selection is taken on the float32 values."""
     logits = (np.asarray(h_norm, F64) @ np.asarray(wg, F64).T).astype(F32)
     n, E = logits.shape
     idx = np.zeros((n, k), dtype=np.int32)
@@ -142,7 +144,7 @@ def router_topk(h_norm, wg, k):
         order = sorted(range(E), key=lambda e: (-float(logits[t, e]), e))[:k]
         idx[t] = order
         s = logits[t, order].astype(F64)
-        p = np.exp(s - s.max())
+        p = 1.0 / (1.0 + np.exp(-s)) if norm == "sigmoid" else np.exp(s - s.max())
         w[t] = (p / p.sum()).astype(F32)
     return idx, w, logits
 
@@ -268,7 +270,7 @@ def moe_block(cfg, W, h, act=None):
 
 def moe_from_normed(cfg, W, h, hn, act=None):
     act = act or cfg.dtype
-    idx, w, logits = router_topk(hn, W["wg"], cfg.k)
+    idx, w, logits = router_topk(hn, W["wg"], cfg.k, getattr(cfg, "router_norm", "softmax"))
     un = expert_union(idx, cfg.E)
     y = moe_experts(hn, idx, W, act)
     shared = None

@@ -45,7 +45,7 @@ class EvictError(RuntimeError):
 class ModelDesc(C.Structure):
     _fields_ = [("dtype", C.c_int32), ("d", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32), ("D", C.c_int32),
                 ("E", C.c_int32), ("k", C.c_int32), ("F", C.c_int32), ("n_shared", C.c_int32),
-                ("rms_eps", C.c_float), ("rope_theta", C.c_float), ("vocab", C.c_int32)]
+                ("rms_eps", C.c_float), ("rope_theta", C.c_float), ("vocab", C.c_int32), ("router_norm", C.c_int32)]
 
 
 class LayerWeights(C.Structure):

@@ -23,6 +23,7 @@ int check_model(const evict_model_desc* m) {
   EVICT_REQUIRE(m->Hq % m->Hkv == 0, EVICT_E_INVALID, "Hq=%d is not a multiple of Hkv=%d", m->Hq, m->Hkv);
   EVICT_REQUIRE(m->k <= m->E, EVICT_E_INVALID, "k=%d exceeds E=%d", m->k, m->E);
   EVICT_REQUIRE(m->rms_eps >= 0.0f && m->rope_theta >= 0.0f, EVICT_E_INVALID, "rms_eps and rope_theta must be >= 0");
+  EVICT_REQUIRE(m->router_norm == 0 || m->router_norm == 1, EVICT_E_INVALID, "router_norm=%d (0 softmax, 1 sigmoid)", m->router_norm);
   const int eb = elem_bytes(m->dtype);
   EVICT_REQUIRE(m->D == 64 || m->D == 128, EVICT_E_UNSUPPORTED, "head dimension %d (supported: 64, 128)", m->D);
   EVICT_REQUIRE(m->d % 16 == 0 && m->F % 16 == 0 && (m->d * eb) % 64 == 0 && (m->F * eb) % 64 == 0,

@@ -684,14 +684,14 @@ __global__ __launch_bounds__(kRouterThreads) void router_logits_kernel(
 
 // ------------------------------------------------------------------------------------
 // router, part 2: TopK of every token's scores with the selected scores normalised by softmax
-// (Eq. 4); 16 tokens per workgroup, one per wavefront.
+// or by sigmoid (Eq. 4 and the sentence after it); 16 tokens per workgroup, one per wavefront.
 // Selection: one wavefront per token; scores become unsigned keys monotone in the float value,
 // each of the k picks is a wavefront maximum (DPP row operations) followed by ballots that find
 // the lowest expert index holding it, so equal scores go to the lower index.
 // ------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kRouterThreads) void topk_kernel(
-    const float* __restrict__ logits, int T, int E, int k, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
-    int32_t* __restrict__ aux_idx, float* __restrict__ aux_w) {
+    const float* __restrict__ logits, int T, int E, int k, int norm, int32_t* __restrict__ topk_idx,
+    float* __restrict__ topk_w, int32_t* __restrict__ aux_idx, float* __restrict__ aux_w) {
   extern __shared__ __attribute__((aligned(16))) int s_all[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -736,7 +736,9 @@ __global__ __launch_bounds__(kRouterThreads) void topk_kernel(
     }
   }
   const float first = s_sel[0];
-  const float ex = lane < k ? __expf(s_sel[lane < k ? lane : 0] - first) : 0.0f;
+  const float mine = s_sel[lane < k ? lane : 0];
+  // selected scores -> weights: softmax, or sigmoid divided by the sum of the selected sigmoids
+  const float ex = lane < k ? (norm ? 1.0f / (1.0f + __expf(-mine)) : __expf(mine - first)) : 0.0f;
   const float denom = wave_sum(ex);
   if (lane < k) {
     const float wv = ex / denom;
@@ -749,7 +751,7 @@ __global__ __launch_bounds__(kRouterThreads) void topk_kernel(
 // selection rule as topk_kernel, without the LDS round trips. Lane j ends up with the j-th pick.
 // Returns the expert index picked at position `lane` (for lane < k) and its softmax weight.
 template <int NR>
-__device__ __forceinline__ void topk_wave_regs(const float* __restrict__ row, int E, int k, int lane, int* my_idx,
+__device__ __forceinline__ void topk_wave_regs(const float* __restrict__ row, int E, int k, int norm, int lane, int* my_idx,
                                                float* my_w) {
   unsigned key[NR];
 #pragma unroll
@@ -785,7 +787,7 @@ __device__ __forceinline__ void topk_wave_regs(const float* __restrict__ row, in
   }
   const float val = __uint_as_float(mine ^ ((mine >> 31) ? 0x80000000u : 0xFFFFFFFFu));
   const float first = __shfl(val, 0);
-  const float ex = lane < k ? __expf(val - first) : 0.0f;
+  const float ex = lane < k ? (norm ? 1.0f / (1.0f + __expf(-val)) : __expf(val - first)) : 0.0f;
   const float denom = wave_sum(ex);
   *my_idx = mine_idx;
   *my_w = ex / denom;
@@ -793,7 +795,7 @@ __device__ __forceinline__ void topk_wave_regs(const float* __restrict__ row, in
 
 // Register variant of topk_kernel for E <= 256: grid over groups of 16 tokens, one per wavefront.
 __global__ __launch_bounds__(kRouterThreads) void topk_regs_kernel(
-    const float* __restrict__ logits, int T, int E, int k, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
+    const float* __restrict__ logits, int T, int E, int k, int norm, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
     int32_t* __restrict__ aux_idx, float* __restrict__ aux_w) {
   const int lane = threadIdx.x & 63;
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -801,7 +803,7 @@ __global__ __launch_bounds__(kRouterThreads) void topk_regs_kernel(
   if (t >= T) return;
   int idx;
   float wv;
-  topk_wave_regs<4>(logits + (size_t)t * E, E, k, lane, &idx, &wv);
+  topk_wave_regs<4>(logits + (size_t)t * E, E, k, norm, lane, &idx, &wv);
   if (lane < k) {
     topk_idx[(size_t)t * k + lane] = idx;
     topk_w[(size_t)t * k + lane] = wv;
@@ -813,7 +815,7 @@ __global__ __launch_bounds__(kRouterThreads) void topk_regs_kernel(
 // Small token counts: TopK (register variant) and the expert union in one workgroup, the
 // wavefronts taking the tokens in turn; saves a launch when there are few tokens to share out.
 __global__ __launch_bounds__(kRouterThreads) void topk_union_kernel(
-    const float* __restrict__ logits, int T, int E, int k, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
+    const float* __restrict__ logits, int T, int E, int k, int norm, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
     int32_t* __restrict__ aux_idx, float* __restrict__ aux_w, int use_masks, int32_t* __restrict__ union_ids,
     int32_t* __restrict__ union_count, int32_t* __restrict__ hist, int32_t* __restrict__ offsets,
     int32_t* __restrict__ perm, int32_t* __restrict__ inv, int32_t* __restrict__ status, WorkRec* __restrict__ work,
@@ -824,7 +826,7 @@ __global__ __launch_bounds__(kRouterThreads) void topk_union_kernel(
   for (int t = w; t < T; t += kRouterWaves) {
     int idx;
     float wv;
-    topk_wave_regs<4>(logits + (size_t)t * E, E, k, lane, &idx, &wv);
+    topk_wave_regs<4>(logits + (size_t)t * E, E, k, norm, lane, &idx, &wv);
     if (lane < k) {
       s_all[t * k + lane] = idx;  // where expert_union_body expects the pairs
       topk_idx[(size_t)t * k + lane] = idx;
@@ -1196,18 +1198,18 @@ int launch_topk_union(const evict_ctx* c, int T, const evict_layer_aux* aux, hip
   const int use_masks = union_mask_plan(T, m.k, m.E, &lds);
   const bool regs = m.E <= 256;
   if (regs && T <= kFusedTopkTokens) {
-    hipLaunchKernelGGL(topk_union_kernel, dim3(1), dim3(kRouterThreads), lds, s, c->logits, T, m.E, m.k, c->topk_idx,
+    hipLaunchKernelGGL(topk_union_kernel, dim3(1), dim3(kRouterThreads), lds, s, c->logits, T, m.E, m.k, m.router_norm, c->topk_idx,
                        c->topk_w, a_idx, a_w, use_masks, c->union_ids, c->union_count, c->hist, c->offsets, c->perm, c->inv,
                        c->status, c->work, c->tok_of_pos, c->sched, m.n_shared);
     return launch_status("topk_union_kernel");
   }
   const dim3 tgrid((T + kRouterWaves - 1) / kRouterWaves);
   if (regs) {
-    hipLaunchKernelGGL(topk_regs_kernel, tgrid, dim3(kRouterThreads), 0, s, c->logits, T, m.E, m.k, c->topk_idx, c->topk_w,
+    hipLaunchKernelGGL(topk_regs_kernel, tgrid, dim3(kRouterThreads), 0, s, c->logits, T, m.E, m.k, m.router_norm, c->topk_idx, c->topk_w,
                        a_idx, a_w);
   } else {
     const size_t lds_topk = (size_t)kRouterWaves * (64 + m.E) * sizeof(float);
-    hipLaunchKernelGGL(topk_kernel, tgrid, dim3(kRouterThreads), lds_topk, s, c->logits, T, m.E, m.k, c->topk_idx, c->topk_w,
+    hipLaunchKernelGGL(topk_kernel, tgrid, dim3(kRouterThreads), lds_topk, s, c->logits, T, m.E, m.k, m.router_norm, c->topk_idx, c->topk_w,
                        a_idx, a_w);
   }
   int rc = launch_status("topk_kernel");

@@ -15,7 +15,7 @@ def storage_code(dtype: str) -> int:
 
 def model_desc(cfg, vocab: int = 0) -> ev.ModelDesc:
     return ev.ModelDesc(storage_code(cfg.dtype), cfg.d, cfg.Hq, cfg.Hkv, cfg.D, cfg.E, cfg.k, cfg.F, cfg.n_shared,
-                        cfg.eps, cfg.theta, vocab)
+                        cfg.eps, cfg.theta, vocab, 1 if getattr(cfg, "router_norm", "softmax") == "sigmoid" else 0)
 
 
 def to_dev(a: np.ndarray, dtype: str, device="cuda:0") -> torch.Tensor:

@@ -43,6 +43,7 @@ class ModelCfg:
     eps: float = 1e-6   # RMSNorm epsilon
     theta: float = 1e6  # RoPE base (0 disables RoPE)
     w_std: float = 0.02
+    router_norm: str = "softmax"  # weights of the selected scores: "softmax" or "sigmoid" (Sec. 2.2)
 
 
 CONFIGS: Dict[str, ModelCfg] = {
@@ -55,6 +56,8 @@ CONFIGS: Dict[str, ModelCfg] = {
                          n_shared=2, theta=1e4),
     # small bf16 shape for fast parity tests spanning several tiles with ragged tails
     "mini_bf16": ModelCfg("mini_bf16", "bf16", d=512, Hq=8, Hkv=2, D=128, E=32, k=4, F=192),
+    # small shape with 256 experts / 8 active (the ratio of Ling-flash-2.0, App. C.2), sigmoid router weights, 64-wide heads
+    "mini_sigmoid": ModelCfg("mini_sigmoid", "bf16", d=512, Hq=8, Hkv=4, D=64, E=256, k=8, F=128, router_norm="sigmoid"),
 }
 
 

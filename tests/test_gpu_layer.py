@@ -49,7 +49,7 @@ def check_against_oracle(case, got):
     assert rel_l2(got["h"], ref["h"]) < tol, "h"
     assert rel_l2(got["h_norm"], ref["h_norm"]) < tol, "h_norm"
     # --- router, stage-wise on the GPU's own normalised hidden state: bit-exact indices
-    idx, w, logits = orc.router_topk(got["h_norm"], case["W"]["wg"], cfg.k)
+    idx, w, logits = orc.router_topk(got["h_norm"], case["W"]["wg"], cfg.k, cfg.router_norm)
     np.testing.assert_allclose(got["router_logits"], logits, rtol=0, atol=2e-5)
     margin = orc.router_margin(logits, cfg.k)
     # ordering inside the top-k can also flip on near-equal neighbours; find the tightest gap
@@ -104,6 +104,13 @@ def test_tiny_fp32_shapes(n, L, tree, seed):
                                            (1, 5, "random", 13), (128, 64, "eagle", 14)])
 def test_mini_bf16_shapes(n, L, tree, seed):
     case = synth.make_case("mini_bf16", n=n, L=L, seed=seed, tree=tree)
+    check_against_oracle(case, run_case(case))
+
+
+@pytest.mark.parametrize("n,L,tree,seed", [(8, 64, "random", 20), (33, 150, "eagle", 21), (70, 129, "bfs", 22)])
+def test_sigmoid_router_256_experts_64_wide_heads(n, L, tree, seed):
+    """Sigmoid-normalised router weights (Sec. 2.2), 256 experts / 8 active, head dimension 64."""
+    case = synth.make_case("mini_sigmoid", n=n, L=L, seed=seed, tree=tree)
     check_against_oracle(case, run_case(case))
 
 

@@ -185,6 +185,28 @@ def test_router_topk_against_library_topk():
     np.testing.assert_allclose(w, sel / sel.sum(-1, keepdims=True), atol=1e-7)
 
 
+def test_router_sigmoid_weights_against_library():
+    g = synth.philox(5, 1)
+    hn = g.standard_normal((20, 48)).astype(np.float32)
+    wg = (0.3 * g.standard_normal((32, 48))).astype(np.float32)
+    idx, w, logits = orc.router_topk(hn, wg, 4, norm="sigmoid")
+    idx0, w0, _ = orc.router_topk(hn, wg, 4)
+    assert np.array_equal(idx, idx0)                 # the selection does not depend on the normalisation
+    sg = torch.sigmoid(torch.tensor(np.take_along_axis(logits, idx.astype(np.int64), axis=1)).double())
+    np.testing.assert_allclose(w, (sg / sg.sum(-1, keepdim=True)).numpy(), atol=1e-7)
+    np.testing.assert_allclose(w.sum(-1), 1.0, atol=1e-6)
+    assert not np.allclose(w, w0)                    # and differs from the softmax weights
+    # the layer uses it when the config says so
+    import dataclasses
+    case = _tiny_case(seed=5)
+    cfg2 = dataclasses.replace(case["cfg"], router_norm="sigmoid")
+    a = orc.verify_layer(cfg2, case["W"], case["tree_off"], case["parent"], case["x"], case["K"], case["V"], case["ctx_len"], act="f64")
+    b = _run(case)
+    assert np.array_equal(a["topk_idx"], b["topk_idx"]) and not np.allclose(a["topk_w"], b["topk_w"])
+    sg = 1 / (1 + np.exp(-np.take_along_axis(a["router_logits"].astype(np.float64), a["topk_idx"].astype(np.int64), axis=1)))
+    np.testing.assert_allclose(a["topk_w"], sg / sg.sum(-1, keepdims=True), atol=1e-6)
+
+
 def test_router_tie_break_lowest_index():
     hn = np.ones((1, 4), np.float32)
     wg = np.zeros((6, 4), np.float32)
