@@ -307,6 +307,19 @@ def main():
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / args.steps
 
+    def spread(fn, batches=20):
+        """p10 / p50 / p90 of the mean step time over batches of steps (outside the timed region)."""
+        per = max(args.steps // batches, 1)
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(batches + 1)]
+        evs[0].record()
+        for b in range(batches):
+            for i in range(per):
+                fn(b * per + i)
+            evs[b + 1].record()
+        torch.cuda.synchronize()
+        t = sorted(evs[b].elapsed_time(evs[b + 1]) * 1e3 / per for b in range(batches))
+        return [round(t[int(q * (batches - 1))], 2) for q in (0.1, 0.5, 0.9)]
+
     other_ms = None
     if args.launch == "graph":
         # one graph per weight copy: the same three calls, recorded once on a side stream
@@ -393,6 +406,7 @@ def main():
         "config": {"workload": f"{'qwen3-30b-a3b' if args.model == 'qwen3' else 'deepseek-v2-lite'}-shaped MoE layer, N={N} tree nodes, ctx={L}, 1 sequence, sigma={args.sigma}",
                    "d_model": cfg.d, "heads": f"{cfg.Hq}q/{cfg.Hkv}kv x {cfg.D}", "experts": f"{cfg.E} top-{cfg.k}",
                    "d_ff": cfg.F, "union_experts": U, "weight_copies": len(weight_sets)},
+        "step_us_p10_p50_p90": spread(step),
         "launch": args.launch,
         "eager_us": None if other_ms is None else round(other_ms * 1e3, 2),
         "tokens_per_s": round(N / (ms_per_step * 1e-3), 1),
