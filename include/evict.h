@@ -281,6 +281,9 @@ int evict_device_status(evict_ctx* ctx, int32_t* status_host, void* stream);
  *   "moe_down_kernel" 1: down projections with one 16-row strip per wavefront over the whole
  *                     contraction range (token operand staged in LDS); 0: contraction split
  *                     over the wavefronts of a workgroup like the other GEMMs
+ *   "dense_nt"        16-token tiles a workgroup of the QKV / output projections takes: 1, 2, or 0 = auto
+ *                     (2 once the call has more than 64 tokens)
+ *   "dense_units"     consecutive 16-row strips a workgroup of the QKV projection takes, 0 = auto
  *   "moe_plain_loads" 1: expert weights with ordinary loads instead of non-temporal ones
  *   "attn_row_blocks" workgroups per (KV split, KV head) in the bf16 attention kernel, 0 = auto
  * Returns EVICT_E_INVALID for an unknown key or a value out of range. */

@@ -122,6 +122,8 @@ int evict_create(evict_ctx** out, const evict_model_desc* m, int max_tokens, int
   c.moe_prefetch = 1;
   c.moe_down_kernel = 1;
   c.moe_plain_loads = 0;
+  c.dense_nt = 0;
+  c.dense_units = 0;
   c.moe_chunk_gateup = 1;
   c.moe_chunk_down = 1;
   for (int cu : {4, 2}) if ((m->d / 16) % cu == 0) { c.moe_chunk_down = cu; break; }
@@ -264,9 +266,14 @@ static int verify_layer_impl(evict_ctx* ctx, const evict_layer_weights* w, const
   if (rc) return rc;
   EVICT_MARK(1);
 
-  const int nt_dense = 1;
-  const int dense_tiles = (T + 15) / 16;
-  auto dense_grid = [&](int units) { return ((units + 7) / 8) * 8 * dense_tiles; };
+  // token tiles per workgroup in the dense projections: two once the tree spans more than two tiles
+  const int nt_dense = ctx->dense_nt ? ctx->dense_nt : (T > 64 ? 2 : 1);
+  const int dense_tiles = (T + 16 * nt_dense - 1) / (16 * nt_dense);
+  // QKV with several token tiles has workgroups to spare: each then takes two consecutive strips and
+  // its weight loads run ahead across them (measured: helps from two tiles on; the output projection,
+  // with a third of the strips and twice the contraction length, is better left at one)
+  const int qkv_units = ctx->dense_units ? ctx->dense_units : (dense_tiles >= 2 ? 2 : 1);
+  auto dense_grid = [&](int units, int du) { return (((units + du - 1) / du + 7) / 8) * 8 * dense_tiles; };
   {  // q, k, v projections + rotation (positions ctx_len + depth)
     GemmArgs a = {};
     a.W = (const u32x4*)w->wqkv_packed;
@@ -279,7 +286,8 @@ static int verify_layer_impl(evict_ctx* ctx, const evict_layer_weights* w, const
     a.rope_cs = ctx->rope_cs;
     a.Hq = m.Hq; a.Hkv = m.Hkv; a.D = m.D;
     a.dense_tiles = dense_tiles;
-    rc = launch_gemm(m.dtype, EPI_QKV, a, nt_dense, dense_grid(a.n_strips), s);
+    a.dense_units = qkv_units;
+    rc = launch_gemm(m.dtype, EPI_QKV, a, nt_dense, dense_grid(a.n_strips, qkv_units), s);
     if (rc) return rc;
     if (aux && aux->q) EVICT_HIP_CHECK(hipMemcpyAsync(aux->q, ctx->q, (size_t)T * HqD * eb, hipMemcpyDeviceToDevice, s));
   }
@@ -300,7 +308,8 @@ static int verify_layer_impl(evict_ctx* ctx, const evict_layer_weights* w, const
     a.ldo = m.d;
     a.resid = x_in;
     a.dense_tiles = dense_tiles;
-    rc = launch_gemm(m.dtype, EPI_RESID, a, nt_dense, dense_grid(a.n_strips), s);
+    a.dense_units = 1;
+    rc = launch_gemm(m.dtype, EPI_RESID, a, nt_dense, dense_grid(a.n_strips, 1), s);
     if (rc) return rc;
     if (aux && aux->h) EVICT_HIP_CHECK(hipMemcpyAsync(aux->h, ctx->h, (size_t)T * m.d * eb, hipMemcpyDeviceToDevice, s));
   }
@@ -501,6 +510,12 @@ int evict_tune(evict_ctx* ctx, const char* key, int value) {
   } else if (!strcmp(key, "moe_chunk_down")) {
     EVICT_REQUIRE(value >= 1 && (ctx->m.d / 16) % value == 0, EVICT_E_INVALID, "evict_tune: moe_chunk_down=%d must divide d/16", value);
     ctx->moe_chunk_down = value;
+  } else if (!strcmp(key, "dense_units")) {
+    EVICT_REQUIRE(value >= 0 && value <= 16, EVICT_E_INVALID, "evict_tune: dense_units must be in [0, 16] (0 = auto)");
+    ctx->dense_units = value;
+  } else if (!strcmp(key, "dense_nt")) {
+    EVICT_REQUIRE(value >= 0 && value <= 2, EVICT_E_INVALID, "evict_tune: dense_nt must be 0 (auto), 1 or 2");
+    ctx->dense_nt = value;
   } else if (!strcmp(key, "moe_plain_loads")) {
     EVICT_REQUIRE(value == 0 || value == 1, EVICT_E_INVALID, "evict_tune: moe_plain_loads must be 0 or 1");
     ctx->moe_plain_loads = value;

@@ -45,6 +45,7 @@ struct GemmArgs {
   int x_by_token;        // grouped: 1 -> X row = tok_of_pos[p], 0 -> X row = p
   int T;                 // dense: token rows
   int dense_tiles;       // dense: workgroups per strip, each taking 16*NT tokens
+  int dense_units;       // dense: consecutive strips a workgroup takes (its weight loads run ahead across them)
   int prefetch;          // host-side choice of the kernel variant (weight-load stages), 0 = default
   int wave_strip;        // host-side: grouped fp32-output GEMM may use gemm_wave_strip_kernel
   int plain_loads;       // 1: never use non-temporal weight loads (measurement knob)
@@ -305,9 +306,11 @@ __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(NT
     // HBM once.
     const unsigned xcd = blockIdx.x & 7u, i = blockIdx.x >> 3;
     const unsigned tile = i % (unsigned)a.dense_tiles;
-    const unsigned unit = (i / (unsigned)a.dense_tiles) * 8u + xcd;
+    const unsigned du = a.dense_units > 0 ? (unsigned)a.dense_units : 1u;
+    const unsigned unit = ((i / (unsigned)a.dense_tiles) * 8u + xcd) * du;
     if (unit >= (unsigned)upg) return;
-    run_segment(0, (int)unit, 1, (int)tile * 16 * NT, (int)(tile + 1) * 16 * NT);
+    const unsigned nu = unit + du <= (unsigned)upg ? du : (unsigned)upg - unit;
+    run_segment(0, (int)unit, (int)nu, (int)tile * 16 * NT, (int)(tile + 1) * 16 * NT);
   }
 }
 
