@@ -36,6 +36,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--nodes", type=int, default=32, help="draft-tree size N")
     ap.add_argument("--ctx", type=int, default=2048, help="KV context length")
+    ap.add_argument("--batch", type=int, default=1, help="sequences per call, each with its own tree of --nodes nodes")
+    ap.add_argument("--ctx-max", type=int, default=0,
+                    help="with --batch: context lengths drawn uniformly from [--ctx, --ctx-max] per sequence")
     ap.add_argument("--sigma", type=float, default=0.5, help="child = parent + sigma*N(0,1)")
     ap.add_argument("--copies", type=int, default=4, help="weight copies rotated between steps")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
@@ -245,9 +248,16 @@ def main():
         spec_loop(args)
         return
     cfg = synth.CONFIGS[args.model]
-    N, L = args.nodes, args.ctx
-    case = synth.make_case(args.model, n=N, L=L, seed=args.seed, sigma=args.sigma)
-    layer = harness.DeviceLayer(cfg, case["W"], max_tokens=N, max_batch=1, max_ctx=L)
+    N, L, B = args.nodes, args.ctx, args.batch
+    L_list = None
+    if B > 1:
+        gl = synth.philox(args.seed, 950)
+        L_list = [int(v) for v in gl.integers(L, max(args.ctx_max, L) + 1, B)]
+        L = max(L_list)
+    case = synth.make_case(args.model, n=N, L=L, seed=args.seed, sigma=args.sigma, batch=B, L_list=L_list,
+                           tree="eagle" if args.model == "qwen3" else "auto")
+    T = int(case["tree_off"][-1])
+    layer = harness.DeviceLayer(cfg, case["W"], max_tokens=T, max_batch=B, max_ctx=L)
     dc = harness.DeviceCase(case, with_aux=True)
     for kv in args.tune:
         key, val = kv.split("=")
@@ -273,24 +283,25 @@ def main():
     q_dev = torch.from_numpy(case["q"]).to(dev)
     cost = synth.cost_linear_in_union(N, cfg.E, cfg.k)
     cost_dev = torch.from_numpy(cost).to(dev)
-    sel = dict(k_star=torch.zeros(1, dtype=i32, device=dev), keep=torch.zeros(N, dtype=i32, device=dev),
-               new_parent=torch.zeros(N, dtype=i32, device=dev), new_off=torch.zeros(2, dtype=i32, device=dev),
-               est=torch.zeros(1, dtype=f32, device=dev))
+    sel = dict(k_star=torch.zeros(B, dtype=i32, device=dev), keep=torch.zeros(T, dtype=i32, device=dev),
+               new_parent=torch.zeros(T, dtype=i32, device=dev), new_off=torch.zeros(B + 1, dtype=i32, device=dev),
+               est=torch.zeros(B, dtype=f32, device=dev))
     g = synth.philox(args.seed, 900)
-    target_next = g.integers(0, 151936, N).astype(np.int32)
-    draft_tok = synth.plant_draft_tokens(case["parent"], target_next, 151936, g)
+    target_next = g.integers(0, 151936, T).astype(np.int32)
+    draft_tok = np.concatenate([synth.plant_draft_tokens(p, target_next[o:o + len(p)], 151936, g)
+                                for p, o in zip(case["parents"], case["tree_off"][:-1])])
     tn_dev, dt_dev = harness.dev_i32(target_next), harness.dev_i32(draft_tok)
-    path = torch.zeros(1, N, dtype=i32, device=dev)
-    path_len = torch.zeros(1, dtype=i32, device=dev)
-    bonus = torch.zeros(1, dtype=i32, device=dev)
+    path = torch.zeros(B, N, dtype=i32, device=dev)
+    path_len = torch.zeros(B, dtype=i32, device=dev)
+    bonus = torch.zeros(B, dtype=i32, device=dev)
 
     def step(i):
-        ev.evict_select_prefix(None, dc.tree_off, dc.parent, q_dev, 1, N, cost_dev, N, sel["k_star"], sel["keep"],
+        ev.evict_select_prefix(None, dc.tree_off, dc.parent, q_dev, B, T, cost_dev, N, sel["k_star"], sel["keep"],
                                sel["new_parent"], sel["new_off"], sel["est"])
-        ev.evict_verify_layer(layer.ctx, weight_sets[i % len(weight_sets)], dc.tree_off, dc.parent, 1, N, dc.k_cache,
+        ev.evict_verify_layer(layer.ctx, weight_sets[i % len(weight_sets)], dc.tree_off, dc.parent, B, T, dc.k_cache,
                               dc.v_cache, dc.seq_stride, dc.head_stride, dc.ctx_len, L, dc.x, dc.out, dc.k_new,
                               dc.v_new, None)
-        ev.evict_accept_path(None, dc.tree_off, dc.parent, dt_dev, tn_dev, 1, path, N, path_len, bonus)
+        ev.evict_accept_path(None, dc.tree_off, dc.parent, dt_dev, tn_dev, B, path, N, path_len, bonus)
 
     # one checked run: union size for the byte count
     dc.run(layer)
@@ -357,7 +368,7 @@ def main():
     # the stage events add per stage is (sum of stage times - this) / stages. (An event pair around
     # nothing, like the empty "shared" stage, costs more than an event between two kernels does.)
     def layer_only(i):
-        ev.evict_verify_layer(layer.ctx, weight_sets[i % len(weight_sets)], dc.tree_off, dc.parent, 1, N, dc.k_cache,
+        ev.evict_verify_layer(layer.ctx, weight_sets[i % len(weight_sets)], dc.tree_off, dc.parent, B, T, dc.k_cache,
                               dc.v_cache, dc.seq_stride, dc.head_stride, dc.ctx_len, L, dc.x, dc.out, dc.k_new,
                               dc.v_new, None)
     for i in range(5):
@@ -372,7 +383,7 @@ def main():
 
     eb = 2
     expert_bytes = 3 * cfg.d * cfg.F * eb
-    kv_bytes = 2 * L * cfg.Hkv * cfg.D * eb
+    kv_bytes = 2 * int(np.sum(case["ctx_len"])) * cfg.Hkv * cfg.D * eb
     proj_bytes = (2 * cfg.Hq * cfg.D * cfg.d + 2 * cfg.Hkv * cfg.D * cfg.d) * eb + cfg.E * cfg.d * eb
     north_star_bytes = (U + cfg.n_shared) * expert_bytes + kv_bytes
     all_bytes = north_star_bytes + proj_bytes
@@ -386,7 +397,7 @@ def main():
     tpath = os.path.join(ROOT, "profiles", "pmc_traffic.json")
     if os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get(f"gateup_N{N}_L{L}")
+            traffic = json.load(open(tpath)).get(f"gateup_N{N}_L{L}") if B == 1 else None
         except Exception:
             traffic = None
 
@@ -403,13 +414,13 @@ def main():
         "vs_baseline": None,
         "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": f"{'qwen3-30b-a3b' if args.model == 'qwen3' else 'deepseek-v2-lite'}-shaped MoE layer, N={N} tree nodes, ctx={L}, 1 sequence, sigma={args.sigma}",
+        "config": {"workload": f"{'qwen3-30b-a3b' if args.model == 'qwen3' else 'deepseek-v2-lite'}-shaped MoE layer, N={N} tree nodes, ctx={L if B == 1 else [int(v) for v in case['ctx_len']]}, {B} sequence{'s' if B > 1 else ''}, sigma={args.sigma}",
                    "d_model": cfg.d, "heads": f"{cfg.Hq}q/{cfg.Hkv}kv x {cfg.D}", "experts": f"{cfg.E} top-{cfg.k}",
                    "d_ff": cfg.F, "union_experts": U, "weight_copies": len(weight_sets)},
         "step_us_p10_p50_p90": spread(step),
         "launch": args.launch,
         "eager_us": None if other_ms is None else round(other_ms * 1e3, 2),
-        "tokens_per_s": round(N / (ms_per_step * 1e-3), 1),
+        "tokens_per_s": round(T / (ms_per_step * 1e-3), 1),
         "step_roofline": {"north_star_bytes": north_star_bytes, "all_required_bytes": all_bytes,
                           "hbm_frac_north_star": round(north_star_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                           "hbm_frac_all_required": round(all_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},

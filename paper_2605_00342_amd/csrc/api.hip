@@ -123,6 +123,7 @@ int evict_create(evict_ctx** out, const evict_model_desc* m, int max_tokens, int
   c.moe_down_kernel = 1;
   c.moe_plain_loads = 0;
   c.dense_nt = 0;
+  c.attn_target_wgs = 512;
   c.dense_units = 0;
   c.moe_chunk_gateup = 1;
   c.moe_chunk_down = 1;
@@ -510,6 +511,9 @@ int evict_tune(evict_ctx* ctx, const char* key, int value) {
   } else if (!strcmp(key, "moe_chunk_down")) {
     EVICT_REQUIRE(value >= 1 && (ctx->m.d / 16) % value == 0, EVICT_E_INVALID, "evict_tune: moe_chunk_down=%d must divide d/16", value);
     ctx->moe_chunk_down = value;
+  } else if (!strcmp(key, "attn_target_wgs")) {
+    EVICT_REQUIRE(value >= 1 && value <= 65536, EVICT_E_INVALID, "evict_tune: attn_target_wgs out of range");
+    ctx->attn_target_wgs = value;
   } else if (!strcmp(key, "dense_units")) {
     EVICT_REQUIRE(value >= 0 && value <= 16, EVICT_E_INVALID, "evict_tune: dense_units must be in [0, 16] (0 = auto)");
     ctx->dense_units = value;

@@ -302,7 +302,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
     long long seq_stride, long long head_stride, const int32_t* __restrict__ ctx_len, int max_ctx,
     const int32_t* __restrict__ tree_off, const uint16_t* __restrict__ k_new, const uint16_t* __restrict__ v_new,
     const uint64_t* __restrict__ anc, int Hq, int Hkv, int ctx_splits, int keys_per_split, int row_blocks, int T,
-    float* __restrict__ part_o, float* __restrict__ part_ml, int n_single) {
+    float* __restrict__ part_o, float* __restrict__ part_ml, int n_single, int n_seq) {
   constexpr int LDK = D + 8;            // bf16 per K row in LDS (16-byte pad)
   constexpr int LDV = kMfmaKeys + 4;    // bf16 per V^T row in LDS
   constexpr int CH = D / 8;             // 16-byte chunks per row
@@ -312,8 +312,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
   extern __shared__ __attribute__((aligned(16))) uint16_t s_kv[];
   uint16_t* s_k = s_kv;                          // [128][LDK]
   uint32_t* s_vt = reinterpret_cast<uint32_t*>(s_kv + kMfmaKeys * LDK);  // [D][LDV/2] key pairs
-  const int split = blockIdx.x / row_blocks, rb = blockIdx.x - split * row_blocks;
-  const int g = blockIdx.y, b = blockIdx.z;
+  // 1-D grid. Workgroup ids go round-robin over the 8 XCDs, so the row blocks of one (split, KV
+  // head, sequence) unit are given ids 8 apart: they share an L2 and the unit's keys and values
+  // leave HBM once, not once per row block.
+  const unsigned xcd = blockIdx.x & 7u, wi = blockIdx.x >> 3;
+  const int rb = (int)(wi % (unsigned)row_blocks);
+  const unsigned unit = (wi / (unsigned)row_blocks) * 8u + xcd;
+  const int nsplits_all = ctx_splits + 1;
+  if (unit >= (unsigned)(nsplits_all * Hkv * n_seq)) return;
+  const int split = (int)(unit % (unsigned)nsplits_all);
+  const int g = (int)((unit / (unsigned)nsplits_all) % (unsigned)Hkv);
+  const int b = (int)(unit / (unsigned)(nsplits_all * Hkv));
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lo = n_single > 0 ? 0 : tree_off[b];
@@ -395,6 +404,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
   for (int kc0 = key_begin; kc0 < key_end; kc0 += kMfmaKeys) {
     int nkeys = key_end - kc0;
     nkeys = nkeys > kMfmaKeys ? kMfmaKeys : nkeys;
+    const bool full = !tree_part && nkeys == kMfmaKeys;
     fetch_chunk(kc0);
     if (kc0 != key_begin) __syncthreads();  // the previous chunk has been consumed by every wavefront
     // ---- K row-major, V transposed (two keys per dword)
@@ -416,27 +426,40 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
     __syncthreads();
     if (!active) continue;
 
-    // S^T tiles: lane holds keys kt*16 + kq*4 + j of query row ln
+    // S^T tiles: lane holds keys kt*16 + kq*4 + j of query row ln. The K fragments of the next
+    // tile are requested from LDS before the MFMAs of the current one (two register buffers), so
+    // the LDS latency hides behind the matrix work instead of preceding every MFMA.
     f32x4 S[KT];
     float mx = -INFINITY;
+    u32x4 kf[2][KB];
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb) kf[0][kb] = *reinterpret_cast<const u32x4*>(s_k + ln * LDK + kb * 32 + kq * 8);
 #pragma unroll
     for (int kt = 0; kt < KT; ++kt) {
+      if (kt + 1 < KT) {
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb)
+          kf[(kt + 1) & 1][kb] = *reinterpret_cast<const u32x4*>(s_k + ((kt + 1) * 16 + ln) * LDK + kb * 32 + kq * 8);
+      }
+      __builtin_amdgcn_sched_barrier(0);
       f32x4 acc = {0, 0, 0, 0};
 #pragma unroll
-      for (int kb = 0; kb < KB; ++kb) {
-        const u32x4 kf = *reinterpret_cast<const u32x4*>(s_k + (kt * 16 + ln) * LDK + kb * 32 + kq * 8);
-        acc = mfma_block<BF16>(kf, Qf[kb], acc);
-      }
+      for (int kb = 0; kb < KB; ++kb) acc = mfma_block<BF16>(kf[kt & 1][kb], Qf[kb], acc);
+      if (full) {  // a whole chunk of cache keys: every key is visible to every row
+        acc *= scale;
+        mx = fmaxf(fmaxf(mx, fmaxf(acc[0], acc[1])), fmaxf(acc[2], acc[3]));
+      } else {
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int key = kt * 16 + kq * 4 + j;  // (the draft-node split has a single chunk: key = node index)
-        const uint64_t word = key < 64 ? a0 : a1;
-        const bool vis = key < nkeys && ((word >> (key & 63)) & 1ull);
-        acc[j] = vis ? acc[j] * scale : -INFINITY;
-        mx = fmaxf(mx, acc[j]);
+        for (int j = 0; j < 4; ++j) {
+          const int key = kt * 16 + kq * 4 + j;  // (the draft-node split has a single chunk: key = node index)
+          const uint64_t word = key < 64 ? a0 : a1;
+          const bool vis = key < nkeys && ((word >> (key & 63)) & 1ull);
+          acc[j] = vis ? acc[j] * scale : -INFINITY;
+          mx = fmaxf(mx, acc[j]);
+        }
       }
       S[kt] = acc;
-      __builtin_amdgcn_sched_barrier(0);  // keep the LDS reads of later tiles from piling up in registers
+      __builtin_amdgcn_sched_barrier(0);
     }
     mx = fmaxf(mx, __shfl_xor(mx, 16));
     mx = fmaxf(mx, __shfl_xor(mx, 32));
@@ -450,8 +473,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
       uint32_t pk[2];
 #pragma unroll
       for (int jj = 0; jj < 2; ++jj) {
-        const float p0 = S[kt][2 * jj] == -INFINITY ? 0.0f : __expf(S[kt][2 * jj] - m_new);
-        const float p1 = S[kt][2 * jj + 1] == -INFINITY ? 0.0f : __expf(S[kt][2 * jj + 1] - m_new);
+        // (exp(-inf - m) is 0 for a masked key as long as m is finite, which a visible key guarantees;
+        // rows without any visible key in this chunk have m_new = -inf and need the explicit zero)
+        const float p0 = (full || S[kt][2 * jj] != -INFINITY) ? __expf(S[kt][2 * jj] - m_new) : 0.0f;
+        const float p1 = (full || S[kt][2 * jj + 1] != -INFINITY) ? __expf(S[kt][2 * jj + 1] - m_new) : 0.0f;
         const uint16_t b0 = f32_to_bf16(p0), b1 = f32_to_bf16(p1);
         lsum += bf16_to_f32(b0) + bf16_to_f32(b1);  // the sum uses the rounded weights the MFMA sees
         pk[jj] = (uint32_t)b0 | ((uint32_t)b1 << 16);
@@ -468,19 +493,27 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
     f32x4 ar;
 #pragma unroll
     for (int j = 0; j < 4; ++j) ar[j] = __shfl(alpha, kq * 4 + j);
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt) {
-      f32x4 acc = O[dt] * ar;
+    // V^T fragments of the next output tile are requested before the MFMAs of the current one
+    auto load_v = [&](u32x4(&dst)[KT / 2], int dt) {
 #pragma unroll
       for (int bk = 0; bk < KT / 2; ++bk) {
         const uint32_t* vrow = s_vt + (dt * 16 + ln) * (LDV / 2) + bk * 16 + kq * 2;
         const uint2 lo2 = *reinterpret_cast<const uint2*>(vrow);
         const uint2 hi2 = *reinterpret_cast<const uint2*>(vrow + 8);
-        const u32x4 vf = {lo2.x, lo2.y, hi2.x, hi2.y};
-        acc = mfma_block<BF16>(Pf[bk], vf, acc);
+        dst[bk] = u32x4{lo2.x, lo2.y, hi2.x, hi2.y};
       }
+    };
+    u32x4 vf[2][KT / 2];
+    load_v(vf[0], 0);
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+      if (dt + 1 < DT) load_v(vf[(dt + 1) & 1], dt + 1);
+      __builtin_amdgcn_sched_barrier(0);
+      f32x4 acc = O[dt] * ar;
+#pragma unroll
+      for (int bk = 0; bk < KT / 2; ++bk) acc = mfma_block<BF16>(Pf[bk], vf[dt & 1][bk], acc);
       O[dt] = acc;
-      if (dt & 1) __builtin_amdgcn_sched_barrier(0);
+      __builtin_amdgcn_sched_barrier(0);
     }
   }
   if (!active) return;
@@ -1134,7 +1167,11 @@ int launch_attention(const evict_ctx* c, const void* kc, const void* vc, long lo
     const int max_nodes = T < EVICT_MAX_TREE_NODES ? T : EVICT_MAX_TREE_NODES;
     const int ntiles = (max_nodes * G + 15) / 16;
     const int rb = c->attn_row_blocks > 0 ? c->attn_row_blocks : (ntiles + 3) / 4;
-    int want = 512 / (m.Hkv * B * rb);  // context splits that give every CU two workgroups to overlap
+    // (the host knows only T and B: row blocks are provisioned for the largest tree allowed, and
+    // those past a sequence's own tiles leave at once; the split count goes by the average tree)
+    const int avg_nodes = (T + B - 1) / B < max_nodes ? (T + B - 1) / B : max_nodes;
+    const int rb_avg = ((avg_nodes * G + 15) / 16 + 3) / 4;
+    int want = c->attn_target_wgs / (m.Hkv * B * rb_avg);  // context splits that give every CU two workgroups to overlap
     want = want < 1 ? 1 : want;
     int chunks = (max_ctx_host + kMfmaKeys - 1) / kMfmaKeys;
     int cps = (chunks + want - 1) / want;  // chunks per split
@@ -1143,11 +1180,12 @@ int launch_attention(const evict_ctx* c, const void* kc, const void* vc, long lo
     ctx_splits = (max_ctx_host + keys - 1) / keys;
     nsplits = ctx_splits + 1;
     EVICT_REQUIRE(rb * 4 >= ntiles, EVICT_E_INVALID, "attn_row_blocks=%d is too small for %d query tiles", rb, ntiles);
-    const dim3 grid(nsplits * rb, m.Hkv, B);
+    const int units = nsplits * m.Hkv * B;
+    const dim3 grid(((units + 7) / 8) * 8 * rb);
     const size_t lds = attn_mfma_lds_bytes(m.D);
 #define EVICT_ATTN_ARGS (const uint16_t*)c->q, (const uint16_t*)kc, (const uint16_t*)vc, seq_stride, head_stride, ctx_len, \
                         max_ctx_host, tree_off, (const uint16_t*)k_new, (const uint16_t*)v_new, c->anc, m.Hq, m.Hkv,       \
-                        ctx_splits, keys, rb, T, c->part_o, c->part_ml, B == 1 ? T : 0
+                        ctx_splits, keys, rb, T, c->part_o, c->part_ml, B == 1 ? T : 0, B
     if (m.D == 128) hipLaunchKernelGGL(attn_partial_mfma_kernel<128>, grid, dim3(256), lds, s, EVICT_ATTN_ARGS);
     else hipLaunchKernelGGL(attn_partial_mfma_kernel<64>, grid, dim3(256), lds, s, EVICT_ATTN_ARGS);
 #undef EVICT_ATTN_ARGS
