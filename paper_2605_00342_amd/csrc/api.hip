@@ -124,6 +124,7 @@ int evict_create(evict_ctx** out, const evict_model_desc* m, int max_tokens, int
   c.moe_plain_loads = 0;
   c.dense_nt = 0;
   c.attn_target_wgs = 512;
+  c.attn_waves = 0;
   c.dense_units = 0;
   c.moe_chunk_gateup = 1;
   c.moe_chunk_down = 1;
@@ -511,6 +512,9 @@ int evict_tune(evict_ctx* ctx, const char* key, int value) {
   } else if (!strcmp(key, "moe_chunk_down")) {
     EVICT_REQUIRE(value >= 1 && (ctx->m.d / 16) % value == 0, EVICT_E_INVALID, "evict_tune: moe_chunk_down=%d must divide d/16", value);
     ctx->moe_chunk_down = value;
+  } else if (!strcmp(key, "attn_waves")) {
+    EVICT_REQUIRE(value == 0 || value == 4 || value == 8, EVICT_E_INVALID, "evict_tune: attn_waves must be 0 (auto), 4 or 8");
+    ctx->attn_waves = value;
   } else if (!strcmp(key, "attn_target_wgs")) {
     EVICT_REQUIRE(value >= 1 && value <= 65536, EVICT_E_INVALID, "evict_tune: attn_target_wgs out of range");
     ctx->attn_target_wgs = value;

@@ -296,8 +296,12 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(
 // ------------------------------------------------------------------------------------
 constexpr int kMfmaKeys = 128;
 
-template <int D>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void attn_partial_mfma_kernel(
+// NW wavefronts per workgroup, one 16-row query tile each. NW = 4: one LDS buffer, two workgroups
+// per CU overlap each other's staging. NW = 8 (many row tiles, several chunks per split): two LDS
+// buffers, the next chunk travels global -> registers while the current one is computed and is
+// written to the other buffer afterwards; one barrier per chunk.
+template <int D, int NW>
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) void attn_partial_mfma_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ kc, const uint16_t* __restrict__ vc,
     long long seq_stride, long long head_stride, const int32_t* __restrict__ ctx_len, int max_ctx,
     const int32_t* __restrict__ tree_off, const uint16_t* __restrict__ k_new, const uint16_t* __restrict__ v_new,
@@ -309,9 +313,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
   constexpr int KT = kMfmaKeys / 16;    // key tiles
   constexpr int KB = D / 32;            // contraction blocks of Q K^T
   constexpr int DT = D / 16;            // output column tiles
-  extern __shared__ __attribute__((aligned(16))) uint16_t s_kv[];
-  uint16_t* s_k = s_kv;                          // [128][LDK]
-  uint32_t* s_vt = reinterpret_cast<uint32_t*>(s_kv + kMfmaKeys * LDK);  // [D][LDV/2] key pairs
+  constexpr int NT = NW * 64;           // threads
+  constexpr int NBUF = NW == 8 ? 2 : 1;
+  constexpr int BUF = kMfmaKeys * LDK + D * LDV;  // bf16 elements of one K + V^T buffer
+  extern __shared__ __attribute__((aligned(16))) uint16_t s_kv[];  // NBUF x { K [128][LDK], V^T [D][LDV/2] key pairs }
   // 1-D grid. Workgroup ids go round-robin over the 8 XCDs, so the row blocks of one (split, KV
   // head, sequence) unit are given ids 8 apart: they share an L2 and the unit's keys and values
   // leave HBM once, not once per row block.
@@ -339,7 +344,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
   const int R = n * G;
   const int ntiles = (R + 15) >> 4;
   // one 16-row query tile per wavefront (the host sizes row_blocks for that)
-  const int rt = rb * 4 + w;
+  const int rt = rb * NW + w;
   const bool active = rt < ntiles;
   const int kq = lane >> 4, ln = lane & 15;
   if (key_begin >= key_end) {
@@ -352,7 +357,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
     }
     return;
   }
-  if (rb * 4 >= ntiles) return;
+  if (rb * NW >= ntiles) return;
 
   // ---- this wavefront's query rows are fetched before the K/V staging: the round trips overlap
   const float scale = 1.0f / sqrtf((float)D);
@@ -379,53 +384,60 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
   float m_run = -INFINITY, l_run = 0.0f;
 
   // K/V of a chunk travel global -> registers -> LDS, all loads issued before the first LDS
-  // write so one memory round trip covers the chunk. (Issuing the next chunk's loads ahead of
-  // the MFMA work was measured and gained nothing: two workgroups per CU already overlap.)
-  constexpr int KI = kMfmaKeys * CH / 256, VI = (kMfmaKeys / 2) * CH / 256;
+  // write so one memory round trip covers the chunk.
+  constexpr int KI = kMfmaKeys * CH / NT, VI = (kMfmaKeys / 2) * CH / NT;
   u32x4 kreg[KI], vreg0[VI], vreg1[VI];
   auto fetch_chunk = [&](int kc0) {
     int nk = key_end - kc0;
     nk = nk > kMfmaKeys ? kMfmaKeys : nk;
 #pragma unroll
     for (int it = 0; it < KI; ++it) {
-      const int idx = tid + 256 * it, j = idx / CH, c = idx - j * CH;
+      const int idx = tid + NT * it, j = idx / CH, c = idx - j * CH;
       kreg[it] = u32x4{0, 0, 0, 0};  // keys past the end are zeros
       if (j < nk) kreg[it] = *reinterpret_cast<const u32x4*>(kbase + (size_t)(kc0 + j) * kstep + c * 8);
     }
 #pragma unroll
     for (int it = 0; it < VI; ++it) {
-      const int idx = tid + 256 * it, jp = idx / CH, c = idx - jp * CH;
+      const int idx = tid + NT * it, jp = idx / CH, c = idx - jp * CH;
       vreg0[it] = u32x4{0, 0, 0, 0};
       vreg1[it] = u32x4{0, 0, 0, 0};
       if (2 * jp < nk) vreg0[it] = *reinterpret_cast<const u32x4*>(vbase + (size_t)(kc0 + 2 * jp) * kstep + c * 8);
       if (2 * jp + 1 < nk) vreg1[it] = *reinterpret_cast<const u32x4*>(vbase + (size_t)(kc0 + 2 * jp + 1) * kstep + c * 8);
     }
   };
+  // K row-major, V transposed (two keys per dword)
+  auto write_chunk = [&](int buf) {
+    uint16_t* wk = s_kv + (size_t)buf * BUF;
+    uint32_t* wv = reinterpret_cast<uint32_t*>(wk + kMfmaKeys * LDK);
+#pragma unroll
+    for (int it = 0; it < KI; ++it) {
+      const int idx = tid + NT * it, j = idx / CH, c = idx - j * CH;
+      *reinterpret_cast<u32x4*>(wk + j * LDK + c * 8) = kreg[it];
+    }
+#pragma unroll
+    for (int it = 0; it < VI; ++it) {
+      const int idx = tid + NT * it, jp = idx / CH, c = idx - jp * CH;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const uint32_t a = vreg0[it][i], bb = vreg1[it][i];
+        wv[(c * 8 + 2 * i) * (LDV / 2) + jp] = (a & 0xFFFFu) | (bb << 16);
+        wv[(c * 8 + 2 * i + 1) * (LDV / 2) + jp] = (a >> 16) | (bb & 0xFFFF0000u);
+      }
+    }
+  };
+  fetch_chunk(key_begin);
+  write_chunk(0);
+  __syncthreads();
+  int cur = 0;
   for (int kc0 = key_begin; kc0 < key_end; kc0 += kMfmaKeys) {
     int nkeys = key_end - kc0;
     nkeys = nkeys > kMfmaKeys ? kMfmaKeys : nkeys;
     const bool full = !tree_part && nkeys == kMfmaKeys;
-    fetch_chunk(kc0);
-    if (kc0 != key_begin) __syncthreads();  // the previous chunk has been consumed by every wavefront
-    // ---- K row-major, V transposed (two keys per dword)
-#pragma unroll
-    for (int it = 0; it < KI; ++it) {
-      const int idx = tid + 256 * it, j = idx / CH, c = idx - j * CH;
-      *reinterpret_cast<u32x4*>(s_k + j * LDK + c * 8) = kreg[it];
-    }
-#pragma unroll
-    for (int it = 0; it < VI; ++it) {
-      const int idx = tid + 256 * it, jp = idx / CH, c = idx - jp * CH;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const uint32_t a = vreg0[it][i], bb = vreg1[it][i];
-        s_vt[(c * 8 + 2 * i) * (LDV / 2) + jp] = (a & 0xFFFFu) | (bb << 16);
-        s_vt[(c * 8 + 2 * i + 1) * (LDV / 2) + jp] = (a >> 16) | (bb & 0xFFFF0000u);
-      }
-    }
-    __syncthreads();
-    if (!active) continue;
-
+    const bool more = kc0 + kMfmaKeys < key_end;
+    if (NBUF == 2 && more) fetch_chunk(kc0 + kMfmaKeys);  // in flight during the MFMA work below
+    const uint16_t* s_k = s_kv + (size_t)cur * BUF;
+    const uint32_t* s_vt = reinterpret_cast<const uint32_t*>(s_k + kMfmaKeys * LDK);
+    if (active) {
     // S^T tiles: lane holds keys kt*16 + kq*4 + j of query row ln. The K fragments of the next
     // tile are requested from LDS before the MFMAs of the current one (two register buffers), so
     // the LDS latency hides behind the matrix work instead of preceding every MFMA.
@@ -514,6 +526,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
       for (int bk = 0; bk < KT / 2; ++bk) acc = mfma_block<BF16>(Pf[bk], vf[dt & 1][bk], acc);
       O[dt] = acc;
       __builtin_amdgcn_sched_barrier(0);
+    }
+    }  // active
+    if (NBUF == 2) {
+      if (more) write_chunk(cur ^ 1);  // nobody reads that buffer during this iteration
+      __syncthreads();
+      cur ^= 1;
+    } else if (more) {
+      __syncthreads();  // the chunk has been consumed by every wavefront
+      fetch_chunk(kc0 + kMfmaKeys);
+      write_chunk(0);
+      __syncthreads();
     }
   }
   if (!active) return;
@@ -1143,8 +1166,10 @@ int kernels_setup(const evict_model_desc& m) {
   // kernels whose dynamic LDS exceeds the default 64 KiB limit
   EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)attn_partial_kernel<BF16>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_partial_lds_bytes(128)));
   EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)attn_partial_kernel<F32>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_partial_lds_bytes(128)));
-  EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)attn_partial_mfma_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_mfma_lds_bytes(128)));
-  EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)attn_partial_mfma_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_mfma_lds_bytes(64)));
+  EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)attn_partial_mfma_kernel<128, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_mfma_lds_bytes(128)));
+  EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)attn_partial_mfma_kernel<64, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_mfma_lds_bytes(64)));
+  EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)attn_partial_mfma_kernel<128, 8>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * (int)attn_mfma_lds_bytes(128)));
+  EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)attn_partial_mfma_kernel<64, 8>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * (int)attn_mfma_lds_bytes(64)));
   const size_t rl = router_lds_bytes(m);
   EVICT_REQUIRE(rl <= 152 * 1024, EVICT_E_UNSUPPORTED, "router needs %zu bytes of LDS (limit 152 KiB): d too large", rl);
   EVICT_REQUIRE(m.d <= 64 * 8 * (m.dtype == EVICT_BF16 ? 8 : 4), EVICT_E_UNSUPPORTED, "router keeps a token row in registers: d=%d too large", m.d);
@@ -1166,28 +1191,37 @@ int launch_attention(const evict_ctx* c, const void* kc, const void* vc, long lo
     const int G = m.Hq / m.Hkv;
     const int max_nodes = T < EVICT_MAX_TREE_NODES ? T : EVICT_MAX_TREE_NODES;
     const int ntiles = (max_nodes * G + 15) / 16;
-    const int rb = c->attn_row_blocks > 0 ? c->attn_row_blocks : (ntiles + 3) / 4;
     // (the host knows only T and B: row blocks are provisioned for the largest tree allowed, and
     // those past a sequence's own tiles leave at once; the split count goes by the average tree)
     const int avg_nodes = (T + B - 1) / B < max_nodes ? (T + B - 1) / B : max_nodes;
-    const int rb_avg = ((avg_nodes * G + 15) / 16 + 3) / 4;
-    int want = c->attn_target_wgs / (m.Hkv * B * rb_avg);  // context splits that give every CU two workgroups to overlap
+    const int avg_tiles = (avg_nodes * G + 15) / 16;
+    const int chunks = (max_ctx_host + kMfmaKeys - 1) / kMfmaKeys;
+    // 8-wavefront workgroups with two LDS buffers once there is more than one round of
+    // 4-wavefront workgroups to run and a workgroup has at least 8 row tiles to share a chunk
+    const long long chunk_wgs4 = (long long)chunks * m.Hkv * B * ((avg_tiles + 3) / 4);
+    int nw = (avg_tiles >= 8 && chunk_wgs4 > c->attn_target_wgs) ? 8 : 4;
+    if (c->attn_waves == 4 || c->attn_waves == 8) nw = c->attn_waves;
+    const int rb = c->attn_row_blocks > 0 ? c->attn_row_blocks : (ntiles + nw - 1) / nw;
+    const int rb_avg = (avg_tiles + nw - 1) / nw;
+    // context splits: two workgroups of 4 wavefronts per CU overlap each other; one of 8 fills it
+    int want = (nw == 8 ? c->attn_target_wgs / 2 : c->attn_target_wgs) / (m.Hkv * B * rb_avg);
     want = want < 1 ? 1 : want;
-    int chunks = (max_ctx_host + kMfmaKeys - 1) / kMfmaKeys;
     int cps = (chunks + want - 1) / want;  // chunks per split
     cps = cps < 1 ? 1 : cps;
     keys = cps * kMfmaKeys;
     ctx_splits = (max_ctx_host + keys - 1) / keys;
     nsplits = ctx_splits + 1;
-    EVICT_REQUIRE(rb * 4 >= ntiles, EVICT_E_INVALID, "attn_row_blocks=%d is too small for %d query tiles", rb, ntiles);
+    EVICT_REQUIRE(rb * nw >= ntiles, EVICT_E_INVALID, "attn_row_blocks=%d is too small for %d query tiles", rb, ntiles);
     const int units = nsplits * m.Hkv * B;
     const dim3 grid(((units + 7) / 8) * 8 * rb);
-    const size_t lds = attn_mfma_lds_bytes(m.D);
+    const size_t lds = attn_mfma_lds_bytes(m.D) * (nw == 8 ? 2 : 1);
 #define EVICT_ATTN_ARGS (const uint16_t*)c->q, (const uint16_t*)kc, (const uint16_t*)vc, seq_stride, head_stride, ctx_len, \
                         max_ctx_host, tree_off, (const uint16_t*)k_new, (const uint16_t*)v_new, c->anc, m.Hq, m.Hkv,       \
                         ctx_splits, keys, rb, T, c->part_o, c->part_ml, B == 1 ? T : 0, B
-    if (m.D == 128) hipLaunchKernelGGL(attn_partial_mfma_kernel<128>, grid, dim3(256), lds, s, EVICT_ATTN_ARGS);
-    else hipLaunchKernelGGL(attn_partial_mfma_kernel<64>, grid, dim3(256), lds, s, EVICT_ATTN_ARGS);
+    if (m.D == 128 && nw == 4) hipLaunchKernelGGL((attn_partial_mfma_kernel<128, 4>), grid, dim3(256), lds, s, EVICT_ATTN_ARGS);
+    else if (m.D == 128) hipLaunchKernelGGL((attn_partial_mfma_kernel<128, 8>), grid, dim3(512), lds, s, EVICT_ATTN_ARGS);
+    else if (nw == 4) hipLaunchKernelGGL((attn_partial_mfma_kernel<64, 4>), grid, dim3(256), lds, s, EVICT_ATTN_ARGS);
+    else hipLaunchKernelGGL((attn_partial_mfma_kernel<64, 8>), grid, dim3(512), lds, s, EVICT_ATTN_ARGS);
 #undef EVICT_ATTN_ARGS
   } else {
     keys = kAttnKeys;

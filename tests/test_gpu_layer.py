@@ -23,10 +23,12 @@ def rel_l2(a, b):
     return float(np.linalg.norm(np.asarray(a, np.float64) - b) / max(np.linalg.norm(b), 1e-30))
 
 
-def run_case(case, max_tokens=None):
+def run_case(case, max_tokens=None, tune=None):
     cfg = case["cfg"]
     T = int(case["tree_off"][-1])
     layer = harness.DeviceLayer(cfg, case["W"], max_tokens or T, len(case["ctx_len"]), int(max(case["ctx_len"])))
+    for key, value in (tune or {}).items():
+        ev.evict_tune(layer.ctx, key, value)
     dc = harness.DeviceCase(case)
     dc.run(layer)
     got = dc.results()
@@ -112,6 +114,21 @@ def test_sigmoid_router_256_experts_64_wide_heads(n, L, tree, seed):
     """Sigmoid-normalised router weights (Sec. 2.2), 256 experts / 8 active, head dimension 64."""
     case = synth.make_case("mini_sigmoid", n=n, L=L, seed=seed, tree=tree)
     check_against_oracle(case, run_case(case))
+
+
+@pytest.mark.parametrize("cfg_name,n,L,tree,seed,batch", [
+    ("mini_bf16", 128, 700, "eagle", 30, 1),      # 32 row tiles, 6 chunks with a ragged last one
+    ("mini_bf16", 40, 1, "bfs", 31, 1),           # a single cache key
+    ("mini_sigmoid", 70, 300, "bfs", 32, 1),      # 64-wide heads
+    ("mini_bf16", 50, 260, "bfs", 33, 3),         # batch with different context lengths
+])
+def test_attention_variants_agree_with_oracle(cfg_name, n, L, tree, seed, batch):
+    """Both workgroup shapes of the bf16 attention kernel (4 wavefronts / one LDS buffer, 8 wavefronts /
+    two buffers with the next chunk in flight) and small split targets, forced through evict_tune."""
+    L_list = [L, max(1, L // 3), L // 2 + 7][:batch] if batch > 1 else None
+    case = synth.make_case(cfg_name, n=n, L=L, seed=seed, tree=tree, batch=batch, L_list=L_list)
+    for tune in ({"attn_waves": 8}, {"attn_waves": 8, "attn_target_wgs": 4}, {"attn_waves": 4, "attn_target_wgs": 2}):
+        check_against_oracle(case, run_case(case, tune=tune))
 
 
 def test_batched_trees_fp32_and_bf16():
