@@ -286,6 +286,7 @@ int evict_device_status(evict_ctx* ctx, int32_t* status_host, void* stream);
  *   "dense_units"     consecutive 16-row strips a workgroup of the QKV projection takes, 0 = auto
  *   "moe_plain_loads" 1: expert weights with ordinary loads instead of non-temporal ones
  *   "attn_target_wgs" workgroups the bf16 attention kernel aims for when it cuts the context into splits
+ *   "moe_nt"          16-token tiles per work-list slot of the grouped expert GEMMs: 1, 2, or 0 = auto
  *   "attn_waves"      wavefronts per workgroup of that kernel: 4, 8 (two LDS buffers, next chunk fetched
  *                     during the matrix work), or 0 = auto
  *   "attn_row_blocks" workgroups per (KV split, KV head) in the bf16 attention kernel, 0 = auto

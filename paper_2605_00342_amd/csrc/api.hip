@@ -125,6 +125,7 @@ int evict_create(evict_ctx** out, const evict_model_desc* m, int max_tokens, int
   c.dense_nt = 0;
   c.attn_target_wgs = 512;
   c.attn_waves = 0;
+  c.moe_nt = 0;
   c.dense_units = 0;
   c.moe_chunk_gateup = 1;
   c.moe_chunk_down = 1;
@@ -319,7 +320,9 @@ static int verify_layer_impl(evict_ctx* ctx, const evict_layer_weights* w, const
   rc = launch_router(ctx, w->g_moe, w->wg_packed, T, aux, s);
   if (rc) return rc;
   EVICT_MARK(5);
-  rc = launch_topk_union(ctx, T, aux, s);
+  // token tiles per work-list slot of the grouped GEMMs: 2 once experts mostly have more than 16 tokens
+  const int nt_exp = ctx->moe_nt ? ctx->moe_nt : 1;
+  rc = launch_topk_union(ctx, T, aux, 16 * nt_exp, s);
   if (rc) return rc;
   if (aux) {
     if (aux->union_ids) EVICT_HIP_CHECK(hipMemcpyAsync(aux->union_ids, ctx->union_ids, (size_t)m.E * 4, hipMemcpyDeviceToDevice, s));
@@ -327,7 +330,6 @@ static int verify_layer_impl(evict_ctx* ctx, const evict_layer_weights* w, const
     if (aux->hist) EVICT_HIP_CHECK(hipMemcpyAsync(aux->hist, ctx->hist, (size_t)m.E * 4, hipMemcpyDeviceToDevice, s));
   }
   EVICT_MARK(6);
-  const int nt_exp = 1;  // token tiles of an expert are separate work slots
   {  // gate/up projections of the union experts + SiLU gating
     GemmArgs a = {};
     a.W = (const u32x4*)w->w_gateup_packed;
@@ -512,6 +514,9 @@ int evict_tune(evict_ctx* ctx, const char* key, int value) {
   } else if (!strcmp(key, "moe_chunk_down")) {
     EVICT_REQUIRE(value >= 1 && (ctx->m.d / 16) % value == 0, EVICT_E_INVALID, "evict_tune: moe_chunk_down=%d must divide d/16", value);
     ctx->moe_chunk_down = value;
+  } else if (!strcmp(key, "moe_nt")) {
+    EVICT_REQUIRE(value >= 0 && value <= 2, EVICT_E_INVALID, "evict_tune: moe_nt must be 0 (auto), 1 or 2");
+    ctx->moe_nt = value;
   } else if (!strcmp(key, "attn_waves")) {
     EVICT_REQUIRE(value == 0 || value == 4 || value == 8, EVICT_E_INVALID, "evict_tune: attn_waves must be 0 (auto), 4 or 8");
     ctx->attn_waves = value;

@@ -323,12 +323,13 @@ __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(NT
 // registers per lane (WIN KiB in flight per wavefront); NB operand blocks are staged per wavefront and
 // pass. A workgroup takes WS consecutive strips
 // of one slot (chunk); chunks are dealt round-robin like in gemm_stream_kernel.
-// Output: fp32 rows y[p0 + column][strip * 16 + ...] (the EPI_F32 contract).
-// LDS: nkb KiB (dynamic).
+// Output: fp32 rows y[p0 + column][strip * 16 + ...] (the EPI_F32 contract). NTW token tiles of 16
+// per slot (the work list is built with tiles of 16 * NTW tokens).
+// LDS: NTW * nkb KiB (dynamic).
 // ------------------------------------------------------------------------------------
-template <typename ST, int WIN, int NB, bool EXACT, int WS = 8>
+template <typename ST, int WIN, int NB, bool EXACT, int NTW = 1, int WS = 8>
 __global__ __launch_bounds__(WS * 64) __attribute__((amdgpu_waves_per_eu(4))) void gemm_wave_strip_kernel(const GemmArgs a) {
-  extern __shared__ __attribute__((aligned(16))) u32x4 s_b[];  // [nkb][64]
+  extern __shared__ __attribute__((aligned(16))) u32x4 s_b[];  // [NTW token tiles][nkb][64]
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int nkb = a.nkb;
@@ -344,21 +345,28 @@ __global__ __launch_bounds__(WS * 64) __attribute__((amdgpu_waves_per_eu(4))) vo
                                          : a.W_shared + (long long)(ex - a.n_routed) * a.group_stride;
     // token operand first, weights behind it: the in-order load counter then lets the operand
     // be consumed while the weight window is still in flight
-    int col = lane & 15;
-    const bool valid = col < ntok;
-    col = valid ? col : ntok - 1;  // padded columns repeat the last token; never stored
-    const long long xr = a.x_by_token ? a.tok_of_pos[p0 + col] : p0 + col;
-    const char* xrow = (const char*)a.X + xr * a.ldx_bytes + (lane >> 4) * 16;
-    constexpr int BMAX = NB;  // operand blocks a wavefront stages per pass
+    const char* xrow[NTW];
+    bool valid[NTW];
+#pragma unroll
+    for (int t = 0; t < NTW; ++t) {
+      int col = t * 16 + (lane & 15);
+      valid[t] = col < ntok;
+      col = valid[t] ? col : ntok - 1;  // padded columns repeat the last token; never stored
+      const long long xr = a.x_by_token ? a.tok_of_pos[p0 + col] : p0 + col;
+      xrow[t] = (const char*)a.X + xr * a.ldx_bytes + (lane >> 4) * 16;
+    }
+    constexpr int BMAX = NB;  // operand blocks a wavefront stages per pass and token tile
     const u32x4* wp = wbase + (long long)strip * nkb * 64 + lane;
     u32x4 A[WIN];
     for (int kb0 = 0; kb0 < nkb; kb0 += BMAX * WS) {
-      u32x4 bst[BMAX];
+      u32x4 bst[NTW][BMAX];
 #pragma unroll
-      for (int i = 0; i < BMAX; ++i) {
-        const int kb = kb0 + i * WS + w;
-        if (kb < nkb) bst[i] = *reinterpret_cast<const u32x4*>(xrow + (long long)kb * 64);
-      }
+      for (int t = 0; t < NTW; ++t)
+#pragma unroll
+        for (int i = 0; i < BMAX; ++i) {
+          const int kb = kb0 + i * WS + w;
+          if (kb < nkb) bst[t][i] = *reinterpret_cast<const u32x4*>(xrow[t] + (long long)kb * 64);
+        }
       if (kb0 == 0) {
 #pragma unroll
         for (int j = 0; j < WIN; ++j)
@@ -366,27 +374,33 @@ __global__ __launch_bounds__(WS * 64) __attribute__((amdgpu_waves_per_eu(4))) vo
         if (!first) lds_barrier();  // every wavefront is done with the previous chunk's operand
       }
 #pragma unroll
-      for (int i = 0; i < BMAX; ++i) {
-        const int kb = kb0 + i * WS + w;
-        if (kb < nkb) s_b[kb * 64 + lane] = bst[i];
-      }
+      for (int t = 0; t < NTW; ++t)
+#pragma unroll
+        for (int i = 0; i < BMAX; ++i) {
+          const int kb = kb0 + i * WS + w;
+          if (kb < nkb) s_b[((size_t)t * nkb + kb) * 64 + lane] = bst[t][i];
+        }
     }
     lds_barrier();
     first = false;
-    f32x4 acc = {0, 0, 0, 0};
+    f32x4 acc[NTW];
+#pragma unroll
+    for (int t = 0; t < NTW; ++t) acc[t] = f32x4{0, 0, 0, 0};
     for (int j0 = 0; j0 < nkb; j0 += WIN) {
 #pragma unroll
       for (int jj = 0; jj < WIN; ++jj) {
         const int j = j0 + jj;
         if (EXACT || j < nkb) {
-          const u32x4 bf = s_b[j * 64 + lane];
-          acc = mfma_block<ST>(A[jj], bf, acc);
+#pragma unroll
+          for (int t = 0; t < NTW; ++t) acc[t] = mfma_block<ST>(A[jj], s_b[((size_t)t * nkb + j) * 64 + lane], acc[t]);
           if (j + WIN < nkb) A[jj] = once ? __builtin_nontemporal_load(wp + (j + WIN) * 64) : wp[(j + WIN) * 64];
         }
       }
     }
-    if (valid)
-      *reinterpret_cast<f32x4*>((float*)a.out0 + (p0 + (lane & 15)) * a.ldo + strip * 16 + (lane >> 4) * 4) = acc;
+#pragma unroll
+    for (int t = 0; t < NTW; ++t)
+      if (valid[t])
+        *reinterpret_cast<f32x4*>((float*)a.out0 + (p0 + t * 16 + (lane & 15)) * a.ldo + strip * 16 + (lane >> 4) * 4) = acc[t];
   }
 }
 

@@ -875,7 +875,7 @@ __global__ __launch_bounds__(kRouterThreads) void topk_union_kernel(
     int32_t* __restrict__ aux_idx, float* __restrict__ aux_w, int use_masks, int32_t* __restrict__ union_ids,
     int32_t* __restrict__ union_count, int32_t* __restrict__ hist, int32_t* __restrict__ offsets,
     int32_t* __restrict__ perm, int32_t* __restrict__ inv, int32_t* __restrict__ status, WorkRec* __restrict__ work,
-    int32_t* __restrict__ tok_of_pos, int32_t* __restrict__ slot_count, int n_shared) {
+    int32_t* __restrict__ tok_of_pos, int32_t* __restrict__ slot_count, int n_shared, int tt) {
   extern __shared__ __attribute__((aligned(16))) int s_all[];
   const int lane = threadIdx.x & 63;
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -893,7 +893,7 @@ __global__ __launch_bounds__(kRouterThreads) void topk_union_kernel(
   }
   __syncthreads();
   expert_union_body(s_all, nullptr, T, k, E, use_masks, union_ids, union_count, hist, offsets, perm, inv, status, work,
-                    tok_of_pos, slot_count, n_shared);
+                    tok_of_pos, slot_count, n_shared, tt);
 }
 
 // expert union and grouping (Eq. 5) with the device-side work list, one workgroup
@@ -901,10 +901,10 @@ __global__ __launch_bounds__(kRouterThreads) void union_worklist_kernel(
     const int32_t* __restrict__ topk_idx, int T, int k, int E, int use_masks, int32_t* __restrict__ union_ids,
     int32_t* __restrict__ union_count, int32_t* __restrict__ hist, int32_t* __restrict__ offsets,
     int32_t* __restrict__ perm, int32_t* __restrict__ inv, int32_t* __restrict__ status, WorkRec* __restrict__ work,
-    int32_t* __restrict__ tok_of_pos, int32_t* __restrict__ slot_count, int n_shared) {
+    int32_t* __restrict__ tok_of_pos, int32_t* __restrict__ slot_count, int n_shared, int tt) {
   extern __shared__ __attribute__((aligned(16))) int s_all[];
   expert_union_body(s_all, topk_idx, T, k, E, use_masks, union_ids, union_count, hist, offsets, perm, inv, status, work,
-                    tok_of_pos, slot_count, n_shared);
+                    tok_of_pos, slot_count, n_shared, tt);
 }
 
 // ------------------------------------------------------------------------------------
@@ -1074,27 +1074,28 @@ int launch_gemm_nt(const GemmArgs& a, int grid, hipStream_t s) {
 }
 
 // one strip per wavefront (see gemm_wave_strip_kernel): grouped, fp32 output rows
-template <typename ST>
+template <typename ST, int NTW>
 int launch_gemm_wave_strip(const GemmArgs& a, int grid, hipStream_t s) {
   const int nkb = a.nkb;
-  const size_t lds = (size_t)nkb * 1024;
+  const size_t lds = (size_t)nkb * 1024 * NTW;
 #define EVICT_WS_LAUNCH(WIN_, NB_, EXACT_) \
-  hipLaunchKernelGGL((gemm_wave_strip_kernel<ST, WIN_, NB_, EXACT_>), dim3(grid), dim3(8 * 64), lds, s, a)
+  hipLaunchKernelGGL((gemm_wave_strip_kernel<ST, WIN_, NB_, EXACT_, NTW>), dim3(grid), dim3(8 * 64), lds, s, a)
   // (windows sized to stay under 128 VGPRs together with the staged operand blocks)
   if (nkb == 24) EVICT_WS_LAUNCH(12, 3, true);
-  else if (nkb == 44) EVICT_WS_LAUNCH(11, 6, true);
-  else if (nkb % 16 == 0) EVICT_WS_LAUNCH(16, 4, true);
-  else if (nkb % 8 == 0) EVICT_WS_LAUNCH(8, 2, true);
-  else EVICT_WS_LAUNCH(16, 4, false);
+  else if (nkb == 44) EVICT_WS_LAUNCH(11, 6 / NTW, true);
+  else if (nkb % 16 == 0) EVICT_WS_LAUNCH(16, 4 / NTW, true);
+  else if (nkb % 8 == 0) EVICT_WS_LAUNCH(8, 2 / NTW, true);
+  else EVICT_WS_LAUNCH(16, 4 / NTW, false);
 #undef EVICT_WS_LAUNCH
   return launch_status("gemm_wave_strip_kernel");
 }
 
-bool wave_strip_applies(const GemmArgs& a) { return a.grouped && a.n_strips % 8 == 0 && a.nkb <= 64; }
+bool wave_strip_applies(const GemmArgs& a, int nt) { return a.grouped && a.n_strips % 8 == 0 && a.nkb * nt <= 64; }
 
 template <typename ST, int EPI>
 int launch_gemm_st(const GemmArgs& a, int nt, int grid, hipStream_t s) {
-  if (EPI == EPI_F32 && a.wave_strip && wave_strip_applies(a)) return launch_gemm_wave_strip<ST>(a, grid, s);
+  if (EPI == EPI_F32 && a.wave_strip && wave_strip_applies(a, nt))
+    return nt == 1 ? launch_gemm_wave_strip<ST, 1>(a, grid, s) : launch_gemm_wave_strip<ST, 2>(a, grid, s);
   return nt == 1 ? launch_gemm_nt<ST, 1, EPI>(a, grid, s) : launch_gemm_nt<ST, 2, EPI>(a, grid, s);
 }
 
@@ -1262,7 +1263,7 @@ int launch_router(const evict_ctx* c, const void* gain, const void* wg, int T, c
   return launch_status("router_logits_kernel");
 }
 
-int launch_topk_union(const evict_ctx* c, int T, const evict_layer_aux* aux, hipStream_t s) {
+int launch_topk_union(const evict_ctx* c, int T, const evict_layer_aux* aux, int tile_tokens, hipStream_t s) {
   const evict_model_desc& m = c->m;
   int32_t* a_idx = aux ? aux->topk_idx : nullptr;
   float* a_w = aux ? aux->topk_w : nullptr;
@@ -1272,7 +1273,7 @@ int launch_topk_union(const evict_ctx* c, int T, const evict_layer_aux* aux, hip
   if (regs && T <= kFusedTopkTokens) {
     hipLaunchKernelGGL(topk_union_kernel, dim3(1), dim3(kRouterThreads), lds, s, c->logits, T, m.E, m.k, m.router_norm, c->topk_idx,
                        c->topk_w, a_idx, a_w, use_masks, c->union_ids, c->union_count, c->hist, c->offsets, c->perm, c->inv,
-                       c->status, c->work, c->tok_of_pos, c->sched, m.n_shared);
+                       c->status, c->work, c->tok_of_pos, c->sched, m.n_shared, tile_tokens);
     return launch_status("topk_union_kernel");
   }
   const dim3 tgrid((T + kRouterWaves - 1) / kRouterWaves);
@@ -1288,7 +1289,7 @@ int launch_topk_union(const evict_ctx* c, int T, const evict_layer_aux* aux, hip
   if (rc) return rc;
   hipLaunchKernelGGL(union_worklist_kernel, dim3(1), dim3(kRouterThreads), lds, s, c->topk_idx, T, m.k, m.E, use_masks,
                      c->union_ids, c->union_count, c->hist, c->offsets, c->perm, c->inv, c->status, c->work, c->tok_of_pos,
-                     c->sched, m.n_shared);
+                     c->sched, m.n_shared, tile_tokens);
   return launch_status("union_worklist_kernel");
 }
 

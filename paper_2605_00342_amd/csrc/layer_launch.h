@@ -18,7 +18,7 @@ int launch_attention(const evict_ctx* c, const void* kc, const void* vc, long lo
                      const int32_t* ctx_len, int max_ctx_host, const int32_t* tree_off, int B, int T, const void* k_new,
                      const void* v_new, void* aux_out, hipStream_t s);
 int launch_router(const evict_ctx* c, const void* gain, const void* wg, int T, const evict_layer_aux* aux, hipStream_t s);
-int launch_topk_union(const evict_ctx* c, int T, const evict_layer_aux* aux, hipStream_t s);
+int launch_topk_union(const evict_ctx* c, int T, const evict_layer_aux* aux, int tile_tokens, hipStream_t s);
 int launch_argmax_reduce(const float* val, const int32_t* idx, int nstrips, int ld, int T, int32_t* next, float* best_out,
                          hipStream_t s);
 int launch_combine(const evict_ctx* c, int T, void* out, const void* next_gain, hipStream_t s);

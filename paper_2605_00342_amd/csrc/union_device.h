@@ -35,13 +35,14 @@ __device__ int block_excl_scan(int v, int* s_wave, int* total) {
   return base + incl - v;
 }
 
-// Token t sits at rank r (of n) inside its expert: enter it into the record of its 16-token tile;
-// the last token of a tile also fills the record's unused entries (padded columns repeat it).
-__device__ inline void work_put_token(WorkRec* first, int r, int n, int t) {
-  WorkRec* rec = first + (r >> 4);
-  const int i = r & 15;
+// Token t sits at rank r (of n) inside its expert: enter it into the record of its tile of tt
+// (16 or 32) tokens; the last token of a tile also fills the record's unused entries (padded
+// columns repeat it).
+__device__ inline void work_put_token(WorkRec* first, int r, int n, int t, int tt) {
+  WorkRec* rec = first + r / tt;
+  const int i = r % tt;
   if (i < kWorkToks) rec->tok[i] = t;
-  if (i == 15 || r == n - 1)
+  if (i == tt - 1 || r == n - 1)
     for (int j = i + 1; j < kWorkToks; ++j) rec->tok[j] = t;
 }
 
@@ -58,7 +59,7 @@ __device__ inline void expert_union_body(
     int* s_mem, const int32_t* __restrict__ topk_idx, int T, int k, int E, int use_masks, int32_t* __restrict__ union_ids,
     int32_t* __restrict__ union_count, int32_t* __restrict__ hist, int32_t* __restrict__ offsets,
     int32_t* __restrict__ perm, int32_t* __restrict__ inv, int32_t* __restrict__ status, WorkRec* __restrict__ work,
-    int32_t* __restrict__ tok_of_pos, int32_t* __restrict__ slot_count = nullptr, int n_shared = 0) {
+    int32_t* __restrict__ tok_of_pos, int32_t* __restrict__ slot_count = nullptr, int n_shared = 0, int tt = 16) {
   const int P = T * k;
   const int words = (T + 63) >> 6;
   int* s_idx = s_mem;            // [P]
@@ -96,23 +97,23 @@ __device__ inline void expert_union_body(
   const int base = block_excl_scan(hcount | ((hcount > 0 ? 1 : 0) << 16), s_wave, &tot);
   const int base_h = base & 0xFFFF, base_f = base >> 16;
   const int tot_h = tot & 0xFFFF, tot_f = tot >> 16;
-  // work list: one slot per (activated expert, tile of 16 of its tokens); second scan for the slots
+  // work list: one slot per (activated expert, tile of tt of its tokens); second scan for the slots
   int wslot = 0;
   if (work) {
     int tot_s;
-    wslot = block_excl_scan((hcount + 15) >> 4, s_wave, &tot_s);
+    wslot = block_excl_scan((hcount + tt - 1) / tt, s_wave, &tot_s);
     // always-on shared experts: every token, in token order, appended behind the routed pairs
-    // (expert id E + s; positions T*k + s*T + t), one slot per tile of 16 tokens
-    const int ttiles = (T + 15) >> 4;
+    // (expert id E + s; positions T*k + s*T + t), one slot per tile of tt tokens
+    const int ttiles = (T + tt - 1) / tt;
     if (tid == 0 && slot_count) slot_count[0] = tot_s + n_shared * ttiles;
     for (int q = tid; q < n_shared * ttiles; q += nthreads) {
       const int sh = q / ttiles, i = q - sh * ttiles;
       WorkRec* rec = work + tot_s + q;
       rec->expert = E + sh;
-      rec->p0 = P + sh * T + 16 * i;
-      rec->ntok = T - 16 * i < 16 ? T - 16 * i : 16;
+      rec->p0 = P + sh * T + tt * i;
+      rec->ntok = T - tt * i < tt ? T - tt * i : tt;
       rec->pad = ttiles | (i << 16);
-      for (int j = 0; j < kWorkToks; ++j) rec->tok[j] = 16 * i + (j < rec->ntok ? j : rec->ntok - 1);
+      for (int j = 0; j < kWorkToks; ++j) rec->tok[j] = tt * i + (j < rec->ntok ? j : rec->ntok - 1);
     }
     if (tok_of_pos)
       for (int q = tid; q < n_shared * T; q += nthreads) tok_of_pos[P + q] = q % T;
@@ -125,12 +126,12 @@ __device__ inline void expert_union_body(
       union_ids[base_f] = tid;
       s_slot[tid] = wslot;
       if (work) {
-        const int ntile = (hcount + 15) >> 4;
+        const int ntile = (hcount + tt - 1) / tt;
         for (int i = 0; i < ntile; ++i) {
           WorkRec* rec = work + wslot + i;
           rec->expert = tid;
-          rec->p0 = base_h + 16 * i;
-          rec->ntok = hcount - 16 * i < 16 ? hcount - 16 * i : 16;
+          rec->p0 = base_h + tt * i;
+          rec->ntok = hcount - tt * i < tt ? hcount - tt * i : tt;
           rec->pad = ntile | (i << 16);  // tiles of this expert (low half), index of this tile (high half)
         }
       }
@@ -150,7 +151,7 @@ __device__ inline void expert_union_body(
       perm[pos] = p;
       inv[p] = pos;
       if (tok_of_pos) tok_of_pos[pos] = t;
-      if (work) work_put_token(work + s_slot[e], pos - s_off[e], s_hist[e], t);
+      if (work) work_put_token(work + s_slot[e], pos - s_off[e], s_hist[e], t, tt);
     }
   } else {
     for (int e = tid; e < E; e += nthreads) {
@@ -161,7 +162,7 @@ __device__ inline void expert_union_body(
           perm[pos] = p;
           inv[p] = pos;
           if (tok_of_pos) tok_of_pos[pos] = p / k;
-          if (work) work_put_token(work + s_slot[e], pos - s_off[e], s_hist[e], p / k);
+          if (work) work_put_token(work + s_slot[e], pos - s_off[e], s_hist[e], p / k, tt);
           ++pos;
         }
       }
