@@ -107,6 +107,9 @@ __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(NT
       u32x4 Bf[NT][KBW];
       f32x4 acc[IS][NT];
       f32x4 gate[NT];
+      f32x4 pre0[IS * NT], pre1[IS * NT];  // epilogue operands requested ahead (QKV / RESID)
+#pragma unroll
+      for (int q = 0; q < IS * NT; ++q) pre0[q] = pre1[q] = f32x4{0, 0, 0, 0};
 #pragma unroll
       for (int t = 0; t < NT; ++t) {
         gate[t] = f32x4{0, 0, 0, 0};
@@ -176,6 +179,30 @@ __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(NT
           if (step < nsteps) {
             const int it = step / nchunks, c = step - it * nchunks;
             if (nchunks > 1) load_b(c);
+            if ((EPI == EPI_QKV || EPI == EPI_RESID) && c == 0) {
+              // the wavefront that will reduce this strip requests what its epilogue needs (rotation
+              // table entries, residual values) now, so that round trip hides behind the weight stream
+              const int rb0 = unit_in_grp + it / SPU;
+#pragma unroll
+              for (int q = 0; q < IS * NT; ++q) {
+                if (w == ((rb0 + q) & (kGemmWaves - 1))) {
+                  const int t = q % NT;
+                  const int strip = strip0 + it * IS + q / NT;
+                  const int col = tok0 + t * 16 + (lane & 15);
+                  const int tokc = col < ntok ? col : 0;
+                  if (EPI == EPI_RESID) {
+                    pre0[q] = load4<ST>(a.resid, (long long)tokc * a.ldo + strip * 16 + (lane >> 4) * 4);
+                  } else {
+                    const int spd = a.D >> 4;
+                    const int head = strip / spd, js = strip - head * spd;
+                    const int idx = js * 8 + ((lane >> 4) & 1) * 4;
+                    const float* cs = a.rope_cs + (long long)tokc * a.D;
+                    pre0[q] = *reinterpret_cast<const f32x4*>(cs + idx);
+                    pre1[q] = *reinterpret_cast<const f32x4*>(cs + (a.D >> 1) + idx);
+                  }
+                }
+              }
+            }
             int b0, nb;
             range(c, b0, nb);
 #pragma unroll
@@ -236,8 +263,7 @@ __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(NT
                   } else if (EPI == EPI_RESID) {
                     if (valid) {
                       const long long o = (long long)col * a.ldo + strip * 16 + m0;
-                      f32x4 rsd = load4<ST>(a.resid, o);
-                      store4<ST>(a.out0, o, rsd + sum);
+                      store4<ST>(a.out0, o, pre0[q] + sum);
                     }
                   } else if (EPI == EPI_SWIGLU) {
                     if ((it & 1) == 0) {
@@ -258,13 +284,11 @@ __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(NT
                     f32x4 other, r4;
 #pragma unroll
                     for (int i = 0; i < 4; ++i) other[i] = __shfl_xor(sum[i], 32);
-                    const int tokc = valid ? col : 0;
-                    const float* cs = a.rope_cs + (long long)tokc * a.D;
                     const bool rot = head < a.Hq + a.Hkv;
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                      const float cv = rot ? cs[idx + i] : 1.0f;
-                      const float sv = rot ? cs[half + idx + i] : 0.0f;
+                      const float cv = rot ? pre0[q][i] : 1.0f;
+                      const float sv = rot ? pre1[q][i] : 0.0f;
                       r4[i] = (g4 < 2) ? (sum[i] * cv - other[i] * sv) : (sum[i] * cv + other[i] * sv);
                     }
                     if (valid) {
