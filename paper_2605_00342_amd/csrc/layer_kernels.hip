@@ -623,7 +623,8 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict
 // ------------------------------------------------------------------------------------
 constexpr int kRouterWaves = 16;
 constexpr int kRouterThreads = kRouterWaves * 64;
-constexpr int kFusedTopkTokens = 32;  // up to here TopK and the union share one workgroup (measured: no loss up to 32)
+constexpr int kFusedTopkTokens = 32;  // up to here TopK and the union share one workgroup (measured: no loss up to 32;
+                                      // two tokens per wavefront at most, which topk_union_kernel relies on)
 
 template <typename ST>
 __global__ __launch_bounds__(kRouterThreads) void router_logits_kernel(
@@ -807,7 +808,16 @@ __global__ __launch_bounds__(kRouterThreads) void topk_kernel(
 // selection rule as topk_kernel, without the LDS round trips. Lane j ends up with the j-th pick.
 // Returns the expert index picked at position `lane` (for lane < k) and its softmax weight.
 template <int NR>
-__device__ __forceinline__ void topk_wave_regs(const float* __restrict__ row, int E, int k, int norm, int lane, int* my_idx,
+__device__ __forceinline__ void topk_load_row(const float* __restrict__ row, int E, int lane, float (&raw)[NR]) {
+#pragma unroll
+  for (int i = 0; i < NR; ++i) {
+    const int e = i * 64 + lane;
+    raw[i] = e < E ? row[e] : 0.0f;
+  }
+}
+
+template <int NR>
+__device__ __forceinline__ void topk_wave_regs(const float (&raw)[NR], int E, int k, int norm, int lane, int* my_idx,
                                                float* my_w) {
   unsigned key[NR];
 #pragma unroll
@@ -815,7 +825,7 @@ __device__ __forceinline__ void topk_wave_regs(const float* __restrict__ row, in
     const int e = i * 64 + lane;
     unsigned o = 0u;
     if (e < E) {
-      unsigned bits = __float_as_uint(row[e]);
+      unsigned bits = __float_as_uint(raw[i]);
       bits = bits == 0x80000000u ? 0u : bits;
       o = bits ^ ((bits >> 31) ? 0xFFFFFFFFu : 0x80000000u);
       o = o == 0u ? 1u : o;
@@ -859,7 +869,9 @@ __global__ __launch_bounds__(kRouterThreads) void topk_regs_kernel(
   if (t >= T) return;
   int idx;
   float wv;
-  topk_wave_regs<4>(logits + (size_t)t * E, E, k, norm, lane, &idx, &wv);
+  float raw[4];
+  topk_load_row<4>(logits + (size_t)t * E, E, lane, raw);
+  topk_wave_regs<4>(raw, E, k, norm, lane, &idx, &wv);
   if (lane < k) {
     topk_idx[(size_t)t * k + lane] = idx;
     topk_w[(size_t)t * k + lane] = wv;
@@ -879,10 +891,18 @@ __global__ __launch_bounds__(kRouterThreads) void topk_union_kernel(
   extern __shared__ __attribute__((aligned(16))) int s_all[];
   const int lane = threadIdx.x & 63;
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  for (int t = w; t < T; t += kRouterWaves) {
+  // the scores of both tokens a wavefront may have (T <= 32) are requested before either is ranked
+  float raw[2][4];
+#pragma unroll
+  for (int r = 0; r < 2; ++r)
+    if (w + r * kRouterWaves < T) topk_load_row<4>(logits + (size_t)(w + r * kRouterWaves) * E, E, lane, raw[r]);
+#pragma unroll
+  for (int r = 0; r < 2; ++r) {
+    const int t = w + r * kRouterWaves;
+    if (t >= T) break;
     int idx;
     float wv;
-    topk_wave_regs<4>(logits + (size_t)t * E, E, k, norm, lane, &idx, &wv);
+    topk_wave_regs<4>(raw[r], E, k, norm, lane, &idx, &wv);
     if (lane < k) {
       s_all[t * k + lane] = idx;  // where expert_union_body expects the pairs
       topk_idx[(size_t)t * k + lane] = idx;

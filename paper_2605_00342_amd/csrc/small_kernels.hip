@@ -193,6 +193,94 @@ __global__ __launch_bounds__(kSelThreads) void select_prefix_kernel(
   }
 }
 
+// One tree of at most 64 nodes in one wavefront, node i in lane i, everything in registers and
+// cross-lane operations: the same arithmetic in the same order as select_prefix_kernel (one
+// rounded multiply per node top-down, ranking by (score descending, index ascending), sequential
+// fp32 running sum, IEEE division, first maximum), without LDS round trips and barriers.
+__global__ __launch_bounds__(64) void select_prefix_wave_kernel(
+    const int32_t* __restrict__ parent, const float* __restrict__ prob, const float* __restrict__ cost, int kmax, int n,
+    float rho, int32_t* __restrict__ k_star, float* __restrict__ est_len, int32_t* __restrict__ order_out,
+    float* __restrict__ psum_out, int32_t* __restrict__ keep, int32_t* __restrict__ new_parent,
+    int32_t* __restrict__ new_tree_off) {
+  const int lane = threadIdx.x;
+  const bool live = lane < n;
+  int p = -1;
+  float q = 0.0f, c = 1.0f;
+  if (live) {
+    p = parent[lane];
+    q = prob[lane];
+    if (cost && lane < kmax) c = cost[lane + 1];  // C(lane + 1)
+    if (lane == 0) p = -1;
+    else if (p < 0 || p >= lane) p = 0;  // invalid ids are clamped (the host check rejects them)
+  }
+  // depth by walking up in lock step
+  int dep = 0, a = p;
+  while (__ballot(a >= 0)) {
+    const int up = __shfl(p, a < 0 ? 0 : a);
+    if (a >= 0) { ++dep; a = up; }
+  }
+  int maxdep = dep;
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) {
+    const int other = __shfl_xor(maxdep, o);
+    maxdep = other > maxdep ? other : maxdep;
+  }
+  // Score(v) = Score(parent(v)) * q(v), level by level (Eq. 7); the root counts as probability 1
+  float sc = lane == 0 ? 1.0f : 0.0f;
+  for (int lvl = 1; lvl <= maxdep; ++lvl) {
+    const float sp = __shfl(sc, p < 0 ? 0 : p);
+    if (live && dep == lvl) sc = __fmul_rn(sp, q);
+  }
+  // rank by (score descending, index ascending); lanes past the tree keep their own position
+  int r = lane;
+  if (live) r = 0;
+  const int sbits = __float_as_int(sc);
+  for (int j = 0; j < n; ++j) {
+    const float sj = __int_as_float(__builtin_amdgcn_readlane(sbits, j));
+    if (live) r += (sj > sc || (sj == sc && j < lane)) ? 1 : 0;
+  }
+  if (live && order_out) order_out[r] = lane;
+  // scores in rank order: lane i sends its score to lane r
+  const int sorted_bits = __builtin_amdgcn_ds_permute(r << 2, live ? sbits : 0);
+  // S_k: sequential fp32 running sum over the ranking
+  float acc = 0.0f, S = 0.0f;
+  for (int j = 0; j < n; ++j) {
+    acc = __fadd_rn(acc, __int_as_float(__builtin_amdgcn_readlane(sorted_bits, j)));
+    if (lane == j) S = acc;
+  }
+  if (live && psum_out) psum_out[lane] = S;
+  const int kk = n < kmax ? n : kmax;
+  const float total = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(S), n - 1));
+  float bv = -1.0f;
+  int bi = 0x7fffffff;
+  if (lane < kk) {
+    bv = rho >= 0.0f ? (__fdiv_rn(S, total) >= rho ? 1.0f : 0.0f) : __fdiv_rn(S, c);
+    bi = lane;
+  }
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) {
+    const float ov = __shfl_xor(bv, o);
+    const int oi = __shfl_xor(bi, o);
+    if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+  }
+  if (rho >= 0.0f && bv == 0.0f) bi = kk - 1;  // coverage not reached within kmax: the whole budget
+  const int kstar = bi + 1;
+  const float est = __shfl(S, bi);
+  // kept nodes ascending, parents re-indexed by counting kept nodes below
+  const unsigned long long kept = __ballot(live && r < kstar);
+  if (live && r < kstar) {
+    const int ni = __popcll(kept & ((1ull << lane) - 1ull));
+    keep[ni] = lane;
+    new_parent[ni] = p < 0 ? -1 : __popcll(kept & ((1ull << p) - 1ull));
+  }
+  if (lane == 0) {
+    k_star[0] = kstar;
+    est_len[0] = est;
+    new_tree_off[0] = 0;
+    new_tree_off[1] = kstar;
+  }
+}
+
 // Second step for batches: one workgroup walks the trees in order, so that tree b's
 // compacted output (which starts at or before tree b's own input offset) never overwrites
 // ranks of a tree not yet read. rank_ws aliases new_parent.
@@ -616,8 +704,12 @@ static int select_prefix_impl(const char* who, const int32_t* tree_off, const in
                 EVICT_MAX_SELECT_NODES);
   hipStream_t s = (hipStream_t)stream;
   const int single = B == 1;
-  // trees of at most 64 nodes are handled by a single wavefront per tree
-  const int sel_threads = (B == 1 && T <= 64) ? 64 : kSelThreads;
+  if (B == 1 && T <= 64) {  // one small tree: the single-wavefront register kernel
+    hipLaunchKernelGGL(select_prefix_wave_kernel, dim3(1), dim3(64), 0, s, parent, node_prob, cost, Kmax, T, rho, k_star,
+                       est_len, order, prefix_sum, keep, new_parent, new_tree_off);
+    return launch_status("select_prefix_wave_kernel");
+  }
+  const int sel_threads = kSelThreads;
   hipLaunchKernelGGL(select_prefix_kernel, dim3(B), dim3(sel_threads), 0, s, tree_off, parent, node_prob, cost, Kmax,
                      k_star, est_len, order, prefix_sum, new_parent /* rank workspace */, single, keep, new_parent,
                      new_tree_off, single ? T : 0, rho);
