@@ -74,28 +74,42 @@ template <> __device__ __forceinline__ f32x4 mfma_block<F32>(u32x4 a, u32x4 b, f
   return c;
 }
 
+// Wavefront-wide sum / maximum of a float through DPP row operations (no LDS traffic): butterflies
+// inside each row of 16 lanes, then row broadcasts into the later rows; the total ends up in the
+// last lane and is returned to every lane as a scalar. Lanes a step leaves out read the identity.
+#define EVICT_DPP_F32(old_, v_, ctrl_, rows_) \
+  __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(old_), __float_as_int(v_), ctrl_, rows_, 0xF, false))
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o);
-  return v;
+  v += EVICT_DPP_F32(0.0f, v, 0xB1, 0xF);   // quad_perm [1,0,3,2]
+  v += EVICT_DPP_F32(0.0f, v, 0x4E, 0xF);   // quad_perm [2,3,0,1]
+  v += EVICT_DPP_F32(0.0f, v, 0x141, 0xF);  // row_half_mirror
+  v += EVICT_DPP_F32(0.0f, v, 0x140, 0xF);  // row_mirror
+  v += EVICT_DPP_F32(0.0f, v, 0x142, 0xA);  // row_bcast:15 into rows 1, 3
+  v += EVICT_DPP_F32(0.0f, v, 0x143, 0xC);  // row_bcast:31 into rows 2, 3
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
-  return v;
+  v = fmaxf(v, EVICT_DPP_F32(-INFINITY, v, 0xB1, 0xF));
+  v = fmaxf(v, EVICT_DPP_F32(-INFINITY, v, 0x4E, 0xF));
+  v = fmaxf(v, EVICT_DPP_F32(-INFINITY, v, 0x141, 0xF));
+  v = fmaxf(v, EVICT_DPP_F32(-INFINITY, v, 0x140, 0xF));
+  v = fmaxf(v, EVICT_DPP_F32(-INFINITY, v, 0x142, 0xA));
+  v = fmaxf(v, EVICT_DPP_F32(-INFINITY, v, 0x143, 0xC));
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
 // Wavefront-wide maximum of an unsigned value through DPP row operations (no LDS traffic):
 // butterflies inside each row of 16 lanes, then row broadcasts; the result is read from the
-// last lane as a scalar.
+// last lane as a scalar. (Lanes a DPP step leaves out read 0, the identity of an unsigned maximum,
+// which lets the compiler fold each step into a single v_max_u32 with a DPP operand.)
 __device__ __forceinline__ unsigned wave_max_u32(unsigned v) {
   auto mx = [](unsigned a, unsigned b) { return a > b ? a : b; };
-  v = mx(v, (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0xB1, 0xF, 0xF, false));   // quad_perm [1,0,3,2]
-  v = mx(v, (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x4E, 0xF, 0xF, false));   // quad_perm [2,3,0,1]
-  v = mx(v, (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x141, 0xF, 0xF, false));  // row_half_mirror
-  v = mx(v, (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x140, 0xF, 0xF, false));  // row_mirror
-  v = mx(v, (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x142, 0xA, 0xF, false));  // row_bcast:15 into rows 1, 3
-  v = mx(v, (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x143, 0xC, 0xF, false));  // row_bcast:31 into rows 2, 3
+  v = mx(v, (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, false));   // quad_perm [1,0,3,2]
+  v = mx(v, (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, false));   // quad_perm [2,3,0,1]
+  v = mx(v, (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xF, 0xF, false));  // row_half_mirror
+  v = mx(v, (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x140, 0xF, 0xF, false));  // row_mirror
+  v = mx(v, (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xA, 0xF, false));  // row_bcast:15 into rows 1, 3
+  v = mx(v, (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xC, 0xF, false));  // row_bcast:31 into rows 2, 3
   return (unsigned)__builtin_amdgcn_readlane((int)v, 63);
 }
 

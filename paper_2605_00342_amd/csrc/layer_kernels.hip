@@ -807,28 +807,33 @@ __global__ __launch_bounds__(kRouterThreads) void topk_kernel(
 // TopK of one token by one wavefront with the scores held in registers (E <= 64 * NR): the same
 // selection rule as topk_kernel, without the LDS round trips. Lane j ends up with the j-th pick.
 // Returns the expert index picked at position `lane` (for lane < k) and its softmax weight.
+// Lane l holds the NR consecutive experts l*NR .. l*NR + NR - 1 (E <= 64 * NR).
 template <int NR>
 __device__ __forceinline__ void topk_load_row(const float* __restrict__ row, int E, int lane, float (&raw)[NR]) {
 #pragma unroll
   for (int i = 0; i < NR; ++i) {
-    const int e = i * 64 + lane;
+    const int e = lane * NR + i;
     raw[i] = e < E ? row[e] : 0.0f;
   }
 }
 
+// The work of this routine is all instruction issue (16 wavefronts of a workgroup share 4 SIMDs),
+// so a pick is kept short: lane maximum, wavefront maximum (DPP), one ballot for the lowest lane
+// holding it, and that lane alone finds and retires its lowest such expert. With experts laid out
+// consecutively per lane, lowest lane then lowest register is the lowest expert index.
 template <int NR>
 __device__ __forceinline__ void topk_wave_regs(const float (&raw)[NR], int E, int k, int norm, int lane, int* my_idx,
                                                float* my_w) {
   unsigned key[NR];
 #pragma unroll
   for (int i = 0; i < NR; ++i) {
-    const int e = i * 64 + lane;
+    const int e = lane * NR + i;
     unsigned o = 0u;
     if (e < E) {
       unsigned bits = __float_as_uint(raw[i]);
-      bits = bits == 0x80000000u ? 0u : bits;
+      bits = bits == 0x80000000u ? 0u : bits;  // -0 and +0 compare equal
       o = bits ^ ((bits >> 31) ? 0xFFFFFFFFu : 0x80000000u);
-      o = o == 0u ? 1u : o;
+      o = o == 0u ? 1u : o;  // 0 marks "taken" (below every key)
     }
     key[i] = o;
   }
@@ -840,15 +845,16 @@ __device__ __forceinline__ void topk_wave_regs(const float (&raw)[NR], int E, in
 #pragma unroll
     for (int i = 1; i < NR; ++i) local = key[i] > local ? key[i] : local;
     const unsigned best = wave_max_u32(local);
-    int sel = -1;
+    const unsigned long long m = __ballot(local == best);
+    const int wl = (int)__ffsll((long long)m) - 1;  // lowest lane holding the maximum
+    int hit = 0;
+    if (lane == wl) {
+      bool done = false;
 #pragma unroll
-    for (int i = 0; i < NR; ++i) {
-      const unsigned long long m = __ballot(key[i] == best);
-      if (sel < 0 && m) sel = i * 64 + (int)__ffsll((long long)m) - 1;
+      for (int i = 0; i < NR; ++i)
+        if (!done && key[i] == best) { key[i] = 0u; hit = i; done = true; }
     }
-#pragma unroll
-    for (int i = 0; i < NR; ++i)
-      if (i * 64 + lane == sel) key[i] = 0u;
+    const int sel = wl * NR + __builtin_amdgcn_readlane(hit, wl);
     if (lane == j) { mine = best; mine_idx = sel; }
   }
   const float val = __uint_as_float(mine ^ ((mine >> 31) ? 0x80000000u : 0xFFFFFFFFu));
@@ -869,9 +875,15 @@ __global__ __launch_bounds__(kRouterThreads) void topk_regs_kernel(
   if (t >= T) return;
   int idx;
   float wv;
-  float raw[4];
-  topk_load_row<4>(logits + (size_t)t * E, E, lane, raw);
-  topk_wave_regs<4>(raw, E, k, norm, lane, &idx, &wv);
+  if (E <= 128) {
+    float raw[2];
+    topk_load_row<2>(logits + (size_t)t * E, E, lane, raw);
+    topk_wave_regs<2>(raw, E, k, norm, lane, &idx, &wv);
+  } else {
+    float raw[4];
+    topk_load_row<4>(logits + (size_t)t * E, E, lane, raw);
+    topk_wave_regs<4>(raw, E, k, norm, lane, &idx, &wv);
+  }
   if (lane < k) {
     topk_idx[(size_t)t * k + lane] = idx;
     topk_w[(size_t)t * k + lane] = wv;
@@ -895,14 +907,27 @@ __global__ __launch_bounds__(kRouterThreads) void topk_union_kernel(
   float raw[2][4];
 #pragma unroll
   for (int r = 0; r < 2; ++r)
-    if (w + r * kRouterWaves < T) topk_load_row<4>(logits + (size_t)(w + r * kRouterWaves) * E, E, lane, raw[r]);
+    if (w + r * kRouterWaves < T) {
+      if (E <= 128) {
+        float r2[2];
+        topk_load_row<2>(logits + (size_t)(w + r * kRouterWaves) * E, E, lane, r2);
+        raw[r][0] = r2[0]; raw[r][1] = r2[1];
+      } else {
+        topk_load_row<4>(logits + (size_t)(w + r * kRouterWaves) * E, E, lane, raw[r]);
+      }
+    }
 #pragma unroll
   for (int r = 0; r < 2; ++r) {
     const int t = w + r * kRouterWaves;
     if (t >= T) break;
     int idx;
     float wv;
-    topk_wave_regs<4>(raw[r], E, k, norm, lane, &idx, &wv);
+    if (E <= 128) {
+      const float r2[2] = {raw[r][0], raw[r][1]};
+      topk_wave_regs<2>(r2, E, k, norm, lane, &idx, &wv);
+    } else {
+      topk_wave_regs<4>(raw[r], E, k, norm, lane, &idx, &wv);
+    }
     if (lane < k) {
       s_all[t * k + lane] = idx;  // where expert_union_body expects the pairs
       topk_idx[(size_t)t * k + lane] = idx;
