@@ -98,6 +98,22 @@ __device__ __forceinline__ float wave_max(float v) {
   return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
+// Sum / maximum over each row of 16 lanes, result in every lane of the row (four DPP butterflies).
+__device__ __forceinline__ float row16_sum(float v) {
+  v += EVICT_DPP_F32(0.0f, v, 0xB1, 0xF);
+  v += EVICT_DPP_F32(0.0f, v, 0x4E, 0xF);
+  v += EVICT_DPP_F32(0.0f, v, 0x141, 0xF);
+  v += EVICT_DPP_F32(0.0f, v, 0x140, 0xF);
+  return v;
+}
+__device__ __forceinline__ float row16_max(float v) {
+  v = fmaxf(v, EVICT_DPP_F32(-INFINITY, v, 0xB1, 0xF));
+  v = fmaxf(v, EVICT_DPP_F32(-INFINITY, v, 0x4E, 0xF));
+  v = fmaxf(v, EVICT_DPP_F32(-INFINITY, v, 0x141, 0xF));
+  v = fmaxf(v, EVICT_DPP_F32(-INFINITY, v, 0x140, 0xF));
+  return v;
+}
+
 // Wavefront-wide maximum of an unsigned value through DPP row operations (no LDS traffic):
 // butterflies inside each row of 16 lanes, then row broadcasts; the result is read from the
 // last lane as a scalar. (Lanes a DPP step leaves out read 0, the identity of an unsigned maximum,

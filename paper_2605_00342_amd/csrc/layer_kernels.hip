@@ -583,13 +583,15 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict
   // global maximum and normaliser: the lanes of a row share the splits between them
   float M = -INFINITY;
   for (int sp = c4; sp < nsplits; sp += lpr) M = fmaxf(M, pml[(size_t)sp * rows * 2]);
-  for (int o = 1; o < lpr; o <<= 1) M = fmaxf(M, __shfl_xor(M, o));
+  M = row16_max(M);  // lpr is 16 or 32: DPP inside the rows of 16, one shuffle across the pair
+  if (lpr == 32) M = fmaxf(M, __shfl_xor(M, 16));
   float l = 0.0f;
   for (int sp = c4; sp < nsplits; sp += lpr) {
     const float2 ml = *reinterpret_cast<const float2*>(pml + (size_t)sp * rows * 2);
     l += ml.x == -INFINITY ? 0.0f : ml.y * __expf(ml.x - M);
   }
-  for (int o = 1; o < lpr; o <<= 1) l += __shfl_xor(l, o);
+  l = row16_sum(l);
+  if (lpr == 32) l += __shfl_xor(l, 16);
   f32x4 acc = {0, 0, 0, 0};
   for (int s0 = 0; s0 < nsplits; s0 += kMergeBatch) {
     if (s0 > 0) {
