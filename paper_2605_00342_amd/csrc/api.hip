@@ -440,11 +440,11 @@ int evict_lm_head_argmax(evict_ctx* ctx, const void* x, const void* g_final, con
   a.T = T;
   a.out0 = ctx->lm_val;
   a.out1 = ctx->lm_idx;
-  a.ldo = T;
+  a.ldo = a.n_strips;
   a.dense_tiles = (T + 15) / 16;
   rc = launch_gemm(m.dtype, EPI_ARGMAX, a, 1, ((a.n_strips + 7) / 8) * 8 * a.dense_tiles, s);
   if (rc) return rc;
-  return launch_argmax_reduce(ctx->lm_val, ctx->lm_idx, a.n_strips, T, T, next, best_logit, s);
+  return launch_argmax_reduce(ctx->lm_val, ctx->lm_idx, a.n_strips, a.n_strips, T, next, best_logit, s);
 }
 
 int evict_lm_head_logits(evict_ctx* ctx, const void* x, const void* g_final, const void* wlm_packed, int T, float* logits,

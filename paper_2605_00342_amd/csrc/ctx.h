@@ -41,8 +41,8 @@ struct evict_ctx {
   int32_t* tok_of_pos;   // [T*k] token of each grouped position
   void* act;             // [T*k + n_shared*T][F] storage dtype (routed pairs, then shared experts x tokens)
   float* y;              // [T*k + n_shared*T][d]
-  float* lm_val;         // [vocab/16][T] best logit per strip and token
-  int32_t* lm_idx;       // [vocab/16][T]
+  float* lm_val;         // [T][vocab/16] best logit per token and strip
+  int32_t* lm_idx;       // [T][vocab/16]
   float* samp_stats;     // [T][2] per node: max logit, sum of exp((logit - max) / temperature)
   void* stack_buf[2];    // [T][d] ping-pong hidden states of evict_verify_stack
   hipEvent_t prof_ev[2]; // evict_profile_cost

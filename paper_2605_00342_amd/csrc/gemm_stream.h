@@ -49,7 +49,7 @@ struct GemmArgs {
   int prefetch;          // host-side choice of the kernel variant (weight-load stages), 0 = default
   int wave_strip;        // host-side: grouped fp32-output GEMM may use gemm_wave_strip_kernel
   int plain_loads;       // 1: never use non-temporal weight loads (measurement knob)
-  void* out0;            // QKV: q; RESID: h; SWIGLU: act; F32: y; ARGMAX: best value per (strip, token)
+  void* out0;            // QKV: q; RESID: h; SWIGLU: act; F32: y; ARGMAX: best value per (token, strip), [T][ldo]
   void* out1;            // QKV: k_new; ARGMAX: row index of the best value per (strip, token)
   void* out2;            // QKV: v_new
   long long ldo;         // elements between output rows (RESID / SWIGLU / F32)
@@ -252,8 +252,8 @@ __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(NT
                       if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
                     }
                     if (valid && lane < 16) {
-                      ((float*)a.out0)[(long long)strip * a.ldo + col] = bv;
-                      ((int*)a.out1)[(long long)strip * a.ldo + col] = bi;
+                      ((float*)a.out0)[(long long)col * a.ldo + strip] = bv;
+                      ((int*)a.out1)[(long long)col * a.ldo + strip] = bi;
                     }
                   } else if (EPI == EPI_F32) {
                     if (valid) {

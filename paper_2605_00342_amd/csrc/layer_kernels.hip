@@ -966,10 +966,21 @@ __global__ __launch_bounds__(256) void argmax_reduce_kernel(const float* __restr
   const int t = blockIdx.x, tid = threadIdx.x;
   float bv = -INFINITY;
   int bi = 0x7fffffff;
-  for (int s = tid; s < nstrips; s += 256) {
-    const float v = val[(size_t)s * ld + t];
-    const int i = idx[(size_t)s * ld + t];
-    if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
+  // candidates of a token are contiguous ([T][ld] with ld >= nstrips): eight loads in flight per thread
+  const float* vrow = val + (size_t)t * ld;
+  const int32_t* irow = idx + (size_t)t * ld;
+  for (int s0 = tid; s0 < nstrips; s0 += 256 * 8) {
+    float v[8];
+    int i[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int s = s0 + 256 * u;
+      v[u] = s < nstrips ? vrow[s] : -INFINITY;
+      i[u] = s < nstrips ? irow[s] : 0x7fffffff;
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (v[u] > bv || (v[u] == bv && i[u] < bi)) { bv = v[u]; bi = i[u]; }
   }
 #pragma unroll
   for (int o = 32; o >= 1; o >>= 1) {
