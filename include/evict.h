@@ -278,6 +278,9 @@ int evict_device_status(evict_ctx* ctx, int32_t* status_host, void* stream);
  *   "moe_prefetch"    1 or 2 weight-load stages in flight per wavefront in the gate/up GEMM
  *   "moe_chunk_gateup", "moe_chunk_down"  units (16-row strips; strip pairs for gate/up) a
  *                     workgroup takes from the device-side work list at a time
+ *   "moe_gateup_kernel" 1: gate/up projections with one (gate, up) strip pair per wavefront and the token
+ *                     operand in LDS; 0: contraction split over the wavefronts of a workgroup; 2 = auto
+ *                     (the former from 128 tokens on)
  *   "moe_down_kernel" 1: down projections with one 16-row strip per wavefront over the whole
  *                     contraction range (token operand staged in LDS); 0: contraction split
  *                     over the wavefronts of a workgroup like the other GEMMs

@@ -121,6 +121,7 @@ int evict_create(evict_ctx** out, const evict_model_desc* m, int max_tokens, int
   c.moe_grid = 2048;
   c.moe_prefetch = 1;
   c.moe_down_kernel = 1;
+  c.moe_gateup_kernel = 2;
   c.moe_plain_loads = 0;
   c.dense_nt = 0;
   c.attn_target_wgs = 512;
@@ -347,6 +348,8 @@ static int verify_layer_impl(evict_ctx* ctx, const evict_layer_weights* w, const
     a.ldo = m.F;
     a.prefetch = ctx->moe_prefetch;
     a.plain_loads = ctx->moe_plain_loads;
+    // (one strip pair per wavefront pays once experts mostly have several token tiles: measured from 128 tokens on)
+    a.wave_strip = ctx->moe_gateup_kernel == 2 ? (T >= 128 ? 1 : 0) : ctx->moe_gateup_kernel;
     a.chunk_units = ctx->moe_chunk_gateup;
     rc = launch_gemm(m.dtype, EPI_SWIGLU, a, nt_exp, ctx->moe_grid, s);
     if (rc) return rc;
@@ -532,6 +535,9 @@ int evict_tune(evict_ctx* ctx, const char* key, int value) {
   } else if (!strcmp(key, "moe_plain_loads")) {
     EVICT_REQUIRE(value == 0 || value == 1, EVICT_E_INVALID, "evict_tune: moe_plain_loads must be 0 or 1");
     ctx->moe_plain_loads = value;
+  } else if (!strcmp(key, "moe_gateup_kernel")) {
+    EVICT_REQUIRE(value >= 0 && value <= 2, EVICT_E_INVALID, "evict_tune: moe_gateup_kernel must be 0, 1 or 2 (auto)");
+    ctx->moe_gateup_kernel = value;
   } else if (!strcmp(key, "moe_down_kernel")) {
     EVICT_REQUIRE(value == 0 || value == 1, EVICT_E_INVALID, "evict_tune: moe_down_kernel must be 0 or 1");
     ctx->moe_down_kernel = value;

@@ -351,12 +351,16 @@ __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(NT
 // per slot (the work list is built with tiles of 16 * NTW tokens).
 // LDS: NTW * nkb KiB (dynamic).
 // ------------------------------------------------------------------------------------
-template <typename ST, int WIN, int NB, bool EXACT, int NTW = 1, int WS = 8>
+// NKB > 0 fixes the number of contraction blocks at compile time: every loop between the issue of
+// a weight load and its use is then fully unrolled, which is what lets the compiler wait for a
+// load by its exact position in the in-order queue (with run-time trip counts it has to drain the
+// queue before the first MFMA, and the window stops rolling).
+template <typename ST, int WIN, int NB, bool EXACT, int NTW = 1, int WS = 8, int NKB = 0>
 __global__ __launch_bounds__(WS * 64) __attribute__((amdgpu_waves_per_eu(4))) void gemm_wave_strip_kernel(const GemmArgs a) {
   extern __shared__ __attribute__((aligned(16))) u32x4 s_b[];  // [NTW token tiles][nkb][64]
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int nkb = a.nkb;
+  const int nkb = NKB > 0 ? NKB : a.nkb;
   const int cpg = a.n_strips / WS;  // chunks per slot (host-checked: divides)
   const int total = *a.union_count * cpg;
   bool first = true;
@@ -382,7 +386,8 @@ __global__ __launch_bounds__(WS * 64) __attribute__((amdgpu_waves_per_eu(4))) vo
     constexpr int BMAX = NB;  // operand blocks a wavefront stages per pass and token tile
     const u32x4* wp = wbase + (long long)strip * nkb * 64 + lane;
     u32x4 A[WIN];
-    for (int kb0 = 0; kb0 < nkb; kb0 += BMAX * WS) {
+#pragma unroll
+    for (int kb0 = 0; kb0 < (NKB > 0 ? NKB : nkb); kb0 += BMAX * WS) {
       u32x4 bst[NTW][BMAX];
 #pragma unroll
       for (int t = 0; t < NTW; ++t)
@@ -410,7 +415,8 @@ __global__ __launch_bounds__(WS * 64) __attribute__((amdgpu_waves_per_eu(4))) vo
     f32x4 acc[NTW];
 #pragma unroll
     for (int t = 0; t < NTW; ++t) acc[t] = f32x4{0, 0, 0, 0};
-    for (int j0 = 0; j0 < nkb; j0 += WIN) {
+#pragma unroll
+    for (int j0 = 0; j0 < (NKB > 0 ? NKB : nkb); j0 += WIN) {
 #pragma unroll
       for (int jj = 0; jj < WIN; ++jj) {
         const int j = j0 + jj;
@@ -418,6 +424,7 @@ __global__ __launch_bounds__(WS * 64) __attribute__((amdgpu_waves_per_eu(4))) vo
 #pragma unroll
           for (int t = 0; t < NTW; ++t) acc[t] = mfma_block<ST>(A[jj], s_b[((size_t)t * nkb + j) * 64 + lane], acc[t]);
           if (j + WIN < nkb) A[jj] = once ? __builtin_nontemporal_load(wp + (j + WIN) * 64) : wp[(j + WIN) * 64];
+          if (NKB > 0) __builtin_amdgcn_sched_barrier(0);  // keep the refill right behind its MFMA: the window stays full
         }
       }
     }
@@ -425,6 +432,97 @@ __global__ __launch_bounds__(WS * 64) __attribute__((amdgpu_waves_per_eu(4))) vo
     for (int t = 0; t < NTW; ++t)
       if (valid[t])
         *reinterpret_cast<f32x4*>((float*)a.out0 + (p0 + t * 16 + (lane & 15)) * a.ldo + strip * 16 + (lane >> 4) * 4) = acc[t];
+  }
+}
+
+// ------------------------------------------------------------------------------------
+// The same decomposition for the gate/up projections: one (gate strip, up strip) pair per
+// wavefront over the whole contraction range (2 x nkb KiB of weights per wavefront and unit),
+// the 16 x d token operand of the slot in LDS, two rolling windows of WIN weight blocks (one per
+// strip; a token operand block read from LDS feeds both MFMAs), SiLU(g) * u applied in the
+// wavefront that owns the pair. WS wavefronts per workgroup share the staged operand; a
+// workgroup lives for WS * 2 * nkb KiB of weights, so the stream has no exchange points.
+// Requires nkb % WIN == 0, (n_strips / 2) % WS == 0, nkb KiB of LDS. Refills go out in runs of 8
+// consecutive blocks per strip once the window is 16 deep.
+// ------------------------------------------------------------------------------------
+template <typename ST, int WIN, int NB, int WS, int NKB = 0>
+__global__ __launch_bounds__(WS * 64) __attribute__((amdgpu_waves_per_eu(2))) void gemm_wave_gateup_kernel(const GemmArgs a) {
+  extern __shared__ __attribute__((aligned(16))) u32x4 s_b[];  // [nkb][64]
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int nkb = NKB > 0 ? NKB : a.nkb;
+  const int cpg = (a.n_strips >> 1) / WS;  // chunks per slot
+  const int total = *a.union_count * cpg;
+  bool first = true;
+  for (int chunk = blockIdx.x; chunk < total; chunk += gridDim.x) {
+    const int slot = chunk / cpg, unit = (chunk - slot * cpg) * WS + w;
+    const WorkRec* rec = a.work + slot;
+    const int lc = lane & 15;
+    const int tok_early = rec->tok[lc < kWorkToks ? lc : kWorkToks - 1];
+    const int p0 = rec->p0, ntok = rec->ntok, ex = rec->expert;
+    const bool once = !a.plain_loads && (rec->pad & 0xFFFF) == 1;
+    const u32x4* wbase = ex < a.n_routed ? a.W + (long long)ex * a.group_stride
+                                         : a.W_shared + (long long)(ex - a.n_routed) * a.group_stride;
+    const bool valid = lc < ntok;
+    const int col = valid ? lc : ntok - 1;  // padded columns repeat the last token; never stored
+    long long xr = p0 + col;
+    if (a.x_by_token) xr = col < kWorkToks ? tok_early : a.tok_of_pos[p0 + col];
+    const char* xrow = (const char*)a.X + xr * a.ldx_bytes + (lane >> 4) * 16;
+    // token operand blocks first, weights behind them (the in-order load counter lets the
+    // operand be consumed while the weight windows are still in flight)
+    u32x4 bst[NB];
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+      const int kb = i * WS + w;
+      if (kb < nkb) bst[i] = *reinterpret_cast<const u32x4*>(xrow + (long long)kb * 64);
+    }
+    const u32x4* wg = wbase + (long long)(2 * unit) * nkb * 64 + lane;
+    const u32x4* wu = wg + (long long)nkb * 64;
+    u32x4 Ag[WIN], Au[WIN];
+#pragma unroll
+    for (int j = 0; j < WIN; ++j) {
+      Ag[j] = once ? __builtin_nontemporal_load(wg + j * 64) : wg[j * 64];
+      Au[j] = once ? __builtin_nontemporal_load(wu + j * 64) : wu[j * 64];
+    }
+    if (!first) lds_barrier();  // every wavefront is done with the previous chunk's operand
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+      const int kb = i * WS + w;
+      if (kb < nkb) s_b[kb * 64 + lane] = bst[i];
+    }
+    lds_barrier();
+    first = false;
+    f32x4 accg = {0, 0, 0, 0}, accu = {0, 0, 0, 0};
+    constexpr int BURST = WIN >= 16 ? 8 : WIN;  // consecutive blocks requested together (DRAM likes runs)
+#pragma unroll
+    for (int j0 = 0; j0 < (NKB > 0 ? NKB : nkb); j0 += WIN) {
+#pragma unroll
+      for (int jj = 0; jj < WIN; ++jj) {
+        const int j = j0 + jj;
+        const u32x4 bf = s_b[j * 64 + lane];
+        accg = mfma_block<ST>(Ag[jj], bf, accg);
+        accu = mfma_block<ST>(Au[jj], bf, accu);
+        if ((jj % BURST) == BURST - 1) {
+          // the BURST window entries just consumed are refilled with the blocks WIN further on
+          const int r0 = jj - (BURST - 1);
+          if (j0 + r0 + WIN < nkb) {
+#pragma unroll
+            for (int r = 0; r < BURST; ++r)
+              Ag[r0 + r] = once ? __builtin_nontemporal_load(wg + (j0 + r0 + r + WIN) * 64) : wg[(j0 + r0 + r + WIN) * 64];
+#pragma unroll
+            for (int r = 0; r < BURST; ++r)
+              Au[r0 + r] = once ? __builtin_nontemporal_load(wu + (j0 + r0 + r + WIN) * 64) : wu[(j0 + r0 + r + WIN) * 64];
+          }
+          if (NKB > 0) __builtin_amdgcn_sched_barrier(0);  // keep the refills where they are: the windows stay full
+        }
+      }
+    }
+    if (valid) {
+      f32x4 r4;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) r4[i] = (accg[i] / (1.0f + __expf(-accg[i]))) * accu[i];
+      store4<ST>(a.out0, (long long)(p0 + lc) * a.ldo + unit * 16 + (lane >> 4) * 4, r4);
+    }
   }
 }
 

@@ -1139,7 +1139,10 @@ int launch_gemm_wave_strip(const GemmArgs& a, int grid, hipStream_t s) {
 #define EVICT_WS_LAUNCH(WIN_, NB_, EXACT_) \
   hipLaunchKernelGGL((gemm_wave_strip_kernel<ST, WIN_, NB_, EXACT_, NTW>), dim3(grid), dim3(8 * 64), lds, s, a)
   // (windows sized to stay under 128 VGPRs together with the staged operand blocks)
-  if (nkb == 24) EVICT_WS_LAUNCH(12, 3, true);
+  if (nkb == 24)
+    hipLaunchKernelGGL((gemm_wave_strip_kernel<ST, 12, 3, true, NTW, 8, 24>), dim3(grid), dim3(8 * 64), lds, s, a);
+  else if (nkb == 44 && NTW == 1)
+    hipLaunchKernelGGL((gemm_wave_strip_kernel<ST, 11, 6, true, 1, 8, 44>), dim3(grid), dim3(8 * 64), lds, s, a);
   else if (nkb == 44) EVICT_WS_LAUNCH(11, 6 / NTW, true);
   else if (nkb % 16 == 0) EVICT_WS_LAUNCH(16, 4 / NTW, true);
   else if (nkb % 8 == 0) EVICT_WS_LAUNCH(8, 2 / NTW, true);
@@ -1148,10 +1151,32 @@ int launch_gemm_wave_strip(const GemmArgs& a, int grid, hipStream_t s) {
   return launch_status("gemm_wave_strip_kernel");
 }
 
+// one gate/up strip pair per wavefront (see gemm_wave_gateup_kernel)
+constexpr int kGateupWaves = 4;
+bool wave_gateup_applies(const GemmArgs& a, int nt) {
+  return a.grouped && nt == 1 && a.nkb % 8 == 0 && a.nkb <= 64 && (a.n_strips / 2) % kGateupWaves == 0;
+}
+template <typename ST>
+int launch_gemm_wave_gateup(const GemmArgs& a, int grid, hipStream_t s) {
+  const size_t lds = (size_t)a.nkb * 1024;
+  const int nb = (a.nkb + kGateupWaves - 1) / kGateupWaves;
+  if (ST::kBytes == 4 && nb > 8) return -1;  // (that variant would spill: the caller falls back)
+  if (nb <= 4) hipLaunchKernelGGL((gemm_wave_gateup_kernel<ST, 8, 4, kGateupWaves>), dim3(grid), dim3(kGateupWaves * 64), lds, s, a);
+  else if (nb <= 8) hipLaunchKernelGGL((gemm_wave_gateup_kernel<ST, 8, 8, kGateupWaves>), dim3(grid), dim3(kGateupWaves * 64), lds, s, a);
+  else if (a.nkb == 64)
+    hipLaunchKernelGGL((gemm_wave_gateup_kernel<ST, 16, 16, kGateupWaves, 64>), dim3(grid), dim3(kGateupWaves * 64), lds, s, a);
+  else hipLaunchKernelGGL((gemm_wave_gateup_kernel<ST, 8, 16, kGateupWaves>), dim3(grid), dim3(kGateupWaves * 64), lds, s, a);
+  return launch_status("gemm_wave_gateup_kernel");
+}
+
 bool wave_strip_applies(const GemmArgs& a, int nt) { return a.grouped && a.n_strips % 8 == 0 && a.nkb * nt <= 64; }
 
 template <typename ST, int EPI>
 int launch_gemm_st(const GemmArgs& a, int nt, int grid, hipStream_t s) {
+  if (EPI == EPI_SWIGLU && a.wave_strip && wave_gateup_applies(a, nt)) {
+    const int rc = launch_gemm_wave_gateup<ST>(a, grid, s);
+    if (rc >= 0) return rc;
+  }
   if (EPI == EPI_F32 && a.wave_strip && wave_strip_applies(a, nt))
     return nt == 1 ? launch_gemm_wave_strip<ST, 1>(a, grid, s) : launch_gemm_wave_strip<ST, 2>(a, grid, s);
   return nt == 1 ? launch_gemm_nt<ST, 1, EPI>(a, grid, s) : launch_gemm_nt<ST, 2, EPI>(a, grid, s);

@@ -166,6 +166,20 @@ def test_two_tile_work_list_slots():
         check_against_oracle(case, run_case(case, tune={"moe_nt": 2, "moe_down_kernel": 0}))
 
 
+def test_gateup_one_strip_pair_per_wavefront():
+    """The second gate/up decomposition (token operand in LDS, one strip pair per wavefront), forced through
+    evict_tune: multi-tile experts, shared experts, fp32 and bf16, 256 experts, and the full-size layer."""
+    cases = [synth.make_case("mini_bf16", n=40, L=16, seed=31, tree="star", sigma=0.0),
+             synth.make_case("mini_bf16", n=128, L=64, seed=14, tree="eagle"),
+             synth.make_case("tiny", n=70, L=20, seed=34, tree="bfs"),
+             synth.make_case("mini_sigmoid", n=90, L=33, seed=35, tree="bfs"),
+             synth.make_case("qwen3", n=32, L=300, seed=37)]
+    cfg = synth.ModelCfg("t_shared", "bf16", d=256, Hq=4, Hkv=4, D=64, E=16, k=3, F=128, n_shared=2, theta=1e4)
+    cases.append(synth.make_case("t_shared", n=50, L=50, seed=36, tree="bfs", cfg=cfg))
+    for case in cases:
+        check_against_oracle(case, run_case(case, tune={"moe_gateup_kernel": 1}))
+
+
 def test_chain_tree_equals_token_by_token_decode_on_gpu():
     # verifying a chain of n nodes equals n single-node verifications with a growing cache
     case = synth.make_case("tiny", n=5, L=30, seed=32, tree="chain")
