@@ -64,7 +64,9 @@ constexpr int kGemmThreads = kGemmWaves * 64;
 // KBW: 1 KiB blocks a wavefront takes per step (EXACT: every step has exactly KBW, no masking);
 // PF: steps of weight loads kept in flight; NT: 16-token tiles held in registers; IS: strips
 // taken per step (one partial-tile exchange per IS strips).
-template <typename ST, int NT, int KBW, int PF, int EPI, bool EXACT, int IS = 1>
+// NS > 0: steps per segment known at compile time (the step loop is unrolled, so the rolling refill of
+// the weight registers is unconditional and every wait is by exact queue position).
+template <typename ST, int NT, int KBW, int PF, int EPI, bool EXACT, int IS = 1, int NS = 0>
 __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 4 : 2))) void gemm_stream_kernel(const GemmArgs a) {
   constexpr int SPU = (EPI == EPI_SWIGLU) ? 2 : 1;  // strips per unit of work
   // expert weights are read exactly once per call: keep them out of the caches' way
@@ -99,7 +101,7 @@ __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(NT
       const int ex = rec->expert;
       wbase = ex < a.n_routed ? a.W + (long long)ex * a.group_stride : a.W_shared + (long long)(ex - a.n_routed) * a.group_stride;
     }
-    const int nsteps = (nitems / IS) * nchunks;  // nitems is a multiple of IS (host-checked)
+    const int nsteps = NS > 0 ? NS : (nitems / IS) * nchunks;  // nitems is a multiple of IS (host-checked)
 
     const int tok_end = ntok < tok_limit ? ntok : tok_limit;
     for (int tok0 = tok_begin; tok0 < tok_end; tok0 += 16 * NT) {
@@ -172,7 +174,8 @@ __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(NT
       };
       if (nchunks == 1) load_b(0);
 
-      for (int s0 = 0; s0 < nsteps; s0 += PF) {
+#pragma unroll
+      for (int s0 = 0; s0 < (NS > 0 ? NS : nsteps); s0 += PF) {
 #pragma unroll
         for (int r = 0; r < PF; ++r) {
           const int step = s0 + r;
@@ -205,15 +208,35 @@ __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(NT
             }
             int b0, nb;
             range(c, b0, nb);
+            if (EXACT && PF == 1 && NS > 0) {
+              // rolling refill: the block of the next step goes into a register as soon as the MFMA has
+              // consumed it, so about KBW loads stay in flight instead of falling to none at the end of
+              // a step (same registers; the queue position of every load stays known at compile time)
+              const bool more = step + 1 < nsteps;
+              const int itn = (step + 1) / nchunks, cn = (step + 1) - itn * nchunks;
+              const long long boff = (long long)(cn * 64 + w * KBW);
 #pragma unroll
-            for (int i = 0; i < IS; ++i)
+              for (int i = 0; i < IS; ++i) {
+                const u32x4* pn = wbase + ((long long)(strip0 + itn * IS + i) * nkb + boff) * 64 + lane;
 #pragma unroll
-              for (int j = 0; j < KBW; ++j)
-                if (EXACT || j < nb) {
+                for (int j = 0; j < KBW; ++j) {
 #pragma unroll
                   for (int t = 0; t < NT; ++t) acc[i][t] = mfma_block<ST>(A[r][i * KBW + j], Bf[t][j], acc[i][t]);
+                  if (more) A[r][i * KBW + j] = once ? __builtin_nontemporal_load(pn + j * 64) : pn[j * 64];
+                  __builtin_amdgcn_sched_barrier(0);  // the refill stays right behind its MFMA
                 }
-            if (step + PF < nsteps) issue(A[r], step + PF);
+              }
+            } else {
+#pragma unroll
+              for (int i = 0; i < IS; ++i)
+#pragma unroll
+                for (int j = 0; j < KBW; ++j)
+                  if (EXACT || j < nb) {
+#pragma unroll
+                    for (int t = 0; t < NT; ++t) acc[i][t] = mfma_block<ST>(A[r][i * KBW + j], Bf[t][j], acc[i][t]);
+                  }
+              if (step + PF < nsteps) issue(A[r], step + PF);
+            }
             if (c == nchunks - 1) {
               // strip finished: exchange partial tiles, one wavefront reduces and stores
 #pragma unroll

@@ -1114,6 +1114,16 @@ int launch_gemm_nt(const GemmArgs& a, int grid, hipStream_t s) {
     // the next step's 8 loads are issued right after the MFMAs, so they fly during the
     // partial-tile exchange; one buffer keeps the kernel under 128 VGPRs (2 workgroups per CU)
     if (a.prefetch == 2) EVICT_GEMM_LAUNCH(8, 2, true);
+    else if (EPI == EPI_SWIGLU && NT == 1 && a.grouped && a.chunk_units == 1 && nkb == 64 && a.prefetch != 3)
+      // one gate/up strip pair per chunk: two steps, known at compile time
+      hipLaunchKernelGGL((gemm_stream_kernel<ST, NT, 8, 1, EPI, true, 1, (EPI == EPI_SWIGLU && NT == 1) ? 2 : 0>), dim3(grid),
+                         dim3(kGemmThreads), 0, s, a);
+    else if (EPI == EPI_RESID && !a.grouped && a.prefetch != 3 &&
+             (a.dense_units > 0 ? a.dense_units : 1) * ((nkb + 63) / 64) == 2)
+      // two steps per workgroup (one strip of two 64-block chunks), known at compile time (the QKV
+      // variant of this would spill)
+      hipLaunchKernelGGL((gemm_stream_kernel<ST, NT, 8, 1, EPI, true, 1, EPI == EPI_RESID ? 2 : 0>), dim3(grid),
+                         dim3(kGemmThreads), 0, s, a);
     else EVICT_GEMM_LAUNCH(8, 1, true);
   } else if (bf16 && nkb == 24) {
     // 3 blocks per wavefront per strip: take 4 strips per exchange step when the chunking allows
