@@ -21,6 +21,11 @@
  *     x_{t+1}, which is sampled from the target and therefore always accepted and always
  *     part of every prefix; Sec. 2.1).
  *   - dtype: storage type of weights and activations; accumulation is always fp32.
+ *   - A context's scratch is shared by every call that takes it: calls on one context must be
+ *     ordered (same stream, or made dependent by the caller); calls that overlap on the GPU race.
+ *     Separate contexts are independent. Host-side, a context is not to be used from two
+ *     threads at once. Results are deterministic: no floating-point atomics, fixed summation
+ *     orders, so a call repeated on the same inputs returns the same bits.
  */
 #ifndef EVICT_H_
 #define EVICT_H_
