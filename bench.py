@@ -43,7 +43,7 @@ def parse():
     ap.add_argument("--copies", type=int, default=4, help="weight copies rotated between steps")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     ap.add_argument("--seed", type=int, default=1000)
-    ap.add_argument("--model", default="qwen3", choices=["qwen3", "dsv2lite"],
+    ap.add_argument("--model", default="qwen3", choices=["qwen3", "dsv2lite", "qwen3_235b_tp8", "ling_flash2_tp4"],
                     help="layer shape; the default line is the Qwen3-30B-A3B-shaped one")
     ap.add_argument("--tune", action="append", default=[], help="key=value launch-shape knob (evict_tune)")
     ap.add_argument("--sweep", action="store_true",
@@ -222,6 +222,11 @@ def spec_loop(args):
     first.close()
 
 
+WORKLOAD_NAMES = {"qwen3": "qwen3-30b-a3b", "dsv2lite": "deepseek-v2-lite",
+                  "qwen3_235b_tp8": "qwen3-235b-a22b (one rank of TP=8)",
+                  "ling_flash2_tp4": "ling-flash-2.0 (one rank of TP=4)"}
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -255,7 +260,7 @@ def main():
         L_list = [int(v) for v in gl.integers(L, max(args.ctx_max, L) + 1, B)]
         L = max(L_list)
     case = synth.make_case(args.model, n=N, L=L, seed=args.seed, sigma=args.sigma, batch=B, L_list=L_list,
-                           tree="eagle" if args.model == "qwen3" else "auto")
+                           tree="auto" if args.model == "dsv2lite" else "eagle")
     T = int(case["tree_off"][-1])
     layer = harness.DeviceLayer(cfg, case["W"], max_tokens=T, max_batch=B, max_ctx=L)
     dc = harness.DeviceCase(case, with_aux=True)
@@ -397,7 +402,7 @@ def main():
     tpath = os.path.join(ROOT, "profiles", "pmc_traffic.json")
     if os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get(f"gateup_N{N}_L{L}") if B == 1 else None
+            traffic = json.load(open(tpath)).get(f"gateup_N{N}_L{L}") if B == 1 and args.model == "qwen3" and args.sigma == 0.5 and not args.tune else None
         except Exception:
             traffic = None
 
@@ -414,7 +419,7 @@ def main():
         "vs_baseline": None,
         "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": f"{'qwen3-30b-a3b' if args.model == 'qwen3' else 'deepseek-v2-lite'}-shaped MoE layer, N={N} tree nodes, ctx={L if B == 1 else [int(v) for v in case['ctx_len']]}, {B} sequence{'s' if B > 1 else ''}, sigma={args.sigma}",
+        "config": {"workload": f"{WORKLOAD_NAMES[args.model]}-shaped MoE layer, N={N} tree nodes, ctx={L if B == 1 else [int(v) for v in case['ctx_len']]}, {B} sequence{'s' if B > 1 else ''}, sigma={args.sigma}",
                    "d_model": cfg.d, "heads": f"{cfg.Hq}q/{cfg.Hkv}kv x {cfg.D}", "experts": f"{cfg.E} top-{cfg.k}",
                    "d_ff": cfg.F, "union_experts": U, "weight_copies": len(weight_sets)},
         "step_us_p10_p50_p90": spread(step),

@@ -58,6 +58,15 @@ CONFIGS: Dict[str, ModelCfg] = {
     "mini_bf16": ModelCfg("mini_bf16", "bf16", d=512, Hq=8, Hkv=2, D=128, E=32, k=4, F=192),
     # small shape with 256 experts / 8 active (the ratio of Ling-flash-2.0, App. C.2), sigmoid router weights, 64-wide heads
     "mini_sigmoid": ModelCfg("mini_sigmoid", "bf16", d=512, Hq=8, Hkv=4, D=64, E=256, k=8, F=128, router_norm="sigmoid"),
+    # One GPU's tensor-parallel share of the paper's two larger targets (App. C.2: 128 experts / 8 active
+    # served with TP=8, 256 experts / 8 active served with TP=4): the full model width and every expert,
+    # with the attention heads and each expert's d_ff divided by the TP degree. The widths are those of
+    # the public model cards (d_model 4096; 64 query / 4 KV heads and expert d_ff 1536 for the first,
+    # 32 / 4 heads, d_ff 1024 and one shared expert for the second); a KV head is replicated where the
+    # TP degree exceeds the KV head count. The layer's output is this rank's partial sum.
+    "qwen3_235b_tp8": ModelCfg("qwen3_235b_tp8", "bf16", d=4096, Hq=8, Hkv=1, D=128, E=128, k=8, F=192),
+    "ling_flash2_tp4": ModelCfg("ling_flash2_tp4", "bf16", d=4096, Hq=8, Hkv=1, D=128, E=256, k=8, F=256,
+                                n_shared=1, router_norm="sigmoid"),
 }
 
 

@@ -223,3 +223,12 @@ def test_dsv2lite_shaped_layer_full_size():
     got = run_case(case)
     info = check_against_oracle(case, got)
     print("dsv2lite N=64:", info)
+
+
+@pytest.mark.parametrize("cfg_name,seed", [("qwen3_235b_tp8", 1005), ("ling_flash2_tp4", 1006)])
+def test_tensor_parallel_share_of_the_larger_targets_full_size(cfg_name, seed):
+    # one GPU's share of the 128-expert / TP=8 and 256-expert / TP=4 targets (App. C.2), N = 32, ctx 2048
+    case = synth.make_case(cfg_name, n=32, L=2048, seed=seed)
+    got = run_case(case)
+    info = check_against_oracle(case, got)
+    print(cfg_name, "N=32:", info)
