@@ -48,6 +48,9 @@ def parse():
     ap.add_argument("--tune", action="append", default=[], help="key=value launch-shape knob (evict_tune)")
     ap.add_argument("--sweep", action="store_true",
                     help="not the default line: one JSON line per (N, sigma) point, N in 1..128, sigma in {0.2, 0.5, 1.0}")
+    ap.add_argument("--cost", default="profile", choices=["profile", "surface"],
+                    help="--loop: C(k) as profiled on the loop's own inputs, or collapsed from a cost surface over "
+                         "(k, expert union) fitted to profiles at child noise 0.2 / the run's sigma / 1.0")
     ap.add_argument("--launch", default="eager", choices=["graph", "eager"],
                     help="timed steps call the entry points (default), or replay one captured HIP graph per weight copy")
     ap.add_argument("--loop", action="store_true",
@@ -180,8 +183,26 @@ def spec_loop(args):
     # up to its token tiles and is left out, as the layers are what grows with k
     d0 = pool[0]
     loop.set_context_length(L0)
-    cost = ev.evict_profile_cost(first.ctx, layers, d0.tree_off, d0.parent, N, kc, vc, cap * cfg.D, loop.ctx_len[loop.cur], L0,
-                                 d0.x, loop.out, loop.k_new, loop.v_new, 6)
+    surface = None
+    if args.cost == "profile":
+        cost = ev.evict_profile_cost(first.ctx, layers, d0.tree_off, d0.parent, N, kc, vc, cap * cfg.D, loop.ctx_len[loop.cur], L0,
+                                     d0.x, loop.out, loop.k_new, loop.v_new, 6)
+    else:
+        # points (k, mean union, ms) at three routing spreads; C(k) = surface at the union this run's inputs show
+        from paper_2605_00342_amd import cost_model as cm
+        sets = []
+        for sg in (0.2, args.sigma, 1.0):
+            dd = synth.draft_iteration(cfg, N, args.seed, 0, sg, vocab)
+            sets.append(dict(tree_off=d0.tree_off, parent=harness.dev_i32(dd["parent"]), k_caches=kc, v_caches=vc,
+                             kv_head_stride=cap * cfg.D, ctx_len=loop.ctx_len[loop.cur], max_ctx_host=L0,
+                             x_in=harness.to_dev(dd["x"], cfg.dtype), x_out=loop.out, k_new=loop.k_new, v_new=loop.v_new))
+        ks_, us_, ts_, _ = cm.profile_cost_surface(first.ctx, layers, sets, N, 6)
+        coef, rms = cm.fit_cost_surface(ks_, us_, ts_)
+        own_union = [0.0] + [float(u) for u in us_[N:2 * N]]
+        cost = [float(c) for c in cm.collapse_cost(coef, N, cfg.E, cfg.k, own_union)]
+        surface = {"ms = a + b*k + c*union": [round(float(c), 6) for c in coef], "rms_residual_ms": round(rms, 5),
+                   "points": int(ks_.size), "union_at_k": [round(u, 2) for u in own_union[1:]],
+                   "union_range_at_N": [round(float(us_[N - 1]), 2), round(float(us_[3 * N - 1]), 2)]}
     results = {}
     cost_dev = None
     for mode in ("verify_all", "evict", "coverage_0.7", "coverage_0.4"):
@@ -218,6 +239,7 @@ def spec_loop(args):
                                                  f"ctx from {L0}, synthetic calibrated drafter, sigma={args.sigma}",
                                      "iterations": args.iters},
                           "cost_table_ms": [round(c, 4) for c in cost[1:]] if mode == "evict" else None,
+                          "cost_surface": surface if mode == "evict" else None,
                           "data": "synthetic", "dtype": "bf16"}), flush=True)
     first.close()
 

@@ -171,6 +171,19 @@ int evict_profile_cost(evict_ctx* ctx, const evict_layer_weights* layers, int n_
                        int64_t kv_head_stride, const int32_t* ctx_len, int max_ctx_host, const void* x_in, void* x_out,
                        void* const* k_new, void* const* v_new, int reps, float* cost_host, void* stream);
 
+/* The same profiling run, also reporting what the cost grew with (Sec. 2.2, Eq. 5; App. A
+ * relates the union size to the token count): union_mean_host [host] float[Kmax+1] receives,
+ * for every k, the number of activated experts |union| averaged over the layers and runs of
+ * that k (union_mean_host[0] = 0; NULL = not wanted). One call gives the points
+ * (k, union_mean[k], cost[k]) of a cost surface over (verification length, expert union) for
+ * the inputs it ran on; calls on inputs with other routing spread (wider or narrower unions
+ * at the same k) fill in the second axis. 1 <= reps <= 4096. */
+int evict_profile_cost_union(evict_ctx* ctx, const evict_layer_weights* layers, int n_layers, const int32_t* tree_off,
+                             const int32_t* parent, int Kmax, const void* const* k_caches, const void* const* v_caches,
+                             int64_t kv_head_stride, const int32_t* ctx_len, int max_ctx_host, const void* x_in,
+                             void* x_out, void* const* k_new, void* const* v_new, int reps, float* cost_host,
+                             float* union_mean_host, void* stream);
+
 /* Union of activated experts over all verified nodes (Eq. 5) and the grouping it induces.
  *   topk_idx [dev] int32[T, k] with values in [0, E).
  *   union_ids [dev] int32[E]: activated experts ascending, tail -1; union_count [dev] int32[1];

@@ -18,7 +18,7 @@ __all__ = [
     "evict_stage_timing", "evict_stage_times", "evict_probe_read", "evict_probe_copy", "evict_tune", "evict_verify_stack", "evict_lm_head_argmax",
     "evict_profile_cost", "evict_graph_begin", "evict_graph_end", "evict_graph_launch", "evict_graph_destroy",
     "evict_lm_head_logits", "evict_accept_path_sampled", "evict_kv_commit", "evict_select_prefix_coverage", "evict_kv_commit_stack",
-    "STAGES", "EXPORTS",
+    "evict_profile_cost_union", "STAGES", "EXPORTS",
 ]
 
 EVICT_F32, EVICT_BF16 = 0, 1
@@ -32,6 +32,7 @@ EXPORTS = [
     "evict_stage_timing", "evict_stage_times", "evict_probe_read", "evict_probe_copy", "evict_tune", "evict_verify_stack", "evict_lm_head_argmax",
     "evict_profile_cost", "evict_graph_begin", "evict_graph_end", "evict_graph_launch", "evict_graph_destroy",
     "evict_lm_head_logits", "evict_accept_path_sampled", "evict_kv_commit", "evict_select_prefix_coverage", "evict_kv_commit_stack",
+    "evict_profile_cost_union",
 ]
 STAGES = ["prep", "qkv", "attention", "oproj", "router", "union", "gateup", "down", "shared", "combine"]
 
@@ -101,6 +102,9 @@ def load():
     lib.evict_lm_head_argmax.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp]
     lib.evict_profile_cost.argtypes = [vp, C.POINTER(LayerWeights), i32, vp, vp, i32, C.POINTER(vp), C.POINTER(vp), i64, vp, i32,
                                        vp, vp, C.POINTER(vp), C.POINTER(vp), i32, C.POINTER(C.c_float), vp]
+    lib.evict_profile_cost_union.argtypes = [vp, C.POINTER(LayerWeights), i32, vp, vp, i32, C.POINTER(vp), C.POINTER(vp), i64, vp,
+                                             i32, vp, vp, C.POINTER(vp), C.POINTER(vp), i32, C.POINTER(C.c_float),
+                                             C.POINTER(C.c_float), vp]
     lib.evict_probe_read.argtypes = [vp, sz, vp, vp]
     lib.evict_probe_copy.argtypes = [vp, vp, sz, vp]
     lib.evict_stage_times.argtypes = [vp, C.POINTER(C.c_float)]
@@ -318,3 +322,14 @@ def evict_profile_cost(ctx, layers, tree_off, parent, Kmax, k_caches, v_caches, 
                                      _ptr_array(k_caches), _ptr_array(v_caches), kv_head_stride, _p(ctx_len), max_ctx_host,
                                      _p(x_in), _p(x_out), _ptr_array(k_new), _ptr_array(v_new), reps, buf, _stream()))
     return [float(v) for v in buf]
+
+
+def evict_profile_cost_union(ctx, layers, tree_off, parent, Kmax, k_caches, v_caches, kv_head_stride, ctx_len, max_ctx_host,
+                             x_in, x_out, k_new, v_new, reps: int):
+    """Returns (cost, union_mean): two lists of Kmax+1 floats (milliseconds; mean number of activated experts)."""
+    buf, ubuf = (C.c_float * (Kmax + 1))(), (C.c_float * (Kmax + 1))()
+    _check(load().evict_profile_cost_union(ctx, _layer_array(layers), len(layers), _p(tree_off), _p(parent), Kmax,
+                                           _ptr_array(k_caches), _ptr_array(v_caches), kv_head_stride, _p(ctx_len),
+                                           max_ctx_host, _p(x_in), _p(x_out), _ptr_array(k_new), _ptr_array(v_new), reps,
+                                           buf, ubuf, _stream()))
+    return [float(v) for v in buf], [float(v) for v in ubuf]

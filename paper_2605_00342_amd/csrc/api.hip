@@ -114,6 +114,7 @@ int evict_create(evict_ctx** out, const evict_model_desc* m, int max_tokens, int
   A(&c.stack_buf[1], T * d * eb);
   if (!rc) {
     he = hipMemset(c.status, 0, 16);
+    if (he == hipSuccess) he = hipMemset(c.sched, 0, 16);
     if (he != hipSuccess) { set_error("hipMemset failed: %s", hipGetErrorString(he)); rc = EVICT_E_HIP; }
   }
   if (!rc) rc = kernels_setup(*m);
@@ -476,17 +477,21 @@ int evict_lm_head_logits(evict_ctx* ctx, const void* x, const void* g_final, con
   return launch_gemm(m.dtype, EPI_F32, a, 1, ((a.n_strips + 7) / 8) * 8 * a.dense_tiles, s);
 }
 
-int evict_profile_cost(evict_ctx* ctx, const evict_layer_weights* layers, int n_layers, const int32_t* tree_off,
-                       const int32_t* parent, int Kmax, const void* const* k_caches, const void* const* v_caches,
-                       int64_t kv_head_stride, const int32_t* ctx_len, int max_ctx_host, const void* x_in, void* x_out,
-                       void* const* k_new, void* const* v_new, int reps, float* cost_host, void* stream) {
+int evict_profile_cost_union(evict_ctx* ctx, const evict_layer_weights* layers, int n_layers, const int32_t* tree_off,
+                             const int32_t* parent, int Kmax, const void* const* k_caches, const void* const* v_caches,
+                             int64_t kv_head_stride, const int32_t* ctx_len, int max_ctx_host, const void* x_in, void* x_out,
+                             void* const* k_new, void* const* v_new, int reps, float* cost_host, float* union_mean_host,
+                             void* stream) {
   EVICT_REQUIRE(ctx && cost_host, EVICT_E_INVALID, "evict_profile_cost: null pointer argument");
   EVICT_REQUIRE(Kmax >= 1 && Kmax <= ctx->max_tokens && Kmax <= EVICT_MAX_TREE_NODES, EVICT_E_INVALID,
                 "evict_profile_cost: Kmax=%d outside [1, min(max_tokens, %d)]", Kmax, EVICT_MAX_TREE_NODES);
-  EVICT_REQUIRE(reps >= 1, EVICT_E_INVALID, "evict_profile_cost: reps must be >= 1");
+  EVICT_REQUIRE(reps >= 1 && reps <= 4096, EVICT_E_INVALID, "evict_profile_cost: reps=%d outside [1, 4096]", reps);
+  EVICT_REQUIRE(!ctx->capturing, EVICT_E_INVALID, "evict_profile_cost synchronises: not inside a graph capture");
   hipStream_t s = (hipStream_t)stream;
   cost_host[0] = 0.0f;
+  if (union_mean_host) union_mean_host[0] = 0.0f;
   for (int k = 1; k <= Kmax; ++k) {
+    EVICT_HIP_CHECK(hipMemsetAsync(ctx->sched + 1, 0, 4, s));  // running total of union sizes
     // B = 1: the kernels take the tree size from T, so the first k nodes are verified as a tree of their own
     for (int r = -1; r < reps; ++r) {
       if (r == 0) EVICT_HIP_CHECK(hipEventRecord(ctx->prof_ev[0], s));
@@ -499,8 +504,22 @@ int evict_profile_cost(evict_ctx* ctx, const evict_layer_weights* layers, int n_
     float ms = 0.0f;
     EVICT_HIP_CHECK(hipEventElapsedTime(&ms, ctx->prof_ev[0], ctx->prof_ev[1]));
     cost_host[k] = ms / (float)reps;
+    if (union_mean_host) {
+      int32_t total = 0;
+      EVICT_HIP_CHECK(hipMemcpyAsync(&total, ctx->sched + 1, 4, hipMemcpyDeviceToHost, s));
+      EVICT_HIP_CHECK(hipStreamSynchronize(s));
+      union_mean_host[k] = (float)total / ((float)(reps + 1) * (float)n_layers);
+    }
   }
   return EVICT_OK;
+}
+
+int evict_profile_cost(evict_ctx* ctx, const evict_layer_weights* layers, int n_layers, const int32_t* tree_off,
+                       const int32_t* parent, int Kmax, const void* const* k_caches, const void* const* v_caches,
+                       int64_t kv_head_stride, const int32_t* ctx_len, int max_ctx_host, const void* x_in, void* x_out,
+                       void* const* k_new, void* const* v_new, int reps, float* cost_host, void* stream) {
+  return evict_profile_cost_union(ctx, layers, n_layers, tree_off, parent, Kmax, k_caches, v_caches, kv_head_stride, ctx_len,
+                                  max_ctx_host, x_in, x_out, k_new, v_new, reps, cost_host, nullptr, stream);
 }
 
 int evict_tune(evict_ctx* ctx, const char* key, int value) {

@@ -37,7 +37,7 @@ struct evict_ctx {
   int32_t* perm;         // [T*k]
   int32_t* inv;          // [T*k]
   evict::WorkRec* work;  // [E] device-side work list, one record per union slot
-  int32_t* sched;        // [4] chunk counters of the grouped GEMMs
+  int32_t* sched;        // [4]: [0] work-list slots of the grouped GEMMs, [1] running total of union sizes over layer calls
   int32_t* tok_of_pos;   // [T*k] token of each grouped position
   void* act;             // [T*k + n_shared*T][F] storage dtype (routed pairs, then shared experts x tokens)
   float* y;              // [T*k + n_shared*T][d]

@@ -73,6 +73,9 @@ __device__ inline void expert_union_body(
   __shared__ int s_wave[16];
   __shared__ int s_dup;
   const int tid = threadIdx.x, nthreads = blockDim.x;
+  // slot_count[1] keeps a running total of the union sizes (read by the cost profiler); the old
+  // value is requested now so that its round trip is over long before the total is written back
+  const int union_total = (tid == 0 && slot_count) ? slot_count[1] : 0;
   for (int e = tid; e < E; e += nthreads) s_hist[e] = 0;
   if (use_masks)
     for (int i = tid; i < E * words; i += nthreads) s_mask[i] = 0ull;
@@ -141,7 +144,11 @@ __device__ inline void expert_union_body(
     }
   }
   for (int e = tot_f + tid; e < E; e += nthreads) union_ids[e] = -1;
-  if (tid == 0) { offsets[E] = tot_h; union_count[0] = tot_f; }
+  if (tid == 0) {
+    offsets[E] = tot_h;
+    union_count[0] = tot_f;
+    if (slot_count) slot_count[1] = (int)((unsigned)union_total + (unsigned)tot_f);  // (wraps; the profiler resets it)
+  }
   __syncthreads();
   if (use_masks && !s_dup) {
     // position of pair (t, slot) inside its expert = number of earlier tokens routed there

@@ -236,3 +236,57 @@ def test_lm_head_full_vocabulary():
     assert np.array_equal(nxt.cpu().numpy()[ok], np.argmax(logits, -1)[ok])
     np.testing.assert_allclose(best.cpu().numpy(), logits.max(-1), rtol=0, atol=5e-5)
     ev.evict_destroy(ctx)
+
+
+def test_profile_reports_mean_union_and_feeds_the_cost_surface():
+    # two input sets of different routing spread (child noise 0.2 and 1.0) on the same weights
+    from paper_2605_00342_amd import cost_model as cm
+    n, L, nl = 16, 64, 2
+    case, Ws, Ks, Vs = make_stack("mini_bf16", nl, n, L, 71)
+    wide = synth.make_case("mini_bf16", n=n, L=L, seed=71, sigma=1.0)
+    narrow = synth.make_case("mini_bf16", n=n, L=L, seed=71, sigma=0.05)
+    cfg = case["cfg"]
+    st = DeviceStack(case, Ws, Ks, Vs)
+    dc = st.dc
+    sets, refs = [], []
+    for c in (narrow, wide):
+        x_dev = harness.to_dev(c["x"], cfg.dtype)
+        par = harness.dev_i32(c["parent"])
+        sets.append(dict(tree_off=dc.tree_off, parent=par, k_caches=[q.k_cache for q in st.cases],
+                         v_caches=[q.v_cache for q in st.cases], kv_head_stride=dc.head_stride, ctx_len=dc.ctx_len,
+                         max_ctx_host=dc.max_ctx, x_in=x_dev, x_out=dc.out, k_new=[q.k_new for q in st.cases],
+                         v_new=[q.v_new for q in st.cases]))
+        # oracle: mean union over the layers for every prefix length
+        means = [0.0]
+        for k in range(1, n + 1):
+            r = oracle_stack(dict(case, x=c["x"]), Ws, Ks, Vs, tree_off=np.array([0, k], np.int32), parent=c["parent"][:k],
+                             x=c["x"][:k])
+            means.append(float(np.mean([q["union_count"] for q in r])))
+        refs.append(means)
+    cost, umean = ev.evict_profile_cost_union(st.ctx, [l.weights for l in st.layers], sets[1]["tree_off"], sets[1]["parent"], n,
+                                              sets[1]["k_caches"], sets[1]["v_caches"], dc.head_stride, dc.ctx_len, dc.max_ctx,
+                                              sets[1]["x_in"], dc.out, sets[1]["k_new"], sets[1]["v_new"], 2)
+    assert len(cost) == n + 1 and len(umean) == n + 1 and umean[0] == 0.0
+    # the union of a single token is its k experts; means agree with the oracle's routing up to
+    # one near-tie flip in one layer
+    assert umean[1] == cfg.k
+    assert np.max(np.abs(np.asarray(umean) - refs[1])) <= 1.0 / nl + 1e-6, (umean, refs[1])
+    ks, us, ts, mean_u = cm.profile_cost_surface(st.ctx, [l.weights for l in st.layers], sets, n, 3)
+    assert ks.size == 2 * n and np.all(np.isfinite(ts)) and np.all(ts > 0)
+    assert np.max(np.abs(us[:n] - refs[0][1:])) <= 1.0 / nl + 1e-6 and np.max(np.abs(us[n:] - refs[1][1:])) <= 1.0 / nl + 1e-6
+    assert us[n:].sum() > us[:n].sum()          # wider child noise activates more experts
+    assert np.allclose(mean_u[1:], 0.5 * (us[:n] + us[n:]))
+    coef, rms = cm.fit_cost_surface(ks, us, ts)
+    assert np.all(np.isfinite(coef)) and np.isfinite(rms)
+    # whatever the timings were, the table built from them drives the device selection as the oracle's
+    table = np.maximum(coef[0] + coef[1] * np.arange(n + 1) + coef[2] * mean_u, 1e-3).astype(np.float32)
+    table[0] = table[1]
+    i32 = torch.int32
+    ksel = torch.zeros(1, dtype=i32, device=DEV); keep = torch.zeros(n, dtype=i32, device=DEV)
+    npar = torch.zeros(n, dtype=i32, device=DEV); noff = torch.zeros(2, dtype=i32, device=DEV); est = torch.zeros(1, device=DEV)
+    ev.evict_select_prefix(None, dc.tree_off, dc.parent, torch.from_numpy(case["q"]).to(DEV), 1, n,
+                           torch.from_numpy(table).to(DEV), n, ksel, keep, npar, noff, est)
+    torch.cuda.synchronize()
+    assert ksel.item() == orc.select_prefix(case["parent"], case["q"], table, n)["k_star"]
+    assert ev.evict_device_status(st.ctx) == 0
+    st.close()
