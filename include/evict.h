@@ -275,6 +275,37 @@ int evict_kv_commit_stack(evict_ctx* ctx, int dtype, int Hkv, int D, const void*
                           int64_t kv_seq_stride, int64_t kv_head_stride, const int32_t* ctx_len, int capacity,
                           int32_t* ctx_len_out, int B, void* stream);
 
+/* Paged KV caches: the block-table layout that serving engines of the kind the method is
+ * integrated into (Sec. 3.3) keep their caches in. Every layer has a key pool and a value
+ * pool [dev] of n_pages pages; page g of a pool holds page_size consecutive positions of one
+ * sequence: position slot r, KV head h, channel c of page g at
+ *   pool + g*page_stride + h*kv_head_stride + r*D + c   (strides in elements, multiples of 8,
+ *   kv_head_stride >= page_size*D, page_stride >= Hkv*kv_head_stride).
+ * block_table [dev] int32[B][table_stride]: entry [b][i] is the page that holds positions
+ * i*page_size .. (i+1)*page_size - 1 of sequence b, the same for every layer; entries past a
+ * sequence's length are never read. page_size is a power of two in [1, 65536];
+ * table_stride*page_size must cover max_ctx_host (verification) or capacity (commit). A table
+ * entry outside [0, n_pages) sets a bit of the context's status word; such a key is read from
+ * page 0 and such a row is not written.
+ *
+ * evict_verify_stack_paged: evict_verify_stack with k_pools / v_pools [host] arrays of n_layers
+ * [dev] pool pointers in place of the contiguous caches; all other arguments, outputs and
+ * results as there (the attention kernels look the page of every key up; nothing is copied).
+ * evict_kv_commit_stack_paged: evict_kv_commit_stack writing row ctx_len[b] + j into the page
+ * the table names for that position; the caller has put pages for all positions below
+ * `capacity` (in positions, per sequence) into the table beforehand. */
+int evict_verify_stack_paged(evict_ctx* ctx, const evict_layer_weights* layers, int n_layers, const int32_t* tree_off,
+                             const int32_t* parent, int B, int T, const void* const* k_pools, const void* const* v_pools,
+                             int64_t page_stride, int64_t kv_head_stride, const int32_t* block_table, int table_stride,
+                             int page_size, int n_pages, const int32_t* ctx_len, int max_ctx_host, const void* x_in,
+                             void* x_out, void* const* k_new, void* const* v_new, void* stream);
+int evict_kv_commit_stack_paged(evict_ctx* ctx, int dtype, int Hkv, int D, const void* const* k_new,
+                                const void* const* v_new, int n_layers, const int32_t* tree_off, const int32_t* path,
+                                int path_stride, const int32_t* path_len, void* const* k_pools, void* const* v_pools,
+                                int64_t page_stride, int64_t kv_head_stride, const int32_t* block_table, int table_stride,
+                                int page_size, int n_pages, const int32_t* ctx_len, int capacity, int32_t* ctx_len_out,
+                                int B, void* stream);
+
 /* Gather rows of a [T, row_bytes] array by the kept node lists of evict_select_prefix:
  * dst row new_tree_off[b] + r = src row tree_off[b] + keep[new_tree_off[b] + r].
  * row_bytes % 4 == 0. Grid is sized for T rows; rows beyond new_tree_off[B] are untouched. */
@@ -287,7 +318,7 @@ int evict_gather_rows(const void* src, void* dst, int row_bytes, const int32_t* 
 int evict_validate_trees_host(const int32_t* tree_off, const int32_t* parent, int B, int max_nodes);
 
 /* Device-side status word of a context: 0, or a bit set when a kernel met an invalid
- * parent id, expert index or context length (such values are clamped, never dereferenced).
+ * parent id, expert index, context length or page id (such values are clamped, never dereferenced).
  * Synchronises the stream. */
 int evict_device_status(evict_ctx* ctx, int32_t* status_host, void* stream);
 

@@ -378,6 +378,28 @@ def kv_commit(K, V, k_new, v_new, path):
             np.concatenate([np.asarray(V), np.transpose(vn, (1, 0, 2))], axis=1))
 
 
+def paged_view(pool, table_row, L, page_size):
+    """A sequence's cache [Hkv, L, D] read out of a page pool [n_pages, Hkv, page_size, D]:
+    position p is row p mod page_size of page table_row[p div page_size] (the block-table layout
+    of serving engines; a storage layout, not part of the method's arithmetic)."""
+    pool = np.asarray(pool)
+    out = np.empty((pool.shape[1], L, pool.shape[3]), dtype=pool.dtype)
+    for p in range(L):
+        out[:, p, :] = pool[int(table_row[p // page_size]), :, p % page_size, :]
+    return out
+
+
+def kv_commit_paged(pool_k, pool_v, table_row, L, k_new, v_new, path, page_size):
+    """kv_commit on a paged cache, in place: the j-th accepted node goes to position L + j, i.e.
+    row (L + j) mod page_size of page table_row[(L + j) div page_size]. Returns the new length."""
+    for j, node in enumerate(path):
+        p = L + j
+        pg, r = int(table_row[p // page_size]), p % page_size
+        pool_k[pg, :, r, :] = np.asarray(k_new)[node]
+        pool_v[pg, :, r, :] = np.asarray(v_new)[node]
+    return L + len(path)
+
+
 # --------------------------------------------------------------------------------------
 # EVICT prefix selection (Sec. 3.1-3.2)
 # --------------------------------------------------------------------------------------

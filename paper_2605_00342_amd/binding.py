@@ -18,7 +18,7 @@ __all__ = [
     "evict_stage_timing", "evict_stage_times", "evict_probe_read", "evict_probe_copy", "evict_tune", "evict_verify_stack", "evict_lm_head_argmax",
     "evict_profile_cost", "evict_graph_begin", "evict_graph_end", "evict_graph_launch", "evict_graph_destroy",
     "evict_lm_head_logits", "evict_accept_path_sampled", "evict_kv_commit", "evict_select_prefix_coverage", "evict_kv_commit_stack",
-    "evict_profile_cost_union", "STAGES", "EXPORTS",
+    "evict_profile_cost_union", "evict_verify_stack_paged", "evict_kv_commit_stack_paged", "STAGES", "EXPORTS",
 ]
 
 EVICT_F32, EVICT_BF16 = 0, 1
@@ -32,7 +32,7 @@ EXPORTS = [
     "evict_stage_timing", "evict_stage_times", "evict_probe_read", "evict_probe_copy", "evict_tune", "evict_verify_stack", "evict_lm_head_argmax",
     "evict_profile_cost", "evict_graph_begin", "evict_graph_end", "evict_graph_launch", "evict_graph_destroy",
     "evict_lm_head_logits", "evict_accept_path_sampled", "evict_kv_commit", "evict_select_prefix_coverage", "evict_kv_commit_stack",
-    "evict_profile_cost_union",
+    "evict_profile_cost_union", "evict_verify_stack_paged", "evict_kv_commit_stack_paged",
 ]
 STAGES = ["prep", "qkv", "attention", "oproj", "router", "union", "gateup", "down", "shared", "combine"]
 
@@ -113,6 +113,10 @@ def load():
     lib.evict_kv_commit.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, i32, vp, vp, vp, i64, i64, vp, i32, vp, i32, vp]
     lib.evict_kv_commit_stack.argtypes = [vp, i32, i32, i32, C.POINTER(vp), C.POINTER(vp), i32, vp, vp, i32, vp, C.POINTER(vp),
                                           C.POINTER(vp), i64, i64, vp, i32, vp, i32, vp]
+    lib.evict_verify_stack_paged.argtypes = [vp, C.POINTER(LayerWeights), i32, vp, vp, i32, i32, C.POINTER(vp), C.POINTER(vp), i64, i64,
+                                             vp, i32, i32, i32, vp, i32, vp, vp, C.POINTER(vp), C.POINTER(vp), vp]
+    lib.evict_kv_commit_stack_paged.argtypes = [vp, i32, i32, i32, C.POINTER(vp), C.POINTER(vp), i32, vp, vp, i32, vp, C.POINTER(vp),
+                                                C.POINTER(vp), i64, i64, vp, i32, i32, i32, vp, i32, vp, i32, vp]
     lib.evict_graph_begin.argtypes = [vp, vp]
     lib.evict_graph_end.argtypes = [vp, vp, C.POINTER(vp)]
     lib.evict_graph_launch.argtypes = [vp, vp]
@@ -264,6 +268,15 @@ def evict_kv_commit_stack(ctx, dtype, Hkv, D, k_new, v_new, tree_off, path, path
                                         kv_seq_stride, kv_head_stride, _p(ctx_len), capacity, _p(ctx_len_out), B, _stream()))
 
 
+def evict_kv_commit_stack_paged(ctx, dtype, Hkv, D, k_new, v_new, tree_off, path, path_stride, path_len, k_pools, v_pools,
+                                page_stride, kv_head_stride, block_table, table_stride, page_size, n_pages, ctx_len, capacity,
+                                ctx_len_out, B) -> None:
+    _check(load().evict_kv_commit_stack_paged(ctx, dtype, Hkv, D, _ptr_array(k_new), _ptr_array(v_new), len(k_new),
+                                              _p(tree_off), _p(path), path_stride, _p(path_len), _ptr_array(k_pools),
+                                              _ptr_array(v_pools), page_stride, kv_head_stride, _p(block_table), table_stride,
+                                              page_size, n_pages, _p(ctx_len), capacity, _p(ctx_len_out), B, _stream()))
+
+
 def evict_graph_begin(ctx) -> None:
     """Start recording the calls made on torch's current (non-default) stream."""
     _check(load().evict_graph_begin(ctx, _stream()))
@@ -307,6 +320,15 @@ def evict_verify_stack(ctx, layers, tree_off, parent, B, T, k_caches, v_caches, 
                                      _ptr_array(k_caches), _ptr_array(v_caches), kv_seq_stride, kv_head_stride,
                                      _p(ctx_len), max_ctx_host, _p(x_in), _p(x_out), _ptr_array(k_new), _ptr_array(v_new),
                                      _stream()))
+
+
+def evict_verify_stack_paged(ctx, layers, tree_off, parent, B, T, k_pools, v_pools, page_stride, kv_head_stride, block_table,
+                             table_stride, page_size, n_pages, ctx_len, max_ctx_host, x_in, x_out, k_new, v_new) -> None:
+    """k_pools, v_pools: lists of page-pool device tensors, one per layer; block_table: int32 [B][table_stride]."""
+    _check(load().evict_verify_stack_paged(ctx, _layer_array(layers), len(layers), _p(tree_off), _p(parent), B, T,
+                                           _ptr_array(k_pools), _ptr_array(v_pools), page_stride, kv_head_stride,
+                                           _p(block_table), table_stride, page_size, n_pages, _p(ctx_len), max_ctx_host,
+                                           _p(x_in), _p(x_out), _ptr_array(k_new), _ptr_array(v_new), _stream()))
 
 
 def evict_lm_head_argmax(ctx, x, g_final, wlm_packed, T, next_out, best_logit=None, x_norm_out=None) -> None:

@@ -135,6 +135,7 @@ int evict_create(evict_ctx** out, const evict_model_desc* m, int max_tokens, int
   c.attn_row_blocks = 0;
   c.timed_once = 0;
   c.capturing = 0;
+  c.paging = KvPaging{nullptr, 0, 0, 0};
   c.prof_ev[0] = c.prof_ev[1] = nullptr;
   for (int i = 0; !rc && i < 2; ++i) {
     he = hipEventCreate(&c.prof_ev[i]);
@@ -243,9 +244,19 @@ static int check_layer_args(evict_ctx* ctx, const evict_layer_weights* w, const 
   EVICT_REQUIRE(max_ctx_host >= 0 && max_ctx_host <= ctx->max_ctx, EVICT_E_INVALID,
                 "evict_verify_layer: max_ctx_host=%d outside [0,%d]", max_ctx_host, ctx->max_ctx);
   EVICT_REQUIRE(max_ctx_host == 0 || (k_cache && v_cache), EVICT_E_INVALID, "evict_verify_layer: null KV cache");
-  EVICT_REQUIRE(kv_head_stride >= (int64_t)max_ctx_host * m.D && kv_seq_stride >= 0, EVICT_E_INVALID,
-                "evict_verify_layer: kv_head_stride=%lld is smaller than max_ctx_host*D", (long long)kv_head_stride);
-  EVICT_REQUIRE(B == 1 || kv_seq_stride >= kv_head_stride * m.Hkv, EVICT_E_INVALID, "evict_verify_layer: kv_seq_stride too small");
+  if (ctx->paging.table) {
+    // paged caches: kv_seq_stride is the distance between pages
+    const int64_t page = (int64_t)1 << ctx->paging.page_shift;
+    EVICT_REQUIRE(kv_head_stride >= page * m.D, EVICT_E_INVALID, "paged KV: kv_head_stride=%lld is smaller than page_size*D",
+                  (long long)kv_head_stride);
+    EVICT_REQUIRE(kv_seq_stride >= kv_head_stride * m.Hkv, EVICT_E_INVALID, "paged KV: page_stride=%lld is smaller than Hkv*kv_head_stride",
+                  (long long)kv_seq_stride);
+    EVICT_REQUIRE(kv_head_stride % 8 == 0 && kv_seq_stride % 8 == 0, EVICT_E_INVALID, "paged KV: strides must be multiples of 8 elements");
+  } else {
+    EVICT_REQUIRE(kv_head_stride >= (int64_t)max_ctx_host * m.D && kv_seq_stride >= 0, EVICT_E_INVALID,
+                  "evict_verify_layer: kv_head_stride=%lld is smaller than max_ctx_host*D", (long long)kv_head_stride);
+    EVICT_REQUIRE(B == 1 || kv_seq_stride >= kv_head_stride * m.Hkv, EVICT_E_INVALID, "evict_verify_layer: kv_seq_stride too small");
+  }
   EVICT_REQUIRE(aligned16(x_in) && aligned16(x_out) && aligned16(k_new) && aligned16(v_new) && aligned16(k_cache) && aligned16(v_cache),
                 EVICT_E_INVALID, "evict_verify_layer: pointers must be 16-byte aligned");
   EVICT_REQUIRE(x_in != x_out, EVICT_E_INVALID, "evict_verify_layer: x_out must not alias x_in");
@@ -421,6 +432,28 @@ int evict_verify_stack(evict_ctx* ctx, const evict_layer_weights* layers, int n_
     if (rc) return rc;
   }
   return EVICT_OK;
+}
+
+int evict_verify_stack_paged(evict_ctx* ctx, const evict_layer_weights* layers, int n_layers, const int32_t* tree_off,
+                             const int32_t* parent, int B, int T, const void* const* k_pools, const void* const* v_pools,
+                             int64_t page_stride, int64_t kv_head_stride, const int32_t* block_table, int table_stride,
+                             int page_size, int n_pages, const int32_t* ctx_len, int max_ctx_host, const void* x_in,
+                             void* x_out, void* const* k_new, void* const* v_new, void* stream) {
+  EVICT_REQUIRE(ctx && block_table && k_pools && v_pools, EVICT_E_INVALID, "evict_verify_stack_paged: null pointer argument");
+  EVICT_REQUIRE(page_size >= 1 && page_size <= 65536 && (page_size & (page_size - 1)) == 0, EVICT_E_INVALID,
+                "evict_verify_stack_paged: page_size=%d must be a power of two in [1, 65536]", page_size);
+  EVICT_REQUIRE(n_pages >= 1 && table_stride >= 1, EVICT_E_INVALID, "evict_verify_stack_paged: n_pages=%d table_stride=%d", n_pages,
+                table_stride);
+  EVICT_REQUIRE((int64_t)table_stride * page_size >= max_ctx_host, EVICT_E_INVALID,
+                "evict_verify_stack_paged: a table row covers %lld positions, max_ctx_host is %d", (long long)table_stride * page_size,
+                max_ctx_host);
+  int shift = 0;
+  while ((1 << shift) < page_size) ++shift;
+  ctx->paging = KvPaging{block_table, table_stride, shift, n_pages};
+  const int rc = evict_verify_stack(ctx, layers, n_layers, tree_off, parent, B, T, k_pools, v_pools, page_stride, kv_head_stride,
+                                    ctx_len, max_ctx_host, x_in, x_out, k_new, v_new, stream);
+  ctx->paging = KvPaging{nullptr, 0, 0, 0};
+  return rc;
 }
 
 int evict_lm_head_argmax(evict_ctx* ctx, const void* x, const void* g_final, const void* wlm_packed, int T, int32_t* next,

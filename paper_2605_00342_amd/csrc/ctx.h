@@ -4,6 +4,15 @@
 
 namespace evict { struct WorkRec; }
 
+// Addressing of a paged KV cache: position p of sequence b lives in page table[b][p >> page_shift]
+// at row p & (page size - 1). table == nullptr: contiguous caches.
+struct KvPaging {
+  const int32_t* table;  // [B][table_stride] page ids
+  int table_stride;
+  int page_shift;        // log2 of the page size in positions
+  int n_pages;           // pages in every pool: ids outside [0, n_pages) are flagged and read as page 0
+};
+
 struct evict_ctx {
   evict_model_desc m;
   int max_tokens, max_batch, max_ctx;
@@ -13,6 +22,7 @@ struct evict_ctx {
   int timing;            // record stage events in evict_verify_layer
   int timed_once;        // a timed call has been recorded
   int capturing;         // a stream capture opened by evict_graph_begin is in progress
+  KvPaging paging;       // set by the paged entry points for the duration of their call, else table == nullptr
   hipEvent_t ev[EVICT_N_STAGES + 1];
   // ---- device scratch (all sized for max_tokens) ----
   int32_t* status;       // [1] sticky status bits

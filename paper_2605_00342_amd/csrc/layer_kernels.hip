@@ -207,7 +207,8 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(
     const void* __restrict__ q, const void* __restrict__ kc, const void* __restrict__ vc, long long seq_stride,
     long long head_stride, const int32_t* __restrict__ ctx_len, int max_ctx, const int32_t* __restrict__ tree_off,
     const void* __restrict__ k_new, const void* __restrict__ v_new, const uint64_t* __restrict__ anc, int Hq, int Hkv,
-    int D, int ctx_splits, int T, float* __restrict__ part_o, float* __restrict__ part_ml) {
+    int D, int ctx_splits, int T, float* __restrict__ part_o, float* __restrict__ part_ml, const KvPaging pg,
+    int32_t* __restrict__ status) {
   extern __shared__ float s_dyn[];
   const int ldk = D + 1;
   float* s_k = s_dyn;                    // [64][D+1]
@@ -236,7 +237,15 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(
     size_t src;
     float kv, vv;
     if (!tree_part) {
-      src = (size_t)b * seq_stride + (size_t)g * head_stride + (size_t)(key0 + j) * D + c;
+      if (pg.table) {
+        // paged cache: seq_stride is the distance between pages
+        const int pos = key0 + j;
+        int pid = pg.table[(size_t)b * pg.table_stride + (pos >> pg.page_shift)];
+        if ((unsigned)pid >= (unsigned)pg.n_pages) { atomicOr(status, ST_BAD_PAGE); pid = 0; }
+        src = (size_t)pid * seq_stride + (size_t)g * head_stride + (size_t)(pos & ((1 << pg.page_shift) - 1)) * D + c;
+      } else {
+        src = (size_t)b * seq_stride + (size_t)g * head_stride + (size_t)(key0 + j) * D + c;
+      }
       kv = load_elem<ST>(kc, src);
       vv = load_elem<ST>(vc, src);
     } else {
@@ -300,13 +309,14 @@ constexpr int kMfmaKeys = 128;
 // per CU overlap each other's staging. NW = 8 (many row tiles, several chunks per split): two LDS
 // buffers, the next chunk travels global -> registers while the current one is computed and is
 // written to the other buffer afterwards; one barrier per chunk.
-template <int D, int NW>
+template <int D, int NW, bool PAGED = false>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) void attn_partial_mfma_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ kc, const uint16_t* __restrict__ vc,
     long long seq_stride, long long head_stride, const int32_t* __restrict__ ctx_len, int max_ctx,
     const int32_t* __restrict__ tree_off, const uint16_t* __restrict__ k_new, const uint16_t* __restrict__ v_new,
     const uint64_t* __restrict__ anc, int Hq, int Hkv, int ctx_splits, int keys_per_split, int row_blocks, int T,
-    float* __restrict__ part_o, float* __restrict__ part_ml, int n_single, int n_seq) {
+    float* __restrict__ part_o, float* __restrict__ part_ml, int n_single, int n_seq, const KvPaging pg,
+    int32_t* __restrict__ status) {
   constexpr int LDK = D + 8;            // bf16 per K row in LDS (16-byte pad)
   constexpr int LDV = kMfmaKeys + 4;    // bf16 per V^T row in LDS
   constexpr int CH = D / 8;             // 16-byte chunks per row
@@ -373,9 +383,21 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
     for (int kb = 0; kb < KB; ++kb) Qf[kb] = *reinterpret_cast<const u32x4*>(qrow + kb * 32);
     if (tree_part) { a0 = anc[2 * (size_t)t]; a1 = anc[2 * (size_t)t + 1]; }
   }
-  const uint16_t* kbase = tree_part ? k_new + ((size_t)lo * Hkv + g) * D : kc + (size_t)b * seq_stride + (size_t)g * head_stride;
-  const uint16_t* vbase = tree_part ? v_new + ((size_t)lo * Hkv + g) * D : vc + (size_t)b * seq_stride + (size_t)g * head_stride;
+  // (paged cache: seq_stride is the distance between pages and the page comes from the table per key)
+  const size_t seq_off = PAGED ? 0 : (size_t)b * seq_stride;
+  const uint16_t* kbase = tree_part ? k_new + ((size_t)lo * Hkv + g) * D : kc + seq_off + (size_t)g * head_stride;
+  const uint16_t* vbase = tree_part ? v_new + ((size_t)lo * Hkv + g) * D : vc + seq_off + (size_t)g * head_stride;
   const size_t kstep = tree_part ? (size_t)Hkv * D : (size_t)D;  // elements between consecutive keys
+  const int32_t* ptab = PAGED ? pg.table + (size_t)b * pg.table_stride : nullptr;
+  // element offset of key position `pos` from kbase / vbase
+  auto key_off = [&](int pos) -> size_t {
+    if (PAGED && !tree_part) {
+      int pid = ptab[pos >> pg.page_shift];
+      if ((unsigned)pid >= (unsigned)pg.n_pages) { atomicOr(status, ST_BAD_PAGE); pid = 0; }
+      return (size_t)pid * seq_stride + (size_t)(pos & ((1 << pg.page_shift) - 1)) * D;
+    }
+    return (size_t)pos * kstep;
+  };
 
   // running softmax state of this wavefront's 16 rows over the chunks of the split
   f32x4 O[DT];
@@ -394,15 +416,15 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
     for (int it = 0; it < KI; ++it) {
       const int idx = tid + NT * it, j = idx / CH, c = idx - j * CH;
       kreg[it] = u32x4{0, 0, 0, 0};  // keys past the end are zeros
-      if (j < nk) kreg[it] = *reinterpret_cast<const u32x4*>(kbase + (size_t)(kc0 + j) * kstep + c * 8);
+      if (j < nk) kreg[it] = *reinterpret_cast<const u32x4*>(kbase + key_off(kc0 + j) + c * 8);
     }
 #pragma unroll
     for (int it = 0; it < VI; ++it) {
       const int idx = tid + NT * it, jp = idx / CH, c = idx - jp * CH;
       vreg0[it] = u32x4{0, 0, 0, 0};
       vreg1[it] = u32x4{0, 0, 0, 0};
-      if (2 * jp < nk) vreg0[it] = *reinterpret_cast<const u32x4*>(vbase + (size_t)(kc0 + 2 * jp) * kstep + c * 8);
-      if (2 * jp + 1 < nk) vreg1[it] = *reinterpret_cast<const u32x4*>(vbase + (size_t)(kc0 + 2 * jp + 1) * kstep + c * 8);
+      if (2 * jp < nk) vreg0[it] = *reinterpret_cast<const u32x4*>(vbase + key_off(kc0 + 2 * jp) + c * 8);
+      if (2 * jp + 1 < nk) vreg1[it] = *reinterpret_cast<const u32x4*>(vbase + key_off(kc0 + 2 * jp + 1) + c * 8);
     }
   };
   // K row-major, V transposed (two keys per dword)
@@ -1264,6 +1286,10 @@ int kernels_setup(const evict_model_desc& m) {
   EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)attn_partial_mfma_kernel<64, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_mfma_lds_bytes(64)));
   EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)attn_partial_mfma_kernel<128, 8>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * (int)attn_mfma_lds_bytes(128)));
   EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)attn_partial_mfma_kernel<64, 8>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * (int)attn_mfma_lds_bytes(64)));
+  EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)attn_partial_mfma_kernel<128, 4, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_mfma_lds_bytes(128)));
+  EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)attn_partial_mfma_kernel<64, 4, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_mfma_lds_bytes(64)));
+  EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)attn_partial_mfma_kernel<128, 8, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * (int)attn_mfma_lds_bytes(128)));
+  EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)attn_partial_mfma_kernel<64, 8, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * (int)attn_mfma_lds_bytes(64)));
   const size_t rl = router_lds_bytes(m);
   EVICT_REQUIRE(rl <= 152 * 1024, EVICT_E_UNSUPPORTED, "router needs %zu bytes of LDS (limit 152 KiB): d too large", rl);
   EVICT_REQUIRE(m.d <= 64 * 8 * (m.dtype == EVICT_BF16 ? 8 : 4), EVICT_E_UNSUPPORTED, "router keeps a token row in registers: d=%d too large", m.d);
@@ -1311,11 +1337,14 @@ int launch_attention(const evict_ctx* c, const void* kc, const void* vc, long lo
     const size_t lds = attn_mfma_lds_bytes(m.D) * (nw == 8 ? 2 : 1);
 #define EVICT_ATTN_ARGS (const uint16_t*)c->q, (const uint16_t*)kc, (const uint16_t*)vc, seq_stride, head_stride, ctx_len, \
                         max_ctx_host, tree_off, (const uint16_t*)k_new, (const uint16_t*)v_new, c->anc, m.Hq, m.Hkv,       \
-                        ctx_splits, keys, rb, T, c->part_o, c->part_ml, B == 1 ? T : 0, B
-    if (m.D == 128 && nw == 4) hipLaunchKernelGGL((attn_partial_mfma_kernel<128, 4>), grid, dim3(256), lds, s, EVICT_ATTN_ARGS);
-    else if (m.D == 128) hipLaunchKernelGGL((attn_partial_mfma_kernel<128, 8>), grid, dim3(512), lds, s, EVICT_ATTN_ARGS);
-    else if (nw == 4) hipLaunchKernelGGL((attn_partial_mfma_kernel<64, 4>), grid, dim3(256), lds, s, EVICT_ATTN_ARGS);
-    else hipLaunchKernelGGL((attn_partial_mfma_kernel<64, 8>), grid, dim3(512), lds, s, EVICT_ATTN_ARGS);
+                        ctx_splits, keys, rb, T, c->part_o, c->part_ml, B == 1 ? T : 0, B, c->paging, c->status
+#define EVICT_ATTN_LAUNCH(PAGED_)                                                                                              \
+    if (m.D == 128 && nw == 4) hipLaunchKernelGGL((attn_partial_mfma_kernel<128, 4, PAGED_>), grid, dim3(256), lds, s, EVICT_ATTN_ARGS); \
+    else if (m.D == 128) hipLaunchKernelGGL((attn_partial_mfma_kernel<128, 8, PAGED_>), grid, dim3(512), lds, s, EVICT_ATTN_ARGS);       \
+    else if (nw == 4) hipLaunchKernelGGL((attn_partial_mfma_kernel<64, 4, PAGED_>), grid, dim3(256), lds, s, EVICT_ATTN_ARGS);           \
+    else hipLaunchKernelGGL((attn_partial_mfma_kernel<64, 8, PAGED_>), grid, dim3(512), lds, s, EVICT_ATTN_ARGS)
+    if (c->paging.table) { EVICT_ATTN_LAUNCH(true); } else { EVICT_ATTN_LAUNCH(false); }
+#undef EVICT_ATTN_LAUNCH
 #undef EVICT_ATTN_ARGS
   } else {
     keys = kAttnKeys;
@@ -1323,7 +1352,7 @@ int launch_attention(const evict_ctx* c, const void* kc, const void* vc, long lo
     nsplits = ctx_splits + EVICT_MAX_TREE_NODES / keys;
     hipLaunchKernelGGL(attn_partial_kernel<F32>, dim3(nsplits, m.Hkv, B), dim3(256), attn_partial_lds_bytes(m.D), s, c->q,
                        kc, vc, seq_stride, head_stride, ctx_len, max_ctx_host, tree_off, k_new, v_new, c->anc, m.Hq,
-                       m.Hkv, m.D, ctx_splits, T, c->part_o, c->part_ml);
+                       m.Hkv, m.D, ctx_splits, T, c->part_o, c->part_ml, c->paging, c->status);
   }
   int rc = launch_status("attention partial kernel");
   if (rc) return rc;

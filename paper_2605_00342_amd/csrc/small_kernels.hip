@@ -620,7 +620,8 @@ __global__ __launch_bounds__(256) void kv_commit_kernel(
     const KvLayerPtrs lp, int Hkv, int head_words,
     const int32_t* __restrict__ tree_off, const int32_t* __restrict__ path, int path_stride,
     const int32_t* __restrict__ path_len, long long seq_words, long long head_stride_words,
-    const int32_t* __restrict__ ctx_len, int capacity, int32_t* __restrict__ ctx_len_out, int32_t* __restrict__ status) {
+    const int32_t* __restrict__ ctx_len, int capacity, int32_t* __restrict__ ctx_len_out, int32_t* __restrict__ status,
+    const KvPaging pg) {
   const int j = blockIdx.x, b = blockIdx.y, layer = blockIdx.z;
   const uint32_t* __restrict__ k_new = lp.k_new[layer];
   const uint32_t* __restrict__ v_new = lp.v_new[layer];
@@ -645,9 +646,21 @@ __global__ __launch_bounds__(256) void kv_commit_kernel(
   }
   const size_t src = (size_t)(tree_off[b] + node) * Hkv * head_words;
   const int row_words = Hkv * head_words;
+  // start of the destination row of head 0: contiguous cache, or (paged: seq_words is the distance
+  // between pages) the page the table names for position L + j
+  size_t row0 = (size_t)b * seq_words + (size_t)(L + j) * head_words;
+  if (pg.table) {
+    const int pos = L + j;
+    const int pid = pg.table[(size_t)b * pg.table_stride + (pos >> pg.page_shift)];
+    if ((unsigned)pid >= (unsigned)pg.n_pages) {  // never write through a bad page id
+      if (status && threadIdx.x == 0) atomicOr(status, ST_BAD_PAGE);
+      return;
+    }
+    row0 = (size_t)pid * seq_words + (size_t)(pos & ((1 << pg.page_shift) - 1)) * head_words;
+  }
   for (int i = threadIdx.x; i < row_words; i += 256) {
     const int h = i / head_words, c = i - h * head_words;
-    const size_t dst = (size_t)b * seq_words + (size_t)h * head_stride_words + (size_t)(L + j) * head_words + c;
+    const size_t dst = row0 + (size_t)h * head_stride_words + c;
     k_cache[dst] = k_new[src + i];
     v_cache[dst] = v_new[src + i];
   }
@@ -820,7 +833,7 @@ static int kv_commit_impl(const char* who, evict_ctx* ctx, int dtype, int Hkv, i
                           const void* const* v_new, int n_layers, const int32_t* tree_off, const int32_t* path, int path_stride,
                           const int32_t* path_len, void* const* k_caches, void* const* v_caches, int64_t kv_seq_stride,
                           int64_t kv_head_stride, const int32_t* ctx_len, int capacity, int32_t* ctx_len_out, int B,
-                          void* stream) {
+                          void* stream, const KvPaging pg = KvPaging{nullptr, 0, 0, 0}) {
   EVICT_REQUIRE(k_new && v_new && tree_off && path && path_len && k_caches && v_caches && ctx_len && ctx_len_out,
                 EVICT_E_INVALID, "%s: null pointer argument", who);
   EVICT_REQUIRE(dtype == EVICT_F32 || dtype == EVICT_BF16, EVICT_E_INVALID, "%s: unknown dtype %d", who, dtype);
@@ -829,9 +842,18 @@ static int kv_commit_impl(const char* who, evict_ctx* ctx, int dtype, int Hkv, i
                 EVICT_E_INVALID, "%s: B, Hkv, D, path_stride out of range", who);
   const int eb = dtype == EVICT_BF16 ? 2 : 4;
   EVICT_REQUIRE((D * eb) % 4 == 0, EVICT_E_INVALID, "%s: a head row must be a multiple of 4 bytes", who);
-  EVICT_REQUIRE(capacity >= 1 && kv_head_stride >= (int64_t)capacity * D && (kv_head_stride * eb) % 4 == 0 &&
-                    (kv_seq_stride * eb) % 4 == 0 && (B == 1 || kv_seq_stride >= kv_head_stride * Hkv),
-                EVICT_E_INVALID, "%s: cache strides do not hold capacity=%d rows per head", who, capacity);
+  if (pg.table) {
+    const int64_t page = (int64_t)1 << pg.page_shift;
+    EVICT_REQUIRE(capacity >= 1 && (int64_t)pg.table_stride * page >= capacity, EVICT_E_INVALID,
+                  "%s: a table row covers %lld positions, capacity is %d", who, (long long)pg.table_stride * page, capacity);
+    EVICT_REQUIRE(kv_head_stride >= page * D && kv_seq_stride >= kv_head_stride * Hkv && (kv_head_stride * eb) % 4 == 0 &&
+                      (kv_seq_stride * eb) % 4 == 0,
+                  EVICT_E_INVALID, "%s: page strides do not hold page_size=%lld rows per head", who, (long long)page);
+  } else {
+    EVICT_REQUIRE(capacity >= 1 && kv_head_stride >= (int64_t)capacity * D && (kv_head_stride * eb) % 4 == 0 &&
+                      (kv_seq_stride * eb) % 4 == 0 && (B == 1 || kv_seq_stride >= kv_head_stride * Hkv),
+                  EVICT_E_INVALID, "%s: cache strides do not hold capacity=%d rows per head", who, capacity);
+  }
   EVICT_REQUIRE(ctx_len_out != ctx_len, EVICT_E_INVALID, "%s: ctx_len_out must not alias ctx_len", who);
   for (int l = 0; l < n_layers; ++l)
     EVICT_REQUIRE(k_new[l] && v_new[l] && k_caches[l] && v_caches[l], EVICT_E_INVALID, "%s: null pointer for layer %d", who, l);
@@ -847,7 +869,7 @@ static int kv_commit_impl(const char* who, evict_ctx* ctx, int dtype, int Hkv, i
     }
     hipLaunchKernelGGL(kv_commit_kernel, dim3(path_stride, B, nl), dim3(256), 0, (hipStream_t)stream, lp, Hkv, head_words,
                        tree_off, path, path_stride, path_len, (long long)(kv_seq_stride * eb / 4),
-                       (long long)(kv_head_stride * eb / 4), ctx_len, capacity, ctx_len_out, ctx ? ctx->status : nullptr);
+                       (long long)(kv_head_stride * eb / 4), ctx_len, capacity, ctx_len_out, ctx ? ctx->status : nullptr, pg);
     int rc = launch_status("kv_commit_kernel");
     if (rc) return rc;
   }
@@ -868,6 +890,23 @@ int evict_kv_commit_stack(evict_ctx* ctx, int dtype, int Hkv, int D, const void*
                           const int32_t* ctx_len, int capacity, int32_t* ctx_len_out, int B, void* stream) {
   return kv_commit_impl("evict_kv_commit_stack", ctx, dtype, Hkv, D, k_new, v_new, n_layers, tree_off, path, path_stride,
                         path_len, k_caches, v_caches, kv_seq_stride, kv_head_stride, ctx_len, capacity, ctx_len_out, B, stream);
+}
+
+int evict_kv_commit_stack_paged(evict_ctx* ctx, int dtype, int Hkv, int D, const void* const* k_new, const void* const* v_new,
+                                int n_layers, const int32_t* tree_off, const int32_t* path, int path_stride,
+                                const int32_t* path_len, void* const* k_pools, void* const* v_pools, int64_t page_stride,
+                                int64_t kv_head_stride, const int32_t* block_table, int table_stride, int page_size, int n_pages,
+                                const int32_t* ctx_len, int capacity, int32_t* ctx_len_out, int B, void* stream) {
+  EVICT_REQUIRE(block_table, EVICT_E_INVALID, "evict_kv_commit_stack_paged: null block table");
+  EVICT_REQUIRE(page_size >= 1 && page_size <= 65536 && (page_size & (page_size - 1)) == 0, EVICT_E_INVALID,
+                "evict_kv_commit_stack_paged: page_size=%d must be a power of two in [1, 65536]", page_size);
+  EVICT_REQUIRE(n_pages >= 1 && table_stride >= 1, EVICT_E_INVALID, "evict_kv_commit_stack_paged: n_pages=%d table_stride=%d",
+                n_pages, table_stride);
+  int shift = 0;
+  while ((1 << shift) < page_size) ++shift;
+  return kv_commit_impl("evict_kv_commit_stack_paged", ctx, dtype, Hkv, D, k_new, v_new, n_layers, tree_off, path, path_stride,
+                        path_len, k_pools, v_pools, page_stride, kv_head_stride, ctx_len, capacity, ctx_len_out, B, stream,
+                        KvPaging{block_table, table_stride, shift, n_pages});
 }
 
 }  // extern "C"

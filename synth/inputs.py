@@ -21,7 +21,7 @@ __all__ = [
     "ModelCfg", "CONFIGS", "philox", "round_to_bf16", "bf16_bits", "store",
     "tree_random_parents", "tree_eagle_style", "tree_bfs_random", "tree_chain", "tree_star",
     "draft_probs", "hidden_states", "layer_weights", "kv_cache", "cost_linear_in_union",
-    "plant_draft_tokens", "make_case", "concat_trees",
+    "plant_draft_tokens", "make_case", "concat_trees", "to_pages",
 ]
 
 
@@ -261,6 +261,31 @@ def kv_cache(cfg: ModelCfg, L: int, g: np.random.Generator):
     K = store(g.standard_normal((cfg.Hkv, L, cfg.D), dtype=np.float32), cfg.dtype)
     V = store(g.standard_normal((cfg.Hkv, L, cfg.D), dtype=np.float32), cfg.dtype)
     return K, V
+
+
+def to_pages(Ks, Vs, page_size: int, capacities, g: np.random.Generator, spare_pages: int = 3, fill: float = 3.0e4):
+    """Scatter per-sequence caches [Hkv, L_b, D] into page pools [n_pages, Hkv, page_size, D] under a
+    random page assignment (pure data movement). Every sequence gets pages for capacities[b]
+    positions; rows no cache position occupies, and `spare_pages` pages nobody owns, hold `fill`
+    (a reader that strays shows up). Table entries past a sequence's pages hold an id outside the
+    pool. Returns pool_k, pool_v, table int32 [B, max pages per sequence], n_pages."""
+    B = len(Ks)
+    Hkv, _, D = np.asarray(Ks[0]).shape
+    need = [(int(c) + page_size - 1) // page_size for c in capacities]
+    n_pages = sum(need) + spare_pages
+    ids = g.permutation(n_pages)
+    pool_k = np.full((n_pages, Hkv, page_size, D), fill, dtype=np.float32)
+    pool_v = np.full((n_pages, Hkv, page_size, D), -fill, dtype=np.float32)
+    table = np.full((B, max(max(need), 1)), n_pages + 5, dtype=np.int32)
+    at = 0
+    for b in range(B):
+        table[b, :need[b]] = ids[at:at + need[b]]
+        at += need[b]
+        K, V = np.asarray(Ks[b]), np.asarray(Vs[b])
+        for p in range(K.shape[1]):
+            pool_k[table[b, p // page_size], :, p % page_size, :] = K[:, p, :]
+            pool_v[table[b, p // page_size], :, p % page_size, :] = V[:, p, :]
+    return pool_k, pool_v, table, n_pages
 
 
 def cost_linear_in_union(kmax: int, E: int, k: int, a: float = 1.0, b: float = 0.05) -> np.ndarray:
