@@ -51,6 +51,8 @@ def parse():
     ap.add_argument("--cost", default="profile", choices=["profile", "surface"],
                     help="--loop: C(k) as profiled on the loop's own inputs, or collapsed from a cost surface over "
                          "(k, expert union) fitted to profiles at child noise 0.2 / the run's sigma / 1.0")
+    ap.add_argument("--kv-page", type=int, default=0,
+                    help="page size of a paged KV cache (power of two; pages assigned at random); 0 = contiguous caches")
     ap.add_argument("--launch", default="eager", choices=["graph", "eager"],
                     help="timed steps call the entry points (default), or replay one captured HIP graph per weight copy")
     ap.add_argument("--loop", action="store_true",
@@ -322,12 +324,29 @@ def main():
     path_len = torch.zeros(B, dtype=i32, device=dev)
     bonus = torch.zeros(B, dtype=i32, device=dev)
 
+    paged = None
+    if args.kv_page:
+        # the same cache contents scattered over randomly assigned pages; read through a block table
+        P = args.kv_page
+        pk, pv, table, n_pages = synth.to_pages(case["K"], case["V"], P, [int(v) for v in case["ctx_len"]],
+                                                synth.philox(args.seed, 960))
+        paged = dict(pk=harness.to_dev(pk, cfg.dtype), pv=harness.to_dev(pv, cfg.dtype), table=harness.dev_i32(table),
+                     stride=table.shape[1], n_pages=n_pages, P=P)
+
+    def layer_call(i):
+        w = weight_sets[i % len(weight_sets)]
+        if paged:
+            ev.evict_verify_stack_paged(layer.ctx, [w], dc.tree_off, dc.parent, B, T, [paged["pk"]], [paged["pv"]],
+                                        cfg.Hkv * paged["P"] * cfg.D, paged["P"] * cfg.D, paged["table"], paged["stride"],
+                                        paged["P"], paged["n_pages"], dc.ctx_len, L, dc.x, dc.out, [dc.k_new], [dc.v_new])
+        else:
+            ev.evict_verify_layer(layer.ctx, w, dc.tree_off, dc.parent, B, T, dc.k_cache, dc.v_cache, dc.seq_stride,
+                                  dc.head_stride, dc.ctx_len, L, dc.x, dc.out, dc.k_new, dc.v_new, None)
+
     def step(i):
         ev.evict_select_prefix(None, dc.tree_off, dc.parent, q_dev, B, T, cost_dev, N, sel["k_star"], sel["keep"],
                                sel["new_parent"], sel["new_off"], sel["est"])
-        ev.evict_verify_layer(layer.ctx, weight_sets[i % len(weight_sets)], dc.tree_off, dc.parent, B, T, dc.k_cache,
-                              dc.v_cache, dc.seq_stride, dc.head_stride, dc.ctx_len, L, dc.x, dc.out, dc.k_new,
-                              dc.v_new, None)
+        layer_call(i)
         ev.evict_accept_path(None, dc.tree_off, dc.parent, dt_dev, tn_dev, B, path, N, path_len, bonus)
 
     # one checked run: union size for the byte count
@@ -394,10 +413,7 @@ def main():
     # The same layer calls without the stage events, between two events on the launch stream: what
     # the stage events add per stage is (sum of stage times - this) / stages. (An event pair around
     # nothing, like the empty "shared" stage, costs more than an event between two kernels does.)
-    def layer_only(i):
-        ev.evict_verify_layer(layer.ctx, weight_sets[i % len(weight_sets)], dc.tree_off, dc.parent, B, T, dc.k_cache,
-                              dc.v_cache, dc.seq_stride, dc.head_stride, dc.ctx_len, L, dc.x, dc.out, dc.k_new,
-                              dc.v_new, None)
+    layer_only = layer_call
     for i in range(5):
         layer_only(i)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)

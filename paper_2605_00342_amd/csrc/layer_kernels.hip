@@ -389,15 +389,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
   const uint16_t* vbase = tree_part ? v_new + ((size_t)lo * Hkv + g) * D : vc + seq_off + (size_t)g * head_stride;
   const size_t kstep = tree_part ? (size_t)Hkv * D : (size_t)D;  // elements between consecutive keys
   const int32_t* ptab = PAGED ? pg.table + (size_t)b * pg.table_stride : nullptr;
-  // element offset of key position `pos` from kbase / vbase
-  auto key_off = [&](int pos) -> size_t {
-    if (PAGED && !tree_part) {
-      int pid = ptab[pos >> pg.page_shift];
-      if ((unsigned)pid >= (unsigned)pg.n_pages) { atomicOr(status, ST_BAD_PAGE); pid = 0; }
-      return (size_t)pid * seq_stride + (size_t)(pos & ((1 << pg.page_shift) - 1)) * D;
-    }
-    return (size_t)pos * kstep;
-  };
+  const int pmask = (1 << pg.page_shift) - 1;
 
   // running softmax state of this wavefront's 16 rows over the chunks of the split
   f32x4 O[DT];
@@ -406,25 +398,61 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
   float m_run = -INFINITY, l_run = 0.0f;
 
   // K/V of a chunk travel global -> registers -> LDS, all loads issued before the first LDS
-  // write so one memory round trip covers the chunk.
+  // write so one memory round trip covers the chunk. Paged cache: the page ids of all of this
+  // thread's keys are requested first (one more round trip per chunk, not one per key), ids
+  // outside the pool are replaced by page 0 and reported once.
   constexpr int KI = kMfmaKeys * CH / NT, VI = (kMfmaKeys / 2) * CH / NT;
   u32x4 kreg[KI], vreg0[VI], vreg1[VI];
   auto fetch_chunk = [&](int kc0) {
     int nk = key_end - kc0;
     nk = nk > kMfmaKeys ? kMfmaKeys : nk;
+    const bool paged = PAGED && !tree_part;
+    int pk[KI], pv0[VI], pv1[VI];
+    if (paged) {
+#pragma unroll
+      for (int it = 0; it < KI; ++it) {
+        const int j = (tid + NT * it) / CH;
+        pk[it] = j < nk ? ptab[(kc0 + j) >> pg.page_shift] : 0;
+      }
+#pragma unroll
+      for (int it = 0; it < VI; ++it) {
+        const int jp = (tid + NT * it) / CH;
+        pv0[it] = 2 * jp < nk ? ptab[(kc0 + 2 * jp) >> pg.page_shift] : 0;
+        pv1[it] = 2 * jp + 1 < nk ? ptab[(kc0 + 2 * jp + 1) >> pg.page_shift] : 0;
+      }
+      bool bad = false;
+#pragma unroll
+      for (int it = 0; it < KI; ++it) {
+        const bool ok = (unsigned)pk[it] < (unsigned)pg.n_pages;
+        bad |= !ok;
+        pk[it] = ok ? pk[it] : 0;
+      }
+#pragma unroll
+      for (int it = 0; it < VI; ++it) {
+        const bool ok0 = (unsigned)pv0[it] < (unsigned)pg.n_pages, ok1 = (unsigned)pv1[it] < (unsigned)pg.n_pages;
+        bad |= !ok0 || !ok1;
+        pv0[it] = ok0 ? pv0[it] : 0;
+        pv1[it] = ok1 ? pv1[it] : 0;
+      }
+      if (bad) atomicOr(status, ST_BAD_PAGE);
+    }
+    // element offset of key position `pos` (page id `pid` when paged) from kbase / vbase
+    auto key_off = [&](int pos, int pid) -> size_t {
+      return paged ? (size_t)pid * seq_stride + (size_t)(pos & pmask) * D : (size_t)pos * kstep;
+    };
 #pragma unroll
     for (int it = 0; it < KI; ++it) {
       const int idx = tid + NT * it, j = idx / CH, c = idx - j * CH;
       kreg[it] = u32x4{0, 0, 0, 0};  // keys past the end are zeros
-      if (j < nk) kreg[it] = *reinterpret_cast<const u32x4*>(kbase + key_off(kc0 + j) + c * 8);
+      if (j < nk) kreg[it] = *reinterpret_cast<const u32x4*>(kbase + key_off(kc0 + j, paged ? pk[it] : 0) + c * 8);
     }
 #pragma unroll
     for (int it = 0; it < VI; ++it) {
       const int idx = tid + NT * it, jp = idx / CH, c = idx - jp * CH;
       vreg0[it] = u32x4{0, 0, 0, 0};
       vreg1[it] = u32x4{0, 0, 0, 0};
-      if (2 * jp < nk) vreg0[it] = *reinterpret_cast<const u32x4*>(vbase + key_off(kc0 + 2 * jp) + c * 8);
-      if (2 * jp + 1 < nk) vreg1[it] = *reinterpret_cast<const u32x4*>(vbase + key_off(kc0 + 2 * jp + 1) + c * 8);
+      if (2 * jp < nk) vreg0[it] = *reinterpret_cast<const u32x4*>(vbase + key_off(kc0 + 2 * jp, paged ? pv0[it] : 0) + c * 8);
+      if (2 * jp + 1 < nk) vreg1[it] = *reinterpret_cast<const u32x4*>(vbase + key_off(kc0 + 2 * jp + 1, paged ? pv1[it] : 0) + c * 8);
     }
   };
   // K row-major, V transposed (two keys per dword)
