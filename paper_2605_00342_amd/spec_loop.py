@@ -43,10 +43,14 @@ class IterationLog:
 
 class SpecLoop:
     def __init__(self, cfg, ctx, layers, k_caches, v_caches, seq_stride, head_stride, capacity, n_max,
-                 lm_head=None, device="cuda:0"):
+                 lm_head=None, device="cuda:0", block_table=None, page_size=0, n_pages=0):
         """layers: list of LayerWeights; k_caches / v_caches: one [1][Hkv][capacity][D] tensor per layer;
-        lm_head: (g_final, wlm_packed) or None (then every draft must carry target_next)."""
+        lm_head: (g_final, wlm_packed) or None (then every draft must carry target_next).
+        Paged caches: block_table int32 [1][pages] (pages for all `capacity` positions), page_size,
+        n_pages; k_caches / v_caches are then the page pools [n_pages][Hkv][page_size][D] and
+        seq_stride is the distance between pages."""
         self.cfg, self.ctx, self.layers = cfg, ctx, layers
+        self.block_table, self.page_size, self.n_pages = block_table, page_size, n_pages
         self.kc, self.vc = k_caches, v_caches
         self.seq_stride, self.head_stride, self.capacity = seq_stride, head_stride, capacity
         self.n_max, self.lm_head = n_max, lm_head
@@ -92,16 +96,27 @@ class SpecLoop:
         else:
             k = n
             off, par, x, tok, tn = d.tree_off, d.parent, d.x, d.tok, d.target_next
-        ev.evict_verify_stack(self.ctx, self.layers, off, par, 1, k, self.kc, self.vc, self.seq_stride, self.head_stride,
-                              cl_in, max(self.ctx_len_host, 1), x, self.out, self.k_new, self.v_new)
+        if self.block_table is not None:
+            ev.evict_verify_stack_paged(self.ctx, self.layers, off, par, 1, k, self.kc, self.vc, self.seq_stride, self.head_stride,
+                                        self.block_table, self.block_table.shape[-1], self.page_size, self.n_pages, cl_in,
+                                        max(self.ctx_len_host, 1), x, self.out, self.k_new, self.v_new)
+        else:
+            ev.evict_verify_stack(self.ctx, self.layers, off, par, 1, k, self.kc, self.vc, self.seq_stride, self.head_stride,
+                                  cl_in, max(self.ctx_len_host, 1), x, self.out, self.k_new, self.v_new)
         if self.lm_head is not None:
             ev.evict_lm_head_argmax(self.ctx, self.out, self.lm_head[0], self.lm_head[1], k, self.next)
         if d.target_next is None:
             tn = self.next
         ev.evict_accept_path(None, off, par, tok, tn, 1, self.path, self.n_max, self.path_len, self.bonus)
-        ev.evict_kv_commit_stack(self.ctx, self.dtype_code, cfg.Hkv, cfg.D, self.k_new, self.v_new, off, self.path, self.n_max,
-                                 self.path_len, self.kc, self.vc, self.seq_stride, self.head_stride, cl_in, self.capacity,
-                                 cl_out, 1)
+        if self.block_table is not None:
+            ev.evict_kv_commit_stack_paged(self.ctx, self.dtype_code, cfg.Hkv, cfg.D, self.k_new, self.v_new, off, self.path,
+                                           self.n_max, self.path_len, self.kc, self.vc, self.seq_stride, self.head_stride,
+                                           self.block_table, self.block_table.shape[-1], self.page_size, self.n_pages, cl_in,
+                                           self.capacity, cl_out, 1)
+        else:
+            ev.evict_kv_commit_stack(self.ctx, self.dtype_code, cfg.Hkv, cfg.D, self.k_new, self.v_new, off, self.path, self.n_max,
+                                     self.path_len, self.kc, self.vc, self.seq_stride, self.head_stride, cl_in, self.capacity,
+                                     cl_out, 1)
         plen = int(self.path_len.item())
         self.cur ^= 1
         self.ctx_len_host = min(self.ctx_len_host + plen, self.capacity)

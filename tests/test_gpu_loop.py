@@ -29,8 +29,9 @@ def to_device(cfg, d):
                          harness.to_dev(d["x"], cfg.dtype), harness.dev_i32(d["tok"]), harness.dev_i32(d["target_next"]), n)
 
 
-@pytest.mark.parametrize("cfg_name,truncate", [("tiny", True), ("tiny", False), ("mini_bf16", True)])
-def test_loop_matches_oracle_composition(cfg_name, truncate):
+@pytest.mark.parametrize("cfg_name,truncate,page", [("tiny", True, 0), ("tiny", False, 0), ("mini_bf16", True, 0),
+                                                    ("tiny", True, 8), ("mini_bf16", True, 16)])
+def test_loop_matches_oracle_composition(cfg_name, truncate, page):
     cfg = synth.CONFIGS[cfg_name]
     n_layers, N, L0, cap, iters, seed = 2, 14, 37, 128, 4, 71
     Ws = [synth.layer_weights(cfg, synth.philox(seed, 1 + l)) for l in range(n_layers)]
@@ -49,7 +50,15 @@ def test_loop_matches_oracle_composition(cfg_name, truncate):
         for l in range(n_layers):
             kc[l][0, :, :L0] = harness.to_dev(kv[l][0], cfg.dtype)
             vc[l][0, :, :L0] = harness.to_dev(kv[l][1], cfg.dtype)
-        loop = SpecLoop(cfg, layers[0].ctx, [l.weights for l in layers], kc, vc, cfg.Hkv * cap * cfg.D, cap * cfg.D, cap, N)
+        if page:
+            # the same caches scattered over randomly assigned pages, with pages for all `cap` positions
+            pools = [synth.to_pages([kv[l][0]], [kv[l][1]], page, [cap], synth.philox(seed, 300)) for l in range(n_layers)]
+            kc = [harness.to_dev(p[0], cfg.dtype) for p in pools]
+            vc = [harness.to_dev(p[1], cfg.dtype) for p in pools]
+            loop = SpecLoop(cfg, layers[0].ctx, [l.weights for l in layers], kc, vc, cfg.Hkv * page * cfg.D, page * cfg.D, cap, N,
+                            block_table=harness.dev_i32(pools[0][2]), page_size=page, n_pages=pools[0][3])
+        else:
+            loop = SpecLoop(cfg, layers[0].ctx, [l.weights for l in layers], kc, vc, cfg.Hkv * cap * cfg.D, cap * cfg.D, cap, N)
         loop.set_context_length(L0)
         cost_dev = torch.from_numpy(cost).to(DEV) if truncate else None
 
