@@ -324,7 +324,8 @@ int evict_device_status(evict_ctx* ctx, int32_t* status_host, void* stream);
 
 /* Launch-shape tuning knobs of a context (defaults are chosen in evict_create):
  *   "moe_grid"        workgroups of the grouped expert GEMMs (chunks are dealt round-robin)
- *   "moe_prefetch"    1 or 2 weight-load stages in flight per wavefront in the gate/up GEMM
+ *   "moe_prefetch"    1: weight registers of the streaming GEMMs refilled right behind each MFMA where the
+ *                     step count is known at compile time (default); 3: refilled per step (measurement knob)
  *   "moe_chunk_gateup", "moe_chunk_down"  units (16-row strips; strip pairs for gate/up) a
  *                     workgroup takes from the device-side work list at a time
  *   "moe_gateup_kernel" 1: gate/up projections with one (gate, up) strip pair per wavefront and the token

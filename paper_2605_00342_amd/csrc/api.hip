@@ -561,7 +561,7 @@ int evict_tune(evict_ctx* ctx, const char* key, int value) {
     EVICT_REQUIRE(value >= 1 && value <= 65535, EVICT_E_INVALID, "evict_tune: moe_grid=%d out of range", value);
     ctx->moe_grid = value;
   } else if (!strcmp(key, "moe_prefetch")) {
-    EVICT_REQUIRE(value >= 1 && value <= 3, EVICT_E_INVALID, "evict_tune: moe_prefetch must be 1, 2 or 3");
+    EVICT_REQUIRE(value == 1 || value == 3, EVICT_E_INVALID, "evict_tune: moe_prefetch must be 1 or 3");
     ctx->moe_prefetch = value;
   } else if (!strcmp(key, "moe_chunk_gateup")) {
     EVICT_REQUIRE(value >= 1 && (ctx->m.F / 16) % value == 0, EVICT_E_INVALID, "evict_tune: moe_chunk_gateup=%d must divide F/16", value);

@@ -46,7 +46,7 @@ struct GemmArgs {
   int T;                 // dense: token rows
   int dense_tiles;       // dense: workgroups per strip, each taking 16*NT tokens
   int dense_units;       // dense: consecutive strips a workgroup takes (its weight loads run ahead across them)
-  int prefetch;          // host-side choice of the kernel variant (weight-load stages), 0 = default
+  int prefetch;          // host-side choice of the kernel variant: 3 = no compile-time step counts (measurement knob)
   int wave_strip;        // host-side: grouped fp32-output GEMM may use gemm_wave_strip_kernel
   int plain_loads;       // 1: never use non-temporal weight loads (measurement knob)
   void* out0;            // QKV: q; RESID: h; SWIGLU: act; F32: y; ARGMAX: best value per (token, strip), [T][ldo]

@@ -1163,8 +1163,7 @@ int launch_gemm_nt(const GemmArgs& a, int grid, hipStream_t s) {
   if (bf16 && nkb % 64 == 0) {
     // the next step's 8 loads are issued right after the MFMAs, so they fly during the
     // partial-tile exchange; one buffer keeps the kernel under 128 VGPRs (2 workgroups per CU)
-    if (a.prefetch == 2) EVICT_GEMM_LAUNCH(8, 2, true);
-    else if (EPI == EPI_SWIGLU && NT == 1 && a.grouped && a.chunk_units == 1 && nkb == 64 && a.prefetch != 3)
+    if (EPI == EPI_SWIGLU && NT == 1 && a.grouped && a.chunk_units == 1 && nkb == 64 && a.prefetch != 3)
       // one gate/up strip pair per chunk: two steps, known at compile time
       hipLaunchKernelGGL((gemm_stream_kernel<ST, NT, 8, 1, EPI, true, 1, (EPI == EPI_SWIGLU && NT == 1) ? 2 : 0>), dim3(grid),
                          dim3(kGemmThreads), 0, s, a);
@@ -1177,13 +1176,15 @@ int launch_gemm_nt(const GemmArgs& a, int grid, hipStream_t s) {
     else EVICT_GEMM_LAUNCH(8, 1, true);
   } else if (bf16 && nkb == 24) {
     // 3 blocks per wavefront per strip: take 4 strips per exchange step when the chunking allows
-    if (EPI == EPI_F32 && NT == 1 && a.grouped && a.chunk_units % 4 == 0 && a.prefetch != 2)
+    if (EPI == EPI_F32 && NT == 1 && a.grouped && a.chunk_units % 4 == 0)
       hipLaunchKernelGGL((gemm_stream_kernel<ST, NT, 3, 1, EPI, true, (EPI == EPI_F32 && NT == 1) ? 4 : 1>), dim3(grid),
                          dim3(kGemmThreads), 0, s, a);
     else
       EVICT_GEMM_LAUNCH(3, 4, true);
   } else if (need <= 4) {
-    EVICT_GEMM_LAUNCH(4, 4, false);
+    // four stages of weight loads; three where the epilogue prefetch also needs registers (four would spill)
+    constexpr int kStages = (EPI == EPI_QKV || EPI == EPI_RESID) ? 3 : 4;
+    EVICT_GEMM_LAUNCH(4, kStages, false);
   } else {
     EVICT_GEMM_LAUNCH(8, 1, false);
   }
