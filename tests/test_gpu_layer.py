@@ -232,3 +232,13 @@ def test_tensor_parallel_share_of_the_larger_targets_full_size(cfg_name, seed):
     got = run_case(case)
     info = check_against_oracle(case, got)
     print(cfg_name, "N=32:", info)
+
+
+@pytest.mark.parametrize("n,sigma,seed", [(128, 1.0, 1010), (8, 0.2, 1011)])
+def test_qwen3_shaped_layer_sweep_extremes_full_size(n, sigma, seed):
+    # configs[2]: the two ends of the tree-size / child-noise sweep at ctx 4096, default launch configuration
+    # (N = 128 takes the strip-pair-per-wavefront gate/up kernel and 8-wavefront attention workgroups)
+    case = synth.make_case("qwen3", n=n, L=4096, seed=seed, sigma=sigma)
+    got = run_case(case)
+    info = check_against_oracle(case, got)
+    print(f"qwen3 N={n} sigma={sigma}:", info)
