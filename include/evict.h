@@ -338,6 +338,10 @@ int evict_device_status(evict_ctx* ctx, int32_t* status_host, void* stream);
  *                     (2 once the call has more than 64 tokens)
  *   "dense_units"     consecutive 16-row strips a workgroup of the QKV projection takes, 0 = auto
  *   "moe_plain_loads" 1: expert weights with ordinary loads instead of non-temporal ones
+ *   "dense_kernel"    QKV / output projections: 0 contraction split over the wavefronts of a workgroup,
+ *                     1 one strip per wavefront with the token operand in LDS (where its shape conditions
+ *                     hold), 2 = auto (the latter from 128 or 256 tokens on); "dense_ntw" its token tiles
+ *                     per workgroup, 1, 2 or 0 = auto
  *   "attn_target_wgs" workgroups the bf16 attention kernel aims for when it cuts the context into splits
  *   "moe_nt"          16-token tiles per work-list slot of the grouped expert GEMMs: 1, 2, or 0 = auto
  *   "attn_waves"      wavefronts per workgroup of that kernel: 4, 8 (two LDS buffers, next chunk fetched

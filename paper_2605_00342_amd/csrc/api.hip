@@ -129,6 +129,8 @@ int evict_create(evict_ctx** out, const evict_model_desc* m, int max_tokens, int
   c.attn_waves = 0;
   c.moe_nt = 0;
   c.dense_units = 0;
+  c.dense_kernel = 2;
+  c.dense_ntw = 0;
   c.moe_chunk_gateup = 1;
   c.moe_chunk_down = 1;
   for (int cu : {4, 2}) if ((m->d / 16) % cu == 0) { c.moe_chunk_down = cu; break; }
@@ -290,6 +292,18 @@ static int verify_layer_impl(evict_ctx* ctx, const evict_layer_weights* w, const
   // with a third of the strips and twice the contraction length, is better left at one)
   const int qkv_units = ctx->dense_units ? ctx->dense_units : (dense_tiles >= 2 ? 2 : 1);
   auto dense_grid = [&](int units, int du) { return (((units + du - 1) / du + 7) / 8) * 8 * dense_tiles; };
+  // With many token tiles the projections are ordinary dense GEMMs: one strip per wavefront with the token
+  // operand of the workgroup in LDS (gemm_dense_strip_kernel) instead of the contraction split. Measured:
+  // pays from 128 tokens on with two token tiles per workgroup (the operand of two tiles must fit in LDS), from
+  // 256 tokens on with one.
+  auto dense_strip_shape = [&](const GemmArgs& a, int* ntw) {
+    if (ctx->dense_kernel == 0) return false;
+    int nt = ctx->dense_ntw ? ctx->dense_ntw : (dense_strip_applies(a, 2) ? 2 : 1);
+    if (!dense_strip_applies(a, nt)) return false;
+    if (ctx->dense_kernel == 2 && T < (nt == 2 ? 128 : 256)) return false;
+    *ntw = nt;
+    return true;
+  };
   {  // q, k, v projections + rotation (positions ctx_len + depth)
     GemmArgs a = {};
     a.W = (const u32x4*)w->wqkv_packed;
@@ -303,7 +317,9 @@ static int verify_layer_impl(evict_ctx* ctx, const evict_layer_weights* w, const
     a.Hq = m.Hq; a.Hkv = m.Hkv; a.D = m.D;
     a.dense_tiles = dense_tiles;
     a.dense_units = qkv_units;
-    rc = launch_gemm(m.dtype, EPI_QKV, a, nt_dense, dense_grid(a.n_strips, qkv_units), s);
+    int ntw;
+    rc = dense_strip_shape(a, &ntw) ? launch_gemm_dense_strip(m.dtype, EPI_QKV, a, ntw, s)
+                                         : launch_gemm(m.dtype, EPI_QKV, a, nt_dense, dense_grid(a.n_strips, qkv_units), s);
     if (rc) return rc;
     if (aux && aux->q) EVICT_HIP_CHECK(hipMemcpyAsync(aux->q, ctx->q, (size_t)T * HqD * eb, hipMemcpyDeviceToDevice, s));
   }
@@ -325,7 +341,9 @@ static int verify_layer_impl(evict_ctx* ctx, const evict_layer_weights* w, const
     a.resid = x_in;
     a.dense_tiles = dense_tiles;
     a.dense_units = 1;
-    rc = launch_gemm(m.dtype, EPI_RESID, a, nt_dense, dense_grid(a.n_strips, 1), s);
+    int ntw;
+    rc = dense_strip_shape(a, &ntw) ? launch_gemm_dense_strip(m.dtype, EPI_RESID, a, ntw, s)
+                                         : launch_gemm(m.dtype, EPI_RESID, a, nt_dense, dense_grid(a.n_strips, 1), s);
     if (rc) return rc;
     if (aux && aux->h) EVICT_HIP_CHECK(hipMemcpyAsync(aux->h, ctx->h, (size_t)T * m.d * eb, hipMemcpyDeviceToDevice, s));
   }
@@ -581,6 +599,12 @@ int evict_tune(evict_ctx* ctx, const char* key, int value) {
   } else if (!strcmp(key, "dense_units")) {
     EVICT_REQUIRE(value >= 0 && value <= 16, EVICT_E_INVALID, "evict_tune: dense_units must be in [0, 16] (0 = auto)");
     ctx->dense_units = value;
+  } else if (!strcmp(key, "dense_kernel")) {
+    EVICT_REQUIRE(value >= 0 && value <= 2, EVICT_E_INVALID, "evict_tune: dense_kernel must be 0, 1 or 2 (auto)");
+    ctx->dense_kernel = value;
+  } else if (!strcmp(key, "dense_ntw")) {
+    EVICT_REQUIRE(value >= 0 && value <= 2, EVICT_E_INVALID, "evict_tune: dense_ntw must be 0 (auto), 1 or 2");
+    ctx->dense_ntw = value;
   } else if (!strcmp(key, "dense_nt")) {
     EVICT_REQUIRE(value >= 0 && value <= 2, EVICT_E_INVALID, "evict_tune: dense_nt must be 0 (auto), 1 or 2");
     ctx->dense_nt = value;

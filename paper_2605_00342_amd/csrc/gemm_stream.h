@@ -549,4 +549,153 @@ __global__ __launch_bounds__(WS * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
   }
 }
 
+// ------------------------------------------------------------------------------------
+// Dense projections with many tokens (QKV, output projection once the call has more than a few
+// token tiles): the strip-per-wavefront decomposition of gemm_wave_strip_kernel applied to one
+// weight matrix and all T tokens. A workgroup takes WS = 8 consecutive strips (one per wavefront,
+// whole contraction range, rolling window of WIN weight blocks per lane) and NTW tiles of 16
+// tokens, whose operand blocks it stages in LDS once ([NTW][nkb][64], NTW * nkb KiB); nothing
+// is exchanged between wavefronts after that, and every wavefront finishes its 16 x 16 tiles
+// itself (QKV: rotation of the pairs (i, i + D/2), which sit 32 lanes apart; output projection:
+// residual add). 1-D grid: workgroup ids go round-robin over the 8 XCDs, so the token groups of
+// one strip group are given ids 8 apart: they share an L2 and read the strips from HBM once.
+// Requires nkb % WIN == 0.
+// ------------------------------------------------------------------------------------
+template <typename ST, int EPI, int NTW, int WS, int NKB = 0>
+__global__ __launch_bounds__(WS * 64) void gemm_dense_strip_kernel(const GemmArgs a) {
+  static_assert(EPI == EPI_QKV || EPI == EPI_RESID, "dense projections only");
+  constexpr int WIN = 16;
+  extern __shared__ __attribute__((aligned(16))) u32x4 s_b[];  // [NTW token tiles][nkb][64]
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int nkb = NKB > 0 ? NKB : a.nkb;
+  const unsigned ntg = (unsigned)a.dense_tiles;  // token groups of NTW * 16 tokens
+  const unsigned xcd = blockIdx.x & 7u, i = blockIdx.x >> 3;
+  const unsigned tg = i % ntg;
+  const unsigned sg = (i / ntg) * 8u + xcd;  // strip group
+  if (sg * WS >= (unsigned)a.n_strips) return;  // (whole workgroup: no barrier is left waiting)
+  const int strip_raw = (int)sg * WS + w;
+  const bool active = strip_raw < a.n_strips;  // the last group may be short: its idle wavefronts still stage and wait
+  const int strip = active ? strip_raw : a.n_strips - 1;
+  const int tok0 = (int)tg * NTW * 16;
+  const int lc = lane & 15;
+
+  // token operand first, weights behind it
+  const char* xrow[NTW];
+  bool valid[NTW];
+#pragma unroll
+  for (int t = 0; t < NTW; ++t) {
+    int col = tok0 + t * 16 + lc;
+    valid[t] = active && col < a.T;
+    col = col < a.T ? col : a.T - 1;  // padded columns repeat the last token; never stored
+    xrow[t] = (const char*)a.X + (long long)col * a.ldx_bytes + (lane >> 4) * 16;
+  }
+  constexpr int BMAX = 4;  // operand blocks a wavefront stages per pass and token tile
+  const u32x4* wp = a.W + (long long)strip * nkb * 64 + lane;
+  u32x4 A[WIN];
+#pragma unroll
+  for (int kb0 = 0; kb0 < (NKB > 0 ? NKB : nkb); kb0 += BMAX * WS) {
+    u32x4 bst[NTW][BMAX];
+#pragma unroll
+    for (int t = 0; t < NTW; ++t)
+#pragma unroll
+      for (int q = 0; q < BMAX; ++q) {
+        const int kb = kb0 + q * WS + w;
+        if (kb < nkb) bst[t][q] = *reinterpret_cast<const u32x4*>(xrow[t] + (long long)kb * 64);
+      }
+    if (kb0 == 0) {
+#pragma unroll
+      for (int j = 0; j < WIN; ++j) A[j] = wp[j * 64];
+    }
+#pragma unroll
+    for (int t = 0; t < NTW; ++t)
+#pragma unroll
+      for (int q = 0; q < BMAX; ++q) {
+        const int kb = kb0 + q * WS + w;
+        if (kb < nkb) s_b[((size_t)t * nkb + kb) * 64 + lane] = bst[t][q];
+      }
+  }
+  // what the epilogue needs is requested now, so that its round trip hides behind the weight stream
+  f32x4 pre0[NTW], pre1[NTW];
+#pragma unroll
+  for (int t = 0; t < NTW; ++t) {
+    const int col = tok0 + t * 16 + lc;
+    const int tokc = col < a.T ? col : 0;
+    if (EPI == EPI_RESID) {
+      pre0[t] = load4<ST>(a.resid, (long long)tokc * a.ldo + strip * 16 + (lane >> 4) * 4);
+      pre1[t] = f32x4{0, 0, 0, 0};
+    } else {
+      const int spd = a.D >> 4;
+      const int head = strip / spd, js = strip - head * spd;
+      const int idx = js * 8 + ((lane >> 4) & 1) * 4;
+      const float* cs = a.rope_cs + (long long)tokc * a.D;
+      pre0[t] = *reinterpret_cast<const f32x4*>(cs + idx);
+      pre1[t] = *reinterpret_cast<const f32x4*>(cs + (a.D >> 1) + idx);
+    }
+  }
+  lds_barrier();
+  f32x4 acc[NTW];
+#pragma unroll
+  for (int t = 0; t < NTW; ++t) acc[t] = f32x4{0, 0, 0, 0};
+  // operand blocks are requested from LDS PD steps ahead of their MFMAs (ring of registers), so the LDS
+  // latency hides behind the matrix work of the steps in between
+  constexpr int PD = 4;
+  static_assert(WIN % PD == 0, "ring positions must repeat with the window");
+  u32x4 bq[PD][NTW];
+#pragma unroll
+  for (int p = 0; p < PD; ++p)
+#pragma unroll
+    for (int t = 0; t < NTW; ++t) bq[p][t] = s_b[((size_t)t * nkb + p) * 64 + lane];
+#pragma unroll
+  for (int j0 = 0; j0 < (NKB > 0 ? NKB : nkb); j0 += WIN) {
+#pragma unroll
+    for (int jj = 0; jj < WIN; ++jj) {
+      const int j = j0 + jj;
+#pragma unroll
+      for (int t = 0; t < NTW; ++t) acc[t] = mfma_block<ST>(A[jj], bq[jj % PD][t], acc[t]);
+      if (j + PD < nkb) {
+#pragma unroll
+        for (int t = 0; t < NTW; ++t) bq[jj % PD][t] = s_b[((size_t)t * nkb + j + PD) * 64 + lane];
+      }
+      if (j + WIN < nkb) A[jj] = wp[(j + WIN) * 64];
+      if (NKB > 0) __builtin_amdgcn_sched_barrier(0);  // keep the refills right behind their MFMA: window and ring stay full
+    }
+  }
+  const int m0 = (lane >> 4) * 4;  // first of this lane's 4 rows in the strip
+#pragma unroll
+  for (int t = 0; t < NTW; ++t) {
+    const int col = tok0 + t * 16 + lc;
+    const f32x4 sum = acc[t];
+    if (EPI == EPI_RESID) {
+      if (valid[t]) store4<ST>(a.out0, (long long)col * a.ldo + strip * 16 + m0, pre0[t] + sum);
+    } else {  // rotate pairs (i, i + D/2), which sit 32 lanes apart
+      const int spd = a.D >> 4;  // strips per head
+      const int head = strip / spd, js = strip - head * spd;
+      const int half = a.D >> 1;
+      const int g4 = lane >> 4;
+      const int idx = js * 8 + (g4 & 1) * 4;  // index inside the half
+      f32x4 other, r4;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) other[q] = __shfl_xor(sum[q], 32);
+      const bool rot = head < a.Hq + a.Hkv;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float cv = rot ? pre0[t][q] : 1.0f;
+        const float sv = rot ? pre1[t][q] : 0.0f;
+        r4[q] = (g4 < 2) ? (sum[q] * cv - other[q] * sv) : (sum[q] * cv + other[q] * sv);
+      }
+      if (valid[t]) {
+        const int hrow = (g4 < 2 ? 0 : half) + idx;
+        if (head < a.Hq) {
+          store4<ST>(a.out0, ((long long)col * a.Hq + head) * a.D + hrow, r4);
+        } else if (head < a.Hq + a.Hkv) {
+          store4<ST>(a.out1, ((long long)col * a.Hkv + (head - a.Hq)) * a.D + hrow, r4);
+        } else {
+          store4<ST>(a.out2, ((long long)col * a.Hkv + (head - a.Hq - a.Hkv)) * a.D + hrow, r4);
+        }
+      }
+    }
+  }
+}
+
 }  // namespace evict

@@ -1243,7 +1243,46 @@ int launch_gemm_st(const GemmArgs& a, int nt, int grid, hipStream_t s) {
   return nt == 1 ? launch_gemm_nt<ST, 1, EPI>(a, grid, s) : launch_gemm_nt<ST, 2, EPI>(a, grid, s);
 }
 
+// dense projections, one strip per wavefront (see gemm_dense_strip_kernel). Every instantiation, once, for
+// the launcher and for the LDS attribute.
+#define EVICT_DENSE_STRIP_SHAPES(X, ST_, EPI_, NKB_) X(ST_, EPI_, 2, 8, NKB_) X(ST_, EPI_, 1, 8, NKB_)
+#define EVICT_DENSE_STRIP_ALL(X)                                                                                   \
+  EVICT_DENSE_STRIP_SHAPES(X, BF16, EPI_QKV, 0) EVICT_DENSE_STRIP_SHAPES(X, BF16, EPI_QKV, 64)                     \
+  EVICT_DENSE_STRIP_SHAPES(X, BF16, EPI_QKV, 128) EVICT_DENSE_STRIP_SHAPES(X, BF16, EPI_RESID, 0)                  \
+  EVICT_DENSE_STRIP_SHAPES(X, BF16, EPI_RESID, 64) EVICT_DENSE_STRIP_SHAPES(X, BF16, EPI_RESID, 128)               \
+  EVICT_DENSE_STRIP_SHAPES(X, F32, EPI_QKV, 0) EVICT_DENSE_STRIP_SHAPES(X, F32, EPI_RESID, 0)
+constexpr size_t kDenseStripLdsMax = 128 * 1024;
+
 }  // namespace
+
+bool dense_strip_applies(const GemmArgs& a, int ntw) {
+  return !a.grouped && a.nkb % 16 == 0 && (size_t)ntw * a.nkb * 1024 <= kDenseStripLdsMax;
+}
+
+// ntw in {1, 2} token tiles per workgroup, 8 strips (wavefronts) per workgroup; the caller has checked
+// dense_strip_applies(a, ntw). Sets a.dense_tiles itself.
+int launch_gemm_dense_strip(int dtype, int epi, GemmArgs a, int ntw, hipStream_t s) {
+  const int ws = 8;
+  a.dense_tiles = (a.T + 16 * ntw - 1) / (16 * ntw);
+  const int n_sg = (a.n_strips + ws - 1) / ws;
+  const int grid = ((n_sg + 7) / 8) * 8 * a.dense_tiles;
+  const size_t lds = (size_t)ntw * a.nkb * 1024;
+  const int nkb_static = (dtype == EVICT_BF16 && (a.nkb == 64 || a.nkb == 128)) ? a.nkb : 0;
+  bool launched = false;
+#define EVICT_DS_TRY(ST_, EPI_, NTW_, WS_, NKB_)                                                                        \
+  if (!launched && dtype == (sizeof(ST_::elem) == 2 ? EVICT_BF16 : EVICT_F32) && epi == EPI_ && ntw == NTW_ && ws == WS_ && \
+      nkb_static == NKB_) {                                                                                             \
+    hipLaunchKernelGGL((gemm_dense_strip_kernel<ST_, EPI_, NTW_, WS_, NKB_>), dim3(grid), dim3(WS_ * 64), lds, s, a);    \
+    launched = true;                                                                                                    \
+  }
+  EVICT_DENSE_STRIP_ALL(EVICT_DS_TRY)
+#undef EVICT_DS_TRY
+  if (!launched) {
+    set_error("gemm_dense_strip_kernel: no variant for dtype %d epilogue %d ntw %d ws %d", dtype, epi, ntw, ws);
+    return EVICT_E_INVALID;
+  }
+  return launch_status("gemm_dense_strip_kernel");
+}
 
 int launch_gemm(int dtype, int epi, const GemmArgs& a, int nt, int grid, hipStream_t s) {
 #define EVICT_GEMM_CASE(E_)                                                   \
@@ -1309,6 +1348,11 @@ int union_mask_plan(int T, int k, int E, size_t* lds_bytes);  // small_kernels.h
 
 int kernels_setup(const evict_model_desc& m) {
   // kernels whose dynamic LDS exceeds the default 64 KiB limit
+#define EVICT_DS_ATTR(ST_, EPI_, NTW_, WS_, NKB_)                                                            \
+  EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)gemm_dense_strip_kernel<ST_, EPI_, NTW_, WS_, NKB_>,      \
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDenseStripLdsMax));
+  EVICT_DENSE_STRIP_ALL(EVICT_DS_ATTR)
+#undef EVICT_DS_ATTR
   EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)attn_partial_kernel<BF16>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_partial_lds_bytes(128)));
   EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)attn_partial_kernel<F32>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_partial_lds_bytes(128)));
   EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)attn_partial_mfma_kernel<128, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_mfma_lds_bytes(128)));

@@ -242,3 +242,26 @@ def test_qwen3_shaped_layer_sweep_extremes_full_size(n, sigma, seed):
     got = run_case(case)
     info = check_against_oracle(case, got)
     print(f"qwen3 N={n} sigma={sigma}:", info)
+
+
+def test_dense_projections_one_strip_per_wavefront():
+    """The many-token decomposition of the QKV / output projections (token operand in LDS, one strip per
+    wavefront), forced through evict_tune on small and ragged token counts, both workgroup shapes, fp32 and
+    bf16, a strip count that is not a multiple of the strips per workgroup (t_odd: 28 QKV strips; its output
+    projection has a contraction length the kernel does not take and stays on the other one), a batch, and
+    the full-size layer."""
+    cfg_odd = synth.ModelCfg("t_odd", "bf16", d=512, Hq=5, Hkv=1, D=64, E=16, k=2, F=64, theta=1e4)
+    cases = [synth.make_case("mini_bf16", n=40, L=16, seed=61, tree="bfs"),
+             synth.make_case("tiny", n=13, L=37, seed=62),
+             synth.make_case("mini_sigmoid", n=33, L=50, seed=63),
+             synth.make_case("t_odd", n=21, L=30, seed=64, tree="bfs", cfg=cfg_odd),
+             synth.make_case("mini_bf16", n=50, L=60, seed=65, tree="bfs", batch=3, L_list=[60, 5, 33])]
+    for case in cases:
+        for tune in ({"dense_kernel": 1, "dense_ntw": 2}, {"dense_kernel": 1, "dense_ntw": 1}):
+            check_against_oracle(case, run_case(case, tune=tune))
+    case = synth.make_case("qwen3", n=32, L=300, seed=66)
+    check_against_oracle(case, run_case(case, tune={"dense_kernel": 1}))
+    # and the default choice equals the contraction-split kernels within rounding on a many-token call
+    case = synth.make_case("mini_bf16", n=128, L=64, seed=14, tree="eagle")
+    a, b = run_case(case), run_case(case, tune={"dense_kernel": 0})
+    assert rel_l2(a["q"], b["q"]) < 1e-2 and rel_l2(a["h"], b["h"]) < 1e-2
