@@ -1213,20 +1213,25 @@ int launch_gemm_wave_strip(const GemmArgs& a, int grid, hipStream_t s) {
 }
 
 // one gate/up strip pair per wavefront (see gemm_wave_gateup_kernel)
-constexpr int kGateupWaves = 4;
+}  // namespace
+int gateup_waves(const GemmArgs& a);
+namespace {
 bool wave_gateup_applies(const GemmArgs& a, int nt) {
-  return a.grouped && nt == 1 && a.nkb % 8 == 0 && a.nkb <= 64 && (a.n_strips / 2) % kGateupWaves == 0;
+  return a.grouped && nt == 1 && a.nkb % 8 == 0 && a.nkb <= 64 && (a.n_strips / 2) % gateup_waves(a) == 0;
 }
 template <typename ST>
 int launch_gemm_wave_gateup(const GemmArgs& a, int grid, hipStream_t s) {
   const size_t lds = (size_t)a.nkb * 1024;
-  const int nb = (a.nkb + kGateupWaves - 1) / kGateupWaves;
+  const int ws = gateup_waves(a);
+  const int nb = (a.nkb + ws - 1) / ws;
   if (ST::kBytes == 4 && nb > 8) return -1;  // (that variant would spill: the caller falls back)
-  if (nb <= 4) hipLaunchKernelGGL((gemm_wave_gateup_kernel<ST, 8, 4, kGateupWaves>), dim3(grid), dim3(kGateupWaves * 64), lds, s, a);
-  else if (nb <= 8) hipLaunchKernelGGL((gemm_wave_gateup_kernel<ST, 8, 8, kGateupWaves>), dim3(grid), dim3(kGateupWaves * 64), lds, s, a);
-  else if (a.nkb == 64)
-    hipLaunchKernelGGL((gemm_wave_gateup_kernel<ST, 16, 16, kGateupWaves, 64>), dim3(grid), dim3(kGateupWaves * 64), lds, s, a);
-  else hipLaunchKernelGGL((gemm_wave_gateup_kernel<ST, 8, 16, kGateupWaves>), dim3(grid), dim3(kGateupWaves * 64), lds, s, a);
+#define EVICT_GU_LAUNCH(WS_)                                                                                              \
+  if (nb <= 4) hipLaunchKernelGGL((gemm_wave_gateup_kernel<ST, 8, 4, WS_>), dim3(grid), dim3(WS_ * 64), lds, s, a);        \
+  else if (nb <= 8) hipLaunchKernelGGL((gemm_wave_gateup_kernel<ST, 8, 8, WS_>), dim3(grid), dim3(WS_ * 64), lds, s, a);   \
+  else if (a.nkb == 64) hipLaunchKernelGGL((gemm_wave_gateup_kernel<ST, 16, 16, WS_, 64>), dim3(grid), dim3(WS_ * 64), lds, s, a); \
+  else hipLaunchKernelGGL((gemm_wave_gateup_kernel<ST, 8, 16, WS_>), dim3(grid), dim3(WS_ * 64), lds, s, a)
+  if (ws == 6) { EVICT_GU_LAUNCH(6); } else { EVICT_GU_LAUNCH(4); }
+#undef EVICT_GU_LAUNCH
   return launch_status("gemm_wave_gateup_kernel");
 }
 
@@ -1255,6 +1260,13 @@ constexpr size_t kDenseStripLdsMax = 128 * 1024;
 
 }  // namespace
 
+// Strip pairs (wavefronts) per workgroup: 6 when that makes the chunks per slot a multiple of 8. Chunk ids go
+// round-robin over the 8 XCDs, so the same unit of every slot then lands on the same XCD, and the second token
+// tile of an expert finds the weights its first tile streamed in that XCD's L2 instead of fetching them again.
+int gateup_waves(const GemmArgs& a) {
+  const int pairs = a.n_strips / 2;
+  return (pairs % 6 == 0 && (pairs / 6) % 8 == 0) ? 6 : 4;
+}
 bool dense_strip_applies(const GemmArgs& a, int ntw) {
   return !a.grouped && a.nkb % 16 == 0 && (size_t)ntw * a.nkb * 1024 <= kDenseStripLdsMax;
 }

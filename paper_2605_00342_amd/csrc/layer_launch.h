@@ -9,6 +9,7 @@ struct WorkRec;
 
 int launch_gemm(int dtype, int epi, const GemmArgs& a, int nt, int grid, hipStream_t s);
 bool dense_strip_applies(const GemmArgs& a, int ntw);
+int gateup_waves(const GemmArgs& a);
 int launch_gemm_dense_strip(int dtype, int epi, GemmArgs a, int ntw, hipStream_t s);
 int launch_pack(const void* src, long long src_group_bytes, int rows, int cols, int dtype, void* dst, int dst_strip0,
                 int dst_strip_step, long long dst_group_strips, int groups, int head_dim, hipStream_t s);
