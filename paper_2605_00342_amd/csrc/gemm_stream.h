@@ -465,12 +465,13 @@ __global__ __launch_bounds__(WS * 64) __attribute__((amdgpu_waves_per_eu(4))) vo
 // strip; a token operand block read from LDS feeds both MFMAs), SiLU(g) * u applied in the
 // wavefront that owns the pair. WS wavefronts per workgroup share the staged operand; a
 // workgroup lives for WS * 2 * nkb KiB of weights, so the stream has no exchange points.
-// Requires nkb % WIN == 0, (n_strips / 2) % WS == 0, nkb KiB of LDS. Refills go out in runs of 8
+// Requires nkb % WIN == 0, (n_strips / 2) % WS == 0, NTW * nkb KiB of LDS (NTW tiles of 16 tokens per
+// work-list slot). Refills go out in runs of 8
 // consecutive blocks per strip once the window is 16 deep.
 // ------------------------------------------------------------------------------------
-template <typename ST, int WIN, int NB, int WS, int NKB = 0>
+template <typename ST, int WIN, int NB, int WS, int NKB = 0, int NTW = 1>
 __global__ __launch_bounds__(WS * 64) __attribute__((amdgpu_waves_per_eu(2))) void gemm_wave_gateup_kernel(const GemmArgs a) {
-  extern __shared__ __attribute__((aligned(16))) u32x4 s_b[];  // [nkb][64]
+  extern __shared__ __attribute__((aligned(16))) u32x4 s_b[];  // [NTW token tiles][nkb][64]
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int nkb = NKB > 0 ? NKB : a.nkb;
@@ -486,18 +487,26 @@ __global__ __launch_bounds__(WS * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
     const bool once = !a.plain_loads && (rec->pad & 0xFFFF) == 1;
     const u32x4* wbase = ex < a.n_routed ? a.W + (long long)ex * a.group_stride
                                          : a.W_shared + (long long)(ex - a.n_routed) * a.group_stride;
-    const bool valid = lc < ntok;
-    const int col = valid ? lc : ntok - 1;  // padded columns repeat the last token; never stored
-    long long xr = p0 + col;
-    if (a.x_by_token) xr = col < kWorkToks ? tok_early : a.tok_of_pos[p0 + col];
-    const char* xrow = (const char*)a.X + xr * a.ldx_bytes + (lane >> 4) * 16;
-    // token operand blocks first, weights behind them (the in-order load counter lets the
-    // operand be consumed while the weight windows are still in flight)
+    // (NTW token tiles of 16 per slot: the work list was built with tiles of 16 * NTW tokens)
+    bool valid[NTW];
+    const char* xrow[NTW];
+#pragma unroll
+    for (int t = 0; t < NTW; ++t) {
+      int col = t * 16 + lc;
+      valid[t] = col < ntok;
+      col = valid[t] ? col : ntok - 1;  // padded columns repeat the last token; never stored
+      long long xr = p0 + col;
+      if (a.x_by_token) xr = (t == 0 && col < kWorkToks) ? tok_early : a.tok_of_pos[p0 + col];
+      xrow[t] = (const char*)a.X + xr * a.ldx_bytes + (lane >> 4) * 16;
+    }
+    // token operand blocks of the first tile first, weights behind them (the in-order load counter lets
+    // the operand be consumed while the weight windows are still in flight); a second tile reuses the
+    // staging registers once the first is in LDS
     u32x4 bst[NB];
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
       const int kb = i * WS + w;
-      if (kb < nkb) bst[i] = *reinterpret_cast<const u32x4*>(xrow + (long long)kb * 64);
+      if (kb < nkb) bst[i] = *reinterpret_cast<const u32x4*>(xrow[0] + (long long)kb * 64);
     }
     const u32x4* wg = wbase + (long long)(2 * unit) * nkb * 64 + lane;
     const u32x4* wu = wg + (long long)nkb * 64;
@@ -509,22 +518,37 @@ __global__ __launch_bounds__(WS * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
     }
     if (!first) lds_barrier();  // every wavefront is done with the previous chunk's operand
 #pragma unroll
-    for (int i = 0; i < NB; ++i) {
-      const int kb = i * WS + w;
-      if (kb < nkb) s_b[kb * 64 + lane] = bst[i];
+    for (int t = 0; t < NTW; ++t) {
+      if (t > 0) {
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+          const int kb = i * WS + w;
+          if (kb < nkb) bst[i] = *reinterpret_cast<const u32x4*>(xrow[t] + (long long)kb * 64);
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < NB; ++i) {
+        const int kb = i * WS + w;
+        if (kb < nkb) s_b[((size_t)t * nkb + kb) * 64 + lane] = bst[i];
+      }
     }
     lds_barrier();
     first = false;
-    f32x4 accg = {0, 0, 0, 0}, accu = {0, 0, 0, 0};
+    f32x4 accg[NTW], accu[NTW];
+#pragma unroll
+    for (int t = 0; t < NTW; ++t) accg[t] = accu[t] = f32x4{0, 0, 0, 0};
     constexpr int BURST = WIN >= 16 ? 8 : WIN;  // consecutive blocks requested together (DRAM likes runs)
 #pragma unroll
     for (int j0 = 0; j0 < (NKB > 0 ? NKB : nkb); j0 += WIN) {
 #pragma unroll
       for (int jj = 0; jj < WIN; ++jj) {
         const int j = j0 + jj;
-        const u32x4 bf = s_b[j * 64 + lane];
-        accg = mfma_block<ST>(Ag[jj], bf, accg);
-        accu = mfma_block<ST>(Au[jj], bf, accu);
+#pragma unroll
+        for (int t = 0; t < NTW; ++t) {
+          const u32x4 bf = s_b[((size_t)t * nkb + j) * 64 + lane];
+          accg[t] = mfma_block<ST>(Ag[jj], bf, accg[t]);
+          accu[t] = mfma_block<ST>(Au[jj], bf, accu[t]);
+        }
         if ((jj % BURST) == BURST - 1) {
           // the BURST window entries just consumed are refilled with the blocks WIN further on
           const int r0 = jj - (BURST - 1);
@@ -540,12 +564,14 @@ __global__ __launch_bounds__(WS * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
         }
       }
     }
-    if (valid) {
-      f32x4 r4;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) r4[i] = (accg[i] / (1.0f + __expf(-accg[i]))) * accu[i];
-      store4<ST>(a.out0, (long long)(p0 + lc) * a.ldo + unit * 16 + (lane >> 4) * 4, r4);
-    }
+    for (int t = 0; t < NTW; ++t)
+      if (valid[t]) {
+        f32x4 r4;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) r4[i] = (accg[t][i] / (1.0f + __expf(-accg[t][i]))) * accu[t][i];
+        store4<ST>(a.out0, (long long)(p0 + t * 16 + lc) * a.ldo + unit * 16 + (lane >> 4) * 4, r4);
+      }
   }
 }
 

@@ -1217,14 +1217,20 @@ int launch_gemm_wave_strip(const GemmArgs& a, int grid, hipStream_t s) {
 int gateup_waves(const GemmArgs& a);
 namespace {
 bool wave_gateup_applies(const GemmArgs& a, int nt) {
-  return a.grouped && nt == 1 && a.nkb % 8 == 0 && a.nkb <= 64 && (a.n_strips / 2) % gateup_waves(a) == 0;
+  if (!(a.grouped && a.nkb % 8 == 0 && a.nkb <= 64 && (a.n_strips / 2) % gateup_waves(a) == 0)) return false;
+  // two token tiles per slot: only the variant with 6 wavefronts and 64 contraction blocks is built
+  return nt == 1 || (nt == 2 && a.nkb == 64 && gateup_waves(a) == 6);
 }
 template <typename ST>
-int launch_gemm_wave_gateup(const GemmArgs& a, int grid, hipStream_t s) {
-  const size_t lds = (size_t)a.nkb * 1024;
+int launch_gemm_wave_gateup(const GemmArgs& a, int nt, int grid, hipStream_t s) {
+  const size_t lds = (size_t)a.nkb * 1024 * nt;
   const int ws = gateup_waves(a);
   const int nb = (a.nkb + ws - 1) / ws;
-  if (ST::kBytes == 4 && nb > 8) return -1;  // (that variant would spill: the caller falls back)
+  if (ST::kBytes == 4 && (nb > 8 || nt == 2)) return -1;  // (those variants would spill: the caller falls back)
+  if (nt == 2) {
+    hipLaunchKernelGGL((gemm_wave_gateup_kernel<ST, 16, 16, 6, 64, 2>), dim3(grid), dim3(6 * 64), lds, s, a);
+    return launch_status("gemm_wave_gateup_kernel");
+  }
 #define EVICT_GU_LAUNCH(WS_)                                                                                              \
   if (nb <= 4) hipLaunchKernelGGL((gemm_wave_gateup_kernel<ST, 8, 4, WS_>), dim3(grid), dim3(WS_ * 64), lds, s, a);        \
   else if (nb <= 8) hipLaunchKernelGGL((gemm_wave_gateup_kernel<ST, 8, 8, WS_>), dim3(grid), dim3(WS_ * 64), lds, s, a);   \
@@ -1240,7 +1246,7 @@ bool wave_strip_applies(const GemmArgs& a, int nt) { return a.grouped && a.n_str
 template <typename ST, int EPI>
 int launch_gemm_st(const GemmArgs& a, int nt, int grid, hipStream_t s) {
   if (EPI == EPI_SWIGLU && a.wave_strip && wave_gateup_applies(a, nt)) {
-    const int rc = launch_gemm_wave_gateup<ST>(a, grid, s);
+    const int rc = launch_gemm_wave_gateup<ST>(a, nt, grid, s);
     if (rc >= 0) return rc;
   }
   if (EPI == EPI_F32 && a.wave_strip && wave_strip_applies(a, nt))
@@ -1365,6 +1371,8 @@ int kernels_setup(const evict_model_desc& m) {
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDenseStripLdsMax));
   EVICT_DENSE_STRIP_ALL(EVICT_DS_ATTR)
 #undef EVICT_DS_ATTR
+  EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)gemm_wave_gateup_kernel<BF16, 16, 16, 6, 64, 2>,
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));
   EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)attn_partial_kernel<BF16>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_partial_lds_bytes(128)));
   EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)attn_partial_kernel<F32>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_partial_lds_bytes(128)));
   EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)attn_partial_mfma_kernel<128, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_mfma_lds_bytes(128)));

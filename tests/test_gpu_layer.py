@@ -164,6 +164,12 @@ def test_two_tile_work_list_slots():
     for case in cases:
         check_against_oracle(case, run_case(case, tune={"moe_nt": 2}))
         check_against_oracle(case, run_case(case, tune={"moe_nt": 2, "moe_down_kernel": 0}))
+    # full-size layer, tightly correlated tokens (experts with 17..64 tokens): the strip-pair gate/up kernel with
+    # two token tiles per slot
+    case = synth.make_case("qwen3", n=64, L=200, seed=38, sigma=0.1)
+    got = run_case(case, tune={"moe_nt": 2, "moe_gateup_kernel": 1})
+    assert got["hist"].max() > 16
+    check_against_oracle(case, got)
 
 
 def test_gateup_one_strip_pair_per_wavefront():
