@@ -1416,8 +1416,11 @@ int launch_attention(const evict_ctx* c, const void* kc, const void* vc, long lo
     if (c->attn_waves == 4 || c->attn_waves == 8) nw = c->attn_waves;
     const int rb = c->attn_row_blocks > 0 ? c->attn_row_blocks : (ntiles + nw - 1) / nw;
     const int rb_avg = (avg_tiles + nw - 1) / nw;
-    // context splits: two workgroups of 4 wavefronts per CU overlap each other; one of 8 fills it
-    int want = (nw == 8 ? c->attn_target_wgs / 2 : c->attn_target_wgs) / (m.Hkv * B * rb_avg);
+    // context splits: two workgroups of 4 wavefronts per CU overlap each other; one of 8 fills it. The
+    // draft-node split of every unit comes on top, so one split of the budget is kept for it: a grid a
+    // few workgroups above what the chip holds at once would run a nearly empty second round. (Not in a
+    // batch: splits past a shorter sequence's context leave at once, so the grid is not what runs.)
+    int want = (nw == 8 ? c->attn_target_wgs / 2 : c->attn_target_wgs) / (m.Hkv * B * rb_avg) - (B == 1 ? 1 : 0);
     want = want < 1 ? 1 : want;
     int cps = (chunks + want - 1) / want;  // chunks per split
     cps = cps < 1 ? 1 : cps;
