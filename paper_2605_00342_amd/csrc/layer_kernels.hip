@@ -1409,10 +1409,11 @@ int launch_attention(const evict_ctx* c, const void* kc, const void* vc, long lo
     const int avg_nodes = (T + B - 1) / B < max_nodes ? (T + B - 1) / B : max_nodes;
     const int avg_tiles = (avg_nodes * G + 15) / 16;
     const int chunks = (max_ctx_host + kMfmaKeys - 1) / kMfmaKeys;
-    // 8-wavefront workgroups with two LDS buffers once there is more than one round of
-    // 4-wavefront workgroups to run and a workgroup has at least 8 row tiles to share a chunk
+    // 8-wavefront workgroups with two LDS buffers (the next chunk is fetched during the matrix work) once
+    // there is more than one round of 4-wavefront workgroups to run. With fewer than 8 row tiles some of the
+    // 8 wavefronts only stage; measured to pay down to 4 tiles (many KV heads, few rows per head).
     const long long chunk_wgs4 = (long long)chunks * m.Hkv * B * ((avg_tiles + 3) / 4);
-    int nw = (avg_tiles >= 8 && chunk_wgs4 > c->attn_target_wgs) ? 8 : 4;
+    int nw = (avg_tiles >= 4 && chunk_wgs4 > c->attn_target_wgs) ? 8 : 4;
     if (c->attn_waves == 4 || c->attn_waves == 8) nw = c->attn_waves;
     const int rb = c->attn_row_blocks > 0 ? c->attn_row_blocks : (ntiles + nw - 1) / nw;
     const int rb_avg = (avg_tiles + nw - 1) / nw;
