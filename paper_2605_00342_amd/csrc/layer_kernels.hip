@@ -608,8 +608,9 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
 }
 
 // merge of the per-split partial softmaxes. D/4 lanes per (token, head) row, each with four
-// consecutive output columns; 256 / (D/4) rows per workgroup (D is 64 or 128, so the lanes of a
-// row sit in one wavefront). Empty splits carry max = -inf and their partial rows are never read
+// consecutive output columns; blockDim / (D/4) rows per workgroup (D is 64 or 128, so the lanes of a
+// row sit in one wavefront; one-wavefront workgroups when there are few rows, so that the serial walk
+// over the splits is spread over more CUs). Empty splits carry max = -inf and their partial rows are never read
 // into the sum. The partial rows of the first splits are requested before the (max, sum) pairs
 // are reduced, so the two round trips overlap.
 constexpr int kMergeBatch = 16;
@@ -620,7 +621,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict
                                                          void* __restrict__ aux_out) {
   const int lpr = D >> 2;  // lanes per row: 16 or 32
   const int tid = threadIdx.x;
-  const int row = blockIdx.x * (256 / lpr) + tid / lpr;
+  const int row = blockIdx.x * ((int)blockDim.x / lpr) + tid / lpr;
   const int c4 = tid & (lpr - 1);
   if (row >= rows) return;  // (whole row groups leave together; no barrier follows)
   const size_t sstride = (size_t)rows * D;
@@ -1423,6 +1424,9 @@ int launch_attention(const evict_ctx* c, const void* kc, const void* vc, long lo
     // batch: splits past a shorter sequence's context leave at once, so the grid is not what runs.)
     int want = (nw == 8 ? c->attn_target_wgs / 2 : c->attn_target_wgs) / (m.Hkv * B * rb_avg) - (B == 1 ? 1 : 0);
     want = want < 1 ? 1 : want;
+    // (the merge walks the splits of a row in batches of 16, one round trip each: beyond about 32 splits a
+    // second chunk per workgroup costs less than the extra batches; measured at 8 nodes, ctx 8192)
+    want = want > 32 ? 32 : want;
     int cps = (chunks + want - 1) / want;  // chunks per split
     cps = cps < 1 ? 1 : cps;
     keys = cps * kMfmaKeys;
@@ -1453,13 +1457,15 @@ int launch_attention(const evict_ctx* c, const void* kc, const void* vc, long lo
   }
   int rc = launch_status("attention partial kernel");
   if (rc) return rc;
-  const int mrows = T * m.Hq, rows_per_wg = 256 / (m.D / 4);
+  const int mrows = T * m.Hq;
+  const int mthreads = (long long)mrows * (m.D / 4) >= 256 * 256 ? 256 : 64;  // at least ~256 workgroups, or one wavefront each
+  const int rows_per_wg = mthreads / (m.D / 4);
   const dim3 mgrid((mrows + rows_per_wg - 1) / rows_per_wg);
   if (m.dtype == EVICT_BF16)
-    hipLaunchKernelGGL(attn_merge_kernel<BF16>, mgrid, dim3(256), 0, s, c->part_o, c->part_ml, nsplits, mrows, m.D,
+    hipLaunchKernelGGL(attn_merge_kernel<BF16>, mgrid, dim3(mthreads), 0, s, c->part_o, c->part_ml, nsplits, mrows, m.D,
                        c->attn_o, aux_out);
   else
-    hipLaunchKernelGGL(attn_merge_kernel<F32>, mgrid, dim3(256), 0, s, c->part_o, c->part_ml, nsplits, mrows, m.D,
+    hipLaunchKernelGGL(attn_merge_kernel<F32>, mgrid, dim3(mthreads), 0, s, c->part_o, c->part_ml, nsplits, mrows, m.D,
                        c->attn_o, aux_out);
   return launch_status("attn_merge_kernel");
 }
