@@ -45,7 +45,8 @@ class SpecLoop:
     def __init__(self, cfg, ctx, layers, k_caches, v_caches, seq_stride, head_stride, capacity, n_max,
                  lm_head=None, device="cuda:0", block_table=None, page_size=0, n_pages=0):
         """layers: list of LayerWeights; k_caches / v_caches: one [1][Hkv][capacity][D] tensor per layer;
-        lm_head: (g_final, wlm_packed) or None (then every draft must carry target_next).
+        lm_head: (g_final, wlm_packed) or (g_final, wlm_packed, vocab) or None (then every draft must carry
+        target_next); the vocabulary size is needed for acceptance under sampling.
         Paged caches: block_table int32 [1][pages] (pages for all `capacity` positions), page_size,
         n_pages; k_caches / v_caches are then the page pools [n_pages][Hkv][page_size][D] and
         seq_stride is the distance between pages."""
@@ -66,6 +67,10 @@ class SpecLoop:
         self.k_new = [z(N, cfg.Hkv, cfg.D, dt=tdt) for _ in range(L)]
         self.v_new = [z(N, cfg.Hkv, cfg.D, dt=tdt) for _ in range(L)]
         self.path, self.path_len, self.bonus = z(1, N), z(1), z(1)
+        # acceptance under sampling: full score rows of the LM head and the compacted per-node random numbers
+        self.vocab = int(lm_head[2]) if (lm_head is not None and len(lm_head) > 2) else 0
+        self.logits = z(N, self.vocab, dt=f32) if self.vocab else None
+        self.ug = z(N, dt=f32)
         self.ctx_len = [z(1), z(1)]  # ping-pong: a commit reads one and writes the other
         self.cur = 0
         self.ctx_len_host = 0
@@ -75,9 +80,14 @@ class SpecLoop:
         self.ctx_len_host = L
 
     def iteration(self, d: DraftOnDevice, cost: Optional[torch.Tensor], log_lists: bool = False,
-                  rho: Optional[float] = None) -> IterationLog:
+                  rho: Optional[float] = None, sample=None) -> IterationLog:
         """cost: device cost table float32[n + 1] -> EVICT truncation; rho -> the cost-agnostic
-        coverage rule instead; neither -> verify all n nodes."""
+        coverage rule instead; neither -> verify all n nodes. sample = (temperature, u_node, u_bonus):
+        acceptance by the sequential sibling rule under sampling (Sec. 2.1, Eq. 3) on the LM head's
+        scores, with one random number per draft node (device float32[n], indexed like the nodes) and
+        one per sequence; else the greedy rule."""
+        if sample is not None and (self.lm_head is None or not self.vocab):
+            raise ValueError("acceptance under sampling needs the LM head and its vocabulary size")
         cfg, n = self.cfg, d.n
         cl_in, cl_out = self.ctx_len[self.cur], self.ctx_len[self.cur ^ 1]
         if cost is not None or rho is not None:
@@ -92,10 +102,15 @@ class SpecLoop:
             ev.evict_gather_rows(d.tok, self.tokg, 4, d.tree_off, self.new_off, self.keep, 1, n)
             if d.target_next is not None:
                 ev.evict_gather_rows(d.target_next, self.tng, 4, d.tree_off, self.new_off, self.keep, 1, n)
+            u_node = None
+            if sample is not None:
+                ev.evict_gather_rows(sample[1], self.ug, 4, d.tree_off, self.new_off, self.keep, 1, n)
+                u_node = self.ug
             off, par, x, tok, tn = self.new_off, self.new_parent, self.xg, self.tokg, self.tng
         else:
             k = n
             off, par, x, tok, tn = d.tree_off, d.parent, d.x, d.tok, d.target_next
+            u_node = sample[1] if sample is not None else None
         if self.block_table is not None:
             ev.evict_verify_stack_paged(self.ctx, self.layers, off, par, 1, k, self.kc, self.vc, self.seq_stride, self.head_stride,
                                         self.block_table, self.block_table.shape[-1], self.page_size, self.n_pages, cl_in,
@@ -103,11 +118,16 @@ class SpecLoop:
         else:
             ev.evict_verify_stack(self.ctx, self.layers, off, par, 1, k, self.kc, self.vc, self.seq_stride, self.head_stride,
                                   cl_in, max(self.ctx_len_host, 1), x, self.out, self.k_new, self.v_new)
-        if self.lm_head is not None:
-            ev.evict_lm_head_argmax(self.ctx, self.out, self.lm_head[0], self.lm_head[1], k, self.next)
-        if d.target_next is None:
-            tn = self.next
-        ev.evict_accept_path(None, off, par, tok, tn, 1, self.path, self.n_max, self.path_len, self.bonus)
+        if sample is not None:
+            ev.evict_lm_head_logits(self.ctx, self.out, self.lm_head[0], self.lm_head[1], k, self.logits)
+            ev.evict_accept_path_sampled(self.ctx, off, par, tok, self.logits, self.vocab, sample[0], u_node, sample[2], 1, k,
+                                         self.path, self.n_max, self.path_len, self.bonus)
+        else:
+            if self.lm_head is not None:
+                ev.evict_lm_head_argmax(self.ctx, self.out, self.lm_head[0], self.lm_head[1], k, self.next)
+            if d.target_next is None:
+                tn = self.next
+            ev.evict_accept_path(None, off, par, tok, tn, 1, self.path, self.n_max, self.path_len, self.bonus)
         if self.block_table is not None:
             ev.evict_kv_commit_stack_paged(self.ctx, self.dtype_code, cfg.Hkv, cfg.D, self.k_new, self.v_new, off, self.path,
                                            self.n_max, self.path_len, self.kc, self.vc, self.seq_stride, self.head_stride,

@@ -98,3 +98,91 @@ def test_loop_matches_oracle_composition(cfg_name, truncate, page):
             assert ev.evict_device_status(layers[0].ctx) == 0
     finally:
         layers[0].close()
+
+
+@pytest.mark.parametrize("cfg_name,truncate", [("tiny", True), ("mini_bf16", False)])
+def test_loop_with_acceptance_under_sampling(cfg_name, truncate):
+    """The same loop with the sequential sibling rule under sampling (Sec. 2.1, Eq. 3) on the LM head's scores.
+    Draft tokens are taken from the most likely tokens under the oracle's scores of the parent (as a drafter's
+    would be), so acceptances and rejections both occur. The accepted path is decided from scores computed in
+    bf16 / fp32 on the GPU: the oracle's rule is applied to the GPU's own score rows (which are checked against
+    the oracle's), and a decision within 1e-5 of its threshold is not compared."""
+    cfg = synth.CONFIGS[cfg_name]
+    n_layers, N, L0, cap, iters, seed, V, temp = 2, 14, 37, 128, 5, 73, 496, 0.8
+    Ws = [synth.layer_weights(cfg, synth.philox(seed, 1 + l)) for l in range(n_layers)]
+    kv = [synth.kv_cache(cfg, L0, synth.philox(seed, 200 + l)) for l in range(n_layers)]
+    g = synth.philox(seed, 64)
+    w_lm = synth.store((0.5 * g.standard_normal((V, cfg.d))).astype(np.float32), cfg.dtype)
+    gain = synth.store((1.0 + 0.1 * g.standard_normal(cfg.d)).astype(np.float32), cfg.dtype)
+    cost = (1.0 + 0.05 * np.arange(N + 1)).astype(np.float32)
+    layers = [harness.DeviceLayer(cfg, Ws[0], max_tokens=N, max_batch=1, max_ctx=cap, vocab=V)]
+    for W in Ws[1:]:
+        layers.append(harness.DeviceLayer(cfg, W, 0, 0, 0, ctx=layers[0].ctx))
+    try:
+        tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+        kc = [torch.zeros(1, cfg.Hkv, cap, cfg.D, dtype=tdt, device=DEV) for _ in range(n_layers)]
+        vc = [torch.zeros_like(k) for k in kc]
+        for l in range(n_layers):
+            kc[l][0, :, :L0] = harness.to_dev(kv[l][0], cfg.dtype)
+            vc[l][0, :, :L0] = harness.to_dev(kv[l][1], cfg.dtype)
+        loop = SpecLoop(cfg, layers[0].ctx, [l.weights for l in layers], kc, vc, cfg.Hkv * cap * cfg.D, cap * cfg.D, cap, N,
+                        lm_head=(harness.to_dev(gain, cfg.dtype), harness.pack_lm_head(cfg, w_lm), V))
+        loop.set_context_length(L0)
+        cost_dev = torch.from_numpy(cost).to(DEV) if truncate else None
+        K = [kv[l][0] for l in range(n_layers)]
+        Vc = [kv[l][1] for l in range(n_layers)]
+        L, lens, compared = L0, [], 0
+        for it in range(iters):
+            d = synth.draft_iteration(cfg, N, seed, it, 0.4, vocab=V)
+            par, x, q = d["parent"], d["x"], d["q"]
+            keep = np.arange(N)
+            if truncate:
+                sel = orc.select_prefix(par, q, cost, N)
+                keep, par_k = sel["keep"], sel["new_parent"]
+            else:
+                par_k = par
+            # the oracle's layers and scores on the kept nodes (they do not depend on the dropped ones)
+            outs, xin = [], x[keep]
+            for l in range(n_layers):
+                r = orc.verify_layer(cfg, Ws[l], np.array([0, len(par_k)]), par_k, xin, [K[l]], [Vc[l]], np.array([L]))
+                outs.append(r)
+                xin = r["out"]
+            _, want_logits = orc.lm_head_argmax(outs[-1]["out"], gain, w_lm, cfg.eps, act=cfg.dtype)
+            tok_k = np.zeros(len(par_k), np.int32)
+            for u in range(len(par_k)):
+                kids = [c for c in range(len(par_k)) if par_k[c] == u]
+                top = np.argsort(-want_logits[u])[: max(6, len(kids))]
+                order = top if g.random() < 0.6 else g.permutation(top)   # mostly the likeliest token first
+                for c, t in zip(kids, order):
+                    tok_k[c] = t
+            tok = np.zeros(N, np.int32); tok[keep] = tok_k
+            u_node = (g.random(N) ** 3).astype(np.float32)
+            u_bonus = g.random(1).astype(np.float32)
+            dd = DraftOnDevice(harness.dev_i32(np.array([0, N])), harness.dev_i32(par), torch.from_numpy(q).to(DEV),
+                               harness.to_dev(x, cfg.dtype), harness.dev_i32(tok), None, N)
+            log = loop.iteration(dd, cost_dev, log_lists=True,
+                                 sample=(temp, torch.from_numpy(u_node).to(DEV), torch.from_numpy(u_bonus).to(DEV)))
+            k = len(par_k)
+            assert log.k_used == k and (not truncate or log.keep == list(keep))
+            got_logits = loop.logits[:k].cpu().numpy()
+            assert np.linalg.norm(got_logits - want_logits) / np.linalg.norm(want_logits) < (3e-2 if cfg.dtype == "bf16" else 2e-4)
+            P = orc.softmax_temperature(got_logits, temp)
+            rp, rb, trace, cdf = orc.accept_path_sampled(par_k, tok_k, P, u_node[keep], u_bonus[0], with_trace=True)
+            if not any(abs(float(u_node[keep][c]) - p) < 1e-5 for c, p, _ in trace):
+                compared += 1
+                assert log.path == list(rp) and log.path_len == len(rp)
+                t = log.bonus
+                below = cdf[t - 1] if t > 0 else 0.0
+                assert cdf[t] - below > 0.0 and below - 1e-5 <= float(u_bonus[0]) <= cdf[t] + 1e-5
+            # both sides commit the path the GPU took (identical to the oracle's whenever compared)
+            path = log.path
+            for l in range(n_layers):
+                K[l], Vc[l] = orc.kv_commit(K[l], Vc[l], orc.handoff(outs[l]["k_new"], cfg.dtype),
+                                            orc.handoff(outs[l]["v_new"], cfg.dtype), path)
+            L += len(path)
+            lens.append(len(path))
+            assert loop.ctx_len_host == L and int(loop.ctx_len[loop.cur].item()) == L
+        assert compared >= iters - 1 and max(lens) > 1, (compared, lens)
+        assert ev.evict_device_status(layers[0].ctx) == 0
+    finally:
+        layers[0].close()
