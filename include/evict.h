@@ -330,7 +330,7 @@ int evict_device_status(evict_ctx* ctx, int32_t* status_host, void* stream);
  *                     workgroup takes from the device-side work list at a time
  *   "moe_gateup_kernel" 1: gate/up projections with one (gate, up) strip pair per wavefront and the token
  *                     operand in LDS; 0: contraction split over the wavefronts of a workgroup; 2 = auto
- *                     (the former from 128 tokens on)
+ *                     (the former from 64 tokens on where its chunks line up with the XCDs, else from 128)
  *   "moe_down_kernel" 1: down projections with one 16-row strip per wavefront over the whole
  *                     contraction range (token operand staged in LDS); 0: contraction split
  *                     over the wavefronts of a workgroup like the other GEMMs
@@ -343,7 +343,7 @@ int evict_device_status(evict_ctx* ctx, int32_t* status_host, void* stream);
  *                     hold), 2 = auto (the latter from 128 or 256 tokens on); "dense_ntw" its token tiles
  *                     per workgroup, 1, 2 or 0 = auto
  *   "attn_target_wgs" workgroups the bf16 attention kernel aims for when it cuts the context into splits
- *   "moe_nt"          16-token tiles per work-list slot of the grouped expert GEMMs: 1, 2, or 0 = auto
+ *   "moe_nt"          16-token tiles per work-list slot of the grouped expert GEMMs: 1, 2, or 0 = auto (1)
  *   "attn_waves"      wavefronts per workgroup of that kernel: 4, 8 (two LDS buffers, next chunk fetched
  *                     during the matrix work), or 0 = auto
  *   "attn_row_blocks" workgroups per (KV split, KV head) in the bf16 attention kernel, 0 = auto
