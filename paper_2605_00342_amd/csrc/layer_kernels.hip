@@ -1384,6 +1384,9 @@ int kernels_setup(const evict_model_desc& m) {
   EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)attn_partial_mfma_kernel<64, 4, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_mfma_lds_bytes(64)));
   EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)attn_partial_mfma_kernel<128, 8, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * (int)attn_mfma_lds_bytes(128)));
   EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)attn_partial_mfma_kernel<64, 8, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * (int)attn_mfma_lds_bytes(64)));
+  if (m.E > 256)  // LDS variant of TopK: one row of keys per wavefront
+    EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)topk_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        (int)((size_t)kRouterWaves * (64 + m.E) * sizeof(float))));
   const size_t rl = router_lds_bytes(m);
   EVICT_REQUIRE(rl <= 152 * 1024, EVICT_E_UNSUPPORTED, "router needs %zu bytes of LDS (limit 152 KiB): d too large", rl);
   EVICT_REQUIRE(m.d <= 64 * 8 * (m.dtype == EVICT_BF16 ? 8 : 4), EVICT_E_UNSUPPORTED, "router keeps a token row in registers: d=%d too large", m.d);

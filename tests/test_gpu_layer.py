@@ -271,3 +271,11 @@ def test_dense_projections_one_strip_per_wavefront():
     case = synth.make_case("mini_bf16", n=128, L=64, seed=14, tree="eagle")
     a, b = run_case(case), run_case(case, tune={"dense_kernel": 0})
     assert rel_l2(a["q"], b["q"]) < 1e-2 and rel_l2(a["h"], b["h"]) < 1e-2
+
+
+@pytest.mark.parametrize("E,k,n,seed", [(512, 8, 40, 81), (1024, 6, 70, 82), (320, 3, 9, 83)])
+def test_more_than_256_experts(E, k, n, seed):
+    """Above 256 experts TopK keeps its keys in LDS instead of registers (and TopK / union are two launches)."""
+    cfg = synth.ModelCfg(f"many{E}", "bf16", d=256, Hq=4, Hkv=2, D=64, E=E, k=k, F=64, theta=1e4)
+    case = synth.make_case(cfg.name, n=n, L=50, seed=seed, tree="bfs", cfg=cfg)
+    check_against_oracle(case, run_case(case))
