@@ -279,3 +279,12 @@ def test_more_than_256_experts(E, k, n, seed):
     cfg = synth.ModelCfg(f"many{E}", "bf16", d=256, Hq=4, Hkv=2, D=64, E=E, k=k, F=64, theta=1e4)
     case = synth.make_case(cfg.name, n=n, L=50, seed=seed, tree="bfs", cfg=cfg)
     check_against_oracle(case, run_case(case))
+
+
+@pytest.mark.parametrize("cfg_name", ["mini_bf16", "mini_sigmoid"])
+def test_largest_call_eight_trees_of_128_nodes(cfg_name):
+    """1024 tokens in one call (8 trees of the largest size); with 8 active experts that is the limit of
+    8192 token-expert pairs, where the grouping leaves the bitmask path (masks no longer fit in LDS)."""
+    case = synth.make_case(cfg_name, n=128, L=40, seed=91, tree="bfs", batch=8, L_list=[40, 0, 129, 7, 300, 64, 1, 200])
+    info = check_against_oracle(case, run_case(case))
+    print(cfg_name, "8 x 128:", info)
