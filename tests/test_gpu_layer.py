@@ -288,3 +288,18 @@ def test_largest_call_eight_trees_of_128_nodes(cfg_name):
     case = synth.make_case(cfg_name, n=128, L=40, seed=91, tree="bfs", batch=8, L_list=[40, 0, 129, 7, 300, 64, 1, 200])
     info = check_against_oracle(case, run_case(case))
     print(cfg_name, "8 x 128:", info)
+
+
+@pytest.mark.parametrize("cfg_name,n,L,seed", [("mini_bf16", 8, 12000, 95), ("tiny", 5, 12100, 96), ("mini_bf16", 40, 9999, 97)])
+def test_longest_contexts(cfg_name, n, L, seed):
+    """Contexts close to the largest a context object can be created for (12160 positions)."""
+    case = synth.make_case(cfg_name, n=n, L=L, seed=seed)
+    check_against_oracle(case, run_case(case))
+
+
+def test_context_limit_is_an_error_not_a_fault():
+    case = synth.make_case("tiny", n=4, L=8, seed=98)
+    with pytest.raises(ev.EvictError):
+        harness.DeviceLayer(case["cfg"], case["W"], 4, 1, 20000)
+    with pytest.raises(ev.EvictError):          # more than 8192 token-expert pairs
+        harness.DeviceLayer(case["cfg"], case["W"], 5000, 1, 64)
