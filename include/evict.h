@@ -101,7 +101,10 @@ const char* evict_last_error(void);
 
 /* Create a context for one model shape. max_tokens bounds T (sum of tree sizes in a call),
  * max_batch bounds B, max_ctx bounds any sequence's KV context length. Allocates all
- * scratch memory on the current device. */
+ * scratch memory on the current device. Limits (EVICT_E_UNSUPPORTED beyond them):
+ * max_tokens * k <= 8192, at most EVICT_MAX_TREE_NODES nodes per tree, max_ctx <= 1048576 for
+ * bf16 storage and <= 12160 for fp32 storage, head dimension 64 or 128, E <= 1024 in multiples
+ * of 16, rows of d elements up to 16 KiB. */
 int evict_create(evict_ctx** out, const evict_model_desc* m, int max_tokens, int max_batch, int max_ctx);
 int evict_destroy(evict_ctx* ctx);
 

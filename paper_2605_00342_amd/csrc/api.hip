@@ -61,7 +61,11 @@ int evict_create(evict_ctx** out, const evict_model_desc* m, int max_tokens, int
                 "evict_create: max_tokens=%d, max_batch=%d, max_ctx=%d", max_tokens, max_batch, max_ctx);
   EVICT_REQUIRE((long long)max_tokens * m->k <= 8192, EVICT_E_UNSUPPORTED, "max_tokens*k=%lld exceeds 8192",
                 (long long)max_tokens * m->k);
-  EVICT_REQUIRE(attn_splits_for(max_ctx) <= 192, EVICT_E_UNSUPPORTED, "max_ctx=%d needs more than 192 attention splits", max_ctx);
+  // attention scratch: the bf16 kernel cuts any context into at most 32 splits (+ the draft-node split); the
+  // fp32 kernel takes 64 keys per split and is kept to 192 splits
+  EVICT_REQUIRE(m->dtype == EVICT_BF16 || attn_splits_for(max_ctx) <= 192, EVICT_E_UNSUPPORTED,
+                "max_ctx=%d needs more than 192 attention splits (fp32 storage: at most 12160 positions)", max_ctx);
+  EVICT_REQUIRE(max_ctx <= (1 << 20), EVICT_E_UNSUPPORTED, "max_ctx=%d exceeds 1048576", max_ctx);
   EVICT_REQUIRE(m->d * (m->dtype == EVICT_BF16 ? 2 : 4) <= 16384, EVICT_E_UNSUPPORTED, "d=%d: rows above 16 KiB are not supported", m->d);
   evict_ctx_owner* o = new (std::nothrow) evict_ctx_owner();
   EVICT_REQUIRE(o, EVICT_E_INVALID, "out of host memory");
@@ -70,7 +74,7 @@ int evict_create(evict_ctx** out, const evict_model_desc* m, int max_tokens, int
   c.max_tokens = max_tokens;
   c.max_batch = max_batch;
   c.max_ctx = max_ctx;
-  c.max_splits = attn_splits_for(max_ctx);
+  c.max_splits = m->dtype == EVICT_BF16 ? kAttnMfmaMaxSplits : attn_splits_for(max_ctx);
   const size_t T = max_tokens, eb = elem_bytes(m->dtype);
   const size_t d = m->d, HqD = (size_t)m->Hq * m->D, E = m->E, k = m->k, F = m->F;
   rc = EVICT_OK;

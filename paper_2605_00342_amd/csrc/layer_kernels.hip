@@ -1436,6 +1436,7 @@ int launch_attention(const evict_ctx* c, const void* kc, const void* vc, long lo
     ctx_splits = (max_ctx_host + keys - 1) / keys;
     nsplits = ctx_splits + 1;
     EVICT_REQUIRE(rb * nw >= ntiles, EVICT_E_INVALID, "attn_row_blocks=%d is too small for %d query tiles", rb, ntiles);
+    EVICT_REQUIRE(nsplits <= c->max_splits, EVICT_E_INVALID, "attention: %d splits exceed the scratch of %d", nsplits, c->max_splits);
     const int units = nsplits * m.Hkv * B;
     const dim3 grid(((units + 7) / 8) * 8 * rb);
     const size_t lds = attn_mfma_lds_bytes(m.D) * (nw == 8 ? 2 : 1);

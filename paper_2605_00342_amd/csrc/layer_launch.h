@@ -17,6 +17,7 @@ int launch_prep(const evict_ctx* c, const int32_t* tree_off, const int32_t* pare
                 int max_ctx, const void* x, const void* gain, int norm_only, hipStream_t s);
 int kernels_setup(const evict_model_desc& m);
 int attn_splits_for(int max_ctx);
+constexpr int kAttnMfmaMaxSplits = 34;  // bf16 attention: at most 32 context splits + the draft-node split (+ 1 spare)
 int launch_attention(const evict_ctx* c, const void* kc, const void* vc, long long seq_stride, long long head_stride,
                      const int32_t* ctx_len, int max_ctx_host, const int32_t* tree_off, int B, int T, const void* k_new,
                      const void* v_new, void* aux_out, hipStream_t s);

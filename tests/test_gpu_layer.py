@@ -290,9 +290,11 @@ def test_largest_call_eight_trees_of_128_nodes(cfg_name):
     print(cfg_name, "8 x 128:", info)
 
 
-@pytest.mark.parametrize("cfg_name,n,L,seed", [("mini_bf16", 8, 12000, 95), ("tiny", 5, 12100, 96), ("mini_bf16", 40, 9999, 97)])
+@pytest.mark.parametrize("cfg_name,n,L,seed", [("mini_bf16", 8, 12000, 95), ("tiny", 5, 12100, 96), ("mini_bf16", 40, 9999, 97),
+                                               ("mini_bf16", 8, 100000, 99), ("mini_sigmoid", 16, 40000, 100)])
 def test_longest_contexts(cfg_name, n, L, seed):
-    """Contexts close to the largest a context object can be created for (12160 positions)."""
+    """Long contexts: close to the fp32 limit of 12160 positions, and 40k / 100k positions with bf16 storage
+    (rotary angles at such positions are formed in double on the device)."""
     case = synth.make_case(cfg_name, n=n, L=L, seed=seed)
     check_against_oracle(case, run_case(case))
 
