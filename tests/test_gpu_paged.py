@@ -128,7 +128,7 @@ def deepest_paths(tree_off, parent):
 @pytest.mark.parametrize("cfg_name,n,Ls,P", [
     ("tiny", 8, [64], 16), ("tiny", 9, [37, 0, 5], 4), ("mini_bf16", 24, [150, 31, 300], 16),
     ("mini_bf16", 40, [700], 64), ("mini_bf16", 20, [130], 1), ("mini_bf16", 33, [260, 129], 256),
-    ("mini_sigmoid", 16, [200, 90], 32),
+    ("mini_sigmoid", 16, [200, 90], 32), ("mini_bf16", 12, [20000, 777], 16),
 ])
 def test_paged_stack_commit_and_second_iteration(cfg_name, n, Ls, P):
     extra = 40
