@@ -482,7 +482,7 @@ def main():
             cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
         except Exception:
             cores = os.cpu_count() or 1
-        reps = 5
+        reps = 25  # about 10 s of CPU work at the default workload
         c0 = time.perf_counter()
         for _ in range(reps):
             orc.select_prefix(case["parent"], case["q"], cost, N)
