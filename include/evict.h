@@ -12,9 +12,11 @@
  *     pointers marked [host] are host pointers. The library owns only evict_ctx and the
  *     scratch memory inside it, allocated once in evict_create.
  *   - Work is enqueued on the caller's hipStream_t (passed as void*; NULL = default
- *     stream); no call synchronises the stream or allocates after evict_create.
- *   - Inputs are never written. The KV cache is read-only: keys/values of the draft nodes
- *     go to caller buffers.
+ *     stream); nothing allocates after evict_create, and only the calls that hand a value
+ *     back to the host synchronise the stream (evict_device_status, evict_profile_cost*,
+ *     evict_stage_times; each says so).
+ *   - Inputs are never written. Verification reads the KV cache only: keys/values of the
+ *     draft nodes go to caller buffers, and only evict_kv_commit* writes them into a cache.
  *   - Trees are batched CSR-style: tree_off int32[B+1] with tree_off[0] = 0 and
  *     tree_off[B] = T (the calls that take T rely on it), node arrays concatenated, parent
  *     ids are tree-local with parent[0] = -1 and parent[i] < i (node 0 is the root
