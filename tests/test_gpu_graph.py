@@ -147,3 +147,59 @@ def test_graph_error_paths():
             ev.evict_graph_destroy(g)
     finally:
         layer.close()
+
+
+def test_one_graph_per_verification_length_dispatched_by_the_selected_length():
+    """Sec. 3.3: the verification of every length k is captured once; at run time the selection runs, its k* is
+    read back and the graph of that length is replayed on the compacted tree. Every replay must equal the
+    direct calls for the same k* bit for bit."""
+    N, L = 12, 50
+    case = synth.make_case("mini_bf16", n=N, L=L, seed=41)
+    cfg = case["cfg"]
+    layer = harness.DeviceLayer(cfg, case["W"], max_tokens=N, max_batch=1, max_ctx=L)
+    dc = harness.DeviceCase(case, with_aux=False)
+    i32, f32 = torch.int32, torch.float32
+    tdt = torch.bfloat16
+    side = torch.cuda.Stream()
+    graphs = {}
+    try:
+        with torch.cuda.stream(side):
+            q = torch.from_numpy(case["q"]).to(DEV)
+            cost = torch.zeros(N + 1, dtype=f32, device=DEV)
+            k_star = torch.zeros(1, dtype=i32, device=DEV); keep = torch.zeros(N, dtype=i32, device=DEV)
+            new_parent = torch.zeros(N, dtype=i32, device=DEV); new_off = torch.zeros(2, dtype=i32, device=DEV)
+            est = torch.zeros(1, dtype=f32, device=DEV)
+            xg = torch.zeros(N, cfg.d, dtype=tdt, device=DEV)
+            out = torch.zeros(N, cfg.d, dtype=tdt, device=DEV)
+            kn = torch.zeros(N, cfg.Hkv, cfg.D, dtype=tdt, device=DEV); vn = torch.zeros_like(kn)
+
+            def verify(k):
+                ev.evict_gather_rows(dc.x, xg, cfg.d * 2, dc.tree_off, new_off, keep, 1, N)
+                ev.evict_verify_layer(layer.ctx, layer.weights, new_off, new_parent, 1, k, dc.k_cache, dc.v_cache, dc.seq_stride,
+                                      dc.head_stride, dc.ctx_len, L, xg, out, kn, vn, None)
+            side.synchronize()
+            for k in range(1, N + 1):
+                ev.evict_graph_begin(layer.ctx)
+                verify(k)
+                graphs[k] = ev.evict_graph_end(layer.ctx)
+            seen = set()
+            for slope in (0.0, 0.02, 0.08, 0.3, 2.0):
+                cost_np = (1.0 + slope * np.arange(N + 1)).astype(np.float32)
+                cost.copy_(torch.from_numpy(cost_np))
+                ev.evict_select_prefix(None, dc.tree_off, dc.parent, q, 1, N, cost, N, k_star, keep, new_parent, new_off, est)
+                k = int(k_star.item())                      # the one read-back that picks the graph
+                assert k == orc.select_prefix(case["parent"], case["q"], cost_np, N)["k_star"]
+                seen.add(k)
+                out.zero_(); kn.zero_()
+                verify(k)
+                side.synchronize()
+                want_out, want_kn = out[:k].clone(), kn[:k].clone()
+                out.zero_(); kn.zero_()
+                ev.evict_graph_launch(graphs[k])
+                side.synchronize()
+                assert torch.equal(out[:k], want_out) and torch.equal(kn[:k], want_kn), f"k* = {k}"
+            assert len(seen) >= 3, seen
+    finally:
+        for g in graphs.values():
+            ev.evict_graph_destroy(g)
+        layer.close()
