@@ -207,8 +207,12 @@ def spec_loop(args):
                    "union_range_at_N": [round(float(us_[N - 1]), 2), round(float(us_[3 * N - 1]), 2)]}
     results = {}
     cost_dev = None
-    for mode in ("verify_all", "evict", "coverage_0.7", "coverage_0.4"):
+    # plain autoregressive decoding for comparison: a one-node tree per iteration (the root alone: one token each)
+    pool1 = [DraftOnDevice(harness.dev_i32(np.array([0, 1])), p.parent[:1], p.q[:1], p.x[:1], p.tok[:1], p.target_next[:1], 1)
+             for p in pool]
+    for mode in ("autoregressive", "verify_all", "evict", "coverage_0.7", "coverage_0.4"):
         rho = float(mode.split("_")[1]) if mode.startswith("coverage") else None
+        drafts = pool1 if mode == "autoregressive" else pool
         if mode == "evict":
             # C(k) must be the cost of a whole iteration at length k: the part outside the layer stack
             # (LM head, acceptance, commits, read-backs) is taken from the measured full-size iteration
@@ -218,13 +222,13 @@ def spec_loop(args):
         table = cost_dev if mode == "evict" else None
         loop.set_context_length(L0)
         for i in range(8):
-            loop.iteration(pool[i % len(pool)], table, rho=rho)
+            loop.iteration(drafts[i % len(drafts)], table, rho=rho)
         loop.set_context_length(L0)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         tokens = ksum = 0
         for i in range(args.iters):
-            log = loop.iteration(pool[i % len(pool)], table, rho=rho)
+            log = loop.iteration(drafts[i % len(drafts)], table, rho=rho)
             tokens += log.path_len
             ksum += log.k_used
         torch.cuda.synchronize()
@@ -237,6 +241,7 @@ def spec_loop(args):
                           "mean_accepted_tokens": round(r["mean_accepted_tokens"], 3),
                           "mean_verified_nodes": round(r["mean_verified_nodes"], 2),
                           "speedup_vs_verify_all": round(r["tokens_per_s"] / results["verify_all"]["tokens_per_s"], 4),
+                          "speedup_vs_autoregressive": round(r["tokens_per_s"] / results["autoregressive"]["tokens_per_s"], 4),
                           "config": {"workload": f"qwen3-30b-a3b-shaped stack of {nl} layers + LM head, N={N} draft nodes, "
                                                  f"ctx from {L0}, synthetic calibrated drafter, sigma={args.sigma}",
                                      "iterations": args.iters},
