@@ -336,6 +336,8 @@ int evict_device_status(evict_ctx* ctx, int32_t* status_host, void* stream);
  *   "moe_gateup_kernel" 1: gate/up projections with one (gate, up) strip pair per wavefront and the token
  *                     operand in LDS; 0: contraction split over the wavefronts of a workgroup; 2 = auto
  *                     (the former from 64 tokens on where its chunks line up with the XCDs, else from 128)
+ *   "moe_lds_dma"     1 (default): that kernel stages its token operand with direct global-to-LDS loads where
+ *                     the shape allows (bf16, 64 contraction blocks); 0: through registers
  *   "moe_down_kernel" 1: down projections with one 16-row strip per wavefront over the whole
  *                     contraction range (token operand staged in LDS); 0: contraction split
  *                     over the wavefronts of a workgroup like the other GEMMs

@@ -134,6 +134,7 @@ int evict_create(evict_ctx** out, const evict_model_desc* m, int max_tokens, int
   c.moe_nt = 0;
   c.dense_units = 0;
   c.dense_kernel = 2;
+  c.moe_lds_dma = 1;
   c.dense_ntw = 0;
   c.moe_chunk_gateup = 1;
   c.moe_chunk_down = 1;
@@ -382,6 +383,7 @@ static int verify_layer_impl(evict_ctx* ctx, const evict_layer_weights* w, const
     a.ldo = m.F;
     a.prefetch = ctx->moe_prefetch;
     a.plain_loads = ctx->moe_plain_loads;
+    a.lds_dma = ctx->moe_lds_dma;
     // (one strip pair per wavefront pays once experts often have several token tiles: measured from 64 tokens on
     // where its chunks line up with the XCDs, see gateup_waves, else from 128)
     a.wave_strip = ctx->moe_gateup_kernel == 2 ? (T >= (gateup_waves(a) == 6 ? 64 : 128) ? 1 : 0) : ctx->moe_gateup_kernel;
@@ -604,6 +606,9 @@ int evict_tune(evict_ctx* ctx, const char* key, int value) {
   } else if (!strcmp(key, "dense_units")) {
     EVICT_REQUIRE(value >= 0 && value <= 16, EVICT_E_INVALID, "evict_tune: dense_units must be in [0, 16] (0 = auto)");
     ctx->dense_units = value;
+  } else if (!strcmp(key, "moe_lds_dma")) {
+    EVICT_REQUIRE(value == 0 || value == 1, EVICT_E_INVALID, "evict_tune: moe_lds_dma must be 0 or 1");
+    ctx->moe_lds_dma = value;
   } else if (!strcmp(key, "dense_kernel")) {
     EVICT_REQUIRE(value >= 0 && value <= 2, EVICT_E_INVALID, "evict_tune: dense_kernel must be 0, 1 or 2 (auto)");
     ctx->dense_kernel = value;

@@ -49,6 +49,7 @@ struct GemmArgs {
   int prefetch;          // host-side choice of the kernel variant: 3 = no compile-time step counts (measurement knob)
   int wave_strip;        // host-side: grouped fp32-output GEMM may use gemm_wave_strip_kernel
   int plain_loads;       // 1: never use non-temporal weight loads (measurement knob)
+  int lds_dma;           // 1: strip-pair gate/up kernel stages its token operand with direct global-to-LDS loads
   void* out0;            // QKV: q; RESID: h; SWIGLU: act; F32: y; ARGMAX: best value per (token, strip), [T][ldo]
   void* out1;            // QKV: k_new; ARGMAX: row index of the best value per (strip, token)
   void* out2;            // QKV: v_new
@@ -469,8 +470,9 @@ __global__ __launch_bounds__(WS * 64) __attribute__((amdgpu_waves_per_eu(4))) vo
 // work-list slot). Refills go out in runs of 8
 // consecutive blocks per strip once the window is 16 deep.
 // ------------------------------------------------------------------------------------
-template <typename ST, int WIN, int NB, int WS, int NKB = 0, int NTW = 1>
+template <typename ST, int WIN, int NB, int WS, int NKB = 0, int NTW = 1, bool DMA = false>
 __global__ __launch_bounds__(WS * 64) __attribute__((amdgpu_waves_per_eu(2))) void gemm_wave_gateup_kernel(const GemmArgs a) {
+  static_assert(!DMA || (NTW == 1 && 2 * WIN <= 48), "direct-to-LDS staging: one token tile, window loads countable in vmcnt");
   extern __shared__ __attribute__((aligned(16))) u32x4 s_b[];  // [NTW token tiles][nkb][64]
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -501,12 +503,25 @@ __global__ __launch_bounds__(WS * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
     }
     // token operand blocks of the first tile first, weights behind them (the in-order load counter lets
     // the operand be consumed while the weight windows are still in flight); a second tile reuses the
-    // staging registers once the first is in LDS
-    u32x4 bst[NB];
+    // staging registers once the first is in LDS. DMA: the operand blocks go from global memory straight
+    // into LDS (16 bytes per lane, a block = 1 KiB contiguous = exactly the LDS layout), no staging registers.
+    u32x4 bst[DMA ? 1 : NB];
+    if (DMA) {
+      if (!first) lds_barrier();  // every wavefront is done with the previous chunk's operand
 #pragma unroll
-    for (int i = 0; i < NB; ++i) {
-      const int kb = i * WS + w;
-      if (kb < nkb) bst[i] = *reinterpret_cast<const u32x4*>(xrow[0] + (long long)kb * 64);
+      for (int i = 0; i < NB; ++i) {
+        const int kb = i * WS + w;
+        if (kb < nkb)
+          __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(xrow[0] + (long long)kb * 64),
+                                           (void __attribute__((address_space(3)))*)(s_b + (size_t)kb * 64), 16, 0, 0);
+      }
+    }
+    if constexpr (!DMA) {
+#pragma unroll
+      for (int i = 0; i < NB; ++i) {
+        const int kb = i * WS + w;
+        if (kb < nkb) bst[i] = *reinterpret_cast<const u32x4*>(xrow[0] + (long long)kb * 64);
+      }
     }
     const u32x4* wg = wbase + (long long)(2 * unit) * nkb * 64 + lane;
     const u32x4* wu = wg + (long long)nkb * 64;
@@ -516,20 +531,28 @@ __global__ __launch_bounds__(WS * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
       Ag[j] = once ? __builtin_nontemporal_load(wg + j * 64) : wg[j * 64];
       Au[j] = once ? __builtin_nontemporal_load(wu + j * 64) : wu[j * 64];
     }
-    if (!first) lds_barrier();  // every wavefront is done with the previous chunk's operand
+    if (DMA) {
+      // the operand blocks were requested before the 2 * WIN window loads: wait until only those are outstanding
+      constexpr int kVm = 2 * WIN;
+      __builtin_amdgcn_s_waitcnt((kVm & 0xF) | ((kVm >> 4) << 14) | (0x7 << 4) | (0xF << 8));
+    } else if (!first) {
+      lds_barrier();  // every wavefront is done with the previous chunk's operand
+    }
+    if constexpr (!DMA) {
 #pragma unroll
-    for (int t = 0; t < NTW; ++t) {
-      if (t > 0) {
+      for (int t = 0; t < NTW; ++t) {
+        if (t > 0) {
+#pragma unroll
+          for (int i = 0; i < NB; ++i) {
+            const int kb = i * WS + w;
+            if (kb < nkb) bst[i] = *reinterpret_cast<const u32x4*>(xrow[t] + (long long)kb * 64);
+          }
+        }
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
           const int kb = i * WS + w;
-          if (kb < nkb) bst[i] = *reinterpret_cast<const u32x4*>(xrow[t] + (long long)kb * 64);
+          if (kb < nkb) s_b[((size_t)t * nkb + kb) * 64 + lane] = bst[i];
         }
-      }
-#pragma unroll
-      for (int i = 0; i < NB; ++i) {
-        const int kb = i * WS + w;
-        if (kb < nkb) s_b[((size_t)t * nkb + kb) * 64 + lane] = bst[i];
       }
     }
     lds_barrier();

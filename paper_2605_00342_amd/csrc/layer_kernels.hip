@@ -1232,6 +1232,11 @@ int launch_gemm_wave_gateup(const GemmArgs& a, int nt, int grid, hipStream_t s) 
     hipLaunchKernelGGL((gemm_wave_gateup_kernel<ST, 16, 16, 6, 64, 2>), dim3(grid), dim3(6 * 64), lds, s, a);
     return launch_status("gemm_wave_gateup_kernel");
   }
+  if (a.lds_dma && a.nkb == 64 && ST::kBytes == 2) {
+    if (ws == 6) hipLaunchKernelGGL((gemm_wave_gateup_kernel<ST, 16, 16, 6, 64, 1, true>), dim3(grid), dim3(6 * 64), lds, s, a);
+    else hipLaunchKernelGGL((gemm_wave_gateup_kernel<ST, 16, 16, 4, 64, 1, true>), dim3(grid), dim3(4 * 64), lds, s, a);
+    return launch_status("gemm_wave_gateup_kernel");
+  }
 #define EVICT_GU_LAUNCH(WS_)                                                                                              \
   if (nb <= 4) hipLaunchKernelGGL((gemm_wave_gateup_kernel<ST, 8, 4, WS_>), dim3(grid), dim3(WS_ * 64), lds, s, a);        \
   else if (nb <= 8) hipLaunchKernelGGL((gemm_wave_gateup_kernel<ST, 8, 8, WS_>), dim3(grid), dim3(WS_ * 64), lds, s, a);   \

@@ -184,6 +184,12 @@ def test_gateup_one_strip_pair_per_wavefront():
     cases.append(synth.make_case("t_shared", n=50, L=50, seed=36, tree="bfs", cfg=cfg))
     for case in cases:
         check_against_oracle(case, run_case(case, tune={"moe_gateup_kernel": 1}))
+    # token operand staged with direct global-to-LDS loads (full-size shape only: 64 contraction blocks), single
+    # and several token tiles per expert, and bit-identical to the register-staged variant
+    for case in (cases[4], synth.make_case("qwen3", n=128, L=100, seed=39, sigma=0.2)):
+        got = run_case(case, tune={"moe_gateup_kernel": 1, "moe_lds_dma": 1})
+        check_against_oracle(case, got)
+        assert np.array_equal(got["out"], run_case(case, tune={"moe_gateup_kernel": 1, "moe_lds_dma": 0})["out"])
 
 
 def test_chain_tree_equals_token_by_token_decode_on_gpu():
