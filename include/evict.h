@@ -349,6 +349,7 @@ int evict_device_status(evict_ctx* ctx, int32_t* status_host, void* stream);
  *                     1 one strip per wavefront with the token operand in LDS (where its shape conditions
  *                     hold), 2 = auto (the latter from 128 or 256 tokens on); "dense_ntw" its token tiles
  *                     per workgroup, 1, 2 or 0 = auto
+ *   "lm_units", "lm_nt" LM head: consecutive 16-row strips and 16-token tiles a workgroup takes, 0 = auto
  *   "attn_target_wgs" workgroups the bf16 attention kernel aims for when it cuts the context into splits
  *   "moe_nt"          16-token tiles per work-list slot of the grouped expert GEMMs: 1, 2, or 0 = auto (1)
  *   "attn_waves"      wavefronts per workgroup of that kernel: 4, 8 (two LDS buffers, next chunk fetched
