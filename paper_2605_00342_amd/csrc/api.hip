@@ -294,10 +294,10 @@ static int verify_layer_impl(evict_ctx* ctx, const evict_layer_weights* w, const
   // token tiles per workgroup in the dense projections: two once the tree spans more than two tiles
   const int nt_dense = ctx->dense_nt ? ctx->dense_nt : (T > 64 ? 2 : 1);
   const int dense_tiles = (T + 16 * nt_dense - 1) / (16 * nt_dense);
-  // QKV with several token tiles has workgroups to spare: each then takes two consecutive strips and
-  // its weight loads run ahead across them (measured: helps from two tiles on; the output projection,
-  // with a third of the strips and twice the contraction length, is better left at one)
-  const int qkv_units = ctx->dense_units ? ctx->dense_units : (dense_tiles >= 2 ? 2 : 1);
+  // QKV: a workgroup takes several consecutive strips, so its token operand is fetched once and its weight loads
+  // run ahead across the strips (measured: 2 strips with one token tile, 4 with more; the output projection, with a
+  // third of the strips and twice the contraction length, is better left at one)
+  const int qkv_units = ctx->dense_units ? ctx->dense_units : (dense_tiles >= 2 ? 4 : 2);
   auto dense_grid = [&](int units, int du) { return (((units + du - 1) / du + 7) / 8) * 8 * dense_tiles; };
   // With many token tiles the projections are ordinary dense GEMMs: one strip per wavefront with the token
   // operand of the workgroup in LDS (gemm_dense_strip_kernel) instead of the contraction split. Measured:
