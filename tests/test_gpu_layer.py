@@ -190,6 +190,9 @@ def test_gateup_one_strip_pair_per_wavefront():
         got = run_case(case, tune={"moe_gateup_kernel": 1, "moe_lds_dma": 1})
         check_against_oracle(case, got)
         assert np.array_equal(got["out"], run_case(case, tune={"moe_gateup_kernel": 1, "moe_lds_dma": 0})["out"])
+        # few workgroups, so each takes many chunks in turn and restages its operand in between
+        few = run_case(case, tune={"moe_gateup_kernel": 1, "moe_lds_dma": 1, "moe_grid": 40})
+        assert np.array_equal(got["out"], few["out"])
 
 
 def test_chain_tree_equals_token_by_token_decode_on_gpu():
