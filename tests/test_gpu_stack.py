@@ -95,7 +95,8 @@ def test_stack_of_layers_matches_oracle(cfg_name, n, L, seed):
     st.close()
 
 
-@pytest.mark.parametrize("cfg_name,vocab,T,seed", [("tiny", 1008, 8, 50), ("mini_bf16", 4000, 37, 51), ("mini_bf16", 160, 1, 52)])
+@pytest.mark.parametrize("cfg_name,vocab,T,seed", [("tiny", 1008, 8, 50), ("mini_bf16", 4000, 37, 51), ("mini_bf16", 160, 1, 52),
+                                                  ("tiny", 1008, 40, 53), ("mini_bf16", 4000, 100, 54), ("mini_bf16", 48, 17, 55)])
 def test_lm_head_argmax_matches_oracle(cfg_name, vocab, T, seed):
     cfg = synth.CONFIGS[cfg_name]
     g = synth.philox(seed, 1)
