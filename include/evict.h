@@ -342,7 +342,7 @@ int evict_device_status(evict_ctx* ctx, int32_t* status_host, void* stream);
  *                     contraction range (token operand staged in LDS); 0: contraction split
  *                     over the wavefronts of a workgroup like the other GEMMs
  *   "dense_nt"        16-token tiles a workgroup of the QKV / output projections takes: 1, 2, or 0 = auto
- *                     (2 once the call has more than 64 tokens)
+ *                     (2 from 64 tokens on)
  *   "dense_units"     consecutive 16-row strips a workgroup of the QKV projection takes, 0 = auto
  *   "moe_plain_loads" 1: expert weights with ordinary loads instead of non-temporal ones
  *   "dense_kernel"    QKV / output projections: 0 contraction split over the wavefronts of a workgroup,

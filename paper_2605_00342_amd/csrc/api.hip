@@ -291,8 +291,8 @@ static int verify_layer_impl(evict_ctx* ctx, const evict_layer_weights* w, const
   if (rc) return rc;
   EVICT_MARK(1);
 
-  // token tiles per workgroup in the dense projections: two once the tree spans more than two tiles
-  const int nt_dense = ctx->dense_nt ? ctx->dense_nt : (T > 64 ? 2 : 1);
+  // token tiles per workgroup in the dense projections: two from 64 tokens on (measured)
+  const int nt_dense = ctx->dense_nt ? ctx->dense_nt : (T >= 64 ? 2 : 1);
   const int dense_tiles = (T + 16 * nt_dense - 1) / (16 * nt_dense);
   // QKV: a workgroup takes several consecutive strips, so its token operand is fetched once and its weight loads
   // run ahead across the strips (measured: 2 strips with one token tile, 4 with more; the output projection, with a
