@@ -388,7 +388,7 @@ static int verify_layer_impl(evict_ctx* ctx, const evict_layer_weights* w, const
     a.lds_dma = ctx->moe_lds_dma;
     // (one strip pair per wavefront pays once experts often have several token tiles: measured from 64 tokens on
     // where its chunks line up with the XCDs, see gateup_waves, else from 128)
-    a.wave_strip = ctx->moe_gateup_kernel == 2 ? (T >= (gateup_waves(a) == 6 ? 64 : 128) ? 1 : 0) : ctx->moe_gateup_kernel;
+    a.wave_strip = ctx->moe_gateup_kernel == 2 ? (T >= (gateup_waves(a) != 4 ? 64 : 128) ? 1 : 0) : ctx->moe_gateup_kernel;
     a.chunk_units = ctx->moe_chunk_gateup;
     rc = launch_gemm(m.dtype, EPI_SWIGLU, a, nt_exp, ctx->moe_grid, s);
     if (rc) return rc;

@@ -1220,7 +1220,7 @@ namespace {
 bool wave_gateup_applies(const GemmArgs& a, int nt) {
   if (!(a.grouped && a.nkb % 8 == 0 && a.nkb <= 64 && (a.n_strips / 2) % gateup_waves(a) == 0)) return false;
   // two token tiles per slot: only the variant with 6 wavefronts and 64 contraction blocks is built
-  return nt == 1 || (nt == 2 && a.nkb == 64 && gateup_waves(a) == 6);
+  return nt == 1 || (nt == 2 && a.nkb == 64 && gateup_waves(a) == 6);  // (gateup_waves: 4, 6 or 11)
 }
 template <typename ST>
 int launch_gemm_wave_gateup(const GemmArgs& a, int nt, int grid, hipStream_t s) {
@@ -1233,7 +1233,8 @@ int launch_gemm_wave_gateup(const GemmArgs& a, int nt, int grid, hipStream_t s) 
     return launch_status("gemm_wave_gateup_kernel");
   }
   if (a.lds_dma && a.nkb == 64 && ST::kBytes == 2) {
-    if (ws == 6) hipLaunchKernelGGL((gemm_wave_gateup_kernel<ST, 16, 16, 6, 64, 1, true>), dim3(grid), dim3(6 * 64), lds, s, a);
+    if (ws == 11) hipLaunchKernelGGL((gemm_wave_gateup_kernel<ST, 16, 16, 11, 64, 1, true>), dim3(grid), dim3(11 * 64), lds, s, a);
+    else if (ws == 6) hipLaunchKernelGGL((gemm_wave_gateup_kernel<ST, 16, 16, 6, 64, 1, true>), dim3(grid), dim3(6 * 64), lds, s, a);
     else hipLaunchKernelGGL((gemm_wave_gateup_kernel<ST, 16, 16, 4, 64, 1, true>), dim3(grid), dim3(4 * 64), lds, s, a);
     return launch_status("gemm_wave_gateup_kernel");
   }
@@ -1242,7 +1243,7 @@ int launch_gemm_wave_gateup(const GemmArgs& a, int nt, int grid, hipStream_t s) 
   else if (nb <= 8) hipLaunchKernelGGL((gemm_wave_gateup_kernel<ST, 8, 8, WS_>), dim3(grid), dim3(WS_ * 64), lds, s, a);   \
   else if (a.nkb == 64) hipLaunchKernelGGL((gemm_wave_gateup_kernel<ST, 16, 16, WS_, 64>), dim3(grid), dim3(WS_ * 64), lds, s, a); \
   else hipLaunchKernelGGL((gemm_wave_gateup_kernel<ST, 8, 16, WS_>), dim3(grid), dim3(WS_ * 64), lds, s, a)
-  if (ws == 6) { EVICT_GU_LAUNCH(6); } else { EVICT_GU_LAUNCH(4); }
+  if (ws == 11) { EVICT_GU_LAUNCH(11); } else if (ws == 6) { EVICT_GU_LAUNCH(6); } else { EVICT_GU_LAUNCH(4); }
 #undef EVICT_GU_LAUNCH
   return launch_status("gemm_wave_gateup_kernel");
 }
@@ -1277,7 +1278,11 @@ constexpr size_t kDenseStripLdsMax = 128 * 1024;
 // tile of an expert finds the weights its first tile streamed in that XCD's L2 instead of fetching them again.
 int gateup_waves(const GemmArgs& a) {
   const int pairs = a.n_strips / 2;
-  return (pairs % 6 == 0 && (pairs / 6) % 8 == 0) ? 6 : 4;
+  if (pairs % 6 == 0 && (pairs / 6) % 8 == 0) return 6;
+  // (88 strip pairs: expert width 1408; 11 wavefronts leave 170 VGPRs each, which only the variant without
+  // staging registers fits)
+  if (pairs % 11 == 0 && (pairs / 11) % 8 == 0 && a.lds_dma && a.nkb == 64) return 11;
+  return 4;
 }
 bool dense_strip_applies(const GemmArgs& a, int ntw) {
   return !a.grouped && a.nkb % 16 == 0 && (size_t)ntw * a.nkb * 1024 <= kDenseStripLdsMax;
