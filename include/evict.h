@@ -169,8 +169,11 @@ int evict_lm_head_logits(evict_ctx* ctx, const void* x, const void* g_final, con
 /* Offline cost profiling (Sec. 3.2.3): for every verification length k = 1..Kmax, the mean
  * latency in milliseconds of evict_verify_stack on the first k nodes of one tree (B = 1; any
  * prefix of a topologically numbered tree is a tree), `reps` timed runs after one warm-up,
- * written to cost_host [host] float[Kmax+1] (cost_host[0] = 0). Synchronises the stream. The
- * table is what evict_select_prefix consumes as C(k) (upload it). */
+ * written to cost_host [host] float[Kmax+1] (cost_host[0] = 0). Synchronises the stream.
+ * The table holds the layer stack's share of an iteration only. Sec. 3.2.3 defines C(k) as the
+ * latency of the whole speculative step, and a term that is constant in k (LM head, acceptance,
+ * commit, drafting) moves the maximiser of Eq. 10 towards larger k: the caller adds its measured
+ * per-iteration constant to every entry before uploading the table for evict_select_prefix. */
 int evict_profile_cost(evict_ctx* ctx, const evict_layer_weights* layers, int n_layers, const int32_t* tree_off,
                        const int32_t* parent, int Kmax, const void* const* k_caches, const void* const* v_caches,
                        int64_t kv_head_stride, const int32_t* ctx_len, int max_ctx_host, const void* x_in, void* x_out,
@@ -235,12 +238,15 @@ int evict_accept_path_sampled(evict_ctx* ctx, const int32_t* tree_off, const int
  * maximising S_k / cost[k] (Eq. 10, evaluated as cumulative sums, division, argmax:
  * Sec. 3.2.3). All arithmetic is single IEEE fp32 operations in a fixed order.
  *   node_prob [dev] float[T] in (0, 1]; cost [dev] float[Kmax+1], cost[0] unused, all > 0.
+ *   The ancestor-closure of the prefixes (Sec. 3.2.1) rests on these ranges: a probability outside
+ *   [0, 1] or NaN is clamped (to 1, resp. 0) and a cost entry that is not > 0 is never selected;
+ *   with a context both set a bit of its status word (EVICT_ST_BAD_PROB, EVICT_ST_BAD_COST).
  *   k_star [dev] int32[B]; keep [dev] int32[T]: kept nodes of tree b, ascending tree-local
  *   ids, written at new_tree_off[b]; new_parent [dev] int32[T] parents re-indexed into the
  *   kept set; new_tree_off [dev] int32[B+1]; est_len [dev] float[B] = S_{k*};
  *   order [dev] int32[T] nullable: full ranking per tree at tree_off[b];
  *   prefix_sum [dev] float[T] nullable: S_1..S_N per tree at tree_off[b].
- * Trees up to 1024 nodes. ctx may be NULL. */
+ * Trees up to 1024 nodes. ctx may be NULL (then nothing is flagged). */
 int evict_select_prefix(evict_ctx* ctx, const int32_t* tree_off, const int32_t* parent,
                         const float* node_prob, int B, int T, const float* cost, int Kmax,
                         int32_t* k_star, int32_t* keep, int32_t* new_parent, int32_t* new_tree_off,
@@ -265,7 +271,10 @@ int evict_select_prefix_coverage(evict_ctx* ctx, const int32_t* tree_off, const 
  * rows per head). ctx_len_out[b] = ctx_len[b] + path_len[b]; it must not alias ctx_len (all
  * workgroups read the old length). Rows past the capacity are dropped and the length clamped;
  * that, a length outside [0, capacity] or a path entry outside its tree set the status word of
- * ctx (ctx may be NULL: no status). dtype / Hkv / D describe the rows (EVICT_F32 / EVICT_BF16). */
+ * ctx (ctx may be NULL: no status). The commit needs the whole path: path_stride >= path_len[b].
+ * When evict_accept_path had to truncate `path` (path_len[b] > path_stride) only the path_stride
+ * rows that are there are committed, ctx_len_out advances by that many, and EVICT_ST_PATH_TRUNCATED
+ * is set. dtype / Hkv / D describe the rows (EVICT_F32 / EVICT_BF16). */
 int evict_kv_commit(evict_ctx* ctx, int dtype, int Hkv, int D, const void* k_new, const void* v_new,
                     const int32_t* tree_off, const int32_t* path, int path_stride, const int32_t* path_len,
                     void* k_cache, void* v_cache, int64_t kv_seq_stride, int64_t kv_head_stride,
@@ -322,9 +331,16 @@ int evict_gather_rows(const void* src, void* dst, int row_bytes, const int32_t* 
  * increasing, or a tree exceeds max_nodes. */
 int evict_validate_trees_host(const int32_t* tree_off, const int32_t* parent, int B, int max_nodes);
 
-/* Device-side status word of a context: 0, or a bit set when a kernel met an invalid
- * parent id, expert index, context length or page id (such values are clamped, never dereferenced).
- * Synchronises the stream. */
+/* Device-side status word of a context: 0, or bits set (sticky) when a kernel met an invalid
+ * value, which is clamped or skipped, never dereferenced. Synchronises the stream. */
+#define EVICT_ST_BAD_PARENT 1      /* parent id outside [0, i) */
+#define EVICT_ST_BAD_EXPERT 2      /* expert index outside [0, E) */
+#define EVICT_ST_BAD_CTXLEN 4      /* context length outside [0, max_ctx_host] / [0, capacity], or rows past the capacity */
+#define EVICT_ST_BAD_TREE_SIZE 8   /* a tree of more than EVICT_MAX_TREE_NODES nodes in evict_verify_layer */
+#define EVICT_ST_BAD_PAGE 16       /* block-table entry outside [0, n_pages) */
+#define EVICT_ST_PATH_TRUNCATED 32 /* evict_kv_commit*: path_len exceeds path_stride */
+#define EVICT_ST_BAD_PROB 64       /* evict_select_prefix*: draft probability outside [0, 1] or NaN */
+#define EVICT_ST_BAD_COST 128      /* evict_select_prefix: cost entry not > 0 */
 int evict_device_status(evict_ctx* ctx, int32_t* status_host, void* stream);
 
 /* Launch-shape tuning knobs of a context (defaults are chosen in evict_create):

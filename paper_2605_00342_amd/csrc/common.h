@@ -39,6 +39,7 @@ inline int launch_status(const char* what) {
 }
 
 // status bits written by kernels into the context's device status word
-enum : int { ST_BAD_PARENT = 1, ST_BAD_EXPERT = 2, ST_BAD_CTXLEN = 4, ST_BAD_TREE_SIZE = 8, ST_BAD_PAGE = 16 };
+enum : int { ST_BAD_PARENT = 1, ST_BAD_EXPERT = 2, ST_BAD_CTXLEN = 4, ST_BAD_TREE_SIZE = 8, ST_BAD_PAGE = 16,
+              ST_PATH_TRUNCATED = 32, ST_BAD_PROB = 64, ST_BAD_COST = 128 };
 
 }  // namespace evict

@@ -208,7 +208,7 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(
     long long head_stride, const int32_t* __restrict__ ctx_len, int max_ctx, const int32_t* __restrict__ tree_off,
     const void* __restrict__ k_new, const void* __restrict__ v_new, const uint64_t* __restrict__ anc, int Hq, int Hkv,
     int D, int ctx_splits, int T, float* __restrict__ part_o, float* __restrict__ part_ml, const KvPaging pg,
-    int32_t* __restrict__ status) {
+    int32_t* __restrict__ status, int n_single) {
   extern __shared__ float s_dyn[];
   const int ldk = D + 1;
   float* s_k = s_dyn;                    // [64][D+1]
@@ -218,7 +218,10 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(
   const int split = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int G = Hq / Hkv;
-  const int lo = tree_off[b], n = tree_off[b + 1] - lo;
+  // a single tree spans [0, T) whatever tree_off says (the cost profiler verifies prefixes of a tree that way)
+  const int lo = n_single > 0 ? 0 : tree_off[b];
+  int n = n_single > 0 ? n_single : tree_off[b + 1] - lo;
+  n = n > EVICT_MAX_TREE_NODES ? EVICT_MAX_TREE_NODES : n;
   int L = ctx_len[b];
   L = L < 0 ? 0 : (L > max_ctx ? max_ctx : L);
   const bool tree_part = split >= ctx_splits;
@@ -1467,7 +1470,7 @@ int launch_attention(const evict_ctx* c, const void* kc, const void* vc, long lo
     nsplits = ctx_splits + EVICT_MAX_TREE_NODES / keys;
     hipLaunchKernelGGL(attn_partial_kernel<F32>, dim3(nsplits, m.Hkv, B), dim3(256), attn_partial_lds_bytes(m.D), s, c->q,
                        kc, vc, seq_stride, head_stride, ctx_len, max_ctx_host, tree_off, k_new, v_new, c->anc, m.Hq,
-                       m.Hkv, m.D, ctx_splits, T, c->part_o, c->part_ml, c->paging, c->status);
+                       m.Hkv, m.D, ctx_splits, T, c->part_o, c->part_ml, c->paging, c->status, B == 1 ? T : 0);
   }
   int rc = launch_status("attention partial kernel");
   if (rc) return rc;

@@ -62,7 +62,7 @@ __global__ __launch_bounds__(kSelThreads) void select_prefix_kernel(
     const int32_t* __restrict__ tree_off, const int32_t* __restrict__ parent, const float* __restrict__ prob,
     const float* __restrict__ cost, int kmax, int32_t* __restrict__ k_star, float* __restrict__ est_len,
     int32_t* __restrict__ order_out, float* __restrict__ psum_out, int32_t* rank_ws, int single, int32_t* keep,
-    int32_t* new_parent, int32_t* __restrict__ new_tree_off, int n_single, float rho) {
+    int32_t* new_parent, int32_t* __restrict__ new_tree_off, int n_single, float rho, int32_t* __restrict__ status) {
   __shared__ int s_par[kMaxSel];
   __shared__ __attribute__((aligned(16))) float s_score[kMaxSel];
   __shared__ float s_sorted[kMaxSel];
@@ -83,14 +83,22 @@ __global__ __launch_bounds__(kSelThreads) void select_prefix_kernel(
   n = n < 1 ? 1 : (n > kMaxSel ? kMaxSel : n);
 
   if (tid == 0) s_maxdep = 0;
+  int bad_in = 0;
   for (int i = tid; i < n; i += nthreads) {
     int p = parent[lo + i];
     if (i == 0) p = -1;
-    else if (p < 0 || p >= i) p = 0;  // invalid ids are clamped (the host check rejects them)
+    else if (p < 0 || p >= i) { p = 0; bad_in |= ST_BAD_PARENT; }  // invalid ids are clamped and flagged
     s_par[i] = p;
-    s_prob[i] = prob[lo + i];                      // all global reads issued together, up front
-    s_cost[i] = (cost && i < kmax) ? cost[i + 1] : 1.0f;  // s_cost[i] = C(i + 1)
+    // all global reads issued together, up front. A probability outside [0, 1] (or NaN) could rank a child
+    // above its parent and break the ancestor-closure of the prefixes (Sec. 3.2.1): it is clamped and flagged.
+    float q = prob[lo + i];
+    if (i > 0 && !(q >= 0.0f && q <= 1.0f)) { q = q > 1.0f ? 1.0f : 0.0f; bad_in |= ST_BAD_PROB; }
+    s_prob[i] = q;
+    float c = (cost && i < kmax) ? cost[i + 1] : 1.0f;  // s_cost[i] = C(i + 1)
+    if (!(c > 0.0f)) { c = 0.0f; bad_in |= ST_BAD_COST; }  // (never selected below)
+    s_cost[i] = c;
   }
+  if (bad_in && status) atomicOr(status, bad_in);
   __syncthreads();
   // depth of every node (walk to the root; parent ids strictly decrease)
   int mydep_max = 0;
@@ -161,7 +169,7 @@ __global__ __launch_bounds__(kSelThreads) void select_prefix_kernel(
       // smallest prefix reaching the coverage.
       float u;
       if (rho >= 0.0f) u = __fdiv_rn(S, s_sorted[n - 1]) >= rho ? 1.0f : 0.0f;
-      else u = __fdiv_rn(S, s_cost[i]);
+      else u = s_cost[i] > 0.0f ? __fdiv_rn(S, s_cost[i]) : -1.0f;  // (a flagged, unusable cost entry is never the maximum)
       if (u > bv || (u == bv && i < bi)) { bv = u; bi = i; }
     }
   }
@@ -201,17 +209,23 @@ __global__ __launch_bounds__(64) void select_prefix_wave_kernel(
     const int32_t* __restrict__ parent, const float* __restrict__ prob, const float* __restrict__ cost, int kmax, int n,
     float rho, int32_t* __restrict__ k_star, float* __restrict__ est_len, int32_t* __restrict__ order_out,
     float* __restrict__ psum_out, int32_t* __restrict__ keep, int32_t* __restrict__ new_parent,
-    int32_t* __restrict__ new_tree_off) {
+    int32_t* __restrict__ new_tree_off, int32_t* __restrict__ status) {
   const int lane = threadIdx.x;
   const bool live = lane < n;
   int p = -1;
   float q = 0.0f, c = 1.0f;
   if (live) {
+    int bad_in = 0;
     p = parent[lane];
     q = prob[lane];
     if (cost && lane < kmax) c = cost[lane + 1];  // C(lane + 1)
     if (lane == 0) p = -1;
-    else if (p < 0 || p >= lane) p = 0;  // invalid ids are clamped (the host check rejects them)
+    else if (p < 0 || p >= lane) { p = 0; bad_in |= ST_BAD_PARENT; }  // invalid ids are clamped and flagged
+    // a probability outside [0, 1] (or NaN) could rank a child above its parent and break the ancestor-closure
+    // of the prefixes (Sec. 3.2.1): clamped and flagged; an unusable cost entry is never selected
+    if (lane > 0 && !(q >= 0.0f && q <= 1.0f)) { q = q > 1.0f ? 1.0f : 0.0f; bad_in |= ST_BAD_PROB; }
+    if (!(c > 0.0f)) { c = 0.0f; bad_in |= ST_BAD_COST; }
+    if (bad_in && status) atomicOr(status, bad_in);
   }
   // depth by walking up in lock step
   int dep = 0, a = p;
@@ -254,7 +268,7 @@ __global__ __launch_bounds__(64) void select_prefix_wave_kernel(
   float bv = -1.0f;
   int bi = 0x7fffffff;
   if (lane < kk) {
-    bv = rho >= 0.0f ? (__fdiv_rn(S, total) >= rho ? 1.0f : 0.0f) : __fdiv_rn(S, c);
+    bv = rho >= 0.0f ? (__fdiv_rn(S, total) >= rho ? 1.0f : 0.0f) : (c > 0.0f ? __fdiv_rn(S, c) : -1.0f);
     bi = lane;
   }
 #pragma unroll
@@ -628,7 +642,10 @@ __global__ __launch_bounds__(256) void kv_commit_kernel(
   uint32_t* __restrict__ k_cache = lp.k_cache[layer];
   uint32_t* __restrict__ v_cache = lp.v_cache[layer];
   int len = path_len[b];
-  len = len < 0 ? 0 : (len > path_stride ? path_stride : len);
+  // an accepted path longer than the rows `path` holds (evict_accept_path truncates it) cannot be committed in
+  // full: the rows that are there are committed, the length advances by that many, and the call is flagged
+  const bool trunc = len > path_stride;
+  len = len < 0 ? 0 : (trunc ? path_stride : len);
   int L = ctx_len[b];
   const bool badL = L < 0 || L > capacity;
   L = L < 0 ? 0 : (L > capacity ? capacity : L);
@@ -636,6 +653,7 @@ __global__ __launch_bounds__(256) void kv_commit_kernel(
   if (j == 0 && layer == 0 && threadIdx.x == 0) {
     ctx_len_out[b] = L + (len < room ? len : room);
     if (status && (badL || len > room)) atomicOr(status, ST_BAD_CTXLEN);
+    if (status && trunc) atomicOr(status, ST_PATH_TRUNCATED);
   }
   if (j >= len || j >= room) return;
   const int n = tree_off[b + 1] - tree_off[b];
@@ -705,7 +723,7 @@ int evict_validate_trees_host(const int32_t* tree_off, const int32_t* parent, in
   return EVICT_OK;
 }
 
-static int select_prefix_impl(const char* who, const int32_t* tree_off, const int32_t* parent, const float* node_prob, int B,
+static int select_prefix_impl(const char* who, evict_ctx* ctx, const int32_t* tree_off, const int32_t* parent, const float* node_prob, int B,
                               int T, const float* cost, float rho, int Kmax, int32_t* k_star, int32_t* keep,
                               int32_t* new_parent, int32_t* new_tree_off, float* est_len, int32_t* order,
                               float* prefix_sum, void* stream) {
@@ -716,16 +734,17 @@ static int select_prefix_impl(const char* who, const int32_t* tree_off, const in
   EVICT_REQUIRE(T <= B * (int64_t)EVICT_MAX_SELECT_NODES, EVICT_E_UNSUPPORTED, "%s: more than %d nodes per tree", who,
                 EVICT_MAX_SELECT_NODES);
   hipStream_t s = (hipStream_t)stream;
+  int32_t* status = ctx ? ctx->status : nullptr;
   const int single = B == 1;
   if (B == 1 && T <= 64) {  // one small tree: the single-wavefront register kernel
     hipLaunchKernelGGL(select_prefix_wave_kernel, dim3(1), dim3(64), 0, s, parent, node_prob, cost, Kmax, T, rho, k_star,
-                       est_len, order, prefix_sum, keep, new_parent, new_tree_off);
+                       est_len, order, prefix_sum, keep, new_parent, new_tree_off, status);
     return launch_status("select_prefix_wave_kernel");
   }
   const int sel_threads = kSelThreads;
   hipLaunchKernelGGL(select_prefix_kernel, dim3(B), dim3(sel_threads), 0, s, tree_off, parent, node_prob, cost, Kmax,
                      k_star, est_len, order, prefix_sum, new_parent /* rank workspace */, single, keep, new_parent,
-                     new_tree_off, single ? T : 0, rho);
+                     new_tree_off, single ? T : 0, rho, status);
   int rc = launch_status("select_prefix_kernel");
   if (rc) return rc;
   if (!single) {
@@ -736,19 +755,19 @@ static int select_prefix_impl(const char* who, const int32_t* tree_off, const in
   return rc;
 }
 
-int evict_select_prefix(evict_ctx*, const int32_t* tree_off, const int32_t* parent, const float* node_prob, int B,
+int evict_select_prefix(evict_ctx* ctx, const int32_t* tree_off, const int32_t* parent, const float* node_prob, int B,
                         int T, const float* cost, int Kmax, int32_t* k_star, int32_t* keep, int32_t* new_parent,
                         int32_t* new_tree_off, float* est_len, int32_t* order, float* prefix_sum, void* stream) {
   EVICT_REQUIRE(cost, EVICT_E_INVALID, "evict_select_prefix: null cost table");
-  return select_prefix_impl("evict_select_prefix", tree_off, parent, node_prob, B, T, cost, -1.0f, Kmax, k_star, keep,
+  return select_prefix_impl("evict_select_prefix", ctx, tree_off, parent, node_prob, B, T, cost, -1.0f, Kmax, k_star, keep,
                             new_parent, new_tree_off, est_len, order, prefix_sum, stream);
 }
 
-int evict_select_prefix_coverage(evict_ctx*, const int32_t* tree_off, const int32_t* parent, const float* node_prob, int B,
+int evict_select_prefix_coverage(evict_ctx* ctx, const int32_t* tree_off, const int32_t* parent, const float* node_prob, int B,
                                  int T, float rho, int Kmax, int32_t* k_star, int32_t* keep, int32_t* new_parent,
                                  int32_t* new_tree_off, float* est_len, int32_t* order, float* prefix_sum, void* stream) {
   EVICT_REQUIRE(rho >= 0.0f && rho <= 1.0f, EVICT_E_INVALID, "evict_select_prefix_coverage: rho=%g outside [0, 1]", (double)rho);
-  return select_prefix_impl("evict_select_prefix_coverage", tree_off, parent, node_prob, B, T, nullptr, rho, Kmax, k_star,
+  return select_prefix_impl("evict_select_prefix_coverage", ctx, tree_off, parent, node_prob, B, T, nullptr, rho, Kmax, k_star,
                             keep, new_parent, new_tree_off, est_len, order, prefix_sum, stream);
 }
 

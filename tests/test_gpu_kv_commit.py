@@ -140,6 +140,20 @@ def test_commit_capacity_and_bad_entries():
         assert ev.evict_device_status(layer.ctx) != 0      # and reported
         with pytest.raises(ev.EvictError):                 # the new length must not alias the old one
             ev.evict_kv_commit(*args, ctx_len, 64, ctx_len, 1)
+        # a path that evict_accept_path had to truncate (path_len > path_stride): the rows that are there are
+        # committed, the length advances by that many, and the call is flagged
+        layer2 = harness.DeviceLayer(cfg, case["W"], max_tokens=8, max_batch=1, max_ctx=64)
+        cache2 = Cache(case, 64)
+        short = harness.dev_i32(np.array([[0, 1, 2]], np.int32))
+        ctx50 = harness.dev_i32(np.array([50], np.int32))
+        ev.evict_kv_commit(layer2.ctx, ev.EVICT_F32, cfg.Hkv, cfg.D, kn, vn, harness.dev_i32(case["tree_off"]), short, 3,
+                           harness.dev_i32(np.array([5], np.int32)), cache2.k, cache2.v, cache2.seq_stride, cache2.head_stride,
+                           ctx50, 64, out_len, 1)
+        torch.cuda.synchronize()
+        assert int(out_len[0]) == 53
+        assert torch.equal(cache2.k[0, :, 50:53], kn[:3].transpose(0, 1))
+        assert ev.evict_device_status(layer2.ctx) == 32
+        layer2.close()
         with pytest.raises(ev.EvictError):                 # strides too small for the capacity
             ev.evict_kv_commit(*args[:12], cache.seq_stride, 10, ctx_len, 64, out_len, 1)
     finally:

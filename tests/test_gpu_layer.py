@@ -23,6 +23,16 @@ def rel_l2(a, b):
     return float(np.linalg.norm(np.asarray(a, np.float64) - b) / max(np.linalg.norm(b), 1e-30))
 
 
+def row_rel_l2_max(a, b):
+    """Largest relative L2 error of any single token row: one wrong token in a large call cannot hide in it."""
+    a = np.asarray(a, np.float64).reshape(len(a), -1)
+    b = np.asarray(b, np.float64).reshape(len(b), -1)
+    return float(np.max(np.linalg.norm(a - b, axis=1) / np.maximum(np.linalg.norm(b, axis=1), 1e-30)))
+
+
+ROW_FACTOR = 3.0  # per-row bound = ROW_FACTOR x the whole-tensor tolerance
+
+
 def run_case(case, max_tokens=None, tune=None):
     cfg = case["cfg"]
     T = int(case["tree_off"][-1])
@@ -50,6 +60,10 @@ def check_against_oracle(case, got):
     assert rel_l2(got["attn_out"], ref["o"]) < tol, "attention output"
     assert rel_l2(got["h"], ref["h"]) < tol, "h"
     assert rel_l2(got["h_norm"], ref["h_norm"]) < tol, "h_norm"
+    # no single token row may be far off either
+    for name, g_, r_ in (("q", got["q"], ref["q"]), ("attention output", got["attn_out"], ref["o"]), ("h", got["h"], ref["h"])):
+        worst = row_rel_l2_max(g_, r_)
+        assert worst < ROW_FACTOR * tol, f"{name}: worst token row {worst}"
     # --- router, stage-wise on the GPU's own normalised hidden state: bit-exact indices
     idx, w, logits = orc.router_topk(got["h_norm"], case["W"]["wg"], cfg.k, cfg.router_norm)
     np.testing.assert_allclose(got["router_logits"], logits, rtol=0, atol=2e-5)
@@ -79,6 +93,8 @@ def check_against_oracle(case, got):
     out_stage = orc.moe_combine(got["h"], y, got["topk_w"], shared)
     out_stored = orc.handoff(out_stage, cfg.dtype)     # the layer output is stored in the storage type
     assert rel_l2(got["out"], out_stored) < (1e-3 if cfg.dtype == "bf16" else 1e-5), "MoE stage"
+    worst = row_rel_l2_max(got["out"], out_stored)
+    assert worst < ROW_FACTOR * (1e-3 if cfg.dtype == "bf16" else 1e-5), f"MoE stage: worst token row {worst}"
     # error measured against the size of the MoE contribution itself (a wrong expert sum gives ~1)
     moe_part = np.linalg.norm(got["out"] - out_stored) / np.linalg.norm(out_stage - np.asarray(got["h"], np.float64))
     assert moe_part < (5e-2 if cfg.dtype == "bf16" else 1e-4), f"MoE contribution {moe_part}"
@@ -86,6 +102,11 @@ def check_against_oracle(case, got):
     flips = int((np.sort(got["topk_idx"], -1) != np.sort(ref["topk_idx"], -1)).any(-1).sum())
     err = rel_l2(got["out"], ref["out"])
     assert err < tol, f"out rel-L2 {err} (routing flips vs end-to-end oracle: {flips})"
+    # per token row, on the rows whose routing agrees with the end-to-end oracle's (a flipped near-tie swaps an expert)
+    same = ~(np.sort(got["topk_idx"], -1) != np.sort(ref["topk_idx"], -1)).any(-1)
+    if same.any():
+        worst = row_rel_l2_max(got["out"][same], ref["out"][same])
+        assert worst < ROW_FACTOR * tol, f"out: worst token row {worst}"
     return {"err": err, "flips": flips, "excluded": excluded, "union": got["union_count"]}
 
 

@@ -201,3 +201,48 @@ def test_select_prefix_coverage_bit_exact(sizes, kind, seed, rho, kdiv):
     with pytest.raises(ev.EvictError):
         ev.evict_select_prefix_coverage(None, _i32(off), _i32(par), _f32(q), B, T, 1.5, kmax, d["k_star"], d["keep"],
                                         d["new_parent"], d["new_off"], d["est"])
+
+
+@pytest.mark.parametrize("n", [20, 100])
+def test_select_prefix_flags_out_of_range_inputs_and_keeps_prefixes_closed(n):
+    """A draft probability above 1 (or NaN) could rank a child above its parent; a cost entry that is not
+    positive makes S_k / C(k) meaningless. Both are clamped / skipped and flagged in the context's status word,
+    the result is the oracle's on the clamped inputs, and every kept node's parent is kept (Sec. 3.2.1)."""
+    cfg = synth.CONFIGS["tiny"]
+    from paper_2605_00342_amd import harness
+    ctx = ev.evict_create(harness.model_desc(cfg), 8, 1, 16)
+    off, par, pars, q, qs = _trees([n], 11, "random")
+    kmax = n
+    cost = synth.cost_linear_in_union(kmax, 128, 8).astype(np.float32)
+    q_bad = q.copy()
+    q_bad[3] = 1.75
+    q_bad[7] = np.nan
+    q_bad[9] = -0.25
+    cost_bad = cost.copy()
+    cost_bad[2] = 0.0
+    cost_bad[5] = np.nan
+    B, T = 1, n
+    d = dict(k_star=torch.zeros(B, dtype=torch.int32, device=DEV), keep=torch.full((T,), -7, dtype=torch.int32, device=DEV),
+             new_parent=torch.full((T,), -7, dtype=torch.int32, device=DEV), new_off=torch.zeros(B + 1, dtype=torch.int32, device=DEV),
+             est=torch.zeros(B, device=DEV))
+    # valid inputs leave the status word alone
+    ev.evict_select_prefix(ctx, _i32(off), _i32(par), _f32(q), B, T, _f32(cost), kmax, d["k_star"], d["keep"], d["new_parent"],
+                           d["new_off"], d["est"])
+    assert ev.evict_device_status(ctx) == 0
+    ev.evict_select_prefix(ctx, _i32(off), _i32(par), _f32(q_bad), B, T, _f32(cost_bad), kmax, d["k_star"], d["keep"],
+                           d["new_parent"], d["new_off"], d["est"])
+    st = ev.evict_device_status(ctx)
+    assert st & 64 and st & 128, st
+    q_fix = q_bad.copy()
+    q_fix[3], q_fix[7], q_fix[9] = 1.0, 0.0, 0.0
+    # the oracle on the clamped probabilities, with the unusable cost entries made so large they cannot win
+    cost_fix = cost_bad.copy()
+    cost_fix[2] = cost_fix[5] = np.float32(3e38)
+    ref = orc.select_prefix(pars[0], q_fix, cost_fix, kmax)
+    ks = int(d["k_star"][0])
+    assert ks == ref["k_star"] and ks not in (2, 5)
+    keep = d["keep"].cpu().numpy()[:ks]
+    npar = d["new_parent"].cpu().numpy()[:ks]
+    assert np.array_equal(keep, ref["keep"]) and np.array_equal(npar, ref["new_parent"])
+    assert npar[0] == -1 and np.all(npar[1:] >= 0)          # one root: every kept node's parent is kept
+    ev.evict_destroy(ctx)

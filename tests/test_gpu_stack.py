@@ -291,3 +291,37 @@ def test_profile_reports_mean_union_and_feeds_the_cost_surface():
     assert ksel.item() == orc.select_prefix(case["parent"], case["q"], table, n)["k_star"]
     assert ev.evict_device_status(st.ctx) == 0
     st.close()
+
+
+def test_profile_prefixes_with_fp32_storage_match_oracle_routing():
+    """The cost profiler verifies the first k nodes of a tree as a tree of their own (B = 1, T = k) while
+    tree_off still describes the whole tree: with fp32 storage too, every prefix length must route as the
+    oracle's evaluation of that prefix does (mean union per length), and a prefix call must equal the
+    oracle's output for that prefix."""
+    n, L, nl = 12, 48, 2
+    case, Ws, Ks, Vs = make_stack("tiny", nl, n, L, 72)
+    cfg = case["cfg"]
+    st = DeviceStack(case, Ws, Ks, Vs)
+    dc = st.dc
+    refs = [0.0]
+    for k in range(1, n + 1):
+        r = oracle_stack(case, Ws, Ks, Vs, tree_off=np.array([0, k], np.int32), parent=case["parent"][:k], x=case["x"][:k])
+        refs.append(float(np.mean([q["union_count"] for q in r])))
+    cost, umean = ev.evict_profile_cost_union(st.ctx, [l.weights for l in st.layers], dc.tree_off, dc.parent, n,
+                                              [c.k_cache for c in st.cases], [c.v_cache for c in st.cases], dc.head_stride,
+                                              dc.ctx_len, dc.max_ctx, dc.x, dc.out, [c.k_new for c in st.cases],
+                                              [c.v_new for c in st.cases], 2)
+    assert umean[1] == cfg.k
+    assert np.max(np.abs(np.asarray(umean) - refs)) <= 1.0 / nl + 1e-6, (umean, refs)
+    # one prefix call with the full tree's offsets still in tree_off, twice: same bits, oracle's values
+    for k in (5, 9):
+        outs = []
+        for _ in range(2):
+            st.run(T=k)
+            torch.cuda.synchronize()
+            outs.append(dc.out[:k].clone())
+        assert torch.equal(outs[0], outs[1])
+        ref = oracle_stack(case, Ws, Ks, Vs, tree_off=np.array([0, k], np.int32), parent=case["parent"][:k], x=case["x"][:k])
+        assert rel_l2(harness.to_host(outs[0]), ref[-1]["out"]) < TOL["f32"]
+    assert ev.evict_device_status(st.ctx) == 0
+    st.close()
