@@ -231,6 +231,22 @@ int evict_accept_path_sampled(evict_ctx* ctx, const int32_t* tree_off, const int
                               const float* u_node, const float* u_bonus, int B, int T, int32_t* path,
                               int path_stride, int32_t* path_len, int32_t* bonus_tok, void* stream);
 
+/* For callers that cannot allocate device memory (code under HIP-graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): evict_accept_path_sampled without a context's scratch.
+ * The per-node softmax statistics (two floats per node) live in a static device array inside the
+ * library, sized for EVICT_NOALLOC_MAX_NODES nodes per call (32 KiB, held on every GPU the library
+ * runs on until the process ends); its device address is looked up on the first call on a device.
+ * The call itself allocates and frees nothing. Arguments, outputs and results are exactly those of
+ * evict_accept_path_sampled; ctx may be NULL (then invalid ids are not reported). T above
+ * EVICT_NOALLOC_MAX_NODES returns EVICT_E_UNSUPPORTED. All calls on one GPU share the array:
+ * calls that overlap on that GPU (different streams) race; calls ordered on one stream do not.
+ * Nothing in the array has to start at zero (the rows a call reads it has written before). */
+#define EVICT_NOALLOC_MAX_NODES 4096
+int evict_accept_path_sampled_noalloc(evict_ctx* ctx, const int32_t* tree_off, const int32_t* parent,
+                                      const int32_t* draft_tok, const float* logits, int vocab, float temperature,
+                                      const float* u_node, const float* u_bonus, int B, int T, int32_t* path,
+                                      int path_stride, int32_t* path_len, int32_t* bonus_tok, void* stream);
+
 /* EVICT prefix selection, entirely on the device (Sec. 3.1-3.2): node score = product of
  * draft probabilities along the root path (Eq. 7, root counted as 1), nodes ranked by score
  * (Sec. 3.2.1; equal scores: lower index first, which keeps every prefix ancestor-closed),

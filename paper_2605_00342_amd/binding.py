@@ -18,7 +18,8 @@ __all__ = [
     "evict_stage_timing", "evict_stage_times", "evict_probe_read", "evict_probe_copy", "evict_tune", "evict_verify_stack", "evict_lm_head_argmax",
     "evict_profile_cost", "evict_graph_begin", "evict_graph_end", "evict_graph_launch", "evict_graph_destroy",
     "evict_lm_head_logits", "evict_accept_path_sampled", "evict_kv_commit", "evict_select_prefix_coverage", "evict_kv_commit_stack",
-    "evict_profile_cost_union", "evict_verify_stack_paged", "evict_kv_commit_stack_paged", "STAGES", "EXPORTS",
+    "evict_profile_cost_union", "evict_verify_stack_paged", "evict_kv_commit_stack_paged", "evict_accept_path_sampled_noalloc",
+    "STAGES", "EXPORTS",
 ]
 
 EVICT_F32, EVICT_BF16 = 0, 1
@@ -32,7 +33,7 @@ EXPORTS = [
     "evict_stage_timing", "evict_stage_times", "evict_probe_read", "evict_probe_copy", "evict_tune", "evict_verify_stack", "evict_lm_head_argmax",
     "evict_profile_cost", "evict_graph_begin", "evict_graph_end", "evict_graph_launch", "evict_graph_destroy",
     "evict_lm_head_logits", "evict_accept_path_sampled", "evict_kv_commit", "evict_select_prefix_coverage", "evict_kv_commit_stack",
-    "evict_profile_cost_union", "evict_verify_stack_paged", "evict_kv_commit_stack_paged",
+    "evict_profile_cost_union", "evict_verify_stack_paged", "evict_kv_commit_stack_paged", "evict_accept_path_sampled_noalloc",
 ]
 STAGES = ["prep", "qkv", "attention", "oproj", "router", "union", "gateup", "down", "shared", "combine"]
 
@@ -110,6 +111,7 @@ def load():
     lib.evict_stage_times.argtypes = [vp, C.POINTER(C.c_float)]
     lib.evict_lm_head_logits.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp]
     lib.evict_accept_path_sampled.argtypes = [vp, vp, vp, vp, vp, i32, C.c_float, vp, vp, i32, i32, vp, i32, vp, vp, vp]
+    lib.evict_accept_path_sampled_noalloc.argtypes = lib.evict_accept_path_sampled.argtypes
     lib.evict_kv_commit.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, i32, vp, vp, vp, i64, i64, vp, i32, vp, i32, vp]
     lib.evict_kv_commit_stack.argtypes = [vp, i32, i32, i32, C.POINTER(vp), C.POINTER(vp), i32, vp, vp, i32, vp, C.POINTER(vp),
                                           C.POINTER(vp), i64, i64, vp, i32, vp, i32, vp]
@@ -251,6 +253,14 @@ def evict_accept_path_sampled(ctx, tree_off, parent, draft_tok, logits, vocab, t
     _check(load().evict_accept_path_sampled(ctx, _p(tree_off), _p(parent), _p(draft_tok), _p(logits), vocab,
                                             float(temperature), _p(u_node), _p(u_bonus), B, T, _p(path), path_stride,
                                             _p(path_len), _p(bonus_tok), _stream()))
+
+
+def evict_accept_path_sampled_noalloc(ctx, tree_off, parent, draft_tok, logits, vocab, temperature, u_node, u_bonus, B, T,
+                                      path, path_stride, path_len, bonus_tok) -> None:
+    """evict_accept_path_sampled on the library's static scratch (no allocation, ctx may be None)."""
+    _check(load().evict_accept_path_sampled_noalloc(ctx, _p(tree_off), _p(parent), _p(draft_tok), _p(logits), vocab,
+                                                    float(temperature), _p(u_node), _p(u_bonus), B, T, _p(path), path_stride,
+                                                    _p(path_len), _p(bonus_tok), _stream()))
 
 
 def evict_kv_commit(ctx, dtype, Hkv, D, k_new, v_new, tree_off, path, path_stride, path_len, k_cache, v_cache,

@@ -4,6 +4,8 @@
 #include <stdarg.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "ctx.h"
 #include "union_device.h"
 
@@ -701,6 +703,34 @@ int union_mask_plan(int T, int k, int E, size_t* lds_bytes) {
 
 using namespace evict;
 
+// ---- scratch of the allocation-free entry point (evict_accept_path_sampled_noalloc) ----
+// Per-node softmax statistics [EVICT_NOALLOC_MAX_NODES][2] floats. Every GPU the library runs on holds its
+// own copy of this array until the process ends. In host code the array's name is only a stand-in: the
+// device address is looked up once per device and kept; kernels and copies use that pointer.
+static __device__ __align__(256) float scratch[EVICT_NOALLOC_MAX_NODES * 2];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+float* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device (looked up on the first call on that device).
+int scratch_address(float** out) {
+  int dev = -1;
+  EVICT_HIP_CHECK(hipGetDevice(&dev));
+  EVICT_REQUIRE(dev >= 0 && dev < kMaxDevices, EVICT_E_UNSUPPORTED, "device ordinal %d outside [0, %d)", dev, kMaxDevices);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    EVICT_HIP_CHECK(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    EVICT_REQUIRE(p != nullptr, EVICT_E_HIP, "hipGetSymbolAddress returned a null address for the static scratch");
+    g_scratch_ptr[dev] = static_cast<float*>(p);
+  }
+  *out = g_scratch_ptr[dev];
+  return EVICT_OK;
+}
+}  // namespace
+
 extern "C" {
 
 int evict_version(void) { return 1; }
@@ -845,6 +875,35 @@ int evict_accept_path_sampled(evict_ctx* ctx, const int32_t* tree_off, const int
   if (rc) return rc;
   hipLaunchKernelGGL(accept_sampled_kernel, dim3(B), dim3(kSampThreads), 0, s, tree_off, parent, draft_tok, logits, vocab,
                      inv_temp, ctx->samp_stats, u_node, u_bonus, path, path_stride, path_len, bonus_tok, ctx->status);
+  return launch_status("accept_sampled_kernel");
+}
+
+int evict_accept_path_sampled_noalloc(evict_ctx* ctx, const int32_t* tree_off, const int32_t* parent, const int32_t* draft_tok,
+                                      const float* logits, int vocab, float temperature, const float* u_node,
+                                      const float* u_bonus, int B, int T, int32_t* path, int path_stride, int32_t* path_len,
+                                      int32_t* bonus_tok, void* stream) {
+  EVICT_REQUIRE(tree_off && parent && draft_tok && logits && u_node && u_bonus && path && path_len && bonus_tok,
+                EVICT_E_INVALID, "evict_accept_path_sampled_noalloc: null pointer argument");
+  EVICT_REQUIRE(B >= 1 && B <= 65535, EVICT_E_INVALID, "evict_accept_path_sampled_noalloc: B=%d outside [1, 65535]", B);
+  EVICT_REQUIRE(T >= B, EVICT_E_INVALID, "evict_accept_path_sampled_noalloc: T=%d is smaller than B=%d", T, B);
+  EVICT_REQUIRE(T <= EVICT_NOALLOC_MAX_NODES, EVICT_E_UNSUPPORTED,
+                "evict_accept_path_sampled_noalloc: T=%d exceeds the static scratch of %d nodes (use evict_accept_path_sampled)", T,
+                EVICT_NOALLOC_MAX_NODES);
+  EVICT_REQUIRE(vocab >= 1, EVICT_E_INVALID, "evict_accept_path_sampled_noalloc: vocab must be >= 1");
+  EVICT_REQUIRE(temperature > 0.0f && temperature == temperature, EVICT_E_INVALID,
+                "evict_accept_path_sampled_noalloc: temperature must be > 0 (use evict_accept_path for the greedy rule)");
+  EVICT_REQUIRE(path_stride >= 1, EVICT_E_INVALID, "evict_accept_path_sampled_noalloc: path_stride must be >= 1");
+  float* stats = nullptr;
+  int rc = scratch_address(&stats);
+  if (rc) return rc;
+  const float inv_temp = 1.0f / temperature;
+  hipStream_t s = (hipStream_t)stream;
+  // (rows [0, T) of the statistics are written in full before they are read: nothing has to start at zero)
+  hipLaunchKernelGGL(softmax_stats_kernel, dim3(T), dim3(kSampThreads), 0, s, logits, vocab, inv_temp, stats);
+  rc = launch_status("softmax_stats_kernel");
+  if (rc) return rc;
+  hipLaunchKernelGGL(accept_sampled_kernel, dim3(B), dim3(kSampThreads), 0, s, tree_off, parent, draft_tok, logits, vocab,
+                     inv_temp, stats, u_node, u_bonus, path, path_stride, path_len, bonus_tok, ctx ? ctx->status : nullptr);
   return launch_status("accept_sampled_kernel");
 }
 
