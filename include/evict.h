@@ -376,7 +376,9 @@ int evict_device_status(evict_ctx* ctx, int32_t* status_host, void* stream);
  *   "dense_nt"        16-token tiles a workgroup of the QKV / output projections takes: 1, 2, or 0 = auto
  *                     (2 from 64 tokens on)
  *   "dense_units"     consecutive 16-row strips a workgroup of the QKV projection takes, 0 = auto
- *   "moe_plain_loads" 1: expert weights with ordinary loads instead of non-temporal ones
+ *   "moe_nt_loads"    expert weights fetched with non-temporal loads: 1, 0 (ordinary loads), 2 = auto;
+ *   "dense_nt_loads"  the same for the QKV / output projections and the LM head (auto: when every strip is read
+ *                     by a single workgroup)
  *   "dense_kernel"    QKV / output projections: 0 contraction split over the wavefronts of a workgroup,
  *                     1 one strip per wavefront with the token operand in LDS (where its shape conditions
  *                     hold), 2 = auto (the latter from 128 or 256 tokens on); "dense_ntw" its token tiles

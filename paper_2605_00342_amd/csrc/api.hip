@@ -127,7 +127,8 @@ int evict_create(evict_ctx** out, const evict_model_desc* m, int max_tokens, int
   c.moe_prefetch = 1;
   c.moe_down_kernel = 1;
   c.moe_gateup_kernel = 2;
-  c.moe_plain_loads = 0;
+  c.moe_nt_loads = 2;
+  c.dense_nt_loads = 2;
   c.dense_nt = 0;
   c.attn_target_wgs = 512;
   c.attn_waves = 0;
@@ -299,6 +300,8 @@ static int verify_layer_impl(evict_ctx* ctx, const evict_layer_weights* w, const
   // third of the strips and twice the contraction length, is better left at one)
   const int qkv_units = ctx->dense_units ? ctx->dense_units : (dense_tiles >= 2 ? 4 : 2);
   auto dense_grid = [&](int units, int du) { return (((units + du - 1) / du + 7) / 8) * 8 * dense_tiles; };
+  // projection weights fetched with non-temporal loads when every strip is read by a single workgroup (one token tile)
+  const int dense_ntl = ctx->dense_nt_loads == 2 ? (dense_tiles == 1 ? 1 : 0) : ctx->dense_nt_loads;
   // With many token tiles the projections are ordinary dense GEMMs: one strip per wavefront with the token
   // operand of the workgroup in LDS (gemm_dense_strip_kernel) instead of the contraction split. Measured:
   // pays from 128 tokens on with two token tiles per workgroup (the operand of two tiles must fit in LDS), from
@@ -324,6 +327,7 @@ static int verify_layer_impl(evict_ctx* ctx, const evict_layer_weights* w, const
     a.Hq = m.Hq; a.Hkv = m.Hkv; a.D = m.D;
     a.dense_tiles = dense_tiles;
     a.dense_units = qkv_units;
+    a.nt_loads = dense_ntl;
     int ntw;
     rc = dense_strip_shape(a, &ntw) ? launch_gemm_dense_strip(m.dtype, EPI_QKV, a, ntw, s)
                                          : launch_gemm(m.dtype, EPI_QKV, a, nt_dense, dense_grid(a.n_strips, qkv_units), s);
@@ -348,6 +352,7 @@ static int verify_layer_impl(evict_ctx* ctx, const evict_layer_weights* w, const
     a.resid = x_in;
     a.dense_tiles = dense_tiles;
     a.dense_units = 1;
+    a.nt_loads = dense_ntl;
     int ntw;
     rc = dense_strip_shape(a, &ntw) ? launch_gemm_dense_strip(m.dtype, EPI_RESID, a, ntw, s)
                                          : launch_gemm(m.dtype, EPI_RESID, a, nt_dense, dense_grid(a.n_strips, 1), s);
@@ -360,6 +365,10 @@ static int verify_layer_impl(evict_ctx* ctx, const evict_layer_weights* w, const
   EVICT_MARK(5);
   // token tiles per work-list slot of the grouped GEMMs: 2 once experts mostly have more than 16 tokens
   const int nt_exp = ctx->moe_nt ? ctx->moe_nt : 1;
+  // expert weights fetched with non-temporal loads: they are read once per call (up to the further token tiles
+  // of an expert, which run next to the first on the same XCD), and kept out of the caches they leave the
+  // activations and projection weights of the next kernels there
+  const int moe_nt = ctx->moe_nt_loads == 2 ? 1 : ctx->moe_nt_loads;
   rc = launch_topk_union(ctx, T, aux, 16 * nt_exp, s);
   if (rc) return rc;
   if (aux) {
@@ -384,7 +393,7 @@ static int verify_layer_impl(evict_ctx* ctx, const evict_layer_weights* w, const
     a.out0 = ctx->act;
     a.ldo = m.F;
     a.prefetch = ctx->moe_prefetch;
-    a.plain_loads = ctx->moe_plain_loads;
+    a.nt_loads = moe_nt;
     a.lds_dma = ctx->moe_lds_dma;
     // (one strip pair per wavefront pays once experts often have several token tiles: measured from 64 tokens on
     // where its chunks line up with the XCDs, see gateup_waves, else from 128)
@@ -412,7 +421,7 @@ static int verify_layer_impl(evict_ctx* ctx, const evict_layer_weights* w, const
     a.chunk_units = ctx->moe_chunk_down;
     a.prefetch = ctx->moe_prefetch;
     a.wave_strip = ctx->moe_down_kernel;
-    a.plain_loads = ctx->moe_plain_loads;
+    a.nt_loads = moe_nt;
     rc = launch_gemm(m.dtype, EPI_F32, a, nt_exp, ctx->moe_grid, s);
     if (rc) return rc;
   }
@@ -491,6 +500,7 @@ static int launch_lm_gemm(evict_ctx* ctx, int epi, GemmArgs& a, int T, hipStream
   const int nt = ctx->lm_nt ? ctx->lm_nt : (T > 16 ? 2 : 1);
   a.dense_tiles = (T + 16 * nt - 1) / (16 * nt);
   a.dense_units = ctx->lm_units ? ctx->lm_units : (T > 16 ? 8 : 2);
+  a.nt_loads = ctx->dense_nt_loads == 2 ? (a.dense_tiles == 1 ? 1 : 0) : ctx->dense_nt_loads;  // every strip is read by one workgroup
   const int grid = (((a.n_strips + a.dense_units - 1) / a.dense_units + 7) / 8) * 8 * a.dense_tiles;
   return launch_gemm(ctx->m.dtype, epi, a, nt, grid, s);
 }
@@ -636,9 +646,12 @@ int evict_tune(evict_ctx* ctx, const char* key, int value) {
   } else if (!strcmp(key, "dense_nt")) {
     EVICT_REQUIRE(value >= 0 && value <= 2, EVICT_E_INVALID, "evict_tune: dense_nt must be 0 (auto), 1 or 2");
     ctx->dense_nt = value;
-  } else if (!strcmp(key, "moe_plain_loads")) {
-    EVICT_REQUIRE(value == 0 || value == 1, EVICT_E_INVALID, "evict_tune: moe_plain_loads must be 0 or 1");
-    ctx->moe_plain_loads = value;
+  } else if (!strcmp(key, "moe_nt_loads")) {
+    EVICT_REQUIRE(value >= 0 && value <= 2, EVICT_E_INVALID, "evict_tune: moe_nt_loads must be 0, 1 or 2 (auto)");
+    ctx->moe_nt_loads = value;
+  } else if (!strcmp(key, "dense_nt_loads")) {
+    EVICT_REQUIRE(value >= 0 && value <= 2, EVICT_E_INVALID, "evict_tune: dense_nt_loads must be 0, 1 or 2 (auto)");
+    ctx->dense_nt_loads = value;
   } else if (!strcmp(key, "moe_gateup_kernel")) {
     EVICT_REQUIRE(value >= 0 && value <= 2, EVICT_E_INVALID, "evict_tune: moe_gateup_kernel must be 0, 1 or 2 (auto)");
     ctx->moe_gateup_kernel = value;

@@ -12,6 +12,8 @@
 // runs the epilogue. The whole work list (union experts x strips) is cut into equal
 // contiguous ranges on the device, so no host knowledge of the union size is needed.
 #pragma once
+#include <type_traits>
+
 #include "device_utils.h"
 
 namespace evict {
@@ -48,7 +50,7 @@ struct GemmArgs {
   int dense_units;       // dense: consecutive strips a workgroup takes (its weight loads run ahead across them)
   int prefetch;          // host-side choice of the kernel variant: 3 = no compile-time step counts (measurement knob)
   int wave_strip;        // host-side: grouped fp32-output GEMM may use gemm_wave_strip_kernel
-  int plain_loads;       // 1: never use non-temporal weight loads (measurement knob)
+  int nt_loads;          // host-side choice of the kernel variant: 1 = weights fetched with non-temporal loads
   int lds_dma;           // 1: strip-pair gate/up kernel stages its token operand with direct global-to-LDS loads
   void* out0;            // QKV: q; RESID: h; SWIGLU: act; F32: y; ARGMAX: best value per (token, strip), [T][ldo]
   void* out1;            // QKV: k_new; ARGMAX: row index of the best value per (strip, token)
@@ -67,11 +69,16 @@ constexpr int kGemmThreads = kGemmWaves * 64;
 // taken per step (one partial-tile exchange per IS strips).
 // NS > 0: steps per segment known at compile time (the step loop is unrolled, so the rolling refill of
 // the weight registers is unconditional and every wait is by exact queue position).
-template <typename ST, int NT, int KBW, int PF, int EPI, bool EXACT, int IS = 1, int NS = 0>
+// NTL: weights are fetched with non-temporal loads (read once, or by the neighbouring token tile at about the
+// same time: kept out of the caches' way). Ordinary loads stream about 15 % slower here and leave L2 and the
+// memory-side cache full of weights nobody reads again, which slows the kernels that follow (measured). This is
+// a compile-time choice on purpose: a run-time choice per load between a non-temporal and an ordinary load of
+// the same address is folded by the compiler into one ordinary load. (Measured too: ordinary loads for all but
+// the last token tile of an expert, so that later tiles find the weights in L2, lose more in the following
+// kernels than they save in this one.)
+template <typename ST, int NT, int KBW, int PF, int EPI, bool EXACT, int IS = 1, int NS = 0, bool NTL = false>
 __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 4 : 2))) void gemm_stream_kernel(const GemmArgs a) {
   constexpr int SPU = (EPI == EPI_SWIGLU) ? 2 : 1;  // strips per unit of work
-  // expert weights are read exactly once per call: keep them out of the caches' way
-  constexpr bool kStreamOnce = (EPI == EPI_SWIGLU || EPI == EPI_F32 || EPI == EPI_ARGMAX);
   static_assert(EPI != EPI_SWIGLU || IS == 1, "gate/up strips are exchanged one at a time");
   __shared__ f32x4 s_part[2][kGemmWaves][IS * NT][64];
 
@@ -84,12 +91,12 @@ __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(NT
 
   // One segment = `nunits` consecutive units (strips, or gate/up strip pairs) of one weight
   // matrix, applied to the tokens [tok_begin, min(ntok, tok_limit)) of its group.
-  auto run_segment = [&](int grp, int unit_in_grp, int nunits, int tok_begin, int tok_limit) {
+  auto run_segment = [&](auto nt_tag, int grp, int unit_in_grp, int nunits, int tok_begin, int tok_limit) {
+    constexpr bool once = decltype(nt_tag)::value;
     const int strip0 = unit_in_grp * SPU;
     const int nitems = nunits * SPU;
     int p0 = 0, ntok = a.T;
     int tok_early = 0;  // token id from the work record (grouped, first kWorkToks positions)
-    bool once = kStreamOnce && !a.plain_loads;  // weights read by this workgroup only: keep them out of the caches' way
     const u32x4* wbase = a.W;
     if (a.grouped) {
       // one hop: the record (scalar) and this lane's token id (vector) are fetched together
@@ -98,7 +105,6 @@ __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(NT
       tok_early = rec->tok[lc < kWorkToks ? lc : kWorkToks - 1];  // entries past ntok repeat the last token
       p0 = rec->p0;
       ntok = rec->ntok;
-      once = kStreamOnce && !a.plain_loads && (rec->pad & 0xFFFF) == 1;
       const int ex = rec->expert;
       wbase = ex < a.n_routed ? a.W + (long long)ex * a.group_stride : a.W_shared + (long long)(ex - a.n_routed) * a.group_stride;
     }
@@ -346,7 +352,7 @@ __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(NT
       // (the token tiles of one expert are consecutive slots: with cpg a multiple of 8 their
       // chunks land on the same XCD, whose L2 serves the second reader of the weights)
       const int slot = chunk / cpg, uc = chunk - slot * cpg;
-      run_segment(slot, uc * a.chunk_units, a.chunk_units, 0, 0x7fffffff);
+      run_segment(std::integral_constant<bool, NTL>{}, slot, uc * a.chunk_units, a.chunk_units, 0, 0x7fffffff);
     }
   } else {
     // one workgroup per (strip, token tile). Workgroup ids go round-robin over the 8 XCDs, so
@@ -358,7 +364,7 @@ __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(NT
     const unsigned unit = ((i / (unsigned)a.dense_tiles) * 8u + xcd) * du;
     if (unit >= (unsigned)upg) return;
     const unsigned nu = unit + du <= (unsigned)upg ? du : (unsigned)upg - unit;
-    run_segment(0, (int)unit, (int)nu, (int)tile * 16 * NT, (int)(tile + 1) * 16 * NT);
+    run_segment(std::integral_constant<bool, NTL>{}, 0, (int)unit, (int)nu, (int)tile * 16 * NT, (int)(tile + 1) * 16 * NT);
   }
 }
 
@@ -379,7 +385,7 @@ __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(NT
 // a weight load and its use is then fully unrolled, which is what lets the compiler wait for a
 // load by its exact position in the in-order queue (with run-time trip counts it has to drain the
 // queue before the first MFMA, and the window stops rolling).
-template <typename ST, int WIN, int NB, bool EXACT, int NTW = 1, int WS = 8, int NKB = 0>
+template <typename ST, int WIN, int NB, bool EXACT, int NTW = 1, int WS = 8, int NKB = 0, bool NTL = false>
 __global__ __launch_bounds__(WS * 64) __attribute__((amdgpu_waves_per_eu(4))) void gemm_wave_strip_kernel(const GemmArgs a) {
   extern __shared__ __attribute__((aligned(16))) u32x4 s_b[];  // [NTW token tiles][nkb][64]
   const int tid = threadIdx.x, lane = tid & 63;
@@ -388,11 +394,12 @@ __global__ __launch_bounds__(WS * 64) __attribute__((amdgpu_waves_per_eu(4))) vo
   const int cpg = a.n_strips / WS;  // chunks per slot (host-checked: divides)
   const int total = *a.union_count * cpg;
   bool first = true;
-  for (int chunk = blockIdx.x; chunk < total; chunk += gridDim.x) {
+  // one chunk; nt_tag: non-temporal weight loads (see gemm_stream_kernel)
+  auto run_chunk = [&](auto nt_tag, int chunk) {
+    constexpr bool once = decltype(nt_tag)::value;
     const int slot = chunk / cpg, strip = (chunk - slot * cpg) * WS + w;
     const WorkRec* rec = a.work + slot;
     const int p0 = rec->p0, ntok = rec->ntok, ex = rec->expert;
-    const bool once = !a.plain_loads && (rec->pad & 0xFFFF) == 1;  // single token tile: nobody else reads these weights
     const u32x4* wbase = ex < a.n_routed ? a.W + (long long)ex * a.group_stride
                                          : a.W_shared + (long long)(ex - a.n_routed) * a.group_stride;
     // token operand first, weights behind it: the in-order load counter then lets the operand
@@ -456,7 +463,8 @@ __global__ __launch_bounds__(WS * 64) __attribute__((amdgpu_waves_per_eu(4))) vo
     for (int t = 0; t < NTW; ++t)
       if (valid[t])
         *reinterpret_cast<f32x4*>((float*)a.out0 + (p0 + t * 16 + (lane & 15)) * a.ldo + strip * 16 + (lane >> 4) * 4) = acc[t];
-  }
+  };
+  for (int chunk = blockIdx.x; chunk < total; chunk += gridDim.x) run_chunk(std::integral_constant<bool, NTL>{}, chunk);
 }
 
 // ------------------------------------------------------------------------------------
@@ -470,7 +478,7 @@ __global__ __launch_bounds__(WS * 64) __attribute__((amdgpu_waves_per_eu(4))) vo
 // work-list slot). Refills go out in runs of 8
 // consecutive blocks per strip once the window is 16 deep.
 // ------------------------------------------------------------------------------------
-template <typename ST, int WIN, int NB, int WS, int NKB = 0, int NTW = 1, bool DMA = false>
+template <typename ST, int WIN, int NB, int WS, int NKB = 0, int NTW = 1, bool DMA = false, bool NTL = false>
 __global__ __launch_bounds__(WS * 64) __attribute__((amdgpu_waves_per_eu(2))) void gemm_wave_gateup_kernel(const GemmArgs a) {
   static_assert(!DMA || (NTW == 1 && 2 * WIN <= 48), "direct-to-LDS staging: one token tile, window loads countable in vmcnt");
   extern __shared__ __attribute__((aligned(16))) u32x4 s_b[];  // [NTW token tiles][nkb][64]
@@ -480,13 +488,14 @@ __global__ __launch_bounds__(WS * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
   const int cpg = (a.n_strips >> 1) / WS;  // chunks per slot
   const int total = *a.union_count * cpg;
   bool first = true;
-  for (int chunk = blockIdx.x; chunk < total; chunk += gridDim.x) {
+  // one chunk; nt_tag: non-temporal weight loads (see gemm_stream_kernel)
+  auto run_chunk = [&](auto nt_tag, int chunk) {
+    constexpr bool once = decltype(nt_tag)::value;
     const int slot = chunk / cpg, unit = (chunk - slot * cpg) * WS + w;
     const WorkRec* rec = a.work + slot;
     const int lc = lane & 15;
     const int tok_early = rec->tok[lc < kWorkToks ? lc : kWorkToks - 1];
     const int p0 = rec->p0, ntok = rec->ntok, ex = rec->expert;
-    const bool once = !a.plain_loads && (rec->pad & 0xFFFF) == 1;
     const u32x4* wbase = ex < a.n_routed ? a.W + (long long)ex * a.group_stride
                                          : a.W_shared + (long long)(ex - a.n_routed) * a.group_stride;
     // (NTW token tiles of 16 per slot: the work list was built with tiles of 16 * NTW tokens)
@@ -595,7 +604,8 @@ __global__ __launch_bounds__(WS * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
         for (int i = 0; i < 4; ++i) r4[i] = (accg[t][i] / (1.0f + __expf(-accg[t][i]))) * accu[t][i];
         store4<ST>(a.out0, (long long)(p0 + t * 16 + lc) * a.ldo + unit * 16 + (lane >> 4) * 4, r4);
       }
-  }
+  };
+  for (int chunk = blockIdx.x; chunk < total; chunk += gridDim.x) run_chunk(std::integral_constant<bool, NTL>{}, chunk);
 }
 
 // ------------------------------------------------------------------------------------

@@ -1159,33 +1159,43 @@ __global__ __launch_bounds__(256) void combine_kernel(const void* __restrict__ h
 
 template <typename ST, int NT, int EPI>
 int launch_gemm_nt(const GemmArgs& a, int grid, hipStream_t s) {
+  // (non-temporal weight loads are a template parameter; they are built for the bf16 production shapes only)
 #define EVICT_GEMM_LAUNCH(KBW_, PF_, EXACT_) \
   hipLaunchKernelGGL((gemm_stream_kernel<ST, NT, KBW_, PF_, EPI, EXACT_>), dim3(grid), dim3(kGemmThreads), 0, s, a)
+#define EVICT_GEMM_LAUNCH_NT(KBW_, PF_, EXACT_, IS_, NS_)                                                                  \
+  do {                                                                                                                    \
+    if (a.nt_loads)                                                                                                       \
+      hipLaunchKernelGGL((gemm_stream_kernel<ST, NT, KBW_, PF_, EPI, EXACT_, IS_, NS_, true>), dim3(grid), dim3(kGemmThreads), 0, s, a);  \
+    else                                                                                                                  \
+      hipLaunchKernelGGL((gemm_stream_kernel<ST, NT, KBW_, PF_, EPI, EXACT_, IS_, NS_, false>), dim3(grid), dim3(kGemmThreads), 0, s, a); \
+  } while (0)
   const int nkb = a.nkb;
   const int need = ((nkb > 64 ? 64 : nkb) + kGemmWaves - 1) / kGemmWaves;
-  const bool bf16 = ST::kBytes == 2;
-  if (bf16 && nkb % 64 == 0) {
+  constexpr bool bf16 = ST::kBytes == 2;
+  if constexpr (bf16) {
+  if (nkb % 64 == 0) {
     // the next step's 8 loads are issued right after the MFMAs, so they fly during the
     // partial-tile exchange; one buffer keeps the kernel under 128 VGPRs (2 workgroups per CU)
     if (EPI == EPI_SWIGLU && NT == 1 && a.grouped && a.chunk_units == 1 && nkb == 64 && a.prefetch != 3)
       // one gate/up strip pair per chunk: two steps, known at compile time
-      hipLaunchKernelGGL((gemm_stream_kernel<ST, NT, 8, 1, EPI, true, 1, (EPI == EPI_SWIGLU && NT == 1) ? 2 : 0>), dim3(grid),
-                         dim3(kGemmThreads), 0, s, a);
+      EVICT_GEMM_LAUNCH_NT(8, 1, true, 1, ((EPI == EPI_SWIGLU && NT == 1) ? 2 : 0));
     else if (EPI == EPI_RESID && !a.grouped && a.prefetch != 3 &&
              (a.dense_units > 0 ? a.dense_units : 1) * ((nkb + 63) / 64) == 2)
       // two steps per workgroup (one strip of two 64-block chunks), known at compile time (the QKV
       // variant of this would spill)
-      hipLaunchKernelGGL((gemm_stream_kernel<ST, NT, 8, 1, EPI, true, 1, EPI == EPI_RESID ? 2 : 0>), dim3(grid),
-                         dim3(kGemmThreads), 0, s, a);
-    else EVICT_GEMM_LAUNCH(8, 1, true);
-  } else if (bf16 && nkb == 24) {
+      EVICT_GEMM_LAUNCH_NT(8, 1, true, 1, (EPI == EPI_RESID ? 2 : 0));
+    else EVICT_GEMM_LAUNCH_NT(8, 1, true, 1, 0);
+    return launch_status("gemm_stream_kernel");
+  } else if (nkb == 24) {
     // 3 blocks per wavefront per strip: take 4 strips per exchange step when the chunking allows
     if (EPI == EPI_F32 && NT == 1 && a.grouped && a.chunk_units % 4 == 0)
-      hipLaunchKernelGGL((gemm_stream_kernel<ST, NT, 3, 1, EPI, true, (EPI == EPI_F32 && NT == 1) ? 4 : 1>), dim3(grid),
-                         dim3(kGemmThreads), 0, s, a);
+      EVICT_GEMM_LAUNCH_NT(3, 1, true, ((EPI == EPI_F32 && NT == 1) ? 4 : 1), 0);
     else
-      EVICT_GEMM_LAUNCH(3, 4, true);
-  } else if (need <= 4) {
+      EVICT_GEMM_LAUNCH_NT(3, 4, true, 1, 0);
+    return launch_status("gemm_stream_kernel");
+  }
+  }
+  if (need <= 4) {
     // four stages of weight loads; three where the epilogue prefetch also needs registers (four would spill)
     constexpr int kStages = (EPI == EPI_QKV || EPI == EPI_RESID) ? 3 : 4;
     EVICT_GEMM_LAUNCH(4, kStages, false);
@@ -1193,6 +1203,7 @@ int launch_gemm_nt(const GemmArgs& a, int grid, hipStream_t s) {
     EVICT_GEMM_LAUNCH(8, 1, false);
   }
 #undef EVICT_GEMM_LAUNCH
+#undef EVICT_GEMM_LAUNCH_NT
   return launch_status("gemm_stream_kernel");
 }
 
@@ -1203,16 +1214,20 @@ int launch_gemm_wave_strip(const GemmArgs& a, int grid, hipStream_t s) {
   const size_t lds = (size_t)nkb * 1024 * NTW;
 #define EVICT_WS_LAUNCH(WIN_, NB_, EXACT_) \
   hipLaunchKernelGGL((gemm_wave_strip_kernel<ST, WIN_, NB_, EXACT_, NTW>), dim3(grid), dim3(8 * 64), lds, s, a)
+#define EVICT_WS_LAUNCH_NT(WIN_, NB_, NKB_)                                                                                       \
+  do {                                                                                                                           \
+    if (a.nt_loads) hipLaunchKernelGGL((gemm_wave_strip_kernel<ST, WIN_, NB_, true, NTW, 8, NKB_, true>), dim3(grid), dim3(8 * 64), lds, s, a); \
+    else hipLaunchKernelGGL((gemm_wave_strip_kernel<ST, WIN_, NB_, true, NTW, 8, NKB_, false>), dim3(grid), dim3(8 * 64), lds, s, a);           \
+  } while (0)
   // (windows sized to stay under 128 VGPRs together with the staged operand blocks)
-  if (nkb == 24)
-    hipLaunchKernelGGL((gemm_wave_strip_kernel<ST, 12, 3, true, NTW, 8, 24>), dim3(grid), dim3(8 * 64), lds, s, a);
-  else if (nkb == 44 && NTW == 1)
-    hipLaunchKernelGGL((gemm_wave_strip_kernel<ST, 11, 6, true, 1, 8, 44>), dim3(grid), dim3(8 * 64), lds, s, a);
+  if (nkb == 24) EVICT_WS_LAUNCH_NT(12, 3, 24);
+  else if (nkb == 44 && NTW == 1) EVICT_WS_LAUNCH_NT(11, 6, 44);
   else if (nkb == 44) EVICT_WS_LAUNCH(11, 6 / NTW, true);
-  else if (nkb % 16 == 0) EVICT_WS_LAUNCH(16, 4 / NTW, true);
+  else if (nkb % 16 == 0) EVICT_WS_LAUNCH_NT(16, 4 / NTW, 0);
   else if (nkb % 8 == 0) EVICT_WS_LAUNCH(8, 2 / NTW, true);
   else EVICT_WS_LAUNCH(16, 4 / NTW, false);
 #undef EVICT_WS_LAUNCH
+#undef EVICT_WS_LAUNCH_NT
   return launch_status("gemm_wave_strip_kernel");
 }
 
@@ -1236,9 +1251,15 @@ int launch_gemm_wave_gateup(const GemmArgs& a, int nt, int grid, hipStream_t s) 
     return launch_status("gemm_wave_gateup_kernel");
   }
   if (a.lds_dma && a.nkb == 64 && ST::kBytes == 2) {
-    if (ws == 11) hipLaunchKernelGGL((gemm_wave_gateup_kernel<ST, 16, 16, 11, 64, 1, true>), dim3(grid), dim3(11 * 64), lds, s, a);
-    else if (ws == 6) hipLaunchKernelGGL((gemm_wave_gateup_kernel<ST, 16, 16, 6, 64, 1, true>), dim3(grid), dim3(6 * 64), lds, s, a);
-    else hipLaunchKernelGGL((gemm_wave_gateup_kernel<ST, 16, 16, 4, 64, 1, true>), dim3(grid), dim3(4 * 64), lds, s, a);
+#define EVICT_GU_DMA(WS_)                                                                                                              \
+    do {                                                                                                                               \
+      if (a.nt_loads) hipLaunchKernelGGL((gemm_wave_gateup_kernel<ST, 16, 16, WS_, 64, 1, true, true>), dim3(grid), dim3(WS_ * 64), lds, s, a); \
+      else hipLaunchKernelGGL((gemm_wave_gateup_kernel<ST, 16, 16, WS_, 64, 1, true, false>), dim3(grid), dim3(WS_ * 64), lds, s, a);           \
+    } while (0)
+    if (ws == 11) EVICT_GU_DMA(11);
+    else if (ws == 6) EVICT_GU_DMA(6);
+    else EVICT_GU_DMA(4);
+#undef EVICT_GU_DMA
     return launch_status("gemm_wave_gateup_kernel");
   }
 #define EVICT_GU_LAUNCH(WS_)                                                                                              \
