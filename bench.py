@@ -210,7 +210,7 @@ def spec_loop(args):
     # plain autoregressive decoding for comparison: a one-node tree per iteration (the root alone: one token each)
     pool1 = [DraftOnDevice(harness.dev_i32(np.array([0, 1])), p.parent[:1], p.q[:1], p.x[:1], p.tok[:1], p.target_next[:1], 1)
              for p in pool]
-    for mode in ("autoregressive", "verify_all", "evict", "coverage_0.7", "coverage_0.4"):
+    for mode in ("autoregressive", "verify_all", "evict", "evict_device_dispatch", "coverage_0.7", "coverage_0.4"):
         rho = float(mode.split("_")[1]) if mode.startswith("coverage") else None
         drafts = pool1 if mode == "autoregressive" else pool
         if mode == "evict":
@@ -219,7 +219,30 @@ def spec_loop(args):
             offset = max(results["verify_all"]["ms_per_iteration"] - cost[N], 0.0)
             cost = [c + offset for c in cost]
             cost_dev = torch.tensor(cost, dtype=torch.float32, device=dev)
-        table = cost_dev if mode == "evict" else None
+        table = cost_dev if mode in ("evict", "evict_device_dispatch") else None
+        if mode == "evict_device_dispatch":
+            # Sec. 3.3: the selected length is dispatched on the device. Launches are sized for the whole tree, the
+            # kernels read the selected length from the selection's output, nothing is read back inside an
+            # iteration; the host refreshes its upper bound of the context length every 16 iterations.
+            assert args.iters <= loop.log_slots, "--iters exceeds the loop's device log"
+            loop.set_context_length(L0)
+            for i in range(8):
+                loop.iteration_on_device(drafts[i % len(drafts)], table)
+            loop.set_context_length(L0)
+            loop.n_logged = 0
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for i in range(args.iters):
+                loop.iteration_on_device(drafts[i % len(drafts)], table)
+                if (i + 1) % 16 == 0:
+                    loop.resync()
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t0
+            tokens = int(loop.plen_log[:args.iters].sum().item())
+            ksum = int(loop.k_log[:args.iters].sum().item())
+            results[mode] = {"tokens_per_s": tokens / dt, "ms_per_iteration": dt * 1e3 / args.iters,
+                             "mean_accepted_tokens": tokens / args.iters, "mean_verified_nodes": ksum / args.iters}
+            continue
         loop.set_context_length(L0)
         for i in range(8):
             loop.iteration(drafts[i % len(drafts)], table, rho=rho)

@@ -150,6 +150,18 @@ int evict_verify_stack(evict_ctx* ctx, const evict_layer_weights* layers, int n_
                        int64_t kv_head_stride, const int32_t* ctx_len, int max_ctx_host,
                        const void* x_in, void* x_out, void* const* k_new, void* const* v_new, void* stream);
 
+/* On-device dispatch of the verification length (Sec. 3.3: the selected length picks the verification
+ * without host logic in between). After evict_dynamic_tokens(ctx, count_dev) every call on this context
+ * that takes a token count T (evict_verify_layer / _stack / _stack_paged, evict_lm_head_argmax / _logits,
+ * evict_accept_path_sampled) treats T as an upper bound -- launch shapes, scratch and output rows are sized
+ * for it -- and the kernels read the actual count from count_dev [dev] int32[1] when they run, clamped to
+ * [1, T]. Pointing it at new_tree_off + B of evict_select_prefix makes select -> gather -> verify -> LM head
+ * -> accept -> commit one sequence of launches with no host read-back, capturable as one graph. With B == 1
+ * the tree size then comes from tree_off (not from T), so tree_off[B] must equal the value at count_dev.
+ * Rows past the actual count are neither computed nor written. count_dev == NULL switches back to host
+ * counts. evict_profile_cost* refuse to run while it is set. */
+int evict_dynamic_tokens(evict_ctx* ctx, const int32_t* count_dev);
+
 /* Target token after every node: final RMSNorm, logits = W_lm x, next = argmax over the
  * vocabulary, lowest index on equal values (the p(. | prefix of node) of Sec. 2.1 at
  * temperature 0; feeds evict_accept_path).

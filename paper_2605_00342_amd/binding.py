@@ -19,7 +19,7 @@ __all__ = [
     "evict_profile_cost", "evict_graph_begin", "evict_graph_end", "evict_graph_launch", "evict_graph_destroy",
     "evict_lm_head_logits", "evict_accept_path_sampled", "evict_kv_commit", "evict_select_prefix_coverage", "evict_kv_commit_stack",
     "evict_profile_cost_union", "evict_verify_stack_paged", "evict_kv_commit_stack_paged", "evict_accept_path_sampled_noalloc",
-    "STAGES", "EXPORTS",
+    "evict_dynamic_tokens", "STAGES", "EXPORTS",
 ]
 
 EVICT_F32, EVICT_BF16 = 0, 1
@@ -34,6 +34,7 @@ EXPORTS = [
     "evict_profile_cost", "evict_graph_begin", "evict_graph_end", "evict_graph_launch", "evict_graph_destroy",
     "evict_lm_head_logits", "evict_accept_path_sampled", "evict_kv_commit", "evict_select_prefix_coverage", "evict_kv_commit_stack",
     "evict_profile_cost_union", "evict_verify_stack_paged", "evict_kv_commit_stack_paged", "evict_accept_path_sampled_noalloc",
+    "evict_dynamic_tokens",
 ]
 STAGES = ["prep", "qkv", "attention", "oproj", "router", "union", "gateup", "down", "shared", "combine"]
 
@@ -112,6 +113,7 @@ def load():
     lib.evict_lm_head_logits.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp]
     lib.evict_accept_path_sampled.argtypes = [vp, vp, vp, vp, vp, i32, C.c_float, vp, vp, i32, i32, vp, i32, vp, vp, vp]
     lib.evict_accept_path_sampled_noalloc.argtypes = lib.evict_accept_path_sampled.argtypes
+    lib.evict_dynamic_tokens.argtypes = [vp, vp]
     lib.evict_kv_commit.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, i32, vp, vp, vp, i64, i64, vp, i32, vp, i32, vp]
     lib.evict_kv_commit_stack.argtypes = [vp, i32, i32, i32, C.POINTER(vp), C.POINTER(vp), i32, vp, vp, i32, vp, C.POINTER(vp),
                                           C.POINTER(vp), i64, i64, vp, i32, vp, i32, vp]
@@ -253,6 +255,11 @@ def evict_accept_path_sampled(ctx, tree_off, parent, draft_tok, logits, vocab, t
     _check(load().evict_accept_path_sampled(ctx, _p(tree_off), _p(parent), _p(draft_tok), _p(logits), vocab,
                                             float(temperature), _p(u_node), _p(u_bonus), B, T, _p(path), path_stride,
                                             _p(path_len), _p(bonus_tok), _stream()))
+
+
+def evict_dynamic_tokens(ctx, count_dev) -> None:
+    """count_dev: int32 device tensor (its first element is the count), an int device address, or None."""
+    _check(load().evict_dynamic_tokens(ctx, count_dev if isinstance(count_dev, int) else _p(count_dev)))
 
 
 def evict_accept_path_sampled_noalloc(ctx, tree_off, parent, draft_tok, logits, vocab, temperature, u_node, u_bonus, B, T,

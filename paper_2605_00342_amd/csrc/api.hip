@@ -146,6 +146,7 @@ int evict_create(evict_ctx** out, const evict_model_desc* m, int max_tokens, int
   c.timed_once = 0;
   c.capturing = 0;
   c.paging = KvPaging{nullptr, 0, 0, 0};
+  c.t_dev = nullptr;
   c.prof_ev[0] = c.prof_ev[1] = nullptr;
   for (int i = 0; !rc && i < 2; ++i) {
     he = hipEventCreate(&c.prof_ev[i]);
@@ -322,6 +323,7 @@ static int verify_layer_impl(evict_ctx* ctx, const evict_layer_weights* w, const
     a.X = ctx->x_norm;
     a.ldx_bytes = (long long)m.d * eb;
     a.T = T;
+    a.T_dev = ctx->t_dev;
     a.out0 = ctx->q; a.out1 = k_new; a.out2 = v_new;
     a.rope_cs = ctx->rope_cs;
     a.Hq = m.Hq; a.Hkv = m.Hkv; a.D = m.D;
@@ -347,6 +349,7 @@ static int verify_layer_impl(evict_ctx* ctx, const evict_layer_weights* w, const
     a.X = ctx->attn_o;
     a.ldx_bytes = (long long)HqD * eb;
     a.T = T;
+    a.T_dev = ctx->t_dev;
     a.out0 = ctx->h;
     a.ldo = m.d;
     a.resid = x_in;
@@ -524,12 +527,13 @@ int evict_lm_head_argmax(evict_ctx* ctx, const void* x, const void* g_final, con
   a.X = ctx->x_norm;
   a.ldx_bytes = (long long)m.d * eb;
   a.T = T;
+  a.T_dev = ctx->t_dev;
   a.out0 = ctx->lm_val;
   a.out1 = ctx->lm_idx;
   a.ldo = a.n_strips;
   rc = launch_lm_gemm(ctx, EPI_ARGMAX, a, T, s);
   if (rc) return rc;
-  return launch_argmax_reduce(ctx->lm_val, ctx->lm_idx, a.n_strips, a.n_strips, T, next, best_logit, s);
+  return launch_argmax_reduce(ctx->lm_val, ctx->lm_idx, a.n_strips, a.n_strips, T, next, best_logit, ctx->t_dev, s);
 }
 
 int evict_lm_head_logits(evict_ctx* ctx, const void* x, const void* g_final, const void* wlm_packed, int T, float* logits,
@@ -552,6 +556,7 @@ int evict_lm_head_logits(evict_ctx* ctx, const void* x, const void* g_final, con
   a.X = ctx->x_norm;
   a.ldx_bytes = (long long)m.d * eb;
   a.T = T;
+  a.T_dev = ctx->t_dev;
   a.out0 = logits;
   a.ldo = m.vocab;
   return launch_lm_gemm(ctx, EPI_F32, a, T, s);
@@ -567,6 +572,7 @@ int evict_profile_cost_union(evict_ctx* ctx, const evict_layer_weights* layers, 
                 "evict_profile_cost: Kmax=%d outside [1, min(max_tokens, %d)]", Kmax, EVICT_MAX_TREE_NODES);
   EVICT_REQUIRE(reps >= 1 && reps <= 4096, EVICT_E_INVALID, "evict_profile_cost: reps=%d outside [1, 4096]", reps);
   EVICT_REQUIRE(!ctx->capturing, EVICT_E_INVALID, "evict_profile_cost synchronises: not inside a graph capture");
+  EVICT_REQUIRE(!ctx->t_dev, EVICT_E_INVALID, "evict_profile_cost: switch evict_dynamic_tokens off first (the profile sets the length per call)");
   hipStream_t s = (hipStream_t)stream;
   cost_host[0] = 0.0f;
   if (union_mean_host) union_mean_host[0] = 0.0f;
@@ -600,6 +606,12 @@ int evict_profile_cost(evict_ctx* ctx, const evict_layer_weights* layers, int n_
                        void* const* k_new, void* const* v_new, int reps, float* cost_host, void* stream) {
   return evict_profile_cost_union(ctx, layers, n_layers, tree_off, parent, Kmax, k_caches, v_caches, kv_head_stride, ctx_len,
                                   max_ctx_host, x_in, x_out, k_new, v_new, reps, cost_host, nullptr, stream);
+}
+
+int evict_dynamic_tokens(evict_ctx* ctx, const int32_t* count_dev) {
+  EVICT_REQUIRE(ctx, EVICT_E_INVALID, "evict_dynamic_tokens: null context");
+  ctx->t_dev = count_dev;
+  return EVICT_OK;
 }
 
 int evict_tune(evict_ctx* ctx, const char* key, int value) {

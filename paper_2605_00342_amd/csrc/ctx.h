@@ -23,6 +23,7 @@ struct evict_ctx {
   int timed_once;        // a timed call has been recorded
   int capturing;         // a stream capture opened by evict_graph_begin is in progress
   KvPaging paging;       // set by the paged entry points for the duration of their call, else table == nullptr
+  const int32_t* t_dev;  // evict_dynamic_tokens: device word with the actual token count of the calls that take T, or nullptr
   hipEvent_t ev[EVICT_N_STAGES + 1];
   // ---- device scratch (all sized for max_tokens) ----
   int32_t* status;       // [1] sticky status bits

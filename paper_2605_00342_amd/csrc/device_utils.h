@@ -129,6 +129,15 @@ __device__ __forceinline__ unsigned wave_max_u32(unsigned v) {
   return (unsigned)__builtin_amdgcn_readlane((int)v, 63);
 }
 
+// Token count of a call: the host's T, or -- when the caller has pointed the context at a device word
+// (evict_dynamic_tokens) -- the value found there when the kernel runs, clamped to [1, T] (T is then the
+// upper bound every grid and buffer was sized for).
+__device__ __forceinline__ int dyn_tokens(const int* t_dev, int t_max) {
+  if (!t_dev) return t_max;
+  const int v = *t_dev;
+  return v < 1 ? 1 : (v > t_max ? t_max : v);
+}
+
 // Workgroup barrier that waits for LDS traffic only, so that global loads already in
 // flight (weight prefetch) stay in flight across it.
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }

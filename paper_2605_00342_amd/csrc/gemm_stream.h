@@ -45,7 +45,8 @@ struct GemmArgs {
   int chunk_units;       // grouped: units per chunk (divides the units per expert)
   const int* tok_of_pos; // token of each grouped position (perm[p] / k)
   int x_by_token;        // grouped: 1 -> X row = tok_of_pos[p], 0 -> X row = p
-  int T;                 // dense: token rows
+  int T;                 // dense: token rows (upper bound when T_dev is set)
+  const int* T_dev;      // dense: nullptr, or device word holding the actual number of token rows (<= T)
   int dense_tiles;       // dense: workgroups per strip, each taking 16*NT tokens
   int dense_units;       // dense: consecutive strips a workgroup takes (its weight loads run ahead across them)
   int prefetch;          // host-side choice of the kernel variant: 3 = no compile-time step counts (measurement knob)
@@ -95,7 +96,7 @@ __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(NT
     constexpr bool once = decltype(nt_tag)::value;
     const int strip0 = unit_in_grp * SPU;
     const int nitems = nunits * SPU;
-    int p0 = 0, ntok = a.T;
+    int p0 = 0, ntok = a.grouped ? 0 : dyn_tokens(a.T_dev, a.T);
     int tok_early = 0;  // token id from the work record (grouped, first kWorkToks positions)
     const u32x4* wbase = a.W;
     if (a.grouped) {
@@ -628,6 +629,7 @@ __global__ __launch_bounds__(WS * 64) void gemm_dense_strip_kernel(const GemmArg
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int nkb = NKB > 0 ? NKB : a.nkb;
+  const int T = dyn_tokens(a.T_dev, a.T);
   const unsigned ntg = (unsigned)a.dense_tiles;  // token groups of NTW * 16 tokens
   const unsigned xcd = blockIdx.x & 7u, i = blockIdx.x >> 3;
   const unsigned tg = i % ntg;
@@ -637,6 +639,7 @@ __global__ __launch_bounds__(WS * 64) void gemm_dense_strip_kernel(const GemmArg
   const bool active = strip_raw < a.n_strips;  // the last group may be short: its idle wavefronts still stage and wait
   const int strip = active ? strip_raw : a.n_strips - 1;
   const int tok0 = (int)tg * NTW * 16;
+  if (tok0 >= T) return;  // (a token group past the call's actual token count: whole workgroup, before any barrier)
   const int lc = lane & 15;
 
   // token operand first, weights behind it
@@ -645,8 +648,8 @@ __global__ __launch_bounds__(WS * 64) void gemm_dense_strip_kernel(const GemmArg
 #pragma unroll
   for (int t = 0; t < NTW; ++t) {
     int col = tok0 + t * 16 + lc;
-    valid[t] = active && col < a.T;
-    col = col < a.T ? col : a.T - 1;  // padded columns repeat the last token; never stored
+    valid[t] = active && col < T;
+    col = col < T ? col : T - 1;  // padded columns repeat the last token; never stored
     xrow[t] = (const char*)a.X + (long long)col * a.ldx_bytes + (lane >> 4) * 16;
   }
   constexpr int BMAX = 4;  // operand blocks a wavefront stages per pass and token tile
@@ -679,7 +682,7 @@ __global__ __launch_bounds__(WS * 64) void gemm_dense_strip_kernel(const GemmArg
 #pragma unroll
   for (int t = 0; t < NTW; ++t) {
     const int col = tok0 + t * 16 + lc;
-    const int tokc = col < a.T ? col : 0;
+    const int tokc = col < T ? col : 0;
     if (EPI == EPI_RESID) {
       pre0[t] = load4<ST>(a.resid, (long long)tokc * a.ldo + strip * 16 + (lane >> 4) * 4);
       pre1[t] = f32x4{0, 0, 0, 0};

@@ -49,7 +49,8 @@ __global__ __launch_bounds__(256) void prep_kernel(const int32_t* __restrict__ t
                                                    float eps, float theta, int D, uint64_t* __restrict__ anc,
                                                    int32_t* __restrict__ depth, int32_t* __restrict__ seq_of,
                                                    float* __restrict__ rope_cs, void* __restrict__ x_norm,
-                                                   int32_t* __restrict__ status, int n_single, int norm_only) {
+                                                   int32_t* __restrict__ status, int n_single, int norm_only,
+                                                   const int* __restrict__ t_dev) {
   constexpr int EB = ST::kBytes;
   constexpr int CE = 16 / EB;
   constexpr int MAXC = 4;  // 16-byte chunks of the row per thread (d <= 256*CE*MAXC)
@@ -57,6 +58,7 @@ __global__ __launch_bounds__(256) void prep_kernel(const int32_t* __restrict__ t
   __shared__ int s_b, s_depth;
   __shared__ float s_red[4];
   const int t = blockIdx.x, tid = threadIdx.x;
+  if (t >= dyn_tokens(t_dev, (int)gridDim.x)) return;  // (rows past the call's actual token count)
   // the row and the gain do not depend on the tree: fetch them first
   u32x4 raw[MAXC], graw[MAXC];
 #pragma unroll
@@ -621,12 +623,13 @@ constexpr int kMergeBatch = 16;
 template <typename ST>
 __global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict__ part_o, const float* __restrict__ part_ml,
                                                          int nsplits, int rows, int D, void* __restrict__ out,
-                                                         void* __restrict__ aux_out) {
+                                                         void* __restrict__ aux_out, int Hq, const int* __restrict__ t_dev) {
   const int lpr = D >> 2;  // lanes per row: 16 or 32
   const int tid = threadIdx.x;
   const int row = blockIdx.x * ((int)blockDim.x / lpr) + tid / lpr;
   const int c4 = tid & (lpr - 1);
-  if (row >= rows) return;  // (whole row groups leave together; no barrier follows)
+  // (`rows` = tokens x heads the partials were laid out for; rows past the call's actual token count hold nothing)
+  if (row >= rows || row >= dyn_tokens(t_dev, rows / Hq) * Hq) return;  // (no barrier follows)
   const size_t sstride = (size_t)rows * D;
   const float* po = part_o + (size_t)row * D + c4 * 4;
   const float* pml = part_ml + (size_t)row * 2;
@@ -684,9 +687,10 @@ constexpr int kFusedTopkTokens = 32;  // up to here TopK and the union share one
 
 template <typename ST>
 __global__ __launch_bounds__(kRouterThreads) void router_logits_kernel(
-    const void* __restrict__ h, const void* __restrict__ gain, const u32x4* __restrict__ wg_packed, int T, int d, int E,
+    const void* __restrict__ h, const void* __restrict__ gain, const u32x4* __restrict__ wg_packed, int T_max, int d, int E,
     int strips_per_wg, int ksplit, float eps, void* __restrict__ h_norm, float* __restrict__ logits,
-    void* __restrict__ aux_hn, float* __restrict__ aux_logits) {
+    void* __restrict__ aux_hn, float* __restrict__ aux_logits, const int* __restrict__ t_dev) {
+  const int T = dyn_tokens(t_dev, T_max);
   constexpr int EB = ST::kBytes;
   constexpr int CE = 16 / EB;   // elements per 16-byte chunk
   constexpr int MAXC = 8;       // 16-byte chunks a lane keeps of its token row (d <= 64*CE*MAXC)
@@ -803,9 +807,10 @@ __global__ __launch_bounds__(kRouterThreads) void router_logits_kernel(
 // the lowest expert index holding it, so equal scores go to the lower index.
 // ------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kRouterThreads) void topk_kernel(
-    const float* __restrict__ logits, int T, int E, int k, int norm, int32_t* __restrict__ topk_idx,
-    float* __restrict__ topk_w, int32_t* __restrict__ aux_idx, float* __restrict__ aux_w) {
+    const float* __restrict__ logits, int T_max, int E, int k, int norm, int32_t* __restrict__ topk_idx,
+    float* __restrict__ topk_w, int32_t* __restrict__ aux_idx, float* __restrict__ aux_w, const int* __restrict__ t_dev) {
   extern __shared__ __attribute__((aligned(16))) int s_all[];
+  const int T = dyn_tokens(t_dev, T_max);
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   float* s_sel = reinterpret_cast<float*>(s_all) + w * 64;                                   // [k] per wavefront
@@ -923,8 +928,9 @@ __device__ __forceinline__ void topk_wave_regs(const float (&raw)[NR], int E, in
 
 // Register variant of topk_kernel for E <= 256: grid over groups of 16 tokens, one per wavefront.
 __global__ __launch_bounds__(kRouterThreads) void topk_regs_kernel(
-    const float* __restrict__ logits, int T, int E, int k, int norm, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
-    int32_t* __restrict__ aux_idx, float* __restrict__ aux_w) {
+    const float* __restrict__ logits, int T_max, int E, int k, int norm, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
+    int32_t* __restrict__ aux_idx, float* __restrict__ aux_w, const int* __restrict__ t_dev) {
+  const int T = dyn_tokens(t_dev, T_max);
   const int lane = threadIdx.x & 63;
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int t = blockIdx.x * kRouterWaves + w;
@@ -951,12 +957,13 @@ __global__ __launch_bounds__(kRouterThreads) void topk_regs_kernel(
 // Small token counts: TopK (register variant) and the expert union in one workgroup, the
 // wavefronts taking the tokens in turn; saves a launch when there are few tokens to share out.
 __global__ __launch_bounds__(kRouterThreads) void topk_union_kernel(
-    const float* __restrict__ logits, int T, int E, int k, int norm, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
+    const float* __restrict__ logits, int T_max, int E, int k, int norm, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
     int32_t* __restrict__ aux_idx, float* __restrict__ aux_w, int use_masks, int32_t* __restrict__ union_ids,
     int32_t* __restrict__ union_count, int32_t* __restrict__ hist, int32_t* __restrict__ offsets,
     int32_t* __restrict__ perm, int32_t* __restrict__ inv, int32_t* __restrict__ status, WorkRec* __restrict__ work,
-    int32_t* __restrict__ tok_of_pos, int32_t* __restrict__ slot_count, int n_shared, int tt) {
+    int32_t* __restrict__ tok_of_pos, int32_t* __restrict__ slot_count, int n_shared, int tt, const int* __restrict__ t_dev) {
   extern __shared__ __attribute__((aligned(16))) int s_all[];
+  const int T = dyn_tokens(t_dev, T_max);
   const int lane = threadIdx.x & 63;
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   // the scores of both tokens a wavefront may have (T <= 32) are requested before either is ranked
@@ -999,11 +1006,12 @@ __global__ __launch_bounds__(kRouterThreads) void topk_union_kernel(
 
 // expert union and grouping (Eq. 5) with the device-side work list, one workgroup
 __global__ __launch_bounds__(kRouterThreads) void union_worklist_kernel(
-    const int32_t* __restrict__ topk_idx, int T, int k, int E, int use_masks, int32_t* __restrict__ union_ids,
+    const int32_t* __restrict__ topk_idx, int T_max, int k, int E, int use_masks, int32_t* __restrict__ union_ids,
     int32_t* __restrict__ union_count, int32_t* __restrict__ hist, int32_t* __restrict__ offsets,
     int32_t* __restrict__ perm, int32_t* __restrict__ inv, int32_t* __restrict__ status, WorkRec* __restrict__ work,
-    int32_t* __restrict__ tok_of_pos, int32_t* __restrict__ slot_count, int n_shared, int tt) {
+    int32_t* __restrict__ tok_of_pos, int32_t* __restrict__ slot_count, int n_shared, int tt, const int* __restrict__ t_dev) {
   extern __shared__ __attribute__((aligned(16))) int s_all[];
+  const int T = dyn_tokens(t_dev, T_max);
   expert_union_body(s_all, topk_idx, T, k, E, use_masks, union_ids, union_count, hist, offsets, perm, inv, status, work,
                     tok_of_pos, slot_count, n_shared, tt);
 }
@@ -1014,10 +1022,11 @@ __global__ __launch_bounds__(kRouterThreads) void union_worklist_kernel(
 // ------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void argmax_reduce_kernel(const float* __restrict__ val, const int32_t* __restrict__ idx,
                                                             int nstrips, int ld, int32_t* __restrict__ next,
-                                                            float* __restrict__ best_out) {
+                                                            float* __restrict__ best_out, const int* __restrict__ t_dev) {
   __shared__ float s_v[4];
   __shared__ int s_i[4];
   const int t = blockIdx.x, tid = threadIdx.x;
+  if (t >= dyn_tokens(t_dev, (int)gridDim.x)) return;  // (rows past the call's actual token count)
   float bv = -INFINITY;
   int bi = 0x7fffffff;
   // candidates of a token are contiguous ([T][ld] with ld >= nstrips): eight loads in flight per thread
@@ -1062,9 +1071,9 @@ __global__ __launch_bounds__(256) void argmax_reduce_kernel(const float* __restr
 template <typename ST>
 __global__ __launch_bounds__(256) void combine_kernel(const void* __restrict__ h, const float* __restrict__ y,
                                                       const float* __restrict__ w, const int32_t* __restrict__ inv,
-                                                      int k, int d, const float* __restrict__ y_sh, int n_shared, int T,
+                                                      int k, int d, int n_shared, int T_max,
                                                       void* __restrict__ out, const void* __restrict__ next_gain, float eps,
-                                                      void* __restrict__ x_norm) {
+                                                      void* __restrict__ x_norm, const int* __restrict__ t_dev) {
   constexpr int EB = ST::kBytes;
   constexpr int CE = 16 / EB;
   constexpr int MAXC = 4;  // 16-byte chunks of the row per thread (d <= 256*CE*MAXC, as in prep_kernel)
@@ -1072,6 +1081,9 @@ __global__ __launch_bounds__(256) void combine_kernel(const void* __restrict__ h
   __shared__ int s_inv[64];
   __shared__ float s_red[4];
   const int t = blockIdx.x, tid = threadIdx.x;
+  const int T = dyn_tokens(t_dev, T_max);
+  if (t >= T) return;  // (rows past the call's actual token count: whole workgroup, before any barrier)
+  const float* y_sh = y + (size_t)T * k * d;  // shared experts' rows follow the T * k routed pairs
   if (tid < k) {
     s_w[tid] = w[(size_t)t * k + tid];
     s_inv[tid] = inv[(size_t)t * k + tid];
@@ -1372,10 +1384,10 @@ int launch_prep(const evict_ctx* c, const int32_t* tree_off, const int32_t* pare
   const evict_model_desc& m = c->m;
   if (m.dtype == EVICT_BF16)
     hipLaunchKernelGGL(prep_kernel<BF16>, dim3(T), dim3(256), 0, s, tree_off, parent, B, ctx_len, max_ctx, x, gain, m.d,
-                       m.rms_eps, m.rope_theta, m.D, c->anc, c->depth, c->seq_of, c->rope_cs, c->x_norm, c->status, B == 1 ? T : 0, norm_only);
+                       m.rms_eps, m.rope_theta, m.D, c->anc, c->depth, c->seq_of, c->rope_cs, c->x_norm, c->status, (B == 1 && !c->t_dev) ? T : 0, norm_only, c->t_dev);
   else
     hipLaunchKernelGGL(prep_kernel<F32>, dim3(T), dim3(256), 0, s, tree_off, parent, B, ctx_len, max_ctx, x, gain, m.d,
-                       m.rms_eps, m.rope_theta, m.D, c->anc, c->depth, c->seq_of, c->rope_cs, c->x_norm, c->status, B == 1 ? T : 0, norm_only);
+                       m.rms_eps, m.rope_theta, m.D, c->anc, c->depth, c->seq_of, c->rope_cs, c->x_norm, c->status, (B == 1 && !c->t_dev) ? T : 0, norm_only, c->t_dev);
   return launch_status("prep_kernel");
 }
 
@@ -1476,7 +1488,7 @@ int launch_attention(const evict_ctx* c, const void* kc, const void* vc, long lo
     const size_t lds = attn_mfma_lds_bytes(m.D) * (nw == 8 ? 2 : 1);
 #define EVICT_ATTN_ARGS (const uint16_t*)c->q, (const uint16_t*)kc, (const uint16_t*)vc, seq_stride, head_stride, ctx_len, \
                         max_ctx_host, tree_off, (const uint16_t*)k_new, (const uint16_t*)v_new, c->anc, m.Hq, m.Hkv,       \
-                        ctx_splits, keys, rb, T, c->part_o, c->part_ml, B == 1 ? T : 0, B, c->paging, c->status
+                        ctx_splits, keys, rb, T, c->part_o, c->part_ml, (B == 1 && !c->t_dev) ? T : 0, B, c->paging, c->status
 #define EVICT_ATTN_LAUNCH(PAGED_)                                                                                              \
     if (m.D == 128 && nw == 4) hipLaunchKernelGGL((attn_partial_mfma_kernel<128, 4, PAGED_>), grid, dim3(256), lds, s, EVICT_ATTN_ARGS); \
     else if (m.D == 128) hipLaunchKernelGGL((attn_partial_mfma_kernel<128, 8, PAGED_>), grid, dim3(512), lds, s, EVICT_ATTN_ARGS);       \
@@ -1491,7 +1503,7 @@ int launch_attention(const evict_ctx* c, const void* kc, const void* vc, long lo
     nsplits = ctx_splits + EVICT_MAX_TREE_NODES / keys;
     hipLaunchKernelGGL(attn_partial_kernel<F32>, dim3(nsplits, m.Hkv, B), dim3(256), attn_partial_lds_bytes(m.D), s, c->q,
                        kc, vc, seq_stride, head_stride, ctx_len, max_ctx_host, tree_off, k_new, v_new, c->anc, m.Hq,
-                       m.Hkv, m.D, ctx_splits, T, c->part_o, c->part_ml, c->paging, c->status, B == 1 ? T : 0);
+                       m.Hkv, m.D, ctx_splits, T, c->part_o, c->part_ml, c->paging, c->status, (B == 1 && !c->t_dev) ? T : 0);
   }
   int rc = launch_status("attention partial kernel");
   if (rc) return rc;
@@ -1501,10 +1513,10 @@ int launch_attention(const evict_ctx* c, const void* kc, const void* vc, long lo
   const dim3 mgrid((mrows + rows_per_wg - 1) / rows_per_wg);
   if (m.dtype == EVICT_BF16)
     hipLaunchKernelGGL(attn_merge_kernel<BF16>, mgrid, dim3(mthreads), 0, s, c->part_o, c->part_ml, nsplits, mrows, m.D,
-                       c->attn_o, aux_out);
+                       c->attn_o, aux_out, m.Hq, c->t_dev);
   else
     hipLaunchKernelGGL(attn_merge_kernel<F32>, mgrid, dim3(mthreads), 0, s, c->part_o, c->part_ml, nsplits, mrows, m.D,
-                       c->attn_o, aux_out);
+                       c->attn_o, aux_out, m.Hq, c->t_dev);
   return launch_status("attn_merge_kernel");
 }
 
@@ -1519,10 +1531,10 @@ int launch_router(const evict_ctx* c, const void* gain, const void* wg, int T, c
   const dim3 grid((T + 15) / 16, (m.E / 16 + spw - 1) / spw);
   if (m.dtype == EVICT_BF16)
     hipLaunchKernelGGL(router_logits_kernel<BF16>, grid, dim3(kRouterThreads), lds, s, c->h, gain, (const u32x4*)wg, T, m.d,
-                       m.E, spw, router_ksplit(m), m.rms_eps, c->h_norm, c->logits, a_hn, a_lg);
+                       m.E, spw, router_ksplit(m), m.rms_eps, c->h_norm, c->logits, a_hn, a_lg, c->t_dev);
   else
     hipLaunchKernelGGL(router_logits_kernel<F32>, grid, dim3(kRouterThreads), lds, s, c->h, gain, (const u32x4*)wg, T, m.d,
-                       m.E, spw, router_ksplit(m), m.rms_eps, c->h_norm, c->logits, a_hn, a_lg);
+                       m.E, spw, router_ksplit(m), m.rms_eps, c->h_norm, c->logits, a_hn, a_lg, c->t_dev);
   return launch_status("router_logits_kernel");
 }
 
@@ -1536,29 +1548,29 @@ int launch_topk_union(const evict_ctx* c, int T, const evict_layer_aux* aux, int
   if (regs && T <= kFusedTopkTokens) {
     hipLaunchKernelGGL(topk_union_kernel, dim3(1), dim3(kRouterThreads), lds, s, c->logits, T, m.E, m.k, m.router_norm, c->topk_idx,
                        c->topk_w, a_idx, a_w, use_masks, c->union_ids, c->union_count, c->hist, c->offsets, c->perm, c->inv,
-                       c->status, c->work, c->tok_of_pos, c->sched, m.n_shared, tile_tokens);
+                       c->status, c->work, c->tok_of_pos, c->sched, m.n_shared, tile_tokens, c->t_dev);
     return launch_status("topk_union_kernel");
   }
   const dim3 tgrid((T + kRouterWaves - 1) / kRouterWaves);
   if (regs) {
     hipLaunchKernelGGL(topk_regs_kernel, tgrid, dim3(kRouterThreads), 0, s, c->logits, T, m.E, m.k, m.router_norm, c->topk_idx, c->topk_w,
-                       a_idx, a_w);
+                       a_idx, a_w, c->t_dev);
   } else {
     const size_t lds_topk = (size_t)kRouterWaves * (64 + m.E) * sizeof(float);
     hipLaunchKernelGGL(topk_kernel, tgrid, dim3(kRouterThreads), lds_topk, s, c->logits, T, m.E, m.k, m.router_norm, c->topk_idx, c->topk_w,
-                       a_idx, a_w);
+                       a_idx, a_w, c->t_dev);
   }
   int rc = launch_status("topk_kernel");
   if (rc) return rc;
   hipLaunchKernelGGL(union_worklist_kernel, dim3(1), dim3(kRouterThreads), lds, s, c->topk_idx, T, m.k, m.E, use_masks,
                      c->union_ids, c->union_count, c->hist, c->offsets, c->perm, c->inv, c->status, c->work, c->tok_of_pos,
-                     c->sched, m.n_shared, tile_tokens);
+                     c->sched, m.n_shared, tile_tokens, c->t_dev);
   return launch_status("union_worklist_kernel");
 }
 
 int launch_argmax_reduce(const float* val, const int32_t* idx, int nstrips, int ld, int T, int32_t* next, float* best_out,
-                         hipStream_t s) {
-  hipLaunchKernelGGL(argmax_reduce_kernel, dim3(T), dim3(256), 0, s, val, idx, nstrips, ld, next, best_out);
+                         const int32_t* t_dev, hipStream_t s) {
+  hipLaunchKernelGGL(argmax_reduce_kernel, dim3(T), dim3(256), 0, s, val, idx, nstrips, ld, next, best_out, t_dev);
   return launch_status("argmax_reduce_kernel");
 }
 
@@ -1566,10 +1578,10 @@ int launch_combine(const evict_ctx* c, int T, void* out, const void* next_gain, 
   const evict_model_desc& m = c->m;
   if (m.dtype == EVICT_BF16)
     hipLaunchKernelGGL(combine_kernel<BF16>, dim3(T), dim3(256), 0, s, c->h, c->y, c->topk_w, c->inv, m.k, m.d,
-                       c->y + (size_t)T * m.k * m.d, m.n_shared, T, out, next_gain, m.rms_eps, c->x_norm);
+                       m.n_shared, T, out, next_gain, m.rms_eps, c->x_norm, c->t_dev);
   else
     hipLaunchKernelGGL(combine_kernel<F32>, dim3(T), dim3(256), 0, s, c->h, c->y, c->topk_w, c->inv, m.k, m.d,
-                       c->y + (size_t)T * m.k * m.d, m.n_shared, T, out, next_gain, m.rms_eps, c->x_norm);
+                       m.n_shared, T, out, next_gain, m.rms_eps, c->x_norm, c->t_dev);
   return launch_status("combine_kernel");
 }
 

@@ -24,7 +24,7 @@ int launch_attention(const evict_ctx* c, const void* kc, const void* vc, long lo
 int launch_router(const evict_ctx* c, const void* gain, const void* wg, int T, const evict_layer_aux* aux, hipStream_t s);
 int launch_topk_union(const evict_ctx* c, int T, const evict_layer_aux* aux, int tile_tokens, hipStream_t s);
 int launch_argmax_reduce(const float* val, const int32_t* idx, int nstrips, int ld, int T, int32_t* next, float* best_out,
-                         hipStream_t s);
+                         const int32_t* t_dev, hipStream_t s);
 int launch_combine(const evict_ctx* c, int T, void* out, const void* next_gain, hipStream_t s);
 
 }  // namespace evict

@@ -377,8 +377,9 @@ constexpr int kSampWaves = kSampThreads / 64;
 // Per node: maximum of the logits and the sum of exp((logit - max) / temperature) over the
 // vocabulary -- the two numbers that turn any logit of the row into a probability.
 __global__ __launch_bounds__(kSampThreads) void softmax_stats_kernel(const float* __restrict__ logits, int V, float inv_temp,
-                                                                     float* __restrict__ stats) {
+                                                                     float* __restrict__ stats, const int* __restrict__ t_dev) {
   __shared__ float s_red[kSampWaves];
+  if ((int)blockIdx.x >= dyn_tokens(t_dev, (int)gridDim.x)) return;  // (rows past the call's actual token count)
   const float* row = logits + (size_t)blockIdx.x * V;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   float m = -INFINITY;
@@ -870,7 +871,7 @@ int evict_accept_path_sampled(evict_ctx* ctx, const int32_t* tree_off, const int
   EVICT_REQUIRE(path_stride >= 1, EVICT_E_INVALID, "evict_accept_path_sampled: path_stride must be >= 1");
   const float inv_temp = 1.0f / temperature;
   hipStream_t s = (hipStream_t)stream;
-  hipLaunchKernelGGL(softmax_stats_kernel, dim3(T), dim3(kSampThreads), 0, s, logits, vocab, inv_temp, ctx->samp_stats);
+  hipLaunchKernelGGL(softmax_stats_kernel, dim3(T), dim3(kSampThreads), 0, s, logits, vocab, inv_temp, ctx->samp_stats, ctx->t_dev);
   int rc = launch_status("softmax_stats_kernel");
   if (rc) return rc;
   hipLaunchKernelGGL(accept_sampled_kernel, dim3(B), dim3(kSampThreads), 0, s, tree_off, parent, draft_tok, logits, vocab,
@@ -899,7 +900,7 @@ int evict_accept_path_sampled_noalloc(evict_ctx* ctx, const int32_t* tree_off, c
   const float inv_temp = 1.0f / temperature;
   hipStream_t s = (hipStream_t)stream;
   // (rows [0, T) of the statistics are written in full before they are read: nothing has to start at zero)
-  hipLaunchKernelGGL(softmax_stats_kernel, dim3(T), dim3(kSampThreads), 0, s, logits, vocab, inv_temp, stats);
+  hipLaunchKernelGGL(softmax_stats_kernel, dim3(T), dim3(kSampThreads), 0, s, logits, vocab, inv_temp, stats, ctx ? ctx->t_dev : nullptr);
   rc = launch_status("softmax_stats_kernel");
   if (rc) return rc;
   hipLaunchKernelGGL(accept_sampled_kernel, dim3(B), dim3(kSampThreads), 0, s, tree_off, parent, draft_tok, logits, vocab,

@@ -4,9 +4,16 @@ One iteration = what the target side does between two calls of the draft model (
 Sec. 3): EVICT prefix selection on the draft tree (optional), compaction of the kept nodes,
 verification through the layer stack, LM head, acceptance, and the commit of the accepted
 path to every layer's KV cache. Every step runs in the library's kernels; this module only
-sequences the calls and reads back two integers per iteration (the selected length, because
-the host sizes the verification launch by it -- the analogue of picking the pre-built graph for
-that length in Sec. 3.3 -- and the accepted length, which the drafter needs to go on).
+sequences the calls. Two ways of dispatching the selected length (Sec. 3.3):
+  * host dispatch: two integers are read back per iteration (the selected length, by which the
+    host sizes the verification launch -- the analogue of picking the pre-built graph for that
+    length -- and the accepted length, which the drafter needs to go on);
+  * device dispatch (`device_dispatch=True`): nothing is read back. The launches are sized for the
+    whole draft tree and the kernels take the selected length from the selection's own output on
+    the device (evict_dynamic_tokens); selected and accepted lengths of every iteration are kept
+    in device logs. The host only tracks an upper bound of the context length (it grows by the tree
+    size per iteration) until `resync()` reads the true one back; the whole iteration is one
+    sequence of launches and can be captured as one graph.
 """
 from __future__ import annotations
 
@@ -74,10 +81,69 @@ class SpecLoop:
         self.ctx_len = [z(1), z(1)]  # ping-pong: a commit reads one and writes the other
         self.cur = 0
         self.ctx_len_host = 0
+        # device dispatch: per-iteration logs of the selected and the accepted length (ring of `log_slots` entries)
+        self.log_slots = 1024
+        self.k_log, self.plen_log = z(self.log_slots), z(self.log_slots)
+        self.n_logged = 0
 
     def set_context_length(self, L: int):
         self.ctx_len[self.cur].fill_(L)
         self.ctx_len_host = L
+
+    def resync(self) -> int:
+        """Device dispatch: read the true context length back (one synchronising read) and drop the host's upper bound."""
+        self.ctx_len_host = int(self.ctx_len[self.cur].item())
+        return self.ctx_len_host
+
+    def iteration_on_device(self, d: DraftOnDevice, cost: Optional[torch.Tensor], rho: Optional[float] = None) -> int:
+        """One iteration with the selected length dispatched on the device: select -> gather -> stack -> LM head ->
+        accept -> commit with no host read-back (greedy acceptance). Returns the log slot of this iteration
+        (k_log / plen_log hold the selected and accepted lengths). Needs a cost table or rho (without a selection
+        the length is the tree size and there is nothing to dispatch)."""
+        if cost is None and rho is None:
+            raise ValueError("device dispatch needs a selection (cost table or rho)")
+        cfg, n = self.cfg, d.n
+        slot = self.n_logged % self.log_slots
+        k_star, plen = self.k_log[slot:slot + 1], self.plen_log[slot:slot + 1]
+        cl_in, cl_out = self.ctx_len[self.cur], self.ctx_len[self.cur ^ 1]
+        if cost is not None:
+            ev.evict_select_prefix(None, d.tree_off, d.parent, d.q, 1, n, cost, n, k_star, self.keep, self.new_parent, self.new_off, self.est)
+        else:
+            ev.evict_select_prefix_coverage(None, d.tree_off, d.parent, d.q, 1, n, rho, n, k_star, self.keep, self.new_parent,
+                                            self.new_off, self.est)
+        ev.evict_gather_rows(d.x, self.xg, cfg.d * self.eb, d.tree_off, self.new_off, self.keep, 1, n)
+        ev.evict_gather_rows(d.tok, self.tokg, 4, d.tree_off, self.new_off, self.keep, 1, n)
+        if d.target_next is not None:
+            ev.evict_gather_rows(d.target_next, self.tng, 4, d.tree_off, self.new_off, self.keep, 1, n)
+        bound = max(self.ctx_len_host, 1)
+        ev.evict_dynamic_tokens(self.ctx, self.new_off[1:])   # the count the kernels read: new_tree_off[B]
+        try:
+            if self.block_table is not None:
+                ev.evict_verify_stack_paged(self.ctx, self.layers, self.new_off, self.new_parent, 1, n, self.kc, self.vc, self.seq_stride,
+                                            self.head_stride, self.block_table, self.block_table.shape[-1], self.page_size, self.n_pages,
+                                            cl_in, bound, self.xg, self.out, self.k_new, self.v_new)
+            else:
+                ev.evict_verify_stack(self.ctx, self.layers, self.new_off, self.new_parent, 1, n, self.kc, self.vc, self.seq_stride,
+                                      self.head_stride, cl_in, bound, self.xg, self.out, self.k_new, self.v_new)
+            tn = self.tng
+            if self.lm_head is not None:
+                ev.evict_lm_head_argmax(self.ctx, self.out, self.lm_head[0], self.lm_head[1], n, self.next)
+                if d.target_next is None:
+                    tn = self.next
+        finally:
+            ev.evict_dynamic_tokens(self.ctx, None)
+        ev.evict_accept_path(None, self.new_off, self.new_parent, self.tokg, tn, 1, self.path, self.n_max, plen, self.bonus)
+        if self.block_table is not None:
+            ev.evict_kv_commit_stack_paged(self.ctx, self.dtype_code, cfg.Hkv, cfg.D, self.k_new, self.v_new, self.new_off, self.path,
+                                           self.n_max, plen, self.kc, self.vc, self.seq_stride, self.head_stride, self.block_table,
+                                           self.block_table.shape[-1], self.page_size, self.n_pages, cl_in, self.capacity, cl_out, 1)
+        else:
+            ev.evict_kv_commit_stack(self.ctx, self.dtype_code, cfg.Hkv, cfg.D, self.k_new, self.v_new, self.new_off, self.path,
+                                     self.n_max, plen, self.kc, self.vc, self.seq_stride, self.head_stride, cl_in, self.capacity, cl_out, 1)
+        self.cur ^= 1
+        self.ctx_len_host = min(self.ctx_len_host + n, self.capacity)   # upper bound: at most n nodes are accepted
+        self.n_logged += 1
+        return slot
 
     def iteration(self, d: DraftOnDevice, cost: Optional[torch.Tensor], log_lists: bool = False,
                   rho: Optional[float] = None, sample=None) -> IterationLog:

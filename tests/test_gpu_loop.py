@@ -186,3 +186,99 @@ def test_loop_with_acceptance_under_sampling(cfg_name, truncate):
         assert ev.evict_device_status(layers[0].ctx) == 0
     finally:
         layers[0].close()
+
+
+class _NoReadback:
+    """While active, any torch read-back to the host (.item(), .cpu(), .tolist(), .numpy()) raises."""
+
+    NAMES = ("item", "cpu", "tolist", "numpy")
+
+    def __enter__(self):
+        self.saved = {n: getattr(torch.Tensor, n) for n in self.NAMES}
+
+        def make(n):
+            def blocked(*a, **k):
+                raise AssertionError(f"host read-back through Tensor.{n}() inside the iteration")
+            return blocked
+        for n in self.NAMES:
+            setattr(torch.Tensor, n, make(n))
+        return self
+
+    def __exit__(self, *exc):
+        for n, f in self.saved.items():
+            setattr(torch.Tensor, n, f)
+        return False
+
+
+@pytest.mark.parametrize("cfg_name,page,use_rho", [("tiny", 0, False), ("mini_bf16", 0, False), ("mini_bf16", 16, False),
+                                                   ("tiny", 0, True)])
+def test_loop_with_device_dispatch_reads_nothing_back_and_matches_oracle(cfg_name, page, use_rho):
+    """Sec. 3.3: the selected length picks the verification without host logic in between. Every launch is sized for
+    the whole draft tree, the kernels take the length from the selection's output on the device, and nothing is read
+    back between selection and commit (the guard makes any read-back raise). After each iteration (outside that window)
+    the logs, the accepted path, the hidden states of the kept nodes and the context length are compared with the same
+    iteration composed from the oracle, exactly as for the host-dispatched loop."""
+    cfg = synth.CONFIGS[cfg_name]
+    n_layers, N, L0, cap, iters, seed = 2, 14, 37, 128, 5, 71
+    Ws = [synth.layer_weights(cfg, synth.philox(seed, 1 + l)) for l in range(n_layers)]
+    kv = [synth.kv_cache(cfg, L0, synth.philox(seed, 200 + l)) for l in range(n_layers)]
+    drafts = [synth.draft_iteration(cfg, N, seed, it, 0.4, vocab=500) for it in range(iters)]
+    cost = (1.0 + 0.35 * np.arange(N + 1)).astype(np.float32)
+    rho = 0.6
+    layers = [harness.DeviceLayer(cfg, Ws[0], max_tokens=N, max_batch=1, max_ctx=cap)]
+    for W in Ws[1:]:
+        layers.append(harness.DeviceLayer(cfg, W, 0, 0, 0, ctx=layers[0].ctx))
+    try:
+        tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+        if page:
+            pools = [synth.to_pages([kv[l][0]], [kv[l][1]], page, [cap], synth.philox(seed, 300)) for l in range(n_layers)]
+            kc = [harness.to_dev(p[0], cfg.dtype) for p in pools]
+            vc = [harness.to_dev(p[1], cfg.dtype) for p in pools]
+            loop = SpecLoop(cfg, layers[0].ctx, [l.weights for l in layers], kc, vc, cfg.Hkv * page * cfg.D, page * cfg.D, cap, N,
+                            block_table=harness.dev_i32(pools[0][2]), page_size=page, n_pages=pools[0][3])
+        else:
+            kc = [torch.zeros(1, cfg.Hkv, cap, cfg.D, dtype=tdt, device=DEV) for _ in range(n_layers)]
+            vc = [torch.zeros_like(k) for k in kc]
+            for l in range(n_layers):
+                kc[l][0, :, :L0] = harness.to_dev(kv[l][0], cfg.dtype)
+                vc[l][0, :, :L0] = harness.to_dev(kv[l][1], cfg.dtype)
+            loop = SpecLoop(cfg, layers[0].ctx, [l.weights for l in layers], kc, vc, cfg.Hkv * cap * cfg.D, cap * cfg.D, cap, N)
+        loop.set_context_length(L0)
+        cost_dev = torch.from_numpy(cost).to(DEV)
+        on_dev = [to_device(cfg, d) for d in drafts]
+        torch.cuda.synchronize()
+        K = [kv[l][0] for l in range(n_layers)]
+        V = [kv[l][1] for l in range(n_layers)]
+        L, lens, ks = L0, [], []
+        for it, d in enumerate(drafts):
+            with _NoReadback():
+                slot = loop.iteration_on_device(on_dev[it], None if use_rho else cost_dev, rho=rho if use_rho else None)
+            torch.cuda.synchronize()
+            # ---- the same iteration from the oracle's functions
+            sel = orc.select_prefix_coverage(d["parent"], d["q"], rho, N) if use_rho else orc.select_prefix(d["parent"], d["q"], cost, N)
+            keep, k = sel["keep"], sel["k_star"]
+            assert int(loop.k_log[slot].item()) == k
+            assert loop.keep[:k].tolist() == list(keep)
+            par, x, tok, tn = sel["new_parent"], d["x"][keep], d["tok"][keep], d["target_next"][keep]
+            outs, xin = [], x
+            for l in range(n_layers):
+                r = orc.verify_layer(cfg, Ws[l], np.array([0, k]), par, xin, [K[l]], [V[l]], np.array([L]))
+                outs.append(r)
+                xin = r["out"]
+            path, bonus = orc.accept_path(par, tok, tn)
+            plen = int(loop.plen_log[slot].item())
+            assert plen == len(path) and loop.path[0, :plen].tolist() == list(path) and int(loop.bonus.item()) == bonus
+            for l in range(n_layers):
+                K[l], V[l] = orc.kv_commit(K[l], V[l], orc.handoff(outs[l]["k_new"], cfg.dtype),
+                                           orc.handoff(outs[l]["v_new"], cfg.dtype), path)
+            L += len(path)
+            lens.append(len(path)); ks.append(k)
+            assert int(loop.ctx_len[loop.cur].item()) == L and loop.ctx_len_host >= L
+            tol = (1e-4 if cfg.dtype == "f32" else 2e-2) * 1.5
+            assert rel_l2(harness.to_host(loop.out[:k]), outs[-1]["out"]) < tol, f"iteration {it}"
+        assert max(lens) > 1 and min(ks) < N, (lens, ks)
+        assert loop.resync() == L
+        assert ev.evict_device_status(layers[0].ctx) == 0
+    finally:
+        ev.evict_dynamic_tokens(layers[0].ctx, None)
+        layers[0].close()
