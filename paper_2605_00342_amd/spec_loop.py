@@ -145,6 +145,25 @@ class SpecLoop:
         self.n_logged += 1
         return slot
 
+    def capture_on_device(self, d: DraftOnDevice, cost: Optional[torch.Tensor], rho: Optional[float] = None):
+        """Record one device-dispatched iteration as a single HIP graph (call on a non-default torch stream).
+        The tensors of `d` and `cost` are the graph's input buffers: refresh them in place before each
+        evict_graph_launch. The context-length bound baked into the launches is the cache capacity, so every
+        replay is covered; the new length is copied back into the buffer the graph reads, and every replay writes
+        log slot 0 (k_log[0], plen_log[0])."""
+        cur, logged = self.cur, self.n_logged
+        self.n_logged = 0
+        self.ctx_len_host = self.capacity
+        ev.evict_graph_begin(self.ctx)
+        try:
+            self.iteration_on_device(d, cost, rho)
+            self.ctx_len[cur].copy_(self.ctx_len[cur ^ 1])
+        finally:
+            graph = ev.evict_graph_end(self.ctx)
+        self.cur, self.n_logged = cur, logged
+        self.ctx_len_host = self.capacity
+        return graph
+
     def iteration(self, d: DraftOnDevice, cost: Optional[torch.Tensor], log_lists: bool = False,
                   rho: Optional[float] = None, sample=None) -> IterationLog:
         """cost: device cost table float32[n + 1] -> EVICT truncation; rho -> the cost-agnostic

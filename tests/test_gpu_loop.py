@@ -282,3 +282,59 @@ def test_loop_with_device_dispatch_reads_nothing_back_and_matches_oracle(cfg_nam
     finally:
         ev.evict_dynamic_tokens(layers[0].ctx, None)
         layers[0].close()
+
+
+def test_device_dispatched_iteration_is_one_graph():
+    """The whole iteration (selection, compaction, layer stack, acceptance, commit) recorded once and replayed with
+    refreshed inputs: every replay equals the same iteration made of direct calls (separate caches, same context
+    bound, so the launches are identical), with eager work of the other loop between the replays."""
+    cfg = synth.CONFIGS["mini_bf16"]
+    n_layers, N, L0, cap, iters, seed = 2, 14, 37, 128, 4, 75
+    Ws = [synth.layer_weights(cfg, synth.philox(seed, 1 + l)) for l in range(n_layers)]
+    kv = [synth.kv_cache(cfg, L0, synth.philox(seed, 200 + l)) for l in range(n_layers)]
+    drafts = [synth.draft_iteration(cfg, N, seed, it, 0.4, vocab=500) for it in range(iters)]
+    cost_dev = torch.from_numpy((1.0 + 0.35 * np.arange(N + 1)).astype(np.float32)).to(DEV)
+    layers = [harness.DeviceLayer(cfg, Ws[0], max_tokens=N, max_batch=1, max_ctx=cap)]
+    for W in Ws[1:]:
+        layers.append(harness.DeviceLayer(cfg, W, 0, 0, 0, ctx=layers[0].ctx))
+    try:
+        def make_loop():
+            kc = [torch.zeros(1, cfg.Hkv, cap, cfg.D, dtype=torch.bfloat16, device=DEV) for _ in range(n_layers)]
+            vc = [torch.zeros_like(k) for k in kc]
+            for l in range(n_layers):
+                kc[l][0, :, :L0] = harness.to_dev(kv[l][0], cfg.dtype)
+                vc[l][0, :, :L0] = harness.to_dev(kv[l][1], cfg.dtype)
+            lp = SpecLoop(cfg, layers[0].ctx, [l.weights for l in layers], kc, vc, cfg.Hkv * cap * cfg.D, cap * cfg.D, cap, N)
+            lp.set_context_length(L0)
+            return lp, kc, vc
+        eager, kc_e, vc_e = make_loop()
+        graphed, kc_g, vc_g = make_loop()
+        on_dev = [to_device(cfg, d) for d in drafts]
+        static = to_device(cfg, drafts[0])               # the graph's input buffers
+        side = torch.cuda.Stream()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            graph = graphed.capture_on_device(static, cost_dev)
+            side.synchronize()
+            for it in range(iters):
+                for name in ("parent", "q", "x", "tok", "target_next"):
+                    getattr(static, name).copy_(getattr(on_dev[it], name))
+                ev.evict_graph_launch(graph)
+                side.synchronize()
+                # the same iteration as direct calls on the other loop (eager work between the replays)
+                eager.ctx_len_host = cap
+                slot = eager.iteration_on_device(on_dev[it], cost_dev)
+                side.synchronize()
+                assert int(graphed.k_log[0].item()) == int(eager.k_log[slot].item())
+                assert int(graphed.plen_log[0].item()) == int(eager.plen_log[slot].item())
+                k = int(eager.k_log[slot].item())
+                assert torch.equal(graphed.out[:k], eager.out[:k]) and torch.equal(graphed.path, eager.path)
+                assert int(graphed.ctx_len[graphed.cur].item()) == int(eager.ctx_len[eager.cur].item())
+            for l in range(n_layers):
+                assert torch.equal(kc_g[l], kc_e[l]) and torch.equal(vc_g[l], vc_e[l])
+            assert int(eager.ctx_len[eager.cur].item()) > L0 + iters   # some draft tokens were accepted
+        ev.evict_graph_destroy(graph)
+        assert ev.evict_device_status(layers[0].ctx) == 0
+    finally:
+        ev.evict_dynamic_tokens(layers[0].ctx, None)
+        layers[0].close()
