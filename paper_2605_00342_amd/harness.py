@@ -46,6 +46,10 @@ class DeviceLayer:
         code = storage_code(cfg.dtype)
 
         def up(name):
+            # (a tensor already on the device in the storage dtype is used as it is: stacks whose layers are
+            # windows of one uploaded array pack straight from views of it)
+            if isinstance(W[name], torch.Tensor):
+                return W[name].contiguous()
             return to_dev(W[name], cfg.dtype, device)
 
         def empty(nbytes):

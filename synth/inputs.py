@@ -21,7 +21,7 @@ __all__ = [
     "ModelCfg", "CONFIGS", "philox", "round_to_bf16", "bf16_bits", "store",
     "tree_random_parents", "tree_eagle_style", "tree_bfs_random", "tree_chain", "tree_star",
     "draft_probs", "hidden_states", "layer_weights", "kv_cache", "cost_linear_in_union",
-    "plant_draft_tokens", "make_case", "concat_trees", "to_pages",
+    "plant_draft_tokens", "make_case", "concat_trees", "to_pages", "stack_weights_windowed", "kv_windowed",
 ]
 
 
@@ -254,6 +254,39 @@ def layer_weights(cfg: ModelCfg, g: np.random.Generator) -> Dict[str, np.ndarray
         W["ws_up"] = w(cfg.n_shared, cfg.F, cfg.d)
         W["ws_down"] = w(cfg.n_shared, cfg.d, cfg.F)
     return W
+
+
+def stack_weights_windowed(cfg: ModelCfg, n_layers: int, g: np.random.Generator):
+    """Weights of an n_layers-deep stack at full size without generating n_layers independent layers (620 M values
+    each at the Qwen3 shape): every matrix is drawn once with n_layers - 1 extra rows (experts for the expert
+    tensors), and layer l is the window [l, l + rows) of it. The layers are distinct matrices of the same
+    distribution (layer l + 1 is layer l shifted by one row / one expert, with one new row / expert), each a
+    zero-copy view. Returns (big, layers): the big arrays by name and the per-layer dicts of views."""
+    s, x = cfg.w_std, n_layers - 1
+
+    def w(*shape):
+        return store(g.standard_normal(shape, dtype=np.float32) * np.float32(s), cfg.dtype)
+
+    big = {
+        "wq": w(cfg.Hq * cfg.D + x, cfg.d), "wk": w(cfg.Hkv * cfg.D + x, cfg.d), "wv": w(cfg.Hkv * cfg.D + x, cfg.d),
+        "wo": w(cfg.d + x, cfg.Hq * cfg.D), "wg": w(cfg.E + x, cfg.d),
+        "w_gate": w(cfg.E + x, cfg.F, cfg.d), "w_up": w(cfg.E + x, cfg.F, cfg.d), "w_down": w(cfg.E + x, cfg.d, cfg.F),
+        "g_attn": store(1.0 + 0.1 * g.standard_normal(cfg.d + x), cfg.dtype),
+        "g_moe": store(1.0 + 0.1 * g.standard_normal(cfg.d + x), cfg.dtype),
+    }
+    if cfg.n_shared:
+        big["ws_gate"] = w(cfg.n_shared + x, cfg.F, cfg.d)
+        big["ws_up"] = w(cfg.n_shared + x, cfg.F, cfg.d)
+        big["ws_down"] = w(cfg.n_shared + x, cfg.d, cfg.F)
+    layers = [{name: a[l:l + a.shape[0] - x] for name, a in big.items()} for l in range(n_layers)]
+    return big, layers
+
+
+def kv_windowed(cfg: ModelCfg, L: int, n_layers: int, g: np.random.Generator):
+    """KV caches of n_layers layers for one sequence as windows over positions of one cache drawn with
+    n_layers - 1 extra positions: layer l reads positions [l, l + L). Returns lists of K, V views [Hkv, L, D]."""
+    K, V = kv_cache(cfg, L + n_layers - 1, g)
+    return [K[:, l:l + L] for l in range(n_layers)], [V[:, l:l + L] for l in range(n_layers)]
 
 
 def kv_cache(cfg: ModelCfg, L: int, g: np.random.Generator):

@@ -15,7 +15,7 @@ ev = pytest.importorskip("paper_2605_00342_amd")
 from paper_2605_00342_amd import harness  # noqa: E402
 
 DEV = "cuda:0"
-TOL = {"f32": 1e-4, "bf16": 2e-2}
+from tolerances import TOL, stack_tol  # noqa: E402,F401
 NL = 2
 
 
@@ -149,7 +149,7 @@ def test_paged_stack_commit_and_second_iteration(cfg_name, n, Ls, P):
         Kv = [[orc.paged_view(pools[l][0], table[b], Ls[b], P) for b in range(B)] for l in range(NL)]
         Vv = [[orc.paged_view(pools[l][1], table[b], Ls[b], P) for b in range(B)] for l in range(NL)]
         ref = oracle_stack(cfg, Ws, Kv, Vv, tree_off, parent, case["x"], case["ctx_len"])
-        assert rel_l2(harness.to_host(out_p), ref[-1]["out"]) < 1.5 * TOL[cfg.dtype]
+        assert rel_l2(harness.to_host(out_p), ref[-1]["out"]) < stack_tol(cfg.dtype, NL)
 
         # ---- commit of one accepted path per sequence into the pages
         paths = deepest_paths(tree_off, parent)
@@ -192,7 +192,7 @@ def test_paged_stack_commit_and_second_iteration(cfg_name, n, Ls, P):
         x2 = np.concatenate([synth.hidden_states(p, cfg.d, 0.5, g, cfg.dtype) for p in pars2])
         out2, _, _ = d.run_paged(off2, par2, ctx_len2, int(new_len.max()), x2)
         ref2 = oracle_stack(cfg, Ws, K2, V2, off2, par2, x2, new_len)
-        assert rel_l2(harness.to_host(out2), ref2[-1]["out"]) < 1.5 * TOL[cfg.dtype]
+        assert rel_l2(harness.to_host(out2), ref2[-1]["out"]) < stack_tol(cfg.dtype, NL)
         assert ev.evict_device_status(d.ctx) == 0
     finally:
         d.close()
