@@ -14,11 +14,13 @@ struct F32 { typedef float elem; static constexpr int kBytes = 4; static constex
 struct BF16 { typedef uint16_t elem; static constexpr int kBytes = 2; static constexpr int kBlockElems = 32; };
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
-// round-to-nearest-even; inputs are finite on this path
-__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
-  uint32_t u = __float_as_uint(f);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
+// round-to-nearest-even, by the hardware conversion of gfx950 (v_cvt_pk_bf16_f32)
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) { return __builtin_bit_cast(uint16_t, (__bf16)f); }
+// two values rounded and packed into one dword (lo in the low half): one instruction
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  const bf16x2_t v = {(__bf16)lo, (__bf16)hi};
+  return __builtin_bit_cast(uint32_t, v);
 }
 
 template <typename ST> __device__ __forceinline__ float load_elem(const void* p, size_t i);
@@ -41,8 +43,8 @@ template <> __device__ __forceinline__ void store4<F32>(void* p, size_t i, f32x4
 }
 template <> __device__ __forceinline__ void store4<BF16>(void* p, size_t i, f32x4 v) {
   uint2 o;
-  o.x = (uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16);
-  o.y = (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16);
+  o.x = pack_bf16x2(v[0], v[1]);
+  o.y = pack_bf16x2(v[2], v[3]);
   *reinterpret_cast<uint2*>((uint16_t*)p + i) = o;
 }
 template <typename ST> __device__ __forceinline__ f32x4 load4(const void* p, size_t i);

@@ -100,7 +100,7 @@ __global__ __launch_bounds__(256) void prep_kernel(const int32_t* __restrict__ t
           if (EB == 2) {
             const float a = __uint_as_float(raw[k][u] << 16) * rinv * __uint_as_float(graw[k][u] << 16);
             const float bb = __uint_as_float(raw[k][u] & 0xFFFF0000u) * rinv * __uint_as_float(graw[k][u] & 0xFFFF0000u);
-            packed[u] = (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(bb) << 16);
+            packed[u] = pack_bf16x2(a, bb);
           } else {
             packed[u] = __float_as_uint(__uint_as_float(raw[k][u]) * rinv * __uint_as_float(graw[k][u]));
           }
@@ -172,7 +172,7 @@ __global__ __launch_bounds__(256) void prep_kernel(const int32_t* __restrict__ t
         if (EB == 2) {
           const float a = __uint_as_float(raw[k][u] << 16) * rinv * __uint_as_float(graw[k][u] << 16);
           const float bb = __uint_as_float(raw[k][u] & 0xFFFF0000u) * rinv * __uint_as_float(graw[k][u] & 0xFFFF0000u);
-          packed[u] = (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(bb) << 16);
+          packed[u] = pack_bf16x2(a, bb);
         } else {
           packed[u] = __float_as_uint(__uint_as_float(raw[k][u]) * rinv * __uint_as_float(graw[k][u]));
         }
@@ -745,7 +745,7 @@ __global__ __launch_bounds__(kRouterThreads) void router_logits_kernel(
             if (EB == 2) {
               const float a = __uint_as_float(raw[i][u] << 16) * rinv * __uint_as_float(graw[i][u] << 16);
               const float b = __uint_as_float(raw[i][u] & 0xFFFF0000u) * rinv * __uint_as_float(graw[i][u] & 0xFFFF0000u);
-              packed[u] = (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
+              packed[u] = pack_bf16x2(a, b);
             } else {
               packed[u] = __float_as_uint(__uint_as_float(raw[i][u]) * rinv * __uint_as_float(graw[i][u]));
             }
@@ -1122,7 +1122,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const void* __restrict__ h
       if (EB == 2) {
 #pragma unroll
         for (int u = 0; u < 4; ++u)
-          raw[i][u] = (uint32_t)f32_to_bf16(acc[u >> 1][(2 * u) & 3]) | ((uint32_t)f32_to_bf16(acc[u >> 1][(2 * u + 1) & 3]) << 16);
+          raw[i][u] = pack_bf16x2(acc[u >> 1][(2 * u) & 3], acc[u >> 1][(2 * u + 1) & 3]);
       } else {
 #pragma unroll
         for (int u = 0; u < 4; ++u) raw[i][u] = __float_as_uint(acc[0][u]);
@@ -1159,7 +1159,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const void* __restrict__ h
         if (EB == 2) {
           const float a = __uint_as_float(raw[kk][u] << 16) * rinv * __uint_as_float(graw[u] << 16);
           const float bb = __uint_as_float(raw[kk][u] & 0xFFFF0000u) * rinv * __uint_as_float(graw[u] & 0xFFFF0000u);
-          packed[u] = (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(bb) << 16);
+          packed[u] = pack_bf16x2(a, bb);
         } else {
           packed[u] = __float_as_uint(__uint_as_float(raw[kk][u]) * rinv * __uint_as_float(graw[u]));
         }
