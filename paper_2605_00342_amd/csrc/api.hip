@@ -1,5 +1,6 @@
 // C-ABI entry points that own state or chain kernels: context, weight packing, the
 // per-layer verification pass (Sec. 2.1-2.2).
+#include <math.h>
 #include <string.h>
 
 #include <new>
@@ -86,6 +87,7 @@ int evict_create(evict_ctx** out, const evict_model_desc* m, int max_tokens, int
   A(&c.depth, T * 4);
   A(&c.seq_of, T * 4);
   A(&c.rope_cs, T * m->D * 4);
+  A(&c.rope_rev, (size_t)(m->D / 2) * 8);
   A(&c.x_norm, T * d * eb);
   A(&c.q, T * HqD * eb);
   A(&c.part_o, (size_t)c.max_splits * T * HqD * 4);
@@ -119,6 +121,12 @@ int evict_create(evict_ctx** out, const evict_model_desc* m, int max_tokens, int
   if (!rc) {
     he = hipMemset(c.status, 0, 16);
     if (he == hipSuccess) he = hipMemset(c.sched, 0, 16);
+    // rotary frequencies theta^(-2i/D) in revolutions per position, in double: the angle of a large
+    // position is reduced to one turn exactly before it meets the fp32 sine and cosine
+    std::vector<double> rev((size_t)(m->D / 2), 0.0);
+    if (m->rope_theta > 0.0f)
+      for (int i = 0; i < m->D / 2; ++i) rev[i] = pow((double)m->rope_theta, -2.0 * i / m->D) / (2.0 * M_PI);
+    if (he == hipSuccess) he = hipMemcpy(c.rope_rev, rev.data(), rev.size() * 8, hipMemcpyHostToDevice);
     if (he != hipSuccess) { set_error("hipMemset failed: %s", hipGetErrorString(he)); rc = EVICT_E_HIP; }
   }
   if (!rc) rc = kernels_setup(*m);

@@ -31,6 +31,7 @@ struct evict_ctx {
   int32_t* depth;        // [T]
   int32_t* seq_of;       // [T] sequence index of each token
   float* rope_cs;        // [T][D] cos (first half) and sin (second half) per token
+  double* rope_rev;      // [D/2] rotary frequencies in revolutions per position
   void* x_norm;          // [T][d] storage dtype
   void* q;               // [T][Hq*D]
   float* part_o;         // [splits+1][T][Hq][D]

@@ -46,7 +46,7 @@ template <typename ST>
 __global__ __launch_bounds__(256) void prep_kernel(const int32_t* __restrict__ tree_off, const int32_t* __restrict__ parent,
                                                    int B, const int32_t* __restrict__ ctx_len, int max_ctx,
                                                    const void* __restrict__ x, const void* __restrict__ gain, int d,
-                                                   float eps, float theta, int D, uint64_t* __restrict__ anc,
+                                                   float eps, const double* __restrict__ rope_rev, int D, uint64_t* __restrict__ anc,
                                                    int32_t* __restrict__ depth, int32_t* __restrict__ seq_of,
                                                    float* __restrict__ rope_cs, void* __restrict__ x_norm,
                                                    int32_t* __restrict__ status, int n_single, int norm_only,
@@ -110,6 +110,8 @@ __global__ __launch_bounds__(256) void prep_kernel(const int32_t* __restrict__ t
     }
     return;
   }
+  const int half = D >> 1;
+  const double rev_per_pos = tid < half ? rope_rev[tid] : 0.0;  // (requested early; used last)
   if (tid == 0) s_b = 0;
   __syncthreads();
   if (n_single == 0)
@@ -182,18 +184,14 @@ __global__ __launch_bounds__(256) void prep_kernel(const int32_t* __restrict__ t
   }
   __syncthreads();
   if (L < 0 || L > max_ctx) { L = L < 0 ? 0 : max_ctx; if (tid == 0) atomicOr(status, ST_BAD_CTXLEN); }
-  const int half = D >> 1;
   if (tid < half) {
-    float cv = 1.0f, sv = 0.0f;
-    if (theta > 0.0f) {
-      // angle = position * theta^(-2i/D), formed in double so that large positions stay exact
-      const double pos = (double)(L + s_depth);
-      const double ang = pos * exp2(-(2.0 * tid / D) * log2((double)theta));
-      cv = (float)cos(ang);
-      sv = (float)sin(ang);
-    }
-    rope_cs[(size_t)t * D + tid] = cv;
-    rope_cs[(size_t)t * D + half + tid] = sv;
+    // angle = position * theta^(-2i/D): the product in turns is formed in double and reduced to
+    // [-1/2, 1/2] there, so large positions stay exact; the hardware sine and cosine take turns.
+    // (A zero frequency table, theta = 0, gives the identity rotation.)
+    double rev = (double)(L + s_depth) * rev_per_pos;
+    rev -= rint(rev);
+    rope_cs[(size_t)t * D + tid] = __builtin_amdgcn_cosf((float)rev);
+    rope_cs[(size_t)t * D + half + tid] = __builtin_amdgcn_sinf((float)rev);
   }
 }
 
@@ -618,7 +616,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
 // over the splits is spread over more CUs). Empty splits carry max = -inf and their partial rows are never read
 // into the sum. The partial rows of the first splits are requested before the (max, sum) pairs
 // are reduced, so the two round trips overlap.
-constexpr int kMergeBatch = 16;
+constexpr int kMergeBatch = 17;  // 16 context splits + the draft-node split: the default shape of a 2048-key context
 
 template <typename ST>
 __global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict__ part_o, const float* __restrict__ part_ml,
@@ -1384,10 +1382,10 @@ int launch_prep(const evict_ctx* c, const int32_t* tree_off, const int32_t* pare
   const evict_model_desc& m = c->m;
   if (m.dtype == EVICT_BF16)
     hipLaunchKernelGGL(prep_kernel<BF16>, dim3(T), dim3(256), 0, s, tree_off, parent, B, ctx_len, max_ctx, x, gain, m.d,
-                       m.rms_eps, m.rope_theta, m.D, c->anc, c->depth, c->seq_of, c->rope_cs, c->x_norm, c->status, (B == 1 && !c->t_dev) ? T : 0, norm_only, c->t_dev);
+                       m.rms_eps, c->rope_rev, m.D, c->anc, c->depth, c->seq_of, c->rope_cs, c->x_norm, c->status, (B == 1 && !c->t_dev) ? T : 0, norm_only, c->t_dev);
   else
     hipLaunchKernelGGL(prep_kernel<F32>, dim3(T), dim3(256), 0, s, tree_off, parent, B, ctx_len, max_ctx, x, gain, m.d,
-                       m.rms_eps, m.rope_theta, m.D, c->anc, c->depth, c->seq_of, c->rope_cs, c->x_norm, c->status, (B == 1 && !c->t_dev) ? T : 0, norm_only, c->t_dev);
+                       m.rms_eps, c->rope_rev, m.D, c->anc, c->depth, c->seq_of, c->rope_cs, c->x_norm, c->status, (B == 1 && !c->t_dev) ? T : 0, norm_only, c->t_dev);
   return launch_status("prep_kernel");
 }
 
@@ -1473,7 +1471,7 @@ int launch_attention(const evict_ctx* c, const void* kc, const void* vc, long lo
     // batch: splits past a shorter sequence's context leave at once, so the grid is not what runs.)
     int want = (nw == 8 ? c->attn_target_wgs / 2 : c->attn_target_wgs) / (m.Hkv * B * rb_avg) - (B == 1 ? 1 : 0);
     want = want < 1 ? 1 : want;
-    // (the merge walks the splits of a row in batches of 16, one round trip each: beyond about 32 splits a
+    // (the merge walks the splits of a row in batches of 17, one round trip each: beyond about 32 splits a
     // second chunk per workgroup costs less than the extra batches; measured at 8 nodes, ctx 8192)
     want = want > 32 ? 32 : want;
     int cps = (chunks + want - 1) / want;  // chunks per split
