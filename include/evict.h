@@ -204,6 +204,31 @@ int evict_profile_cost_union(evict_ctx* ctx, const evict_layer_weights* layers, 
                              void* x_out, void* const* k_new, void* const* v_new, int reps, float* cost_host,
                              float* union_mean_host, void* stream);
 
+/* Cost model on the host (Sec. 3.2.3, App. A). These five take host arrays only, touch no GPU and
+ * need no context; they turn the profiling points above into the table evict_select_prefix divides by.
+ *
+ * evict_cost_expected_union_host: out[i] = M (1 - (1 - K/M)^t[i]), the number of distinct experts
+ *   t tokens activate under independent uniform top-K routing over M experts (App. A); t >= 0, not
+ *   necessarily whole. t, out [host] double[n].
+ * evict_cost_fit_surface_host: least squares of ms ~ a + b k + c U over n >= 3 points
+ *   (k[i], u[i], ms[i]) [host] double[n]; coef [host] double[3] receives (a, b, c), *rms (NULL = not
+ *   wanted) the root-mean-square residual. EVICT_E_INVALID when the points lie on one line of the
+ *   (k, U) plane (the two axes cannot be told apart: profile inputs of another routing spread).
+ * evict_cost_collapse_host: cost[kk] = a + b kk + c U(kk) for kk = 0..k_max, [host] float[k_max+1],
+ *   with U(kk) = union_of_k[kk] where kk < n_union and the entry is > 0 (a union measured at that
+ *   length), the closed form of App. A otherwise; entry 0 repeats entry 1. EVICT_E_INVALID when an
+ *   entry is not positive and finite (Eq. 10 divides by it).
+ * evict_cost_table_save_host / _load_host: the table as a text file, one header line
+ *   "evict-cost-table 1 <k_max>" and then k_max+1 values, one per line, with 9 significant digits
+ *   (a float survives the round trip). Load with cost = NULL only reports *k_max; otherwise capacity
+ *   (entries of `cost`) must be at least k_max+1, and every entry must be a positive number. */
+int evict_cost_expected_union_host(int n_experts, int top_k, const double* t, int n, double* out);
+int evict_cost_fit_surface_host(const double* k, const double* u, const double* ms, int n, double* coef, double* rms);
+int evict_cost_collapse_host(const double* coef, int k_max, int n_experts, int top_k, const double* union_of_k,
+                             int n_union, float* cost);
+int evict_cost_table_save_host(const char* path, const float* cost, int k_max);
+int evict_cost_table_load_host(const char* path, float* cost, int capacity, int* k_max);
+
 /* Union of activated experts over all verified nodes (Eq. 5) and the grouping it induces.
  *   topk_idx [dev] int32[T, k] with values in [0, E).
  *   union_ids [dev] int32[E]: activated experts ascending, tail -1; union_count [dev] int32[1];

@@ -19,7 +19,8 @@ __all__ = [
     "evict_profile_cost", "evict_graph_begin", "evict_graph_end", "evict_graph_launch", "evict_graph_destroy",
     "evict_lm_head_logits", "evict_accept_path_sampled", "evict_kv_commit", "evict_select_prefix_coverage", "evict_kv_commit_stack",
     "evict_profile_cost_union", "evict_verify_stack_paged", "evict_kv_commit_stack_paged", "evict_accept_path_sampled_noalloc",
-    "evict_dynamic_tokens", "STAGES", "EXPORTS",
+    "evict_dynamic_tokens", "evict_cost_expected_union_host", "evict_cost_fit_surface_host", "evict_cost_collapse_host",
+    "evict_cost_table_save_host", "evict_cost_table_load_host", "STAGES", "EXPORTS",
 ]
 
 EVICT_F32, EVICT_BF16 = 0, 1
@@ -34,7 +35,8 @@ EXPORTS = [
     "evict_profile_cost", "evict_graph_begin", "evict_graph_end", "evict_graph_launch", "evict_graph_destroy",
     "evict_lm_head_logits", "evict_accept_path_sampled", "evict_kv_commit", "evict_select_prefix_coverage", "evict_kv_commit_stack",
     "evict_profile_cost_union", "evict_verify_stack_paged", "evict_kv_commit_stack_paged", "evict_accept_path_sampled_noalloc",
-    "evict_dynamic_tokens",
+    "evict_dynamic_tokens", "evict_cost_expected_union_host", "evict_cost_fit_surface_host", "evict_cost_collapse_host",
+    "evict_cost_table_save_host", "evict_cost_table_load_host",
 ]
 STAGES = ["prep", "qkv", "attention", "oproj", "router", "union", "gateup", "down", "shared", "combine"]
 
@@ -114,6 +116,12 @@ def load():
     lib.evict_accept_path_sampled.argtypes = [vp, vp, vp, vp, vp, i32, C.c_float, vp, vp, i32, i32, vp, i32, vp, vp, vp]
     lib.evict_accept_path_sampled_noalloc.argtypes = lib.evict_accept_path_sampled.argtypes
     lib.evict_dynamic_tokens.argtypes = [vp, vp]
+    dp, fp = C.POINTER(C.c_double), C.POINTER(C.c_float)
+    lib.evict_cost_expected_union_host.argtypes = [i32, i32, dp, i32, dp]
+    lib.evict_cost_fit_surface_host.argtypes = [dp, dp, dp, i32, dp, dp]
+    lib.evict_cost_collapse_host.argtypes = [dp, i32, i32, i32, dp, i32, fp]
+    lib.evict_cost_table_save_host.argtypes = [C.c_char_p, fp, i32]
+    lib.evict_cost_table_load_host.argtypes = [C.c_char_p, fp, i32, C.POINTER(i32)]
     lib.evict_kv_commit.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, i32, vp, vp, vp, i64, i64, vp, i32, vp, i32, vp]
     lib.evict_kv_commit_stack.argtypes = [vp, i32, i32, i32, C.POINTER(vp), C.POINTER(vp), i32, vp, vp, i32, vp, C.POINTER(vp),
                                           C.POINTER(vp), i64, i64, vp, i32, vp, i32, vp]
@@ -260,6 +268,53 @@ def evict_accept_path_sampled(ctx, tree_off, parent, draft_tok, logits, vocab, t
 def evict_dynamic_tokens(ctx, count_dev) -> None:
     """count_dev: int32 device tensor (its first element is the count), an int device address, or None."""
     _check(load().evict_dynamic_tokens(ctx, count_dev if isinstance(count_dev, int) else _p(count_dev)))
+
+
+def _darr(values):
+    vals = [float(v) for v in values]
+    return (C.c_double * len(vals))(*vals), len(vals)
+
+
+def evict_cost_expected_union_host(n_experts: int, top_k: int, t) -> list:
+    """t: sequence of token counts; returns the expected union for each as a list of floats."""
+    tt, n = _darr(t)
+    out = (C.c_double * n)()
+    _check(load().evict_cost_expected_union_host(n_experts, top_k, tt, n, out))
+    return list(out)
+
+
+def evict_cost_fit_surface_host(k, u, ms):
+    """Returns ([a, b, c], rms) of ms ~ a + b k + c U."""
+    (kk, n), (uu, nu), (mm, nm) = _darr(k), _darr(u), _darr(ms)
+    if not n == nu == nm:
+        raise ValueError("evict_cost_fit_surface_host: k, u and ms differ in length")
+    coef, rms = (C.c_double * 3)(), C.c_double()
+    _check(load().evict_cost_fit_surface_host(kk, uu, mm, n, coef, C.byref(rms)))
+    return list(coef), rms.value
+
+
+def evict_cost_collapse_host(coef, k_max: int, n_experts: int, top_k: int, union_of_k=None) -> list:
+    """Returns C(k), k = 0..k_max, as a list of floats (float32 values)."""
+    cc, nc = _darr(coef)
+    if nc != 3:
+        raise ValueError("evict_cost_collapse_host: coef must hold (a, b, c)")
+    uu, nu = _darr(union_of_k) if union_of_k is not None else (None, 0)
+    out = (C.c_float * (k_max + 1))()
+    _check(load().evict_cost_collapse_host(cc, k_max, n_experts, top_k, uu, nu, out))
+    return list(out)
+
+
+def evict_cost_table_save_host(path: str, cost) -> None:
+    vals = [float(v) for v in cost]
+    _check(load().evict_cost_table_save_host(os.fsencode(path), (C.c_float * len(vals))(*vals), len(vals) - 1))
+
+
+def evict_cost_table_load_host(path: str) -> list:
+    k_max = C.c_int(0)
+    _check(load().evict_cost_table_load_host(os.fsencode(path), None, 0, C.byref(k_max)))
+    out = (C.c_float * (k_max.value + 1))()
+    _check(load().evict_cost_table_load_host(os.fsencode(path), out, k_max.value + 1, C.byref(k_max)))
+    return list(out)
 
 
 def evict_accept_path_sampled_noalloc(ctx, tree_off, parent, draft_tok, logits, vocab, temperature, u_node, u_bonus, B, T,

@@ -8,8 +8,9 @@ form under uniform routing. This module is the host logic between the two: it ta
 points (k, mean |union|, milliseconds) measured by evict_profile_cost_union on inputs of
 different routing spread, fits the surface  C(k, U) = a + b k + c U  by least squares, and
 collapses it to a table over k with the union expected at each k -- measured on the profiling
-inputs, or the closed form when no measurement covers that k. Plain numpy on a few hundred
-points; nothing here runs per decoding step.
+inputs, or the closed form when no measurement covers that k. The arithmetic (closed form, fit,
+collapse, table file) is the library's, behind its evict_cost_*_host entry points; this module only
+shapes arrays for them and drives the profiling runs. Nothing here runs per decoding step.
 """
 from __future__ import annotations
 
@@ -20,31 +21,26 @@ import numpy as np
 from . import binding as ev
 
 
+def _invalid_as_value_error(fn, *args):
+    try:
+        return fn(*args)
+    except ev.EvictError as e:
+        raise ValueError(str(e)) from None
+
+
 def expected_union(t, n_experts: int, top_k: int):
-    """Unique experts activated by t tokens under independent uniform routing (App. A):
-    M (1 - (1 - K/M)^t)."""
+    """Unique experts activated by t tokens under independent uniform routing (App. A)."""
     t = np.asarray(t, np.float64)
-    return n_experts * (1.0 - (1.0 - top_k / n_experts) ** t)
+    out = np.asarray(_invalid_as_value_error(ev.evict_cost_expected_union_host, n_experts, top_k, t.ravel()), np.float64)
+    return out.reshape(t.shape) if t.ndim else float(out[0])
 
 
 def fit_cost_surface(k: Sequence[float], union: Sequence[float], ms: Sequence[float]) -> Tuple[np.ndarray, float]:
     """Least-squares (a, b, c) of ms ~ a + b k + c U, and the root-mean-square residual.
     Needs at least three points that do not lie on one line in the (k, U) plane."""
     k, union, ms = (np.asarray(v, np.float64).ravel() for v in (k, union, ms))
-    if not (k.size == union.size == ms.size) or k.size < 3:
-        raise ValueError("fit_cost_surface: need >= 3 points with k, union and ms of one length")
-    A = np.stack([np.ones_like(k), k, union], axis=1)
-    if np.linalg.matrix_rank(A) < 3:
-        raise ValueError("fit_cost_surface: the (k, union) points lie on one line; profile inputs of another routing spread")
-    coef, *_ = np.linalg.lstsq(A, ms, rcond=None)
-    rms = float(np.sqrt(np.mean((A @ coef - ms) ** 2)))
-    return coef, rms
-
-
-def cost_surface(coef: np.ndarray, k_max: int, n_experts: int) -> np.ndarray:
-    """The fitted surface as a table float32[k_max + 1][n_experts + 1] over (k, U)."""
-    kk, uu = np.meshgrid(np.arange(k_max + 1), np.arange(n_experts + 1), indexing="ij")
-    return (coef[0] + coef[1] * kk + coef[2] * uu).astype(np.float32)
+    coef, rms = _invalid_as_value_error(ev.evict_cost_fit_surface_host, k, union, ms)
+    return np.asarray(coef, np.float64), rms
 
 
 def collapse_cost(coef: np.ndarray, k_max: int, n_experts: int, top_k: int,
@@ -52,16 +48,17 @@ def collapse_cost(coef: np.ndarray, k_max: int, n_experts: int, top_k: int,
     """C(k) = a + b k + c U(k) as float32[k_max + 1], the table evict_select_prefix consumes
     (entry 0 repeats entry 1: no prefix is empty). union_of_k[k] is the union expected at
     length k (entries <= 0 or missing fall back to the closed form of App. A)."""
-    u = expected_union(np.arange(k_max + 1), n_experts, top_k)
-    if union_of_k is not None:
-        m = np.asarray(union_of_k, np.float64)
-        n = min(m.size, k_max + 1)
-        u[:n] = np.where(m[:n] > 0, m[:n], u[:n])
-    cost = coef[0] + coef[1] * np.arange(k_max + 1) + coef[2] * u
-    cost[0] = cost[1] if k_max >= 1 else cost[0]
-    if not np.all(cost > 0):
-        raise ValueError("collapse_cost: the fitted surface is not positive over the table's range")
-    return cost.astype(np.float32)
+    return np.asarray(_invalid_as_value_error(ev.evict_cost_collapse_host, np.asarray(coef, np.float64), k_max, n_experts, top_k,
+                                              None if union_of_k is None else np.asarray(union_of_k, np.float64)), np.float32)
+
+
+def save_cost_table(path: str, cost: Sequence[float]) -> None:
+    """Writes C(k), k = 0..len(cost)-1, as the library's text format."""
+    _invalid_as_value_error(ev.evict_cost_table_save_host, path, cost)
+
+
+def load_cost_table(path: str) -> np.ndarray:
+    return np.asarray(_invalid_as_value_error(ev.evict_cost_table_load_host, path), np.float32)
 
 
 def profile_cost_surface(ctx, layers, input_sets: Iterable[dict], k_max: int, reps: int):

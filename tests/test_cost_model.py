@@ -35,8 +35,9 @@ def test_planted_surface_is_recovered_and_collapsed():
     coef_n, rms_n = cm.fit_cost_surface(k, u, ms * (1 + 0.01 * g.standard_normal(ms.size)))
     np.testing.assert_allclose(coef_n, coef, rtol=0.25)
     assert 0 < rms_n < 0.01
-    surf = cm.cost_surface(coef, 32, 128)
-    assert surf.shape == (33, 129) and abs(surf[7, 40] - (0.08 + 0.0004 * 7 + 0.0011 * 40)) < 1e-6
+    # the surface evaluated at one point: the collapse with the union pinned to 40 at every length
+    pinned = cm.collapse_cost(coef, 32, 128, 8, np.full(33, 40.0))
+    assert pinned.shape == (33,) and abs(pinned[7] - (0.08 + 0.0004 * 7 + 0.0011 * 40)) < 1e-6
     # closed-form unions, then measured ones for the lengths that have them
     c0 = cm.collapse_cost(coef, 32, 128, 8)
     want = 0.08 + 0.0004 * np.arange(33) + 0.0011 * cm.expected_union(np.arange(33), 128, 8)
@@ -66,3 +67,40 @@ def test_collapsed_table_makes_selection_stop_earlier_when_experts_cost_more():
     k_cheap = orc.select_prefix(case["parent"], case["q"], cheap, 8)["k_star"]
     k_dear = orc.select_prefix(case["parent"], case["q"], dear, 8)["k_star"]
     assert 1 <= k_dear <= k_cheap <= 8
+
+
+def test_cost_table_file_round_trip_and_refusals(tmp_path):
+    cost = cm.collapse_cost(np.array([0.08, 0.0004, 0.0011]), 64, 128, 8)
+    path = str(tmp_path / "cost.txt")
+    cm.save_cost_table(path, cost)
+    back = cm.load_cost_table(path)
+    assert back.dtype == np.float32 and np.array_equal(back, cost)  # 9 significant digits: bit-exact floats
+    head = open(path).read().splitlines()[0]
+    assert head == "evict-cost-table 1 64"
+    with pytest.raises(ValueError):
+        cm.load_cost_table(str(tmp_path / "absent.txt"))
+    bad = tmp_path / "bad.txt"
+    bad.write_text("evict-cost-table 1 2\n0.1\n-0.2\n0.3\n")  # a cost must be positive (Eq. 10 divides by it)
+    with pytest.raises(ValueError):
+        cm.load_cost_table(str(bad))
+    short = tmp_path / "short.txt"
+    short.write_text("evict-cost-table 1 3\n0.1\n0.2\n")
+    with pytest.raises(ValueError):
+        cm.load_cost_table(str(short))
+    other = tmp_path / "other.txt"
+    other.write_text("something else\n")
+    with pytest.raises(ValueError):
+        cm.load_cost_table(str(other))
+
+
+def test_fit_is_pinned_to_numpy_least_squares():
+    # the library's centred normal equations against a library least-squares solve on random points
+    g = np.random.default_rng(11)
+    k = g.integers(1, 129, 200).astype(np.float64)
+    u = 128 * (1 - (1 - 8 / 128) ** k) * g.uniform(0.5, 1.0, 200)
+    ms = 0.07 + 0.0005 * k + 0.0012 * u + 0.002 * g.standard_normal(200)
+    coef, rms = cm.fit_cost_surface(k, u, ms)
+    A = np.stack([np.ones_like(k), k, u], axis=1)
+    want, *_ = np.linalg.lstsq(A, ms, rcond=None)
+    np.testing.assert_allclose(coef, want, rtol=1e-8)
+    assert abs(rms - np.sqrt(np.mean((A @ want - ms) ** 2))) < 1e-12
