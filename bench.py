@@ -49,6 +49,8 @@ def parse():
     ap.add_argument("--model", default="qwen3", choices=["qwen3", "dsv2lite", "qwen3_235b_tp8", "ling_flash2_tp4"],
                     help="layer shape; the default line is the Qwen3-30B-A3B-shaped one")
     ap.add_argument("--tune", action="append", default=[], help="key=value launch-shape knob (evict_tune)")
+    ap.add_argument("--no-sweep", action="store_true",
+                    help="default workload: leave the tree-size curve out (profiling runs: every launch is then the named workload)")
     ap.add_argument("--sweep", action="store_true",
                     help="not the default line: one JSON line per (N, sigma) point, N in 1..128, sigma in {0.2, 0.5, 1.0}")
     ap.add_argument("--cost", default="profile", choices=["profile", "surface"],
@@ -530,7 +532,7 @@ def main():
     out["step_roofline"]["frac_of_read_ceiling_north_star"] = round(north_star_bytes / (ms_per_step * 1e-3) / 1e9 / ceiling, 4)
 
     # the metric's curve: the same step against the tree size N (same layer, context and child noise)
-    if default_workload:
+    if default_workload and not args.no_sweep:
         pts = []
         for Ns in (8, 16, 32, 64, 128):
             if Ns == N:
