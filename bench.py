@@ -43,7 +43,9 @@ def parse():
     ap.add_argument("--ctx-max", type=int, default=0,
                     help="with --batch: context lengths drawn uniformly from [--ctx, --ctx-max] per sequence")
     ap.add_argument("--sigma", type=float, default=0.5, help="child = parent + sigma*N(0,1)")
-    ap.add_argument("--copies", type=int, default=4, help="weight copies rotated between steps")
+    ap.add_argument("--copies", type=int, default=8,
+                    help="weight copies rotated between steps (8: the projection weights of all copies, 308 MB, do not fit the "
+                         "256 MB memory-side cache; with 4 they do and the projections read from it)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     ap.add_argument("--seed", type=int, default=1000)
     ap.add_argument("--model", default="qwen3", choices=["qwen3", "dsv2lite", "qwen3_235b_tp8", "ling_flash2_tp4"],
@@ -164,6 +166,9 @@ def spec_loop(args):
     cap = L0 + 4096
     base = synth.make_case("qwen3", n=N, L=16, seed=args.seed)
     first = harness.DeviceLayer(cfg, base["W"], max_tokens=N, max_batch=1, max_ctx=cap, vocab=vocab)
+    for kv in args.tune:
+        key, val = kv.split("=")
+        ev.evict_tune(first.ctx, key, int(val))
     # further layers: independent values of the same distribution, drawn directly in the packed layout
     # (packing is a permutation, so i.i.d. values packed or not are the same thing)
     gen = torch.Generator(device=dev).manual_seed(args.seed)

@@ -414,8 +414,8 @@ int evict_device_status(evict_ctx* ctx, int32_t* status_host, void* stream);
  *                     (2 from 64 tokens on)
  *   "dense_units"     consecutive 16-row strips a workgroup of the QKV projection takes, 0 = auto
  *   "moe_nt_loads"    expert weights fetched with non-temporal loads: 1, 0 (ordinary loads), 2 = auto;
- *   "dense_nt_loads"  the same for the QKV / output projections and the LM head (auto: when every strip is read
- *                     by a single workgroup)
+ *   "dense_nt_loads"  the same for the QKV / output projections and the LM head (auto: always for the
+ *                     projections; for the LM head when every strip is read by a single workgroup)
  *   "dense_kernel"    QKV / output projections: 0 contraction split over the wavefronts of a workgroup,
  *                     1 one strip per wavefront with the token operand in LDS (where its shape conditions
  *                     hold), 2 = auto (the latter from 128 or 256 tokens on); "dense_ntw" its token tiles
