@@ -51,6 +51,9 @@ def parse():
     ap.add_argument("--model", default="qwen3", choices=["qwen3", "dsv2lite", "qwen3_235b_tp8", "ling_flash2_tp4"],
                     help="layer shape; the default line is the Qwen3-30B-A3B-shaped one")
     ap.add_argument("--tune", action="append", default=[], help="key=value launch-shape knob (evict_tune)")
+    ap.add_argument("--device-count", type=int, default=0, metavar="T",
+                    help="on-device dispatch: the layer reads its token count (T, at most the tree size) from device memory "
+                         "and the call passes the tree size as the upper bound (evict_dynamic_tokens)")
     ap.add_argument("--no-sweep", action="store_true",
                     help="default workload: leave the tree-size curve out (profiling runs: every launch is then the named workload)")
     ap.add_argument("--sweep", action="store_true",
@@ -324,12 +327,16 @@ def main():
     case = synth.make_case(args.model, n=N, L=L, seed=args.seed, sigma=args.sigma, batch=B, L_list=L_list,
                            tree="auto" if args.model == "dsv2lite" else "eagle")
     T = int(case["tree_off"][-1])
-    default_workload = (B == 1 and args.model == "qwen3" and not args.kv_page and not args.tune and args.launch == "eager")
+    default_workload = (B == 1 and args.model == "qwen3" and not args.kv_page and not args.tune and args.launch == "eager"
+                        and not args.device_count)
     layer = harness.DeviceLayer(cfg, case["W"], max_tokens=max(T, 128) if default_workload else T, max_batch=B, max_ctx=L)
     dc = harness.DeviceCase(case, with_aux=True)
     for kv in args.tune:
         key, val = kv.split("=")
         ev.evict_tune(layer.ctx, key, int(val))
+    if args.device_count:
+        count_dev = torch.tensor([min(args.device_count, T)], dtype=torch.int32, device="cuda:0")
+        ev.evict_dynamic_tokens(layer.ctx, count_dev)
 
     # weight copies (same values, distinct addresses) so that no step finds its weights in cache
     names = ("wqkv", "wo", "wg", "w_gateup", "w_down")
