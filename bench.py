@@ -328,7 +328,7 @@ def main():
                            tree="auto" if args.model == "dsv2lite" else "eagle")
     T = int(case["tree_off"][-1])
     default_workload = (B == 1 and args.model == "qwen3" and not args.kv_page and not args.tune and args.launch == "eager"
-                        and not args.device_count)
+                        and not args.device_count and (N, L, args.sigma) == (32, 2048, 0.5))
     layer = harness.DeviceLayer(cfg, case["W"], max_tokens=max(T, 128) if default_workload else T, max_batch=B, max_ctx=L)
     dc = harness.DeviceCase(case, with_aux=True)
     for kv in args.tune:
