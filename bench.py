@@ -335,7 +335,11 @@ def main():
         key, val = kv.split("=")
         ev.evict_tune(layer.ctx, key, int(val))
     if args.device_count:
+        if B != 1:
+            sys.exit("bench.py --device-count: one sequence only")
+        # the first `count` nodes of a topologically numbered tree are a tree: offsets and the device word agree on it
         count_dev = torch.tensor([min(args.device_count, T)], dtype=torch.int32, device="cuda:0")
+        dc.tree_off = torch.tensor([0, min(args.device_count, T)], dtype=torch.int32, device="cuda:0")
         ev.evict_dynamic_tokens(layer.ctx, count_dev)
 
     # weight copies (same values, distinct addresses) so that no step finds its weights in cache

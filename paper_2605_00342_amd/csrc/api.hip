@@ -304,11 +304,16 @@ static int verify_layer_impl(evict_ctx* ctx, const evict_layer_weights* w, const
   // token tiles per workgroup in the dense projections: two from 64 tokens on (measured)
   const int nt_dense = ctx->dense_nt ? ctx->dense_nt : (T >= 64 ? 2 : 1);
   const int dense_tiles = (T + 16 * nt_dense - 1) / (16 * nt_dense);
+  // QKV takes two token tiles per workgroup already from 17 tokens on: as fast as two workgroups per strip when
+  // both tiles are full (9.6 vs 9.8 us at 32 tokens), and when the count in device memory turns out to fill one
+  // tile only, there is no second grid half whose workgroups leave at once (7.3 vs 9.4 us at 7 of 32 tokens)
+  const int nt_qkv = ctx->dense_nt ? ctx->dense_nt : (T > 16 ? 2 : 1);
+  const int qkv_tiles = (T + 16 * nt_qkv - 1) / (16 * nt_qkv);
   // QKV: a workgroup takes several consecutive strips, so its token operand is fetched once and its weight loads
   // run ahead across the strips (measured: 2 strips with one token tile, 4 with more; the output projection, with a
   // third of the strips and twice the contraction length, is better left at one)
-  const int qkv_units = ctx->dense_units ? ctx->dense_units : (dense_tiles >= 2 ? 4 : 2);
-  auto dense_grid = [&](int units, int du) { return (((units + du - 1) / du + 7) / 8) * 8 * dense_tiles; };
+  const int qkv_units = ctx->dense_units ? ctx->dense_units : (qkv_tiles >= 2 ? 4 : 2);
+  auto dense_grid = [&](int units, int du, int tiles) { return (((units + du - 1) / du + 7) / 8) * 8 * tiles; };
   // Projection weights are fetched with non-temporal loads. (Measured on a 48-layer stack, where no weight is
   // read twice within an iteration: never slower than ordinary loads at 1, 2 and 4 token tiles per strip, 5 % faster
   // per iteration at one tile. A benchmark that rotates few enough weight copies to keep the projections of all
@@ -338,12 +343,12 @@ static int verify_layer_impl(evict_ctx* ctx, const evict_layer_weights* w, const
     a.out0 = ctx->q; a.out1 = k_new; a.out2 = v_new;
     a.rope_cs = ctx->rope_cs;
     a.Hq = m.Hq; a.Hkv = m.Hkv; a.D = m.D;
-    a.dense_tiles = dense_tiles;
+    a.dense_tiles = qkv_tiles;
     a.dense_units = qkv_units;
     a.nt_loads = dense_ntl;
     int ntw;
     rc = dense_strip_shape(a, &ntw) ? launch_gemm_dense_strip(m.dtype, EPI_QKV, a, ntw, s)
-                                         : launch_gemm(m.dtype, EPI_QKV, a, nt_dense, dense_grid(a.n_strips, qkv_units), s);
+                                         : launch_gemm(m.dtype, EPI_QKV, a, nt_qkv, dense_grid(a.n_strips, qkv_units, qkv_tiles), s);
     if (rc) return rc;
     if (aux && aux->q) EVICT_HIP_CHECK(hipMemcpyAsync(aux->q, ctx->q, (size_t)T * HqD * eb, hipMemcpyDeviceToDevice, s));
   }
@@ -369,7 +374,7 @@ static int verify_layer_impl(evict_ctx* ctx, const evict_layer_weights* w, const
     a.nt_loads = dense_ntl;
     int ntw;
     rc = dense_strip_shape(a, &ntw) ? launch_gemm_dense_strip(m.dtype, EPI_RESID, a, ntw, s)
-                                         : launch_gemm(m.dtype, EPI_RESID, a, nt_dense, dense_grid(a.n_strips, 1), s);
+                                         : launch_gemm(m.dtype, EPI_RESID, a, nt_dense, dense_grid(a.n_strips, 1, dense_tiles), s);
     if (rc) return rc;
     if (aux && aux->h) EVICT_HIP_CHECK(hipMemcpyAsync(aux->h, ctx->h, (size_t)T * m.d * eb, hipMemcpyDeviceToDevice, s));
   }
