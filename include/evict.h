@@ -204,6 +204,12 @@ int evict_profile_cost_union(evict_ctx* ctx, const evict_layer_weights* layers, 
                              void* x_out, void* const* k_new, void* const* v_new, int reps, float* cost_host,
                              float* union_mean_host, void* stream);
 
+/* Running total of |union| (Eq. 5) over every layer pass this context has run since the last reset: what the
+ * cost of a step grew with (Sec. 2.2), for callers that time stacks themselves. total_host [host] int64[1]
+ * (the device counter is 32 bits wide and wraps: reset it before a measurement); reset != 0 clears the
+ * counter behind the read. Synchronises the stream; not inside a graph capture. */
+int evict_union_total(evict_ctx* ctx, int64_t* total_host, int reset, void* stream);
+
 /* Cost model on the host (Sec. 3.2.3, App. A). These five take host arrays only, touch no GPU and
  * need no context; they turn the profiling points above into the table evict_select_prefix divides by.
  *
@@ -219,15 +225,18 @@ int evict_profile_cost_union(evict_ctx* ctx, const evict_layer_weights* layers, 
  *   length), the closed form of App. A otherwise; entry 0 repeats entry 1. EVICT_E_INVALID when an
  *   entry is not positive and finite (Eq. 10 divides by it).
  * evict_cost_table_save_host / _load_host: the table as a text file, one header line
- *   "evict-cost-table 1 <k_max>" and then k_max+1 values, one per line, with 9 significant digits
- *   (a float survives the round trip). Load with cost = NULL only reports *k_max; otherwise capacity
- *   (entries of `cost`) must be at least k_max+1, and every entry must be a positive number. */
+ *   "evict-cost-table 1 <k_max> <key>" and then k_max+1 values, one per line, with 9 significant digits
+ *   (a float survives the round trip). key: what the table was profiled for (device, model shape,
+ *   storage type, context length ...), 1 to 255 printable characters without white space, chosen by the
+ *   caller. Load refuses a file whose key differs from expect_key (NULL = any key). Load with
+ *   cost = NULL only reports *k_max; otherwise capacity (entries of `cost`) must be at least k_max+1, and
+ *   every entry must be a positive number. */
 int evict_cost_expected_union_host(int n_experts, int top_k, const double* t, int n, double* out);
 int evict_cost_fit_surface_host(const double* k, const double* u, const double* ms, int n, double* coef, double* rms);
 int evict_cost_collapse_host(const double* coef, int k_max, int n_experts, int top_k, const double* union_of_k,
                              int n_union, float* cost);
-int evict_cost_table_save_host(const char* path, const float* cost, int k_max);
-int evict_cost_table_load_host(const char* path, float* cost, int capacity, int* k_max);
+int evict_cost_table_save_host(const char* path, const float* cost, int k_max, const char* key);
+int evict_cost_table_load_host(const char* path, const char* expect_key, float* cost, int capacity, int* k_max);
 
 /* Union of activated experts over all verified nodes (Eq. 5) and the grouping it induces.
  *   topk_idx [dev] int32[T, k] with values in [0, E).

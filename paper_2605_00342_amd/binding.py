@@ -20,7 +20,7 @@ __all__ = [
     "evict_lm_head_logits", "evict_accept_path_sampled", "evict_kv_commit", "evict_select_prefix_coverage", "evict_kv_commit_stack",
     "evict_profile_cost_union", "evict_verify_stack_paged", "evict_kv_commit_stack_paged", "evict_accept_path_sampled_noalloc",
     "evict_dynamic_tokens", "evict_cost_expected_union_host", "evict_cost_fit_surface_host", "evict_cost_collapse_host",
-    "evict_cost_table_save_host", "evict_cost_table_load_host", "STAGES", "EXPORTS",
+    "evict_cost_table_save_host", "evict_cost_table_load_host", "evict_union_total", "STAGES", "EXPORTS",
 ]
 
 EVICT_F32, EVICT_BF16 = 0, 1
@@ -36,7 +36,7 @@ EXPORTS = [
     "evict_lm_head_logits", "evict_accept_path_sampled", "evict_kv_commit", "evict_select_prefix_coverage", "evict_kv_commit_stack",
     "evict_profile_cost_union", "evict_verify_stack_paged", "evict_kv_commit_stack_paged", "evict_accept_path_sampled_noalloc",
     "evict_dynamic_tokens", "evict_cost_expected_union_host", "evict_cost_fit_surface_host", "evict_cost_collapse_host",
-    "evict_cost_table_save_host", "evict_cost_table_load_host",
+    "evict_cost_table_save_host", "evict_cost_table_load_host", "evict_union_total",
 ]
 STAGES = ["prep", "qkv", "attention", "oproj", "router", "union", "gateup", "down", "shared", "combine"]
 
@@ -120,8 +120,9 @@ def load():
     lib.evict_cost_expected_union_host.argtypes = [i32, i32, dp, i32, dp]
     lib.evict_cost_fit_surface_host.argtypes = [dp, dp, dp, i32, dp, dp]
     lib.evict_cost_collapse_host.argtypes = [dp, i32, i32, i32, dp, i32, fp]
-    lib.evict_cost_table_save_host.argtypes = [C.c_char_p, fp, i32]
-    lib.evict_cost_table_load_host.argtypes = [C.c_char_p, fp, i32, C.POINTER(i32)]
+    lib.evict_cost_table_save_host.argtypes = [C.c_char_p, fp, i32, C.c_char_p]
+    lib.evict_cost_table_load_host.argtypes = [C.c_char_p, C.c_char_p, fp, i32, C.POINTER(i32)]
+    lib.evict_union_total.argtypes = [vp, C.POINTER(i64), i32, vp]
     lib.evict_kv_commit.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, i32, vp, vp, vp, i64, i64, vp, i32, vp, i32, vp]
     lib.evict_kv_commit_stack.argtypes = [vp, i32, i32, i32, C.POINTER(vp), C.POINTER(vp), i32, vp, vp, i32, vp, C.POINTER(vp),
                                           C.POINTER(vp), i64, i64, vp, i32, vp, i32, vp]
@@ -304,17 +305,25 @@ def evict_cost_collapse_host(coef, k_max: int, n_experts: int, top_k: int, union
     return list(out)
 
 
-def evict_cost_table_save_host(path: str, cost) -> None:
+def evict_cost_table_save_host(path: str, cost, key: str) -> None:
     vals = [float(v) for v in cost]
-    _check(load().evict_cost_table_save_host(os.fsencode(path), (C.c_float * len(vals))(*vals), len(vals) - 1))
+    _check(load().evict_cost_table_save_host(os.fsencode(path), (C.c_float * len(vals))(*vals), len(vals) - 1, key.encode()))
 
 
-def evict_cost_table_load_host(path: str) -> list:
+def evict_cost_table_load_host(path: str, expect_key: Optional[str] = None) -> list:
     k_max = C.c_int(0)
-    _check(load().evict_cost_table_load_host(os.fsencode(path), None, 0, C.byref(k_max)))
+    ek = None if expect_key is None else expect_key.encode()
+    _check(load().evict_cost_table_load_host(os.fsencode(path), ek, None, 0, C.byref(k_max)))
     out = (C.c_float * (k_max.value + 1))()
-    _check(load().evict_cost_table_load_host(os.fsencode(path), out, k_max.value + 1, C.byref(k_max)))
+    _check(load().evict_cost_table_load_host(os.fsencode(path), ek, out, k_max.value + 1, C.byref(k_max)))
     return list(out)
+
+
+def evict_union_total(ctx, reset: bool = False) -> int:
+    """Sum of the union sizes over every layer pass of this context since the last reset (synchronises)."""
+    total = C.c_int64(0)
+    _check(load().evict_union_total(ctx, C.byref(total), 1 if reset else 0, _stream()))
+    return total.value
 
 
 def evict_accept_path_sampled_noalloc(ctx, tree_off, parent, draft_tok, logits, vocab, temperature, u_node, u_bonus, B, T,

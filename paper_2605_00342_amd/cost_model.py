@@ -52,13 +52,20 @@ def collapse_cost(coef: np.ndarray, k_max: int, n_experts: int, top_k: int,
                                               None if union_of_k is None else np.asarray(union_of_k, np.float64)), np.float32)
 
 
-def save_cost_table(path: str, cost: Sequence[float]) -> None:
-    """Writes C(k), k = 0..len(cost)-1, as the library's text format."""
-    _invalid_as_value_error(ev.evict_cost_table_save_host, path, cost)
+def table_key(device: str, model: str, dtype: str, n_layers: int, ctx_len: int) -> str:
+    """The key a cost table is filed under: a table profiled on another device, model shape, storage type,
+    depth or context length does not describe this one's costs."""
+    return f"{device}:{model}:{dtype}:L{n_layers}:ctx{ctx_len}".replace(" ", "_")
 
 
-def load_cost_table(path: str) -> np.ndarray:
-    return np.asarray(_invalid_as_value_error(ev.evict_cost_table_load_host, path), np.float32)
+def save_cost_table(path: str, cost: Sequence[float], key: str) -> None:
+    """Writes C(k), k = 0..len(cost)-1, in the library's text format under `key`."""
+    _invalid_as_value_error(ev.evict_cost_table_save_host, path, cost, key)
+
+
+def load_cost_table(path: str, expect_key: Optional[str] = None) -> np.ndarray:
+    """Reads a table; with expect_key, a table filed under another key is refused."""
+    return np.asarray(_invalid_as_value_error(ev.evict_cost_table_load_host, path, expect_key), np.float32)
 
 
 def profile_cost_surface(ctx, layers, input_sets: Iterable[dict], k_max: int, reps: int):

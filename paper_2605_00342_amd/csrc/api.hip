@@ -624,6 +624,18 @@ int evict_profile_cost(evict_ctx* ctx, const evict_layer_weights* layers, int n_
                                   max_ctx_host, x_in, x_out, k_new, v_new, reps, cost_host, nullptr, stream);
 }
 
+int evict_union_total(evict_ctx* ctx, int64_t* total_host, int reset, void* stream) {
+  EVICT_REQUIRE(ctx && total_host, EVICT_E_INVALID, "evict_union_total: null argument");
+  EVICT_REQUIRE(!ctx->capturing, EVICT_E_INVALID, "evict_union_total synchronises: not inside a graph capture");
+  hipStream_t s = (hipStream_t)stream;
+  int32_t total = 0;
+  EVICT_HIP_CHECK(hipMemcpyAsync(&total, ctx->sched + 1, 4, hipMemcpyDeviceToHost, s));
+  if (reset) EVICT_HIP_CHECK(hipMemsetAsync(ctx->sched + 1, 0, 4, s));
+  EVICT_HIP_CHECK(hipStreamSynchronize(s));
+  *total_host = (int64_t)(uint32_t)total;
+  return EVICT_OK;
+}
+
 int evict_dynamic_tokens(evict_ctx* ctx, const int32_t* count_dev) {
   EVICT_REQUIRE(ctx, EVICT_E_INVALID, "evict_dynamic_tokens: null context");
   ctx->t_dev = count_dev;

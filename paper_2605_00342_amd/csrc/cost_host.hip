@@ -20,6 +20,15 @@ double union_closed_form(int M, int K, double t) { return M * (1.0 - pow(1.0 - (
 
 const char kTableMagic[] = "evict-cost-table";
 
+bool key_ok(const char* key) {
+  if (!key) return false;
+  const size_t n = strlen(key);
+  if (n < 1 || n > 255) return false;
+  for (size_t i = 0; i < n; ++i)
+    if (key[i] <= ' ' || key[i] > '~') return false;
+  return true;
+}
+
 }  // namespace
 
 extern "C" {
@@ -85,27 +94,35 @@ int evict_cost_collapse_host(const double* coef, int k_max, int n_experts, int t
   return EVICT_OK;
 }
 
-int evict_cost_table_save_host(const char* path, const float* cost, int k_max) {
+int evict_cost_table_save_host(const char* path, const float* cost, int k_max, const char* key) {
   EVICT_REQUIRE(path && cost && k_max >= 0, EVICT_E_INVALID, "evict_cost_table_save_host: bad argument");
+  EVICT_REQUIRE(key_ok(key), EVICT_E_INVALID, "evict_cost_table_save_host: the key must be 1..255 printable characters without white space");
+  for (int kk = 0; kk <= k_max; ++kk)
+    EVICT_REQUIRE(cost[kk] > 0.0f && isfinite(cost[kk]), EVICT_E_INVALID, "evict_cost_table_save_host: C(%d) = %g is not a positive number", kk, (double)cost[kk]);
   FILE* f = fopen(path, "w");
   EVICT_REQUIRE(f, EVICT_E_INVALID, "evict_cost_table_save_host: cannot open %s: %s", path, strerror(errno));
-  bool ok = fprintf(f, "%s 1 %d\n", kTableMagic, k_max) > 0;
+  bool ok = fprintf(f, "%s 1 %d %s\n", kTableMagic, k_max, key) > 0;
   for (int kk = 0; ok && kk <= k_max; ++kk) ok = fprintf(f, "%.9g\n", (double)cost[kk]) > 0;  // 9 digits: a float survives the round trip
   ok = (fclose(f) == 0) && ok;
   EVICT_REQUIRE(ok, EVICT_E_INVALID, "evict_cost_table_save_host: write to %s failed", path);
   return EVICT_OK;
 }
 
-int evict_cost_table_load_host(const char* path, float* cost, int capacity, int* k_max) {
+int evict_cost_table_load_host(const char* path, const char* expect_key, float* cost, int capacity, int* k_max) {
   EVICT_REQUIRE(path && k_max, EVICT_E_INVALID, "evict_cost_table_load_host: bad argument");
   FILE* f = fopen(path, "r");
   EVICT_REQUIRE(f, EVICT_E_INVALID, "evict_cost_table_load_host: cannot open %s: %s", path, strerror(errno));
-  char magic[32] = {0};
+  char magic[32] = {0}, key[256] = {0};
   int version = 0, km = -1;
-  const bool head = fscanf(f, "%31s %d %d", magic, &version, &km) == 3 && !strcmp(magic, kTableMagic) && version == 1 && km >= 0;
+  const bool head = fscanf(f, "%31s %d %d %255s", magic, &version, &km, key) == 4 && !strcmp(magic, kTableMagic) && version == 1 && km >= 0;
   if (!head) {
     fclose(f);
     set_error("evict_cost_table_load_host: %s is not a cost table of format 1", path);
+    return EVICT_E_INVALID;
+  }
+  if (expect_key && strcmp(expect_key, key)) {
+    fclose(f);
+    set_error("evict_cost_table_load_host: %s was profiled for \"%s\", not for \"%s\"", path, key, expect_key);
     return EVICT_E_INVALID;
   }
   *k_max = km;

@@ -72,19 +72,27 @@ def test_collapsed_table_makes_selection_stop_earlier_when_experts_cost_more():
 def test_cost_table_file_round_trip_and_refusals(tmp_path):
     cost = cm.collapse_cost(np.array([0.08, 0.0004, 0.0011]), 64, 128, 8)
     path = str(tmp_path / "cost.txt")
-    cm.save_cost_table(path, cost)
-    back = cm.load_cost_table(path)
+    key = cm.table_key("gfx950", "qwen3-30b-a3b", "bf16", 48, 2048)
+    cm.save_cost_table(path, cost, key)
+    back = cm.load_cost_table(path, key)
     assert back.dtype == np.float32 and np.array_equal(back, cost)  # 9 significant digits: bit-exact floats
+    assert np.array_equal(cm.load_cost_table(path), cost)           # any key
     head = open(path).read().splitlines()[0]
-    assert head == "evict-cost-table 1 64"
+    assert head == "evict-cost-table 1 64 gfx950:qwen3-30b-a3b:bf16:L48:ctx2048"
+    with pytest.raises(ValueError):  # profiled for another context length
+        cm.load_cost_table(path, cm.table_key("gfx950", "qwen3-30b-a3b", "bf16", 48, 8192))
+    with pytest.raises(ValueError):
+        cm.save_cost_table(path, cost, "two words")
+    with pytest.raises(ValueError):
+        cm.save_cost_table(path, [0.1, -1.0], key)
     with pytest.raises(ValueError):
         cm.load_cost_table(str(tmp_path / "absent.txt"))
     bad = tmp_path / "bad.txt"
-    bad.write_text("evict-cost-table 1 2\n0.1\n-0.2\n0.3\n")  # a cost must be positive (Eq. 10 divides by it)
+    bad.write_text("evict-cost-table 1 2 k\n0.1\n-0.2\n0.3\n")  # a cost must be positive (Eq. 10 divides by it)
     with pytest.raises(ValueError):
         cm.load_cost_table(str(bad))
     short = tmp_path / "short.txt"
-    short.write_text("evict-cost-table 1 3\n0.1\n0.2\n")
+    short.write_text("evict-cost-table 1 3 k\n0.1\n0.2\n")
     with pytest.raises(ValueError):
         cm.load_cost_table(str(short))
     other = tmp_path / "other.txt"

@@ -75,10 +75,15 @@ def oracle_stack(case, Ws, Ks, Vs, tree_off=None, parent=None, x=None):
 def test_stack_of_layers_matches_oracle(cfg_name, n, L, seed):
     case, Ws, Ks, Vs = make_stack(cfg_name, 3, n, L, seed)
     st = DeviceStack(case, Ws, Ks, Vs)
+    ev.evict_union_total(st.ctx, reset=True)
     st.run()
     torch.cuda.synchronize()
     ref = oracle_stack(case, Ws, Ks, Vs)
     assert rel_l2(harness.to_host(st.dc.out), ref[-1]["out"]) < stack_tol(case["cfg"].dtype, 3)
+    # the running total of |union| (Eq. 5) over the three layer passes: the oracle's routing, up to one near-tie flip per layer
+    total = ev.evict_union_total(st.ctx, reset=True)
+    assert abs(total - sum(int(r["union_count"]) for r in ref)) <= 3
+    assert ev.evict_union_total(st.ctx) == 0  # the read above cleared it
     for l in range(3):
         assert rel_l2(harness.to_host(st.cases[l].k_new), ref[l]["k_new"]) < stack_tol(case["cfg"].dtype, l + 1)
     assert ev.evict_device_status(st.ctx) == 0
