@@ -68,7 +68,14 @@ def parse():
     ap.add_argument("--loop", action="store_true",
                     help="not the default line: multi-iteration speculative loop with a synthetic calibrated drafter, "
                          "fixed-size verification against EVICT truncation (one JSON line each)")
-    ap.add_argument("--layers", type=int, default=8, help="--loop: layers in the stack (distinct weights each)")
+    ap.add_argument("--layers", type=int, default=0,
+                    help="--loop / --stack: layers in the stack, distinct weights each (0: 8 for --loop; the model's depth for "
+                         "--stack: 48 Qwen3-shaped, 27 DeepSeek-V2-Lite-shaped)")
+    ap.add_argument("--stack", action="store_true",
+                    help="not the default line: the whole target-side verification on the full-depth stack + LM head + acceptance, one "
+                         "JSON line per point. Default: tree sizes 8..128 at child noise 0.2 and 1.0, ctx 4096; with --model "
+                         "dsv2lite: N = 64, ctx 8192; with --batch B: B trees of --nodes nodes, contexts from [--ctx, --ctx-max], "
+                         "cost table profiled on the device, the batch verified whole and truncated by the selection")
     ap.add_argument("--iters", type=int, default=128, help="--loop: timed iterations per mode")
     ap.add_argument("--probe-copy", type=int, default=0, metavar="MiB",
                     help="not the default line: run the plain copy and read kernels on MiB bytes (counter "
@@ -165,7 +172,7 @@ def spec_loop(args):
 
     dev = "cuda:0"
     cfg = synth.CONFIGS["qwen3"]
-    N, L0, nl, vocab = args.nodes, args.ctx, args.layers, 151936
+    N, L0, nl, vocab = args.nodes, args.ctx, args.layers or 8, 151936
     cap = L0 + 4096
     base = synth.make_case("qwen3", n=N, L=16, seed=args.seed)
     first = harness.DeviceLayer(cfg, base["W"], max_tokens=N, max_batch=1, max_ctx=cap, vocab=vocab)
@@ -287,6 +294,186 @@ def spec_loop(args):
     first.close()
 
 
+def stack_bench(args):
+    """The whole target-side verification at full depth: layer stack, LM head + argmax, greedy acceptance
+    (and, for a batch, EVICT's selection and the row gather in front of it), against tree size and child
+    noise. Weights of the layers after the first are independent draws made directly in the packed layout
+    (packing is a permutation, so the distribution is the same); caches are N(0, 1)."""
+    import torch
+
+    import synth
+    import paper_2605_00342_amd as ev
+    from paper_2605_00342_amd import harness
+
+    dev = "cuda:0"
+    cfg = synth.CONFIGS[args.model]
+    nl = args.layers or {"qwen3": 48, "dsv2lite": 27}.get(args.model, 8)
+    vocab, B = 151936, args.batch
+    batched = B > 1
+    if batched:
+        L_list = [int(v) for v in synth.philox(args.seed, 950).integers(args.ctx, max(args.ctx_max, args.ctx) + 1, B)]
+        points = [(args.nodes, args.sigma)]
+    elif args.model == "dsv2lite":
+        L_list, points = [8192 if args.ctx == 2048 else args.ctx], [(64, args.sigma)]
+    else:
+        L_list = [4096 if args.ctx == 2048 else args.ctx]
+        points = [(n, s) for s in (0.2, 1.0) for n in (8, 16, 32, 64, 128)]
+    L = max(L_list)
+    n_max = max(n for n, _ in points)
+    T_max = n_max * B
+    tree = "bfs" if (args.model == "dsv2lite" or batched) else "eagle"
+    base = synth.make_case(args.model, n=n_max, L=16, seed=args.seed, tree=tree)
+    first = harness.DeviceLayer(cfg, base["W"], max_tokens=T_max, max_batch=B, max_ctx=L, vocab=vocab)
+    for kv in args.tune:
+        key, val = kv.split("=")
+        ev.evict_tune(first.ctx, key, int(val))
+    gen = torch.Generator(device=dev).manual_seed(args.seed)
+    names = ["wqkv", "wo", "wg", "w_gateup", "w_down"] + (["ws_gateup", "ws_down"] if cfg.n_shared else [])
+    keep, layers = [], [first.weights]
+    for _ in range(nl - 1):
+        cp = {n: (torch.randn(getattr(first, n).shape, generator=gen, device=dev) * 0.02).to(torch.bfloat16) for n in names}
+        keep.append(cp)
+        layers.append(ev.LayerWeights(first.g_attn.data_ptr(), first.g_moe.data_ptr(), cp["wqkv"].data_ptr(), cp["wo"].data_ptr(),
+                                      cp["wg"].data_ptr(), cp["w_gateup"].data_ptr(), cp["w_down"].data_ptr(),
+                                      cp["ws_gateup"].data_ptr() if cfg.n_shared else None,
+                                      cp["ws_down"].data_ptr() if cfg.n_shared else None))
+    wlm = (torch.randn(vocab * cfg.d, generator=gen, device=dev) * 0.02).to(torch.bfloat16)
+    g_final = torch.ones(cfg.d, dtype=torch.bfloat16, device=dev)
+    kc = [torch.randn(B, cfg.Hkv, L, cfg.D, generator=gen, device=dev).to(torch.bfloat16) for _ in range(nl)]
+    vc = [torch.randn(B, cfg.Hkv, L, cfg.D, generator=gen, device=dev).to(torch.bfloat16) for _ in range(nl)]
+    seq_stride, head_stride = cfg.Hkv * L * cfg.D, L * cfg.D
+    ctx_len = harness.dev_i32(np.array(L_list))
+    i32, f32, bf = torch.int32, torch.float32, torch.bfloat16
+    out = torch.zeros(T_max, cfg.d, dtype=bf, device=dev)
+    k_new = [torch.zeros(T_max, cfg.Hkv, cfg.D, dtype=bf, device=dev) for _ in range(nl)]
+    v_new = [torch.zeros(T_max, cfg.Hkv, cfg.D, dtype=bf, device=dev) for _ in range(nl)]
+    nxt = torch.zeros(T_max, dtype=i32, device=dev)
+    path = torch.zeros(B, 16, dtype=i32, device=dev)
+    plen, bonus = torch.zeros(B, dtype=i32, device=dev), torch.zeros(B, dtype=i32, device=dev)
+    eb = 2
+    expert_bytes = 3 * cfg.d * cfg.F * eb
+    kv_bytes = 2 * int(sum(L_list)) * cfg.Hkv * cfg.D * eb
+    proj_bytes = (2 * cfg.Hq * cfg.D * cfg.d + 2 * cfg.Hkv * cfg.D * cfg.d) * eb + cfg.E * cfg.d * eb
+    lm_bytes = vocab * cfg.d * eb
+
+    def measure(fn, reps):
+        """ms per call and mean union per layer over `reps` timed calls."""
+        for _ in range(3):
+            fn()
+        ev.evict_union_total(first.ctx, reset=True)
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / reps
+        return ms, ev.evict_union_total(first.ctx, reset=True) / (reps * nl)
+
+    def record(what, ms, U, T, extra):
+        ns = nl * ((U + cfg.n_shared) * expert_bytes + kv_bytes)
+        print(json.dumps({"metric": "verify_stack_latency_ms", "value": round(ms, 4), "unit": "ms", "what": what,
+                          "tokens_per_s": round(T / ms * 1e3, 1), "us_per_layer": round(ms * 1e3 / nl, 2),
+                          "mean_union_per_layer": round(U, 2), "north_star_bytes": int(ns),
+                          "hbm_frac_north_star": round(ns / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                          "hbm_frac_all_required": round((ns + nl * proj_bytes + lm_bytes) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                          **extra, "config": {"workload": f"{WORKLOAD_NAMES[args.model]}-shaped stack of {nl} layers + LM head "
+                                                          f"({vocab} rows) + greedy acceptance, ctx={L_list}",
+                                              "layers": nl}, "data": "synthetic", "dtype": "bf16"}), flush=True)
+
+    reps = max(args.steps // 10, 5)
+    if not batched:
+        for N, sigma in points:
+            g = synth.philox(args.seed, 100)
+            if tree == "eagle":
+                par, q = synth.tree_eagle_style(N, g)
+            else:
+                par = synth.tree_bfs_random(N, g)
+            x = harness.to_dev(synth.hidden_states(par, cfg.d, sigma, synth.philox(args.seed, 300), cfg.dtype), cfg.dtype)
+            toff, pard = harness.dev_i32(np.array([0, N])), harness.dev_i32(par)
+            tok = harness.dev_i32(synth.philox(args.seed, 900).integers(0, vocab, N).astype(np.int32))
+
+            def verify():
+                ev.evict_verify_stack(first.ctx, layers, toff, pard, 1, N, kc, vc, seq_stride, head_stride, ctx_len, L, x, out,
+                                      k_new, v_new)
+                ev.evict_lm_head_argmax(first.ctx, out, g_final, wlm, N, nxt, None, None)
+                ev.evict_accept_path(None, toff, pard, tok, nxt, 1, path, 16, plen, bonus)
+            ms, U = measure(verify, reps)
+            record("verify all nodes", ms, U, N, {"nodes": N, "sigma": sigma})
+        first.close()
+        return
+
+    # a batch: the whole step first, then the cost table profiled on the device, then the step truncated by the selection
+    N = args.nodes
+    case = synth.make_case(args.model, n=N, L=16, seed=args.seed, sigma=args.sigma, batch=B, L_list=[16] * B, tree="bfs")
+    T = int(case["tree_off"][-1])
+    x = harness.to_dev(case["x"], cfg.dtype)
+    toff, pard = harness.dev_i32(case["tree_off"]), harness.dev_i32(case["parent"])
+    q_dev = torch.from_numpy(case["q"]).to(dev)
+    tok = harness.dev_i32(synth.philox(args.seed, 900).integers(0, vocab, T).astype(np.int32))
+    def whole():
+        ev.evict_verify_stack(first.ctx, layers, toff, pard, B, T, kc, vc, seq_stride, head_stride, ctx_len, L, x, out, k_new, v_new)
+        ev.evict_lm_head_argmax(first.ctx, out, g_final, wlm, T, nxt, None, None)
+        ev.evict_accept_path(None, toff, pard, tok, nxt, B, path, 16, plen, bonus)
+    ms_all, U_all = measure(whole, reps)
+
+    # Cost table on the device (Sec. 3.2.3; App. C.5 applies the same rule per sequence of a batch): C(k) = latency
+    # of this batch's whole step (stack, LM head, acceptance) when every tree is cut to its first k nodes (parents
+    # precede children, so those are a tree), timed with events on the stream; the mean union per layer beside it
+    cost, umean = [0.0], [0.0]
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    off_h = case["tree_off"]
+    for k in range(1, N + 1):
+        rows = np.concatenate([np.arange(off_h[b], off_h[b] + k) for b in range(B)])
+        rd = torch.from_numpy(rows).to(dev)
+        xk, pk_, tk = x[rd].contiguous(), pard[rd].contiguous(), tok[rd].contiguous()
+        ok = harness.dev_i32(np.arange(B + 1) * k)
+
+        def cut():
+            ev.evict_verify_stack(first.ctx, layers, ok, pk_, B, B * k, kc, vc, seq_stride, head_stride, ctx_len, L, xk, out, k_new, v_new)
+            ev.evict_lm_head_argmax(first.ctx, out, g_final, wlm, B * k, nxt, None, None)
+            ev.evict_accept_path(None, ok, pk_, tk, nxt, B, path, 16, plen, bonus)
+        cut()
+        ev.evict_union_total(first.ctx, reset=True)
+        e0.record()
+        for _ in range(3):
+            cut()
+        e1.record()
+        torch.cuda.synchronize()
+        cost.append(e0.elapsed_time(e1) / 3)
+        umean.append(ev.evict_union_total(first.ctx, reset=True) / (3 * nl))
+    cost[0] = cost[1]
+    cost_dev = torch.tensor(cost, dtype=f32, device=dev)
+    ks = torch.zeros(B, dtype=i32, device=dev); keepn = torch.zeros(T, dtype=i32, device=dev)
+    npar = torch.zeros(T, dtype=i32, device=dev); noff = torch.zeros(B + 1, dtype=i32, device=dev)
+    est = torch.zeros(B, dtype=f32, device=dev); order = torch.zeros(T, dtype=i32, device=dev)
+    psum = torch.zeros(T, dtype=f32, device=dev)
+    x2, tok2 = torch.zeros_like(x), torch.zeros_like(tok)
+    ev.evict_select_prefix(None, toff, pard, q_dev, B, T, cost_dev, N, ks, keepn, npar, noff, est, order, psum)
+    torch.cuda.synchronize()
+    T2 = int(noff[B].item())   # outside the timed region: sizes the launches of the truncated step
+
+    def truncated():
+        ev.evict_select_prefix(None, toff, pard, q_dev, B, T, cost_dev, N, ks, keepn, npar, noff, est, order, psum)
+        ev.evict_gather_rows(x, x2, cfg.d * eb, toff, noff, keepn, B, T)
+        ev.evict_gather_rows(tok, tok2, 4, toff, noff, keepn, B, T)
+        ev.evict_verify_stack(first.ctx, layers, noff, npar, B, T2, kc, vc, seq_stride, head_stride, ctx_len, L, x2, out, k_new, v_new)
+        ev.evict_lm_head_argmax(first.ctx, out, g_final, wlm, T2, nxt, None, None)
+        ev.evict_accept_path(None, noff, npar, tok2, nxt, B, path, 16, plen, bonus)
+    ms_tr, U_tr = measure(truncated, reps)
+    # expected accepted tokens of a step (Eq. 8): the sum of the kept nodes' scores, per sequence, summed over the batch
+    ps, ksh, off_h = psum.cpu().numpy(), ks.cpu().numpy(), case["tree_off"]
+    s_full = float(sum(ps[off_h[b + 1] - 1] for b in range(B)))
+    s_kept = float(sum(ps[off_h[b] + int(ksh[b]) - 1] for b in range(B)))
+    common = {"sequences": B, "nodes_per_tree": N, "sigma": args.sigma,
+              "cost_table_ms": [round(c, 4) for c in cost[1:]], "profiled_union_at_k": [round(u, 2) for u in umean[1:]]}
+    record("batch verified whole", ms_all, U_all, T, {**common, "verified_nodes": T, "expected_accepted_tokens": round(s_full, 3),
+                                                      "expected_accepted_tokens_per_s": round(s_full / ms_all * 1e3, 1)})
+    record("batch truncated by the selection (Eq. 10), selection and gather inside the timed step", ms_tr, U_tr, T2,
+           {**common, "verified_nodes": T2, "k_star": [int(v) for v in ksh], "expected_accepted_tokens": round(s_kept, 3),
+            "expected_accepted_tokens_per_s": round(s_kept / ms_tr * 1e3, 1),
+            "speedup_in_expected_tokens_per_s": round((s_kept / ms_tr) / (s_full / ms_all), 4)})
+    first.close()
+
+
 WORKLOAD_NAMES = {"qwen3": "qwen3-30b-a3b", "dsv2lite": "deepseek-v2-lite",
                   "qwen3_235b_tp8": "qwen3-235b-a22b (one rank of TP=8)",
                   "ling_flash2_tp4": "ling-flash-2.0 (one rank of TP=4)"}
@@ -316,6 +503,9 @@ def main():
         return
     if args.loop:
         spec_loop(args)
+        return
+    if args.stack:
+        stack_bench(args)
         return
     cfg = synth.CONFIGS[args.model]
     N, L, B = args.nodes, args.ctx, args.batch

@@ -132,6 +132,7 @@ int evict_create(evict_ctx** out, const evict_model_desc* m, int max_tokens, int
   if (!rc) rc = kernels_setup(*m);
   c.timing = 0;
   c.moe_grid = 2048;
+  c.moe_pair_down = 2;
   c.moe_prefetch = 1;
   c.moe_down_kernel = 1;
   c.moe_gateup_kernel = 2;
@@ -441,7 +442,13 @@ static int verify_layer_impl(evict_ctx* ctx, const evict_layer_weights* w, const
     a.prefetch = ctx->moe_prefetch;
     a.wave_strip = ctx->moe_down_kernel;
     a.nt_loads = moe_nt;
-    rc = launch_gemm(m.dtype, EPI_F32, a, nt_exp, ctx->moe_grid, s);
+    // An expert with more than 16 tokens has several 16-token slots. The strip-per-wavefront kernel can take two
+    // consecutive ones of an expert through one weight stream (its operand of 32 tokens must fit the LDS budget of
+    // that kernel); measured to pay once there are enough tokens for such experts to be common.
+    const bool can_pair = nt_exp == 1 && a.wave_strip && a.n_strips % 8 == 0 && a.nkb * 2 <= 64;
+    const bool pair = can_pair && (ctx->moe_pair_down == 2 ? T >= 128 : ctx->moe_pair_down == 1);
+    a.pair_tiles = pair ? 1 : 0;
+    rc = launch_gemm(m.dtype, EPI_F32, a, pair ? 2 : nt_exp, ctx->moe_grid, s);
     if (rc) return rc;
   }
   EVICT_MARK(8);
@@ -698,6 +705,9 @@ int evict_tune(evict_ctx* ctx, const char* key, int value) {
   } else if (!strcmp(key, "moe_down_kernel")) {
     EVICT_REQUIRE(value == 0 || value == 1, EVICT_E_INVALID, "evict_tune: moe_down_kernel must be 0 or 1");
     ctx->moe_down_kernel = value;
+  } else if (!strcmp(key, "moe_pair_down")) {
+    EVICT_REQUIRE(value >= 0 && value <= 2, EVICT_E_INVALID, "evict_tune: moe_pair_down must be 0, 1 or 2 (auto)");
+    ctx->moe_pair_down = value;
   } else if (!strcmp(key, "attn_row_blocks")) {
     EVICT_REQUIRE(value >= 0 && value <= 64, EVICT_E_INVALID, "evict_tune: attn_row_blocks=%d out of range", value);
     ctx->attn_row_blocks = value;

@@ -53,6 +53,7 @@ struct GemmArgs {
   int wave_strip;        // host-side: grouped fp32-output GEMM may use gemm_wave_strip_kernel
   int nt_loads;          // host-side choice of the kernel variant: 1 = weights fetched with non-temporal loads
   int lds_dma;           // 1: strip-pair gate/up kernel stages its token operand with direct global-to-LDS loads
+  int pair_tiles;        // 1: gemm_wave_strip_kernel with two token tiles takes them from two consecutive 16-token records
   void* out0;            // QKV: q; RESID: h; SWIGLU: act; F32: y; ARGMAX: best value per (token, strip), [T][ldo]
   void* out1;            // QKV: k_new; ARGMAX: row index of the best value per (strip, token)
   void* out2;            // QKV: v_new
@@ -400,7 +401,15 @@ __global__ __launch_bounds__(WS * 64) __attribute__((amdgpu_waves_per_eu(4))) vo
     constexpr bool once = decltype(nt_tag)::value;
     const int slot = chunk / cpg, strip = (chunk - slot * cpg) * WS + w;
     const WorkRec* rec = a.work + slot;
-    const int p0 = rec->p0, ntok = rec->ntok, ex = rec->expert;
+    const int p0 = rec->p0, ex = rec->expert;
+    int ntok = rec->ntok;
+    if (NTW == 2 && a.pair_tiles) {
+      // The work list holds 16-token tiles; the tiles of an expert are consecutive records over consecutive
+      // positions. An even tile takes its successor along (one weight stream for both), an odd one is done.
+      const int ntile = rec->pad & 0xFFFF, ti = rec->pad >> 16;
+      if (ti & 1) return;
+      if (ti + 1 < ntile) ntok += rec[1].ntok;
+    }
     const u32x4* wbase = ex < a.n_routed ? a.W + (long long)ex * a.group_stride
                                          : a.W_shared + (long long)(ex - a.n_routed) * a.group_stride;
     // token operand first, weights behind it: the in-order load counter then lets the operand
@@ -426,7 +435,7 @@ __global__ __launch_bounds__(WS * 64) __attribute__((amdgpu_waves_per_eu(4))) vo
 #pragma unroll
         for (int i = 0; i < BMAX; ++i) {
           const int kb = kb0 + i * WS + w;
-          if (kb < nkb) bst[t][i] = *reinterpret_cast<const u32x4*>(xrow[t] + (long long)kb * 64);
+          if (kb < nkb && t * 16 < ntok) bst[t][i] = *reinterpret_cast<const u32x4*>(xrow[t] + (long long)kb * 64);
         }
       if (kb0 == 0) {
 #pragma unroll
@@ -439,7 +448,7 @@ __global__ __launch_bounds__(WS * 64) __attribute__((amdgpu_waves_per_eu(4))) vo
 #pragma unroll
         for (int i = 0; i < BMAX; ++i) {
           const int kb = kb0 + i * WS + w;
-          if (kb < nkb) s_b[((size_t)t * nkb + kb) * 64 + lane] = bst[t][i];
+          if (kb < nkb && t * 16 < ntok) s_b[((size_t)t * nkb + kb) * 64 + lane] = bst[t][i];
         }
     }
     lds_barrier();
@@ -454,7 +463,8 @@ __global__ __launch_bounds__(WS * 64) __attribute__((amdgpu_waves_per_eu(4))) vo
         const int j = j0 + jj;
         if (EXACT || j < nkb) {
 #pragma unroll
-          for (int t = 0; t < NTW; ++t) acc[t] = mfma_block<ST>(A[jj], s_b[((size_t)t * nkb + j) * 64 + lane], acc[t]);
+          for (int t = 0; t < NTW; ++t)
+            if (t == 0 || ntok > 16) acc[t] = mfma_block<ST>(A[jj], s_b[((size_t)t * nkb + j) * 64 + lane], acc[t]);
           if (j + WIN < nkb) A[jj] = once ? __builtin_nontemporal_load(wp + (j + WIN) * 64) : wp[(j + WIN) * 64];
           if (NKB > 0) __builtin_amdgcn_sched_barrier(0);  // keep the refill right behind its MFMA: the window stays full
         }

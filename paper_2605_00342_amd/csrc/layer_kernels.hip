@@ -321,7 +321,10 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
     float* __restrict__ part_o, float* __restrict__ part_ml, int n_single, int n_seq, const KvPaging pg,
     int32_t* __restrict__ status, int rb_major) {
   constexpr int LDK = D + 8;            // bf16 per K row in LDS (16-byte pad)
-  constexpr int LDV = kMfmaKeys + 4;    // bf16 per V^T row in LDS
+  constexpr int LDV = kMfmaKeys + 8;    // bf16 per V^T row in LDS: 68 dwords, 4 banks on from the row above. With that and the
+                                        // dword column of output tile dt XORed with 4*dt, both the transposing writes (lanes
+                                        // 16 rows apart in steps of 8 rows, 4 adjacent key pairs) and the 8-byte fragment reads
+                                        // (16 consecutive rows x 2 key-pair offsets per half wavefront) hit 64 different banks
   constexpr int CH = D / 8;             // 16-byte chunks per row
   constexpr int KT = kMfmaKeys / 16;    // key tiles
   constexpr int KB = D / 32;            // contraction blocks of Q K^T
@@ -404,7 +407,14 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
   f32x4 O[DT];
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt) O[dt] = f32x4{0, 0, 0, 0};
-  float m_run = -INFINITY, l_run = 0.0f;
+  // The row sums of the rounded weights come from the matrix cores as well: P times a column of ones, as one
+  // more output tile whose column 0 (lanes with ln == 0) holds the sums of rows kq*4 + j. (The vector unit is
+  // the busiest unit of this kernel; the matrix cores are not.)
+  f32x4 Lsum = {0, 0, 0, 0};
+  const uint32_t one2 = ln == 0 ? 0x3F803F80u : 0u;  // two bf16 ones in column 0
+  const u32x4 ones = {one2, one2, one2, one2};
+  float m_run = -INFINITY;  // running maximum of the scaled scores of row ln
+  const float c2 = scale * 1.44269504088896341f;  // raw score -> exponent of 2
 
   // K/V of a chunk travel global -> registers -> LDS, all loads issued before the first LDS
   // write so one memory round trip covers the chunk. Paged cache: the page ids of all of this
@@ -479,8 +489,9 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const uint32_t a = vreg0[it][i], bb = vreg1[it][i];
-        wv[(c * 8 + 2 * i) * (LDV / 2) + jp] = (a & 0xFFFFu) | (bb << 16);
-        wv[(c * 8 + 2 * i + 1) * (LDV / 2) + jp] = (a >> 16) | (bb & 0xFFFF0000u);
+        const int col = jp ^ ((c >> 1) << 2);  // rows c*8 .. c*8+7 belong to output tile c/2
+        wv[(c * 8 + 2 * i) * (LDV / 2) + col] = (a & 0xFFFFu) | (bb << 16);
+        wv[(c * 8 + 2 * i + 1) * (LDV / 2) + col] = (a >> 16) | (bb & 0xFFFF0000u);
       }
     }
   };
@@ -488,10 +499,13 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
   write_chunk(0);
   __syncthreads();
   int cur = 0;
-  for (int kc0 = key_begin; kc0 < key_end; kc0 += kMfmaKeys) {
+  // One chunk, compiled twice: for a whole chunk of cache keys (every key visible to every row: no mask, no test
+  // for masked scores) and for the ragged last chunk / the draft nodes under the ancestor mask. (With the choice
+  // left to run time the compiler keeps one body and pays the mask arithmetic on every chunk.)
+  auto run_chunk = [&](auto full_tag, int kc0) {
+    constexpr bool full = decltype(full_tag)::value;
     int nkeys = key_end - kc0;
     nkeys = nkeys > kMfmaKeys ? kMfmaKeys : nkeys;
-    const bool full = !tree_part && nkeys == kMfmaKeys;
     const bool more = kc0 + kMfmaKeys < key_end;
     if (NBUF == 2 && more) fetch_chunk(kc0 + kMfmaKeys);  // in flight during the MFMA work below
     const uint16_t* s_k = s_kv + (size_t)cur * BUF;
@@ -516,8 +530,9 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
       f32x4 acc = {0, 0, 0, 0};
 #pragma unroll
       for (int kb = 0; kb < KB; ++kb) acc = mfma_block<BF16>(kf[kt & 1][kb], Qf[kb], acc);
+      // (scores stay unscaled here: the scale is positive, so the maximum commutes with it, and it is applied
+      // inside the one multiply-add that feeds the exponential below)
       if (full) {  // a whole chunk of cache keys: every key is visible to every row
-        acc *= scale;
         mx = fmaxf(fmaxf(mx, fmaxf(acc[0], acc[1])), fmaxf(acc[2], acc[3]));
       } else {
 #pragma unroll
@@ -525,7 +540,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
           const int key = kt * 16 + kq * 4 + j;  // (the draft-node split has a single chunk: key = node index)
           const uint64_t word = key < 64 ? a0 : a1;
           const bool vis = key < nkeys && ((word >> (key & 63)) & 1ull);
-          acc[j] = vis ? acc[j] * scale : -INFINITY;
+          acc[j] = vis ? acc[j] : -INFINITY;
           mx = fmaxf(mx, acc[j]);
         }
       }
@@ -535,42 +550,45 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
     mx = fmaxf(mx, __shfl_xor(mx, 16));
     mx = fmaxf(mx, __shfl_xor(mx, 32));
     // online softmax: new running maximum, rescale of what has been accumulated so far
-    const float m_new = fmaxf(m_run, mx);
+    const float m_new = fmaxf(m_run, mx * scale);
     const float alpha = m_run == -INFINITY ? 0.0f : __expf(m_run - m_new);
-    float lsum = 0.0f;
+    const float moff = -m_new * 1.44269504088896341f;  // exp(s*scale - m) = 2^(s*c2 + moff)
     u32x4 Pf[KT / 2];
 #pragma unroll
     for (int kt = 0; kt < KT; ++kt) {
       uint32_t pk[2];
 #pragma unroll
       for (int jj = 0; jj < 2; ++jj) {
-        // (exp(-inf - m) is 0 for a masked key as long as m is finite, which a visible key guarantees;
+        // (2^(-inf) is 0 for a masked key as long as m is finite, which a visible key guarantees;
         // rows without any visible key in this chunk have m_new = -inf and need the explicit zero)
-        const float p0 = (full || S[kt][2 * jj] != -INFINITY) ? __expf(S[kt][2 * jj] - m_new) : 0.0f;
-        const float p1 = (full || S[kt][2 * jj + 1] != -INFINITY) ? __expf(S[kt][2 * jj + 1] - m_new) : 0.0f;
-        const uint16_t b0 = f32_to_bf16(p0), b1 = f32_to_bf16(p1);
-        lsum += bf16_to_f32(b0) + bf16_to_f32(b1);  // the sum uses the rounded weights the MFMA sees
-        pk[jj] = (uint32_t)b0 | ((uint32_t)b1 << 16);
+        const float p0 = (full || S[kt][2 * jj] != -INFINITY) ? __builtin_amdgcn_exp2f(fmaf(S[kt][2 * jj], c2, moff)) : 0.0f;
+        const float p1 = (full || S[kt][2 * jj + 1] != -INFINITY) ? __builtin_amdgcn_exp2f(fmaf(S[kt][2 * jj + 1], c2, moff)) : 0.0f;
+        pk[jj] = pack_bf16x2(p0, p1);
       }
       // contraction block kt/2 takes keys 32b + 4kq + {0..3} (even tile) and 32b + 16 + 4kq + {0..3} (odd tile)
       if (kt & 1) { Pf[kt >> 1][2] = pk[0]; Pf[kt >> 1][3] = pk[1]; }
       else        { Pf[kt >> 1][0] = pk[0]; Pf[kt >> 1][1] = pk[1]; }
     }
-    lsum += __shfl_xor(lsum, 16);
-    lsum += __shfl_xor(lsum, 32);
-    l_run = l_run * alpha + lsum;
-    m_run = m_new;
-    // O = O * alpha + P V: lane holds rows kq*4 + j (their alpha lives in lane kq*4 + j), column dt*16 + ln
-    f32x4 ar;
+    // O = O * alpha + P V: lane holds rows kq*4 + j (their alpha lives in lane kq*4 + j), column dt*16 + ln.
+    // Once the running maxima have settled no row is rescaled any more: the multiplications are skipped then.
+    if (__builtin_amdgcn_ballot_w64(m_new != m_run)) {
+      f32x4 ar;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) ar[j] = __shfl(alpha, kq * 4 + j);
+      for (int j = 0; j < 4; ++j) ar[j] = __shfl(alpha, kq * 4 + j);
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) O[dt] *= ar;
+      Lsum *= ar;
+    }
+    m_run = m_new;
+#pragma unroll
+    for (int bk = 0; bk < KT / 2; ++bk) Lsum = mfma_block<BF16>(Pf[bk], ones, Lsum);  // the sums use the rounded weights
     // V^T fragments of the next output tile are requested before the MFMAs of the current one
     auto load_v = [&](u32x4(&dst)[KT / 2], int dt) {
 #pragma unroll
       for (int bk = 0; bk < KT / 2; ++bk) {
-        const uint32_t* vrow = s_vt + (dt * 16 + ln) * (LDV / 2) + bk * 16 + kq * 2;
-        const uint2 lo2 = *reinterpret_cast<const uint2*>(vrow);
-        const uint2 hi2 = *reinterpret_cast<const uint2*>(vrow + 8);
+        const uint32_t* vrow = s_vt + (dt * 16 + ln) * (LDV / 2);
+        const uint2 lo2 = *reinterpret_cast<const uint2*>(vrow + ((bk * 16 + kq * 2) ^ (dt << 2)));
+        const uint2 hi2 = *reinterpret_cast<const uint2*>(vrow + ((bk * 16 + kq * 2 + 8) ^ (dt << 2)));
         dst[bk] = u32x4{lo2.x, lo2.y, hi2.x, hi2.y};
       }
     };
@@ -580,7 +598,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
     for (int dt = 0; dt < DT; ++dt) {
       if (dt + 1 < DT) load_v(vf[(dt + 1) & 1], dt + 1);
       __builtin_amdgcn_sched_barrier(0);
-      f32x4 acc = O[dt] * ar;
+      f32x4 acc = O[dt];
 #pragma unroll
       for (int bk = 0; bk < KT / 2; ++bk) acc = mfma_block<BF16>(Pf[bk], vf[dt & 1][bk], acc);
       O[dt] = acc;
@@ -597,19 +615,24 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
       write_chunk(0);
       __syncthreads();
     }
-  }
+  };
+  int kc0 = key_begin;
+  if (!tree_part)
+    for (; kc0 + kMfmaKeys <= key_end; kc0 += kMfmaKeys) run_chunk(std::true_type{}, kc0);
+  if (kc0 < key_end) run_chunk(std::false_type{}, kc0);  // (a cache range ends with at most one ragged chunk; the draft nodes are one chunk)
   if (!active) return;
   if (kq == 0 && rt * 16 + ln < R) {
     const size_t prow = ((size_t)split * T + t) * Hq + g * G + qh;
     part_ml[prow * 2] = m_run;
-    part_ml[prow * 2 + 1] = l_run;
   }
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const int r2 = rt * 16 + kq * 4 + j;
     if (r2 < R) {
       const int i2 = r2 / G, h2 = r2 - i2 * G;
-      float* dst = part_o + (((size_t)split * T + lo + i2) * Hq + g * G + h2) * D + ln;
+      const size_t prow = ((size_t)split * T + lo + i2) * Hq + g * G + h2;
+      if (ln == 0) part_ml[prow * 2 + 1] = Lsum[j];
+      float* dst = part_o + prow * D + ln;
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt) dst[dt * 16] = O[dt][j];
     }
@@ -1396,7 +1419,7 @@ int launch_prep(const evict_ctx* c, const int32_t* tree_off, const int32_t* pare
 }
 
 size_t attn_partial_lds_bytes(int D) { return sizeof(float) * (size_t)(2 * kAttnKeys * (D + 1) + 4 * D + 4 * 64); }
-size_t attn_mfma_lds_bytes(int D) { return 2 * (size_t)(kMfmaKeys * (D + 8) + D * (kMfmaKeys + 4)); }
+size_t attn_mfma_lds_bytes(int D) { return 2 * (size_t)(kMfmaKeys * (D + 8) + D * (kMfmaKeys + 8)); }
 // strips of 16 experts per workgroup and contraction split of the score kernel: enough
 // workgroups to spread W_g over the chip, 16 (strip, slice) items per workgroup
 int router_strips_per_wg(const evict_model_desc& m) {
