@@ -422,10 +422,42 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
   // outside the pool are replaced by page 0 and reported once.
   constexpr int KI = kMfmaKeys * CH / NT, VI = (kMfmaKeys / 2) * CH / NT;
   u32x4 kreg[KI], vreg0[VI], vreg1[VI];
+  // contiguous caches: where this thread's pieces sit relative to the first key of a chunk (elements), worked
+  // out once; per chunk only the chunk's base moves, and that is the same for every lane
+  unsigned koff[KI], voff[VI];
+#pragma unroll
+  for (int it = 0; it < KI; ++it) {
+    const int idx = tid + NT * it, j = idx / CH, c = idx - j * CH;
+    koff[it] = (unsigned)j * (unsigned)kstep + c * 8;
+  }
+#pragma unroll
+  for (int it = 0; it < VI; ++it) {
+    const int idx = tid + NT * it, jp = idx / CH, c = idx - jp * CH;
+    voff[it] = (unsigned)(2 * jp) * (unsigned)kstep + c * 8;
+  }
   auto fetch_chunk = [&](int kc0) {
     int nk = key_end - kc0;
     nk = nk > kMfmaKeys ? kMfmaKeys : nk;
     const bool paged = PAGED && !tree_part;
+    if (!paged) {
+      const uint16_t* kchunk = kbase + (size_t)kc0 * kstep;
+      const uint16_t* vchunk = vbase + (size_t)kc0 * kstep;
+#pragma unroll
+      for (int it = 0; it < KI; ++it) {
+        const int j = (tid + NT * it) / CH;
+        kreg[it] = u32x4{0, 0, 0, 0};  // keys past the end are zeros
+        if (j < nk) kreg[it] = *reinterpret_cast<const u32x4*>(kchunk + koff[it]);
+      }
+#pragma unroll
+      for (int it = 0; it < VI; ++it) {
+        const int jp = (tid + NT * it) / CH;
+        vreg0[it] = u32x4{0, 0, 0, 0};
+        vreg1[it] = u32x4{0, 0, 0, 0};
+        if (2 * jp < nk) vreg0[it] = *reinterpret_cast<const u32x4*>(vchunk + voff[it]);
+        if (2 * jp + 1 < nk) vreg1[it] = *reinterpret_cast<const u32x4*>(vchunk + voff[it] + kstep);
+      }
+      return;
+    }
     int pk[KI], pv0[VI], pv1[VI];
     if (paged) {
 #pragma unroll
@@ -533,7 +565,10 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
       // (scores stay unscaled here: the scale is positive, so the maximum commutes with it, and it is applied
       // inside the one multiply-add that feeds the exponential below)
       if (full) {  // a whole chunk of cache keys: every key is visible to every row
-        mx = fmaxf(fmaxf(mx, fmaxf(acc[0], acc[1])), fmaxf(acc[2], acc[3]));
+        // (maximum as the median with +inf: one instruction each, where fmaxf first spends one per operand on
+        // quieting signalling NaNs, which matrix-core outputs of finite inputs cannot be)
+        const float m01 = __builtin_amdgcn_fmed3f(acc[0], acc[1], INFINITY), m23 = __builtin_amdgcn_fmed3f(acc[2], acc[3], INFINITY);
+        mx = __builtin_amdgcn_fmed3f(mx, __builtin_amdgcn_fmed3f(m01, m23, INFINITY), INFINITY);
       } else {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
