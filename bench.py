@@ -294,8 +294,8 @@ def spec_loop(args):
     first.close()
 
 
-def stack_bench(args):
-    """The whole target-side verification at full depth: layer stack, LM head + argmax, greedy acceptance
+def stack_bench(args, collect=None):
+    """(collect: a list that takes the records instead of stdout.) The whole target-side verification at full depth: layer stack, LM head + argmax, greedy acceptance
     (and, for a batch, EVICT's selection and the row gather in front of it), against tree size and child
     noise. Weights of the layers after the first are independent draws made directly in the packed layout
     (packing is a permutation, so the distribution is the same); caches are N(0, 1)."""
@@ -370,14 +370,18 @@ def stack_bench(args):
 
     def record(what, ms, U, T, extra):
         ns = nl * ((U + cfg.n_shared) * expert_bytes + kv_bytes)
-        print(json.dumps({"metric": "verify_stack_latency_ms", "value": round(ms, 4), "unit": "ms", "what": what,
-                          "tokens_per_s": round(T / ms * 1e3, 1), "us_per_layer": round(ms * 1e3 / nl, 2),
-                          "mean_union_per_layer": round(U, 2), "north_star_bytes": int(ns),
-                          "hbm_frac_north_star": round(ns / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                          "hbm_frac_all_required": round((ns + nl * proj_bytes + lm_bytes) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                          **extra, "config": {"workload": f"{WORKLOAD_NAMES[args.model]}-shaped stack of {nl} layers + LM head "
-                                                          f"({vocab} rows) + greedy acceptance, ctx={L_list}",
-                                              "layers": nl}, "data": "synthetic", "dtype": "bf16"}), flush=True)
+        rec = {"metric": "verify_stack_latency_ms", "value": round(ms, 4), "unit": "ms", "what": what,
+               "tokens_per_s": round(T / ms * 1e3, 1), "us_per_layer": round(ms * 1e3 / nl, 2),
+               "mean_union_per_layer": round(U, 2), "north_star_bytes": int(ns),
+               "hbm_frac_north_star": round(ns / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+               "hbm_frac_all_required": round((ns + nl * proj_bytes + lm_bytes) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+               **extra, "config": {"workload": f"{WORKLOAD_NAMES[args.model]}-shaped stack of {nl} layers + LM head "
+                                               f"({vocab} rows) + greedy acceptance, ctx={L_list}",
+                                   "layers": nl}, "data": "synthetic", "dtype": "bf16"}
+        if collect is not None:
+            collect.append(rec)
+        else:
+            print(json.dumps(rec), flush=True)
 
     reps = max(args.steps // 10, 5)
     if not batched:
@@ -782,6 +786,15 @@ def main():
                         "hbm_frac_north_star": round(nsb / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
                         "tokens_per_s": round(Ns / (us * 1e-6), 1)})
         out["sweep"] = pts
+
+    # the same model at full depth: 48 layers + LM head + acceptance, tree sizes 8..128 at child noise 0.2 and 1.0,
+    # ctx 4096 (`bench.py --stack` prints these as lines of their own, with the other stack workloads)
+    if default_workload and not args.no_sweep:
+        recs = []
+        stack_bench(args, collect=recs)
+        out["stack_48_layers_ctx4096"] = [{"nodes": r["nodes"], "sigma": r["sigma"], "ms": r["value"], "tokens_per_s": r["tokens_per_s"],
+                                           "mean_union_per_layer": r["mean_union_per_layer"], "us_per_layer": r["us_per_layer"],
+                                           "hbm_frac_north_star": r["hbm_frac_north_star"]} for r in recs]
 
     if not args.no_cpu:
         from oracle import evict_oracle as orc

@@ -133,6 +133,7 @@ int evict_create(evict_ctx** out, const evict_model_desc* m, int max_tokens, int
   c.timing = 0;
   c.moe_grid = 2048;
   c.moe_pair_down = 2;
+  c.moe_down_ws = 0;
   c.moe_prefetch = 1;
   c.moe_down_kernel = 1;
   c.moe_gateup_kernel = 2;
@@ -448,6 +449,8 @@ static int verify_layer_impl(evict_ctx* ctx, const evict_layer_weights* w, const
     const bool can_pair = nt_exp == 1 && a.wave_strip && a.n_strips % 8 == 0 && a.nkb * 2 <= 64;
     const bool pair = can_pair && (ctx->moe_pair_down == 2 ? T >= 128 : ctx->moe_pair_down == 1);
     a.pair_tiles = pair ? 1 : 0;
+    // 16 strips per workgroup stage a slot's operand half as often: pays with many slots, costs with few (measured)
+    a.down_ws = ctx->moe_down_ws ? ctx->moe_down_ws : (T >= 128 ? 16 : 8);
     rc = launch_gemm(m.dtype, EPI_F32, a, pair ? 2 : nt_exp, ctx->moe_grid, s);
     if (rc) return rc;
   }
@@ -705,6 +708,9 @@ int evict_tune(evict_ctx* ctx, const char* key, int value) {
   } else if (!strcmp(key, "moe_down_kernel")) {
     EVICT_REQUIRE(value == 0 || value == 1, EVICT_E_INVALID, "evict_tune: moe_down_kernel must be 0 or 1");
     ctx->moe_down_kernel = value;
+  } else if (!strcmp(key, "moe_down_ws")) {
+    EVICT_REQUIRE(value == 0 || value == 8 || value == 16, EVICT_E_INVALID, "evict_tune: moe_down_ws must be 0 (auto), 8 or 16");
+    ctx->moe_down_ws = value;
   } else if (!strcmp(key, "moe_pair_down")) {
     EVICT_REQUIRE(value >= 0 && value <= 2, EVICT_E_INVALID, "evict_tune: moe_pair_down must be 0, 1 or 2 (auto)");
     ctx->moe_pair_down = value;

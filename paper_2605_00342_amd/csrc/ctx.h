@@ -18,7 +18,7 @@ struct evict_ctx {
   int max_tokens, max_batch, max_ctx;
   int device;
   int max_splits;        // KV splits the attention scratch is sized for (context part)
-  int moe_grid, moe_prefetch, moe_chunk_gateup, moe_chunk_down, moe_down_kernel, moe_gateup_kernel, moe_nt_loads, dense_nt_loads, dense_nt, dense_units, attn_target_wgs, attn_waves, moe_nt, attn_row_blocks, dense_kernel, dense_ntw, moe_lds_dma, lm_units, lm_nt, moe_pair_down;  // launch-shape knobs (evict_tune)
+  int moe_grid, moe_prefetch, moe_chunk_gateup, moe_chunk_down, moe_down_kernel, moe_gateup_kernel, moe_nt_loads, dense_nt_loads, dense_nt, dense_units, attn_target_wgs, attn_waves, moe_nt, attn_row_blocks, dense_kernel, dense_ntw, moe_lds_dma, lm_units, lm_nt, moe_pair_down, moe_down_ws;  // launch-shape knobs (evict_tune)
   int timing;            // record stage events in evict_verify_layer
   int timed_once;        // a timed call has been recorded
   int capturing;         // a stream capture opened by evict_graph_begin is in progress

@@ -53,6 +53,7 @@ struct GemmArgs {
   int wave_strip;        // host-side: grouped fp32-output GEMM may use gemm_wave_strip_kernel
   int nt_loads;          // host-side choice of the kernel variant: 1 = weights fetched with non-temporal loads
   int lds_dma;           // 1: strip-pair gate/up kernel stages its token operand with direct global-to-LDS loads
+  int down_ws;           // gemm_wave_strip_kernel: strips (wavefronts) per workgroup, 8 or 16
   int pair_tiles;        // 1: gemm_wave_strip_kernel with two token tiles takes them from two consecutive 16-token records
   void* out0;            // QKV: q; RESID: h; SWIGLU: act; F32: y; ARGMAX: best value per (token, strip), [T][ldo]
   void* out1;            // QKV: k_new; ARGMAX: row index of the best value per (strip, token)

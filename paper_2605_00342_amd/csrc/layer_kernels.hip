@@ -1294,7 +1294,11 @@ int launch_gemm_wave_strip(const GemmArgs& a, int grid, hipStream_t s) {
     else hipLaunchKernelGGL((gemm_wave_strip_kernel<ST, WIN_, NB_, true, NTW, 8, NKB_, false>), dim3(grid), dim3(8 * 64), lds, s, a);           \
   } while (0)
   // (windows sized to stay under 128 VGPRs together with the staged operand blocks)
-  if (nkb == 24) EVICT_WS_LAUNCH_NT(12, 3, 24);
+  if (nkb == 24 && a.down_ws == 16 && a.n_strips % 16 == 0 && ST::kBytes == 2) {
+    // 16 strips per workgroup: the slot's token operand is staged half as often
+    if (a.nt_loads) hipLaunchKernelGGL((gemm_wave_strip_kernel<ST, 12, 2, true, NTW, 16, 24, true>), dim3(grid), dim3(16 * 64), lds, s, a);
+    else hipLaunchKernelGGL((gemm_wave_strip_kernel<ST, 12, 2, true, NTW, 16, 24, false>), dim3(grid), dim3(16 * 64), lds, s, a);
+  } else if (nkb == 24) EVICT_WS_LAUNCH_NT(12, 3, 24);
   else if (nkb == 44 && NTW == 1) EVICT_WS_LAUNCH_NT(11, 6, 44);
   else if (nkb == 44) EVICT_WS_LAUNCH(11, 6 / NTW, true);
   else if (nkb % 16 == 0) EVICT_WS_LAUNCH_NT(16, 4 / NTW, 0);

@@ -193,6 +193,32 @@ def test_two_tile_work_list_slots():
     check_against_oracle(case, got)
 
 
+def test_down_projection_paired_slots_and_16_strip_workgroups():
+    """The down projection taking two consecutive 16-token slots of an expert through one weight stream, and its
+    workgroups of 16 strips, forced through evict_tune on small shapes: experts with 1..3 slots and ragged tails
+    (odd slot counts leave a last slot unpaired), shared experts, fp32 and bf16; the paired result is bit-identical
+    to the unpaired one (same products, same order per output)."""
+    cases = [synth.make_case("mini_bf16", n=40, L=16, seed=31, tree="star", sigma=0.0),      # 40 tokens per expert: 3 slots
+             synth.make_case("mini_bf16", n=128, L=64, seed=14, tree="eagle"),
+             synth.make_case("tiny", n=70, L=20, seed=34, tree="bfs"),
+             synth.make_case("mini_sigmoid", n=90, L=33, seed=35, tree="bfs")]
+    cfg = synth.ModelCfg("t_shared", "bf16", d=256, Hq=4, Hkv=4, D=64, E=16, k=3, F=96, n_shared=2, theta=1e4)
+    cases.append(synth.make_case("t_shared", n=50, L=50, seed=36, tree="bfs", cfg=cfg))
+    for case in cases:
+        plain = run_case(case, tune={"moe_pair_down": 0, "moe_down_ws": 8})
+        paired = run_case(case, tune={"moe_pair_down": 1, "moe_down_ws": 8})
+        check_against_oracle(case, paired)
+        assert np.array_equal(paired["out"], plain["out"])
+    # full-size layer (the 16-strip variant is built for its expert width): many tokens per expert
+    case = synth.make_case("qwen3", n=128, L=100, seed=39, sigma=0.2)
+    base = run_case(case, tune={"moe_pair_down": 0, "moe_down_ws": 8})
+    assert base["hist"].max() > 32
+    for tune in ({"moe_pair_down": 1, "moe_down_ws": 16}, {"moe_pair_down": 0, "moe_down_ws": 16}, {"moe_pair_down": 1, "moe_down_ws": 8}):
+        got = run_case(case, tune=tune)
+        check_against_oracle(case, got)
+        assert np.array_equal(got["out"], base["out"])
+
+
 def test_gateup_one_strip_pair_per_wavefront():
     """The second gate/up decomposition (token operand in LDS, one strip pair per wavefront), forced through
     evict_tune: multi-tile experts, shared experts, fp32 and bf16, 256 experts, and the full-size layer."""
