@@ -321,10 +321,11 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
     float* __restrict__ part_o, float* __restrict__ part_ml, int n_single, int n_seq, const KvPaging pg,
     int32_t* __restrict__ status, int rb_major) {
   constexpr int LDK = D + 8;            // bf16 per K row in LDS (16-byte pad)
-  constexpr int LDV = kMfmaKeys + 8;    // bf16 per V^T row in LDS: 68 dwords, 4 banks on from the row above. With that and the
-                                        // dword column of output tile dt XORed with 4*dt, both the transposing writes (lanes
-                                        // 16 rows apart in steps of 8 rows, 4 adjacent key pairs) and the 8-byte fragment reads
-                                        // (16 consecutive rows x 2 key-pair offsets per half wavefront) hit 64 different banks
+  constexpr int LDV = kMfmaKeys + 4;    // bf16 per V^T row in LDS: 66 dwords. The LDS serves 32 banks of 4 bytes per clock (bank
+                                        // conflict counters settle this, not the data sheet): a half wavefront's 8-byte fragment
+                                        // reads (16 consecutive rows, one key-pair offset) then hit 32 different banks, and with the
+                                        // dword column of output tile dt XORed with 2*dt so do the transposing 4-byte writes (lanes
+                                        // 8 rows apart over the 16 d-chunks, two adjacent key pairs per 32 lanes)
   constexpr int CH = D / 8;             // 16-byte chunks per row
   constexpr int KT = kMfmaKeys / 16;    // key tiles
   constexpr int KB = D / 32;            // contraction blocks of Q K^T
@@ -521,7 +522,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const uint32_t a = vreg0[it][i], bb = vreg1[it][i];
-        const int col = jp ^ ((c >> 1) << 2);  // rows c*8 .. c*8+7 belong to output tile c/2
+        const int col = jp ^ ((c >> 1) << 1);  // rows c*8 .. c*8+7 belong to output tile c/2
         wv[(c * 8 + 2 * i) * (LDV / 2) + col] = (a & 0xFFFFu) | (bb << 16);
         wv[(c * 8 + 2 * i + 1) * (LDV / 2) + col] = (a >> 16) | (bb & 0xFFFF0000u);
       }
@@ -622,8 +623,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
 #pragma unroll
       for (int bk = 0; bk < KT / 2; ++bk) {
         const uint32_t* vrow = s_vt + (dt * 16 + ln) * (LDV / 2);
-        const uint2 lo2 = *reinterpret_cast<const uint2*>(vrow + ((bk * 16 + kq * 2) ^ (dt << 2)));
-        const uint2 hi2 = *reinterpret_cast<const uint2*>(vrow + ((bk * 16 + kq * 2 + 8) ^ (dt << 2)));
+        const uint2 lo2 = *reinterpret_cast<const uint2*>(vrow + ((bk * 16 + kq * 2) ^ (dt << 1)));
+        const uint2 hi2 = *reinterpret_cast<const uint2*>(vrow + ((bk * 16 + kq * 2 + 8) ^ (dt << 1)));
         dst[bk] = u32x4{lo2.x, lo2.y, hi2.x, hi2.y};
       }
     };
@@ -1458,7 +1459,7 @@ int launch_prep(const evict_ctx* c, const int32_t* tree_off, const int32_t* pare
 }
 
 size_t attn_partial_lds_bytes(int D) { return sizeof(float) * (size_t)(2 * kAttnKeys * (D + 1) + 4 * D + 4 * 64); }
-size_t attn_mfma_lds_bytes(int D) { return 2 * (size_t)(kMfmaKeys * (D + 8) + D * (kMfmaKeys + 8)); }
+size_t attn_mfma_lds_bytes(int D) { return 2 * (size_t)(kMfmaKeys * (D + 8) + D * (kMfmaKeys + 4)); }
 // strips of 16 experts per workgroup and contraction split of the score kernel: enough
 // workgroups to spread W_g over the chip, 16 (strip, slice) items per workgroup
 int router_strips_per_wg(const evict_model_desc& m) {
