@@ -446,11 +446,13 @@ static int verify_layer_impl(evict_ctx* ctx, const evict_layer_weights* w, const
     // An expert with more than 16 tokens has several 16-token slots. The strip-per-wavefront kernel can take two
     // consecutive ones of an expert through one weight stream (its operand of 32 tokens must fit the LDS budget of
     // that kernel); measured to pay once there are enough tokens for such experts to be common.
-    const bool can_pair = nt_exp == 1 && a.wave_strip && a.n_strips % 8 == 0 && a.nkb * 2 <= 64;
+    // 16 strips per workgroup stage a slot's operand half as often: pays with many slots, costs with few (measured)
+    // (from 128 tokens on at expert width 768, from 64 on at width 1408, where an operand is twice as long)
+    a.down_ws = ctx->moe_down_ws ? ctx->moe_down_ws : (T >= (a.nkb == 44 ? 64 : 128) ? 16 : 8);
+    const bool wide16 = a.nkb == 44 && a.down_ws == 16 && a.n_strips % 16 == 0 && m.dtype == EVICT_BF16;  // (expert width 1408)
+    const bool can_pair = nt_exp == 1 && a.wave_strip && a.n_strips % 8 == 0 && (a.nkb * 2 <= 64 || wide16);
     const bool pair = can_pair && (ctx->moe_pair_down == 2 ? T >= 128 : ctx->moe_pair_down == 1);
     a.pair_tiles = pair ? 1 : 0;
-    // 16 strips per workgroup stage a slot's operand half as often: pays with many slots, costs with few (measured)
-    a.down_ws = ctx->moe_down_ws ? ctx->moe_down_ws : (T >= 128 ? 16 : 8);
     rc = launch_gemm(m.dtype, EPI_F32, a, pair ? 2 : nt_exp, ctx->moe_grid, s);
     if (rc) return rc;
   }

@@ -1299,6 +1299,11 @@ int launch_gemm_wave_strip(const GemmArgs& a, int grid, hipStream_t s) {
     // 16 strips per workgroup: the slot's token operand is staged half as often
     if (a.nt_loads) hipLaunchKernelGGL((gemm_wave_strip_kernel<ST, 12, 2, true, NTW, 16, 24, true>), dim3(grid), dim3(16 * 64), lds, s, a);
     else hipLaunchKernelGGL((gemm_wave_strip_kernel<ST, 12, 2, true, NTW, 16, 24, false>), dim3(grid), dim3(16 * 64), lds, s, a);
+  } else if (nkb == 44 && a.down_ws == 16 && a.n_strips % 16 == 0 && ST::kBytes == 2) {
+    // expert width 1408, 16 strips per workgroup: with two token tiles the operand takes 88 KiB of LDS, one
+    // workgroup of 16 wavefronts per CU
+    if (a.nt_loads) hipLaunchKernelGGL((gemm_wave_strip_kernel<ST, 11, 3, true, NTW, 16, 44, true>), dim3(grid), dim3(16 * 64), lds, s, a);
+    else hipLaunchKernelGGL((gemm_wave_strip_kernel<ST, 11, 3, true, NTW, 16, 44, false>), dim3(grid), dim3(16 * 64), lds, s, a);
   } else if (nkb == 24) EVICT_WS_LAUNCH_NT(12, 3, 24);
   else if (nkb == 44 && NTW == 1) EVICT_WS_LAUNCH_NT(11, 6, 44);
   else if (nkb == 44) EVICT_WS_LAUNCH(11, 6 / NTW, true);
@@ -1351,7 +1356,11 @@ int launch_gemm_wave_gateup(const GemmArgs& a, int nt, int grid, hipStream_t s) 
   return launch_status("gemm_wave_gateup_kernel");
 }
 
-bool wave_strip_applies(const GemmArgs& a, int nt) { return a.grouped && a.n_strips % 8 == 0 && a.nkb * nt <= 64; }
+bool wave_strip_applies(const GemmArgs& a, int nt) {
+  if (!(a.grouped && a.n_strips % 8 == 0)) return false;
+  // (the 16-strip variant for 44 contraction blocks is given 88 KiB of dynamic LDS in kernels_setup)
+  return a.nkb * nt <= 64 || (a.nkb == 44 && nt == 2 && a.down_ws == 16 && a.n_strips % 16 == 0);
+}
 
 template <typename ST, int EPI>
 int launch_gemm_st(const GemmArgs& a, int nt, int grid, hipStream_t s) {
@@ -1497,6 +1506,8 @@ int kernels_setup(const evict_model_desc& m) {
   EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)attn_partial_mfma_kernel<64, 4, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_mfma_lds_bytes(64)));
   EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)attn_partial_mfma_kernel<128, 8, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * (int)attn_mfma_lds_bytes(128)));
   EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)attn_partial_mfma_kernel<64, 8, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * (int)attn_mfma_lds_bytes(64)));
+  EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)gemm_wave_strip_kernel<BF16, 11, 3, true, 2, 16, 44, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 88 * 1024));
+  EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)gemm_wave_strip_kernel<BF16, 11, 3, true, 2, 16, 44, false>, hipFuncAttributeMaxDynamicSharedMemorySize, 88 * 1024));
   if (m.E > 256)  // LDS variant of TopK: one row of keys per wavefront
     EVICT_HIP_CHECK(hipFuncSetAttribute((const void*)topk_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                         (int)((size_t)kRouterWaves * (64 + m.E) * sizeof(float))));
