@@ -217,6 +217,13 @@ def test_down_projection_paired_slots_and_16_strip_workgroups():
         got = run_case(case, tune=tune)
         check_against_oracle(case, got)
         assert np.array_equal(got["out"], base["out"])
+    # expert width 1408 (44 contraction blocks): the 16-strip variant alone and with paired slots (88 KiB operand),
+    # shared experts with 8 slots each
+    case = synth.make_case("dsv2lite", n=128, L=64, seed=40, sigma=0.2)
+    base = run_case(case, tune={"moe_pair_down": 0, "moe_down_ws": 8})
+    check_against_oracle(case, base)
+    for tune in ({"moe_pair_down": 1, "moe_down_ws": 16}, {"moe_pair_down": 0, "moe_down_ws": 16}):
+        assert np.array_equal(run_case(case, tune=tune)["out"], base["out"])
 
 
 def test_gateup_one_strip_pair_per_wavefront():
