@@ -822,8 +822,13 @@ __global__ __launch_bounds__(kRouterThreads) void router_logits_kernel(
             if (aux_hn) *reinterpret_cast<u32x4*>((char*)aux_hn + ((size_t)t * d + c) * EB) = packed;
           }
         }
-        const int byte = c * EB;  // position in the row -> operand block, quarter, column n
-        s_b[(byte >> 6) * 64 + ((byte >> 4) & 3) * 16 + n] = packed;
+        // position in the row -> operand block, quarter, column n. All lanes of this wavefront write column n of
+        // different (block, quarter) groups, 256 bytes apart: into one bank group, unless the column is XORed with
+        // (quarter | odd block << 2), which sends the 8 lanes the LDS serves per clock to 8 different bank groups
+        // (the readers undo it: a permutation inside the 16 columns they read anyway)
+        const int byte = c * EB;
+        const int kbw = byte >> 6, qw = (byte >> 4) & 3;
+        s_b[kbw * 64 + qw * 16 + (n ^ (qw | ((kbw & 1) << 2)))] = packed;
       }
     }
   }
@@ -847,7 +852,8 @@ __global__ __launch_bounds__(kRouterThreads) void router_logits_kernel(
         if (kb0 + j < kb_hi) a[j] = wp[(size_t)(kb0 + j) * 64];
 #pragma unroll
       for (int j = 0; j < 8; ++j)
-        if (kb0 + j < kb_hi) acc = mfma_block<ST>(a[j], s_b[(kb0 + j) * 64 + lane], acc);
+        if (kb0 + j < kb_hi)
+          acc = mfma_block<ST>(a[j], s_b[(kb0 + j) * 64 + (lane ^ ((lane >> 4) | (((kb0 + j) & 1) << 2)))], acc);
     }
     s_p[((size_t)ks * strips_per_wg + sl) * 64 + lane] = acc;
   }
