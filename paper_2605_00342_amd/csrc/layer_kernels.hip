@@ -440,7 +440,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
     const int idx = tid + NT * it, jp = idx / CH, c = idx - jp * CH;
     voff[it] = (unsigned)(2 * jp) * (unsigned)kstep + c * 8;
   }
-  auto fetch_chunk = [&](int kc0) {
+  auto fetch_chunk = [&](int kc0) __attribute__((always_inline)) {
     int nk = key_end - kc0;
     nk = nk > kMfmaKeys ? kMfmaKeys : nk;
     const bool paged = PAGED && !tree_part;
@@ -512,7 +512,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
     }
   };
   // K row-major, V transposed (two keys per dword)
-  auto write_chunk = [&](int buf) {
+  auto write_chunk = [&](int buf) __attribute__((always_inline)) {
     uint16_t* wk = s_kv + (size_t)buf * BUF;
     uint32_t* wv = reinterpret_cast<uint32_t*>(wk + kMfmaKeys * LDK);
 #pragma unroll
@@ -539,7 +539,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
   // One chunk, compiled twice: for a whole chunk of cache keys (every key visible to every row: no mask, no test
   // for masked scores) and for the ragged last chunk / the draft nodes under the ancestor mask. (With the choice
   // left to run time the compiler keeps one body and pays the mask arithmetic on every chunk.)
-  auto run_chunk = [&](auto full_tag, int kc0) {
+  auto run_chunk = [&](auto full_tag, int kc0) __attribute__((always_inline)) {
     constexpr bool full = decltype(full_tag)::value;
     int nkeys = key_end - kc0;
     nkeys = nkeys > kMfmaKeys ? kMfmaKeys : nkeys;
