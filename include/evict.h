@@ -324,6 +324,28 @@ int evict_select_prefix_coverage(evict_ctx* ctx, const int32_t* tree_off, const 
                                  int32_t* keep, int32_t* new_parent, int32_t* new_tree_off, float* est_len,
                                  int32_t* order, float* prefix_sum, void* stream);
 
+/* Host twins of evict_accept_path, evict_select_prefix(_coverage) and evict_expert_union: the same contracts
+ * (Sec. 2.1; Sec. 3.1-3.2, Eq. 7, 8, 10; Eq. 5) evaluated by plain sequential code on HOST arrays, for callers that
+ * hold these small arrays on the host (a scheduler choosing a verification length, tests of the error
+ * conventions). Every argument has the meaning, layout and limits of its device namesake, with [host] pointers
+ * throughout; there is no context and no stream. Outputs equal the device entry points' bit for bit (selection:
+ * the same single fp32 operations in the same order). Inputs the device entry points clamp and flag are
+ * clamped the same way and their EVICT_ST_* bits are ORed into *status_out (nullable). They touch no GPU, are
+ * not called by the device path and are no fallback for it. */
+int evict_accept_path_host(const int32_t* tree_off, const int32_t* parent, const int32_t* draft_tok,
+                           const int32_t* target_next, int B, int32_t* path, int path_stride, int32_t* path_len,
+                           int32_t* bonus_tok);
+int evict_select_prefix_host(const int32_t* tree_off, const int32_t* parent, const float* node_prob, int B, int T,
+                             const float* cost, int Kmax, int32_t* k_star, int32_t* keep, int32_t* new_parent,
+                             int32_t* new_tree_off, float* est_len, int32_t* order, float* prefix_sum,
+                             int32_t* status_out);
+int evict_select_prefix_coverage_host(const int32_t* tree_off, const int32_t* parent, const float* node_prob, int B,
+                                      int T, float rho, int Kmax, int32_t* k_star, int32_t* keep, int32_t* new_parent,
+                                      int32_t* new_tree_off, float* est_len, int32_t* order, float* prefix_sum,
+                                      int32_t* status_out);
+int evict_expert_union_host(const int32_t* topk_idx, int T, int k, int E, int32_t* union_ids, int32_t* union_count,
+                            int32_t* hist, int32_t* offsets, int32_t* perm, int32_t* inv, int32_t* status_out);
+
 /* Commit of the accepted path to the KV cache of one layer (what follows acceptance in every
  * speculative iteration, Sec. 2.1): for sequence b and j < path_len[b], the draft key/value row
  * of node path[b][j] (k_new / v_new [dev] [T][Hkv][D], storage dtype, as written by

@@ -20,10 +20,16 @@ __all__ = [
     "evict_lm_head_logits", "evict_accept_path_sampled", "evict_kv_commit", "evict_select_prefix_coverage", "evict_kv_commit_stack",
     "evict_profile_cost_union", "evict_verify_stack_paged", "evict_kv_commit_stack_paged", "evict_accept_path_sampled_noalloc",
     "evict_dynamic_tokens", "evict_cost_expected_union_host", "evict_cost_fit_surface_host", "evict_cost_collapse_host",
-    "evict_cost_table_save_host", "evict_cost_table_load_host", "evict_union_total", "STAGES", "EXPORTS",
+    "evict_cost_table_save_host", "evict_cost_table_load_host", "evict_union_total", "evict_accept_path_host",
+    "evict_select_prefix_host", "evict_select_prefix_coverage_host", "evict_expert_union_host", "STAGES", "EXPORTS",
+    "EvictError", "EVICT_ST_BAD_PARENT", "EVICT_ST_BAD_EXPERT", "EVICT_ST_BAD_CTXLEN", "EVICT_ST_BAD_TREE_SIZE", "EVICT_ST_BAD_PAGE",
+    "EVICT_ST_PATH_TRUNCATED", "EVICT_ST_BAD_PROB", "EVICT_ST_BAD_COST",
 ]
 
 EVICT_F32, EVICT_BF16 = 0, 1
+# bits of the status word (evict_device_status, status_out of the host twins)
+EVICT_ST_BAD_PARENT, EVICT_ST_BAD_EXPERT, EVICT_ST_BAD_CTXLEN, EVICT_ST_BAD_TREE_SIZE = 1, 2, 4, 8
+EVICT_ST_BAD_PAGE, EVICT_ST_PATH_TRUNCATED, EVICT_ST_BAD_PROB, EVICT_ST_BAD_COST = 16, 32, 64, 128
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
 
@@ -36,7 +42,8 @@ EXPORTS = [
     "evict_lm_head_logits", "evict_accept_path_sampled", "evict_kv_commit", "evict_select_prefix_coverage", "evict_kv_commit_stack",
     "evict_profile_cost_union", "evict_verify_stack_paged", "evict_kv_commit_stack_paged", "evict_accept_path_sampled_noalloc",
     "evict_dynamic_tokens", "evict_cost_expected_union_host", "evict_cost_fit_surface_host", "evict_cost_collapse_host",
-    "evict_cost_table_save_host", "evict_cost_table_load_host", "evict_union_total",
+    "evict_cost_table_save_host", "evict_cost_table_load_host", "evict_union_total", "evict_accept_path_host",
+    "evict_select_prefix_host", "evict_select_prefix_coverage_host", "evict_expert_union_host",
 ]
 STAGES = ["prep", "qkv", "attention", "oproj", "router", "union", "gateup", "down", "shared", "combine"]
 
@@ -123,6 +130,10 @@ def load():
     lib.evict_cost_table_save_host.argtypes = [C.c_char_p, fp, i32, C.c_char_p]
     lib.evict_cost_table_load_host.argtypes = [C.c_char_p, C.c_char_p, fp, i32, C.POINTER(i32)]
     lib.evict_union_total.argtypes = [vp, C.POINTER(i64), i32, vp]
+    lib.evict_accept_path_host.argtypes = [vp, vp, vp, vp, i32, vp, i32, vp, vp]
+    lib.evict_select_prefix_host.argtypes = [vp, vp, vp, i32, i32, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.evict_select_prefix_coverage_host.argtypes = [vp, vp, vp, i32, i32, C.c_float, i32, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.evict_expert_union_host.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.evict_kv_commit.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, i32, vp, vp, vp, i64, i64, vp, i32, vp, i32, vp]
     lib.evict_kv_commit_stack.argtypes = [vp, i32, i32, i32, C.POINTER(vp), C.POINTER(vp), i32, vp, vp, i32, vp, C.POINTER(vp),
                                           C.POINTER(vp), i64, i64, vp, i32, vp, i32, vp]
@@ -324,6 +335,64 @@ def evict_union_total(ctx, reset: bool = False) -> int:
     total = C.c_int64(0)
     _check(load().evict_union_total(ctx, C.byref(total), 1 if reset else 0, _stream()))
     return total.value
+
+
+# ---- host twins: contiguous numpy arrays on the host in, numpy arrays out (marshalling only) ----
+def _h(a, dtype):
+    import numpy as np
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a, a.ctypes.data
+
+
+def evict_accept_path_host(tree_off, parent, draft_tok, target_next, path_stride: int):
+    """Returns (path [B, path_stride], path_len [B], bonus_tok [B]) as int32 numpy arrays."""
+    import numpy as np
+    (to, pto), (pa, ppa), (dt, pdt), (tn, ptn) = _h(tree_off, np.int32), _h(parent, np.int32), _h(draft_tok, np.int32), _h(target_next, np.int32)
+    B = len(to) - 1
+    path = np.zeros((max(B, 0), max(path_stride, 0)), np.int32); plen = np.zeros(max(B, 0), np.int32); bonus = np.zeros(max(B, 0), np.int32)
+    _check(load().evict_accept_path_host(pto, ppa, pdt, ptn, B, path.ctypes.data, path_stride, plen.ctypes.data, bonus.ctypes.data))
+    return path, plen, bonus
+
+
+def _select_host(fn, tree_off, parent, node_prob, mid, Kmax):
+    import numpy as np
+    (to, pto), (pa, ppa), (q, pq) = _h(tree_off, np.int32), _h(parent, np.int32), _h(node_prob, np.float32)
+    B, T = len(to) - 1, len(pa)
+    out = dict(k_star=np.zeros(B, np.int32), keep=np.full(T, -1, np.int32), new_parent=np.full(T, -1, np.int32),
+               new_tree_off=np.zeros(B + 1, np.int32), est_len=np.zeros(B, np.float32), order=np.zeros(T, np.int32),
+               prefix_sum=np.zeros(T, np.float32))
+    status = np.zeros(1, np.int32)
+    _check(fn(pto, ppa, pq, B, T, mid, Kmax, out["k_star"].ctypes.data, out["keep"].ctypes.data, out["new_parent"].ctypes.data,
+              out["new_tree_off"].ctypes.data, out["est_len"].ctypes.data, out["order"].ctypes.data, out["prefix_sum"].ctypes.data,
+              status.ctypes.data))
+    out["status"] = int(status[0])
+    return out
+
+
+def evict_select_prefix_host(tree_off, parent, node_prob, cost, Kmax: int) -> dict:
+    import numpy as np
+    c, pc = _h(cost, np.float32)
+    if len(c) < Kmax + 1:
+        raise ValueError("cost needs Kmax + 1 entries")
+    return _select_host(load().evict_select_prefix_host, tree_off, parent, node_prob, pc, Kmax)
+
+
+def evict_select_prefix_coverage_host(tree_off, parent, node_prob, rho: float, Kmax: int) -> dict:
+    return _select_host(load().evict_select_prefix_coverage_host, tree_off, parent, node_prob, C.c_float(rho), Kmax)
+
+
+def evict_expert_union_host(topk_idx, E: int) -> dict:
+    import numpy as np
+    idx, pidx = _h(topk_idx, np.int32)
+    T, k = idx.shape
+    out = dict(union_ids=np.zeros(E, np.int32), union_count=np.zeros(1, np.int32), hist=np.zeros(E, np.int32),
+               offsets=np.zeros(E + 1, np.int32), perm=np.zeros(T * k, np.int32), inv=np.zeros(T * k, np.int32))
+    status = np.zeros(1, np.int32)
+    _check(load().evict_expert_union_host(pidx, T, k, E, out["union_ids"].ctypes.data, out["union_count"].ctypes.data,
+                                          out["hist"].ctypes.data, out["offsets"].ctypes.data, out["perm"].ctypes.data,
+                                          out["inv"].ctypes.data, status.ctypes.data))
+    out["status"] = int(status[0])
+    return out
 
 
 def evict_accept_path_sampled_noalloc(ctx, tree_off, parent, draft_tok, logits, vocab, temperature, u_node, u_bonus, B, T,

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libevict.so")
-SOURCES = ["small_kernels.hip", "layer_kernels.hip", "api.hip", "cost_host.hip"]
+SOURCES = ["small_kernels.hip", "layer_kernels.hip", "api.hip", "cost_host.hip", "host_twins.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function", "-Wno-pass-failed",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -246,3 +246,50 @@ def test_select_prefix_flags_out_of_range_inputs_and_keeps_prefixes_closed(n):
     assert np.array_equal(keep, ref["keep"]) and np.array_equal(npar, ref["new_parent"])
     assert npar[0] == -1 and np.all(npar[1:] >= 0)          # one root: every kept node's parent is kept
     ev.evict_destroy(ctx)
+
+
+@pytest.mark.parametrize("sizes,kind,seed", [([32], "eagle", 21), ([64, 64, 64, 64], "random", 22), ([5, 128, 1, 77, 32], "random", 23),
+                                             ([300, 1024, 17], "eagle", 24)])
+def test_host_twins_equal_the_device_entry_points(sizes, kind, seed):
+    """evict_select_prefix_host / evict_accept_path_host / evict_expert_union_host on the host against their
+    device namesakes: every output bit for bit, including the clamped-and-flagged bad inputs."""
+    off, par, pars, q, qs = _trees(sizes, seed, kind)
+    g = synth.philox(seed, 9)
+    kmax = max(1, max(sizes) // 2)
+    cost = (1.0 + 0.03 * np.arange(kmax + 1) + 0.2 * g.random(kmax + 1)).astype(np.float32)
+    par_bad, q_bad = par.copy(), q.copy()
+    if len(par) > 3:  # a parent that does not precede its child, a probability above 1, a NaN, an unusable cost entry
+        par_bad[3] = 3; q_bad[2] = 1.5; q_bad[len(q) - 1] = np.nan
+        cost[min(2, kmax)] = -1.0
+    for P, Q in ((par, q), (par_bad, q_bad)):
+        dev = _select_gpu(off, P, Q, cost, kmax)
+        host = ev.evict_select_prefix_host(off, P, Q, cost, kmax)
+        T2 = int(dev["new_off"][-1])
+        assert np.array_equal(dev["k_star"], host["k_star"]) and np.array_equal(dev["new_off"], host["new_tree_off"])
+        assert np.array_equal(dev["keep"][:T2], host["keep"][:T2]) and np.array_equal(dev["new_parent"][:T2], host["new_parent"][:T2])
+        assert np.array_equal(dev["order"], host["order"])
+        assert np.array_equal(dev["psum"].view(np.uint32), host["prefix_sum"].view(np.uint32))
+        assert np.array_equal(dev["est"].view(np.uint32), host["est_len"].view(np.uint32))
+    # acceptance
+    B, T = len(sizes), int(off[-1])
+    nxt = g.integers(0, 40, T).astype(np.int32)
+    tok = np.concatenate([synth.plant_draft_tokens(p, nxt[o:o + len(p)], 40, g, 0.8) for p, o in zip(pars, off[:-1])]).astype(np.int32)
+    path = torch.zeros(B, 6, dtype=torch.int32, device=DEV); plen = torch.zeros(B, dtype=torch.int32, device=DEV)
+    bonus = torch.zeros(B, dtype=torch.int32, device=DEV)
+    ev.evict_accept_path(None, _i32(off), _i32(par), _i32(tok), _i32(nxt), B, path, 6, plen, bonus)
+    torch.cuda.synchronize()
+    hp, hl, hb = ev.evict_accept_path_host(off, par, tok, nxt, 6)
+    assert np.array_equal(path.cpu().numpy(), hp) and np.array_equal(plen.cpu().numpy(), hl) and np.array_equal(bonus.cpu().numpy(), hb)
+    # expert union, with one expert id out of range
+    E, k = 64, 6
+    Tn = min(T, 8192 // k)
+    idx = np.stack([g.permutation(E)[:k] for _ in range(Tn)]).astype(np.int32)
+    idx[0, 0] = E + 3
+    d = {n_: torch.zeros(s_, dtype=torch.int32, device=DEV) for n_, s_ in
+         (("union_ids", E), ("union_count", 1), ("hist", E), ("offsets", E + 1), ("perm", Tn * k), ("inv", Tn * k))}
+    ev.evict_expert_union(None, _i32(idx), Tn, k, E, d["union_ids"], d["union_count"], d["hist"], d["offsets"], d["perm"], d["inv"])
+    torch.cuda.synchronize()
+    hu = ev.evict_expert_union_host(idx, E)
+    assert hu["status"] == ev.EVICT_ST_BAD_EXPERT
+    for n_ in d:
+        assert np.array_equal(d[n_].cpu().numpy(), hu[n_]), n_
