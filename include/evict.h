@@ -457,6 +457,10 @@ int evict_device_status(evict_ctx* ctx, int32_t* status_host, void* stream);
  *   "attn_waves"      wavefronts per workgroup of that kernel: 4, 8 (two LDS buffers, next chunk fetched
  *                     during the matrix work), or 0 = auto
  *   "attn_row_blocks" workgroups per (KV split, KV head) in the bf16 attention kernel, 0 = auto
+ *   "moe_pair_down"   down projection: two consecutive 16-token slots of an expert through one weight stream:
+ *                     0 off, 1 on (where the kernel's LDS budget allows), 2 = auto (from 128 tokens on)
+ *   "moe_down_ws"     down projection, strip-per-wavefront kernel: strips (wavefronts) per workgroup, 8, 16,
+ *                     or 0 = auto (16 from 128 tokens on, from 64 at expert width 1408)
  * Returns EVICT_E_INVALID for an unknown key or a value out of range. */
 int evict_tune(evict_ctx* ctx, const char* key, int value);
 
