@@ -48,6 +48,9 @@ def random_case(seed):
     if g.random() < 0.4:
         tune["attn_waves"] = int(g.choice([4, 8]))
         tune["attn_target_wgs"] = int(g.choice([2, 16, 512]))
+    if g.random() < 0.4:  # (drawn last: the shapes of earlier seeds stay what they were)
+        tune["moe_pair_down"] = int(g.choice([0, 1]))
+        tune["moe_down_ws"] = int(g.choice([8, 16]))
     return cfg, case, tune, dict(n=n, Ls=Ls, tree=tree, sigma=sigma, batch=batch)
 
 
